@@ -1,0 +1,198 @@
+/*
+ * libtgnn -- the per-mini-batch training step of a memory-based temporal graph neural network
+ * (TGN-attn with static node memory, as trained by DistTGL, arXiv 2307.07649) on one AMD MI355X.
+ *
+ * Conventions
+ *   - plain C ABI; every call returns 0 (TGNN_OK) or a negative TGNN_E_* code, and leaves a message
+ *     that tgnn_last_error() returns (thread-local, valid until the next failing call on the thread);
+ *   - unless marked HOST, every pointer is a DEVICE pointer owned by the caller, row-major,
+ *     contiguous, 16-byte aligned; the library never frees or reallocates caller memory;
+ *   - the structs themselves (tgnn_config, tgnn_graph, ...) are host structs passed by pointer;
+ *   - node and event ids are int32, CSR offsets int64, timestamps double, everything else float;
+ *   - `stream` is a hipStream_t (NULL = the default stream); calls are asynchronous on it and never
+ *     synchronise the device, except tgnn_destroy;
+ *   - a context owns a device workspace sized at tgnn_create; two calls that use one context must
+ *     be ordered on one stream;
+ *   - padding: nbr = eid = -1 for a missing neighbour, mail_eid = -1 for "no cached mail".
+ *
+ * Notation: B events in a batch; roots R = 3B in the order [sources | destinations | negative
+ * destinations]; k most recent neighbours per root; d_m memory width, d_t time-encoding width,
+ * d_e edge-feature width, d_s static-memory width (0 = none), H heads;
+ *   d_in = 2 d_m + d_t + d_e,  d_x = d_m + d_s,  d_q = d_x + d_t,  d_kv = d_x + d_e + d_t,  d_o = d_m.
+ */
+#ifndef TGNN_H
+#define TGNN_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define TGNN_OK 0
+#define TGNN_E_INVALID_ARG (-1)
+#define TGNN_E_NULL_PTR (-2)
+#define TGNN_E_MISALIGNED (-3)
+#define TGNN_E_OUT_OF_RANGE (-4)
+#define TGNN_E_UNSORTED_TS (-5)
+#define TGNN_E_UNSUPPORTED_DIM (-6)
+#define TGNN_E_WORKSPACE (-7)
+#define TGNN_E_HIP (-8)
+
+#define TGNN_MAX_K 32        /* neighbours per root */
+#define TGNN_MAX_BATCHES 16  /* mini-batches (memory replicas) per tgnn_train_step call */
+#define TGNN_MAX_HEADS 8
+
+typedef struct tgnn_ctx tgnn_ctx;
+
+typedef struct {
+  int32_t n_nodes, d_mem, d_time, d_edge, d_static, n_heads, k;
+  int32_t max_batch;  /* largest number of events in one mini-batch */
+  int32_t n_replicas; /* independent memory/mailbox copies (memory parallelism, Sec. 3.2.3); >= 1 */
+  int32_t dt_source;  /* time difference in the attention keys (Eq. 5-6): 0 = query time minus the update
+                         time of the neighbour's memory as used (the paper's wording), 1 = minus the edge time */
+  int32_t flags;      /* reserved, 0 */
+} tgnn_config;
+
+/* Temporal CSR: node v's incident events (both directions) are entries indptr[v] .. indptr[v+1]-1 of
+ * nbr/eid/ts, ascending in (time, event id).  efeat is [n_events, d_edge]. */
+typedef struct {
+  const int64_t* indptr; /* [n_nodes + 1] */
+  const int32_t* nbr;    /* [2 n_events] other endpoint */
+  const int32_t* eid;    /* [2 n_events] event id */
+  const double* ts;      /* [2 n_events] event time */
+  const float* efeat;    /* [n_events, d_edge], may be NULL when d_edge == 0 */
+  int64_t n_events;
+} tgnn_graph;
+
+/* Node state; every array has leading dimension n_replicas (replica r, node v -> row r*n_nodes + v).
+ * Sec. 2.1: memory s_v (zero-initialised), its last-update time t_v^-, and the cached mail. */
+typedef struct {
+  float* mem;        /* [n_replicas * n_nodes, d_mem] */
+  double* mem_ts;    /* [n_replicas * n_nodes] */
+  float* mail;       /* [n_replicas * n_nodes, 2 d_mem]  {s'_self || s'_other} of the last event */
+  double* mail_ts;   /* [n_replicas * n_nodes] time of that event */
+  int32_t* mail_eid; /* [n_replicas * n_nodes] id of that event (its edge feature is looked up), -1 = none */
+  const float* stat; /* [n_nodes, d_static] frozen static node memory (Sec. 3.1), NULL when d_static == 0 */
+} tgnn_state;
+
+/* Parameters; the same struct carries gradients.  Matrices are [out, in] row-major.
+ *   time_w, time_b [d_t]                         Phi(dt)_c = cos(time_w[c] * dt + time_b[c])
+ *   gru_wih [3 d_m, d_in], gru_whh [3 d_m, d_m], gru_bih, gru_bhh [3 d_m]    gate order r, z, n;
+ *           input columns ordered {mail (2 d_m) || Phi (d_t) || edge feature (d_e)}  (Eq. 1-2)
+ *   wq [d_o, d_q], wk, wv [d_o, d_kv], biases [d_o]; key/value input {x_w || e_vw || Phi} (Eq. 4-6)
+ *   wo [d_o, d_o + d_x], bo [d_o]                merge layer on {h_v || x_v}
+ *   dec_ws, dec_wd [d_o, d_o], dec_b1 [d_o], dec_w2 [d_o], dec_b2 [1]        link decoder */
+typedef struct {
+  float *time_w, *time_b, *gru_wih, *gru_whh, *gru_bih, *gru_bhh, *wq, *bq, *wk, *bk, *wv, *bv, *wo, *bo,
+      *dec_ws, *dec_wd, *dec_b1, *dec_w2, *dec_b2;
+} tgnn_params;
+
+/* One chronological mini-batch of events (u_i, v_i, e_i, t_i) with one sampled negative destination
+ * n_i per event, advancing memory replica `replica`. */
+typedef struct {
+  const int32_t *src, *dst, *neg, *eid; /* [n] */
+  const double* t;                      /* [n] */
+  int32_t n;
+  int32_t replica;
+} tgnn_batch;
+
+const char* tgnn_last_error(void);
+
+/* Validates the configuration (TGNN_E_UNSUPPORTED_DIM: d_mem % n_heads != 0, k > TGNN_MAX_K, n_heads >
+ * TGNN_MAX_HEADS, a width that is not positive, d_edge or d_static negative) and allocates the workspace
+ * on the current HIP device (TGNN_E_WORKSPACE / TGNN_E_HIP on failure). */
+int32_t tgnn_create(const tgnn_config* cfg, tgnn_ctx** out);
+/* Synchronises the device and frees the workspace.  NULL is accepted. */
+int32_t tgnn_destroy(tgnn_ctx* ctx);
+/* Bytes of device workspace the context holds. */
+int64_t tgnn_workspace_bytes(const tgnn_ctx* ctx);
+
+/* HOST.  Builds the temporal CSR from a chronological event list (src, dst, ts: HOST arrays [n_events],
+ * ts non-decreasing -> else TGNN_E_UNSORTED_TS; ids in [0, n_nodes) -> else TGNN_E_OUT_OF_RANGE) into
+ * caller-allocated HOST arrays indptr [n_nodes+1], nbr/eid/ts_out [2 n_events].  Every event is listed
+ * under both endpoints; each list ascends in (time, event id).  (Sec. 2.1, "most recent neighbors".) */
+int32_t tgnn_build_tcsr(const int32_t* src, const int32_t* dst, const double* ts, int64_t n_events,
+                        int32_t n_nodes, int64_t* indptr, int32_t* nbr, int32_t* eid, double* ts_out);
+
+/* Epoch start (Alg. 1 "reset memory and mail"): zero memory, mails and both time arrays and set
+ * mail_eid = -1 for one replica (replica = -1: all replicas). */
+int32_t tgnn_state_reset(tgnn_ctx* ctx, tgnn_state* st, int32_t replica, void* stream);
+
+/* Sec. 2.1 "most recent neighbors", k = 10 in Sec. 4.  For each query (node[r], t[r]), r < n_roots: the
+ * min(k, #) incident events with time strictly below t[r] that are last in (time, event id) order, most
+ * recent first.  out_nbr, out_eid [n_roots, k] int32 (-1 padded), out_ts [n_roots, k] double (0 padded),
+ * out_cnt [n_roots].  n_roots <= 3 * max_batch * n_replicas.  Node ids must lie in [0, n_nodes)
+ * (not checked on the device: rows of out-of-range nodes are reported as empty). */
+int32_t tgnn_sample_recent(tgnn_ctx* ctx, const tgnn_graph* g, const int32_t* node, const double* t,
+                           int32_t n_roots, int32_t* out_nbr, int32_t* out_eid, double* out_ts,
+                           int32_t* out_cnt, void* stream);
+
+/* Sec. 3.2.1: fetch the node memory and cached mails of root and supporting nodes.  For each slot
+ * s < n_slots with node w = slot_node[s] of replica `replica` (w = -1: padding, the row is zero-filled):
+ * out_mem [n_slots, d_m] = mem[w]; out_mail [n_slots, 2 d_m] = mail[w]; out_mail_efeat [n_slots, d_e] =
+ * efeat[mail_eid[w]] (zeros when there is no mail); out_mem_ts, out_mail_ts [n_slots]; out_has_mail
+ * [n_slots] = 1 if mail_eid[w] >= 0.  n_slots <= workspace slot capacity (3 B (1+k) per batch). */
+int32_t tgnn_gather_memory(tgnn_ctx* ctx, const tgnn_graph* g, const tgnn_state* st, int32_t replica,
+                           const int32_t* slot_node, int32_t n_slots, float* out_mem, float* out_mail,
+                           float* out_mail_efeat, double* out_mem_ts, double* out_mail_ts,
+                           int32_t* out_has_mail, void* stream);
+
+/* Eq. 3 with the mail of Eq. 1-2: for each staged row s (the outputs of tgnn_gather_memory):
+ * has_mail ? s' = GRU({mail || Phi(mail_ts - mem_ts) || mail_efeat}, mem), tau = mail_ts
+ *          : s' = mem, tau = mem_ts.    out_s_new [n_slots, d_m], out_tau [n_slots]. */
+int32_t tgnn_gru_update(tgnn_ctx* ctx, const tgnn_params* p, int32_t n_slots, const float* mem,
+                        const float* mail, const float* mail_efeat, const double* mem_ts,
+                        const double* mail_ts, const int32_t* has_mail, float* out_s_new, double* out_tau,
+                        void* stream);
+
+/* Eq. 4-7 plus the merge layer.  x_root [n_roots, d_x] = {s'_v || static_v}; x_nbr [n_roots*k, d_x];
+ * e_nbr [n_roots*k, d_e]; dt_nbr [n_roots*k] double (time difference of Eq. 5-6); cnt [n_roots] valid
+ * neighbours per root (the first cnt of each k).  q = W_q{x_v || Phi(0)} + b_q; K, V from
+ * {x_w || e_vw || Phi(dt)}; per head softmax(q K^T / sqrt(cnt)) V; out_z [n_roots, d_o] =
+ * ReLU(W_o{h_v || x_v} + b_o).  Activations are kept in the context for tgnn_temporal_attn_bwd. */
+int32_t tgnn_temporal_attn_fwd(tgnn_ctx* ctx, const tgnn_params* p, int32_t n_roots, const float* x_root,
+                               const float* x_nbr, const float* e_nbr, const double* dt_nbr,
+                               const int32_t* cnt, float* out_z, void* stream);
+
+/* Reverse mode through the most recent tgnn_temporal_attn_fwd on this context (same n_roots, same p).
+ * dz [n_roots, d_o].  Adds the gradients of wq,bq,wk,bk,wv,bv,wo,bo,time_w,time_b into `grads` (+=) and
+ * writes d_x_root [n_roots, d_m] and d_x_nbr [n_roots*k, d_m]: the gradient with respect to the dynamic
+ * (first d_m) columns of x_root / x_nbr.  Static memory and edge features are constants. */
+int32_t tgnn_temporal_attn_bwd(tgnn_ctx* ctx, const tgnn_params* p, int32_t n_roots, const float* dz,
+                               tgnn_params* grads, float* d_x_root, float* d_x_nbr, void* stream);
+
+/* COMB = most recent mail (Eq. 8, Sec. 2.1.1) and "only root nodes are written" (Sec. 3.2.1).  Occurrence
+ * (i, role) with role 0 = source, 1 = destination has key 2i+role; for every distinct node among the 2n
+ * endpoints the occurrence with the largest key wins and writes mem = s'_self, mem_ts = tau_self,
+ * mail = {s'_self || s'_other}, mail_eid = eid[i], mail_ts = t[i].  s_new_src/dst [n, d_m], tau_src/dst [n].
+ * out_winner [2n] (may be NULL): 1 where occurrence role*n+i won, else 0. */
+int32_t tgnn_memory_writeback(tgnn_ctx* ctx, tgnn_state* st, int32_t replica, const int32_t* src,
+                              const int32_t* dst, const int32_t* eid, const double* t, int32_t n_events,
+                              const float* s_new_src, const float* s_new_dst, const double* tau_src,
+                              const double* tau_dst, int32_t* out_winner, void* stream);
+
+/* The whole step for n_batches mini-batches (one per memory replica, distinct replicas) that share one
+ * weight set: sample -> gather -> UPDT for root and supporting nodes -> attention -> decoder ->
+ * loss = mean binary cross-entropy over each batch's n positive and n negative pairs -> backward (the
+ * stored memory and mails are constants: no back-propagation through time) -> last-event-wins write-back.
+ *   grads      gradients of sum_b loss_b are ADDED (+=) to these tensors;
+ *   lr         if nonzero, plain SGD p -= lr * grads on every tensor except time_w/time_b after the
+ *              backward pass (grads must then hold only this step's gradients, i.e. be zero on entry);
+ *   out_loss   device scalar, mean over the batches of loss_b;
+ *   out_logits [2 * sum n] or NULL; batch b at offset 2 * (events before b): n positive then n negative;
+ *   out_winner [2 * sum n] or NULL; as in tgnn_memory_writeback, per batch.
+ * Each batches[b].n <= max_batch, n_batches <= min(n_replicas, TGNN_MAX_BATCHES). */
+int32_t tgnn_train_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, const tgnn_params* p,
+                        tgnn_params* grads, const tgnn_batch* batches, int32_t n_batches, float lr,
+                        float* out_loss, float* out_logits, int32_t* out_winner, void* stream);
+
+/* Debug/parity access to what the last tgnn_train_step left in the workspace.  `what`:
+ * 0 nbr [R,k] i32, 1 eid [R,k] i32, 2 nts [R,k] f64, 3 cnt [R] i32, 4 s_new [R(1+k), d_m] f32,
+ * 5 tau [R(1+k)] f64, 6 z [R, d_o] f32.  Copies n_bytes (device to device) into dst on `stream`. */
+int32_t tgnn_debug_read(tgnn_ctx* ctx, int32_t what, void* dst, int64_t n_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,179 @@
+// Softmax attention over the k sampled neighbours of one root (Eq. 7), forward and backward.
+// One wavefront per root: the k key (or value) rows are staged in LDS, the H*k scores are computed by
+// H*k lanes, the per-head softmax runs over at most 32 values, and the weighted sums are taken with one
+// lane per output element.  The projections themselves (Eq. 4-6) are MFMA GEMMs.
+#include "tgnn_internal.h"
+
+namespace tgnn {
+
+struct AttnShape {
+  int R, k, H, dO, dh, ldq, ldkv, ldm;
+};
+
+// LDS floats per wave
+__host__ __device__ inline int attn_lds_floats(int k, int H, int dO) { return dO + k * (dO + 1) + 2 * H * k; }
+
+__global__ __launch_bounds__(256) void attn_fwd_kernel(AttnShape sh, const float* __restrict__ q,
+                                                       const float* __restrict__ KV,
+                                                       const int32_t* __restrict__ cnt, float* __restrict__ prob,
+                                                       float* __restrict__ Min) {
+  extern __shared__ float lds[];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int r = blockIdx.x * 4 + wave;
+  if (r >= sh.R) return;
+  float* sq = lds + (size_t)wave * attn_lds_floats(sh.k, sh.H, sh.dO);
+  float* sK = sq + sh.dO;
+  float* sa = sK + sh.k * (sh.dO + 1);
+  const int c = cnt[r];
+  const int HK = sh.H * sh.k;
+  float* pr = prob + (size_t)r * HK;
+  float* out = Min + (size_t)r * sh.ldm;
+  if (c == 0) {
+    for (int p = lane; p < HK; p += 64) pr[p] = 0.f;
+    for (int e = lane; e < sh.dO; e += 64) out[e] = 0.f;
+    return;
+  }
+  const float scale = 1.0f / sqrtf((float)c);
+  for (int e = lane; e < sh.dO; e += 64) sq[e] = q[(size_t)r * sh.ldq + e];
+  for (int j = 0; j < c; ++j) {
+    const float* krow = KV + ((size_t)r * sh.k + j) * sh.ldkv;
+    for (int e = lane; e < sh.dO; e += 64) sK[j * (sh.dO + 1) + e] = krow[e];
+  }
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): LDS writes of this wave are visible to all its lanes
+  for (int p = lane; p < HK; p += 64) {
+    const int h = p / sh.k, j = p - h * sh.k;
+    float a = -INFINITY;
+    if (j < c) {
+      a = 0.f;
+      const float* qq = sq + h * sh.dh;
+      const float* kk = sK + j * (sh.dO + 1) + h * sh.dh;
+      for (int d = 0; d < sh.dh; ++d) a += qq[d] * kk[d];
+      a *= scale;
+    }
+    sa[p] = a;
+  }
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_s_waitcnt(0xc07f);
+  for (int p = lane; p < HK; p += 64) {
+    const int h = p / sh.k, j = p - h * sh.k;
+    float v = 0.f;
+    if (j < c) {
+      float mx = -INFINITY;
+      for (int jj = 0; jj < c; ++jj) mx = fmaxf(mx, sa[h * sh.k + jj]);
+      float den = 0.f;
+      for (int jj = 0; jj < c; ++jj) den += expf(sa[h * sh.k + jj] - mx);
+      v = expf(sa[p] - mx) / den;
+    }
+    sa[HK + p] = v;
+    pr[p] = v;
+  }
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_s_waitcnt(0xc07f);
+  for (int e = lane; e < sh.dO; e += 64) {
+    const int h = e / sh.dh;
+    float o = 0.f;
+    for (int j = 0; j < c; ++j) o += sa[HK + h * sh.k + j] * KV[((size_t)r * sh.k + j) * sh.ldkv + sh.dO + e];
+    out[e] = o;
+  }
+}
+
+__global__ __launch_bounds__(256) void attn_bwd_kernel(AttnShape sh, const float* __restrict__ q,
+                                                       const float* __restrict__ KV,
+                                                       const int32_t* __restrict__ cnt,
+                                                       const float* __restrict__ prob,
+                                                       const float* __restrict__ dMin, float* __restrict__ dq,
+                                                       float* __restrict__ dKV) {
+  extern __shared__ float lds[];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int r = blockIdx.x * 4 + wave;
+  if (r >= sh.R) return;
+  float* sdo = lds + (size_t)wave * attn_lds_floats(sh.k, sh.H, sh.dO);
+  float* sV = sdo + sh.dO;
+  float* sa = sV + sh.k * (sh.dO + 1);  // [0,HK): prob, [HK,2HK): d(score)
+  const int c = cnt[r];
+  const int HK = sh.H * sh.k;
+  // rows of absent neighbours get zero gradients
+  for (int j = c; j < sh.k; ++j) {
+    float* row = dKV + ((size_t)r * sh.k + j) * sh.ldkv;
+    for (int e = lane; e < 2 * sh.dO; e += 64) row[e] = 0.f;
+  }
+  if (c == 0) {
+    for (int e = lane; e < sh.dO; e += 64) dq[(size_t)r * sh.ldq + e] = 0.f;
+    return;
+  }
+  const float scale = 1.0f / sqrtf((float)c);
+  for (int e = lane; e < sh.dO; e += 64) sdo[e] = dMin[(size_t)r * sh.ldm + e];
+  for (int j = 0; j < c; ++j) {
+    const float* vrow = KV + ((size_t)r * sh.k + j) * sh.ldkv + sh.dO;
+    for (int e = lane; e < sh.dO; e += 64) sV[j * (sh.dO + 1) + e] = vrow[e];
+  }
+  for (int p = lane; p < HK; p += 64) sa[p] = prob[(size_t)r * HK + p];
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_s_waitcnt(0xc07f);
+  for (int p = lane; p < HK; p += 64) {
+    const int h = p / sh.k, j = p - h * sh.k;
+    float dp = 0.f;
+    if (j < c) {
+      const float* dd = sdo + h * sh.dh;
+      const float* vv = sV + j * (sh.dO + 1) + h * sh.dh;
+      for (int d = 0; d < sh.dh; ++d) dp += dd[d] * vv[d];
+    }
+    sa[HK + p] = dp;
+  }
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_s_waitcnt(0xc07f);
+  float da_keep[(TGNN_MAX_HEADS * TGNN_MAX_K + 63) / 64];
+  int it = 0;
+  for (int p = lane; p < HK; p += 64, ++it) {
+    const int h = p / sh.k, j = p - h * sh.k;
+    float da = 0.f;
+    if (j < c) {
+      float sdot = 0.f;
+      for (int jj = 0; jj < c; ++jj) sdot += sa[h * sh.k + jj] * sa[HK + h * sh.k + jj];
+      da = sa[p] * (sa[HK + p] - sdot) * scale;
+    }
+    da_keep[it] = da;
+  }
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_s_waitcnt(0xc07f);
+  it = 0;
+  for (int p = lane; p < HK; p += 64, ++it) sa[HK + p] = da_keep[it];
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_s_waitcnt(0xc07f);
+  for (int e = lane; e < sh.dO; e += 64) {
+    const int h = e / sh.dh;
+    const float qe = q[(size_t)r * sh.ldq + e], doe = sdo[e];
+    float dqe = 0.f;
+    for (int j = 0; j < c; ++j) {
+      const size_t row = ((size_t)r * sh.k + j) * sh.ldkv;
+      const float da = sa[HK + h * sh.k + j];
+      dqe += da * KV[row + e];
+      dKV[row + e] = da * qe;
+      dKV[row + sh.dO + e] = sa[h * sh.k + j] * doe;
+    }
+    dq[(size_t)r * sh.ldq + e] = dqe;
+  }
+}
+
+static AttnShape shape_of(const Dims& d, int R, int ldq, int ldkv, int ldm) {
+  return AttnShape{R, d.k, d.H, d.dO, d.dO / d.H, ldq, ldkv, ldm};
+}
+
+void attn_core_fwd(const Dims& d, int R, const float* q, int ldq, const float* KV, int ldkv, const int32_t* cnt,
+                   float* prob, float* Min, int ldm, hipStream_t s) {
+  if (R <= 0) return;
+  const size_t lds = 4 * sizeof(float) * attn_lds_floats(d.k, d.H, d.dO);
+  hipLaunchKernelGGL(attn_fwd_kernel, dim3((R + 3) / 4), dim3(256), lds, s, shape_of(d, R, ldq, ldkv, ldm), q, KV, cnt,
+                     prob, Min);
+}
+
+void attn_core_bwd(const Dims& d, int R, const float* q, int ldq, const float* KV, int ldkv, const int32_t* cnt,
+                   const float* prob, const float* dMin, int ldm, float* dq, float* dKV, hipStream_t s) {
+  if (R <= 0) return;
+  const size_t lds = 4 * sizeof(float) * attn_lds_floats(d.k, d.H, d.dO);
+  hipLaunchKernelGGL(attn_bwd_kernel, dim3((R + 3) / 4), dim3(256), lds, s, shape_of(d, R, ldq, ldkv, ldm), q, KV, cnt,
+                     prob, dMin, dq, dKV);
+}
+
+}  // namespace tgnn

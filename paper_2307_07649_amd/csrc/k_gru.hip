@@ -1,0 +1,145 @@
+// Element-wise parts of UPDT = GRU cell (Eq. 3): gates forward and backward, and the gradients of the
+// time-encoding parameters.  The matrix products live in k_gemm.hip.
+#include "tgnn_internal.h"
+#include "device_math.h"
+
+namespace tgnn {
+
+__device__ __forceinline__ float sigmoidf_(float x) { return 1.0f / (1.0f + expf(-x)); }
+__device__ __forceinline__ float tanhf_(float x) {
+  // tanh(x) = 1 - 2 / (exp(2x) + 1); exact limits at +-inf, no cancellation problem near 0 at 1e-7 level
+  const float e = expf(2.0f * x);
+  return 1.0f - 2.0f / (e + 1.0f);
+}
+
+// gates layout per row: [r | z | n | W_hn h + b_hn], each block ldh floats wide
+__global__ void gru_fwd_kernel(int n, int dm, int ldh, int ld3, const float* __restrict__ gi,
+                               const float* __restrict__ gh, const float* __restrict__ Hm,
+                               const int32_t* __restrict__ has, float* __restrict__ gates,
+                               float* __restrict__ s_new) {
+  const long long total = (long long)n * dm;
+  for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < total;
+       i += (long long)gridDim.x * blockDim.x) {
+    const int row = (int)(i / dm), c = (int)(i - (long long)row * dm);
+    const float h = Hm[(size_t)row * ldh + c];
+    float out = h;
+    if (has[row]) {
+      const float* a = gi + (size_t)row * ld3;
+      const float* b = gh + (size_t)row * ld3;
+      const float r = sigmoidf_(a[c] + b[c]);
+      const float z = sigmoidf_(a[dm + c] + b[dm + c]);
+      const float hn = b[2 * dm + c];
+      const float nn = tanhf_(a[2 * dm + c] + r * hn);
+      out = (1.0f - z) * nn + z * h;
+      float* g = gates + (size_t)row * 4 * ldh;
+      g[c] = r;
+      g[ldh + c] = z;
+      g[2 * ldh + c] = nn;
+      g[3 * ldh + c] = hn;
+    }
+    s_new[(size_t)row * ldh + c] = out;
+  }
+}
+
+void gru_gates_fwd(const Dims& d, int n, const float* gi, const float* gh, const float* Hm, const int32_t* has,
+                   float* gates, float* s_new, hipStream_t s) {
+  if (n <= 0) return;
+  const long long total = (long long)n * d.dm;
+  const int blocks = (int)((total + 255) / 256);
+  hipLaunchKernelGGL(gru_fwd_kernel, dim3(blocks), dim3(256), 0, s, n, d.dm, d.ldh, d.ld3, gi, gh, Hm, has, gates,
+                     s_new);
+}
+
+// The gradient reaching s' of slot `row` comes from the merge layer and the query (roots) or from the
+// key/value input (neighbour slots).  It stops here: stored memory and mails are constants (Sec. 2.1, no BPTT).
+__global__ void gru_bwd_kernel(int R, int n, int dm, int dO, int ldh, int ld3, const float* __restrict__ dMin,
+                               int ldm, const float* __restrict__ dQsub, const float* __restrict__ dCsub, int ldsub,
+                               const float* __restrict__ gates, const float* __restrict__ Hm,
+                               const int32_t* __restrict__ has, float* __restrict__ dgi, float* __restrict__ dgh) {
+  const long long total = (long long)n * dm;
+  for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < total;
+       i += (long long)gridDim.x * blockDim.x) {
+    const int row = (int)(i / dm), c = (int)(i - (long long)row * dm);
+    float drp = 0.f, dzp = 0.f, dnp = 0.f, dnr = 0.f;
+    if (has[row]) {
+      float ds;
+      if (row < R) ds = dMin[(size_t)row * ldm + dO + c] + dQsub[(size_t)row * ldsub + c];
+      else ds = dCsub[(size_t)(row - R) * ldsub + c];
+      const float* g = gates + (size_t)row * 4 * ldh;
+      const float r = g[c], z = g[ldh + c], nn = g[2 * ldh + c], hn = g[3 * ldh + c];
+      const float h = Hm[(size_t)row * ldh + c];
+      const float dn = ds * (1.0f - z);
+      const float dz = ds * (h - nn);
+      dnp = dn * (1.0f - nn * nn);
+      const float dr = dnp * hn;
+      dzp = dz * z * (1.0f - z);
+      drp = dr * r * (1.0f - r);
+      dnr = dnp * r;
+    }
+    float* a = dgi + (size_t)row * ld3;
+    float* b = dgh + (size_t)row * ld3;
+    a[c] = drp; a[dm + c] = dzp; a[2 * dm + c] = dnp;
+    b[c] = drp; b[dm + c] = dzp; b[2 * dm + c] = dnr;
+  }
+}
+
+void gru_gates_bwd(const Dims& d, int R, int n, const float* dMin, int ldm, const float* dQsub, const float* dCsub,
+                   int ldsub, const float* gates, const float* Hm, const int32_t* has, float* dgi, float* dgh,
+                   hipStream_t s) {
+  if (n <= 0) return;
+  const long long total = (long long)n * d.dm;
+  const int blocks = (int)((total + 255) / 256);
+  hipLaunchKernelGGL(gru_bwd_kernel, dim3(blocks), dim3(256), 0, s, R, n, d.dm, d.dO, d.ldh, d.ld3, dMin, ldm, dQsub,
+                     dCsub, ldsub, gates, Hm, has, dgi, dgh);
+}
+
+// g_w[c] += sum_n dphi[n, col0 + c] * (-sin(w_c delta_n + b_c)) * delta_n ;  g_b[c] += sum_n dphi * (-sin(..))
+constexpr int TG_ROWS = 64;
+__global__ __launch_bounds__(256) void time_grad_kernel(const float* __restrict__ dphi, int ld, int col0,
+                                                        const double* __restrict__ delta, int n, int dt,
+                                                        const float* __restrict__ time_w,
+                                                        const float* __restrict__ time_b, float* __restrict__ g_w,
+                                                        float* __restrict__ g_b) {
+  __shared__ float sw[4][64], sb[4][64];
+  const int cx = threadIdx.x & 63, cy = threadIdx.x >> 6;
+  const int r0 = blockIdx.x * TG_ROWS;
+  const int r1 = min(n, r0 + TG_ROWS);
+  for (int c0 = 0; c0 < dt; c0 += 64) {
+    const int c = c0 + cx;
+    float aw = 0.f, ab = 0.f;
+    if (c < dt) {
+      const float w = time_w[c], b = time_b[c];
+      for (int r = r0 + cy; r < r1; r += 4) {
+        const float g = dphi[(size_t)r * ld + col0 + c];
+        if (g != 0.f) {
+          const double dl = delta ? delta[r] : 0.0;
+          float sn, cs;
+          sincos_reduced(fma((double)w, dl, (double)b), sn, cs);
+          const float t = -g * sn;
+          ab += t;
+          aw += t * (float)dl;
+        }
+      }
+    }
+    sw[cy][cx] = aw;
+    sb[cy][cx] = ab;
+    __syncthreads();
+    if (cy == 0 && c < dt) {
+      const float tw = sw[0][cx] + sw[1][cx] + sw[2][cx] + sw[3][cx];
+      const float tb = sb[0][cx] + sb[1][cx] + sb[2][cx] + sb[3][cx];
+      if (delta) atomicAdd(g_w + c, tw);
+      atomicAdd(g_b + c, tb);
+    }
+    __syncthreads();
+  }
+}
+
+void time_grad(const float* dphi, int ld, int col0, const double* delta, const int32_t* valid, int n, int dt,
+               const float* time_w, const float* time_b, float* g_w, float* g_b, hipStream_t s) {
+  (void)valid;
+  if (n <= 0) return;
+  hipLaunchKernelGGL(time_grad_kernel, dim3((n + TG_ROWS - 1) / TG_ROWS), dim3(256), 0, s, dphi, ld, col0, delta, n, dt,
+                     time_w, time_b, g_w, g_b);
+}
+
+}  // namespace tgnn

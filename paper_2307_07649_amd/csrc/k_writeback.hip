@@ -1,0 +1,105 @@
+// Last-event-wins write-back: COMB keeps the most recent mail of a batch (Eq. 8, Sec. 2.1.1) and only
+// root nodes are written (Sec. 3.2.1).  Arbitration is a segmented maximum over occurrence keys, taken
+// with a 64-bit atomic max on a per-(replica, node) scratch word; maximum is order-independent, so the
+// winners are deterministic.  Occurrence (event e = off + i, role) has key 1 + 2e + role; 0 = idle.
+#include "tgnn_internal.h"
+#include "device_math.h"
+
+namespace tgnn {
+
+__device__ __forceinline__ bool occ_decode(const BatchSet& bs, int o, int& b, int& i, int& role) {
+  if (o >= 2 * bs.total) return false;
+  b = 0;
+  while (b + 1 < bs.nb && o >= 2 * bs.b[b + 1].ev_off) ++b;
+  const int local = o - 2 * bs.b[b].ev_off;
+  role = local >= bs.b[b].n ? 1 : 0;
+  i = local - role * bs.b[b].n;
+  return true;
+}
+
+__global__ void wb_mark_kernel(BatchSet bs, int N, unsigned long long* winkey) {
+  int b, i, role;
+  if (!occ_decode(bs, blockIdx.x * blockDim.x + threadIdx.x, b, i, role)) return;
+  const BatchDesc& bd = bs.b[b];
+  const int node = role ? bd.dst[i] : bd.src[i];
+  const unsigned long long key = 1ull + 2ull * (unsigned long long)(bd.ev_off + i) + (unsigned long long)role;
+  atomicMax(winkey + (size_t)bd.replica * N + node, key);
+}
+
+void writeback_mark(const Dims& d, const BatchSet& bs, unsigned long long* winkey, hipStream_t s) {
+  if (bs.total <= 0) return;
+  hipLaunchKernelGGL(wb_mark_kernel, dim3((2 * bs.total + 255) / 256), dim3(256), 0, s, bs, d.N, winkey);
+}
+
+struct WbPtrs {
+  float *mem, *mail;
+  double *mem_ts, *mail_ts;
+  int32_t* mail_eid;
+  const float *s_new, *s_src, *s_dst;
+  const double *tau, *tau_src, *tau_dst;
+  int p_s;
+};
+
+template <int VEC>
+__global__ __launch_bounds__(256) void wb_scatter_kernel(BatchSet bs, int N, int dm, WbPtrs w,
+                                                         const unsigned long long* __restrict__ winkey,
+                                                         int32_t* __restrict__ out_winner) {
+  const int lane = threadIdx.x & 63;
+  int b, i, role;
+  const int o = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (!occ_decode(bs, o, b, i, role)) return;
+  const BatchDesc& bd = bs.b[b];
+  const int node = role ? bd.dst[i] : bd.src[i];
+  const size_t gid = (size_t)bd.replica * N + node;
+  const unsigned long long key = 1ull + 2ull * (unsigned long long)(bd.ev_off + i) + (unsigned long long)role;
+  const bool win = winkey[gid] == key;
+  if (lane == 0 && out_winner) out_winner[o] = win ? 1 : 0;
+  if (!win) return;
+  const float *self_row, *other_row;
+  double tau;
+  if (w.s_new) {  // fused layout: rows indexed by root slot [src | dst | neg] of the batch
+    const size_t rs = (size_t)(3 * bd.ev_off + i), rd = (size_t)(3 * bd.ev_off + bd.n + i);
+    self_row = w.s_new + (role ? rd : rs) * w.p_s;
+    other_row = w.s_new + (role ? rs : rd) * w.p_s;
+    tau = w.tau[role ? rd : rs];
+  } else {
+    self_row = (role ? w.s_dst : w.s_src) + (size_t)i * w.p_s;
+    other_row = (role ? w.s_src : w.s_dst) + (size_t)i * w.p_s;
+    tau = role ? w.tau_dst[i] : w.tau_src[i];
+  }
+  wave_copy<VEC>(w.mem + gid * dm, self_row, dm, 0, lane);
+  wave_copy<VEC>(w.mail + gid * 2 * dm, self_row, dm, 0, lane);
+  wave_copy<VEC>(w.mail + gid * 2 * dm + dm, other_row, dm, 0, lane);
+  if (lane == 0) {
+    w.mem_ts[gid] = tau;
+    w.mail_ts[gid] = bd.t[i];
+    w.mail_eid[gid] = bd.eid[i];
+  }
+}
+
+void writeback_scatter(const Dims& d, const BatchSet& bs, const tgnn_state* st, unsigned long long* winkey,
+                       const float* s_new, int p_s, const double* tau, const float* s_src, const float* s_dst,
+                       const double* tau_src, const double* tau_dst, int32_t* out_winner, hipStream_t s) {
+  if (bs.total <= 0) return;
+  WbPtrs w{st->mem, st->mail, st->mem_ts, st->mail_ts, st->mail_eid, s_new, s_src, s_dst, tau, tau_src, tau_dst, p_s};
+  const int blocks = (2 * bs.total + 3) / 4;
+  if (d.dm % 4 == 0 && p_s % 4 == 0)
+    hipLaunchKernelGGL(wb_scatter_kernel<4>, dim3(blocks), dim3(256), 0, s, bs, d.N, d.dm, w, winkey, out_winner);
+  else
+    hipLaunchKernelGGL(wb_scatter_kernel<1>, dim3(blocks), dim3(256), 0, s, bs, d.N, d.dm, w, winkey, out_winner);
+}
+
+__global__ void wb_clear_kernel(BatchSet bs, int N, unsigned long long* winkey) {
+  int b, i, role;
+  if (!occ_decode(bs, blockIdx.x * blockDim.x + threadIdx.x, b, i, role)) return;
+  const BatchDesc& bd = bs.b[b];
+  const int node = role ? bd.dst[i] : bd.src[i];
+  winkey[(size_t)bd.replica * N + node] = 0ull;
+}
+
+void writeback_clear(const Dims& d, const BatchSet& bs, unsigned long long* winkey, hipStream_t s) {
+  if (bs.total <= 0) return;
+  hipLaunchKernelGGL(wb_clear_kernel, dim3((2 * bs.total + 255) / 256), dim3(256), 0, s, bs, d.N, winkey);
+}
+
+}  // namespace tgnn

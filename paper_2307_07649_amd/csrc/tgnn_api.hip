@@ -1,0 +1,579 @@
+// C-ABI entry points of libtgnn: argument validation, workspace layout, and the stream-ordered kernel
+// sequence of each call.  See include/tgnn.h for the contract of every function.
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <new>
+#include <vector>
+
+#include "tgnn_internal.h"
+
+namespace tgnn {
+
+static thread_local char g_err[512] = "";
+
+int set_error(int code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+#define REQ_PTR(p)                                                                      \
+  do {                                                                                  \
+    if ((p) == nullptr) return tgnn::set_error(TGNN_E_NULL_PTR, "%s is NULL", #p);      \
+    if (!tgnn::aligned16(p)) return tgnn::set_error(TGNN_E_MISALIGNED, "%s is not 16-byte aligned", #p); \
+  } while (0)
+#define OPT_PTR(p)                                                                      \
+  do {                                                                                  \
+    if ((p) != nullptr && !tgnn::aligned16(p))                                          \
+      return tgnn::set_error(TGNN_E_MISALIGNED, "%s is not 16-byte aligned", #p);       \
+  } while (0)
+
+static int check_params(const tgnn_params* p, const char* what) {
+  if (p == nullptr) return set_error(TGNN_E_NULL_PTR, "%s is NULL", what);
+  const float* const* f = reinterpret_cast<const float* const*>(p);
+  static const char* names[] = {"time_w", "time_b", "gru_wih", "gru_whh", "gru_bih", "gru_bhh", "wq", "bq", "wk", "bk",
+                                "wv", "bv", "wo", "bo", "dec_ws", "dec_wd", "dec_b1", "dec_w2", "dec_b2"};
+  for (int i = 0; i < 19; ++i) {
+    if (f[i] == nullptr) return set_error(TGNN_E_NULL_PTR, "%s.%s is NULL", what, names[i]);
+    if (!aligned16(f[i])) return set_error(TGNN_E_MISALIGNED, "%s.%s is not 16-byte aligned", what, names[i]);
+  }
+  return TGNN_OK;
+}
+
+static int check_graph(const tgnn_ctx* ctx, const tgnn_graph* g) {
+  if (g == nullptr) return set_error(TGNN_E_NULL_PTR, "graph is NULL");
+  REQ_PTR(g->indptr);
+  REQ_PTR(g->nbr);
+  REQ_PTR(g->eid);
+  REQ_PTR(g->ts);
+  if (ctx->d.de > 0) REQ_PTR(g->efeat);
+  if (g->n_events < 0) return set_error(TGNN_E_INVALID_ARG, "graph.n_events < 0");
+  return TGNN_OK;
+}
+
+static int check_state(const tgnn_ctx* ctx, const tgnn_state* st) {
+  if (st == nullptr) return set_error(TGNN_E_NULL_PTR, "state is NULL");
+  REQ_PTR(st->mem);
+  REQ_PTR(st->mem_ts);
+  REQ_PTR(st->mail);
+  REQ_PTR(st->mail_ts);
+  REQ_PTR(st->mail_eid);
+  if (ctx->d.ds > 0) REQ_PTR(st->stat);
+  return TGNN_OK;
+}
+
+// Bump allocator over the arena; first pass (base == nullptr) only measures.
+struct Bump {
+  char* base;
+  size_t off = 0;
+  template <typename T>
+  T* take(size_t n) {
+    off = (off + 255) & ~size_t(255);
+    T* p = base ? reinterpret_cast<T*>(base + off) : nullptr;
+    off += n * sizeof(T);
+    return p;
+  }
+};
+
+static void layout(const Dims& d, Ws& w, Bump& b) {
+  const size_t R = d.maxR, RK = d.maxRK, S = d.maxS, B2 = 2 * (size_t)d.maxEv;
+  w.root_node = b.take<int32_t>(R); w.root_gid = b.take<int32_t>(R); w.root_batch = b.take<int32_t>(R);
+  w.root_t = b.take<double>(R);
+  w.nbr = b.take<int32_t>(RK); w.neid = b.take<int32_t>(RK); w.cnt = b.take<int32_t>(R); w.nts = b.take<double>(RK);
+  w.slot_gid = b.take<int32_t>(S); w.slot_node = b.take<int32_t>(S); w.has = b.take<int32_t>(S);
+  w.tau = b.take<double>(S); w.delta = b.take<double>(S); w.dtk = b.take<double>(RK);
+  w.winkey = b.take<unsigned long long>((size_t)d.nrep * d.N);
+  w.X = b.take<float>(S * d.ldx); w.Hm = b.take<float>(S * d.ldh);
+  w.gi = b.take<float>(S * d.ld3); w.gh = b.take<float>(S * d.ld3);
+  w.gates = b.take<float>(S * 4 * d.ldh); w.s_new = b.take<float>(S * d.ldh);
+  w.dgi = b.take<float>(S * d.ld3); w.dgh = b.take<float>(S * d.ld3); w.dphi_g = b.take<float>(S * d.ldt);
+  w.Cmat = b.take<float>(RK * d.ldc); w.Qin = b.take<float>(R * d.ldq); w.KV = b.take<float>(RK * d.ldkv);
+  w.q = b.take<float>(R * d.ldh); w.prob = b.take<float>(R * d.H * d.k); w.Min = b.take<float>(R * d.ldm);
+  w.z = b.take<float>(R * d.ldh);
+  w.dz = b.take<float>(R * d.ldh); w.dMin = b.take<float>(R * d.ldm); w.dq = b.take<float>(R * d.ldh);
+  w.dKV = b.take<float>(RK * d.ldkv); w.dCsub = b.take<float>(RK * d.ldsub); w.dQsub = b.take<float>(R * d.ldsub);
+  w.Adec = b.take<float>(B2 * d.ldkv); w.h1 = b.take<float>(B2 * d.ldh); w.dh1 = b.take<float>(B2 * d.ldh);
+  w.dAdec = b.take<float>(B2 * d.ldkv); w.logits = b.take<float>(B2); w.dlogit = b.take<float>(B2);
+  w.loss_acc = b.take<float>(TGNN_MAX_BATCHES);
+  w.Wih_p = b.take<float>((size_t)3 * d.dm * d.ldx); w.Whh_p = b.take<float>((size_t)3 * d.dm * d.ldh);
+  w.Wkv_p = b.take<float>((size_t)2 * d.dO * d.ldc); w.Wq_p = b.take<float>((size_t)d.dO * d.ldq);
+  w.Wo_p = b.take<float>((size_t)d.dO * d.ldm); w.Wdec_p = b.take<float>((size_t)d.dO * d.ldkv);
+  w.bkv_p = b.take<float>((size_t)2 * d.dO);
+  w.WdecT = b.take<float>((size_t)2 * d.dO * d.ldh); w.WoT = b.take<float>((size_t)(d.dO + d.dx) * d.ldh);
+  w.WkvT_sub = b.take<float>((size_t)(d.dm + d.dt) * d.ldkv); w.WqT_sub = b.take<float>((size_t)(d.dm + d.dt) * d.ldh);
+  w.WihT_phi = b.take<float>((size_t)d.dt * d.ld3);
+  b.take<char>(256);
+}
+
+static OutMap single_out(float* g, int ld, float* bias) {
+  OutMap o;
+  memset(&o, 0, sizeof(o));
+  o.p[0][0] = g; o.ld[0][0] = ld;
+  o.n_split = 1 << 30; o.k_split = 1 << 30;
+  o.bias[0] = bias;
+  return o;
+}
+
+// UPDT on n rows already staged in ws.X / ws.Hm / ws.has: projections (MFMA) + gates.
+static void gru_forward(tgnn_ctx* ctx, const tgnn_params* p, int n, hipStream_t s) {
+  const Dims& d = ctx->d; Ws& w = ctx->w;
+  gemm_nt(w.X, d.ldx, w.Wih_p, d.ldx, p->gru_bih, w.gi, d.ld3, n, 3 * d.dm, d.ldx, d.ld3, false, s);
+  gemm_nt(w.Hm, d.ldh, w.Whh_p, d.ldh, p->gru_bhh, w.gh, d.ld3, n, 3 * d.dm, d.ldh, d.ld3, false, s);
+  gru_gates_fwd(d, n, w.gi, w.gh, w.Hm, w.has, w.gates, w.s_new, s);
+}
+
+// Projections, per-root softmax attention and the merge layer from ws.Cmat / ws.Qin / ws.Min[:, dO:].
+static void attn_forward(tgnn_ctx* ctx, const tgnn_params* p, int R, const int32_t* cnt, hipStream_t s) {
+  const Dims& d = ctx->d; Ws& w = ctx->w;
+  const int RK = R * d.k;
+  gemm_nt(w.Cmat, d.ldc, w.Wkv_p, d.ldc, w.bkv_p, w.KV, d.ldkv, RK, 2 * d.dO, d.ldc, d.ldkv, false, s);
+  gemm_nt(w.Qin, d.ldq, w.Wq_p, d.ldq, p->bq, w.q, d.ldh, R, d.dO, d.ldq, d.ldh, false, s);
+  attn_core_fwd(d, R, w.q, d.ldh, w.KV, d.ldkv, cnt, w.prob, w.Min, d.ldm, s);
+  gemm_nt(w.Min, d.ldm, w.Wo_p, d.ldm, p->bo, w.z, d.ldh, R, d.dO, d.ldm, d.ldh, true, s);
+}
+
+// From ws.dz (already masked by the merge ReLU) down to ws.dMin / ws.dQsub / ws.dCsub, adding the
+// gradients of W_o, W_q, W_k, W_v, their biases and the time encoding.
+static void attn_backward(tgnn_ctx* ctx, tgnn_params* g, const tgnn_params* p, int R, const int32_t* cnt,
+                          hipStream_t s) {
+  const Dims& d = ctx->d; Ws& w = ctx->w;
+  const int RK = R * d.k;
+  gemm_tn_acc(w.dz, d.ldh, w.Min, d.ldm, R, d.dO, d.dO + d.dx, single_out(g->wo, d.dO + d.dx, g->bo), s);
+  gemm_nt(w.dz, d.ldh, w.WoT, d.ldh, nullptr, w.dMin, d.ldm, R, d.dO + d.dx, d.ldh, d.ldm, false, s);
+  attn_core_bwd(d, R, w.q, d.ldh, w.KV, d.ldkv, cnt, w.prob, w.dMin, d.ldm, w.dq, w.dKV, s);
+  OutMap kv;
+  memset(&kv, 0, sizeof(kv));
+  kv.p[0][0] = g->wk; kv.p[1][0] = g->wv; kv.ld[0][0] = kv.ld[1][0] = d.dkv;
+  kv.n_split = d.dO; kv.k_split = 1 << 30;
+  kv.bias[0] = g->bk; kv.bias[1] = g->bv;
+  gemm_tn_acc(w.dKV, d.ldkv, w.Cmat, d.ldc, RK, 2 * d.dO, d.dkv, kv, s);
+  gemm_nt(w.dKV, d.ldkv, w.WkvT_sub, d.ldkv, nullptr, w.dCsub, d.ldsub, RK, d.dm + d.dt, d.ldkv, d.ldsub, false, s);
+  gemm_tn_acc(w.dq, d.ldh, w.Qin, d.ldq, R, d.dO, d.dq, single_out(g->wq, d.dq, g->bq), s);
+  gemm_nt(w.dq, d.ldh, w.WqT_sub, d.ldh, nullptr, w.dQsub, d.ldsub, R, d.dm + d.dt, d.ldh, d.ldsub, false, s);
+  time_grad(w.dCsub, d.ldsub, d.dm, w.dtk, nullptr, RK, d.dt, p->time_w, p->time_b, g->time_w, g->time_b, s);
+  time_grad(w.dQsub, d.ldsub, d.dm, nullptr, nullptr, R, d.dt, p->time_w, p->time_b, g->time_w, g->time_b, s);
+}
+
+static hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
+
+}  // namespace tgnn
+
+using namespace tgnn;
+
+extern "C" {
+
+const char* tgnn_last_error(void) { return g_err; }
+
+int32_t tgnn_create(const tgnn_config* cfg, tgnn_ctx** out) {
+  if (cfg == nullptr || out == nullptr) return set_error(TGNN_E_NULL_PTR, "cfg or out is NULL");
+  *out = nullptr;
+  if (cfg->n_nodes <= 0 || cfg->max_batch <= 0 || cfg->n_replicas <= 0)
+    return set_error(TGNN_E_INVALID_ARG, "n_nodes, max_batch and n_replicas must be positive");
+  if (cfg->d_mem <= 0 || cfg->d_time <= 0 || cfg->d_edge < 0 || cfg->d_static < 0 || cfg->n_heads <= 0 || cfg->k <= 0)
+    return set_error(TGNN_E_UNSUPPORTED_DIM, "d_mem, d_time, n_heads, k must be positive; d_edge, d_static >= 0");
+  if (cfg->k > TGNN_MAX_K) return set_error(TGNN_E_UNSUPPORTED_DIM, "k = %d exceeds TGNN_MAX_K = %d", cfg->k, TGNN_MAX_K);
+  if (cfg->n_heads > TGNN_MAX_HEADS)
+    return set_error(TGNN_E_UNSUPPORTED_DIM, "n_heads = %d exceeds TGNN_MAX_HEADS = %d", cfg->n_heads, TGNN_MAX_HEADS);
+  if (cfg->d_mem % cfg->n_heads != 0)
+    return set_error(TGNN_E_UNSUPPORTED_DIM, "d_mem = %d is not a multiple of n_heads = %d", cfg->d_mem, cfg->n_heads);
+  if (cfg->d_mem > 256 || cfg->d_time > 1024 || cfg->d_edge > 4096 || cfg->d_static > 4096)
+    return set_error(TGNN_E_UNSUPPORTED_DIM, "width too large (d_mem <= 256, d_time <= 1024, d_edge, d_static <= 4096)");
+  if (4LL * 4 * (cfg->d_mem + (long long)cfg->k * (cfg->d_mem + 1) + 2LL * cfg->n_heads * cfg->k) > 64 * 1024)
+    return set_error(TGNN_E_UNSUPPORTED_DIM, "k * d_mem too large for the attention kernel's LDS staging");
+  if (cfg->dt_source != 0 && cfg->dt_source != 1) return set_error(TGNN_E_INVALID_ARG, "dt_source must be 0 or 1");
+  if ((long long)cfg->n_nodes * cfg->n_replicas > 0x7fffffffLL)
+    return set_error(TGNN_E_OUT_OF_RANGE, "n_nodes * n_replicas exceeds int32");
+
+  tgnn_ctx* ctx = new (std::nothrow) tgnn_ctx();
+  if (ctx == nullptr) return set_error(TGNN_E_WORKSPACE, "out of host memory");
+  ctx->cfg = *cfg;
+  Dims& d = ctx->d;
+  d.N = cfg->n_nodes; d.dm = cfg->d_mem; d.dt = cfg->d_time; d.de = cfg->d_edge; d.ds = cfg->d_static;
+  d.H = cfg->n_heads; d.k = cfg->k; d.nrep = cfg->n_replicas; d.maxB = cfg->max_batch; d.dt_source = cfg->dt_source;
+  d.d_in = 2 * d.dm + d.dt + d.de; d.dx = d.dm + d.ds; d.dq = d.dx + d.dt; d.dkv = d.dx + d.de + d.dt; d.dO = d.dm;
+  d.ldx = pad16(d.d_in); d.ldh = pad16(d.dm); d.ld3 = pad16(3 * d.dm); d.ldc = pad16(d.dkv); d.ldq = pad16(d.dq);
+  d.ldkv = pad16(2 * d.dO); d.ldm = pad16(d.dO + d.dx); d.ldsub = pad16(d.dm + d.dt); d.ldt = pad16(d.dt);
+  const int nb = d.nrep < TGNN_MAX_BATCHES ? d.nrep : TGNN_MAX_BATCHES;
+  const long long maxEv = (long long)d.maxB * nb;
+  if (maxEv * 3 * (1 + d.k) > 0x3fffffffLL) {
+    delete ctx;
+    return set_error(TGNN_E_OUT_OF_RANGE, "max_batch * n_replicas * 3 * (1 + k) exceeds the slot index range");
+  }
+  d.maxEv = (int)maxEv; d.maxR = 3 * d.maxEv; d.maxRK = d.maxR * d.k; d.maxS = d.maxR + d.maxRK;
+
+  Bump measure{nullptr};
+  layout(d, ctx->w, measure);
+  ctx->arena_bytes = measure.off;
+  hipError_t e = hipGetDevice(&ctx->device);
+  if (e == hipSuccess) e = hipMalloc(&ctx->arena, ctx->arena_bytes);
+  if (e != hipSuccess) {
+    delete ctx;
+    return set_error(e == hipErrorOutOfMemory ? TGNN_E_WORKSPACE : TGNN_E_HIP, "workspace allocation of %zu bytes failed: %s",
+                     measure.off, hipGetErrorString(e));
+  }
+  e = hipMemset(ctx->arena, 0, ctx->arena_bytes);
+  if (e != hipSuccess) {
+    (void)hipFree(ctx->arena);
+    delete ctx;
+    return set_error(TGNN_E_HIP, "workspace clear failed: %s", hipGetErrorString(e));
+  }
+  Bump place{static_cast<char*>(ctx->arena)};
+  layout(d, ctx->w, place);
+  ctx->last_attn_roots = -1;
+  *out = ctx;
+  return TGNN_OK;
+}
+
+int32_t tgnn_destroy(tgnn_ctx* ctx) {
+  if (ctx == nullptr) return TGNN_OK;
+  hipError_t e = hipDeviceSynchronize();
+  hipError_t e2 = hipFree(ctx->arena);
+  delete ctx;
+  if (e != hipSuccess) return set_error(TGNN_E_HIP, "hipDeviceSynchronize: %s", hipGetErrorString(e));
+  if (e2 != hipSuccess) return set_error(TGNN_E_HIP, "hipFree: %s", hipGetErrorString(e2));
+  return TGNN_OK;
+}
+
+int64_t tgnn_workspace_bytes(const tgnn_ctx* ctx) { return ctx ? (int64_t)ctx->arena_bytes : 0; }
+
+int32_t tgnn_build_tcsr(const int32_t* src, const int32_t* dst, const double* ts, int64_t n_events, int32_t n_nodes,
+                        int64_t* indptr, int32_t* nbr, int32_t* eid, double* ts_out) {
+  if (!src || !dst || !ts || !indptr || !nbr || !eid || !ts_out) return set_error(TGNN_E_NULL_PTR, "NULL argument");
+  if (n_events < 0 || n_nodes <= 0 || n_events > 0x3fffffffLL) return set_error(TGNN_E_INVALID_ARG, "bad sizes");
+  for (int64_t e = 0; e < n_events; ++e) {
+    if (src[e] < 0 || src[e] >= n_nodes || dst[e] < 0 || dst[e] >= n_nodes)
+      return set_error(TGNN_E_OUT_OF_RANGE, "event %lld has an endpoint outside [0, %d)", (long long)e, n_nodes);
+    if (e > 0 && !(ts[e] >= ts[e - 1]))
+      return set_error(TGNN_E_UNSORTED_TS, "timestamps decrease (or are NaN) at event %lld", (long long)e);
+  }
+  // counting sort by node; events are visited in (time, id) order, source entry before destination entry,
+  // so every list ascends in (time, event id)
+  for (int32_t v = 0; v <= n_nodes; ++v) indptr[v] = 0;
+  for (int64_t e = 0; e < n_events; ++e) { indptr[src[e] + 1]++; indptr[dst[e] + 1]++; }
+  for (int32_t v = 0; v < n_nodes; ++v) indptr[v + 1] += indptr[v];
+  std::vector<int64_t> cur(indptr, indptr + n_nodes);
+  for (int64_t e = 0; e < n_events; ++e) {
+    int64_t a = cur[src[e]]++;
+    nbr[a] = dst[e]; eid[a] = (int32_t)e; ts_out[a] = ts[e];
+    int64_t b = cur[dst[e]]++;
+    nbr[b] = src[e]; eid[b] = (int32_t)e; ts_out[b] = ts[e];
+  }
+  return TGNN_OK;
+}
+
+int32_t tgnn_state_reset(tgnn_ctx* ctx, tgnn_state* st, int32_t replica, void* stream) {
+  if (ctx == nullptr) return set_error(TGNN_E_NULL_PTR, "ctx is NULL");
+  if (int rc = check_state(ctx, st)) return rc;
+  if (replica < -1 || replica >= ctx->d.nrep) return set_error(TGNN_E_OUT_OF_RANGE, "replica %d out of range", replica);
+  fill_state(ctx, st, replica, as_stream(stream));
+  TGNN_LAUNCH_CHECK();
+  return TGNN_OK;
+}
+
+int32_t tgnn_sample_recent(tgnn_ctx* ctx, const tgnn_graph* g, const int32_t* node, const double* t, int32_t n_roots,
+                           int32_t* out_nbr, int32_t* out_eid, double* out_ts, int32_t* out_cnt, void* stream) {
+  if (ctx == nullptr) return set_error(TGNN_E_NULL_PTR, "ctx is NULL");
+  if (int rc = check_graph(ctx, g)) return rc;
+  if (n_roots < 0) return set_error(TGNN_E_INVALID_ARG, "n_roots < 0");
+  if (n_roots == 0) return TGNN_OK;
+  REQ_PTR(node); REQ_PTR(t); REQ_PTR(out_nbr); REQ_PTR(out_eid); REQ_PTR(out_ts); REQ_PTR(out_cnt);
+  sample_recent(ctx->d, g, node, t, nullptr, n_roots, out_nbr, out_eid, out_ts, out_cnt, nullptr, nullptr,
+                as_stream(stream));
+  TGNN_LAUNCH_CHECK();
+  return TGNN_OK;
+}
+
+int32_t tgnn_gather_memory(tgnn_ctx* ctx, const tgnn_graph* g, const tgnn_state* st, int32_t replica,
+                           const int32_t* slot_node, int32_t n_slots, float* out_mem, float* out_mail,
+                           float* out_mail_efeat, double* out_mem_ts, double* out_mail_ts, int32_t* out_has_mail,
+                           void* stream) {
+  if (ctx == nullptr) return set_error(TGNN_E_NULL_PTR, "ctx is NULL");
+  if (int rc = check_graph(ctx, g)) return rc;
+  if (int rc = check_state(ctx, st)) return rc;
+  const Dims& d = ctx->d;
+  if (replica < 0 || replica >= d.nrep) return set_error(TGNN_E_OUT_OF_RANGE, "replica %d out of range", replica);
+  if (n_slots < 0) return set_error(TGNN_E_INVALID_ARG, "n_slots < 0");
+  if (n_slots == 0) return TGNN_OK;
+  REQ_PTR(slot_node); REQ_PTR(out_mem); REQ_PTR(out_mail); REQ_PTR(out_mem_ts); REQ_PTR(out_mail_ts);
+  REQ_PTR(out_has_mail);
+  if (d.de > 0) REQ_PTR(out_mail_efeat);
+  GatherArgs a;
+  memset(&a, 0, sizeof(a));
+  a.mem = st->mem; a.mail = st->mail; a.efeat = g->efeat; a.mem_ts = st->mem_ts; a.mail_ts = st->mail_ts;
+  a.mail_eid = st->mail_eid; a.slot_gid = slot_node; a.gid_add = replica * d.N;
+  a.o_mem = out_mem; a.p_mem = d.dm; a.o_mail = out_mail; a.p_mail = 2 * d.dm;
+  a.o_ef = d.de > 0 ? out_mail_efeat : nullptr; a.p_ef = d.de;
+  a.o_mem_ts = out_mem_ts; a.o_mail_ts = out_mail_ts; a.o_has = out_has_mail;
+  a.n_slots = n_slots; a.dm = d.dm; a.dt = d.dt; a.de = d.de;
+  gather_rows(a, as_stream(stream));
+  TGNN_LAUNCH_CHECK();
+  return TGNN_OK;
+}
+
+int32_t tgnn_gru_update(tgnn_ctx* ctx, const tgnn_params* p, int32_t n_slots, const float* mem, const float* mail,
+                        const float* mail_efeat, const double* mem_ts, const double* mail_ts, const int32_t* has_mail,
+                        float* out_s_new, double* out_tau, void* stream) {
+  if (ctx == nullptr) return set_error(TGNN_E_NULL_PTR, "ctx is NULL");
+  if (int rc = check_params(p, "params")) return rc;
+  const Dims& d = ctx->d; Ws& w = ctx->w;
+  if (n_slots < 0 || n_slots > d.maxS)
+    return set_error(TGNN_E_WORKSPACE, "n_slots = %d outside [0, %d] (workspace slot capacity)", n_slots, d.maxS);
+  if (n_slots == 0) return TGNN_OK;
+  REQ_PTR(mem); REQ_PTR(mail); REQ_PTR(mem_ts); REQ_PTR(mail_ts); REQ_PTR(has_mail); REQ_PTR(out_s_new); REQ_PTR(out_tau);
+  if (d.de > 0) REQ_PTR(mail_efeat);
+  hipStream_t s = as_stream(stream);
+  pack_all(ctx, p, s);
+  GatherArgs a;
+  memset(&a, 0, sizeof(a));
+  a.mem = mem; a.mail = mail; a.efeat = mail_efeat; a.mem_ts = mem_ts; a.mail_ts = mail_ts;
+  a.mail_eid = nullptr; a.has_in = has_mail; a.slot_gid = nullptr;
+  a.o_mem = w.Hm; a.p_mem = d.ldh; a.z_mem = d.ldh - d.dm;
+  a.o_mail = w.X; a.p_mail = d.ldx;
+  a.o_phi = w.X + 2 * d.dm; a.p_phi = d.ldx;
+  a.o_ef = w.X + 2 * d.dm + d.dt; a.p_ef = d.ldx; a.z_ef = d.ldx - d.d_in;
+  a.o_tau = out_tau; a.o_delta = w.delta; a.o_has = w.has;
+  a.time_w = p->time_w; a.time_b = p->time_b;
+  a.n_slots = n_slots; a.dm = d.dm; a.dt = d.dt; a.de = d.de;
+  gather_rows(a, s);
+  gru_forward(ctx, p, n_slots, s);
+  TGNN_HIP_CHECK(hipMemcpy2DAsync(out_s_new, (size_t)d.dm * 4, w.s_new, (size_t)d.ldh * 4, (size_t)d.dm * 4, n_slots,
+                                  hipMemcpyDeviceToDevice, s));
+  TGNN_LAUNCH_CHECK();
+  return TGNN_OK;
+}
+
+int32_t tgnn_temporal_attn_fwd(tgnn_ctx* ctx, const tgnn_params* p, int32_t n_roots, const float* x_root,
+                               const float* x_nbr, const float* e_nbr, const double* dt_nbr, const int32_t* cnt,
+                               float* out_z, void* stream) {
+  if (ctx == nullptr) return set_error(TGNN_E_NULL_PTR, "ctx is NULL");
+  if (int rc = check_params(p, "params")) return rc;
+  const Dims& d = ctx->d; Ws& w = ctx->w;
+  if (n_roots < 0 || n_roots > d.maxR)
+    return set_error(TGNN_E_WORKSPACE, "n_roots = %d outside [0, %d] (workspace root capacity)", n_roots, d.maxR);
+  if (n_roots == 0) { ctx->last_attn_roots = 0; return TGNN_OK; }
+  REQ_PTR(x_root); REQ_PTR(x_nbr); REQ_PTR(dt_nbr); REQ_PTR(cnt); REQ_PTR(out_z);
+  if (d.de > 0) REQ_PTR(e_nbr);
+  hipStream_t s = as_stream(stream);
+  pack_all(ctx, p, s);
+  TGNN_HIP_CHECK(hipMemcpyAsync(w.cnt, cnt, sizeof(int32_t) * n_roots, hipMemcpyDeviceToDevice, s));
+  AttnAssembleArgs a;
+  memset(&a, 0, sizeof(a));
+  a.s_root = x_root; a.s_nbr = x_nbr; a.p_s = d.dx;
+  a.stat = nullptr; a.efeat = e_nbr; a.neid = nullptr; a.cnt = cnt; a.dt_in = dt_nbr;
+  a.time_w = p->time_w; a.time_b = p->time_b;
+  a.Cmat = w.Cmat; a.Qin = w.Qin; a.Min = w.Min; a.ldc = d.ldc; a.ldq = d.ldq; a.ldm = d.ldm; a.dtk = w.dtk;
+  a.R = n_roots; a.k = d.k; a.dm = d.dx; a.ds = 0; a.de = d.de; a.dt = d.dt; a.dO = d.dO; a.dt_source = 0;
+  attn_assemble(a, s);
+  attn_forward(ctx, p, n_roots, w.cnt, s);
+  TGNN_HIP_CHECK(hipMemcpy2DAsync(out_z, (size_t)d.dO * 4, w.z, (size_t)d.ldh * 4, (size_t)d.dO * 4, n_roots,
+                                  hipMemcpyDeviceToDevice, s));
+  TGNN_LAUNCH_CHECK();
+  ctx->last_attn_roots = n_roots;
+  return TGNN_OK;
+}
+
+int32_t tgnn_temporal_attn_bwd(tgnn_ctx* ctx, const tgnn_params* p, int32_t n_roots, const float* dz, tgnn_params* grads,
+                               float* d_x_root, float* d_x_nbr, void* stream) {
+  if (ctx == nullptr) return set_error(TGNN_E_NULL_PTR, "ctx is NULL");
+  if (int rc = check_params(p, "params")) return rc;
+  if (int rc = check_params(grads, "grads")) return rc;
+  const Dims& d = ctx->d; Ws& w = ctx->w;
+  if (n_roots != ctx->last_attn_roots)
+    return set_error(TGNN_E_INVALID_ARG, "n_roots = %d does not match the last tgnn_temporal_attn_fwd (%d)", n_roots,
+                     ctx->last_attn_roots);
+  if (n_roots == 0) return TGNN_OK;
+  REQ_PTR(dz); REQ_PTR(d_x_root); REQ_PTR(d_x_nbr);
+  hipStream_t s = as_stream(stream);
+  mask_dz(n_roots, d.dO, dz, d.dO, w.z, d.ldh, w.dz, s);
+  attn_backward(ctx, grads, p, n_roots, w.cnt, s);
+  attn_dx_out(n_roots, n_roots * d.k, d.dm, d.dO, w.dMin, d.ldm, w.dQsub, w.dCsub, d.ldsub, d_x_root, d_x_nbr, s);
+  TGNN_LAUNCH_CHECK();
+  return TGNN_OK;
+}
+
+static int make_batchset(const tgnn_ctx* ctx, const tgnn_batch* batches, int n_batches, BatchSet& bs) {
+  const Dims& d = ctx->d;
+  if (batches == nullptr) return set_error(TGNN_E_NULL_PTR, "batches is NULL");
+  const int cap = d.nrep < TGNN_MAX_BATCHES ? d.nrep : TGNN_MAX_BATCHES;
+  if (n_batches < 1 || n_batches > cap)
+    return set_error(TGNN_E_INVALID_ARG, "n_batches = %d outside [1, %d]", n_batches, cap);
+  memset(&bs, 0, sizeof(bs));
+  int off = 0;
+  unsigned seen = 0;
+  for (int b = 0; b < n_batches; ++b) {
+    const tgnn_batch& tb = batches[b];
+    if (tb.n < 0 || tb.n > d.maxB) return set_error(TGNN_E_OUT_OF_RANGE, "batch %d: n = %d outside [0, %d]", b, tb.n, d.maxB);
+    if (tb.replica < 0 || tb.replica >= d.nrep)
+      return set_error(TGNN_E_OUT_OF_RANGE, "batch %d: replica %d outside [0, %d)", b, tb.replica, d.nrep);
+    if (tb.replica < 32) {
+      if (seen & (1u << tb.replica)) return set_error(TGNN_E_INVALID_ARG, "replica %d appears twice in one step", tb.replica);
+      seen |= 1u << tb.replica;
+    }
+    if (tb.n > 0) {
+      REQ_PTR(tb.src); REQ_PTR(tb.dst); REQ_PTR(tb.eid); REQ_PTR(tb.t);
+    }
+    bs.b[b] = BatchDesc{tb.src, tb.dst, tb.neg, tb.eid, tb.t, tb.n, tb.replica, off};
+    off += tb.n;
+  }
+  bs.nb = n_batches;
+  bs.total = off;
+  return TGNN_OK;
+}
+
+int32_t tgnn_memory_writeback(tgnn_ctx* ctx, tgnn_state* st, int32_t replica, const int32_t* src, const int32_t* dst,
+                              const int32_t* eid, const double* t, int32_t n_events, const float* s_new_src,
+                              const float* s_new_dst, const double* tau_src, const double* tau_dst,
+                              int32_t* out_winner, void* stream) {
+  if (ctx == nullptr) return set_error(TGNN_E_NULL_PTR, "ctx is NULL");
+  if (int rc = check_state(ctx, st)) return rc;
+  const Dims& d = ctx->d;
+  if (replica < 0 || replica >= d.nrep) return set_error(TGNN_E_OUT_OF_RANGE, "replica %d out of range", replica);
+  if (n_events < 0 || n_events > d.maxB)
+    return set_error(TGNN_E_OUT_OF_RANGE, "n_events = %d outside [0, %d]", n_events, d.maxB);
+  if (n_events == 0) return TGNN_OK;
+  REQ_PTR(src); REQ_PTR(dst); REQ_PTR(eid); REQ_PTR(t); REQ_PTR(s_new_src); REQ_PTR(s_new_dst); REQ_PTR(tau_src);
+  REQ_PTR(tau_dst); OPT_PTR(out_winner);
+  BatchSet bs;
+  memset(&bs, 0, sizeof(bs));
+  bs.b[0] = BatchDesc{src, dst, nullptr, eid, t, n_events, replica, 0};
+  bs.nb = 1; bs.total = n_events;
+  hipStream_t s = as_stream(stream);
+  writeback_mark(d, bs, ctx->w.winkey, s);
+  writeback_scatter(d, bs, st, ctx->w.winkey, nullptr, d.dm, nullptr, s_new_src, s_new_dst, tau_src, tau_dst, out_winner, s);
+  writeback_clear(d, bs, ctx->w.winkey, s);
+  TGNN_LAUNCH_CHECK();
+  return TGNN_OK;
+}
+
+int32_t tgnn_train_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, const tgnn_params* p, tgnn_params* grads,
+                        const tgnn_batch* batches, int32_t n_batches, float lr, float* out_loss, float* out_logits,
+                        int32_t* out_winner, void* stream) {
+  if (ctx == nullptr) return set_error(TGNN_E_NULL_PTR, "ctx is NULL");
+  if (int rc = check_graph(ctx, g)) return rc;
+  if (int rc = check_state(ctx, st)) return rc;
+  if (int rc = check_params(p, "params")) return rc;
+  if (int rc = check_params(grads, "grads")) return rc;
+  BatchSet bs;
+  if (int rc = make_batchset(ctx, batches, n_batches, bs)) return rc;
+  for (int b = 0; b < bs.nb; ++b)
+    if (bs.b[b].n > 0) REQ_PTR(bs.b[b].neg);
+  REQ_PTR(out_loss); OPT_PTR(out_logits); OPT_PTR(out_winner);
+  if (!(lr == lr)) return set_error(TGNN_E_INVALID_ARG, "lr is NaN");
+  const Dims& d = ctx->d; Ws& w = ctx->w;
+  hipStream_t s = as_stream(stream);
+  zero_f32(out_loss, 1, s);
+  if (bs.total == 0) { TGNN_LAUNCH_CHECK(); return TGNN_OK; }
+  const int R = 3 * bs.total, RK = R * d.k, S = R + RK, B2 = 2 * bs.total;
+
+  pack_all(ctx, p, s);
+  build_roots(ctx, bs, s);
+  writeback_mark(d, bs, w.winkey, s);
+  sample_recent(d, g, w.root_node, w.root_t, w.root_gid, R, w.nbr, w.neid, w.nts, w.cnt, w.slot_gid, w.slot_node, s);
+
+  // UPDT for root and supporting nodes from the pre-batch state
+  GatherArgs a;
+  memset(&a, 0, sizeof(a));
+  a.mem = st->mem; a.mail = st->mail; a.efeat = g->efeat; a.mem_ts = st->mem_ts; a.mail_ts = st->mail_ts;
+  a.mail_eid = st->mail_eid; a.slot_gid = w.slot_gid; a.gid_add = 0;
+  a.o_mem = w.Hm; a.p_mem = d.ldh; a.z_mem = d.ldh - d.dm;
+  a.o_mail = w.X; a.p_mail = d.ldx;
+  a.o_phi = w.X + 2 * d.dm; a.p_phi = d.ldx;
+  a.o_ef = w.X + 2 * d.dm + d.dt; a.p_ef = d.ldx; a.z_ef = d.ldx - d.d_in;
+  a.o_tau = w.tau; a.o_delta = w.delta; a.o_has = w.has;
+  a.time_w = p->time_w; a.time_b = p->time_b;
+  a.n_slots = S; a.dm = d.dm; a.dt = d.dt; a.de = d.de;
+  gather_rows(a, s);
+  gru_forward(ctx, p, S, s);
+
+  // attention + merge
+  AttnAssembleArgs aa;
+  memset(&aa, 0, sizeof(aa));
+  aa.s_root = w.s_new; aa.s_nbr = w.s_new + (size_t)R * d.ldh; aa.p_s = d.ldh;
+  aa.stat = st->stat; aa.efeat = g->efeat; aa.root_node = w.root_node; aa.nbr = w.nbr; aa.neid = w.neid; aa.cnt = w.cnt;
+  aa.root_t = w.root_t; aa.nts = w.nts; aa.tau_nbr = w.tau + R; aa.dt_in = nullptr;
+  aa.time_w = p->time_w; aa.time_b = p->time_b;
+  aa.Cmat = w.Cmat; aa.Qin = w.Qin; aa.Min = w.Min; aa.ldc = d.ldc; aa.ldq = d.ldq; aa.ldm = d.ldm; aa.dtk = w.dtk;
+  aa.R = R; aa.k = d.k; aa.dm = d.dm; aa.ds = d.ds; aa.de = d.de; aa.dt = d.dt; aa.dO = d.dO; aa.dt_source = d.dt_source;
+  attn_assemble(aa, s);
+  attn_forward(ctx, p, R, w.cnt, s);
+
+  // decoder + loss (also produces d loss / d hidden)
+  decoder_assemble(d, bs, w.z, d.ldh, w.Adec, d.ldkv, s);
+  gemm_nt(w.Adec, d.ldkv, w.Wdec_p, d.ldkv, p->dec_b1, w.h1, d.ldh, B2, d.dO, d.ldkv, d.ldh, true, s);
+  decoder_loss(d, bs, w.h1, d.ldh, p->dec_w2, p->dec_b2, w.logits, out_loss, w.dh1, grads->dec_w2, grads->dec_b2, s);
+
+  // backward
+  OutMap dec;
+  memset(&dec, 0, sizeof(dec));
+  dec.p[0][0] = grads->dec_ws; dec.p[0][1] = grads->dec_wd; dec.ld[0][0] = dec.ld[0][1] = d.dO;
+  dec.n_split = 1 << 30; dec.k_split = d.dO; dec.bias[0] = grads->dec_b1;
+  gemm_tn_acc(w.dh1, d.ldh, w.Adec, d.ldkv, B2, d.dO, 2 * d.dO, dec, s);
+  gemm_nt(w.dh1, d.ldh, w.WdecT, d.ldh, nullptr, w.dAdec, d.ldkv, B2, 2 * d.dO, d.ldh, d.ldkv, false, s);
+  decoder_dz(d, bs, w.dAdec, d.ldkv, w.z, d.ldh, w.dz, s);
+  attn_backward(ctx, grads, p, R, w.cnt, s);
+  gru_gates_bwd(d, R, S, w.dMin, d.ldm, w.dQsub, w.dCsub, d.ldsub, w.gates, w.Hm, w.has, w.dgi, w.dgh, s);
+  gemm_tn_acc(w.dgi, d.ld3, w.X, d.ldx, S, 3 * d.dm, d.d_in, single_out(grads->gru_wih, d.d_in, grads->gru_bih), s);
+  gemm_tn_acc(w.dgh, d.ld3, w.Hm, d.ldh, S, 3 * d.dm, d.dm, single_out(grads->gru_whh, d.dm, grads->gru_bhh), s);
+  gemm_nt(w.dgi, d.ld3, w.WihT_phi, d.ld3, nullptr, w.dphi_g, d.ldt, S, d.dt, d.ld3, d.ldt, false, s);
+  time_grad(w.dphi_g, d.ldt, 0, w.delta, nullptr, S, d.dt, p->time_w, p->time_b, grads->time_w, grads->time_b, s);
+
+  if (lr != 0.0f) {
+    SgdSet set;
+    memset(&set, 0, sizeof(set));
+    float* const* pp = reinterpret_cast<float* const*>(p);
+    float* const* gg = reinterpret_cast<float* const*>(grads);
+    const int sizes[19] = {d.dt, d.dt, 3 * d.dm * d.d_in, 3 * d.dm * d.dm, 3 * d.dm, 3 * d.dm, d.dO * d.dq, d.dO,
+                           d.dO * d.dkv, d.dO, d.dO * d.dkv, d.dO, d.dO * (d.dO + d.dx), d.dO, d.dO * d.dO, d.dO * d.dO,
+                           d.dO, d.dO, 1};
+    for (int i = 2; i < 19; ++i) {  // time_w, time_b stay frozen
+      set.p[set.cnt] = pp[i]; set.g[set.cnt] = gg[i]; set.n[set.cnt] = sizes[i]; set.cnt++;
+    }
+    sgd_update(set, lr, s);
+  }
+
+  writeback_scatter(d, bs, st, w.winkey, w.s_new, d.ldh, w.tau, nullptr, nullptr, nullptr, nullptr, out_winner, s);
+  writeback_clear(d, bs, w.winkey, s);
+  if (out_logits)
+    TGNN_HIP_CHECK(hipMemcpyAsync(out_logits, w.logits, sizeof(float) * B2, hipMemcpyDeviceToDevice, s));
+  TGNN_LAUNCH_CHECK();
+  ctx->last_attn_roots = -1;
+  return TGNN_OK;
+}
+
+int32_t tgnn_debug_read(tgnn_ctx* ctx, int32_t what, void* dst, int64_t n_bytes, void* stream) {
+  if (ctx == nullptr || dst == nullptr) return set_error(TGNN_E_NULL_PTR, "NULL argument");
+  const Dims& d = ctx->d; Ws& w = ctx->w;
+  const void* src = nullptr;
+  size_t cap = 0;
+  switch (what) {
+    case 0: src = w.nbr; cap = sizeof(int32_t) * d.maxRK; break;
+    case 1: src = w.neid; cap = sizeof(int32_t) * d.maxRK; break;
+    case 2: src = w.nts; cap = sizeof(double) * d.maxRK; break;
+    case 3: src = w.cnt; cap = sizeof(int32_t) * d.maxR; break;
+    case 5: src = w.tau; cap = sizeof(double) * d.maxS; break;
+    case 4: case 6: break;
+    default: return set_error(TGNN_E_INVALID_ARG, "unknown item %d", what);
+  }
+  hipStream_t s = as_stream(stream);
+  if (what == 4 || what == 6) {  // pitched float rows -> dense [rows, d_m]
+    const float* base = what == 4 ? w.s_new : w.z;
+    const size_t max_rows = what == 4 ? d.maxS : d.maxR;
+    const size_t row_b = sizeof(float) * d.dm;
+    if (n_bytes < 0 || (size_t)n_bytes % row_b != 0 || (size_t)n_bytes / row_b > max_rows)
+      return set_error(TGNN_E_OUT_OF_RANGE, "n_bytes is not a whole number of rows within capacity");
+    TGNN_HIP_CHECK(hipMemcpy2DAsync(dst, row_b, base, sizeof(float) * d.ldh, row_b, (size_t)n_bytes / row_b,
+                                    hipMemcpyDeviceToDevice, s));
+    return TGNN_OK;
+  }
+  if (n_bytes < 0 || (size_t)n_bytes > cap) return set_error(TGNN_E_OUT_OF_RANGE, "n_bytes exceeds the buffer");
+  TGNN_HIP_CHECK(hipMemcpyAsync(dst, src, (size_t)n_bytes, hipMemcpyDeviceToDevice, s));
+  return TGNN_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,215 @@
+// Internal declarations shared by the HIP sources of libtgnn (not part of the public ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "../../include/tgnn.h"
+
+namespace tgnn {
+
+constexpr int WAVE = 64;
+
+static inline int pad16(int x) { return (x + 15) & ~15; }
+
+// Widths derived from the configuration, plus the row pitches (in floats, multiples of 16) of the
+// workspace matrices.  Pad columns of every workspace matrix are kept at zero.
+struct Dims {
+  int N, dm, dt, de, ds, H, k, nrep, maxB, dt_source;
+  int d_in, dx, dq, dkv, dO;
+  int ldx;    // GRU input rows {mail | Phi | efeat}
+  int ldh;    // rows of width d_m
+  int ld3;    // rows of width 3 d_m
+  int ldc;    // key/value input rows {x_w | e | Phi}
+  int ldq;    // query input rows {x_v | Phi(0)}
+  int ldkv;   // rows of width 2 d_o  (K | V), also decoder input {z_a | z_b}
+  int ldm;    // merge input rows {h_v | x_v}
+  int ldsub;  // rows of width d_m + d_t (gradient wrt the dynamic and time-encoding columns)
+  int ldt;    // rows of width d_t
+  int maxEv, maxR, maxRK, maxS;
+};
+
+struct BatchDesc {
+  const int32_t *src, *dst, *neg, *eid;
+  const double* t;
+  int32_t n, replica, ev_off;
+};
+struct BatchSet {
+  BatchDesc b[TGNN_MAX_BATCHES];
+  int32_t nb, total;
+};
+
+// Device workspace.  S slots = R roots followed by R*k neighbour slots (slot R + r*k + j).
+struct Ws {
+  // indices
+  int32_t *root_node, *root_gid, *root_batch;  // [R]
+  double* root_t;                              // [R]
+  int32_t *nbr, *neid, *cnt;                   // [R,k], [R,k], [R]
+  double* nts;                                 // [R,k]
+  int32_t *slot_gid, *slot_node, *has;         // [S]
+  double *tau, *delta;                         // [S]
+  double* dtk;                                 // [R*k] time difference in the keys
+  unsigned long long* winkey;                  // [nrep*N] write-back arbitration, 0 when idle
+  // GRU
+  float *X, *Hm, *gi, *gh, *gates, *s_new;     // [S,ldx] [S,ldh] [S,ld3] [S,ld3] [S,4*ldh] [S,ldh]
+  float *dgi, *dgh, *dphi_g;                   // [S,ld3] [S,ld3] [S,ldh(dt)]
+  // attention
+  float *Cmat, *Qin, *KV, *q, *prob, *Min, *z; // [RK,ldc] [R,ldq] [RK,ldkv] [R,ldh] [R,H*k] [R,ldm] [R,ldh]
+  float *dz, *dMin, *dq, *dKV, *dCsub, *dQsub; // [R,ldh] [R,ldm] [R,ldh] [RK,ldkv] [RK,ldsub] [R,ldsub]
+  // decoder
+  float *Adec, *h1, *dh1, *dAdec, *logits, *dlogit;  // [2B,ldkv] [2B,ldh] [2B,ldh] [2B,ldkv] [2B] [2B]
+  float* loss_acc;                                   // [TGNN_MAX_BATCHES] per-batch loss sums
+  // standalone-call staging
+  float *x_root_s, *x_nbr_s;                         // unused placeholders
+  // packed weights
+  float *Wih_p, *Whh_p, *Wkv_p, *Wq_p, *Wo_p, *Wdec_p, *bkv_p;
+  float *WdecT, *WoT, *WkvT_sub, *WqT_sub, *WihT_phi;
+};
+
+}  // namespace tgnn
+
+struct tgnn_ctx {
+  tgnn_config cfg;
+  tgnn::Dims d;
+  void* arena;
+  size_t arena_bytes;
+  tgnn::Ws w;
+  int last_attn_roots;
+  int device;
+};
+
+namespace tgnn {
+
+int set_error(int code, const char* fmt, ...);
+#define TGNN_HIP_CHECK(expr)                                                              \
+  do {                                                                                    \
+    hipError_t _e = (expr);                                                               \
+    if (_e != hipSuccess)                                                                 \
+      return tgnn::set_error(TGNN_E_HIP, "%s failed: %s", #expr, hipGetErrorString(_e));  \
+  } while (0)
+#define TGNN_LAUNCH_CHECK() TGNN_HIP_CHECK(hipGetLastError())
+
+// ---- k_gemm.hip ---------------------------------------------------------------------
+// C[m, n] = sum_k A[m, k] * B[n, k] + bias[n]  (m < M, n < N), optional ReLU; columns [N, n_store) of C are
+// set to zero.  Kp (multiple of 16) columns of A and B are read; B rows >= N and A rows >= M read as zero.
+void gemm_nt(const float* A, int lda, const float* B, int ldb, const float* bias, float* C, int ldc, int M,
+             int N, int Kp, int n_store, bool relu, hipStream_t s);
+
+// Where the weight-gradient GEMM adds its result: element (n, k) goes to p[n >= n_split][k >= k_split]
+// (indices taken relative to the split) with row pitch ld[..][..]; column sums of D go to bias[n >= n_split].
+struct OutMap {
+  float* p[2][2];
+  int ld[2][2];
+  int n_split, k_split;
+  float* bias[2];
+};
+// G[n, k] += sum_m D[m, n] * A[m, k]  (n < N, k < K), bias[n] += sum_m D[m, n]; float atomics.
+void gemm_tn_acc(const float* D, int ldd, const float* A, int lda, int M, int N, int K, const OutMap& out,
+                 hipStream_t s);
+
+// ---- k_misc.hip ---------------------------------------------------------------------
+struct PackDesc {
+  const float* src;
+  float* dst;
+  int rows, cols, zero_to, ldd;  // dst[r*ldd + c] = src[r*srs + c*scs] for c < cols, 0 for cols <= c < zero_to
+  int srs, scs;
+};
+void pack_all(tgnn_ctx* ctx, const tgnn_params* p, hipStream_t s);
+void fill_state(tgnn_ctx* ctx, tgnn_state* st, int replica, hipStream_t s);
+struct SgdSet {
+  float* p[20];
+  const float* g[20];
+  int n[20];
+  int cnt;
+};
+void sgd_update(const SgdSet& set, float lr, hipStream_t s);
+
+// ---- k_sample.hip -------------------------------------------------------------------
+void build_roots(tgnn_ctx* ctx, const BatchSet& bs, hipStream_t s);
+void sample_recent(const Dims& d, const tgnn_graph* g, const int32_t* node, const double* t, const int32_t* gid_base,
+                   int n_roots, int32_t* out_nbr, int32_t* out_eid, double* out_ts, int32_t* out_cnt,
+                   int32_t* slot_gid, int32_t* slot_node, hipStream_t s);
+
+// ---- k_gather.hip -------------------------------------------------------------------
+struct GatherArgs {
+  // sources
+  const float *mem, *mail, *efeat;
+  const double *mem_ts, *mail_ts;
+  const int32_t* mail_eid;  // NULL: the staged layout of tgnn_gru_update (row index = slot, has_in given)
+  const int32_t* has_in;
+  const int32_t* slot_gid;  // NULL: identity
+  int gid_add;              // added to every non-negative slot_gid entry (replica offset)
+  // destinations (pitches in floats)
+  float *o_mem, *o_mail, *o_ef, *o_phi;  // o_phi NULL: no time encoding
+  int p_mem, p_mail, p_ef, p_phi;
+  int z_mem, z_mail, z_ef, z_phi;  // number of zero floats to append after each segment (row padding)
+  double *o_mem_ts, *o_mail_ts, *o_tau, *o_delta;
+  int32_t* o_has;
+  const float *time_w, *time_b;
+  int n_slots, dm, dt, de;
+};
+void gather_rows(const GatherArgs& a, hipStream_t s);
+
+struct AttnAssembleArgs {
+  const float *s_root, *s_nbr;  int p_s;  // dynamic rows of the roots [R, p_s] and of the neighbour slots [R*k, p_s]
+  const float* stat;                    // [N, ds] or NULL
+  const float* efeat;                   // [E, de], or [R*k, de] when neid == NULL
+  const int32_t *root_node, *nbr, *neid, *cnt;
+  const double *root_t, *nts, *tau_nbr; // tau_nbr [R*k]
+  const double* dt_in;                  // non-NULL: time differences given directly [R*k]
+  const float *time_w, *time_b;
+  float *Cmat, *Qin, *Min;  int ldc, ldq, ldm;
+  double* dtk;
+  int R, k, dm, ds, de, dt, dO, dt_source;
+};
+void attn_assemble(const AttnAssembleArgs& a, hipStream_t s);
+
+// ---- k_gru.hip ----------------------------------------------------------------------
+void gru_gates_fwd(const Dims& d, int n, const float* gi, const float* gh, const float* Hm, const int32_t* has,
+                   float* gates, float* s_new, hipStream_t s);
+// ds = gradient reaching s' per slot, assembled from dMin / dQsub (roots) and dCsub (neighbours)
+void gru_gates_bwd(const Dims& d, int R, int n, const float* dMin, int ldm, const float* dQsub, const float* dCsub,
+                   int ldsub, const float* gates, const float* Hm, const int32_t* has, float* dgi, float* dgh,
+                   hipStream_t s);
+// time_w/time_b gradients: dPhi [n, ld] (first dt columns at col0), delta [n] (NULL: all zero), valid [n] or NULL
+void time_grad(const float* dphi, int ld, int col0, const double* delta, const int32_t* valid, int n, int dt,
+               const float* time_w, const float* time_b, float* g_w, float* g_b, hipStream_t s);
+
+// ---- k_attn.hip ---------------------------------------------------------------------
+void attn_core_fwd(const Dims& d, int R, const float* q, int ldq_, const float* KV, int ldkv, const int32_t* cnt,
+                   float* prob, float* Min, int ldm, hipStream_t s);
+void attn_core_bwd(const Dims& d, int R, const float* q, int ldq_, const float* KV, int ldkv, const int32_t* cnt,
+                   const float* prob, const float* dMin, int ldm, float* dq, float* dKV, hipStream_t s);
+
+// ---- k_decoder.hip ------------------------------------------------------------------
+void decoder_assemble(const Dims& d, const BatchSet& bs, const float* z, int ldz, float* Adec, int lda,
+                      hipStream_t s);
+void decoder_loss(const Dims& d, const BatchSet& bs, const float* h1, int ldh, const float* w2, const float* b2,
+                  float* logits, float* out_loss, float* dh1, float* g_w2, float* g_b2, hipStream_t s);
+void decoder_dz(const Dims& d, const BatchSet& bs, const float* dAdec, int lda, const float* z, int ldz, float* dz,
+                hipStream_t s);
+// dz_out[r, c] = z[r, c] > 0 ? dz_in[r, c] : 0   (dz_in pitch p_in)
+void mask_dz(int R, int dO, const float* dz_in, int p_in, const float* z, int ldz, float* dz_out, hipStream_t s);
+// d_x_root[r, c] = dMin[r, dO + c] + dQsub[r, c];  d_x_nbr[row, c] = dCsub[row, c]   (c < dm, outputs pitch dm)
+void attn_dx_out(int R, int RK, int dm, int dO, const float* dMin, int ldm, const float* dQsub, const float* dCsub,
+                 int ldsub, float* d_x_root, float* d_x_nbr, hipStream_t s);
+void zero_f32(float* p, int n, hipStream_t s);
+
+// ---- k_writeback.hip ----------------------------------------------------------------
+struct WbArgs {
+  float *mem, *mail;
+  double *mem_ts, *mail_ts;
+  int32_t* mail_eid;
+  unsigned long long* winkey;
+  const float *s_src, *s_dst;  int p_s;  // [n_occ/2 rows each] only in the standalone layout
+  const double *tau_src, *tau_dst;
+  int dm;
+};
+void writeback_mark(const Dims& d, const BatchSet& bs, unsigned long long* winkey, hipStream_t s);
+// Fused layout: s_new/tau indexed by root slot.  Standalone layout: separate src/dst arrays.
+void writeback_scatter(const Dims& d, const BatchSet& bs, const tgnn_state* st, unsigned long long* winkey,
+                       const float* s_new, int p_s, const double* tau, const float* s_src, const float* s_dst,
+                       const double* tau_src, const double* tau_dst, int32_t* out_winner, hipStream_t s);
+void writeback_clear(const Dims& d, const BatchSet& bs, unsigned long long* winkey, hipStream_t s);
+
+}  // namespace tgnn
