@@ -1,0 +1,184 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused M-TGNN training step (tgnn_train_step) on one MI355X.
+
+A step = one pass of the whole hot path over one mini-batch: sample -> gather -> time-encode -> GRU ->
+attention -> decoder/BCE forward and backward -> SGD -> last-event-wins write-back.  Inputs (graph, edge
+features, node state, weights, every mini-batch of the epoch) are resident in HBM before the clock starts.
+Prints one JSON line; see the design doc for the roofline and cpu_baseline fields.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_HBM_GBS = 8000.0
+PEAK_MFMA_F32_TFLOPS = 157.3
+
+STAGE_GATHER, STAGE_GRU_IH = 3, 4
+
+
+def flops_gru_ih(d, n_slots):
+    return 2.0 * n_slots * d.d_in * 3 * d.d_mem
+
+
+def gather_bytes(d, n_slots):
+    # per slot: read mem row, mail row, mail edge-feature row, two timestamps + event id; write the same rows staged
+    row = 4 * (d.d_mem + 2 * d.d_mem + d.d_edge)
+    return n_slots * (2 * row + 20 + 4 * d.d_time)
+
+
+def step_flops(d, B):
+    R = 3 * B; RK = R * d.k; S = R + RK
+    gru = S * 2 * (d.d_in + d.d_mem) * 3 * d.d_mem
+    attn = R * 2 * d.d_q * d.d_out + RK * 2 * 2 * d.d_kv * d.d_out + RK * 4 * d.d_out
+    merge = R * 2 * (d.d_out + d.d_x) * d.d_out
+    dec = 2 * B * (4 * d.d_out ** 2 + 2 * d.d_out)
+    return 3.0 * (gru + attn + merge + dec)     # forward + backward ~ 3x forward
+
+
+def step_bytes(d, B):
+    R = 3 * B; RK = R * d.k; S = R + RK
+    gather = S * (4 * d.d_mem + 8 * d.d_mem + 4 * d.d_edge + 4 * d.d_static + 20) + RK * 4 * d.d_edge
+    sampler = R * (2 * d.k * 16 + 8 * 16)
+    wb = 2 * B * (12 * d.d_mem + 20)
+    return float(gather + sampler + wb)
+
+
+def cpu_baseline(P, budget_s=15.0):
+    """The oracle as it stands, timed on the host cores on the first mini-batches of the same workload."""
+    from oracle import tgnn_oracle as O
+    d = P["d"]
+    adj = O.build_adjacency(P["src"], P["dst"], P["ts"], d.n_nodes)
+    st = O.new_state(d.n_nodes, d.d_mem)
+    p = O.to_f64(P["params"])
+    ev = 0; steps = 0
+    t0 = time.perf_counter()
+    while time.perf_counter() - t0 < budget_s and (steps + 1) * d.batch <= P["E"]:
+        lo = steps * d.batch; hi = lo + d.batch
+        b = dict(src=P["src"][lo:hi], dst=P["dst"][lo:hi], neg=P["neg"][lo:hi], eid=np.arange(lo, hi), t=P["ts"][lo:hi])
+        O.train_step([st], adj, P["efeat"], P["static"], p, [b], d.k, d.n_heads, lr=1e-4)
+        ev += hi - lo; steps += 1
+    dt = time.perf_counter() - t0
+    try:
+        import threadpoolctl
+        cores = max([i.get("num_threads", 1) for i in threadpoolctl.threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count()
+    return dict(value=ev / dt, unit="events/s", cores=int(cores), kind="oracle",
+                sample=f"first {steps} mini-batches of {d.batch} events of {P['name']} from zero state "
+                       f"(fp64 numpy, {dt:.1f} s)")
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=263)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", default="C1", choices=["C0", "C1", "C2", "C3", "C4"])
+    ap.add_argument("--events", type=int, default=None, help="shorten the event list (C4: default 2,000,000)")
+    ap.add_argument("--lr", type=float, default=1e-4)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2307_07649_amd import tgnn
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    from gpu_common import make_problem
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+
+    name = args.config
+    n_events = args.events
+    if name == "C4" and n_events is None:
+        n_events = 2_000_000
+    P = make_problem(name, n_events=n_events)
+    d = P["d"]
+    nrep = d.n_replicas
+    ctx = tgnn.Context(d.n_nodes, d.d_mem, d.d_time, d.d_edge, d.d_static, d.n_heads, d.k, d.batch, n_replicas=nrep)
+    graph = tgnn.Graph(P["src"], P["dst"], P["ts"], d.n_nodes, P["efeat"])
+    state = tgnn.State(d.n_nodes, d.d_mem, nrep, P["static"])
+    params = tgnn.Params.from_numpy(P["params"])
+    grads = tgnn.Params.zeros_like(params)
+    loss = torch.zeros(4, device="cuda")
+
+    # every mini-batch of the epoch, resident on the device
+    import synth
+    spans = synth.batches_of(P["E"], d.batch)
+    M = len(spans)
+    eid_all = np.arange(P["E"], dtype=np.int32)
+    batches = [[tgnn.Batch(P["src"][lo:hi], P["dst"][lo:hi], P["neg"][lo:hi], eid_all[lo:hi], P["ts"][lo:hi], replica=r)
+                for (lo, hi) in spans] for r in range(nrep)]
+    shift = -(-M // nrep)
+
+    def run_step(s):
+        """Step s: replica r trains mini-batch (s + r*shift) mod M; a replica that wraps to mini-batch 0 starts a
+        new epoch with its memory and mails reset."""
+        bl = []
+        for r in range(nrep):
+            m = (s + r * shift) % M
+            if m == 0 and s > 0:
+                ctx.tgnn_state_reset(state, r)
+            bl.append(batches[r][m])
+        ctx.tgnn_zero_params(grads)
+        ctx.tgnn_train_step(graph, state, params, grads, bl, lr=args.lr, out_loss=loss)
+        return sum(b.n for b in bl)
+
+    for s in range(args.warmup):
+        run_step(s)
+    torch.cuda.synchronize()
+    ctx.tgnn_profile_enable((1 << STAGE_GATHER) | (1 << STAGE_GRU_IH))
+    ev = 0
+    t0 = time.perf_counter()
+    for s in range(args.warmup, args.warmup + args.steps):
+        ev += run_step(s)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    final_loss = float(loss[0].item())
+    n_g, ms_g = ctx.tgnn_profile_read(STAGE_GATHER)
+    n_m, ms_m = ctx.tgnn_profile_read(STAGE_GRU_IH)
+    ctx.tgnn_profile_enable(0)
+
+    ev_step = ev / args.steps
+    S_avg = 3 * ev_step * (1 + d.k)
+    gru_tflops = flops_gru_ih(d, S_avg) / (ms_m / n_m * 1e-3) / 1e12 if n_m else None
+    gather_gbs = gather_bytes(d, S_avg) / (ms_g / n_g * 1e-3) / 1e9 if n_g else None
+    out = {
+        "metric": "training events/sec (fwd+bwd+memory update) at 1 GPU",
+        "value": ev / dt, "unit": "events/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": dt / args.steps * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{name}: {d.n_nodes} nodes, {P['E']} events, d_mem {d.d_mem}, d_time {d.d_time}, "
+                               f"d_edge {d.d_edge}, d_static {d.d_static}, {d.n_heads} heads, k {d.k}, "
+                               f"batch {d.batch} x {nrep} replica(s), 1 negative/event, SGD lr {args.lr}",
+                   "events_per_step": ev_step, "final_loss": final_loss},
+        "roofline": {"bound": "mfma", "kernel": "gemm_nt_kernel (GRU input projection, fp32 MFMA 16x16x4)",
+                     "achieved": gru_tflops, "peak": PEAK_MFMA_F32_TFLOPS, "unit": "TFLOP/s",
+                     "frac": gru_tflops / PEAK_MFMA_F32_TFLOPS if gru_tflops else None,
+                     "avg_launch_us": ms_m / n_m * 1e3 if n_m else None, "traffic": None},
+        "gather": {"bound": "hbm", "kernel": "gather_kernel (memory + mail + edge-feature rows, time encoding)",
+                   "achieved": gather_gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                   "frac": gather_gbs / PEAK_HBM_GBS if gather_gbs else None,
+                   "avg_launch_us": ms_g / n_g * 1e3 if n_g else None},
+        "step_model": {"flops_per_step": step_flops(d, ev_step), "bytes_per_step": step_bytes(d, ev_step),
+                       "whole_step_tflops": step_flops(d, ev_step) / (dt / args.steps) / 1e12},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(P)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

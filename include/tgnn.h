@@ -187,6 +187,23 @@ int32_t tgnn_train_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
                         tgnn_params* grads, const tgnn_batch* batches, int32_t n_batches, float lr,
                         float* out_loss, float* out_logits, int32_t* out_winner, void* stream);
 
+/* Sets every tensor of `g` (a gradient set laid out like the parameters) to zero with one kernel. */
+int32_t tgnn_zero_params(tgnn_ctx* ctx, tgnn_params* g, void* stream);
+
+/* Stage timing with HIP events on the call's own stream.  Stages of tgnn_train_step:
+ *  0 pack weights   1 roots + write-back arbitration   2 sample   3 gather + time-encode (GRU input)
+ *  4 GRU input projection (MFMA)   5 GRU hidden projection (MFMA)   6 GRU gates   7 attention input assembly
+ *  8 K/V projection (MFMA)   9 query projection   10 softmax attention   11 merge layer   12 decoder forward + loss
+ *  13 decoder backward   14 attention backward (GEMMs + softmax)   15 GRU gates backward
+ *  16 GRU weight gradients (MFMA)   17 time-encoding gradients of the mail   18 SGD   19 write-back scatter
+ * tgnn_profile_enable: time the stages whose bit is set in `stage_mask` in every following tgnn_train_step
+ * (0 = off); each timed stage costs two event records per step.  At most 4096 steps are kept per stage;
+ * enabling resets the record.  tgnn_profile_read: synchronises the recorded events and returns the number
+ * of recorded launches of `stage` and their total duration in milliseconds.  HOST pointers. */
+#define TGNN_N_STAGES 20
+int32_t tgnn_profile_enable(tgnn_ctx* ctx, uint32_t stage_mask);
+int32_t tgnn_profile_read(tgnn_ctx* ctx, int32_t stage, int32_t* out_count, double* out_total_ms);
+
 /* Debug/parity access to what the last tgnn_train_step left in the workspace.  `what`:
  * 0 nbr [R,k] i32, 1 eid [R,k] i32, 2 nts [R,k] f64, 3 cnt [R] i32, 4 s_new [R(1+k), d_m] f32,
  * 5 tau [R(1+k)] f64, 6 z [R, d_o] f32.  Copies n_bytes (device to device) into dst on `stream`. */

@@ -2,94 +2,136 @@
 // (Eq. 3-6), the merge layer, the decoder, and their data / weight gradients.
 //
 // v_mfma_f32_16x16x4_f32: lane l supplies A[i = l%16][kk = l/16] and B[kk = l/16][j = l%16]; its four
-// accumulators hold D[i = 4*(l/16) + v][j = l%16].
+// accumulators hold D[i = 4*(l/16) + v][j = l%16].  The sum over kk is order independent, so a lane may
+// feed any four k indices per instruction as long as both operands use the same ones: lane group g reads
+// one float4 (k = 4g .. 4g+3 of a 16-wide slab) and issues four MFMAs from it.
+//
+// Both kernels keep two register tile sets in flight (global loads issued two stages ahead) and two LDS
+// buffers, so a workgroup waits for memory only when the chip has nothing else resident to run.
+#include <stdlib.h>
+
 #include "tgnn_internal.h"
 
 namespace tgnn {
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
-constexpr int BK = 16;     // k-depth of one LDS stage
-constexpr int LDS_P = 20;  // row pitch (floats) of an NT stage: 16 lanes * 20 floats hit 16 distinct bank quads
+// ------------------------------------------------------------------------------------------------
+// NT: C = A * B^T.  One workgroup = 4 waves stacked along M (16 rows each); every wave spans the
+// whole 16*TN-wide column tile.  A stage is 32 k-columns.
+// ------------------------------------------------------------------------------------------------
+constexpr int NT_BK = 32;
+constexpr int NT_P = 32;
+// LDS rows are 32 floats = 8 chunks of 16 bytes, unpadded; chunk c of row r is stored at chunk position
+// c ^ ((r >> 1) & 7).  Sixteen lanes that access the same logical chunk of sixteen consecutive rows (MFMA
+// operand reads), or the eight chunks of two consecutive rows (stage stores), then cover all 64 banks once.
+__device__ __forceinline__ int nt_swz(int row, int chunk) { return row * NT_P + ((chunk ^ ((row >> 1) & 7)) << 2); }
 
-// ------------------------------------------------------------------------------------------------
-// NT: C = A * B^T.  One workgroup = 4 waves stacked along M; a wave owns a (16*TM) x (16*TN) tile.
-// ------------------------------------------------------------------------------------------------
-template <int TM, int TN>
-__global__ __launch_bounds__(256) void gemm_nt_kernel(const float* __restrict__ A, int lda,
+template <int TN>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 2))) void gemm_nt_kernel(const float* __restrict__ A, int lda,
                                                       const float* __restrict__ B, int ldb,
                                                       const float* __restrict__ bias, float* __restrict__ C, int ldc,
                                                       int M, int N, int Kp, int n_store, int relu) {
-  constexpr int BM = 64 * TM, BN = 16 * TN;
-  constexpr int A_F4 = BM * 4, B_F4 = BN * 4;  // float4 loads per stage
-  constexpr int A_PER = (A_F4 + 255) / 256, B_PER = (B_F4 + 255) / 256;
-  __shared__ __attribute__((aligned(16))) float As[2][BM * LDS_P];
-  __shared__ __attribute__((aligned(16))) float Bs[2][BN * LDS_P];
+  constexpr int BM = 64, BN = 16 * TN;
+  constexpr int A_PER = BM * 8 / 256, B_F4 = BN * 8;  // float4 loads per stage and thread
+  constexpr int B_PER = (B_F4 + 255) / 256;
+  __shared__ __attribute__((aligned(16))) float As[2][BM * NT_P];
+  __shared__ __attribute__((aligned(16))) float Bs[2][BN * NT_P];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int li = lane & 15, lg = lane >> 4;
   const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
 
-  floatx4 acc[TM][TN];
+  floatx4 acc[TN];
 #pragma unroll
-  for (int a = 0; a < TM; ++a)
-#pragma unroll
-    for (int b = 0; b < TN; ++b) acc[a][b] = floatx4{0.f, 0.f, 0.f, 0.f};
+  for (int b = 0; b < TN; ++b) acc[b] = floatx4{0.f, 0.f, 0.f, 0.f};
 
-  float4 ra[A_PER], rb[B_PER];
-  auto gload = [&](int k0) {
+  // Row indices are clamped instead of guarded, so the hot loop has no branches: rows >= M and weight
+  // rows >= N read valid memory whose products are dropped in the epilogue.
+  const float* pa[A_PER];
+  const float* pb[B_PER];
+#pragma unroll
+  for (int u = 0; u < A_PER; ++u) {
+    const int f = tid + u * 256;
+    pa[u] = A + (size_t)min(m0 + (f >> 3), M - 1) * lda + (f & 7) * 4;
+  }
+#pragma unroll
+  for (int u = 0; u < B_PER; ++u) {
+    const int f = min(tid + u * 256, B_F4 - 1);
+    pb[u] = B + (size_t)min(n0 + (f >> 3), N - 1) * ldb + (f & 7) * 4;
+  }
+  struct Regs {
+    floatx4 a[A_PER], b[B_PER];
+  };
+  Regs r0, r1;  // the two register tile sets
+  auto gload = [&](Regs& r, int k0) __attribute__((always_inline)) {
+#pragma unroll
+    for (int u = 0; u < A_PER; ++u) r.a[u] = *reinterpret_cast<const floatx4*>(pa[u] + k0);
+#pragma unroll
+    for (int u = 0; u < B_PER; ++u) r.b[u] = *reinterpret_cast<const floatx4*>(pb[u] + k0);
+  };
+  auto sstore = [&](const Regs& r, int buf) __attribute__((always_inline)) {
 #pragma unroll
     for (int u = 0; u < A_PER; ++u) {
-      int f = tid + u * 256;
-      int row = f >> 2, c4 = (f & 3) * 4;
-      ra[u] = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (f < A_F4 && m0 + row < M) ra[u] = *reinterpret_cast<const float4*>(A + (size_t)(m0 + row) * lda + k0 + c4);
+      const int f = tid + u * 256;
+      *reinterpret_cast<floatx4*>(&As[buf][nt_swz(f >> 3, f & 7)]) = r.a[u];
     }
 #pragma unroll
     for (int u = 0; u < B_PER; ++u) {
-      int f = tid + u * 256;
-      int row = f >> 2, c4 = (f & 3) * 4;
-      rb[u] = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (f < B_F4 && n0 + row < N) rb[u] = *reinterpret_cast<const float4*>(B + (size_t)(n0 + row) * ldb + k0 + c4);
+      const int f = tid + u * 256;
+      if (B_F4 % 256 == 0 || f < B_F4) *reinterpret_cast<floatx4*>(&Bs[buf][nt_swz(f >> 3, f & 7)]) = r.b[u];
     }
   };
-  auto sstore = [&](int buf) {
+  auto compute = [&](int buf) __attribute__((always_inline)) {
 #pragma unroll
-    for (int u = 0; u < A_PER; ++u) {
-      int f = tid + u * 256;
-      if (f < A_F4) *reinterpret_cast<float4*>(&As[buf][(f >> 2) * LDS_P + (f & 3) * 4]) = ra[u];
-    }
+    for (int h = 0; h < 2; ++h) {  // two 16-wide k slabs per stage
+      const floatx4 a4 = *reinterpret_cast<const floatx4*>(&As[buf][nt_swz(wave * 16 + li, h * 4 + lg)]);
+      floatx4 b4[TN];
 #pragma unroll
-    for (int u = 0; u < B_PER; ++u) {
-      int f = tid + u * 256;
-      if (f < B_F4) *reinterpret_cast<float4*>(&Bs[buf][(f >> 2) * LDS_P + (f & 3) * 4]) = rb[u];
+      for (int b = 0; b < TN; ++b)
+        b4[b] = *reinterpret_cast<const floatx4*>(&Bs[buf][nt_swz(b * 16 + li, h * 4 + lg)]);
+#pragma unroll
+      for (int b = 0; b < TN; ++b) acc[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a4.x, b4[b].x, acc[b], 0, 0, 0);
+#pragma unroll
+      for (int b = 0; b < TN; ++b) acc[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a4.y, b4[b].y, acc[b], 0, 0, 0);
+#pragma unroll
+      for (int b = 0; b < TN; ++b) acc[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a4.z, b4[b].z, acc[b], 0, 0, 0);
+#pragma unroll
+      for (int b = 0; b < TN; ++b) acc[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a4.w, b4[b].w, acc[b], 0, 0, 0);
     }
   };
 
-  const int nk = Kp / BK;
-  gload(0);
-  sstore(0);
+  // Kp is a multiple of the stage depth.  Stage s lives in register set s & 1 until it is stored to LDS
+  // buffer s & 1; loads run two stages ahead of the MFMAs.
+  const int nk = Kp / NT_BK;
+  gload(r0, 0);
+  gload(r1, nk > 1 ? NT_BK : 0);
+  sstore(r0, 0);
   __syncthreads();
-  for (int kt = 0; kt < nk; ++kt) {
-    const int cur = kt & 1;
-    if (kt + 1 < nk) gload((kt + 1) * BK);
-    float4 a4[TM];
-#pragma unroll
-    for (int a = 0; a < TM; ++a)
-      a4[a] = *reinterpret_cast<const float4*>(&As[cur][(wave * 16 * TM + a * 16 + li) * LDS_P + lg * 4]);
-#pragma unroll
-    for (int b = 0; b < TN; ++b) {
-      float4 b4 = *reinterpret_cast<const float4*>(&Bs[cur][(b * 16 + li) * LDS_P + lg * 4]);
-#pragma unroll
-      for (int a = 0; a < TM; ++a) {
-        acc[a][b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a4[a].x, b4.x, acc[a][b], 0, 0, 0);
-        acc[a][b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a4[a].y, b4.y, acc[a][b], 0, 0, 0);
-        acc[a][b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a4[a].z, b4.z, acc[a][b], 0, 0, 0);
-        acc[a][b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a4[a].w, b4.w, acc[a][b], 0, 0, 0);
-      }
-    }
-    if (kt + 1 < nk) sstore(cur ^ 1);
+  int kt = 0;
+  for (; kt + 3 < nk; kt += 2) {
+    gload(r0, (kt + 2) * NT_BK);
+    compute(0);
+    sstore(r1, 1);
     __syncthreads();
+    gload(r1, (kt + 3) * NT_BK);
+    compute(1);
+    sstore(r0, 0);
+    __syncthreads();
+  }
+  // 1, 2 or 3 stages remain: kt (in LDS 0), kt+1 (in set 1), kt+2 (not loaded yet)
+  const int rem = nk - kt;
+  if (rem == 3) gload(r0, (kt + 2) * NT_BK);
+  compute(0);
+  if (rem >= 2) {
+    sstore(r1, 1);
+    __syncthreads();
+    compute(1);
+    if (rem == 3) {
+      sstore(r0, 0);
+      __syncthreads();
+      compute(0);
+    }
   }
 
 #pragma unroll
@@ -98,29 +140,26 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(const float* __restrict__ 
     if (col >= n_store) continue;
     const float bv = (bias != nullptr && col < N) ? bias[col] : 0.f;
 #pragma unroll
-    for (int a = 0; a < TM; ++a) {
-#pragma unroll
-      for (int v = 0; v < 4; ++v) {
-        const int row = m0 + wave * 16 * TM + a * 16 + lg * 4 + v;
-        if (row < M) {
-          float x = 0.f;
-          if (col < N) {
-            x = acc[a][b][v] + bv;
-            if (relu) x = fmaxf(x, 0.f);
-          }
-          C[(size_t)row * ldc + col] = x;
+    for (int v = 0; v < 4; ++v) {
+      const int row = m0 + wave * 16 + lg * 4 + v;
+      if (row < M) {
+        float x = 0.f;
+        if (col < N) {
+          x = acc[b][v] + bv;
+          if (relu) x = fmaxf(x, 0.f);
         }
+        C[(size_t)row * ldc + col] = x;
       }
     }
   }
 }
 
-template <int TM, int TN>
+template <int TN>
 static void launch_nt(const float* A, int lda, const float* B, int ldb, const float* bias, float* C, int ldc, int M,
                       int N, int Kp, int n_store, bool relu, hipStream_t s) {
-  constexpr int BM = 64 * TM, BN = 16 * TN;
+  constexpr int BM = 64, BN = 16 * TN;
   dim3 grid((n_store + BN - 1) / BN, (M + BM - 1) / BM);
-  hipLaunchKernelGGL((gemm_nt_kernel<TM, TN>), grid, dim3(256), 0, s, A, lda, B, ldb, bias, C, ldc, M, N, Kp, n_store,
+  hipLaunchKernelGGL((gemm_nt_kernel<TN>), grid, dim3(256), 0, s, A, lda, B, ldb, bias, C, ldc, M, N, Kp, n_store,
                      relu ? 1 : 0);
 }
 
@@ -128,21 +167,29 @@ void gemm_nt(const float* A, int lda, const float* B, int ldb, const float* bias
              int Kp, int n_store, bool relu, hipStream_t s) {
   if (M <= 0 || N <= 0) return;
   if (n_store < N) n_store = N;
-  // pick the column-tile width (in 16-wide MFMA blocks) that wastes the fewest padded columns
-  static const int cand[] = {13, 10, 7, 4, 2, 1};
+  // Column-tile width in 16-wide MFMA blocks.  Measured on MI355X the throughput is flat between 2 and 10
+  // blocks, so the choice is about padding waste and about having enough workgroups to fill 256 CUs:
+  // small-M problems take narrow tiles (many short workgroups), large ones 4-5 blocks.
   const int nb = (n_store + 15) / 16;
-  int best = 1, best_cost = 1 << 30;
+  const int row_tiles = (M + 63) / 64;
+  int best = 1;
+  float best_cost = 1e30f;
+  static const int cand[] = {5, 4, 7, 2, 10, 1};
   for (int c : cand) {
-    int tiles = (nb + c - 1) / c;
-    int cost = tiles * c;
-    if (cost < best_cost) { best_cost = cost; best = c; }
+    const int tiles = (nb + c - 1) / c;
+    const int wgs = tiles * row_tiles;
+    float cost = (float)(tiles * c) / nb;                 // padded / useful columns
+    if (wgs < 512) cost *= 1.0f + 0.5f * (512 - wgs) / 512.0f;   // too few workgroups for the chip
+    if (c == 1) cost *= 1.15f;
+    if (cost < best_cost - 1e-6f) { best_cost = cost; best = c; }
   }
+  if (const char* e = getenv("TGNN_NT_TN")) best = atoi(e);
 #define TGNN_NT_CASE(TNV) \
-  case TNV: launch_nt<1, TNV>(A, lda, B, ldb, bias, C, ldc, M, N, Kp, n_store, relu, s); break;
+  case TNV: launch_nt<TNV>(A, lda, B, ldb, bias, C, ldc, M, N, Kp, n_store, relu, s); break;
   switch (best) {
-    TGNN_NT_CASE(13)
     TGNN_NT_CASE(10)
     TGNN_NT_CASE(7)
+    TGNN_NT_CASE(5)
     TGNN_NT_CASE(4)
     TGNN_NT_CASE(2)
     TGNN_NT_CASE(1)
@@ -152,17 +199,18 @@ void gemm_nt(const float* A, int lda, const float* B, int ldb, const float* bias
 
 // ------------------------------------------------------------------------------------------------
 // TN with accumulation: G[n, k] += sum_m D[m, n] * A[m, k].  Both operands are m-major, so a stage is
-// 16 rows of D (64 columns) and 16 rows of A (64 columns); 2 x 2 waves each own a 32 x 32 block of G.
+// 32 rows of D (64 columns) and 32 rows of A (64 columns); 2 x 2 waves each own a 32 x 32 block of G.
 // The reduction over m is split over blockIdx.y; partial results are added with float atomics.
 // ------------------------------------------------------------------------------------------------
 constexpr int TT = 64;     // output tile edge
 constexpr int TN_P = 80;   // stage row pitch: rows 4 apart land 16 banks apart
+constexpr int TN_ROWS = 32;
 
 __global__ __launch_bounds__(256) void gemm_tn_kernel(const float* __restrict__ D, int ldd,
                                                       const float* __restrict__ A, int lda, int M, int N, int K,
                                                       int m_chunk, int k_tiles, OutMap out) {
-  __shared__ __attribute__((aligned(16))) float Ds[2][16 * TN_P];
-  __shared__ __attribute__((aligned(16))) float Asm[2][16 * TN_P];
+  __shared__ __attribute__((aligned(16))) float Ds[2][TN_ROWS * TN_P];
+  __shared__ __attribute__((aligned(16))) float Asm[2][TN_ROWS * TN_P];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int li = lane & 15, lg = lane >> 4;
   const int wn = wave >> 1, wk = wave & 1;
@@ -178,37 +226,42 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(const float* __restrict__ 
     for (int b = 0; b < 2; ++b) acc[a][b] = floatx4{0.f, 0.f, 0.f, 0.f};
   float bsum = 0.f;
 
-  const int lrow = tid >> 4, lc4 = (tid & 15) * 4;  // this thread's float4 of a 16 x 64 stage
-  float4 rd, ra;
-  auto gload = [&](int m) {
-    rd = make_float4(0.f, 0.f, 0.f, 0.f);
-    ra = rd;
-    if (m + lrow < m_hi) {
-      if (n0 + lc4 < ldd) rd = *reinterpret_cast<const float4*>(D + (size_t)(m + lrow) * ldd + n0 + lc4);
-      if (k0 + lc4 < lda) ra = *reinterpret_cast<const float4*>(A + (size_t)(m + lrow) * lda + k0 + lc4);
+  // This thread's float4s of a stage: rows lrow and lrow + 16.  Column offsets are clamped into the row
+  // (results of clamped columns are dropped at the end); rows >= m_hi are clamped and zeroed by a select.
+  const int lrow = tid >> 4, lc4 = (tid & 15) * 4;
+  const float* pd = D + min(n0 + lc4, ldd - 4);
+  const float* pa = A + min(k0 + lc4, lda - 4);
+  struct Regs {
+    floatx4 d[2], a[2];
+  };
+  Regs r0, r1;
+  auto gload = [&](Regs& r, int m) __attribute__((always_inline)) {
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      const int row = m + lrow + u * 16;
+      const size_t rr = (size_t)min(row, M - 1);
+      const floatx4 vd = *reinterpret_cast<const floatx4*>(pd + rr * ldd);
+      const floatx4 va = *reinterpret_cast<const floatx4*>(pa + rr * lda);
+      const bool ok = row < m_hi;
+      r.d[u] = ok ? vd : floatx4{0.f, 0.f, 0.f, 0.f};
+      r.a[u] = va;   // multiplied by the zeros of r.d when the row is out of range
     }
   };
-  auto sstore = [&](int buf) {
-    *reinterpret_cast<float4*>(&Ds[buf][lrow * TN_P + lc4]) = rd;
-    *reinterpret_cast<float4*>(&Asm[buf][lrow * TN_P + lc4]) = ra;
-  };
-
-  const int nst = (m_hi - m_lo + 15) / 16;
-  if (nst > 0) {
-    gload(m_lo);
-    sstore(0);
-  }
-  __syncthreads();
-  for (int st = 0; st < nst; ++st) {
-    const int cur = st & 1;
-    if (st + 1 < nst) gload(m_lo + (st + 1) * 16);
+  auto sstore = [&](const Regs& r, int buf) __attribute__((always_inline)) {
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
+    for (int u = 0; u < 2; ++u) {
+      *reinterpret_cast<floatx4*>(&Ds[buf][(lrow + u * 16) * TN_P + lc4]) = r.d[u];
+      *reinterpret_cast<floatx4*>(&Asm[buf][(lrow + u * 16) * TN_P + lc4]) = r.a[u];
+    }
+  };
+  auto compute = [&](int buf) __attribute__((always_inline)) {
+#pragma unroll
+    for (int q = 0; q < TN_ROWS / 4; ++q) {
       const int mm = q * 4 + lg;
-      float a0 = Ds[cur][mm * TN_P + wn * 32 + li];
-      float a1 = Ds[cur][mm * TN_P + wn * 32 + 16 + li];
-      float b0 = Asm[cur][mm * TN_P + wk * 32 + li];
-      float b1 = Asm[cur][mm * TN_P + wk * 32 + 16 + li];
+      const float a0 = Ds[buf][mm * TN_P + wn * 32 + li];
+      const float a1 = Ds[buf][mm * TN_P + wn * 32 + 16 + li];
+      const float b0 = Asm[buf][mm * TN_P + wk * 32 + li];
+      const float b1 = Asm[buf][mm * TN_P + wk * 32 + 16 + li];
       acc[0][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(a0, b0, acc[0][0], 0, 0, 0);
       acc[0][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(a0, b1, acc[0][1], 0, 0, 0);
       acc[1][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(a1, b0, acc[1][0], 0, 0, 0);
@@ -216,10 +269,38 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(const float* __restrict__ 
     }
     if (do_bias && tid < TT) {
 #pragma unroll
-      for (int mm = 0; mm < 16; ++mm) bsum += Ds[cur][mm * TN_P + tid];
+      for (int mm = 0; mm < TN_ROWS; ++mm) bsum += Ds[buf][mm * TN_P + tid];
     }
-    if (st + 1 < nst) sstore(cur ^ 1);
+  };
+
+  const int nst = (m_hi - m_lo + TN_ROWS - 1) / TN_ROWS;   // >= 1 by construction of the grid
+  gload(r0, m_lo);
+  gload(r1, m_lo + TN_ROWS);
+  sstore(r0, 0);
+  __syncthreads();
+  int st = 0;
+  for (; st + 3 < nst; st += 2) {
+    gload(r0, m_lo + (st + 2) * TN_ROWS);
+    compute(0);
+    sstore(r1, 1);
     __syncthreads();
+    gload(r1, m_lo + (st + 3) * TN_ROWS);
+    compute(1);
+    sstore(r0, 0);
+    __syncthreads();
+  }
+  const int rem = nst - st;
+  if (rem == 3) gload(r0, m_lo + (st + 2) * TN_ROWS);
+  compute(0);
+  if (rem >= 2) {
+    sstore(r1, 1);
+    __syncthreads();
+    compute(1);
+    if (rem == 3) {
+      sstore(r0, 0);
+      __syncthreads();
+      compute(0);
+    }
   }
 
 #pragma unroll
@@ -253,12 +334,12 @@ void gemm_tn_acc(const float* D, int ldd, const float* A, int lda, int M, int N,
   if (M <= 0 || N <= 0 || K <= 0) return;
   const int n_tiles = (N + TT - 1) / TT, k_tiles = (K + TT - 1) / TT;
   const int tiles = n_tiles * k_tiles;
-  // enough m-chunks to give the chip ~4 workgroups per CU, at least 64 rows each
+  // enough m-chunks to give the chip ~4 workgroups per CU, at least 128 rows each
   int chunks = (1024 + tiles - 1) / tiles;
-  int max_chunks = (M + 63) / 64;
+  int max_chunks = (M + 127) / 128;
   if (chunks > max_chunks) chunks = max_chunks;
   if (chunks < 1) chunks = 1;
-  int m_chunk = ((M + chunks - 1) / chunks + 15) & ~15;
+  int m_chunk = ((M + chunks - 1) / chunks + TN_ROWS - 1) / TN_ROWS * TN_ROWS;
   chunks = (M + m_chunk - 1) / m_chunk;
   hipLaunchKernelGGL(gemm_tn_kernel, dim3(tiles, chunks), dim3(256), 0, s, D, ldd, A, lda, M, N, K, m_chunk, k_tiles,
                      out);

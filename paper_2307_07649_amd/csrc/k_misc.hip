@@ -90,4 +90,15 @@ void sgd_update(const SgdSet& set, float lr, hipStream_t s) {
   hipLaunchKernelGGL(sgd_kernel, dim3(64, set.cnt), dim3(256), 0, s, set, lr);
 }
 
+__global__ void zero_set_kernel(SgdSet set) {
+  const int t = blockIdx.y;
+  float* p = set.p[t];
+  const int n = set.n[t];
+  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) p[i] = 0.f;
+}
+
+void zero_set(const SgdSet& set, hipStream_t s) {
+  hipLaunchKernelGGL(zero_set_kernel, dim3(64, set.cnt), dim3(256), 0, s, set);
+}
+
 }  // namespace tgnn

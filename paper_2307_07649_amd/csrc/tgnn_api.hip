@@ -162,6 +162,41 @@ static void attn_backward(tgnn_ctx* ctx, tgnn_params* g, const tgnn_params* p, i
 
 static hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
 
+// Records a pair of events around a stage when its bit is set in the profiler mask.
+struct StageTimer {
+  tgnn_ctx* c;
+  hipStream_t s;
+  bool on(int st) const { return (c->prof.mask >> st) & 1u && c->prof.count[st] < PROF_RING; }
+  void begin(int st) {
+    if (!on(st)) return;
+    Profiler& pr = c->prof;
+    for (int e = 0; e < 2; ++e)
+      if (pr.ev[st][e] == nullptr) {
+        pr.ev[st][e] = new hipEvent_t[PROF_RING];
+        for (int i = 0; i < PROF_RING; ++i) (void)hipEventCreate(&pr.ev[st][e][i]);
+      }
+    (void)hipEventRecord(pr.ev[st][0][pr.count[st]], s);
+  }
+  void end(int st) {
+    if (!on(st)) return;
+    Profiler& pr = c->prof;
+    (void)hipEventRecord(pr.ev[st][1][pr.count[st]], s);
+    pr.count[st]++;
+  }
+};
+
+static void fill_param_set(const Dims& d, const tgnn_params* p, const tgnn_params* g, int first, SgdSet& set) {
+  memset(&set, 0, sizeof(set));
+  float* const* pp = reinterpret_cast<float* const*>(p);
+  float* const* gg = reinterpret_cast<float* const*>(g);
+  const int sizes[19] = {d.dt, d.dt, 3 * d.dm * d.d_in, 3 * d.dm * d.dm, 3 * d.dm, 3 * d.dm, d.dO * d.dq, d.dO,
+                         d.dO * d.dkv, d.dO, d.dO * d.dkv, d.dO, d.dO * (d.dO + d.dx), d.dO, d.dO * d.dO, d.dO * d.dO,
+                         d.dO, d.dO, 1};
+  for (int i = first; i < 19; ++i) {
+    set.p[set.cnt] = pp[i]; set.g[set.cnt] = gg ? gg[i] : nullptr; set.n[set.cnt] = sizes[i]; set.cnt++;
+  }
+}
+
 }  // namespace tgnn
 
 using namespace tgnn;
@@ -197,8 +232,8 @@ int32_t tgnn_create(const tgnn_config* cfg, tgnn_ctx** out) {
   d.N = cfg->n_nodes; d.dm = cfg->d_mem; d.dt = cfg->d_time; d.de = cfg->d_edge; d.ds = cfg->d_static;
   d.H = cfg->n_heads; d.k = cfg->k; d.nrep = cfg->n_replicas; d.maxB = cfg->max_batch; d.dt_source = cfg->dt_source;
   d.d_in = 2 * d.dm + d.dt + d.de; d.dx = d.dm + d.ds; d.dq = d.dx + d.dt; d.dkv = d.dx + d.de + d.dt; d.dO = d.dm;
-  d.ldx = pad16(d.d_in); d.ldh = pad16(d.dm); d.ld3 = pad16(3 * d.dm); d.ldc = pad16(d.dkv); d.ldq = pad16(d.dq);
-  d.ldkv = pad16(2 * d.dO); d.ldm = pad16(d.dO + d.dx); d.ldsub = pad16(d.dm + d.dt); d.ldt = pad16(d.dt);
+  d.ldx = padrow(d.d_in); d.ldh = padrow(d.dm); d.ld3 = padrow(3 * d.dm); d.ldc = padrow(d.dkv); d.ldq = padrow(d.dq);
+  d.ldkv = padrow(2 * d.dO); d.ldm = padrow(d.dO + d.dx); d.ldsub = padrow(d.dm + d.dt); d.ldt = padrow(d.dt);
   const int nb = d.nrep < TGNN_MAX_BATCHES ? d.nrep : TGNN_MAX_BATCHES;
   const long long maxEv = (long long)d.maxB * nb;
   if (maxEv * 3 * (1 + d.k) > 0x3fffffffLL) {
@@ -234,6 +269,12 @@ int32_t tgnn_destroy(tgnn_ctx* ctx) {
   if (ctx == nullptr) return TGNN_OK;
   hipError_t e = hipDeviceSynchronize();
   hipError_t e2 = hipFree(ctx->arena);
+  for (int st = 0; st < TGNN_N_STAGES; ++st)
+    for (int k2 = 0; k2 < 2; ++k2)
+      if (ctx->prof.ev[st][k2]) {
+        for (int i = 0; i < PROF_RING; ++i) (void)hipEventDestroy(ctx->prof.ev[st][k2][i]);
+        delete[] ctx->prof.ev[st][k2];
+      }
   delete ctx;
   if (e != hipSuccess) return set_error(TGNN_E_HIP, "hipDeviceSynchronize: %s", hipGetErrorString(e));
   if (e2 != hipSuccess) return set_error(TGNN_E_HIP, "hipFree: %s", hipGetErrorString(e2));
@@ -471,10 +512,17 @@ int32_t tgnn_train_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
   if (bs.total == 0) { TGNN_LAUNCH_CHECK(); return TGNN_OK; }
   const int R = 3 * bs.total, RK = R * d.k, S = R + RK, B2 = 2 * bs.total;
 
+  StageTimer tm{ctx, s};
+  tm.begin(0);
   pack_all(ctx, p, s);
+  tm.end(0);
+  tm.begin(1);
   build_roots(ctx, bs, s);
   writeback_mark(d, bs, w.winkey, s);
+  tm.end(1);
+  tm.begin(2);
   sample_recent(d, g, w.root_node, w.root_t, w.root_gid, R, w.nbr, w.neid, w.nts, w.cnt, w.slot_gid, w.slot_node, s);
+  tm.end(2);
 
   // UPDT for root and supporting nodes from the pre-batch state
   GatherArgs a;
@@ -488,8 +536,18 @@ int32_t tgnn_train_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
   a.o_tau = w.tau; a.o_delta = w.delta; a.o_has = w.has;
   a.time_w = p->time_w; a.time_b = p->time_b;
   a.n_slots = S; a.dm = d.dm; a.dt = d.dt; a.de = d.de;
+  tm.begin(3);
   gather_rows(a, s);
-  gru_forward(ctx, p, S, s);
+  tm.end(3);
+  tm.begin(4);
+  gemm_nt(w.X, d.ldx, w.Wih_p, d.ldx, p->gru_bih, w.gi, d.ld3, S, 3 * d.dm, d.ldx, d.ld3, false, s);
+  tm.end(4);
+  tm.begin(5);
+  gemm_nt(w.Hm, d.ldh, w.Whh_p, d.ldh, p->gru_bhh, w.gh, d.ld3, S, 3 * d.dm, d.ldh, d.ld3, false, s);
+  tm.end(5);
+  tm.begin(6);
+  gru_gates_fwd(d, S, w.gi, w.gh, w.Hm, w.has, w.gates, w.s_new, s);
+  tm.end(6);
 
   // attention + merge
   AttnAssembleArgs aa;
@@ -500,15 +558,31 @@ int32_t tgnn_train_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
   aa.time_w = p->time_w; aa.time_b = p->time_b;
   aa.Cmat = w.Cmat; aa.Qin = w.Qin; aa.Min = w.Min; aa.ldc = d.ldc; aa.ldq = d.ldq; aa.ldm = d.ldm; aa.dtk = w.dtk;
   aa.R = R; aa.k = d.k; aa.dm = d.dm; aa.ds = d.ds; aa.de = d.de; aa.dt = d.dt; aa.dO = d.dO; aa.dt_source = d.dt_source;
+  tm.begin(7);
   attn_assemble(aa, s);
-  attn_forward(ctx, p, R, w.cnt, s);
+  tm.end(7);
+  tm.begin(8);
+  gemm_nt(w.Cmat, d.ldc, w.Wkv_p, d.ldc, w.bkv_p, w.KV, d.ldkv, RK, 2 * d.dO, d.ldc, d.ldkv, false, s);
+  tm.end(8);
+  tm.begin(9);
+  gemm_nt(w.Qin, d.ldq, w.Wq_p, d.ldq, p->bq, w.q, d.ldh, R, d.dO, d.ldq, d.ldh, false, s);
+  tm.end(9);
+  tm.begin(10);
+  attn_core_fwd(d, R, w.q, d.ldh, w.KV, d.ldkv, w.cnt, w.prob, w.Min, d.ldm, s);
+  tm.end(10);
+  tm.begin(11);
+  gemm_nt(w.Min, d.ldm, w.Wo_p, d.ldm, p->bo, w.z, d.ldh, R, d.dO, d.ldm, d.ldh, true, s);
+  tm.end(11);
 
   // decoder + loss (also produces d loss / d hidden)
+  tm.begin(12);
   decoder_assemble(d, bs, w.z, d.ldh, w.Adec, d.ldkv, s);
   gemm_nt(w.Adec, d.ldkv, w.Wdec_p, d.ldkv, p->dec_b1, w.h1, d.ldh, B2, d.dO, d.ldkv, d.ldh, true, s);
   decoder_loss(d, bs, w.h1, d.ldh, p->dec_w2, p->dec_b2, w.logits, out_loss, w.dh1, grads->dec_w2, grads->dec_b2, s);
+  tm.end(12);
 
   // backward
+  tm.begin(13);
   OutMap dec;
   memset(&dec, 0, sizeof(dec));
   dec.p[0][0] = grads->dec_ws; dec.p[0][1] = grads->dec_wd; dec.ld[0][0] = dec.ld[0][1] = d.dO;
@@ -516,33 +590,71 @@ int32_t tgnn_train_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
   gemm_tn_acc(w.dh1, d.ldh, w.Adec, d.ldkv, B2, d.dO, 2 * d.dO, dec, s);
   gemm_nt(w.dh1, d.ldh, w.WdecT, d.ldh, nullptr, w.dAdec, d.ldkv, B2, 2 * d.dO, d.ldh, d.ldkv, false, s);
   decoder_dz(d, bs, w.dAdec, d.ldkv, w.z, d.ldh, w.dz, s);
+  tm.end(13);
+  tm.begin(14);
   attn_backward(ctx, grads, p, R, w.cnt, s);
+  tm.end(14);
+  tm.begin(15);
   gru_gates_bwd(d, R, S, w.dMin, d.ldm, w.dQsub, w.dCsub, d.ldsub, w.gates, w.Hm, w.has, w.dgi, w.dgh, s);
+  tm.end(15);
+  tm.begin(16);
   gemm_tn_acc(w.dgi, d.ld3, w.X, d.ldx, S, 3 * d.dm, d.d_in, single_out(grads->gru_wih, d.d_in, grads->gru_bih), s);
   gemm_tn_acc(w.dgh, d.ld3, w.Hm, d.ldh, S, 3 * d.dm, d.dm, single_out(grads->gru_whh, d.dm, grads->gru_bhh), s);
+  tm.end(16);
+  tm.begin(17);
   gemm_nt(w.dgi, d.ld3, w.WihT_phi, d.ld3, nullptr, w.dphi_g, d.ldt, S, d.dt, d.ld3, d.ldt, false, s);
   time_grad(w.dphi_g, d.ldt, 0, w.delta, nullptr, S, d.dt, p->time_w, p->time_b, grads->time_w, grads->time_b, s);
+  tm.end(17);
 
   if (lr != 0.0f) {
+    tm.begin(18);
     SgdSet set;
-    memset(&set, 0, sizeof(set));
-    float* const* pp = reinterpret_cast<float* const*>(p);
-    float* const* gg = reinterpret_cast<float* const*>(grads);
-    const int sizes[19] = {d.dt, d.dt, 3 * d.dm * d.d_in, 3 * d.dm * d.dm, 3 * d.dm, 3 * d.dm, d.dO * d.dq, d.dO,
-                           d.dO * d.dkv, d.dO, d.dO * d.dkv, d.dO, d.dO * (d.dO + d.dx), d.dO, d.dO * d.dO, d.dO * d.dO,
-                           d.dO, d.dO, 1};
-    for (int i = 2; i < 19; ++i) {  // time_w, time_b stay frozen
-      set.p[set.cnt] = pp[i]; set.g[set.cnt] = gg[i]; set.n[set.cnt] = sizes[i]; set.cnt++;
-    }
+    fill_param_set(d, p, grads, 2, set);  // time_w, time_b stay frozen
     sgd_update(set, lr, s);
+    tm.end(18);
   }
 
+  tm.begin(19);
   writeback_scatter(d, bs, st, w.winkey, w.s_new, d.ldh, w.tau, nullptr, nullptr, nullptr, nullptr, out_winner, s);
   writeback_clear(d, bs, w.winkey, s);
+  tm.end(19);
   if (out_logits)
     TGNN_HIP_CHECK(hipMemcpyAsync(out_logits, w.logits, sizeof(float) * B2, hipMemcpyDeviceToDevice, s));
   TGNN_LAUNCH_CHECK();
   ctx->last_attn_roots = -1;
+  return TGNN_OK;
+}
+
+int32_t tgnn_zero_params(tgnn_ctx* ctx, tgnn_params* g, void* stream) {
+  if (ctx == nullptr) return set_error(TGNN_E_NULL_PTR, "ctx is NULL");
+  if (int rc = check_params(g, "grads")) return rc;
+  SgdSet set;
+  fill_param_set(ctx->d, g, nullptr, 0, set);
+  zero_set(set, as_stream(stream));
+  TGNN_LAUNCH_CHECK();
+  return TGNN_OK;
+}
+
+int32_t tgnn_profile_enable(tgnn_ctx* ctx, uint32_t stage_mask) {
+  if (ctx == nullptr) return set_error(TGNN_E_NULL_PTR, "ctx is NULL");
+  ctx->prof.mask = stage_mask;
+  for (int i = 0; i < TGNN_N_STAGES; ++i) ctx->prof.count[i] = 0;
+  return TGNN_OK;
+}
+
+int32_t tgnn_profile_read(tgnn_ctx* ctx, int32_t stage, int32_t* out_count, double* out_total_ms) {
+  if (ctx == nullptr || out_count == nullptr || out_total_ms == nullptr) return set_error(TGNN_E_NULL_PTR, "NULL argument");
+  if (stage < 0 || stage >= TGNN_N_STAGES) return set_error(TGNN_E_OUT_OF_RANGE, "stage %d out of range", stage);
+  Profiler& pr = ctx->prof;
+  double total = 0.0;
+  for (int i = 0; i < pr.count[stage]; ++i) {
+    TGNN_HIP_CHECK(hipEventSynchronize(pr.ev[stage][1][i]));
+    float ms = 0.f;
+    TGNN_HIP_CHECK(hipEventElapsedTime(&ms, pr.ev[stage][0][i], pr.ev[stage][1][i]));
+    total += ms;
+  }
+  *out_count = pr.count[stage];
+  *out_total_ms = total;
   return TGNN_OK;
 }
 

@@ -10,9 +10,9 @@ namespace tgnn {
 
 constexpr int WAVE = 64;
 
-static inline int pad16(int x) { return (x + 15) & ~15; }
+static inline int padrow(int x) { return (x + 31) & ~31; }  // row pitches are multiples of 32 floats
 
-// Widths derived from the configuration, plus the row pitches (in floats, multiples of 16) of the
+// Widths derived from the configuration, plus the row pitches (in floats, multiples of 32) of the
 // workspace matrices.  Pad columns of every workspace matrix are kept at zero.
 struct Dims {
   int N, dm, dt, de, ds, H, k, nrep, maxB, dt_source;
@@ -68,7 +68,17 @@ struct Ws {
 
 }  // namespace tgnn
 
+namespace tgnn {
+constexpr int PROF_RING = 4096;
+struct Profiler {
+  uint32_t mask = 0;
+  hipEvent_t* ev[TGNN_N_STAGES][2] = {};  // lazily created rings
+  int count[TGNN_N_STAGES] = {};
+};
+}  // namespace tgnn
+
 struct tgnn_ctx {
+  tgnn::Profiler prof;
   tgnn_config cfg;
   tgnn::Dims d;
   void* arena;
@@ -91,7 +101,7 @@ int set_error(int code, const char* fmt, ...);
 
 // ---- k_gemm.hip ---------------------------------------------------------------------
 // C[m, n] = sum_k A[m, k] * B[n, k] + bias[n]  (m < M, n < N), optional ReLU; columns [N, n_store) of C are
-// set to zero.  Kp (multiple of 16) columns of A and B are read; B rows >= N and A rows >= M read as zero.
+// set to zero.  Kp (multiple of 32) columns of A and B are read; B rows >= N and A rows >= M read as zero.
 void gemm_nt(const float* A, int lda, const float* B, int ldb, const float* bias, float* C, int ldc, int M,
              int N, int Kp, int n_store, bool relu, hipStream_t s);
 
@@ -123,6 +133,7 @@ struct SgdSet {
   int cnt;
 };
 void sgd_update(const SgdSet& set, float lr, hipStream_t s);
+void zero_set(const SgdSet& set, hipStream_t s);
 
 // ---- k_sample.hip -------------------------------------------------------------------
 void build_roots(tgnn_ctx* ctx, const BatchSet& bs, hipStream_t s);

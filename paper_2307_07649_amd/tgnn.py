@@ -63,6 +63,9 @@ _SIGS = {
     "tgnn_train_step": (_I, [_P, C.POINTER(tgnn_graph), C.POINTER(tgnn_state), C.POINTER(tgnn_params),
                              C.POINTER(tgnn_params), C.POINTER(tgnn_batch), _I, C.c_float, _P, _P, _P, _P]),
     "tgnn_debug_read": (_I, [_P, _I, _P, C.c_int64, _P]),
+    "tgnn_zero_params": (_I, [_P, C.POINTER(tgnn_params), _P]),
+    "tgnn_profile_enable": (_I, [_P, C.c_uint32]),
+    "tgnn_profile_read": (_I, [_P, _I, C.POINTER(_I), C.POINTER(C.c_double)]),
 }
 EXPORTS = list(_SIGS)
 for _name, (_res, _args) in _SIGS.items():
@@ -258,6 +261,17 @@ class Context:
         arr = (tgnn_batch * len(batches))(*[b.c for b in batches])
         _check(_lib.tgnn_train_step(self.h, C.byref(g.c), C.byref(st.c), C.byref(p.c), C.byref(grads.c), arr,
                                     len(batches), lr, _ptr(out_loss), _ptr(out_logits), _ptr(out_winner), _stream()))
+
+    def tgnn_zero_params(self, grads: Params):
+        _check(_lib.tgnn_zero_params(self.h, C.byref(grads.c), _stream()))
+
+    def tgnn_profile_enable(self, stage_mask: int):
+        _check(_lib.tgnn_profile_enable(self.h, stage_mask))
+
+    def tgnn_profile_read(self, stage: int):
+        cnt = _I(0); ms = C.c_double(0.0)
+        _check(_lib.tgnn_profile_read(self.h, stage, C.byref(cnt), C.byref(ms)))
+        return cnt.value, ms.value
 
     def tgnn_debug_read(self, what, dst):
         _check(_lib.tgnn_debug_read(self.h, what, _ptr(dst), dst.numel() * dst.element_size(), _stream()))
