@@ -107,7 +107,8 @@ def main():
     P = make_problem(name, n_events=n_events)
     d = P["d"]
     nrep = d.n_replicas
-    ctx = tgnn.Context(d.n_nodes, d.d_mem, d.d_time, d.d_edge, d.d_static, d.n_heads, d.k, d.batch, n_replicas=nrep)
+    ctx = tgnn.Context(d.n_nodes, d.d_mem, d.d_time, d.d_edge, d.d_static, d.n_heads, d.k, d.batch, n_replicas=nrep,
+                       flags=tgnn.FLAG_OVERWRITE_GRADS)
     graph = tgnn.Graph(P["src"], P["dst"], P["ts"], d.n_nodes, P["efeat"])
     state = tgnn.State(d.n_nodes, d.d_mem, nrep, P["static"])
     params = tgnn.Params.from_numpy(P["params"])
@@ -132,7 +133,6 @@ def main():
             if m == 0 and s > 0:
                 ctx.tgnn_state_reset(state, r)
             bl.append(batches[r][m])
-        ctx.tgnn_zero_params(grads)
         ctx.tgnn_train_step(graph, state, params, grads, bl, lr=args.lr, out_loss=loss)
         return sum(b.n for b in bl)
 

@@ -39,6 +39,8 @@ extern "C" {
 #define TGNN_E_WORKSPACE (-7)
 #define TGNN_E_HIP (-8)
 
+#define TGNN_FLAG_OVERWRITE_GRADS 1 /* tgnn_train_step clears `grads` first instead of adding to them */
+
 #define TGNN_MAX_K 32        /* neighbours per root */
 #define TGNN_MAX_BATCHES 16  /* mini-batches (memory replicas) per tgnn_train_step call */
 #define TGNN_MAX_HEADS 8
@@ -51,7 +53,7 @@ typedef struct {
   int32_t n_replicas; /* independent memory/mailbox copies (memory parallelism, Sec. 3.2.3); >= 1 */
   int32_t dt_source;  /* time difference in the attention keys (Eq. 5-6): 0 = query time minus the update
                          time of the neighbour's memory as used (the paper's wording), 1 = minus the edge time */
-  int32_t flags;      /* reserved, 0 */
+  int32_t flags;      /* TGNN_FLAG_* bits */
 } tgnn_config;
 
 /* Temporal CSR: node v's incident events (both directions) are entries indptr[v] .. indptr[v+1]-1 of
@@ -176,7 +178,8 @@ int32_t tgnn_memory_writeback(tgnn_ctx* ctx, tgnn_state* st, int32_t replica, co
  * weight set: sample -> gather -> UPDT for root and supporting nodes -> attention -> decoder ->
  * loss = mean binary cross-entropy over each batch's n positive and n negative pairs -> backward (the
  * stored memory and mails are constants: no back-propagation through time) -> last-event-wins write-back.
- *   grads      gradients of sum_b loss_b are ADDED (+=) to these tensors;
+ *   grads      gradients of sum_b loss_b are ADDED (+=) to these tensors (with TGNN_FLAG_OVERWRITE_GRADS in the
+ *              configuration they are cleared first, inside the step);
  *   lr         if nonzero, plain SGD p -= lr * grads on every tensor except time_w/time_b after the
  *              backward pass (grads must then hold only this step's gradients, i.e. be zero on entry);
  *   out_loss   device scalar, mean over the batches of loss_b;
@@ -191,7 +194,7 @@ int32_t tgnn_train_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
 int32_t tgnn_zero_params(tgnn_ctx* ctx, tgnn_params* g, void* stream);
 
 /* Stage timing with HIP events on the call's own stream.  Stages of tgnn_train_step:
- *  0 pack weights   1 roots + write-back arbitration   2 sample   3 gather + time-encode (GRU input)
+ *  0 prologue (pack weights, clear loss/grads)   1 roots + write-back arbitration   2 sample   3 gather + time-encode (GRU input)
  *  4 GRU input projection (MFMA)   5 GRU hidden projection (MFMA)   6 GRU gates   7 attention input assembly
  *  8 K/V projection (MFMA)   9 query projection   10 softmax attention   11 merge layer   12 decoder forward + loss
  *  13 decoder backward   14 attention backward (GEMMs + softmax)   15 GRU gates backward

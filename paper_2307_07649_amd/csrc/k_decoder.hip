@@ -14,8 +14,9 @@ __device__ __forceinline__ int batch_of_row(const BatchSet& bs, int row, int mul
 }
 
 template <int VEC>
-__global__ __launch_bounds__(256) void dec_assemble_kernel(BatchSet bs, int dO, const float* __restrict__ z, int ldz,
+__global__ __launch_bounds__(256) void dec_assemble_kernel(const BatchSet* __restrict__ bsp, int dO, const float* __restrict__ z, int ldz,
                                                            float* __restrict__ Adec, int lda) {
+  const BatchSet& bs = *bsp;
   const int lane = threadIdx.x & 63;
   const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= 2 * bs.total) return;
@@ -30,10 +31,10 @@ __global__ __launch_bounds__(256) void dec_assemble_kernel(BatchSet bs, int dO, 
   wave_copy<VEC>(out + dO, z + (size_t)rb * ldz, dO, lda - 2 * dO, lane);
 }
 
-void decoder_assemble(const Dims& d, const BatchSet& bs, const float* z, int ldz, float* Adec, int lda,
+void decoder_assemble(const Dims& d, const BatchSet* bs, int total, const float* z, int ldz, float* Adec, int lda,
                       hipStream_t s) {
-  if (bs.total <= 0) return;
-  const int blocks = (2 * bs.total + 3) / 4;
+  if (total <= 0) return;
+  const int blocks = (2 * total + 3) / 4;
   if (d.dO % 4 == 0) hipLaunchKernelGGL(dec_assemble_kernel<4>, dim3(blocks), dim3(256), 0, s, bs, d.dO, z, ldz, Adec, lda);
   else hipLaunchKernelGGL(dec_assemble_kernel<1>, dim3(blocks), dim3(256), 0, s, bs, d.dO, z, ldz, Adec, lda);
 }
@@ -41,12 +42,13 @@ void decoder_assemble(const Dims& d, const BatchSet& bs, const float* z, int ldz
 // Per row: logit, loss term, d(loss)/d(logit), gradient into the hidden layer; per block: partial sums of
 // the w2 / b2 gradients.  loss = mean over batches of (1 / 2n_b) sum softplus(-+logit).
 constexpr int DL_ROWS = 16;  // rows per block
-__global__ __launch_bounds__(256) void dec_loss_kernel(BatchSet bs, int dO, const float* __restrict__ h1, int ldh,
+__global__ __launch_bounds__(256) void dec_loss_kernel(const BatchSet* __restrict__ bsp, int dO, const float* __restrict__ h1, int ldh,
                                                        const float* __restrict__ w2, const float* __restrict__ b2,
                                                        float* __restrict__ logits, float* __restrict__ out_loss,
                                                        float* __restrict__ dh1, float* __restrict__ g_w2,
                                                        float* __restrict__ g_b2) {
   __shared__ float red[4][260];
+  const BatchSet& bs = *bsp;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int rows = 2 * bs.total;
   float gw[4] = {0.f, 0.f, 0.f, 0.f};  // columns lane, lane+64, lane+128, lane+192
@@ -92,16 +94,17 @@ __global__ __launch_bounds__(256) void dec_loss_kernel(BatchSet bs, int dO, cons
   }
 }
 
-void decoder_loss(const Dims& d, const BatchSet& bs, const float* h1, int ldh, const float* w2, const float* b2,
+void decoder_loss(const Dims& d, const BatchSet* bs, int total, const float* h1, int ldh, const float* w2, const float* b2,
                   float* logits, float* out_loss, float* dh1, float* g_w2, float* g_b2, hipStream_t s) {
-  if (bs.total <= 0) return;
-  hipLaunchKernelGGL(dec_loss_kernel, dim3((2 * bs.total + DL_ROWS - 1) / DL_ROWS), dim3(256), 0, s, bs, d.dO, h1, ldh,
+  if (total <= 0) return;
+  hipLaunchKernelGGL(dec_loss_kernel, dim3((2 * total + DL_ROWS - 1) / DL_ROWS), dim3(256), 0, s, bs, d.dO, h1, ldh,
                      w2, b2, logits, out_loss, dh1, g_w2, g_b2);
 }
 
 // dz (already multiplied by the ReLU mask of the merge layer) per root from the decoder-input gradient.
-__global__ void dec_dz_kernel(BatchSet bs, int dO, const float* __restrict__ dA, int lda, const float* __restrict__ z,
+__global__ void dec_dz_kernel(const BatchSet* __restrict__ bsp, int dO, const float* __restrict__ dA, int lda, const float* __restrict__ z,
                               int ldz, float* __restrict__ dz) {
+  const BatchSet& bs = *bsp;
   const long long total = 3LL * bs.total * dO;
   for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < total;
        i += (long long)gridDim.x * blockDim.x) {
@@ -119,10 +122,10 @@ __global__ void dec_dz_kernel(BatchSet bs, int dO, const float* __restrict__ dA,
   }
 }
 
-void decoder_dz(const Dims& d, const BatchSet& bs, const float* dAdec, int lda, const float* z, int ldz, float* dz,
-                hipStream_t s) {
-  if (bs.total <= 0) return;
-  const long long total = 3LL * bs.total * d.dO;
+void decoder_dz(const Dims& d, const BatchSet* bs, int total_ev, const float* dAdec, int lda, const float* z, int ldz,
+                float* dz, hipStream_t s) {
+  if (total_ev <= 0) return;
+  const long long total = 3LL * total_ev * d.dO;
   hipLaunchKernelGGL(dec_dz_kernel, dim3((int)((total + 255) / 256)), dim3(256), 0, s, bs, d.dO, dAdec, lda, z, ldz, dz);
 }
 

@@ -36,7 +36,13 @@ __global__ __launch_bounds__(256) void gather_kernel(GatherArgs a) {
     }
     const double delta = has ? mail_ts - mem_ts : 0.0;
     if (o_phi) {
-      for (int c = lane; c < a.dt; c += 64) o_phi[c] = time_enc(delta, a.time_w[c], a.time_b[c]);
+      float* o_ms = a.o_msin ? a.o_msin + (size_t)s * a.p_msin : nullptr;
+      for (int c = lane; c < a.dt; c += 64) {
+        float sn, cs;
+        sincos_reduced(fma((double)a.time_w[c], delta, (double)a.time_b[c]), sn, cs);
+        o_phi[c] = cs;
+        if (o_ms) o_ms[c] = -sn;
+      }
       for (int c = lane; c < a.z_phi; c += 64) o_phi[a.dt + c] = 0.f;
     }
     if (lane == 0) {
@@ -92,7 +98,13 @@ __global__ __launch_bounds__(256) void attn_assemble_kernel(AttnAssembleArgs a) 
       const double delta = a.dt_in ? a.dt_in[row]
                                    : a.root_t[r] - (a.dt_source == 0 ? a.tau_nbr[row] : a.nts[row]);
       float* phi = out + dx + a.de;
-      for (int c = lane; c < a.dt; c += 64) phi[c] = time_enc(delta, a.time_w[c], a.time_b[c]);
+      float* ms = a.msin + (size_t)row * a.p_msin;
+      for (int c = lane; c < a.dt; c += 64) {
+        float sn, cs;
+        sincos_reduced(fma((double)a.time_w[c], delta, (double)a.time_b[c]), sn, cs);
+        phi[c] = cs;
+        ms[c] = -sn;
+      }
       for (int c = dkv + lane; c < a.ldc; c += 64) out[c] = 0.f;
       if (lane == 0) a.dtk[row] = delta;
     } else {

@@ -93,53 +93,53 @@ void gru_gates_bwd(const Dims& d, int R, int n, const float* dMin, int ldm, cons
                      dCsub, ldsub, gates, Hm, has, dgi, dgh);
 }
 
-// g_w[c] += sum_n dphi[n, col0 + c] * (-sin(w_c delta_n + b_c)) * delta_n ;  g_b[c] += sum_n dphi * (-sin(..))
-constexpr int TG_ROWS = 64;
+// g_b[c] += sum_n dphi[n, col0 + c] * msin[n, c] ;  g_w[c] += sum_n dphi * msin * delta_n.
+// A block owns a contiguous range of rows; thread (cy, cx) sums rows cy, cy + 4, ... of column cx (+64, ...).
+// Few blocks (<= 128): every block ends with one atomic per column, and atomics on one address serialise.
+constexpr int TG_MAX_BLOCKS = 128;
 __global__ __launch_bounds__(256) void time_grad_kernel(const float* __restrict__ dphi, int ld, int col0,
-                                                        const double* __restrict__ delta, int n, int dt,
-                                                        const float* __restrict__ time_w,
-                                                        const float* __restrict__ time_b, float* __restrict__ g_w,
-                                                        float* __restrict__ g_b) {
+                                                        const float* __restrict__ msin, int p_msin,
+                                                        const double* __restrict__ delta, int n, int rows_per_block,
+                                                        int dt, const float* __restrict__ time_b,
+                                                        float* __restrict__ g_w, float* __restrict__ g_b) {
   __shared__ float sw[4][64], sb[4][64];
   const int cx = threadIdx.x & 63, cy = threadIdx.x >> 6;
-  const int r0 = blockIdx.x * TG_ROWS;
-  const int r1 = min(n, r0 + TG_ROWS);
+  const int r0 = blockIdx.x * rows_per_block;
+  const int r1 = min(n, r0 + rows_per_block);
   for (int c0 = 0; c0 < dt; c0 += 64) {
     const int c = c0 + cx;
     float aw = 0.f, ab = 0.f;
     if (c < dt) {
-      const float w = time_w[c], b = time_b[c];
-      for (int r = r0 + cy; r < r1; r += 4) {
-        const float g = dphi[(size_t)r * ld + col0 + c];
-        if (g != 0.f) {
-          const double dl = delta ? delta[r] : 0.0;
-          float sn, cs;
-          sincos_reduced(fma((double)w, dl, (double)b), sn, cs);
-          const float t = -g * sn;
+      if (msin != nullptr) {
+        for (int r = r0 + cy; r < r1; r += 4) {
+          const float t = dphi[(size_t)r * ld + col0 + c] * msin[(size_t)r * p_msin + c];
           ab += t;
-          aw += t * (float)dl;
+          aw += t * (float)delta[r];
         }
+      } else {
+        float sn, cs;
+        sincos_reduced((double)time_b[c], sn, cs);
+        for (int r = r0 + cy; r < r1; r += 4) ab -= dphi[(size_t)r * ld + col0 + c] * sn;
       }
     }
     sw[cy][cx] = aw;
     sb[cy][cx] = ab;
     __syncthreads();
     if (cy == 0 && c < dt) {
-      const float tw = sw[0][cx] + sw[1][cx] + sw[2][cx] + sw[3][cx];
-      const float tb = sb[0][cx] + sb[1][cx] + sb[2][cx] + sb[3][cx];
-      if (delta) atomicAdd(g_w + c, tw);
-      atomicAdd(g_b + c, tb);
+      if (msin != nullptr) atomicAdd(g_w + c, sw[0][cx] + sw[1][cx] + sw[2][cx] + sw[3][cx]);
+      atomicAdd(g_b + c, sb[0][cx] + sb[1][cx] + sb[2][cx] + sb[3][cx]);
     }
     __syncthreads();
   }
 }
 
-void time_grad(const float* dphi, int ld, int col0, const double* delta, const int32_t* valid, int n, int dt,
-               const float* time_w, const float* time_b, float* g_w, float* g_b, hipStream_t s) {
-  (void)valid;
+void time_grad(const float* dphi, int ld, int col0, const float* msin, int p_msin, const double* delta, int n, int dt,
+               const float* time_b, float* g_w, float* g_b, hipStream_t s) {
   if (n <= 0) return;
-  hipLaunchKernelGGL(time_grad_kernel, dim3((n + TG_ROWS - 1) / TG_ROWS), dim3(256), 0, s, dphi, ld, col0, delta, n, dt,
-                     time_w, time_b, g_w, g_b);
+  int rpb = (n + TG_MAX_BLOCKS - 1) / TG_MAX_BLOCKS;
+  rpb = (rpb + 3) & ~3;
+  hipLaunchKernelGGL(time_grad_kernel, dim3((n + rpb - 1) / rpb), dim3(256), 0, s, dphi, ld, col0, msin, p_msin, delta,
+                     n, rpb, dt, time_b, g_w, g_b);
 }
 
 }  // namespace tgnn

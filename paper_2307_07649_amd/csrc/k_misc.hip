@@ -1,58 +1,101 @@
 // Small utility kernels: weight packing into padded / transposed workspace copies, state reset, SGD.
+#include <string.h>
+
 #include "tgnn_internal.h"
 
 namespace tgnn {
 
 constexpr int MAX_PACK = 24;
-struct PackSet {
+struct PrologueArgs {
   PackDesc d[MAX_PACK];
+  int n_pack;
+  SgdSet zero;          // tensors to clear (cnt = 0: none)
+  BatchSet bs;          // copied to *bs_dev when bs_dev != NULL
+  BatchSet* bs_dev;
+  SgdSet sgd;           // copied to *sgd_dev when sgd_dev != NULL
+  SgdSet* sgd_dev;
+  float* loss;
+  unsigned long long* epoch;
 };
 
-__global__ void pack_kernel(PackSet set) {
-  const PackDesc d = set.d[blockIdx.y];
-  const int total = d.rows * d.zero_to;
-  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < total; i += gridDim.x * blockDim.x) {
-    const int r = i / d.zero_to, c = i - r * d.zero_to;
-    d.dst[(size_t)r * d.ldd + c] = c < d.cols ? d.src[(size_t)r * d.srs + (size_t)c * d.scs] : 0.f;
+__global__ void prologue_kernel(PrologueArgs a) {
+  const int y = blockIdx.y;
+  if (y < a.n_pack) {
+    const PackDesc d = a.d[y];
+    const int total = d.rows * d.zero_to;
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < total; i += gridDim.x * blockDim.x) {
+      const int r = i / d.zero_to, c = i - r * d.zero_to;
+      d.dst[(size_t)r * d.ldd + c] = c < d.cols ? d.src[(size_t)r * d.srs + (size_t)c * d.scs] : 0.f;
+    }
+  } else if (y < a.n_pack + a.zero.cnt) {
+    float* p = a.zero.p[y - a.n_pack];
+    const int n = a.zero.n[y - a.n_pack];
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) p[i] = 0.f;
+  } else if (blockIdx.x == 0) {
+    if (a.bs_dev) {
+      const int* src = reinterpret_cast<const int*>(&a.bs);
+      int* dst = reinterpret_cast<int*>(a.bs_dev);
+      for (int i = threadIdx.x; i < (int)(sizeof(BatchSet) / sizeof(int)); i += blockDim.x) dst[i] = src[i];
+    }
+    if (a.sgd_dev) {
+      const int* src = reinterpret_cast<const int*>(&a.sgd);
+      int* dst = reinterpret_cast<int*>(a.sgd_dev);
+      for (int i = threadIdx.x; i < (int)(sizeof(SgdSet) / sizeof(int)); i += blockDim.x) dst[i] = src[i];
+    }
+    if (threadIdx.x == 0) {
+      if (a.loss) *a.loss = 0.f;
+      *a.epoch += 1ull;
+    }
   }
 }
 
 // Padded copies of the weights (row pitch = the pitch of the activation matrix they multiply) and the
 // transposed copies / column subsets that the data-gradient GEMMs read.
-void pack_all(tgnn_ctx* ctx, const tgnn_params* p, hipStream_t s) {
+void prologue(tgnn_ctx* ctx, const tgnn_params* p, const BatchSet* bs, const SgdSet* sgd, const SgdSet* zero,
+              float* loss, hipStream_t s) {
   const Dims& d = ctx->d;
   Ws& w = ctx->w;
-  PackSet set;
+  static_assert(sizeof(PrologueArgs) <= 4096, "kernel argument block too large");
+  PrologueArgs pa;
+  memset(&pa, 0, sizeof(pa));
   int n = 0;
   auto add = [&](const float* src, float* dst, int rows, int cols, int zero_to, int ldd, int srs, int scs) {
-    set.d[n++] = PackDesc{src, dst, rows, cols, zero_to, ldd, srs, scs};
+    pa.d[n++] = PackDesc{src, dst, rows, cols, zero_to, ldd, srs, scs};
   };
-  const int dO = d.dO, dm = d.dm;
-  add(p->gru_wih, w.Wih_p, 3 * dm, d.d_in, d.ldx, d.ldx, d.d_in, 1);
-  add(p->gru_whh, w.Whh_p, 3 * dm, dm, d.ldh, d.ldh, dm, 1);
-  add(p->wk, w.Wkv_p, dO, d.dkv, d.ldc, d.ldc, d.dkv, 1);
-  add(p->wv, w.Wkv_p + (size_t)dO * d.ldc, dO, d.dkv, d.ldc, d.ldc, d.dkv, 1);
-  add(p->wq, w.Wq_p, dO, d.dq, d.ldq, d.ldq, d.dq, 1);
-  add(p->wo, w.Wo_p, dO, dO + d.dx, d.ldm, d.ldm, dO + d.dx, 1);
-  // decoder input is {z_a | z_b}: weights side by side
-  add(p->dec_ws, w.Wdec_p, dO, dO, dO, d.ldkv, dO, 1);
-  add(p->dec_wd, w.Wdec_p + dO, dO, dO, d.ldkv - dO, d.ldkv, dO, 1);
-  // transposes: XT[c, n] = X[n, c]
-  add(p->dec_ws, w.WdecT, dO, dO, d.ldh, d.ldh, 1, dO);
-  add(p->dec_wd, w.WdecT + (size_t)dO * d.ldh, dO, dO, d.ldh, d.ldh, 1, dO);
-  add(p->wo, w.WoT, dO + d.dx, dO, d.ldh, d.ldh, 1, dO + d.dx);
-  // columns of {W_k ; W_v} that multiply the dynamic memory (first d_m) and the time encoding (last d_t)
-  const int phi_kv = d.dx + d.de;
-  add(p->wk, w.WkvT_sub, dm, dO, dO, d.ldkv, 1, d.dkv);
-  add(p->wv, w.WkvT_sub + dO, dm, dO, d.ldkv - dO, d.ldkv, 1, d.dkv);
-  add(p->wk + phi_kv, w.WkvT_sub + (size_t)dm * d.ldkv, d.dt, dO, dO, d.ldkv, 1, d.dkv);
-  add(p->wv + phi_kv, w.WkvT_sub + (size_t)dm * d.ldkv + dO, d.dt, dO, d.ldkv - dO, d.ldkv, 1, d.dkv);
-  add(p->wq, w.WqT_sub, dm, dO, d.ldh, d.ldh, 1, d.dq);
-  add(p->wq + d.dx, w.WqT_sub + (size_t)dm * d.ldh, d.dt, dO, d.ldh, d.ldh, 1, d.dq);
-  add(p->gru_wih + 2 * dm, w.WihT_phi, d.dt, 3 * dm, d.ld3, d.ld3, 1, d.d_in);
-  add(p->bk, w.bkv_p, 1, dO, dO, 2 * dO, 0, 1);
-  add(p->bv, w.bkv_p + dO, 1, dO, dO, 2 * dO, 0, 1);
-  hipLaunchKernelGGL(pack_kernel, dim3(32, n), dim3(256), 0, s, set);
+  if (p != nullptr) {
+    const int dO = d.dO, dm = d.dm;
+    add(p->gru_wih, w.Wih_p, 3 * dm, d.d_in, d.ldx, d.ldx, d.d_in, 1);
+    add(p->gru_whh, w.Whh_p, 3 * dm, dm, d.ldh, d.ldh, dm, 1);
+    add(p->wk, w.Wkv_p, dO, d.dkv, d.ldc, d.ldc, d.dkv, 1);
+    add(p->wv, w.Wkv_p + (size_t)dO * d.ldc, dO, d.dkv, d.ldc, d.ldc, d.dkv, 1);
+    add(p->wq, w.Wq_p, dO, d.dq, d.ldq, d.ldq, d.dq, 1);
+    add(p->wo, w.Wo_p, dO, dO + d.dx, d.ldm, d.ldm, dO + d.dx, 1);
+    // decoder input is {z_a | z_b}: weights side by side
+    add(p->dec_ws, w.Wdec_p, dO, dO, dO, d.ldkv, dO, 1);
+    add(p->dec_wd, w.Wdec_p + dO, dO, dO, d.ldkv - dO, d.ldkv, dO, 1);
+    // transposes: XT[c, n] = X[n, c]
+    add(p->dec_ws, w.WdecT, dO, dO, d.ldh, d.ldh, 1, dO);
+    add(p->dec_wd, w.WdecT + (size_t)dO * d.ldh, dO, dO, d.ldh, d.ldh, 1, dO);
+    add(p->wo, w.WoT, dO + d.dx, dO, d.ldh, d.ldh, 1, dO + d.dx);
+    // columns of {W_k ; W_v} that multiply the dynamic memory (first d_m) and the time encoding (last d_t)
+    const int phi_kv = d.dx + d.de;
+    add(p->wk, w.WkvT_sub, dm, dO, dO, d.ldkv, 1, d.dkv);
+    add(p->wv, w.WkvT_sub + dO, dm, dO, d.ldkv - dO, d.ldkv, 1, d.dkv);
+    add(p->wk + phi_kv, w.WkvT_sub + (size_t)dm * d.ldkv, d.dt, dO, dO, d.ldkv, 1, d.dkv);
+    add(p->wv + phi_kv, w.WkvT_sub + (size_t)dm * d.ldkv + dO, d.dt, dO, d.ldkv - dO, d.ldkv, 1, d.dkv);
+    add(p->wq, w.WqT_sub, dm, dO, d.ldh, d.ldh, 1, d.dq);
+    add(p->wq + d.dx, w.WqT_sub + (size_t)dm * d.ldh, d.dt, dO, d.ldh, d.ldh, 1, d.dq);
+    add(p->gru_wih + 2 * dm, w.WihT_phi, d.dt, 3 * dm, d.ld3, d.ld3, 1, d.d_in);
+    add(p->bk, w.bkv_p, 1, dO, dO, 2 * dO, 0, 1);
+    add(p->bv, w.bkv_p + dO, 1, dO, dO, 2 * dO, 0, 1);
+  }
+  pa.n_pack = n;
+  if (zero) pa.zero = *zero;
+  if (bs) { pa.bs = *bs; pa.bs_dev = w.bs_dev; }
+  if (sgd) { pa.sgd = *sgd; pa.sgd_dev = w.sgd_dev; }
+  pa.loss = loss;
+  pa.epoch = w.epoch;
+  hipLaunchKernelGGL(prologue_kernel, dim3(32, n + pa.zero.cnt + 1), dim3(256), 0, s, pa);
 }
 
 __global__ void fill_state_kernel(float* mem, double* mem_ts, float* mail, double* mail_ts, int32_t* mail_eid,
@@ -78,16 +121,16 @@ void fill_state(tgnn_ctx* ctx, tgnn_state* st, int replica, hipStream_t s) {
                      st->mail_eid, row0, rows, d.dm);
 }
 
-__global__ void sgd_kernel(SgdSet set, float lr) {
+__global__ void sgd_kernel(const SgdSet* __restrict__ set, float lr) {
   const int t = blockIdx.y;
-  float* p = set.p[t];
-  const float* g = set.g[t];
-  const int n = set.n[t];
+  float* p = set->p[t];
+  const float* g = set->g[t];
+  const int n = set->n[t];
   for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) p[i] -= lr * g[i];
 }
 
-void sgd_update(const SgdSet& set, float lr, hipStream_t s) {
-  hipLaunchKernelGGL(sgd_kernel, dim3(64, set.cnt), dim3(256), 0, s, set, lr);
+void sgd_update(const SgdSet* set_dev, int cnt, float lr, hipStream_t s) {
+  hipLaunchKernelGGL(sgd_kernel, dim3(64, cnt), dim3(256), 0, s, set_dev, lr);
 }
 
 __global__ void zero_set_kernel(SgdSet set) {

@@ -5,32 +5,37 @@
 
 namespace tgnn {
 
-__global__ void roots_kernel(BatchSet bs, int N, int32_t* root_node, int32_t* root_gid, int32_t* root_batch,
-                             double* root_t, int32_t* slot_gid, int32_t* slot_node) {
+__global__ void roots_kernel(const BatchSet* __restrict__ bsp, int N, int32_t* root_node, int32_t* root_gid,
+                             int32_t* root_batch, double* root_t, int32_t* slot_gid, int32_t* slot_node,
+                             unsigned long long* winkey, const unsigned long long* __restrict__ epoch) {
+  const BatchSet& bs = *bsp;
   const int e = blockIdx.x * blockDim.x + threadIdx.x;
   if (e >= bs.total) return;
   int b = 0;
   while (b + 1 < bs.nb && e >= bs.b[b + 1].ev_off) ++b;
-  const BatchDesc& bd = bs.b[b];
+  const BatchDesc bd = bs.b[b];
   const int i = e - bd.ev_off;
   const double t = bd.t[i];
   const int nodes[3] = {bd.src[i], bd.dst[i], bd.neg[i]};
+  const unsigned long long ep = *epoch;
 #pragma unroll
   for (int role = 0; role < 3; ++role) {
     const int r = 3 * bd.ev_off + role * bd.n + i;
+    const int gid = bd.replica * N + nodes[role];
     root_node[r] = nodes[role];
-    root_gid[r] = bd.replica * N + nodes[role];
+    root_gid[r] = gid;
     root_batch[r] = b;
     root_t[r] = t;
-    slot_gid[r] = bd.replica * N + nodes[role];
+    slot_gid[r] = gid;
     slot_node[r] = nodes[role];
+    if (role < 2) atomicMax(winkey + gid, wb_key(ep, e, role));   // last-event-wins arbitration
   }
 }
 
-void build_roots(tgnn_ctx* ctx, const BatchSet& bs, hipStream_t s) {
+void build_roots(tgnn_ctx* ctx, int total, hipStream_t s) {
   Ws& w = ctx->w;
-  hipLaunchKernelGGL(roots_kernel, dim3((bs.total + 255) / 256), dim3(256), 0, s, bs, ctx->d.N, w.root_node,
-                     w.root_gid, w.root_batch, w.root_t, w.slot_gid, w.slot_node);
+  hipLaunchKernelGGL(roots_kernel, dim3((total + 255) / 256), dim3(256), 0, s, w.bs_dev, ctx->d.N, w.root_node,
+                     w.root_gid, w.root_batch, w.root_t, w.slot_gid, w.slot_node, w.winkey, w.epoch);
 }
 
 // gid = replica * N + node for roots of the fused step (root_gid given), plain node ids otherwise.

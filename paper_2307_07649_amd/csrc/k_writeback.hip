@@ -1,7 +1,8 @@
 // Last-event-wins write-back: COMB keeps the most recent mail of a batch (Eq. 8, Sec. 2.1.1) and only
 // root nodes are written (Sec. 3.2.1).  Arbitration is a segmented maximum over occurrence keys, taken
 // with a 64-bit atomic max on a per-(replica, node) scratch word; maximum is order-independent, so the
-// winners are deterministic.  Occurrence (event e = off + i, role) has key 1 + 2e + role; 0 = idle.
+// winners are deterministic.  Occurrence (event e = off + i, role) has key 1 + 2e + role, prefixed by a
+// per-step epoch counter so that the words never need clearing: entries of earlier steps always lose.
 #include "tgnn_internal.h"
 #include "device_math.h"
 
@@ -17,18 +18,20 @@ __device__ __forceinline__ bool occ_decode(const BatchSet& bs, int o, int& b, in
   return true;
 }
 
-__global__ void wb_mark_kernel(BatchSet bs, int N, unsigned long long* winkey) {
+__global__ void wb_mark_kernel(const BatchSet* __restrict__ bsp, int N, unsigned long long* winkey,
+                               const unsigned long long* __restrict__ epoch) {
+  const BatchSet& bs = *bsp;
   int b, i, role;
   if (!occ_decode(bs, blockIdx.x * blockDim.x + threadIdx.x, b, i, role)) return;
   const BatchDesc& bd = bs.b[b];
   const int node = role ? bd.dst[i] : bd.src[i];
-  const unsigned long long key = 1ull + 2ull * (unsigned long long)(bd.ev_off + i) + (unsigned long long)role;
-  atomicMax(winkey + (size_t)bd.replica * N + node, key);
+  atomicMax(winkey + (size_t)bd.replica * N + node, wb_key(*epoch, bd.ev_off + i, role));
 }
 
-void writeback_mark(const Dims& d, const BatchSet& bs, unsigned long long* winkey, hipStream_t s) {
-  if (bs.total <= 0) return;
-  hipLaunchKernelGGL(wb_mark_kernel, dim3((2 * bs.total + 255) / 256), dim3(256), 0, s, bs, d.N, winkey);
+void writeback_mark(const Dims& d, const BatchSet* bs, int total, unsigned long long* winkey,
+                    const unsigned long long* epoch, hipStream_t s) {
+  if (total <= 0) return;
+  hipLaunchKernelGGL(wb_mark_kernel, dim3((2 * total + 255) / 256), dim3(256), 0, s, bs, d.N, winkey, epoch);
 }
 
 struct WbPtrs {
@@ -41,9 +44,11 @@ struct WbPtrs {
 };
 
 template <int VEC>
-__global__ __launch_bounds__(256) void wb_scatter_kernel(BatchSet bs, int N, int dm, WbPtrs w,
+__global__ __launch_bounds__(256) void wb_scatter_kernel(const BatchSet* __restrict__ bsp, int N, int dm, WbPtrs w,
                                                          const unsigned long long* __restrict__ winkey,
+                                                         const unsigned long long* __restrict__ epoch,
                                                          int32_t* __restrict__ out_winner) {
+  const BatchSet& bs = *bsp;
   const int lane = threadIdx.x & 63;
   int b, i, role;
   const int o = blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -51,8 +56,7 @@ __global__ __launch_bounds__(256) void wb_scatter_kernel(BatchSet bs, int N, int
   const BatchDesc& bd = bs.b[b];
   const int node = role ? bd.dst[i] : bd.src[i];
   const size_t gid = (size_t)bd.replica * N + node;
-  const unsigned long long key = 1ull + 2ull * (unsigned long long)(bd.ev_off + i) + (unsigned long long)role;
-  const bool win = winkey[gid] == key;
+  const bool win = winkey[gid] == wb_key(*epoch, bd.ev_off + i, role);
   if (lane == 0 && out_winner) out_winner[o] = win ? 1 : 0;
   if (!win) return;
   const float *self_row, *other_row;
@@ -77,29 +81,17 @@ __global__ __launch_bounds__(256) void wb_scatter_kernel(BatchSet bs, int N, int
   }
 }
 
-void writeback_scatter(const Dims& d, const BatchSet& bs, const tgnn_state* st, unsigned long long* winkey,
-                       const float* s_new, int p_s, const double* tau, const float* s_src, const float* s_dst,
-                       const double* tau_src, const double* tau_dst, int32_t* out_winner, hipStream_t s) {
-  if (bs.total <= 0) return;
+void writeback_scatter(const Dims& d, const BatchSet* bs, int total, const tgnn_state* st,
+                       const unsigned long long* winkey, const unsigned long long* epoch, const float* s_new, int p_s,
+                       const double* tau, const float* s_src, const float* s_dst, const double* tau_src,
+                       const double* tau_dst, int32_t* out_winner, hipStream_t s) {
+  if (total <= 0) return;
   WbPtrs w{st->mem, st->mail, st->mem_ts, st->mail_ts, st->mail_eid, s_new, s_src, s_dst, tau, tau_src, tau_dst, p_s};
-  const int blocks = (2 * bs.total + 3) / 4;
+  const int blocks = (2 * total + 3) / 4;
   if (d.dm % 4 == 0 && p_s % 4 == 0)
-    hipLaunchKernelGGL(wb_scatter_kernel<4>, dim3(blocks), dim3(256), 0, s, bs, d.N, d.dm, w, winkey, out_winner);
+    hipLaunchKernelGGL(wb_scatter_kernel<4>, dim3(blocks), dim3(256), 0, s, bs, d.N, d.dm, w, winkey, epoch, out_winner);
   else
-    hipLaunchKernelGGL(wb_scatter_kernel<1>, dim3(blocks), dim3(256), 0, s, bs, d.N, d.dm, w, winkey, out_winner);
-}
-
-__global__ void wb_clear_kernel(BatchSet bs, int N, unsigned long long* winkey) {
-  int b, i, role;
-  if (!occ_decode(bs, blockIdx.x * blockDim.x + threadIdx.x, b, i, role)) return;
-  const BatchDesc& bd = bs.b[b];
-  const int node = role ? bd.dst[i] : bd.src[i];
-  winkey[(size_t)bd.replica * N + node] = 0ull;
-}
-
-void writeback_clear(const Dims& d, const BatchSet& bs, unsigned long long* winkey, hipStream_t s) {
-  if (bs.total <= 0) return;
-  hipLaunchKernelGGL(wb_clear_kernel, dim3((2 * bs.total + 255) / 256), dim3(256), 0, s, bs, d.N, winkey);
+    hipLaunchKernelGGL(wb_scatter_kernel<1>, dim3(blocks), dim3(256), 0, s, bs, d.N, d.dm, w, winkey, epoch, out_winner);
 }
 
 }  // namespace tgnn

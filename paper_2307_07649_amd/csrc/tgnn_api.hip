@@ -89,6 +89,10 @@ static void layout(const Dims& d, Ws& w, Bump& b) {
   w.slot_gid = b.take<int32_t>(S); w.slot_node = b.take<int32_t>(S); w.has = b.take<int32_t>(S);
   w.tau = b.take<double>(S); w.delta = b.take<double>(S); w.dtk = b.take<double>(RK);
   w.winkey = b.take<unsigned long long>((size_t)d.nrep * d.N);
+  w.epoch = b.take<unsigned long long>(1);
+  w.bs_dev = b.take<BatchSet>(1);
+  w.sgd_dev = b.take<SgdSet>(1);
+  w.msinX = b.take<float>(S * d.ldt); w.msinC = b.take<float>(RK * d.ldt);
   w.X = b.take<float>(S * d.ldx); w.Hm = b.take<float>(S * d.ldh);
   w.gi = b.take<float>(S * d.ld3); w.gh = b.take<float>(S * d.ld3);
   w.gates = b.take<float>(S * 4 * d.ldh); w.s_new = b.take<float>(S * d.ldh);
@@ -156,8 +160,8 @@ static void attn_backward(tgnn_ctx* ctx, tgnn_params* g, const tgnn_params* p, i
   gemm_nt(w.dKV, d.ldkv, w.WkvT_sub, d.ldkv, nullptr, w.dCsub, d.ldsub, RK, d.dm + d.dt, d.ldkv, d.ldsub, false, s);
   gemm_tn_acc(w.dq, d.ldh, w.Qin, d.ldq, R, d.dO, d.dq, single_out(g->wq, d.dq, g->bq), s);
   gemm_nt(w.dq, d.ldh, w.WqT_sub, d.ldh, nullptr, w.dQsub, d.ldsub, R, d.dm + d.dt, d.ldh, d.ldsub, false, s);
-  time_grad(w.dCsub, d.ldsub, d.dm, w.dtk, nullptr, RK, d.dt, p->time_w, p->time_b, g->time_w, g->time_b, s);
-  time_grad(w.dQsub, d.ldsub, d.dm, nullptr, nullptr, R, d.dt, p->time_w, p->time_b, g->time_w, g->time_b, s);
+  time_grad(w.dCsub, d.ldsub, d.dm, w.msinC, d.ldt, w.dtk, RK, d.dt, p->time_b, g->time_w, g->time_b, s);
+  time_grad(w.dQsub, d.ldsub, d.dm, nullptr, 0, nullptr, R, d.dt, p->time_b, g->time_w, g->time_b, s);
 }
 
 static hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
@@ -369,7 +373,7 @@ int32_t tgnn_gru_update(tgnn_ctx* ctx, const tgnn_params* p, int32_t n_slots, co
   REQ_PTR(mem); REQ_PTR(mail); REQ_PTR(mem_ts); REQ_PTR(mail_ts); REQ_PTR(has_mail); REQ_PTR(out_s_new); REQ_PTR(out_tau);
   if (d.de > 0) REQ_PTR(mail_efeat);
   hipStream_t s = as_stream(stream);
-  pack_all(ctx, p, s);
+  prologue(ctx, p, nullptr, nullptr, nullptr, nullptr, s);
   GatherArgs a;
   memset(&a, 0, sizeof(a));
   a.mem = mem; a.mail = mail; a.efeat = mail_efeat; a.mem_ts = mem_ts; a.mail_ts = mail_ts;
@@ -401,7 +405,7 @@ int32_t tgnn_temporal_attn_fwd(tgnn_ctx* ctx, const tgnn_params* p, int32_t n_ro
   REQ_PTR(x_root); REQ_PTR(x_nbr); REQ_PTR(dt_nbr); REQ_PTR(cnt); REQ_PTR(out_z);
   if (d.de > 0) REQ_PTR(e_nbr);
   hipStream_t s = as_stream(stream);
-  pack_all(ctx, p, s);
+  prologue(ctx, p, nullptr, nullptr, nullptr, nullptr, s);
   TGNN_HIP_CHECK(hipMemcpyAsync(w.cnt, cnt, sizeof(int32_t) * n_roots, hipMemcpyDeviceToDevice, s));
   AttnAssembleArgs a;
   memset(&a, 0, sizeof(a));
@@ -409,6 +413,7 @@ int32_t tgnn_temporal_attn_fwd(tgnn_ctx* ctx, const tgnn_params* p, int32_t n_ro
   a.stat = nullptr; a.efeat = e_nbr; a.neid = nullptr; a.cnt = cnt; a.dt_in = dt_nbr;
   a.time_w = p->time_w; a.time_b = p->time_b;
   a.Cmat = w.Cmat; a.Qin = w.Qin; a.Min = w.Min; a.ldc = d.ldc; a.ldq = d.ldq; a.ldm = d.ldm; a.dtk = w.dtk;
+  a.msin = w.msinC; a.p_msin = d.ldt;
   a.R = n_roots; a.k = d.k; a.dm = d.dx; a.ds = 0; a.de = d.de; a.dt = d.dt; a.dO = d.dO; a.dt_source = 0;
   attn_assemble(a, s);
   attn_forward(ctx, p, n_roots, w.cnt, s);
@@ -485,9 +490,11 @@ int32_t tgnn_memory_writeback(tgnn_ctx* ctx, tgnn_state* st, int32_t replica, co
   bs.b[0] = BatchDesc{src, dst, nullptr, eid, t, n_events, replica, 0};
   bs.nb = 1; bs.total = n_events;
   hipStream_t s = as_stream(stream);
-  writeback_mark(d, bs, ctx->w.winkey, s);
-  writeback_scatter(d, bs, st, ctx->w.winkey, nullptr, d.dm, nullptr, s_new_src, s_new_dst, tau_src, tau_dst, out_winner, s);
-  writeback_clear(d, bs, ctx->w.winkey, s);
+  Ws& w = ctx->w;
+  prologue(ctx, nullptr, &bs, nullptr, nullptr, nullptr, s);
+  writeback_mark(d, w.bs_dev, n_events, w.winkey, w.epoch, s);
+  writeback_scatter(d, w.bs_dev, n_events, st, w.winkey, w.epoch, nullptr, d.dm, nullptr, s_new_src, s_new_dst, tau_src,
+                    tau_dst, out_winner, s);
   TGNN_LAUNCH_CHECK();
   return TGNN_OK;
 }
@@ -508,17 +515,23 @@ int32_t tgnn_train_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
   if (!(lr == lr)) return set_error(TGNN_E_INVALID_ARG, "lr is NaN");
   const Dims& d = ctx->d; Ws& w = ctx->w;
   hipStream_t s = as_stream(stream);
-  zero_f32(out_loss, 1, s);
-  if (bs.total == 0) { TGNN_LAUNCH_CHECK(); return TGNN_OK; }
+  if (bs.total == 0) {
+    zero_f32(out_loss, 1, s);
+    TGNN_LAUNCH_CHECK();
+    return TGNN_OK;
+  }
   const int R = 3 * bs.total, RK = R * d.k, S = R + RK, B2 = 2 * bs.total;
 
   StageTimer tm{ctx, s};
+  SgdSet sgd_set, zero_set_;
+  fill_param_set(d, p, grads, 2, sgd_set);  // time_w, time_b stay frozen
+  fill_param_set(d, grads, nullptr, 0, zero_set_);
+  const bool overwrite = (ctx->cfg.flags & TGNN_FLAG_OVERWRITE_GRADS) != 0;
   tm.begin(0);
-  pack_all(ctx, p, s);
+  prologue(ctx, p, &bs, lr != 0.0f ? &sgd_set : nullptr, overwrite ? &zero_set_ : nullptr, out_loss, s);
   tm.end(0);
   tm.begin(1);
-  build_roots(ctx, bs, s);
-  writeback_mark(d, bs, w.winkey, s);
+  build_roots(ctx, bs.total, s);
   tm.end(1);
   tm.begin(2);
   sample_recent(d, g, w.root_node, w.root_t, w.root_gid, R, w.nbr, w.neid, w.nts, w.cnt, w.slot_gid, w.slot_node, s);
@@ -532,6 +545,7 @@ int32_t tgnn_train_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
   a.o_mem = w.Hm; a.p_mem = d.ldh; a.z_mem = d.ldh - d.dm;
   a.o_mail = w.X; a.p_mail = d.ldx;
   a.o_phi = w.X + 2 * d.dm; a.p_phi = d.ldx;
+  a.o_msin = w.msinX; a.p_msin = d.ldt;
   a.o_ef = w.X + 2 * d.dm + d.dt; a.p_ef = d.ldx; a.z_ef = d.ldx - d.d_in;
   a.o_tau = w.tau; a.o_delta = w.delta; a.o_has = w.has;
   a.time_w = p->time_w; a.time_b = p->time_b;
@@ -557,6 +571,7 @@ int32_t tgnn_train_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
   aa.root_t = w.root_t; aa.nts = w.nts; aa.tau_nbr = w.tau + R; aa.dt_in = nullptr;
   aa.time_w = p->time_w; aa.time_b = p->time_b;
   aa.Cmat = w.Cmat; aa.Qin = w.Qin; aa.Min = w.Min; aa.ldc = d.ldc; aa.ldq = d.ldq; aa.ldm = d.ldm; aa.dtk = w.dtk;
+  aa.msin = w.msinC; aa.p_msin = d.ldt;
   aa.R = R; aa.k = d.k; aa.dm = d.dm; aa.ds = d.ds; aa.de = d.de; aa.dt = d.dt; aa.dO = d.dO; aa.dt_source = d.dt_source;
   tm.begin(7);
   attn_assemble(aa, s);
@@ -576,9 +591,9 @@ int32_t tgnn_train_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
 
   // decoder + loss (also produces d loss / d hidden)
   tm.begin(12);
-  decoder_assemble(d, bs, w.z, d.ldh, w.Adec, d.ldkv, s);
+  decoder_assemble(d, w.bs_dev, bs.total, w.z, d.ldh, w.Adec, d.ldkv, s);
   gemm_nt(w.Adec, d.ldkv, w.Wdec_p, d.ldkv, p->dec_b1, w.h1, d.ldh, B2, d.dO, d.ldkv, d.ldh, true, s);
-  decoder_loss(d, bs, w.h1, d.ldh, p->dec_w2, p->dec_b2, w.logits, out_loss, w.dh1, grads->dec_w2, grads->dec_b2, s);
+  decoder_loss(d, w.bs_dev, bs.total, w.h1, d.ldh, p->dec_w2, p->dec_b2, w.logits, out_loss, w.dh1, grads->dec_w2, grads->dec_b2, s);
   tm.end(12);
 
   // backward
@@ -589,7 +604,7 @@ int32_t tgnn_train_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
   dec.n_split = 1 << 30; dec.k_split = d.dO; dec.bias[0] = grads->dec_b1;
   gemm_tn_acc(w.dh1, d.ldh, w.Adec, d.ldkv, B2, d.dO, 2 * d.dO, dec, s);
   gemm_nt(w.dh1, d.ldh, w.WdecT, d.ldh, nullptr, w.dAdec, d.ldkv, B2, 2 * d.dO, d.ldh, d.ldkv, false, s);
-  decoder_dz(d, bs, w.dAdec, d.ldkv, w.z, d.ldh, w.dz, s);
+  decoder_dz(d, w.bs_dev, bs.total, w.dAdec, d.ldkv, w.z, d.ldh, w.dz, s);
   tm.end(13);
   tm.begin(14);
   attn_backward(ctx, grads, p, R, w.cnt, s);
@@ -603,20 +618,18 @@ int32_t tgnn_train_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
   tm.end(16);
   tm.begin(17);
   gemm_nt(w.dgi, d.ld3, w.WihT_phi, d.ld3, nullptr, w.dphi_g, d.ldt, S, d.dt, d.ld3, d.ldt, false, s);
-  time_grad(w.dphi_g, d.ldt, 0, w.delta, nullptr, S, d.dt, p->time_w, p->time_b, grads->time_w, grads->time_b, s);
+  time_grad(w.dphi_g, d.ldt, 0, w.msinX, d.ldt, w.delta, S, d.dt, p->time_b, grads->time_w, grads->time_b, s);
   tm.end(17);
 
   if (lr != 0.0f) {
     tm.begin(18);
-    SgdSet set;
-    fill_param_set(d, p, grads, 2, set);  // time_w, time_b stay frozen
-    sgd_update(set, lr, s);
+    sgd_update(w.sgd_dev, sgd_set.cnt, lr, s);
     tm.end(18);
   }
 
   tm.begin(19);
-  writeback_scatter(d, bs, st, w.winkey, w.s_new, d.ldh, w.tau, nullptr, nullptr, nullptr, nullptr, out_winner, s);
-  writeback_clear(d, bs, w.winkey, s);
+  writeback_scatter(d, w.bs_dev, bs.total, st, w.winkey, w.epoch, w.s_new, d.ldh, w.tau, nullptr, nullptr, nullptr,
+                    nullptr, out_winner, s);
   tm.end(19);
   if (out_logits)
     TGNN_HIP_CHECK(hipMemcpyAsync(out_logits, w.logits, sizeof(float) * B2, hipMemcpyDeviceToDevice, s));

@@ -49,7 +49,11 @@ struct Ws {
   int32_t *slot_gid, *slot_node, *has;         // [S]
   double *tau, *delta;                         // [S]
   double* dtk;                                 // [R*k] time difference in the keys
-  unsigned long long* winkey;                  // [nrep*N] write-back arbitration, 0 when idle
+  unsigned long long* winkey;                  // [nrep*N] write-back arbitration: (epoch << 33) | occurrence key
+  unsigned long long* epoch;                   // [1] bumped once per step, makes stale winkey entries lose
+  BatchSet* bs_dev;                            // device copy of the step's batch descriptors
+  struct SgdSet* sgd_dev;                      // device copy of the parameter/gradient pointer table
+  float *msinX, *msinC;                        // [S,ldt] [RK,ldt]  -sin of the time-encoding arguments
   // GRU
   float *X, *Hm, *gi, *gh, *gates, *s_new;     // [S,ldx] [S,ldh] [S,ld3] [S,ld3] [S,4*ldh] [S,ldh]
   float *dgi, *dgh, *dphi_g;                   // [S,ld3] [S,ld3] [S,ldh(dt)]
@@ -124,7 +128,11 @@ struct PackDesc {
   int rows, cols, zero_to, ldd;  // dst[r*ldd + c] = src[r*srs + c*scs] for c < cols, 0 for cols <= c < zero_to
   int srs, scs;
 };
-void pack_all(tgnn_ctx* ctx, const tgnn_params* p, hipStream_t s);
+// One launch at the start of a call: packs the weights, optionally zeroes the gradient tensors in `zero`,
+// copies the batch descriptors and the SGD pointer table to the device, zeroes *loss, bumps the epoch.
+// bs / sgd / zero / loss may be NULL.
+void prologue(tgnn_ctx* ctx, const tgnn_params* p, const BatchSet* bs, const struct SgdSet* sgd,
+              const struct SgdSet* zero, float* loss, hipStream_t s);
 void fill_state(tgnn_ctx* ctx, tgnn_state* st, int replica, hipStream_t s);
 struct SgdSet {
   float* p[20];
@@ -132,11 +140,12 @@ struct SgdSet {
   int n[20];
   int cnt;
 };
-void sgd_update(const SgdSet& set, float lr, hipStream_t s);
+void sgd_update(const SgdSet* set_dev, int cnt, float lr, hipStream_t s);
 void zero_set(const SgdSet& set, hipStream_t s);
 
 // ---- k_sample.hip -------------------------------------------------------------------
-void build_roots(tgnn_ctx* ctx, const BatchSet& bs, hipStream_t s);
+// Roots of every batch (+ their slot ids) and the write-back arbitration marks of the positive endpoints.
+void build_roots(tgnn_ctx* ctx, int total, hipStream_t s);
 void sample_recent(const Dims& d, const tgnn_graph* g, const int32_t* node, const double* t, const int32_t* gid_base,
                    int n_roots, int32_t* out_nbr, int32_t* out_eid, double* out_ts, int32_t* out_cnt,
                    int32_t* slot_gid, int32_t* slot_node, hipStream_t s);
@@ -152,6 +161,7 @@ struct GatherArgs {
   int gid_add;              // added to every non-negative slot_gid entry (replica offset)
   // destinations (pitches in floats)
   float *o_mem, *o_mail, *o_ef, *o_phi;  // o_phi NULL: no time encoding
+  float* o_msin;  int p_msin;            // -sin of the time-encoding argument (for the backward pass), may be NULL
   int p_mem, p_mail, p_ef, p_phi;
   int z_mem, z_mail, z_ef, z_phi;  // number of zero floats to append after each segment (row padding)
   double *o_mem_ts, *o_mail_ts, *o_tau, *o_delta;
@@ -170,6 +180,7 @@ struct AttnAssembleArgs {
   const double* dt_in;                  // non-NULL: time differences given directly [R*k]
   const float *time_w, *time_b;
   float *Cmat, *Qin, *Min;  int ldc, ldq, ldm;
+  float* msin;  int p_msin;             // -sin of the key time-encoding arguments [R*k, p_msin]
   double* dtk;
   int R, k, dm, ds, de, dt, dO, dt_source;
 };
@@ -182,9 +193,11 @@ void gru_gates_fwd(const Dims& d, int n, const float* gi, const float* gh, const
 void gru_gates_bwd(const Dims& d, int R, int n, const float* dMin, int ldm, const float* dQsub, const float* dCsub,
                    int ldsub, const float* gates, const float* Hm, const int32_t* has, float* dgi, float* dgh,
                    hipStream_t s);
-// time_w/time_b gradients: dPhi [n, ld] (first dt columns at col0), delta [n] (NULL: all zero), valid [n] or NULL
-void time_grad(const float* dphi, int ld, int col0, const double* delta, const int32_t* valid, int n, int dt,
-               const float* time_w, const float* time_b, float* g_w, float* g_b, hipStream_t s);
+// time_w/time_b gradients from dPhi [n, ld] (dt columns starting at col0) and the stored -sin(arg) [n, p_msin]:
+// g_b[c] += sum_n dPhi * msin, g_w[c] += sum_n dPhi * msin * delta[n].  msin == NULL: delta = 0 for every row
+// (the query's Phi(0)), -sin(time_b[c]) is used and only g_b is updated.
+void time_grad(const float* dphi, int ld, int col0, const float* msin, int p_msin, const double* delta, int n, int dt,
+               const float* time_b, float* g_w, float* g_b, hipStream_t s);
 
 // ---- k_attn.hip ---------------------------------------------------------------------
 void attn_core_fwd(const Dims& d, int R, const float* q, int ldq_, const float* KV, int ldkv, const int32_t* cnt,
@@ -193,11 +206,11 @@ void attn_core_bwd(const Dims& d, int R, const float* q, int ldq_, const float* 
                    const float* prob, const float* dMin, int ldm, float* dq, float* dKV, hipStream_t s);
 
 // ---- k_decoder.hip ------------------------------------------------------------------
-void decoder_assemble(const Dims& d, const BatchSet& bs, const float* z, int ldz, float* Adec, int lda,
+void decoder_assemble(const Dims& d, const BatchSet* bs, int total, const float* z, int ldz, float* Adec, int lda,
                       hipStream_t s);
-void decoder_loss(const Dims& d, const BatchSet& bs, const float* h1, int ldh, const float* w2, const float* b2,
+void decoder_loss(const Dims& d, const BatchSet* bs, int total, const float* h1, int ldh, const float* w2, const float* b2,
                   float* logits, float* out_loss, float* dh1, float* g_w2, float* g_b2, hipStream_t s);
-void decoder_dz(const Dims& d, const BatchSet& bs, const float* dAdec, int lda, const float* z, int ldz, float* dz,
+void decoder_dz(const Dims& d, const BatchSet* bs, int total, const float* dAdec, int lda, const float* z, int ldz, float* dz,
                 hipStream_t s);
 // dz_out[r, c] = z[r, c] > 0 ? dz_in[r, c] : 0   (dz_in pitch p_in)
 void mask_dz(int R, int dO, const float* dz_in, int p_in, const float* z, int ldz, float* dz_out, hipStream_t s);
@@ -216,11 +229,16 @@ struct WbArgs {
   const double *tau_src, *tau_dst;
   int dm;
 };
-void writeback_mark(const Dims& d, const BatchSet& bs, unsigned long long* winkey, hipStream_t s);
+void writeback_mark(const Dims& d, const BatchSet* bs, int total, unsigned long long* winkey,
+                    const unsigned long long* epoch, hipStream_t s);
 // Fused layout: s_new/tau indexed by root slot.  Standalone layout: separate src/dst arrays.
-void writeback_scatter(const Dims& d, const BatchSet& bs, const tgnn_state* st, unsigned long long* winkey,
-                       const float* s_new, int p_s, const double* tau, const float* s_src, const float* s_dst,
-                       const double* tau_src, const double* tau_dst, int32_t* out_winner, hipStream_t s);
-void writeback_clear(const Dims& d, const BatchSet& bs, unsigned long long* winkey, hipStream_t s);
+void writeback_scatter(const Dims& d, const BatchSet* bs, int total, const tgnn_state* st,
+                       const unsigned long long* winkey, const unsigned long long* epoch, const float* s_new, int p_s,
+                       const double* tau, const float* s_src, const float* s_dst, const double* tau_src,
+                       const double* tau_dst, int32_t* out_winner, hipStream_t s);
+// key of occurrence (event e = ev_off + i, role) in the step with epoch counter `epoch`
+__host__ __device__ inline unsigned long long wb_key(unsigned long long epoch, int e, int role) {
+  return (epoch << 33) | (1ull + 2ull * (unsigned long long)e + (unsigned long long)role);
+}
 
 }  // namespace tgnn

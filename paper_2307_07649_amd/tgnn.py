@@ -20,6 +20,7 @@ _lib = C.CDLL(_LIB_PATH)
 PARAM_NAMES = ["time_w", "time_b", "gru_wih", "gru_whh", "gru_bih", "gru_bhh", "wq", "bq", "wk", "bk",
                "wv", "bv", "wo", "bo", "dec_ws", "dec_wd", "dec_b1", "dec_w2", "dec_b2"]
 MAX_BATCHES = 16
+FLAG_OVERWRITE_GRADS = 1
 
 
 class tgnn_config(C.Structure):
@@ -178,8 +179,10 @@ class Batch:
 
 
 class Context:
-    def __init__(self, n_nodes, d_mem, d_time, d_edge, d_static, n_heads, k, max_batch, n_replicas=1, dt_source=0):
-        self.cfg = tgnn_config(n_nodes, d_mem, d_time, d_edge, d_static, n_heads, k, max_batch, n_replicas, dt_source, 0)
+    def __init__(self, n_nodes, d_mem, d_time, d_edge, d_static, n_heads, k, max_batch, n_replicas=1, dt_source=0,
+                 flags=0):
+        self.cfg = tgnn_config(n_nodes, d_mem, d_time, d_edge, d_static, n_heads, k, max_batch, n_replicas, dt_source,
+                               flags)
         self.h = _P()
         _check(_lib.tgnn_create(C.byref(self.cfg), C.byref(self.h)))
         self.d_x = d_mem + d_static
