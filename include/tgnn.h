@@ -209,7 +209,7 @@ int32_t tgnn_profile_read(tgnn_ctx* ctx, int32_t stage, int32_t* out_count, doub
 
 /* Debug/parity access to what the last tgnn_train_step left in the workspace.  `what`:
  * 0 nbr [R,k] i32, 1 eid [R,k] i32, 2 nts [R,k] f64, 3 cnt [R] i32, 4 s_new [R(1+k), d_m] f32,
- * 5 tau [R(1+k)] f64, 6 z [R, d_o] f32.  Copies n_bytes (device to device) into dst on `stream`. */
+ * 5 tau [R(1+k)] f64, 6 z [R, d_o] f32, 7 decoder hidden layer [2 sum n, d_o] f32.  Copies n_bytes (device to device) into dst on `stream`. */
 int32_t tgnn_debug_read(tgnn_ctx* ctx, int32_t what, void* dst, int64_t n_bytes, void* stream);
 
 #ifdef __cplusplus

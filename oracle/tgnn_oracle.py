@@ -305,7 +305,7 @@ def forward_backward(state, adj, efeat, static, p, batch, k, n_heads, dt_source=
     z, ac = attention_fwd(p, x_root, x_nbr, e_nbr, dt_nbr, cnt, n_heads)
     loss, logits, dc = decoder_loss(p, z[:B], z[B:2 * B], z[2 * B:])
     out = dict(loss=loss, logits=logits, nbr=nbr, neid=neid, nts=nts, cnt=cnt, s_new=s_new, tau=tau, z=z,
-               dt_nbr=dt_nbr)
+               dt_nbr=dt_nbr, zpre=ac["zpre"], hpre=dc["hpre"])
     if not want_grads:
         return out
 

@@ -682,13 +682,13 @@ int32_t tgnn_debug_read(tgnn_ctx* ctx, int32_t what, void* dst, int64_t n_bytes,
     case 2: src = w.nts; cap = sizeof(double) * d.maxRK; break;
     case 3: src = w.cnt; cap = sizeof(int32_t) * d.maxR; break;
     case 5: src = w.tau; cap = sizeof(double) * d.maxS; break;
-    case 4: case 6: break;
+    case 4: case 6: case 7: break;
     default: return set_error(TGNN_E_INVALID_ARG, "unknown item %d", what);
   }
   hipStream_t s = as_stream(stream);
-  if (what == 4 || what == 6) {  // pitched float rows -> dense [rows, d_m]
-    const float* base = what == 4 ? w.s_new : w.z;
-    const size_t max_rows = what == 4 ? d.maxS : d.maxR;
+  if (what == 4 || what == 6 || what == 7) {  // pitched float rows -> dense [rows, d_m]
+    const float* base = what == 4 ? w.s_new : (what == 6 ? w.z : w.h1);
+    const size_t max_rows = what == 4 ? d.maxS : (what == 6 ? (size_t)d.maxR : 2 * (size_t)d.maxEv);
     const size_t row_b = sizeof(float) * d.dm;
     if (n_bytes < 0 || (size_t)n_bytes % row_b != 0 || (size_t)n_bytes / row_b > max_rows)
       return set_error(TGNN_E_OUT_OF_RANGE, "n_bytes is not a whole number of rows within capacity");

@@ -5,6 +5,7 @@ import numpy as np
 import synth
 from oracle import tgnn_oracle as O
 
+GRAD_TOL_TIE = 2e-3   # gradient bound on a step where a ReLU pre-activation tied at zero flipped (see compare_step)
 TOL = 1e-4   # spec bound: relative error (against the tensor's largest magnitude), fp32 path vs fp64 oracle
 
 
@@ -99,6 +100,7 @@ class GpuSide:
         out["s_new"] = dbg(4, torch.empty(R * (1 + k), self.d.d_mem, device="cuda")).cpu().numpy()
         out["tau"] = dbg(5, torch.empty(R * (1 + k), dtype=torch.float64, device="cuda")).cpu().numpy()
         out["z"] = dbg(6, torch.empty(R, self.d.d_mem, device="cuda")).cpu().numpy()
+        out["h1"] = dbg(7, torch.empty(2 * tot, self.d.d_mem, device="cuda")).cpu().numpy()
         torch.cuda.synchronize()
         return out
 
@@ -127,14 +129,29 @@ def compare_step(g, o_res, tol=TOL, check_grads=True, label=""):
     s_roots = np.concatenate([o["s_new"][:3 * len(o["logits"]) // 2] for o in outs])
     errs["s_new_roots"] = rel_err(g["s_new"][:R], s_roots)
     errs["loss"] = abs(g["loss"] - o_res["loss"]) / max(abs(o_res["loss"]), 1e-30)
+    # ReLU gates: a pre-activation within rounding of zero may be gated differently by the fp32 path and the
+    # fp64 oracle.  The outputs are continuous there (checked above at full tolerance) but the gradient is not,
+    # so a step where such a tie flipped is compared at GRAD_TOL_TIE; any flip away from a tie is an error.
+    zpre = np.concatenate([o["zpre"] for o in outs]); hpre = np.concatenate([o["hpre"] for o in outs])
+    flips = 0
+    for pre, act in ((zpre, g["z"]), (hpre, g["h1"])):
+        diff = (act > 0) != (pre > 0)
+        assert np.all(np.abs(pre[diff]) <= 1e-5 * np.abs(pre).max()), (label, "ReLU gate differs away from zero")
+        flips += int(diff.sum())
+    assert flips <= 4, (label, flips)
+    errs["relu_tie_flips"] = 0.0
     if check_grads:
+        gtol = tol if flips == 0 else GRAD_TOL_TIE
         # The key-bias gradient is identically zero in exact arithmetic (softmax is shift invariant), so a
         # tensor's error is taken relative to max(its own largest entry, 1e-3 of the largest gradient entry).
         gmax = max(float(np.max(np.abs(o_res["grads"][n]))) for n in O.PARAM_NAMES)
         for n in O.PARAM_NAMES:
             errs["g_" + n] = rel_err(g["grads"][n], o_res["grads"][n], floor=1e-3 * gmax)
-    bad = {k_: v for k_, v in errs.items() if not (v <= tol)}
+    else:
+        gtol = tol
+    bad = {k_: v for k_, v in errs.items() if not (v <= (gtol if k_.startswith("g_") else tol))}
     assert not bad, (label, bad, errs)
+    errs["relu_tie_flips"] = float(flips)
     return errs
 
 

@@ -1,0 +1,107 @@
+"""GPU parity of tgnn_train_step at the benchmark configurations' full sizes (C1, C2, C3) and on a C4-shaped
+graph: sampled neighbours and winners bit-exact on every checked step, logits / gradients / memory within
+1e-4 after consecutive batches."""
+import numpy as np
+import pytest
+
+from gpu_common import GpuSide, OracleSide, batch_np, compare_state, compare_step, make_problem, rel_err
+import synth
+
+pytestmark = pytest.mark.gpu
+
+
+def run(P, n_steps, lr, check_at, first=0):
+    d = P["d"]
+    G = GpuSide(P); Or = OracleSide(P)
+    out = {}
+    for s in range(n_steps):
+        lo = (first + s) * d.batch; hi = min(lo + d.batch, P["E"])
+        b = batch_np(P, lo, hi)
+        want = s in check_at
+        g = G.step([b], lr=lr, want=want)
+        o = Or.step([b], lr=lr)
+        if want:
+            out[s] = compare_step(g, o, label=f"{P['name']} step {s}")
+    compare_state(G.state_np(), Or.states[0], label=P["name"])
+    assert sum(1 for e in out.values() if e["relu_tie_flips"] == 0) >= max(1, len(out) - 1), out
+    return out
+
+
+def test_c1_full_size_50_batches_sgd():
+    P = make_problem("C1")
+    errs = run(P, 50, lr=1e-3, check_at=(0, 1, 25, 49))
+    print({k: max(v.values()) for k, v in errs.items()})
+
+
+def test_c1_last_ragged_batch():
+    P = make_problem("C1")
+    M = len(synth.batches_of(P["E"], P["d"].batch))
+    run(P, 3, lr=0.0, check_at=(0, 2), first=M - 3)          # the epoch's last mini-batch has 274 events
+
+
+def test_c2_static_memory_20_batches():
+    P = make_problem("C2", n_events=60_000)
+    run(P, 20, lr=0.0, check_at=(0, 19))
+
+
+def test_c3_eight_replicas_time_shifted():
+    P = make_problem("C3", n_events=48_000)
+    d = P["d"]
+    nrep = 8
+    G = GpuSide(P, n_replicas=nrep); Or = OracleSide(P, n_replicas=nrep)
+    spans = synth.batches_of(P["E"], d.batch)
+    M = len(spans); shift = -(-M // nrep)
+    for s in range(6):
+        bl = [batch_np(P, *spans[(s + r * shift) % M]) for r in range(nrep)]
+        g = G.step(bl, lr=1e-3)
+        o = Or.step(bl, lr=1e-3)
+        compare_step(g, o, label=f"C3 step {s}")
+    for r in range(nrep):
+        compare_state(G.state_np(r), Or.states[r], label=f"C3 replica {r}")
+    for n, v in G.params.numpy().items():
+        assert rel_err(v, Or.p[n]) <= 1e-4, n
+
+
+def test_c3_replica_subset_and_order():
+    P = make_problem("C3", n_events=12_000)
+    d = P["d"]
+    G = GpuSide(P, n_replicas=8); Or = OracleSide(P, n_replicas=8)
+    spans = synth.batches_of(P["E"], d.batch)
+    for s in range(3):
+        reps = [5, 0, 7]                                     # any subset, any order; others stay untouched
+        bl = [batch_np(P, *spans[s + 3 * i]) for i in range(3)]
+        g = G.step(bl, replicas=reps)
+        o = Or.step(bl, replicas=reps)
+        compare_step(g, o, label=f"subset step {s}")
+    for r in range(8):
+        compare_state(G.state_np(r), Or.states[r], label=f"replica {r}")
+    assert not G.state_np(3)["mem"].any()
+
+
+def test_c4_shape_three_batches():
+    P = make_problem("C4", n_events=400_000)
+    run(P, 3, lr=0.0, check_at=(0, 2), first=90)             # start late: neighbour lists are long, memory empty
+    run(P, 4, lr=0.0, check_at=(1, 3))
+
+
+@pytest.mark.slow
+def test_c4_full_graph_sampler():
+    """Sampler on the full 20,000,000-event graph (node degrees up to millions) against the oracle."""
+    import torch
+    from paper_2307_07649_amd import tgnn
+    from oracle import tgnn_oracle as O
+    g = synth.gen_graph("C4", with_efeat=False)
+    n = synth.CONFIGS["C4"]["n_nodes"]
+    ctx = tgnn.Context(n, 8, 4, 0, 0, 1, 10, 40_000)
+    graph = tgnn.Graph(g["src"], g["dst"], g["ts"], n, None)
+    rng = np.random.default_rng(0)
+    Q = 100_000
+    ev = rng.integers(0, len(g["src"]), Q)
+    qn = np.where(rng.random(Q) < 0.5, g["src"][ev], g["dst"][ev]).astype(np.int32)
+    qt = g["ts"][ev].copy()
+    qt[::7] = rng.uniform(0, 1.4e5, len(qt[::7]))
+    nbr, eid, ts, cnt = ctx.tgnn_sample_recent(graph, torch.from_numpy(qn).cuda(), torch.from_numpy(qt).cuda())
+    adj = O.build_adjacency(g["src"], g["dst"], g["ts"], n)
+    o = O.sample_recent(adj, qn, qt, 10)
+    assert np.array_equal(cnt.cpu().numpy(), o[3]) and np.array_equal(eid.cpu().numpy(), o[1])
+    assert np.array_equal(nbr.cpu().numpy(), o[0]) and np.array_equal(ts.cpu().numpy(), o[2])
