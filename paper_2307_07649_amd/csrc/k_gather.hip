@@ -10,7 +10,8 @@ template <int VEC>
 __global__ __launch_bounds__(256) void gather_kernel(GatherArgs a) {
   const int lane = threadIdx.x & 63;
   const int wpb = blockDim.x >> 6;
-  for (int s = blockIdx.x * wpb + (threadIdx.x >> 6); s < a.n_slots; s += gridDim.x * wpb) {
+  const int n_slots = a.n_dev ? min(a.n_slots, *a.n_dev) : a.n_slots;
+  for (int s = blockIdx.x * wpb + (threadIdx.x >> 6); s < n_slots; s += gridDim.x * wpb) {
     int gid = a.slot_gid ? a.slot_gid[s] : s;
     if (gid >= 0) gid += a.gid_add;
     float* o_mem = a.o_mem + (size_t)s * a.p_mem;
@@ -92,11 +93,12 @@ __global__ __launch_bounds__(256) void attn_assemble_kernel(AttnAssembleArgs a) 
         if (lane == 0) a.dtk[row] = 0.0;
         continue;
       }
-      wave_copy<VEC>(out, a.s_nbr + (size_t)row * a.p_s, a.dm, 0, lane);
+      const int srow = a.slot_row ? a.slot_row[a.R + row] : row;
+      wave_copy<VEC>(out, a.s_nbr + (size_t)srow * a.p_s, a.dm, 0, lane);
       if (a.ds) wave_copy<VEC>(out + a.dm, a.stat + (size_t)a.nbr[row] * a.ds, a.ds, 0, lane);
       if (a.de) wave_copy<VEC>(out + dx, a.efeat + (size_t)(a.neid ? a.neid[row] : row) * a.de, a.de, 0, lane);
       const double delta = a.dt_in ? a.dt_in[row]
-                                   : a.root_t[r] - (a.dt_source == 0 ? a.tau_nbr[row] : a.nts[row]);
+                                   : a.root_t[r] - (a.dt_source == 0 ? a.tau_nbr[srow] : a.nts[row]);
       float* phi = out + dx + a.de;
       float* ms = a.msin + (size_t)row * a.p_msin;
       for (int c = lane; c < a.dt; c += 64) {
@@ -112,7 +114,7 @@ __global__ __launch_bounds__(256) void attn_assemble_kernel(AttnAssembleArgs a) 
       const int v = a.ds ? a.root_node[r] : 0;
       float* qi = a.Qin + (size_t)r * a.ldq;
       float* mi = a.Min + (size_t)r * a.ldm + a.dO;
-      const float* sv = a.s_root + (size_t)r * a.p_s;
+      const float* sv = a.s_root + (size_t)(a.slot_row ? a.slot_row[r] : r) * a.p_s;
       wave_copy<VEC>(qi, sv, a.dm, 0, lane);
       wave_copy<VEC>(mi, sv, a.dm, 0, lane);
       if (a.ds) {

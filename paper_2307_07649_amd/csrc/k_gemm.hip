@@ -31,8 +31,13 @@ template <int TN>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 2))) void gemm_nt_kernel(const float* __restrict__ A, int lda,
                                                       const float* __restrict__ B, int ldb,
                                                       const float* __restrict__ bias, float* __restrict__ C, int ldc,
-                                                      int M, int N, int Kp, int n_store, int relu) {
+                                                      int M, int N, int Kp, int n_store, int relu,
+                                                      const int* __restrict__ m_dev) {
   constexpr int BM = 64, BN = 16 * TN;
+  if (m_dev != nullptr) {
+    M = min(M, *m_dev);
+    if ((int)blockIdx.y * BM >= M) return;   // uniform for the workgroup, before any barrier
+  }
   constexpr int A_PER = BM * 8 / 256, B_F4 = BN * 8;  // float4 loads per stage and thread
   constexpr int B_PER = (B_F4 + 255) / 256;
   __shared__ __attribute__((aligned(16))) float As[2][BM * NT_P];
@@ -156,15 +161,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 2))) voi
 
 template <int TN>
 static void launch_nt(const float* A, int lda, const float* B, int ldb, const float* bias, float* C, int ldc, int M,
-                      int N, int Kp, int n_store, bool relu, hipStream_t s) {
+                      int N, int Kp, int n_store, bool relu, hipStream_t s, const int* m_dev) {
   constexpr int BM = 64, BN = 16 * TN;
   dim3 grid((n_store + BN - 1) / BN, (M + BM - 1) / BM);
   hipLaunchKernelGGL((gemm_nt_kernel<TN>), grid, dim3(256), 0, s, A, lda, B, ldb, bias, C, ldc, M, N, Kp, n_store,
-                     relu ? 1 : 0);
+                     relu ? 1 : 0, m_dev);
 }
 
 void gemm_nt(const float* A, int lda, const float* B, int ldb, const float* bias, float* C, int ldc, int M, int N,
-             int Kp, int n_store, bool relu, hipStream_t s) {
+             int Kp, int n_store, bool relu, hipStream_t s, const int* m_dev) {
   if (M <= 0 || N <= 0) return;
   if (n_store < N) n_store = N;
   // Column-tile width in 16-wide MFMA blocks.  Measured on MI355X the throughput is flat between 2 and 10
@@ -185,7 +190,7 @@ void gemm_nt(const float* A, int lda, const float* B, int ldb, const float* bias
   }
   if (const char* e = getenv("TGNN_NT_TN")) best = atoi(e);
 #define TGNN_NT_CASE(TNV) \
-  case TNV: launch_nt<TNV>(A, lda, B, ldb, bias, C, ldc, M, N, Kp, n_store, relu, s); break;
+  case TNV: launch_nt<TNV>(A, lda, B, ldb, bias, C, ldc, M, N, Kp, n_store, relu, s, m_dev); break;
   switch (best) {
     TGNN_NT_CASE(10)
     TGNN_NT_CASE(7)
@@ -208,7 +213,13 @@ constexpr int TN_ROWS = 32;
 
 __global__ __launch_bounds__(256) void gemm_tn_kernel(const float* __restrict__ D, int ldd,
                                                       const float* __restrict__ A, int lda, int M, int N, int K,
-                                                      int m_chunk, int k_tiles, OutMap out) {
+                                                      int m_chunk, int k_tiles, OutMap out,
+                                                      const int* __restrict__ m_dev) {
+  if (m_dev != nullptr) {  // row count known only on the device: split it evenly over the launched chunks
+    M = min(M, *m_dev);
+    m_chunk = ((M + (int)gridDim.y - 1) / (int)gridDim.y + TN_ROWS - 1) / TN_ROWS * TN_ROWS;
+    if ((int)blockIdx.y * m_chunk >= M) return;
+  }
   __shared__ __attribute__((aligned(16))) float Ds[2][TN_ROWS * TN_P];
   __shared__ __attribute__((aligned(16))) float Asm[2][TN_ROWS * TN_P];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -330,7 +341,7 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(const float* __restrict__ 
 }
 
 void gemm_tn_acc(const float* D, int ldd, const float* A, int lda, int M, int N, int K, const OutMap& out,
-                 hipStream_t s) {
+                 hipStream_t s, const int* m_dev) {
   if (M <= 0 || N <= 0 || K <= 0) return;
   const int n_tiles = (N + TT - 1) / TT, k_tiles = (K + TT - 1) / TT;
   const int tiles = n_tiles * k_tiles;
@@ -341,8 +352,9 @@ void gemm_tn_acc(const float* D, int ldd, const float* A, int lda, int M, int N,
   if (chunks < 1) chunks = 1;
   int m_chunk = ((M + chunks - 1) / chunks + TN_ROWS - 1) / TN_ROWS * TN_ROWS;
   chunks = (M + m_chunk - 1) / m_chunk;
+  if (m_dev != nullptr && chunks > 16) chunks = 16;   // the device-side row count is usually far below M
   hipLaunchKernelGGL(gemm_tn_kernel, dim3(tiles, chunks), dim3(256), 0, s, D, ldd, A, lda, M, N, K, m_chunk, k_tiles,
-                     out);
+                     out, m_dev);
 }
 
 }  // namespace tgnn

@@ -13,10 +13,11 @@ __device__ __forceinline__ float tanhf_(float x) {
 }
 
 // gates layout per row: [r | z | n | W_hn h + b_hn], each block ldh floats wide
-__global__ void gru_fwd_kernel(int n, int dm, int ldh, int ld3, const float* __restrict__ gi,
-                               const float* __restrict__ gh, const float* __restrict__ Hm,
-                               const int32_t* __restrict__ has, float* __restrict__ gates,
-                               float* __restrict__ s_new) {
+__global__ void gru_fwd_kernel(int n_max, const int* __restrict__ n_dev, int dm, int ldh, int ld3,
+                               const float* __restrict__ gi, const float* __restrict__ gh,
+                               const float* __restrict__ Hm, const int32_t* __restrict__ has,
+                               float* __restrict__ gates, float* __restrict__ s_new, float* __restrict__ ds_zero) {
+  const int n = n_dev ? min(n_max, *n_dev) : n_max;
   const long long total = (long long)n * dm;
   for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < total;
        i += (long long)gridDim.x * blockDim.x) {
@@ -38,33 +39,33 @@ __global__ void gru_fwd_kernel(int n, int dm, int ldh, int ld3, const float* __r
       g[3 * ldh + c] = hn;
     }
     s_new[(size_t)row * ldh + c] = out;
+    if (ds_zero) ds_zero[(size_t)row * ldh + c] = 0.f;
   }
 }
 
-void gru_gates_fwd(const Dims& d, int n, const float* gi, const float* gh, const float* Hm, const int32_t* has,
-                   float* gates, float* s_new, hipStream_t s) {
+void gru_gates_fwd(const Dims& d, int n, const int* n_dev, const float* gi, const float* gh, const float* Hm,
+                   const int32_t* has, float* gates, float* s_new, float* ds_zero, hipStream_t s) {
   if (n <= 0) return;
   const long long total = (long long)n * d.dm;
   const int blocks = (int)((total + 255) / 256);
-  hipLaunchKernelGGL(gru_fwd_kernel, dim3(blocks), dim3(256), 0, s, n, d.dm, d.ldh, d.ld3, gi, gh, Hm, has, gates,
-                     s_new);
+  hipLaunchKernelGGL(gru_fwd_kernel, dim3(blocks), dim3(256), 0, s, n, n_dev, d.dm, d.ldh, d.ld3, gi, gh, Hm, has, gates,
+                     s_new, ds_zero);
 }
 
-// The gradient reaching s' of slot `row` comes from the merge layer and the query (roots) or from the
-// key/value input (neighbour slots).  It stops here: stored memory and mails are constants (Sec. 2.1, no BPTT).
-__global__ void gru_bwd_kernel(int R, int n, int dm, int dO, int ldh, int ld3, const float* __restrict__ dMin,
-                               int ldm, const float* __restrict__ dQsub, const float* __restrict__ dCsub, int ldsub,
-                               const float* __restrict__ gates, const float* __restrict__ Hm,
-                               const int32_t* __restrict__ has, float* __restrict__ dgi, float* __restrict__ dgh) {
+// From the gradient reaching s' of a row to the gradients of the gate pre-activations.  The chain stops at
+// the stored memory and mails, which are constants of the step (Sec. 2.1: no back-propagation through time).
+__global__ void gru_bwd_kernel(int n_max, const int* __restrict__ n_dev, int dm, int ldh, int ld3,
+                               const float* __restrict__ ds_row, const float* __restrict__ gates,
+                               const float* __restrict__ Hm, const int32_t* __restrict__ has,
+                               float* __restrict__ dgi, float* __restrict__ dgh) {
+  const int n = n_dev ? min(n_max, *n_dev) : n_max;
   const long long total = (long long)n * dm;
   for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < total;
        i += (long long)gridDim.x * blockDim.x) {
     const int row = (int)(i / dm), c = (int)(i - (long long)row * dm);
     float drp = 0.f, dzp = 0.f, dnp = 0.f, dnr = 0.f;
     if (has[row]) {
-      float ds;
-      if (row < R) ds = dMin[(size_t)row * ldm + dO + c] + dQsub[(size_t)row * ldsub + c];
-      else ds = dCsub[(size_t)(row - R) * ldsub + c];
+      const float ds = ds_row[(size_t)row * ldh + c];
       const float* g = gates + (size_t)row * 4 * ldh;
       const float r = g[c], z = g[ldh + c], nn = g[2 * ldh + c], hn = g[3 * ldh + c];
       const float h = Hm[(size_t)row * ldh + c];
@@ -83,14 +84,13 @@ __global__ void gru_bwd_kernel(int R, int n, int dm, int dO, int ldh, int ld3, c
   }
 }
 
-void gru_gates_bwd(const Dims& d, int R, int n, const float* dMin, int ldm, const float* dQsub, const float* dCsub,
-                   int ldsub, const float* gates, const float* Hm, const int32_t* has, float* dgi, float* dgh,
-                   hipStream_t s) {
+void gru_gates_bwd(const Dims& d, int n, const int* n_dev, const float* ds, const float* gates, const float* Hm,
+                   const int32_t* has, float* dgi, float* dgh, hipStream_t s) {
   if (n <= 0) return;
   const long long total = (long long)n * d.dm;
   const int blocks = (int)((total + 255) / 256);
-  hipLaunchKernelGGL(gru_bwd_kernel, dim3(blocks), dim3(256), 0, s, R, n, d.dm, d.dO, d.ldh, d.ld3, dMin, ldm, dQsub,
-                     dCsub, ldsub, gates, Hm, has, dgi, dgh);
+  hipLaunchKernelGGL(gru_bwd_kernel, dim3(blocks), dim3(256), 0, s, n, n_dev, d.dm, d.ldh, d.ld3, ds, gates, Hm, has, dgi,
+                     dgh);
 }
 
 // g_b[c] += sum_n dphi[n, col0 + c] * msin[n, c] ;  g_w[c] += sum_n dphi * msin * delta_n.
@@ -99,10 +99,13 @@ void gru_gates_bwd(const Dims& d, int R, int n, const float* dMin, int ldm, cons
 constexpr int TG_MAX_BLOCKS = 128;
 __global__ __launch_bounds__(256) void time_grad_kernel(const float* __restrict__ dphi, int ld, int col0,
                                                         const float* __restrict__ msin, int p_msin,
-                                                        const double* __restrict__ delta, int n, int rows_per_block,
-                                                        int dt, const float* __restrict__ time_b,
-                                                        float* __restrict__ g_w, float* __restrict__ g_b) {
+                                                        const double* __restrict__ delta, int n_max,
+                                                        const int* __restrict__ n_dev, int rows_per_block, int dt,
+                                                        const float* __restrict__ time_b, float* __restrict__ g_w,
+                                                        float* __restrict__ g_b) {
   __shared__ float sw[4][64], sb[4][64];
+  const int n = n_dev ? min(n_max, *n_dev) : n_max;
+  if ((int)blockIdx.x * rows_per_block >= n) return;
   const int cx = threadIdx.x & 63, cy = threadIdx.x >> 6;
   const int r0 = blockIdx.x * rows_per_block;
   const int r1 = min(n, r0 + rows_per_block);
@@ -134,12 +137,12 @@ __global__ __launch_bounds__(256) void time_grad_kernel(const float* __restrict_
 }
 
 void time_grad(const float* dphi, int ld, int col0, const float* msin, int p_msin, const double* delta, int n, int dt,
-               const float* time_b, float* g_w, float* g_b, hipStream_t s) {
+               const float* time_b, float* g_w, float* g_b, hipStream_t s, const int* n_dev) {
   if (n <= 0) return;
   int rpb = (n + TG_MAX_BLOCKS - 1) / TG_MAX_BLOCKS;
   rpb = (rpb + 3) & ~3;
   hipLaunchKernelGGL(time_grad_kernel, dim3((n + rpb - 1) / rpb), dim3(256), 0, s, dphi, ld, col0, msin, p_msin, delta,
-                     n, rpb, dt, time_b, g_w, g_b);
+                     n, n_dev, rpb, dt, time_b, g_w, g_b);
 }
 
 }  // namespace tgnn

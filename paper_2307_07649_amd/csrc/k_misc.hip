@@ -16,6 +16,7 @@ struct PrologueArgs {
   SgdSet* sgd_dev;
   float* loss;
   unsigned long long* epoch;
+  int32_t* ucount;
 };
 
 __global__ void prologue_kernel(PrologueArgs a) {
@@ -45,6 +46,7 @@ __global__ void prologue_kernel(PrologueArgs a) {
     if (threadIdx.x == 0) {
       if (a.loss) *a.loss = 0.f;
       *a.epoch += 1ull;
+      *a.ucount = 0;
     }
   }
 }
@@ -95,6 +97,7 @@ void prologue(tgnn_ctx* ctx, const tgnn_params* p, const BatchSet* bs, const Sgd
   if (sgd) { pa.sgd = *sgd; pa.sgd_dev = w.sgd_dev; }
   pa.loss = loss;
   pa.epoch = w.epoch;
+  pa.ucount = w.ucount;
   hipLaunchKernelGGL(prologue_kernel, dim3(32, n + pa.zero.cnt + 1), dim3(256), 0, s, pa);
 }
 

@@ -7,7 +7,8 @@ namespace tgnn {
 
 __global__ void roots_kernel(const BatchSet* __restrict__ bsp, int N, int32_t* root_node, int32_t* root_gid,
                              int32_t* root_batch, double* root_t, int32_t* slot_gid, int32_t* slot_node,
-                             unsigned long long* winkey, const unsigned long long* __restrict__ epoch) {
+                             unsigned long long* winkey, const unsigned long long* __restrict__ epoch,
+                             unsigned long long* utag, int32_t* uidx, int32_t* ucount, int32_t* ulist, int32_t* ucnt) {
   const BatchSet& bs = *bsp;
   const int e = blockIdx.x * blockDim.x + threadIdx.x;
   if (e >= bs.total) return;
@@ -29,13 +30,15 @@ __global__ void roots_kernel(const BatchSet* __restrict__ bsp, int N, int32_t* r
     slot_gid[r] = gid;
     slot_node[r] = nodes[role];
     if (role < 2) atomicMax(winkey + gid, wb_key(ep, e, role));   // last-event-wins arbitration
+    uniq_claim(utag, uidx, ucount, ulist, ucnt, gid, ep);
   }
 }
 
 void build_roots(tgnn_ctx* ctx, int total, hipStream_t s) {
   Ws& w = ctx->w;
   hipLaunchKernelGGL(roots_kernel, dim3((total + 255) / 256), dim3(256), 0, s, w.bs_dev, ctx->d.N, w.root_node,
-                     w.root_gid, w.root_batch, w.root_t, w.slot_gid, w.slot_node, w.winkey, w.epoch);
+                     w.root_gid, w.root_batch, w.root_t, w.slot_gid, w.slot_node, w.winkey, w.epoch, w.utag, w.uidx,
+                     w.ucount, w.ulist, w.ucnt);
 }
 
 // gid = replica * N + node for roots of the fused step (root_gid given), plain node ids otherwise.
@@ -48,7 +51,8 @@ __global__ __launch_bounds__(256) void sample_kernel(const int64_t* __restrict__
                                                      const int32_t* __restrict__ root_gid, int n_roots, int k,
                                                      int32_t* __restrict__ out_nbr, int32_t* __restrict__ out_eid,
                                                      double* __restrict__ out_ts, int32_t* __restrict__ out_cnt,
-                                                     int32_t* __restrict__ slot_gid, int32_t* __restrict__ slot_node) {
+                                                     int32_t* __restrict__ slot_gid, int32_t* __restrict__ slot_node,
+                                                     UniqPtrs uq) {
   const int lane = threadIdx.x & 63;
   const int r = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
   if (r >= n_roots) return;  // whole wave leaves together
@@ -97,16 +101,20 @@ __global__ __launch_bounds__(256) void sample_kernel(const int64_t* __restrict__
       const int rep_base = root_gid[r] - node;
       slot_gid[(size_t)n_roots + o] = nb >= 0 ? rep_base + nb : -1;
       slot_node[(size_t)n_roots + o] = nb;
+      if (nb >= 0 && uq.utag != nullptr)
+        uniq_claim(uq.utag, uq.uidx, uq.ucount, uq.ulist, uq.ucnt, rep_base + nb, *uq.epoch);
     }
   }
 }
 
 void sample_recent(const Dims& d, const tgnn_graph* g, const int32_t* node, const double* t, const int32_t* root_gid,
                    int n_roots, int32_t* out_nbr, int32_t* out_eid, double* out_ts, int32_t* out_cnt,
-                   int32_t* slot_gid, int32_t* slot_node, hipStream_t s) {
+                   int32_t* slot_gid, int32_t* slot_node, const UniqPtrs* uq, hipStream_t s) {
   if (n_roots <= 0) return;
+  UniqPtrs u{};
+  if (uq) u = *uq;
   hipLaunchKernelGGL(sample_kernel, dim3((n_roots + 3) / 4), dim3(256), 0, s, g->indptr, g->nbr, g->eid, g->ts, d.N,
-                     node, t, root_gid, n_roots, d.k, out_nbr, out_eid, out_ts, out_cnt, slot_gid, slot_node);
+                     node, t, root_gid, n_roots, d.k, out_nbr, out_eid, out_ts, out_cnt, slot_gid, slot_node, u);
 }
 
 }  // namespace tgnn

@@ -40,6 +40,7 @@ struct WbPtrs {
   int32_t* mail_eid;
   const float *s_new, *s_src, *s_dst;
   const double *tau, *tau_src, *tau_dst;
+  const int32_t* slot_row;
   int p_s;
 };
 
@@ -62,7 +63,8 @@ __global__ __launch_bounds__(256) void wb_scatter_kernel(const BatchSet* __restr
   const float *self_row, *other_row;
   double tau;
   if (w.s_new) {  // fused layout: rows indexed by root slot [src | dst | neg] of the batch
-    const size_t rs = (size_t)(3 * bd.ev_off + i), rd = (size_t)(3 * bd.ev_off + bd.n + i);
+    size_t rs = (size_t)(3 * bd.ev_off + i), rd = (size_t)(3 * bd.ev_off + bd.n + i);
+    if (w.slot_row) { rs = (size_t)w.slot_row[rs]; rd = (size_t)w.slot_row[rd]; }
     self_row = w.s_new + (role ? rd : rs) * w.p_s;
     other_row = w.s_new + (role ? rs : rd) * w.p_s;
     tau = w.tau[role ? rd : rs];
@@ -83,10 +85,11 @@ __global__ __launch_bounds__(256) void wb_scatter_kernel(const BatchSet* __restr
 
 void writeback_scatter(const Dims& d, const BatchSet* bs, int total, const tgnn_state* st,
                        const unsigned long long* winkey, const unsigned long long* epoch, const float* s_new, int p_s,
-                       const double* tau, const float* s_src, const float* s_dst, const double* tau_src,
-                       const double* tau_dst, int32_t* out_winner, hipStream_t s) {
+                       const double* tau, const int32_t* slot_row, const float* s_src, const float* s_dst,
+                       const double* tau_src, const double* tau_dst, int32_t* out_winner, hipStream_t s) {
   if (total <= 0) return;
-  WbPtrs w{st->mem, st->mail, st->mem_ts, st->mail_ts, st->mail_eid, s_new, s_src, s_dst, tau, tau_src, tau_dst, p_s};
+  WbPtrs w{st->mem, st->mail, st->mem_ts, st->mail_ts, st->mail_eid, s_new, s_src, s_dst, tau, tau_src, tau_dst,
+           slot_row, p_s};
   const int blocks = (2 * total + 3) / 4;
   if (d.dm % 4 == 0 && p_s % 4 == 0)
     hipLaunchKernelGGL(wb_scatter_kernel<4>, dim3(blocks), dim3(256), 0, s, bs, d.N, d.dm, w, winkey, epoch, out_winner);

@@ -90,6 +90,11 @@ static void layout(const Dims& d, Ws& w, Bump& b) {
   w.tau = b.take<double>(S); w.delta = b.take<double>(S); w.dtk = b.take<double>(RK);
   w.winkey = b.take<unsigned long long>((size_t)d.nrep * d.N);
   w.epoch = b.take<unsigned long long>(1);
+  const size_t NG = (size_t)d.nrep * d.N, U = d.maxU;
+  w.utag = b.take<unsigned long long>(NG); w.uidx = b.take<int32_t>(NG); w.ucount = b.take<int32_t>(1);
+  w.ulist = b.take<int32_t>(U); w.slot_row = b.take<int32_t>(S); w.ucnt = b.take<int32_t>(U);
+  w.rowptr = b.take<int32_t>(U + 1); w.cursor = b.take<int32_t>(U); w.sorted = b.take<int32_t>(S);
+  w.ds_row = b.take<float>(U * d.ldh);
   w.bs_dev = b.take<BatchSet>(1);
   w.sgd_dev = b.take<SgdSet>(1);
   w.msinX = b.take<float>(S * d.ldt); w.msinC = b.take<float>(RK * d.ldt);
@@ -129,7 +134,7 @@ static void gru_forward(tgnn_ctx* ctx, const tgnn_params* p, int n, hipStream_t 
   const Dims& d = ctx->d; Ws& w = ctx->w;
   gemm_nt(w.X, d.ldx, w.Wih_p, d.ldx, p->gru_bih, w.gi, d.ld3, n, 3 * d.dm, d.ldx, d.ld3, false, s);
   gemm_nt(w.Hm, d.ldh, w.Whh_p, d.ldh, p->gru_bhh, w.gh, d.ld3, n, 3 * d.dm, d.ldh, d.ld3, false, s);
-  gru_gates_fwd(d, n, w.gi, w.gh, w.Hm, w.has, w.gates, w.s_new, s);
+  gru_gates_fwd(d, n, nullptr, w.gi, w.gh, w.Hm, w.has, w.gates, w.s_new, nullptr, s);
 }
 
 // Projections, per-root softmax attention and the merge layer from ws.Cmat / ws.Qin / ws.Min[:, dO:].
@@ -245,6 +250,10 @@ int32_t tgnn_create(const tgnn_config* cfg, tgnn_ctx** out) {
     return set_error(TGNN_E_OUT_OF_RANGE, "max_batch * n_replicas * 3 * (1 + k) exceeds the slot index range");
   }
   d.maxEv = (int)maxEv; d.maxR = 3 * d.maxEv; d.maxRK = d.maxR * d.k; d.maxS = d.maxR + d.maxRK;
+  {  // distinct (replica, node) rows a step can touch
+    const long long ng = (long long)d.nrep * d.N;
+    d.maxU = (int)(ng < d.maxS ? ng : d.maxS);
+  }
 
   Bump measure{nullptr};
   layout(d, ctx->w, measure);
@@ -328,7 +337,7 @@ int32_t tgnn_sample_recent(tgnn_ctx* ctx, const tgnn_graph* g, const int32_t* no
   if (n_roots < 0) return set_error(TGNN_E_INVALID_ARG, "n_roots < 0");
   if (n_roots == 0) return TGNN_OK;
   REQ_PTR(node); REQ_PTR(t); REQ_PTR(out_nbr); REQ_PTR(out_eid); REQ_PTR(out_ts); REQ_PTR(out_cnt);
-  sample_recent(ctx->d, g, node, t, nullptr, n_roots, out_nbr, out_eid, out_ts, out_cnt, nullptr, nullptr,
+  sample_recent(ctx->d, g, node, t, nullptr, n_roots, out_nbr, out_eid, out_ts, out_cnt, nullptr, nullptr, nullptr,
                 as_stream(stream));
   TGNN_LAUNCH_CHECK();
   return TGNN_OK;
@@ -367,8 +376,8 @@ int32_t tgnn_gru_update(tgnn_ctx* ctx, const tgnn_params* p, int32_t n_slots, co
   if (ctx == nullptr) return set_error(TGNN_E_NULL_PTR, "ctx is NULL");
   if (int rc = check_params(p, "params")) return rc;
   const Dims& d = ctx->d; Ws& w = ctx->w;
-  if (n_slots < 0 || n_slots > d.maxS)
-    return set_error(TGNN_E_WORKSPACE, "n_slots = %d outside [0, %d] (workspace slot capacity)", n_slots, d.maxS);
+  if (n_slots < 0 || n_slots > d.maxU)
+    return set_error(TGNN_E_WORKSPACE, "n_slots = %d outside [0, %d] (workspace row capacity)", n_slots, d.maxU);
   if (n_slots == 0) return TGNN_OK;
   REQ_PTR(mem); REQ_PTR(mail); REQ_PTR(mem_ts); REQ_PTR(mail_ts); REQ_PTR(has_mail); REQ_PTR(out_s_new); REQ_PTR(out_tau);
   if (d.de > 0) REQ_PTR(mail_efeat);
@@ -493,8 +502,8 @@ int32_t tgnn_memory_writeback(tgnn_ctx* ctx, tgnn_state* st, int32_t replica, co
   Ws& w = ctx->w;
   prologue(ctx, nullptr, &bs, nullptr, nullptr, nullptr, s);
   writeback_mark(d, w.bs_dev, n_events, w.winkey, w.epoch, s);
-  writeback_scatter(d, w.bs_dev, n_events, st, w.winkey, w.epoch, nullptr, d.dm, nullptr, s_new_src, s_new_dst, tau_src,
-                    tau_dst, out_winner, s);
+  writeback_scatter(d, w.bs_dev, n_events, st, w.winkey, w.epoch, nullptr, d.dm, nullptr, nullptr, s_new_src, s_new_dst,
+                    tau_src, tau_dst, out_winner, s);
   TGNN_LAUNCH_CHECK();
   return TGNN_OK;
 }
@@ -534,14 +543,17 @@ int32_t tgnn_train_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
   build_roots(ctx, bs.total, s);
   tm.end(1);
   tm.begin(2);
-  sample_recent(d, g, w.root_node, w.root_t, w.root_gid, R, w.nbr, w.neid, w.nts, w.cnt, w.slot_gid, w.slot_node, s);
+  UniqPtrs uq{w.utag, w.epoch, w.uidx, w.ucount, w.ulist, w.ucnt};
+  sample_recent(d, g, w.root_node, w.root_t, w.root_gid, R, w.nbr, w.neid, w.nts, w.cnt, w.slot_gid, w.slot_node, &uq, s);
+  uniq_finalize(ctx, S, s);
   tm.end(2);
 
-  // UPDT for root and supporting nodes from the pre-batch state
+  // UPDT once per distinct (replica, node) among the root and supporting nodes, from the pre-batch state
+  const int U = S < d.maxU ? S : d.maxU;   // launch bound; the actual row count is *w.ucount on the device
   GatherArgs a;
   memset(&a, 0, sizeof(a));
   a.mem = st->mem; a.mail = st->mail; a.efeat = g->efeat; a.mem_ts = st->mem_ts; a.mail_ts = st->mail_ts;
-  a.mail_eid = st->mail_eid; a.slot_gid = w.slot_gid; a.gid_add = 0;
+  a.mail_eid = st->mail_eid; a.slot_gid = w.ulist; a.gid_add = 0; a.n_dev = w.ucount;
   a.o_mem = w.Hm; a.p_mem = d.ldh; a.z_mem = d.ldh - d.dm;
   a.o_mail = w.X; a.p_mail = d.ldx;
   a.o_phi = w.X + 2 * d.dm; a.p_phi = d.ldx;
@@ -549,26 +561,26 @@ int32_t tgnn_train_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
   a.o_ef = w.X + 2 * d.dm + d.dt; a.p_ef = d.ldx; a.z_ef = d.ldx - d.d_in;
   a.o_tau = w.tau; a.o_delta = w.delta; a.o_has = w.has;
   a.time_w = p->time_w; a.time_b = p->time_b;
-  a.n_slots = S; a.dm = d.dm; a.dt = d.dt; a.de = d.de;
+  a.n_slots = U; a.dm = d.dm; a.dt = d.dt; a.de = d.de;
   tm.begin(3);
   gather_rows(a, s);
   tm.end(3);
   tm.begin(4);
-  gemm_nt(w.X, d.ldx, w.Wih_p, d.ldx, p->gru_bih, w.gi, d.ld3, S, 3 * d.dm, d.ldx, d.ld3, false, s);
+  gemm_nt(w.X, d.ldx, w.Wih_p, d.ldx, p->gru_bih, w.gi, d.ld3, U, 3 * d.dm, d.ldx, d.ld3, false, s, w.ucount);
   tm.end(4);
   tm.begin(5);
-  gemm_nt(w.Hm, d.ldh, w.Whh_p, d.ldh, p->gru_bhh, w.gh, d.ld3, S, 3 * d.dm, d.ldh, d.ld3, false, s);
+  gemm_nt(w.Hm, d.ldh, w.Whh_p, d.ldh, p->gru_bhh, w.gh, d.ld3, U, 3 * d.dm, d.ldh, d.ld3, false, s, w.ucount);
   tm.end(5);
   tm.begin(6);
-  gru_gates_fwd(d, S, w.gi, w.gh, w.Hm, w.has, w.gates, w.s_new, s);
+  gru_gates_fwd(d, U, w.ucount, w.gi, w.gh, w.Hm, w.has, w.gates, w.s_new, w.ds_row, s);
   tm.end(6);
 
   // attention + merge
   AttnAssembleArgs aa;
   memset(&aa, 0, sizeof(aa));
-  aa.s_root = w.s_new; aa.s_nbr = w.s_new + (size_t)R * d.ldh; aa.p_s = d.ldh;
+  aa.s_root = w.s_new; aa.s_nbr = w.s_new; aa.p_s = d.ldh; aa.slot_row = w.slot_row;
   aa.stat = st->stat; aa.efeat = g->efeat; aa.root_node = w.root_node; aa.nbr = w.nbr; aa.neid = w.neid; aa.cnt = w.cnt;
-  aa.root_t = w.root_t; aa.nts = w.nts; aa.tau_nbr = w.tau + R; aa.dt_in = nullptr;
+  aa.root_t = w.root_t; aa.nts = w.nts; aa.tau_nbr = w.tau; aa.dt_in = nullptr;
   aa.time_w = p->time_w; aa.time_b = p->time_b;
   aa.Cmat = w.Cmat; aa.Qin = w.Qin; aa.Min = w.Min; aa.ldc = d.ldc; aa.ldq = d.ldq; aa.ldm = d.ldm; aa.dtk = w.dtk;
   aa.msin = w.msinC; aa.p_msin = d.ldt;
@@ -610,15 +622,18 @@ int32_t tgnn_train_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
   attn_backward(ctx, grads, p, R, w.cnt, s);
   tm.end(14);
   tm.begin(15);
-  gru_gates_bwd(d, R, S, w.dMin, d.ldm, w.dQsub, w.dCsub, d.ldsub, w.gates, w.Hm, w.has, w.dgi, w.dgh, s);
+  seg_reduce(ctx, R, S, s);   // per-row sum of the gradients of the slots that share the row
+  gru_gates_bwd(d, U, w.ucount, w.ds_row, w.gates, w.Hm, w.has, w.dgi, w.dgh, s);
   tm.end(15);
   tm.begin(16);
-  gemm_tn_acc(w.dgi, d.ld3, w.X, d.ldx, S, 3 * d.dm, d.d_in, single_out(grads->gru_wih, d.d_in, grads->gru_bih), s);
-  gemm_tn_acc(w.dgh, d.ld3, w.Hm, d.ldh, S, 3 * d.dm, d.dm, single_out(grads->gru_whh, d.dm, grads->gru_bhh), s);
+  gemm_tn_acc(w.dgi, d.ld3, w.X, d.ldx, U, 3 * d.dm, d.d_in, single_out(grads->gru_wih, d.d_in, grads->gru_bih), s,
+              w.ucount);
+  gemm_tn_acc(w.dgh, d.ld3, w.Hm, d.ldh, U, 3 * d.dm, d.dm, single_out(grads->gru_whh, d.dm, grads->gru_bhh), s,
+              w.ucount);
   tm.end(16);
   tm.begin(17);
-  gemm_nt(w.dgi, d.ld3, w.WihT_phi, d.ld3, nullptr, w.dphi_g, d.ldt, S, d.dt, d.ld3, d.ldt, false, s);
-  time_grad(w.dphi_g, d.ldt, 0, w.msinX, d.ldt, w.delta, S, d.dt, p->time_b, grads->time_w, grads->time_b, s);
+  gemm_nt(w.dgi, d.ld3, w.WihT_phi, d.ld3, nullptr, w.dphi_g, d.ldt, U, d.dt, d.ld3, d.ldt, false, s, w.ucount);
+  time_grad(w.dphi_g, d.ldt, 0, w.msinX, d.ldt, w.delta, U, d.dt, p->time_b, grads->time_w, grads->time_b, s, w.ucount);
   tm.end(17);
 
   if (lr != 0.0f) {
@@ -628,8 +643,8 @@ int32_t tgnn_train_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
   }
 
   tm.begin(19);
-  writeback_scatter(d, w.bs_dev, bs.total, st, w.winkey, w.epoch, w.s_new, d.ldh, w.tau, nullptr, nullptr, nullptr,
-                    nullptr, out_winner, s);
+  writeback_scatter(d, w.bs_dev, bs.total, st, w.winkey, w.epoch, w.s_new, d.ldh, w.tau, w.slot_row, nullptr, nullptr,
+                    nullptr, nullptr, out_winner, s);
   tm.end(19);
   if (out_logits)
     TGNN_HIP_CHECK(hipMemcpyAsync(out_logits, w.logits, sizeof(float) * B2, hipMemcpyDeviceToDevice, s));
@@ -681,14 +696,24 @@ int32_t tgnn_debug_read(tgnn_ctx* ctx, int32_t what, void* dst, int64_t n_bytes,
     case 1: src = w.neid; cap = sizeof(int32_t) * d.maxRK; break;
     case 2: src = w.nts; cap = sizeof(double) * d.maxRK; break;
     case 3: src = w.cnt; cap = sizeof(int32_t) * d.maxR; break;
-    case 5: src = w.tau; cap = sizeof(double) * d.maxS; break;
+    case 5: break;
     case 4: case 6: case 7: break;
     default: return set_error(TGNN_E_INVALID_ARG, "unknown item %d", what);
   }
   hipStream_t s = as_stream(stream);
-  if (what == 4 || what == 6 || what == 7) {  // pitched float rows -> dense [rows, d_m]
-    const float* base = what == 4 ? w.s_new : (what == 6 ? w.z : w.h1);
-    const size_t max_rows = what == 4 ? d.maxS : (what == 6 ? (size_t)d.maxR : 2 * (size_t)d.maxEv);
+  if (what == 4 || what == 5) {  // per-slot view of the per-row s' / tau of the last tgnn_train_step
+    const size_t unit = what == 4 ? sizeof(float) * d.dm : sizeof(double);
+    if (n_bytes < 0 || (size_t)n_bytes % unit != 0 || (size_t)n_bytes / unit > (size_t)d.maxS)
+      return set_error(TGNN_E_OUT_OF_RANGE, "n_bytes is not a whole number of slots within capacity");
+    const int n = (int)((size_t)n_bytes / unit);
+    if (what == 4) expand_rows(ctx, n, w.s_new, d.ldh, nullptr, static_cast<float*>(dst), nullptr, s);
+    else expand_rows(ctx, n, nullptr, 0, w.tau, nullptr, static_cast<double*>(dst), s);
+    TGNN_LAUNCH_CHECK();
+    return TGNN_OK;
+  }
+  if (what == 6 || what == 7) {  // pitched float rows -> dense [rows, d_m]
+    const float* base = what == 6 ? w.z : w.h1;
+    const size_t max_rows = what == 6 ? (size_t)d.maxR : 2 * (size_t)d.maxEv;
     const size_t row_b = sizeof(float) * d.dm;
     if (n_bytes < 0 || (size_t)n_bytes % row_b != 0 || (size_t)n_bytes / row_b > max_rows)
       return set_error(TGNN_E_OUT_OF_RANGE, "n_bytes is not a whole number of rows within capacity");

@@ -26,7 +26,7 @@ struct Dims {
   int ldm;    // merge input rows {h_v | x_v}
   int ldsub;  // rows of width d_m + d_t (gradient wrt the dynamic and time-encoding columns)
   int ldt;    // rows of width d_t
-  int maxEv, maxR, maxRK, maxS;
+  int maxEv, maxR, maxRK, maxS, maxU;
 };
 
 struct BatchDesc {
@@ -51,6 +51,11 @@ struct Ws {
   double* dtk;                                 // [R*k] time difference in the keys
   unsigned long long* winkey;                  // [nrep*N] write-back arbitration: (epoch << 33) | occurrence key
   unsigned long long* epoch;                   // [1] bumped once per step, makes stale winkey entries lose
+  // distinct (replica, node) rows of the step
+  unsigned long long* utag;                    // [nrep*N] epoch of the last step that claimed the node
+  int32_t *uidx, *ucount, *ulist;              // [nrep*N] row of a claimed node; [1] number of rows; [maxU] row -> gid
+  int32_t *slot_row, *ucnt, *rowptr, *cursor, *sorted;  // [S] slot -> row; [maxU] slots per row; CSR of slots by row
+  float* ds_row;                               // [maxU, ldh] gradient reaching s' per row
   BatchSet* bs_dev;                            // device copy of the step's batch descriptors
   struct SgdSet* sgd_dev;                      // device copy of the parameter/gradient pointer table
   float *msinX, *msinC;                        // [S,ldt] [RK,ldt]  -sin of the time-encoding arguments
@@ -106,8 +111,9 @@ int set_error(int code, const char* fmt, ...);
 // ---- k_gemm.hip ---------------------------------------------------------------------
 // C[m, n] = sum_k A[m, k] * B[n, k] + bias[n]  (m < M, n < N), optional ReLU; columns [N, n_store) of C are
 // set to zero.  Kp (multiple of 32) columns of A and B are read; B rows >= N and A rows >= M read as zero.
+// m_dev (device pointer, may be NULL): the number of valid rows is min(M, *m_dev); the grid is sized for M.
 void gemm_nt(const float* A, int lda, const float* B, int ldb, const float* bias, float* C, int ldc, int M,
-             int N, int Kp, int n_store, bool relu, hipStream_t s);
+             int N, int Kp, int n_store, bool relu, hipStream_t s, const int* m_dev = nullptr);
 
 // Where the weight-gradient GEMM adds its result: element (n, k) goes to p[n >= n_split][k >= k_split]
 // (indices taken relative to the split) with row pitch ld[..][..]; column sums of D go to bias[n >= n_split].
@@ -119,7 +125,7 @@ struct OutMap {
 };
 // G[n, k] += sum_m D[m, n] * A[m, k]  (n < N, k < K), bias[n] += sum_m D[m, n]; float atomics.
 void gemm_tn_acc(const float* D, int ldd, const float* A, int lda, int M, int N, int K, const OutMap& out,
-                 hipStream_t s);
+                 hipStream_t s, const int* m_dev = nullptr);
 
 // ---- k_misc.hip ---------------------------------------------------------------------
 struct PackDesc {
@@ -146,9 +152,31 @@ void zero_set(const SgdSet& set, hipStream_t s);
 // ---- k_sample.hip -------------------------------------------------------------------
 // Roots of every batch (+ their slot ids) and the write-back arbitration marks of the positive endpoints.
 void build_roots(tgnn_ctx* ctx, int total, hipStream_t s);
+struct UniqPtrs {
+  unsigned long long* utag;
+  const unsigned long long* epoch;
+  int32_t *uidx, *ucount, *ulist, *ucnt;
+};
+// slot_gid / slot_node / uq may be NULL (plain sampling)
 void sample_recent(const Dims& d, const tgnn_graph* g, const int32_t* node, const double* t, const int32_t* gid_base,
                    int n_roots, int32_t* out_nbr, int32_t* out_eid, double* out_ts, int32_t* out_cnt,
-                   int32_t* slot_gid, int32_t* slot_node, hipStream_t s);
+                   int32_t* slot_gid, int32_t* slot_node, const UniqPtrs* uq, hipStream_t s);
+
+// ---- k_unique.hip -------------------------------------------------------------------
+// Claim (replica, node) `gid` for this step; the first claimant allocates the node's row.
+__device__ __forceinline__ void uniq_claim(unsigned long long* utag, int32_t* uidx, int32_t* ucount, int32_t* ulist,
+                                           int32_t* ucnt, int gid, unsigned long long epoch) {
+  if (atomicMax(utag + gid, epoch) < epoch) {
+    const int row = atomicAdd(ucount, 1);
+    uidx[gid] = row;
+    ulist[row] = gid;
+    ucnt[row] = 0;
+  }
+}
+void uniq_finalize(tgnn_ctx* ctx, int S, hipStream_t s);   // slot -> row map and the row-sorted slot list
+void seg_reduce(tgnn_ctx* ctx, int R, int S, hipStream_t s);
+void expand_rows(tgnn_ctx* ctx, int S, const float* src, int ld, const double* src_d, float* dst, double* dst_d,
+                 hipStream_t s);
 
 // ---- k_gather.hip -------------------------------------------------------------------
 struct GatherArgs {
@@ -157,6 +185,7 @@ struct GatherArgs {
   const double *mem_ts, *mail_ts;
   const int32_t* mail_eid;  // NULL: the staged layout of tgnn_gru_update (row index = slot, has_in given)
   const int32_t* has_in;
+  const int32_t* n_dev;     // device row count (NULL: n_slots)
   const int32_t* slot_gid;  // NULL: identity
   int gid_add;              // added to every non-negative slot_gid entry (replica offset)
   // destinations (pitches in floats)
@@ -173,6 +202,8 @@ void gather_rows(const GatherArgs& a, hipStream_t s);
 
 struct AttnAssembleArgs {
   const float *s_root, *s_nbr;  int p_s;  // dynamic rows of the roots [R, p_s] and of the neighbour slots [R*k, p_s]
+  const int32_t* slot_row;              // non-NULL: rows are s_root[slot_row[slot] * p_s] with slot = r or R + r*k + j,
+                                        // and tau_nbr is indexed by row as well
   const float* stat;                    // [N, ds] or NULL
   const float* efeat;                   // [E, de], or [R*k, de] when neid == NULL
   const int32_t *root_node, *nbr, *neid, *cnt;
@@ -187,17 +218,17 @@ struct AttnAssembleArgs {
 void attn_assemble(const AttnAssembleArgs& a, hipStream_t s);
 
 // ---- k_gru.hip ----------------------------------------------------------------------
-void gru_gates_fwd(const Dims& d, int n, const float* gi, const float* gh, const float* Hm, const int32_t* has,
-                   float* gates, float* s_new, hipStream_t s);
-// ds = gradient reaching s' per slot, assembled from dMin / dQsub (roots) and dCsub (neighbours)
-void gru_gates_bwd(const Dims& d, int R, int n, const float* dMin, int ldm, const float* dQsub, const float* dCsub,
-                   int ldsub, const float* gates, const float* Hm, const int32_t* has, float* dgi, float* dgh,
-                   hipStream_t s);
+// n_dev (device, may be NULL) caps the row count; ds_zero (may be NULL) [n, ldh] is cleared for the backward pass
+void gru_gates_fwd(const Dims& d, int n, const int* n_dev, const float* gi, const float* gh, const float* Hm,
+                   const int32_t* has, float* gates, float* s_new, float* ds_zero, hipStream_t s);
+// ds [n, ldh] = gradient reaching s' per row
+void gru_gates_bwd(const Dims& d, int n, const int* n_dev, const float* ds, const float* gates, const float* Hm,
+                   const int32_t* has, float* dgi, float* dgh, hipStream_t s);
 // time_w/time_b gradients from dPhi [n, ld] (dt columns starting at col0) and the stored -sin(arg) [n, p_msin]:
 // g_b[c] += sum_n dPhi * msin, g_w[c] += sum_n dPhi * msin * delta[n].  msin == NULL: delta = 0 for every row
 // (the query's Phi(0)), -sin(time_b[c]) is used and only g_b is updated.
 void time_grad(const float* dphi, int ld, int col0, const float* msin, int p_msin, const double* delta, int n, int dt,
-               const float* time_b, float* g_w, float* g_b, hipStream_t s);
+               const float* time_b, float* g_w, float* g_b, hipStream_t s, const int* n_dev = nullptr);
 
 // ---- k_attn.hip ---------------------------------------------------------------------
 void attn_core_fwd(const Dims& d, int R, const float* q, int ldq_, const float* KV, int ldkv, const int32_t* cnt,
@@ -234,7 +265,7 @@ void writeback_mark(const Dims& d, const BatchSet* bs, int total, unsigned long 
 // Fused layout: s_new/tau indexed by root slot.  Standalone layout: separate src/dst arrays.
 void writeback_scatter(const Dims& d, const BatchSet* bs, int total, const tgnn_state* st,
                        const unsigned long long* winkey, const unsigned long long* epoch, const float* s_new, int p_s,
-                       const double* tau, const float* s_src, const float* s_dst, const double* tau_src,
+                       const double* tau, const int32_t* slot_row, const float* s_src, const float* s_dst, const double* tau_src,
                        const double* tau_dst, int32_t* out_winner, hipStream_t s);
 // key of occurrence (event e = ev_off + i, role) in the step with epoch counter `epoch`
 __host__ __device__ inline unsigned long long wb_key(unsigned long long epoch, int e, int role) {
