@@ -93,27 +93,28 @@ void gru_gates_bwd(const Dims& d, int n, const int* n_dev, const float* ds, cons
                      dgh);
 }
 
-// g_b[c] += sum_n dphi[n, col0 + c] * msin[n, c] ;  g_w[c] += sum_n dphi * msin * delta_n.
-// A block owns a contiguous range of rows; thread (cy, cx) sums rows cy, cy + 4, ... of column cx (+64, ...).
-// Few blocks (<= 128): every block ends with one atomic per column, and atomics on one address serialise.
-constexpr int TG_MAX_BLOCKS = 128;
+// Time-encoding gradients: g_b[c] += sum_n dphi[n, col0 + c] * msin[n, c] ;  g_w[c] += sum_n dphi * msin * delta_n.
+// Stage 1 (time_grad): a block owns a contiguous range of rows and writes its column sums to a partial
+// buffer [TG_BLOCKS, 2, dt] (no atomics: hundreds of blocks adding to the same 2*dt addresses serialise).
+// Stage 2 (time_grad_finish): one block adds all partials of the step to the gradient tensors.
 __global__ __launch_bounds__(256) void time_grad_kernel(const float* __restrict__ dphi, int ld, int col0,
                                                         const float* __restrict__ msin, int p_msin,
                                                         const double* __restrict__ delta, int n_max,
                                                         const int* __restrict__ n_dev, int rows_per_block, int dt,
-                                                        const float* __restrict__ time_b, float* __restrict__ g_w,
-                                                        float* __restrict__ g_b) {
+                                                        const float* __restrict__ time_b,
+                                                        float* __restrict__ partial) {
   __shared__ float sw[4][64], sb[4][64];
   const int n = n_dev ? min(n_max, *n_dev) : n_max;
-  if ((int)blockIdx.x * rows_per_block >= n) return;
   const int cx = threadIdx.x & 63, cy = threadIdx.x >> 6;
-  const int r0 = blockIdx.x * rows_per_block;
+  const int r0 = min(n, (int)blockIdx.x * rows_per_block);
   const int r1 = min(n, r0 + rows_per_block);
+  float* out = partial + (size_t)blockIdx.x * 2 * dt;
   for (int c0 = 0; c0 < dt; c0 += 64) {
     const int c = c0 + cx;
     float aw = 0.f, ab = 0.f;
     if (c < dt) {
       if (msin != nullptr) {
+#pragma unroll 8
         for (int r = r0 + cy; r < r1; r += 4) {
           const float t = dphi[(size_t)r * ld + col0 + c] * msin[(size_t)r * p_msin + c];
           ab += t;
@@ -122,6 +123,7 @@ __global__ __launch_bounds__(256) void time_grad_kernel(const float* __restrict_
       } else {
         float sn, cs;
         sincos_reduced((double)time_b[c], sn, cs);
+#pragma unroll 8
         for (int r = r0 + cy; r < r1; r += 4) ab -= dphi[(size_t)r * ld + col0 + c] * sn;
       }
     }
@@ -129,20 +131,47 @@ __global__ __launch_bounds__(256) void time_grad_kernel(const float* __restrict_
     sb[cy][cx] = ab;
     __syncthreads();
     if (cy == 0 && c < dt) {
-      if (msin != nullptr) atomicAdd(g_w + c, sw[0][cx] + sw[1][cx] + sw[2][cx] + sw[3][cx]);
-      atomicAdd(g_b + c, sb[0][cx] + sb[1][cx] + sb[2][cx] + sb[3][cx]);
+      out[c] = sw[0][cx] + sw[1][cx] + sw[2][cx] + sw[3][cx];
+      out[dt + c] = sb[0][cx] + sb[1][cx] + sb[2][cx] + sb[3][cx];
     }
     __syncthreads();
   }
 }
 
 void time_grad(const float* dphi, int ld, int col0, const float* msin, int p_msin, const double* delta, int n, int dt,
-               const float* time_b, float* g_w, float* g_b, hipStream_t s, const int* n_dev) {
+               const float* time_b, float* partial, hipStream_t s, const int* n_dev) {
   if (n <= 0) return;
-  int rpb = (n + TG_MAX_BLOCKS - 1) / TG_MAX_BLOCKS;
-  rpb = (rpb + 3) & ~3;
-  hipLaunchKernelGGL(time_grad_kernel, dim3((n + rpb - 1) / rpb), dim3(256), 0, s, dphi, ld, col0, msin, p_msin, delta,
-                     n, n_dev, rpb, dt, time_b, g_w, g_b);
+  const int rpb = (((n + TG_BLOCKS - 1) / TG_BLOCKS) + 3) & ~3;
+  hipLaunchKernelGGL(time_grad_kernel, dim3(TG_BLOCKS), dim3(256), 0, s, dphi, ld, col0, msin, p_msin, delta, n, n_dev,
+                     rpb, dt, time_b, partial);
+}
+
+// grid (ceil(2 dt / 32), TGF_SPLIT); block = 32 columns x 32 partial groups
+constexpr int TGF_SPLIT = 8;
+__global__ __launch_bounds__(1024) void time_grad_finish_kernel(const float* __restrict__ partial, int n_partials,
+                                                                int dt, float* __restrict__ g_w,
+                                                                float* __restrict__ g_b) {
+  __shared__ float red[32][33];
+  const int cx = threadIdx.x & 31, cy = threadIdx.x >> 5;
+  const int c = blockIdx.x * 32 + cx;
+  float acc = 0.f;
+  if (c < 2 * dt) {
+#pragma unroll 4
+    for (int b = blockIdx.y * 32 + cy; b < n_partials; b += 32 * TGF_SPLIT) acc += partial[(size_t)b * 2 * dt + c];
+  }
+  red[cy][cx] = acc;
+  __syncthreads();
+  if (cy == 0 && c < 2 * dt) {
+    float t = 0.f;
+#pragma unroll
+    for (int j = 0; j < 32; ++j) t += red[j][cx];
+    atomicAdd(c < dt ? g_w + c : g_b + (c - dt), t);
+  }
+}
+
+void time_grad_finish(const float* partial, int n_calls, int dt, float* g_w, float* g_b, hipStream_t s) {
+  hipLaunchKernelGGL(time_grad_finish_kernel, dim3((2 * dt + 31) / 32, TGF_SPLIT), dim3(1024), 0, s, partial,
+                     n_calls * TG_BLOCKS, dt, g_w, g_b);
 }
 
 }  // namespace tgnn

@@ -8,18 +8,49 @@
 
 namespace tgnn {
 
+// Adds 1 to counter[key] for every lane with key >= 0 and returns the value before this lane's increment.
+// Lanes of a wavefront that share a key are merged into one atomic (power-law graphs put thousands of
+// slots on one node, and atomics on one address serialise).  The grouping loop uses only cross-lane ALU
+// operations; the atomics of all group leaders are then issued together, so the wave pays one round trip.
+__device__ __forceinline__ int wave_counted_add(int32_t* counter, int key, bool want_result) {
+  const int lane = threadIdx.x & 63;
+  bool pending = key >= 0;
+  int leader = lane, count = 0, rank = 0;
+  while (true) {
+    const unsigned long long todo = __ballot(pending);
+    if (todo == 0ull) break;
+    const int first = __ffsll((long long)todo) - 1;
+    const int k = __shfl(key, first);
+    const bool mine = pending && key == k;
+    const unsigned long long same = __ballot(mine);
+    if (mine) {
+      leader = first;
+      count = __popcll(same);
+      rank = __popcll(same & ((1ull << lane) - 1ull));
+      pending = false;
+    }
+  }
+  int base = 0;
+  if (key >= 0 && leader == lane) {
+    if (want_result) base = atomicAdd(counter + key, count);
+    else atomicAdd(counter + key, count);
+  }
+  if (!want_result) return 0;
+  base = __shfl(base, leader);
+  return base + rank;
+}
+
 // slot -> row, and the number of slots per row
 __global__ void uniq_map_kernel(int S, const int32_t* __restrict__ slot_gid, const int32_t* __restrict__ uidx,
                                 int32_t* __restrict__ slot_row, int32_t* __restrict__ ucnt) {
   const int s = blockIdx.x * blockDim.x + threadIdx.x;
-  if (s >= S) return;
-  const int gid = slot_gid[s];
   int row = -1;
-  if (gid >= 0) {
-    row = uidx[gid];
-    atomicAdd(ucnt + row, 1);
+  if (s < S) {
+    const int gid = slot_gid[s];
+    if (gid >= 0) row = uidx[gid];
+    slot_row[s] = row;
   }
-  slot_row[s] = row;
+  wave_counted_add(ucnt, row, false);
 }
 
 // exclusive scan of ucnt[0 .. U) into rowptr[0 .. U] and cursor[0 .. U); one block
@@ -52,9 +83,9 @@ __global__ __launch_bounds__(1024) void uniq_scan_kernel(const int32_t* __restri
 __global__ void uniq_fill_kernel(int S, const int32_t* __restrict__ slot_row, int32_t* __restrict__ cursor,
                                  int32_t* __restrict__ sorted) {
   const int s = blockIdx.x * blockDim.x + threadIdx.x;
-  if (s >= S) return;
-  const int row = slot_row[s];
-  if (row >= 0) sorted[atomicAdd(cursor + row, 1)] = s;
+  const int row = s < S ? slot_row[s] : -1;
+  const int pos = wave_counted_add(cursor, row, true);
+  if (row >= 0) sorted[pos] = s;
 }
 
 void uniq_finalize(tgnn_ctx* ctx, int S, hipStream_t s) {
@@ -68,7 +99,7 @@ void uniq_finalize(tgnn_ctx* ctx, int S, hipStream_t s) {
 //   root slot r      : dMin[r, dO + c] + dQsub[r, c]     (merge layer + query)
 //   neighbour slot   : dCsub[slot - R, c]                (key/value input)
 // One wavefront owns SEG_CHUNK consecutive entries of the row-sorted slot list.
-constexpr int SEG_CHUNK = 32;
+constexpr int SEG_CHUNK = 16;
 __global__ __launch_bounds__(256) void seg_reduce_kernel(int R, int dm, int dO, const int32_t* __restrict__ ucount,
                                                          const int32_t* __restrict__ rowptr,
                                                          const int32_t* __restrict__ sorted,
@@ -84,37 +115,49 @@ __global__ __launch_bounds__(256) void seg_reduce_kernel(int R, int dm, int dO, 
   const int p0 = chunk * SEG_CHUNK;
   if (p0 >= total) return;
   const int n = min(SEG_CHUNK, total - p0);
-  // lanes fetch the chunk's slot ids and rows in parallel, the loop below broadcasts them
+  // lanes fetch the chunk's slot ids and rows in parallel; they are broadcast below
   int my_slot = -1, my_row = -1;
   if (lane < n) {
     my_slot = sorted[p0 + lane];
     my_row = slot_row[my_slot];
     if (!has[my_row]) my_row = -1;   // no mail consumed: s' is the stored memory, a constant
   }
+  // all row loads of the chunk are issued before any is consumed
+  float v[SEG_CHUNK][4];
+  int rows[SEG_CHUNK];
+#pragma unroll
+  for (int i = 0; i < SEG_CHUNK; ++i) {
+    const int slot = __shfl(my_slot, i);
+    rows[i] = __shfl(my_row, i);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int c = lane + 64 * q;
+      float x = 0.f;
+      if (rows[i] >= 0 && c < dm) {
+        if (slot < R) x = dMin[(size_t)slot * ldm + dO + c] + dQsub[(size_t)slot * ldsub + c];
+        else x = dCsub[(size_t)(slot - R) * ldsub + c];
+      }
+      v[i][q] = x;
+    }
+  }
   float acc[4] = {0.f, 0.f, 0.f, 0.f};
   int cur = -1;
-  for (int i = 0; i < n; ++i) {
-    const int slot = __shfl(my_slot, i), row = __shfl(my_row, i);
-    if (row != cur) {
+#pragma unroll
+  for (int i = 0; i < SEG_CHUNK; ++i) {
+    if (rows[i] != cur) {
       if (cur >= 0) {
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
           const int c = lane + 64 * q;
           if (c < dm) atomicAdd(ds_row + (size_t)cur * ldh + c, acc[q]);
-          acc[q] = 0.f;
         }
       }
-      cur = row;
-    }
-    if (row < 0) continue;
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const int c = lane + 64 * q;
-      if (c < dm) {
-        if (slot < R) acc[q] += dMin[(size_t)slot * ldm + dO + c] + dQsub[(size_t)slot * ldsub + c];
-        else acc[q] += dCsub[(size_t)(slot - R) * ldsub + c];
-      }
+      for (int q = 0; q < 4; ++q) acc[q] = 0.f;
+      cur = rows[i];
     }
+#pragma unroll
+    for (int q = 0; q < 4; ++q) acc[q] += v[i][q];
   }
   if (cur >= 0) {
 #pragma unroll

@@ -98,6 +98,7 @@ static void layout(const Dims& d, Ws& w, Bump& b) {
   w.bs_dev = b.take<BatchSet>(1);
   w.sgd_dev = b.take<SgdSet>(1);
   w.msinX = b.take<float>(S * d.ldt); w.msinC = b.take<float>(RK * d.ldt);
+  w.tg_partial = b.take<float>((size_t)3 * TG_BLOCKS * 2 * d.dt);
   w.X = b.take<float>(S * d.ldx); w.Hm = b.take<float>(S * d.ldh);
   w.gi = b.take<float>(S * d.ld3); w.gh = b.take<float>(S * d.ld3);
   w.gates = b.take<float>(S * 4 * d.ldh); w.s_new = b.take<float>(S * d.ldh);
@@ -150,7 +151,7 @@ static void attn_forward(tgnn_ctx* ctx, const tgnn_params* p, int R, const int32
 // From ws.dz (already masked by the merge ReLU) down to ws.dMin / ws.dQsub / ws.dCsub, adding the
 // gradients of W_o, W_q, W_k, W_v, their biases and the time encoding.
 static void attn_backward(tgnn_ctx* ctx, tgnn_params* g, const tgnn_params* p, int R, const int32_t* cnt,
-                          hipStream_t s) {
+                          bool finish_time_grad, hipStream_t s) {
   const Dims& d = ctx->d; Ws& w = ctx->w;
   const int RK = R * d.k;
   gemm_tn_acc(w.dz, d.ldh, w.Min, d.ldm, R, d.dO, d.dO + d.dx, single_out(g->wo, d.dO + d.dx, g->bo), s);
@@ -165,8 +166,10 @@ static void attn_backward(tgnn_ctx* ctx, tgnn_params* g, const tgnn_params* p, i
   gemm_nt(w.dKV, d.ldkv, w.WkvT_sub, d.ldkv, nullptr, w.dCsub, d.ldsub, RK, d.dm + d.dt, d.ldkv, d.ldsub, false, s);
   gemm_tn_acc(w.dq, d.ldh, w.Qin, d.ldq, R, d.dO, d.dq, single_out(g->wq, d.dq, g->bq), s);
   gemm_nt(w.dq, d.ldh, w.WqT_sub, d.ldh, nullptr, w.dQsub, d.ldsub, R, d.dm + d.dt, d.ldh, d.ldsub, false, s);
-  time_grad(w.dCsub, d.ldsub, d.dm, w.msinC, d.ldt, w.dtk, RK, d.dt, p->time_b, g->time_w, g->time_b, s);
-  time_grad(w.dQsub, d.ldsub, d.dm, nullptr, 0, nullptr, R, d.dt, p->time_b, g->time_w, g->time_b, s);
+  const size_t tgp = (size_t)TG_BLOCKS * 2 * d.dt;
+  time_grad(w.dCsub, d.ldsub, d.dm, w.msinC, d.ldt, w.dtk, RK, d.dt, p->time_b, w.tg_partial, s);
+  time_grad(w.dQsub, d.ldsub, d.dm, nullptr, 0, nullptr, R, d.dt, p->time_b, w.tg_partial + tgp, s);
+  if (finish_time_grad) time_grad_finish(w.tg_partial, 2, d.dt, g->time_w, g->time_b, s);
 }
 
 static hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
@@ -446,7 +449,7 @@ int32_t tgnn_temporal_attn_bwd(tgnn_ctx* ctx, const tgnn_params* p, int32_t n_ro
   REQ_PTR(dz); REQ_PTR(d_x_root); REQ_PTR(d_x_nbr);
   hipStream_t s = as_stream(stream);
   mask_dz(n_roots, d.dO, dz, d.dO, w.z, d.ldh, w.dz, s);
-  attn_backward(ctx, grads, p, n_roots, w.cnt, s);
+  attn_backward(ctx, grads, p, n_roots, w.cnt, true, s);
   attn_dx_out(n_roots, n_roots * d.k, d.dm, d.dO, w.dMin, d.ldm, w.dQsub, w.dCsub, d.ldsub, d_x_root, d_x_nbr, s);
   TGNN_LAUNCH_CHECK();
   return TGNN_OK;
@@ -619,7 +622,7 @@ int32_t tgnn_train_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
   decoder_dz(d, w.bs_dev, bs.total, w.dAdec, d.ldkv, w.z, d.ldh, w.dz, s);
   tm.end(13);
   tm.begin(14);
-  attn_backward(ctx, grads, p, R, w.cnt, s);
+  attn_backward(ctx, grads, p, R, w.cnt, false, s);
   tm.end(14);
   tm.begin(15);
   seg_reduce(ctx, R, S, s);   // per-row sum of the gradients of the slots that share the row
@@ -633,7 +636,9 @@ int32_t tgnn_train_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
   tm.end(16);
   tm.begin(17);
   gemm_nt(w.dgi, d.ld3, w.WihT_phi, d.ld3, nullptr, w.dphi_g, d.ldt, U, d.dt, d.ld3, d.ldt, false, s, w.ucount);
-  time_grad(w.dphi_g, d.ldt, 0, w.msinX, d.ldt, w.delta, U, d.dt, p->time_b, grads->time_w, grads->time_b, s, w.ucount);
+  time_grad(w.dphi_g, d.ldt, 0, w.msinX, d.ldt, w.delta, U, d.dt, p->time_b,
+            w.tg_partial + (size_t)2 * TG_BLOCKS * 2 * d.dt, s, w.ucount);
+  time_grad_finish(w.tg_partial, 3, d.dt, grads->time_w, grads->time_b, s);
   tm.end(17);
 
   if (lr != 0.0f) {

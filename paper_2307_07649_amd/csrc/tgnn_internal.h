@@ -59,6 +59,7 @@ struct Ws {
   BatchSet* bs_dev;                            // device copy of the step's batch descriptors
   struct SgdSet* sgd_dev;                      // device copy of the parameter/gradient pointer table
   float *msinX, *msinC;                        // [S,ldt] [RK,ldt]  -sin of the time-encoding arguments
+  float* tg_partial;                           // [3, TG_BLOCKS, 2, dt] partial time-encoding gradient sums
   // GRU
   float *X, *Hm, *gi, *gh, *gates, *s_new;     // [S,ldx] [S,ldh] [S,ld3] [S,ld3] [S,4*ldh] [S,ldh]
   float *dgi, *dgh, *dphi_g;                   // [S,ld3] [S,ld3] [S,ldh(dt)]
@@ -166,6 +167,8 @@ void sample_recent(const Dims& d, const tgnn_graph* g, const int32_t* node, cons
 // Claim (replica, node) `gid` for this step; the first claimant allocates the node's row.
 __device__ __forceinline__ void uniq_claim(unsigned long long* utag, int32_t* uidx, int32_t* ucount, int32_t* ulist,
                                            int32_t* ucnt, int gid, unsigned long long epoch) {
+  // popular nodes are claimed thousands of times per step: look before touching the atomic unit
+  if (__atomic_load_n(utag + gid, __ATOMIC_RELAXED) >= epoch) return;
   if (atomicMax(utag + gid, epoch) < epoch) {
     const int row = atomicAdd(ucount, 1);
     uidx[gid] = row;
@@ -224,11 +227,15 @@ void gru_gates_fwd(const Dims& d, int n, const int* n_dev, const float* gi, cons
 // ds [n, ldh] = gradient reaching s' per row
 void gru_gates_bwd(const Dims& d, int n, const int* n_dev, const float* ds, const float* gates, const float* Hm,
                    const int32_t* has, float* dgi, float* dgh, hipStream_t s);
-// time_w/time_b gradients from dPhi [n, ld] (dt columns starting at col0) and the stored -sin(arg) [n, p_msin]:
-// g_b[c] += sum_n dPhi * msin, g_w[c] += sum_n dPhi * msin * delta[n].  msin == NULL: delta = 0 for every row
-// (the query's Phi(0)), -sin(time_b[c]) is used and only g_b is updated.
+// Time-encoding gradients in two stages.  time_grad: column sums of dPhi [n, ld] (dt columns from col0) times
+// the stored -sin(arg) [n, p_msin] (and times delta[n] for time_w) per block of rows, written to
+// partial[TG_BLOCKS, 2, dt] (always all TG_BLOCKS entries).  msin == NULL: delta = 0 for every row (the
+// query's Phi(0)); -sin(time_b[c]) is used and the time_w sums are zero.  time_grad_finish: adds the
+// partials of n_calls consecutive regions to g_w / g_b.
+constexpr int TG_BLOCKS = 1024;
 void time_grad(const float* dphi, int ld, int col0, const float* msin, int p_msin, const double* delta, int n, int dt,
-               const float* time_b, float* g_w, float* g_b, hipStream_t s, const int* n_dev = nullptr);
+               const float* time_b, float* partial, hipStream_t s, const int* n_dev = nullptr);
+void time_grad_finish(const float* partial, int n_calls, int dt, float* g_w, float* g_b, hipStream_t s);
 
 // ---- k_attn.hip ---------------------------------------------------------------------
 void attn_core_fwd(const Dims& d, int R, const float* q, int ldq_, const float* KV, int ldkv, const int32_t* cnt,
