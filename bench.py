@@ -22,17 +22,26 @@ sys.path.insert(0, ROOT)
 PEAK_HBM_GBS = 8000.0
 PEAK_MFMA_F32_TFLOPS = 157.3
 
-STAGE_GATHER, STAGE_GRU_IH = 3, 4
+STAGE_NAMES = ["prologue (pack weights, clear)", "roots + write-back arbitration", "sample + distinct-node rows",
+               "gather + time-encode (GRU input)", "GRU input projection (MFMA)", "GRU hidden projection (MFMA)",
+               "GRU gates", "attention input assembly (gather)", "K/V projection (MFMA)", "query projection (MFMA)",
+               "softmax attention", "merge layer (MFMA)", "decoder forward + loss", "decoder backward",
+               "attention backward (MFMA + softmax)", "segmented gradient sum + GRU gates backward",
+               "GRU weight gradients (MFMA)", "time-encoding gradients", "SGD", "write-back scatter"]
+STAGE_ASSEMBLE, STAGE_KV = 7, 8
 
 
-def flops_gru_ih(d, n_slots):
-    return 2.0 * n_slots * d.d_in * 3 * d.d_mem
+def flops_kv(d, n_roots):
+    """K and V projections of every neighbour slot: [R k, d_kv] x [d_kv, 2 d_o]."""
+    return 2.0 * n_roots * d.k * d.d_kv * 2 * d.d_out
 
 
-def gather_bytes(d, n_slots):
-    # per slot: read mem row, mail row, mail edge-feature row, two timestamps + event id; write the same rows staged
-    row = 4 * (d.d_mem + 2 * d.d_mem + d.d_edge)
-    return n_slots * (2 * row + 20 + 4 * d.d_time)
+def assemble_bytes(d, n_roots):
+    """Attention input assembly: per neighbour slot read the s' row, the static row and the edge-feature row and
+    write the key/value input row, the -sin row and the time difference; per root the query / merge inputs."""
+    per_nbr = 4 * (d.d_mem + d.d_static + d.d_edge) + 4 * d.d_kv + 4 * d.d_time + 8 + 8
+    per_root = 4 * (d.d_mem + d.d_static) + 4 * d.d_q + 4 * d.d_x
+    return n_roots * (d.k * per_nbr + per_root)
 
 
 def step_flops(d, B):
@@ -86,6 +95,9 @@ def main():
     ap.add_argument("--events", type=int, default=None, help="shorten the event list (C4: default 2,000,000)")
     ap.add_argument("--lr", type=float, default=1e-4)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="first run the library's plain copy kernel on 256 MiB three times (reference for rocprofv3 --pmc "
+                         "FETCH_SIZE / WRITE_SIZE readings)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -99,6 +111,13 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(3)
+
+    if args.calibrate_copy:
+        a = torch.ones(64 << 20, device="cuda"); b = torch.empty_like(a)      # 256 MiB each
+        for _ in range(3):
+            tgnn.tgnn_debug_copy(b, a)
+        torch.cuda.synchronize()
+        del a, b
 
     name = args.config
     n_events = args.events
@@ -139,7 +158,7 @@ def main():
     for s in range(args.warmup):
         run_step(s)
     torch.cuda.synchronize()
-    ctx.tgnn_profile_enable((1 << STAGE_GATHER) | (1 << STAGE_GRU_IH))
+    ctx.tgnn_profile_enable((1 << STAGE_ASSEMBLE) | (1 << STAGE_KV))
     ev = 0
     t0 = time.perf_counter()
     for s in range(args.warmup, args.warmup + args.steps):
@@ -147,14 +166,27 @@ def main():
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     final_loss = float(loss[0].item())
-    n_g, ms_g = ctx.tgnn_profile_read(STAGE_GATHER)
-    n_m, ms_m = ctx.tgnn_profile_read(STAGE_GRU_IH)
+    n_g, ms_g = ctx.tgnn_profile_read(STAGE_ASSEMBLE)
+    n_m, ms_m = ctx.tgnn_profile_read(STAGE_KV)
+    ctx.tgnn_profile_enable(0)
+
+    # per-stage breakdown from a separate, untimed pass with every stage bracketed by events
+    n_prof = min(args.steps, 64)
+    ctx.tgnn_profile_enable((1 << len(STAGE_NAMES)) - 1)
+    for s in range(args.warmup + args.steps, args.warmup + args.steps + n_prof):
+        run_step(s)
+    torch.cuda.synchronize()
+    stages = {}
+    for i, nm in enumerate(STAGE_NAMES):
+        c, ms = ctx.tgnn_profile_read(i)
+        if c:
+            stages[nm] = round(ms / c * 1e3, 2)
     ctx.tgnn_profile_enable(0)
 
     ev_step = ev / args.steps
-    S_avg = 3 * ev_step * (1 + d.k)
-    gru_tflops = flops_gru_ih(d, S_avg) / (ms_m / n_m * 1e-3) / 1e12 if n_m else None
-    gather_gbs = gather_bytes(d, S_avg) / (ms_g / n_g * 1e-3) / 1e9 if n_g else None
+    R_avg = 3 * ev_step
+    kv_tflops = flops_kv(d, R_avg) / (ms_m / n_m * 1e-3) / 1e12 if n_m else None
+    asm_gbs = assemble_bytes(d, R_avg) / (ms_g / n_g * 1e-3) / 1e9 if n_g else None
     out = {
         "metric": "training events/sec (fwd+bwd+memory update) at 1 GPU",
         "value": ev / dt, "unit": "events/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -164,16 +196,20 @@ def main():
                                f"d_edge {d.d_edge}, d_static {d.d_static}, {d.n_heads} heads, k {d.k}, "
                                f"batch {d.batch} x {nrep} replica(s), 1 negative/event, SGD lr {args.lr}",
                    "events_per_step": ev_step, "final_loss": final_loss},
-        "roofline": {"bound": "mfma", "kernel": "gemm_nt_kernel (GRU input projection, fp32 MFMA 16x16x4)",
-                     "achieved": gru_tflops, "peak": PEAK_MFMA_F32_TFLOPS, "unit": "TFLOP/s",
-                     "frac": gru_tflops / PEAK_MFMA_F32_TFLOPS if gru_tflops else None,
+        "roofline": {"bound": "mfma", "kernel": "gemm_nt_kernel: K/V projection of all neighbour slots "
+                                                "(fp32 MFMA 16x16x4), the longest kernel of the step",
+                     "achieved": kv_tflops, "peak": PEAK_MFMA_F32_TFLOPS, "unit": "TFLOP/s",
+                     "frac": kv_tflops / PEAK_MFMA_F32_TFLOPS if kv_tflops else None,
                      "avg_launch_us": ms_m / n_m * 1e3 if n_m else None, "traffic": None},
-        "gather": {"bound": "hbm", "kernel": "gather_kernel (memory + mail + edge-feature rows, time encoding)",
-                   "achieved": gather_gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                   "frac": gather_gbs / PEAK_HBM_GBS if gather_gbs else None,
+        "gather": {"bound": "hbm", "kernel": "attn_assemble_kernel: s' / static / edge-feature row gather + time "
+                                             "encoding into the key/value inputs",
+                   "achieved": asm_gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                   "frac": asm_gbs / PEAK_HBM_GBS if asm_gbs else None,
                    "avg_launch_us": ms_g / n_g * 1e3 if n_g else None},
-        "step_model": {"flops_per_step": step_flops(d, ev_step), "bytes_per_step": step_bytes(d, ev_step),
-                       "whole_step_tflops": step_flops(d, ev_step) / (dt / args.steps) / 1e12},
+        "step_model": {"flops_per_step_per_slot_updt": step_flops(d, ev_step), "bytes_per_step": step_bytes(d, ev_step),
+                       "note": "flops counted with UPDT per slot as the method states it; the library evaluates "
+                               "UPDT once per distinct node, so executed flops are lower"},
+        "stages_us": stages,
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(P)

@@ -207,6 +207,10 @@ int32_t tgnn_zero_params(tgnn_ctx* ctx, tgnn_params* g, void* stream);
 int32_t tgnn_profile_enable(tgnn_ctx* ctx, uint32_t stage_mask);
 int32_t tgnn_profile_read(tgnn_ctx* ctx, int32_t stage, int32_t* out_count, double* out_total_ms);
 
+/* A plain streaming copy kernel (dst[i] = src[i], 16-byte words; n_bytes % 16 == 0; buffers must not overlap).
+ * It moves a known number of bytes, which calibrates hardware HBM-traffic counters. */
+int32_t tgnn_debug_copy(void* dst, const void* src, int64_t n_bytes, void* stream);
+
 /* Debug/parity access to what the last tgnn_train_step left in the workspace.  `what`:
  * 0 nbr [R,k] i32, 1 eid [R,k] i32, 2 nts [R,k] f64, 3 cnt [R] i32, 4 s_new [R(1+k), d_m] f32,
  * 5 tau [R(1+k)] f64, 6 z [R, d_o] f32, 7 decoder hidden layer [2 sum n, d_o] f32.  Copies n_bytes (device to device) into dst on `stream`. */

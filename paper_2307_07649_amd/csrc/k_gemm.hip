@@ -32,12 +32,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 2))) voi
                                                       const float* __restrict__ B, int ldb,
                                                       const float* __restrict__ bias, float* __restrict__ C, int ldc,
                                                       int M, int N, int Kp, int n_store, int relu,
-                                                      const int* __restrict__ m_dev) {
+                                                      const int* __restrict__ m_dev, int col_tiles) {
   constexpr int BM = 64, BN = 16 * TN;
-  if (m_dev != nullptr) {
-    M = min(M, *m_dev);
-    if ((int)blockIdx.y * BM >= M) return;   // uniform for the workgroup, before any barrier
-  }
+  // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  The column tiles of one row tile
+  // read the same rows of A, so they are given consecutive slots of one XCD.
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int row_tile = (slot / col_tiles) * 8 + xcd, col_tile = slot % col_tiles;
+  if (m_dev != nullptr) M = min(M, *m_dev);
+  if (row_tile * BM >= M) return;   // uniform for the workgroup, before any barrier
   constexpr int A_PER = BM * 8 / 256, B_F4 = BN * 8;  // float4 loads per stage and thread
   constexpr int B_PER = (B_F4 + 255) / 256;
   __shared__ __attribute__((aligned(16))) float As[2][BM * NT_P];
@@ -45,7 +47,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 2))) voi
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int li = lane & 15, lg = lane >> 4;
-  const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+  const int m0 = row_tile * BM, n0 = col_tile * BN;
 
   floatx4 acc[TN];
 #pragma unroll
@@ -163,9 +165,10 @@ template <int TN>
 static void launch_nt(const float* A, int lda, const float* B, int ldb, const float* bias, float* C, int ldc, int M,
                       int N, int Kp, int n_store, bool relu, hipStream_t s, const int* m_dev) {
   constexpr int BM = 64, BN = 16 * TN;
-  dim3 grid((n_store + BN - 1) / BN, (M + BM - 1) / BM);
-  hipLaunchKernelGGL((gemm_nt_kernel<TN>), grid, dim3(256), 0, s, A, lda, B, ldb, bias, C, ldc, M, N, Kp, n_store,
-                     relu ? 1 : 0, m_dev);
+  const int col_tiles = (n_store + BN - 1) / BN;
+  const int row_tiles8 = ((M + BM - 1) / BM + 7) & ~7;
+  hipLaunchKernelGGL((gemm_nt_kernel<TN>), dim3(col_tiles * row_tiles8), dim3(256), 0, s, A, lda, B, ldb, bias, C, ldc, M,
+                     N, Kp, n_store, relu ? 1 : 0, m_dev, col_tiles);
 }
 
 void gemm_nt(const float* A, int lda, const float* B, int ldb, const float* bias, float* C, int ldc, int M, int N,
@@ -213,22 +216,26 @@ constexpr int TN_ROWS = 32;
 
 __global__ __launch_bounds__(256) void gemm_tn_kernel(const float* __restrict__ D, int ldd,
                                                       const float* __restrict__ A, int lda, int M, int N, int K,
-                                                      int m_chunk, int k_tiles, OutMap out,
-                                                      const int* __restrict__ m_dev) {
+                                                      int m_chunk, int k_tiles, int tiles, int chunks,
+                                                      OutMap out, const int* __restrict__ m_dev) {
+  // All output tiles of one m-chunk read the same rows of D and A: keep them on one XCD (one L2).
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int chunk = (slot / tiles) * 8 + xcd, tile = slot % tiles;
+  if (chunk >= chunks) return;
   if (m_dev != nullptr) {  // row count known only on the device: split it evenly over the launched chunks
     M = min(M, *m_dev);
-    m_chunk = ((M + (int)gridDim.y - 1) / (int)gridDim.y + TN_ROWS - 1) / TN_ROWS * TN_ROWS;
-    if ((int)blockIdx.y * m_chunk >= M) return;
+    m_chunk = ((M + chunks - 1) / chunks + TN_ROWS - 1) / TN_ROWS * TN_ROWS;
   }
+  if (chunk * m_chunk >= M) return;
   __shared__ __attribute__((aligned(16))) float Ds[2][TN_ROWS * TN_P];
   __shared__ __attribute__((aligned(16))) float Asm[2][TN_ROWS * TN_P];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int li = lane & 15, lg = lane >> 4;
   const int wn = wave >> 1, wk = wave & 1;
-  const int n0 = (blockIdx.x / k_tiles) * TT, k0 = (blockIdx.x % k_tiles) * TT;
-  const int m_lo = blockIdx.y * m_chunk;
+  const int n0 = (tile / k_tiles) * TT, k0 = (tile % k_tiles) * TT;
+  const int m_lo = chunk * m_chunk;
   const int m_hi = min(M, m_lo + m_chunk);
-  const bool do_bias = (blockIdx.x % k_tiles) == 0 && (out.bias[0] != nullptr);
+  const bool do_bias = (tile % k_tiles) == 0 && (out.bias[0] != nullptr);
 
   floatx4 acc[2][2];
 #pragma unroll
@@ -353,8 +360,9 @@ void gemm_tn_acc(const float* D, int ldd, const float* A, int lda, int M, int N,
   int m_chunk = ((M + chunks - 1) / chunks + TN_ROWS - 1) / TN_ROWS * TN_ROWS;
   chunks = (M + m_chunk - 1) / m_chunk;
   if (m_dev != nullptr && chunks > 16) chunks = 16;   // the device-side row count is usually far below M
-  hipLaunchKernelGGL(gemm_tn_kernel, dim3(tiles, chunks), dim3(256), 0, s, D, ldd, A, lda, M, N, K, m_chunk, k_tiles,
-                     out, m_dev);
+  const int chunks8 = (chunks + 7) & ~7;
+  hipLaunchKernelGGL(gemm_tn_kernel, dim3(tiles * chunks8), dim3(256), 0, s, D, ldd, A, lda, M, N, K, m_chunk, k_tiles,
+                     tiles, chunks, out, m_dev);
 }
 
 }  // namespace tgnn

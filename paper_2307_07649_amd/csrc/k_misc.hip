@@ -136,6 +136,16 @@ void sgd_update(const SgdSet* set_dev, int cnt, float lr, hipStream_t s) {
   hipLaunchKernelGGL(sgd_kernel, dim3(64, cnt), dim3(256), 0, s, set_dev, lr);
 }
 
+// plain streaming copy: the reference point for HBM-traffic counters (known bytes in, known bytes out)
+__global__ void copy_kernel(const float4* __restrict__ src, float4* __restrict__ dst, size_t n) {
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n; i += stride) dst[i] = src[i];
+}
+void copy_f4(const void* src, void* dst, size_t n_float4, hipStream_t s) {
+  hipLaunchKernelGGL(copy_kernel, dim3(8192), dim3(256), 0, s, static_cast<const float4*>(src),
+                     static_cast<float4*>(dst), n_float4);
+}
+
 __global__ void zero_set_kernel(SgdSet set) {
   const int t = blockIdx.y;
   float* p = set.p[t];

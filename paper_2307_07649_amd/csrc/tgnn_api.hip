@@ -668,6 +668,15 @@ int32_t tgnn_zero_params(tgnn_ctx* ctx, tgnn_params* g, void* stream) {
   return TGNN_OK;
 }
 
+int32_t tgnn_debug_copy(void* dst, const void* src, int64_t n_bytes, void* stream) {
+  REQ_PTR(dst); REQ_PTR(src);
+  if (n_bytes < 0 || n_bytes % 16 != 0) return set_error(TGNN_E_INVALID_ARG, "n_bytes must be a non-negative multiple of 16");
+  if (n_bytes == 0) return TGNN_OK;
+  copy_f4(src, dst, (size_t)n_bytes / 16, as_stream(stream));
+  TGNN_LAUNCH_CHECK();
+  return TGNN_OK;
+}
+
 int32_t tgnn_profile_enable(tgnn_ctx* ctx, uint32_t stage_mask) {
   if (ctx == nullptr) return set_error(TGNN_E_NULL_PTR, "ctx is NULL");
   ctx->prof.mask = stage_mask;

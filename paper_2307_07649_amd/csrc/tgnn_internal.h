@@ -149,6 +149,7 @@ struct SgdSet {
 };
 void sgd_update(const SgdSet* set_dev, int cnt, float lr, hipStream_t s);
 void zero_set(const SgdSet& set, hipStream_t s);
+void copy_f4(const void* src, void* dst, size_t n_float4, hipStream_t s);
 
 // ---- k_sample.hip -------------------------------------------------------------------
 // Roots of every batch (+ their slot ids) and the write-back arbitration marks of the positive endpoints.

@@ -64,6 +64,7 @@ _SIGS = {
     "tgnn_train_step": (_I, [_P, C.POINTER(tgnn_graph), C.POINTER(tgnn_state), C.POINTER(tgnn_params),
                              C.POINTER(tgnn_params), C.POINTER(tgnn_batch), _I, C.c_float, _P, _P, _P, _P]),
     "tgnn_debug_read": (_I, [_P, _I, _P, C.c_int64, _P]),
+    "tgnn_debug_copy": (_I, [_P, _P, C.c_int64, _P]),
     "tgnn_zero_params": (_I, [_P, C.POINTER(tgnn_params), _P]),
     "tgnn_profile_enable": (_I, [_P, C.c_uint32]),
     "tgnn_profile_read": (_I, [_P, _I, C.POINTER(_I), C.POINTER(C.c_double)]),
@@ -107,6 +108,12 @@ def build_tcsr(src, dst, ts, n_nodes):
     _check(_lib.tgnn_build_tcsr(src.ctypes.data, dst.ctypes.data, ts.ctypes.data, E, n_nodes, indptr.ctypes.data,
                                 nbr.ctypes.data, eid.ctypes.data, tso.ctypes.data))
     return indptr, nbr, eid, tso
+
+
+def tgnn_debug_copy(dst, src):
+    """dst[:] = src through the library's plain copy kernel (HBM-traffic counter calibration)."""
+    assert dst.numel() * dst.element_size() == src.numel() * src.element_size()
+    _check(_lib.tgnn_debug_copy(_ptr(dst), _ptr(src), src.numel() * src.element_size(), _stream()))
 
 
 class Graph:
