@@ -28,7 +28,7 @@ constexpr int NT_P = 32;
 __device__ __forceinline__ int nt_swz(int row, int chunk) { return row * NT_P + ((chunk ^ ((row >> 1) & 7)) << 2); }
 
 template <int TN>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 2))) void gemm_nt_kernel(const float* __restrict__ A, int lda,
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, (TN <= 5 ? 4 : 2)))) void gemm_nt_kernel(const float* __restrict__ A, int lda,
                                                       const float* __restrict__ B, int ldb,
                                                       const float* __restrict__ bias, float* __restrict__ C, int ldc,
                                                       int M, int N, int Kp, int n_store, int relu,
@@ -175,21 +175,20 @@ void gemm_nt(const float* A, int lda, const float* B, int ldb, const float* bias
              int Kp, int n_store, bool relu, hipStream_t s, const int* m_dev) {
   if (M <= 0 || N <= 0) return;
   if (n_store < N) n_store = N;
-  // Column-tile width in 16-wide MFMA blocks.  Measured on MI355X the throughput is flat between 2 and 10
-  // blocks, so the choice is about padding waste and about having enough workgroups to fill 256 CUs:
-  // small-M problems take narrow tiles (many short workgroups), large ones 4-5 blocks.
+  // Column-tile width in 16-wide MFMA blocks, from sweeps on MI355X: problems of a few thousand rows want the
+  // narrowest tiles (many short workgroups, all resident at once), tens of thousands of rows want 2 blocks,
+  // and only beyond that do wider tiles (less re-reading of A) pay off.
   const int nb = (n_store + 15) / 16;
-  const int row_tiles = (M + 63) / 64;
   int best = 1;
-  float best_cost = 1e30f;
-  static const int cand[] = {5, 4, 7, 2, 10, 1};
-  for (int c : cand) {
-    const int tiles = (nb + c - 1) / c;
-    const int wgs = tiles * row_tiles;
-    float cost = (float)(tiles * c) / nb;                 // padded / useful columns
-    if (wgs < 512) cost *= 1.0f + 0.5f * (512 - wgs) / 512.0f;   // too few workgroups for the chip
-    if (c == 1) cost *= 1.15f;
-    if (cost < best_cost - 1e-6f) { best_cost = cost; best = c; }
+  if (M > 4096 && M <= 65536) {
+    best = 2;
+  } else if (M > 65536) {
+    float best_cost = 1e30f;
+    static const int cand[] = {5, 4, 7, 2};
+    for (int c : cand) {
+      const float cost = (float)(((nb + c - 1) / c) * c) / nb;   // padded / useful columns
+      if (cost < best_cost - 1e-6f) { best_cost = cost; best = c; }
+    }
   }
   if (const char* e = getenv("TGNN_NT_TN")) best = atoi(e);
 #define TGNN_NT_CASE(TNV) \
