@@ -150,11 +150,12 @@ static void attn_forward(tgnn_ctx* ctx, const tgnn_params* p, int R, const int32
 
 // From ws.dz (already masked by the merge ReLU) down to ws.dMin / ws.dQsub / ws.dCsub, adding the
 // gradients of W_o, W_q, W_k, W_v, their biases and the time encoding.
+// Weight-gradient GEMMs are queued in `tn` (launched by the caller, later, as one grouped kernel).
 static void attn_backward(tgnn_ctx* ctx, tgnn_params* g, const tgnn_params* p, int R, const int32_t* cnt,
-                          bool finish_time_grad, hipStream_t s) {
+                          bool finish_time_grad, TnBatch& tn, hipStream_t s) {
   const Dims& d = ctx->d; Ws& w = ctx->w;
   const int RK = R * d.k;
-  gemm_tn_acc(w.dz, d.ldh, w.Min, d.ldm, R, d.dO, d.dO + d.dx, single_out(g->wo, d.dO + d.dx, g->bo), s);
+  tn.add(w.dz, d.ldh, w.Min, d.ldm, R, d.dO, d.dO + d.dx, single_out(g->wo, d.dO + d.dx, g->bo));
   gemm_nt(w.dz, d.ldh, w.WoT, d.ldh, nullptr, w.dMin, d.ldm, R, d.dO + d.dx, d.ldh, d.ldm, false, s);
   attn_core_bwd(d, R, w.q, d.ldh, w.KV, d.ldkv, cnt, w.prob, w.dMin, d.ldm, w.dq, w.dKV, s);
   OutMap kv;
@@ -162,9 +163,9 @@ static void attn_backward(tgnn_ctx* ctx, tgnn_params* g, const tgnn_params* p, i
   kv.p[0][0] = g->wk; kv.p[1][0] = g->wv; kv.ld[0][0] = kv.ld[1][0] = d.dkv;
   kv.n_split = d.dO; kv.k_split = 1 << 30;
   kv.bias[0] = g->bk; kv.bias[1] = g->bv;
-  gemm_tn_acc(w.dKV, d.ldkv, w.Cmat, d.ldc, RK, 2 * d.dO, d.dkv, kv, s);
+  tn.add(w.dKV, d.ldkv, w.Cmat, d.ldc, RK, 2 * d.dO, d.dkv, kv);
   gemm_nt(w.dKV, d.ldkv, w.WkvT_sub, d.ldkv, nullptr, w.dCsub, d.ldsub, RK, d.dm + d.dt, d.ldkv, d.ldsub, false, s);
-  gemm_tn_acc(w.dq, d.ldh, w.Qin, d.ldq, R, d.dO, d.dq, single_out(g->wq, d.dq, g->bq), s);
+  tn.add(w.dq, d.ldh, w.Qin, d.ldq, R, d.dO, d.dq, single_out(g->wq, d.dq, g->bq));
   gemm_nt(w.dq, d.ldh, w.WqT_sub, d.ldh, nullptr, w.dQsub, d.ldsub, R, d.dm + d.dt, d.ldh, d.ldsub, false, s);
   const size_t tgp = (size_t)TG_BLOCKS * 2 * d.dt;
   time_grad(w.dCsub, d.ldsub, d.dm, w.msinC, d.ldt, w.dtk, RK, d.dt, p->time_b, w.tg_partial, s);
@@ -449,7 +450,9 @@ int32_t tgnn_temporal_attn_bwd(tgnn_ctx* ctx, const tgnn_params* p, int32_t n_ro
   REQ_PTR(dz); REQ_PTR(d_x_root); REQ_PTR(d_x_nbr);
   hipStream_t s = as_stream(stream);
   mask_dz(n_roots, d.dO, dz, d.dO, w.z, d.ldh, w.dz, s);
-  attn_backward(ctx, grads, p, n_roots, w.cnt, true, s);
+  TnBatch tn;
+  attn_backward(ctx, grads, p, n_roots, w.cnt, true, tn, s);
+  tn.launch(s);
   attn_dx_out(n_roots, n_roots * d.k, d.dm, d.dO, w.dMin, d.ldm, w.dQsub, w.dCsub, d.ldsub, d_x_root, d_x_nbr, s);
   TGNN_LAUNCH_CHECK();
   return TGNN_OK;
@@ -617,22 +620,22 @@ int32_t tgnn_train_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
   memset(&dec, 0, sizeof(dec));
   dec.p[0][0] = grads->dec_ws; dec.p[0][1] = grads->dec_wd; dec.ld[0][0] = dec.ld[0][1] = d.dO;
   dec.n_split = 1 << 30; dec.k_split = d.dO; dec.bias[0] = grads->dec_b1;
-  gemm_tn_acc(w.dh1, d.ldh, w.Adec, d.ldkv, B2, d.dO, 2 * d.dO, dec, s);
+  TnBatch tn;   // every weight gradient of the step, launched as one kernel after the data gradients
+  tn.add(w.dh1, d.ldh, w.Adec, d.ldkv, B2, d.dO, 2 * d.dO, dec);
   gemm_nt(w.dh1, d.ldh, w.WdecT, d.ldh, nullptr, w.dAdec, d.ldkv, B2, 2 * d.dO, d.ldh, d.ldkv, false, s);
   decoder_dz(d, w.bs_dev, bs.total, w.dAdec, d.ldkv, w.z, d.ldh, w.dz, s);
   tm.end(13);
   tm.begin(14);
-  attn_backward(ctx, grads, p, R, w.cnt, false, s);
+  attn_backward(ctx, grads, p, R, w.cnt, false, tn, s);
   tm.end(14);
   tm.begin(15);
   seg_reduce(ctx, R, S, s);   // per-row sum of the gradients of the slots that share the row
   gru_gates_bwd(d, U, w.ucount, w.ds_row, w.gates, w.Hm, w.has, w.dgi, w.dgh, s);
   tm.end(15);
   tm.begin(16);
-  gemm_tn_acc(w.dgi, d.ld3, w.X, d.ldx, U, 3 * d.dm, d.d_in, single_out(grads->gru_wih, d.d_in, grads->gru_bih), s,
-              w.ucount);
-  gemm_tn_acc(w.dgh, d.ld3, w.Hm, d.ldh, U, 3 * d.dm, d.dm, single_out(grads->gru_whh, d.dm, grads->gru_bhh), s,
-              w.ucount);
+  tn.add(w.dgi, d.ld3, w.X, d.ldx, U, 3 * d.dm, d.d_in, single_out(grads->gru_wih, d.d_in, grads->gru_bih), w.ucount);
+  tn.add(w.dgh, d.ld3, w.Hm, d.ldh, U, 3 * d.dm, d.dm, single_out(grads->gru_whh, d.dm, grads->gru_bhh), w.ucount);
+  tn.launch(s);
   tm.end(16);
   tm.begin(17);
   gemm_nt(w.dgi, d.ld3, w.WihT_phi, d.ld3, nullptr, w.dphi_g, d.ldt, U, d.dt, d.ld3, d.ldt, false, s, w.ucount);

@@ -124,6 +124,28 @@ struct OutMap {
   int n_split, k_split;
   float* bias[2];
 };
+// One weight-gradient problem G[n, k] += sum_m D[m, n] * A[m, k] and a group of them for one launch.
+struct TnProblem {
+  const float* D;
+  const float* A;
+  const int* m_dev;
+  int ldd, lda, M, N, K;
+  int m_chunk, k_tiles, tiles, chunks, wg_begin;
+  OutMap out;
+};
+constexpr int TN_MAX_GROUP = 8;
+struct TnGroup {
+  TnProblem p[TN_MAX_GROUP];
+  int n;
+};
+struct TnBatch {
+  TnGroup g;
+  int total_wgs = 0;
+  TnBatch() { g.n = 0; }
+  void add(const float* D, int ldd, const float* A, int lda, int M, int N, int K, const OutMap& out,
+           const int* m_dev = nullptr);
+  void launch(hipStream_t s);   // one kernel for all added problems; empties the batch
+};
 // G[n, k] += sum_m D[m, n] * A[m, k]  (n < N, k < K), bias[n] += sum_m D[m, n]; float atomics.
 void gemm_tn_acc(const float* D, int ldd, const float* A, int lda, int M, int N, int K, const OutMap& out,
                  hipStream_t s, const int* m_dev = nullptr);
