@@ -155,6 +155,9 @@ def main():
         ctx.tgnn_train_step(graph, state, params, grads, bl, lr=args.lr, out_loss=loss)
         return sum(b.n for b in bl)
 
+    # a stream of its own: the library replays a captured HIP graph there (the NULL stream cannot be captured)
+    torch.cuda.synchronize()
+    torch.cuda.set_stream(torch.cuda.Stream())
     for s in range(args.warmup):
         run_step(s)
     torch.cuda.synchronize()

@@ -40,6 +40,17 @@ extern "C" {
 #define TGNN_E_HIP (-8)
 
 #define TGNN_FLAG_OVERWRITE_GRADS 1 /* tgnn_train_step clears `grads` first instead of adding to them */
+#define TGNN_FLAG_NO_GRAPH 4        /* tgnn_train_step enqueues its ~40 launches one by one; by default it records
+                                       them once per call signature (same pointers, batch sizes, lr, stream) into a
+                                       HIP graph and replays that with one launch, updating only the batch
+                                       descriptors.  Not used on the NULL (legacy default) stream, while the caller's stream is itself being captured
+                                       or while stage timing is enabled. */
+#define TGNN_FLAG_SIDE_STREAM 2     /* tgnn_train_step moves work that is off the critical path (weight gradients,
+                                       write-back, slot sorting, the query projection) to a second stream of the
+                                       context, forked from and joined back into the caller's stream with events
+                                       inside the call.  Off by default: on MI355X the step is then bound by the host's
+                                       launch rate (measured), and captured graphs with parallel branches replay
+                                       slower than a linear one. */
 
 #define TGNN_MAX_K 32        /* neighbours per root */
 #define TGNN_MAX_BATCHES 16  /* mini-batches (memory replicas) per tgnn_train_step call */

@@ -5,20 +5,6 @@
 
 namespace tgnn {
 
-constexpr int MAX_PACK = 24;
-struct PrologueArgs {
-  PackDesc d[MAX_PACK];
-  int n_pack;
-  SgdSet zero;          // tensors to clear (cnt = 0: none)
-  BatchSet bs;          // copied to *bs_dev when bs_dev != NULL
-  BatchSet* bs_dev;
-  SgdSet sgd;           // copied to *sgd_dev when sgd_dev != NULL
-  SgdSet* sgd_dev;
-  float* loss;
-  unsigned long long* epoch;
-  int32_t* ucount;
-};
-
 __global__ void prologue_kernel(PrologueArgs a) {
   const int y = blockIdx.y;
   if (y < a.n_pack) {
@@ -53,12 +39,11 @@ __global__ void prologue_kernel(PrologueArgs a) {
 
 // Padded copies of the weights (row pitch = the pitch of the activation matrix they multiply) and the
 // transposed copies / column subsets that the data-gradient GEMMs read.
-void prologue(tgnn_ctx* ctx, const tgnn_params* p, const BatchSet* bs, const SgdSet* sgd, const SgdSet* zero,
-              float* loss, hipStream_t s) {
+void prologue_fill(tgnn_ctx* ctx, const tgnn_params* p, const BatchSet* bs, const SgdSet* sgd, const SgdSet* zero,
+                   float* loss, PrologueArgs& pa) {
   const Dims& d = ctx->d;
   Ws& w = ctx->w;
   static_assert(sizeof(PrologueArgs) <= 4096, "kernel argument block too large");
-  PrologueArgs pa;
   memset(&pa, 0, sizeof(pa));
   int n = 0;
   auto add = [&](const float* src, float* dst, int rows, int cols, int zero_to, int ldd, int srs, int scs) {
@@ -98,7 +83,16 @@ void prologue(tgnn_ctx* ctx, const tgnn_params* p, const BatchSet* bs, const Sgd
   pa.loss = loss;
   pa.epoch = w.epoch;
   pa.ucount = w.ucount;
-  hipLaunchKernelGGL(prologue_kernel, dim3(32, n + pa.zero.cnt + 1), dim3(256), 0, s, pa);
+}
+
+dim3 prologue_grid(const PrologueArgs& pa) { return dim3(32, pa.n_pack + pa.zero.cnt + 1); }
+void* prologue_func() { return reinterpret_cast<void*>(prologue_kernel); }
+
+void prologue(tgnn_ctx* ctx, const tgnn_params* p, const BatchSet* bs, const SgdSet* sgd, const SgdSet* zero,
+              float* loss, hipStream_t s) {
+  PrologueArgs pa;
+  prologue_fill(ctx, p, bs, sgd, zero, loss, pa);
+  hipLaunchKernelGGL(prologue_kernel, prologue_grid(pa), dim3(256), 0, s, pa);
 }
 
 __global__ void fill_state_kernel(float* mem, double* mem_ts, float* mail, double* mail_ts, int32_t* mail_eid,

@@ -5,59 +5,53 @@
 
 namespace tgnn {
 
-__global__ void roots_kernel(const BatchSet* __restrict__ bsp, int N, int32_t* root_node, int32_t* root_gid,
-                             int32_t* root_batch, double* root_t, int32_t* slot_gid, int32_t* slot_node,
-                             unsigned long long* winkey, const unsigned long long* __restrict__ epoch,
-                             unsigned long long* utag, int32_t* uidx, int32_t* ucount, int32_t* ulist, int32_t* ucnt) {
-  const BatchSet& bs = *bsp;
-  const int e = blockIdx.x * blockDim.x + threadIdx.x;
-  if (e >= bs.total) return;
-  int b = 0;
-  while (b + 1 < bs.nb && e >= bs.b[b + 1].ev_off) ++b;
-  const BatchDesc bd = bs.b[b];
-  const int i = e - bd.ev_off;
-  const double t = bd.t[i];
-  const int nodes[3] = {bd.src[i], bd.dst[i], bd.neg[i]};
-  const unsigned long long ep = *epoch;
-#pragma unroll
-  for (int role = 0; role < 3; ++role) {
-    const int r = 3 * bd.ev_off + role * bd.n + i;
-    const int gid = bd.replica * N + nodes[role];
-    root_node[r] = nodes[role];
-    root_gid[r] = gid;
-    root_batch[r] = b;
-    root_t[r] = t;
-    slot_gid[r] = gid;
-    slot_node[r] = nodes[role];
-    if (role < 2) atomicMax(winkey + gid, wb_key(ep, e, role));   // last-event-wins arbitration
-    uniq_claim(utag, uidx, ucount, ulist, ucnt, gid, ep);
-  }
-}
-
-void build_roots(tgnn_ctx* ctx, int total, hipStream_t s) {
-  Ws& w = ctx->w;
-  hipLaunchKernelGGL(roots_kernel, dim3((total + 255) / 256), dim3(256), 0, s, w.bs_dev, ctx->d.N, w.root_node,
-                     w.root_gid, w.root_batch, w.root_t, w.slot_gid, w.slot_node, w.winkey, w.epoch, w.utag, w.uidx,
-                     w.ucount, w.ulist, w.ucnt);
-}
-
-// gid = replica * N + node for roots of the fused step (root_gid given), plain node ids otherwise.
+// FUSED: the query of wave r is root r of the step's batches ([src | dst | neg] per batch); the wave also
+// records the root (node, time, slot ids), marks the write-back arbitration word of a positive endpoint
+// (last-event-wins: largest key survives) and claims rows for the root and its neighbours.
+// Otherwise the queries are the caller's (node, t) arrays.
+template <bool FUSED>
 __global__ __launch_bounds__(256) void sample_kernel(const int64_t* __restrict__ indptr,
                                                      const int32_t* __restrict__ g_nbr,
                                                      const int32_t* __restrict__ g_eid,
                                                      const double* __restrict__ g_ts, int N,
                                                      const int32_t* __restrict__ q_node,
-                                                     const double* __restrict__ q_t,
-                                                     const int32_t* __restrict__ root_gid, int n_roots, int k,
+                                                     const double* __restrict__ q_t, int n_roots, int k,
                                                      int32_t* __restrict__ out_nbr, int32_t* __restrict__ out_eid,
                                                      double* __restrict__ out_ts, int32_t* __restrict__ out_cnt,
-                                                     int32_t* __restrict__ slot_gid, int32_t* __restrict__ slot_node,
+                                                     const BatchSet* __restrict__ bsp, int32_t* __restrict__ root_node,
+                                                     double* __restrict__ root_t, int32_t* __restrict__ slot_gid,
+                                                     int32_t* __restrict__ slot_node, unsigned long long* winkey,
                                                      UniqPtrs uq) {
   const int lane = threadIdx.x & 63;
   const int r = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
   if (r >= n_roots) return;  // whole wave leaves together
-  const int node = q_node[r];
-  const double t = q_t[r];
+  int node, rep_base = 0;
+  double t;
+  unsigned long long ep = 0ull;
+  if (FUSED) {
+    const BatchSet& bs = *bsp;
+    int b = 0;
+    while (b + 1 < bs.nb && r >= 3 * bs.b[b + 1].ev_off) ++b;
+    const BatchDesc bd = bs.b[b];
+    const int local = r - 3 * bd.ev_off;
+    const int role = local / bd.n, i = local - role * bd.n;
+    node = (role == 0 ? bd.src : role == 1 ? bd.dst : bd.neg)[i];
+    t = bd.t[i];
+    rep_base = bd.replica * N;
+    ep = *uq.epoch;
+    if (lane == 0) {
+      const int gid = rep_base + node;
+      root_node[r] = node;
+      root_t[r] = t;
+      slot_gid[r] = gid;
+      slot_node[r] = node;
+      if (role < 2) atomicMax(winkey + gid, wb_key(ep, bd.ev_off + i, role));
+      uniq_claim(uq.utag, uq.uidx, uq.ucount, uq.ulist, uq.ucnt, gid, ep);
+    }
+  } else {
+    node = q_node[r];
+    t = q_t[r];
+  }
   long long base = 0, lo = 0, hi = 0;
   if (node >= 0 && node < N) {
     base = indptr[node];
@@ -97,24 +91,31 @@ __global__ __launch_bounds__(256) void sample_kernel(const int64_t* __restrict__
     out_nbr[o] = nb;
     out_eid[o] = ei;
     out_ts[o] = ts;
-    if (slot_gid != nullptr) {
-      const int rep_base = root_gid[r] - node;
+    if (FUSED) {
       slot_gid[(size_t)n_roots + o] = nb >= 0 ? rep_base + nb : -1;
       slot_node[(size_t)n_roots + o] = nb;
-      if (nb >= 0 && uq.utag != nullptr)
-        uniq_claim(uq.utag, uq.uidx, uq.ucount, uq.ulist, uq.ucnt, rep_base + nb, *uq.epoch);
+      if (nb >= 0) uniq_claim(uq.utag, uq.uidx, uq.ucount, uq.ulist, uq.ucnt, rep_base + nb, ep);
     }
   }
 }
 
-void sample_recent(const Dims& d, const tgnn_graph* g, const int32_t* node, const double* t, const int32_t* root_gid,
-                   int n_roots, int32_t* out_nbr, int32_t* out_eid, double* out_ts, int32_t* out_cnt,
-                   int32_t* slot_gid, int32_t* slot_node, const UniqPtrs* uq, hipStream_t s) {
+void sample_roots(tgnn_ctx* ctx, const tgnn_graph* g, int n_roots, hipStream_t s) {
   if (n_roots <= 0) return;
-  UniqPtrs u{};
-  if (uq) u = *uq;
-  hipLaunchKernelGGL(sample_kernel, dim3((n_roots + 3) / 4), dim3(256), 0, s, g->indptr, g->nbr, g->eid, g->ts, d.N,
-                     node, t, root_gid, n_roots, d.k, out_nbr, out_eid, out_ts, out_cnt, slot_gid, slot_node, u);
+  const Dims& d = ctx->d;
+  Ws& w = ctx->w;
+  UniqPtrs uq{w.utag, w.epoch, w.uidx, w.ucount, w.ulist, w.ucnt};
+  hipLaunchKernelGGL(sample_kernel<true>, dim3((n_roots + 3) / 4), dim3(256), 0, s, g->indptr, g->nbr, g->eid, g->ts, d.N,
+                     nullptr, nullptr, n_roots, d.k, w.nbr, w.neid, w.nts, w.cnt, w.bs_dev, w.root_node, w.root_t,
+                     w.slot_gid, w.slot_node, w.winkey, uq);
+}
+
+void sample_recent(const Dims& d, const tgnn_graph* g, const int32_t* node, const double* t, int n_roots,
+                   int32_t* out_nbr, int32_t* out_eid, double* out_ts, int32_t* out_cnt, hipStream_t s) {
+  if (n_roots <= 0) return;
+  UniqPtrs uq{};
+  hipLaunchKernelGGL(sample_kernel<false>, dim3((n_roots + 3) / 4), dim3(256), 0, s, g->indptr, g->nbr, g->eid, g->ts, d.N,
+                     node, t, n_roots, d.k, out_nbr, out_eid, out_ts, out_cnt, nullptr, nullptr, nullptr, nullptr, nullptr,
+                     nullptr, uq);
 }
 
 }  // namespace tgnn

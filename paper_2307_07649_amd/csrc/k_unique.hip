@@ -88,9 +88,13 @@ __global__ void uniq_fill_kernel(int S, const int32_t* __restrict__ slot_row, in
   if (row >= 0) sorted[pos] = s;
 }
 
-void uniq_finalize(tgnn_ctx* ctx, int S, hipStream_t s) {
+void uniq_map(tgnn_ctx* ctx, int S, hipStream_t s) {
   Ws& w = ctx->w;
   hipLaunchKernelGGL(uniq_map_kernel, dim3((S + 255) / 256), dim3(256), 0, s, S, w.slot_gid, w.uidx, w.slot_row, w.ucnt);
+}
+
+void uniq_sort(tgnn_ctx* ctx, int S, hipStream_t s) {
+  Ws& w = ctx->w;
   hipLaunchKernelGGL(uniq_scan_kernel, dim3(1), dim3(1024), 0, s, w.ucount, w.ucnt, w.rowptr, w.cursor);
   hipLaunchKernelGGL(uniq_fill_kernel, dim3((S + 255) / 256), dim3(256), 0, s, S, w.slot_row, w.cursor, w.sorted);
 }

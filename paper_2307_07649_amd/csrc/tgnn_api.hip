@@ -83,7 +83,7 @@ struct Bump {
 
 static void layout(const Dims& d, Ws& w, Bump& b) {
   const size_t R = d.maxR, RK = d.maxRK, S = d.maxS, B2 = 2 * (size_t)d.maxEv;
-  w.root_node = b.take<int32_t>(R); w.root_gid = b.take<int32_t>(R); w.root_batch = b.take<int32_t>(R);
+  w.root_node = b.take<int32_t>(R);
   w.root_t = b.take<double>(R);
   w.nbr = b.take<int32_t>(RK); w.neid = b.take<int32_t>(RK); w.cnt = b.take<int32_t>(R); w.nts = b.take<double>(RK);
   w.slot_gid = b.take<int32_t>(S); w.slot_node = b.take<int32_t>(S); w.has = b.take<int32_t>(S);
@@ -130,6 +130,33 @@ static OutMap single_out(float* g, int ld, float* bias) {
   return o;
 }
 
+// Fork/join between the caller's stream and the context's side stream.
+struct Side {
+  tgnn_ctx* c;
+  hipStream_t main;
+  bool on;
+  hipStream_t stream() const { return on ? c->side : main; }
+  hipEvent_t next() { hipEvent_t e = c->fork_ev[c->next_ev]; c->next_ev = (c->next_ev + 1) & 15; return e; }
+  void fork() {   // side continues after everything queued on main so far
+    if (!on) return;
+    hipEvent_t e = next();
+    (void)hipEventRecord(e, main);
+    (void)hipStreamWaitEvent(c->side, e, 0);
+  }
+  void join() {   // main continues after everything queued on side so far
+    if (!on) return;
+    hipEvent_t e = next();
+    (void)hipEventRecord(e, c->side);
+    (void)hipStreamWaitEvent(main, e, 0);
+  }
+  // weight-gradient problems queued so far: start them now on the side stream, or keep them queued
+  void flush(TnBatch& tn) {
+    if (!on) return;
+    fork();
+    tn.launch(c->side);
+  }
+};
+
 // UPDT on n rows already staged in ws.X / ws.Hm / ws.has: projections (MFMA) + gates.
 static void gru_forward(tgnn_ctx* ctx, const tgnn_params* p, int n, hipStream_t s) {
   const Dims& d = ctx->d; Ws& w = ctx->w;
@@ -152,10 +179,11 @@ static void attn_forward(tgnn_ctx* ctx, const tgnn_params* p, int R, const int32
 // gradients of W_o, W_q, W_k, W_v, their biases and the time encoding.
 // Weight-gradient GEMMs are queued in `tn` (launched by the caller, later, as one grouped kernel).
 static void attn_backward(tgnn_ctx* ctx, tgnn_params* g, const tgnn_params* p, int R, const int32_t* cnt,
-                          bool finish_time_grad, TnBatch& tn, hipStream_t s) {
+                          bool finish_time_grad, TnBatch& tn, Side& side, hipStream_t s) {
   const Dims& d = ctx->d; Ws& w = ctx->w;
   const int RK = R * d.k;
   tn.add(w.dz, d.ldh, w.Min, d.ldm, R, d.dO, d.dO + d.dx, single_out(g->wo, d.dO + d.dx, g->bo));
+  side.flush(tn);
   gemm_nt(w.dz, d.ldh, w.WoT, d.ldh, nullptr, w.dMin, d.ldm, R, d.dO + d.dx, d.ldh, d.ldm, false, s);
   attn_core_bwd(d, R, w.q, d.ldh, w.KV, d.ldkv, cnt, w.prob, w.dMin, d.ldm, w.dq, w.dKV, s);
   OutMap kv;
@@ -166,6 +194,7 @@ static void attn_backward(tgnn_ctx* ctx, tgnn_params* g, const tgnn_params* p, i
   tn.add(w.dKV, d.ldkv, w.Cmat, d.ldc, RK, 2 * d.dO, d.dkv, kv);
   gemm_nt(w.dKV, d.ldkv, w.WkvT_sub, d.ldkv, nullptr, w.dCsub, d.ldsub, RK, d.dm + d.dt, d.ldkv, d.ldsub, false, s);
   tn.add(w.dq, d.ldh, w.Qin, d.ldq, R, d.dO, d.dq, single_out(g->wq, d.dq, g->bq));
+  side.flush(tn);
   gemm_nt(w.dq, d.ldh, w.WqT_sub, d.ldh, nullptr, w.dQsub, d.ldsub, R, d.dm + d.dt, d.ldh, d.ldsub, false, s);
   const size_t tgp = (size_t)TG_BLOCKS * 2 * d.dt;
   time_grad(w.dCsub, d.ldsub, d.dm, w.msinC, d.ldt, w.dtk, RK, d.dt, p->time_b, w.tg_partial, s);
@@ -180,6 +209,8 @@ struct StageTimer {
   tgnn_ctx* c;
   hipStream_t s;
   bool on(int st) const { return (c->prof.mask >> st) & 1u && c->prof.count[st] < PROF_RING; }
+  void begin(int st, hipStream_t on_stream) { hipStream_t keep = s; s = on_stream; begin(st); s = keep; }
+  void end(int st, hipStream_t on_stream) { hipStream_t keep = s; s = on_stream; end(st); s = keep; }
   void begin(int st) {
     if (!on(st)) return;
     Profiler& pr = c->prof;
@@ -213,6 +244,10 @@ static void fill_param_set(const Dims& d, const tgnn_params* p, const tgnn_param
 }  // namespace tgnn
 
 using namespace tgnn;
+
+static int enqueue_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, const tgnn_params* p, tgnn_params* grads,
+                        const BatchSet& bs, float lr, float* out_loss, float* out_logits, int32_t* out_winner,
+                        hipStream_t s);
 
 extern "C" {
 
@@ -278,6 +313,13 @@ int32_t tgnn_create(const tgnn_config* cfg, tgnn_ctx** out) {
   Bump place{static_cast<char*>(ctx->arena)};
   layout(d, ctx->w, place);
   ctx->last_attn_roots = -1;
+  e = hipStreamCreateWithFlags(&ctx->side, hipStreamNonBlocking);
+  for (int i = 0; i < 16 && e == hipSuccess; ++i) e = hipEventCreateWithFlags(&ctx->fork_ev[i], hipEventDisableTiming);
+  if (e != hipSuccess) {
+    (void)hipFree(ctx->arena);
+    delete ctx;
+    return set_error(TGNN_E_HIP, "stream/event creation failed: %s", hipGetErrorString(e));
+  }
   *out = ctx;
   return TGNN_OK;
 }
@@ -286,6 +328,11 @@ int32_t tgnn_destroy(tgnn_ctx* ctx) {
   if (ctx == nullptr) return TGNN_OK;
   hipError_t e = hipDeviceSynchronize();
   hipError_t e2 = hipFree(ctx->arena);
+  for (StepGraph& sg : ctx->graphs)
+    if (sg.used) { (void)hipGraphExecDestroy(sg.exec); (void)hipGraphDestroy(sg.graph); }
+  for (int i = 0; i < 16; ++i)
+    if (ctx->fork_ev[i]) (void)hipEventDestroy(ctx->fork_ev[i]);
+  if (ctx->side) (void)hipStreamDestroy(ctx->side);
   for (int st = 0; st < TGNN_N_STAGES; ++st)
     for (int k2 = 0; k2 < 2; ++k2)
       if (ctx->prof.ev[st][k2]) {
@@ -341,8 +388,7 @@ int32_t tgnn_sample_recent(tgnn_ctx* ctx, const tgnn_graph* g, const int32_t* no
   if (n_roots < 0) return set_error(TGNN_E_INVALID_ARG, "n_roots < 0");
   if (n_roots == 0) return TGNN_OK;
   REQ_PTR(node); REQ_PTR(t); REQ_PTR(out_nbr); REQ_PTR(out_eid); REQ_PTR(out_ts); REQ_PTR(out_cnt);
-  sample_recent(ctx->d, g, node, t, nullptr, n_roots, out_nbr, out_eid, out_ts, out_cnt, nullptr, nullptr, nullptr,
-                as_stream(stream));
+  sample_recent(ctx->d, g, node, t, n_roots, out_nbr, out_eid, out_ts, out_cnt, as_stream(stream));
   TGNN_LAUNCH_CHECK();
   return TGNN_OK;
 }
@@ -451,7 +497,8 @@ int32_t tgnn_temporal_attn_bwd(tgnn_ctx* ctx, const tgnn_params* p, int32_t n_ro
   hipStream_t s = as_stream(stream);
   mask_dz(n_roots, d.dO, dz, d.dO, w.z, d.ldh, w.dz, s);
   TnBatch tn;
-  attn_backward(ctx, grads, p, n_roots, w.cnt, true, tn, s);
+  Side side{ctx, s, false};
+  attn_backward(ctx, grads, p, n_roots, w.cnt, true, tn, side, s);
   tn.launch(s);
   attn_dx_out(n_roots, n_roots * d.k, d.dm, d.dO, w.dMin, d.ldm, w.dQsub, w.dCsub, d.ldsub, d_x_root, d_x_nbr, s);
   TGNN_LAUNCH_CHECK();
@@ -528,16 +575,105 @@ int32_t tgnn_train_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
     if (bs.b[b].n > 0) REQ_PTR(bs.b[b].neg);
   REQ_PTR(out_loss); OPT_PTR(out_logits); OPT_PTR(out_winner);
   if (!(lr == lr)) return set_error(TGNN_E_INVALID_ARG, "lr is NaN");
-  const Dims& d = ctx->d; Ws& w = ctx->w;
   hipStream_t s = as_stream(stream);
   if (bs.total == 0) {
     zero_f32(out_loss, 1, s);
     TGNN_LAUNCH_CHECK();
     return TGNN_OK;
   }
+  ctx->last_attn_roots = -1;
+
+  // the legacy default stream (NULL) cannot be captured
+  bool use_graph = (ctx->cfg.flags & TGNN_FLAG_NO_GRAPH) == 0 && ctx->prof.mask == 0 && s != nullptr;
+  if (use_graph) {
+    hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(s, &cs) != hipSuccess || cs != hipStreamCaptureStatusNone) use_graph = false;
+  }
+  if (!use_graph) return enqueue_step(ctx, g, st, p, grads, bs, lr, out_loss, out_logits, out_winner, s);
+
+  // look the call signature up among the captured steps
+  StepKey key;
+  memset(&key, 0, sizeof(key));
+  {
+    int q = 0;
+    key.ptr[q++] = g->indptr; key.ptr[q++] = g->nbr; key.ptr[q++] = g->eid; key.ptr[q++] = g->ts; key.ptr[q++] = g->efeat;
+    key.ptr[q++] = st->mem; key.ptr[q++] = st->mem_ts; key.ptr[q++] = st->mail; key.ptr[q++] = st->mail_ts;
+    key.ptr[q++] = st->mail_eid; key.ptr[q++] = st->stat;
+    const float* const* pp = reinterpret_cast<const float* const*>(p);
+    const float* const* gg = reinterpret_cast<const float* const*>(grads);
+    for (int i = 0; i < 19; ++i) { key.ptr[q++] = pp[i]; key.ptr[q++] = gg[i]; }
+    key.ptr[q++] = out_loss; key.ptr[q++] = out_logits; key.ptr[q++] = out_winner; key.ptr[q++] = s;
+    for (int b = 0; b < bs.nb; ++b) { key.n[b] = bs.b[b].n; key.rep[b] = bs.b[b].replica; }
+    key.nb = bs.nb; key.lr = lr;
+  }
+  StepGraph* hit = nullptr;
+  StepGraph* victim = &ctx->graphs[0];
+  for (StepGraph& sg : ctx->graphs) {
+    if (sg.used && memcmp(&sg.key, &key, sizeof(key)) == 0) { hit = &sg; break; }
+    if (!sg.used || (victim->used && sg.last_use < victim->last_use)) victim = &sg;
+  }
+  const Dims& d = ctx->d;
+  if (hit == nullptr) {
+    if (victim->used) {
+      (void)hipGraphExecDestroy(victim->exec);
+      (void)hipGraphDestroy(victim->graph);
+      victim->used = false;
+    }
+    TGNN_HIP_CHECK(hipStreamBeginCapture(s, hipStreamCaptureModeThreadLocal));
+    const int rc = enqueue_step(ctx, g, st, p, grads, bs, lr, out_loss, out_logits, out_winner, s);
+    hipGraph_t graph = nullptr;
+    const hipError_t ce = hipStreamEndCapture(s, &graph);
+    if (rc != TGNN_OK) { if (graph) (void)hipGraphDestroy(graph); return rc; }
+    if (ce != hipSuccess) return set_error(TGNN_E_HIP, "hipStreamEndCapture failed: %s", hipGetErrorString(ce));
+    hipGraphNode_t roots[4];
+    size_t n_roots = 4;
+    hipError_t e = hipGraphGetRootNodes(graph, roots, &n_roots);
+    hipGraphNodeType ty = hipGraphNodeTypeEmpty;
+    if (e == hipSuccess && n_roots == 1) e = hipGraphNodeGetType(roots[0], &ty);
+    if (e != hipSuccess || n_roots != 1 || ty != hipGraphNodeTypeKernel) {
+      (void)hipGraphDestroy(graph);
+      return set_error(TGNN_E_HIP, "captured step has an unexpected shape (%zu root nodes)", n_roots);
+    }
+    hipGraphExec_t exec = nullptr;
+    e = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
+    if (e != hipSuccess) {
+      (void)hipGraphDestroy(graph);
+      return set_error(TGNN_E_HIP, "hipGraphInstantiate failed: %s", hipGetErrorString(e));
+    }
+    victim->used = true; victim->key = key; victim->graph = graph; victim->exec = exec; victim->prologue_node = roots[0];
+    hit = victim;
+  } else {
+    // same launches as the recorded step; only the prologue's argument block (batch descriptors) is new
+    SgdSet sgd_set, zero_set_;
+    fill_param_set(d, p, grads, 2, sgd_set);
+    fill_param_set(d, grads, nullptr, 0, zero_set_);
+    const bool overwrite = (ctx->cfg.flags & TGNN_FLAG_OVERWRITE_GRADS) != 0;
+    PrologueArgs pa;
+    prologue_fill(ctx, p, &bs, lr != 0.0f ? &sgd_set : nullptr, overwrite ? &zero_set_ : nullptr, out_loss, pa);
+    void* kargs[1] = {&pa};
+    hipKernelNodeParams np;
+    memset(&np, 0, sizeof(np));
+    np.func = prologue_func();
+    np.gridDim = prologue_grid(pa);
+    np.blockDim = dim3(256);
+    np.kernelParams = kargs;
+    TGNN_HIP_CHECK(hipGraphExecKernelNodeSetParams(hit->exec, hit->prologue_node, &np));
+  }
+  hit->last_use = ++ctx->graph_clock;
+  TGNN_HIP_CHECK(hipGraphLaunch(hit->exec, s));
+  return TGNN_OK;
+}
+
+// Enqueues every launch of one training step on `s` (and the context's side stream).
+static int enqueue_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, const tgnn_params* p, tgnn_params* grads,
+                        const BatchSet& bs, float lr, float* out_loss, float* out_logits, int32_t* out_winner,
+                        hipStream_t s) {
+  const Dims& d = ctx->d; Ws& w = ctx->w;
   const int R = 3 * bs.total, RK = R * d.k, S = R + RK, B2 = 2 * bs.total;
 
   StageTimer tm{ctx, s};
+  Side side{ctx, s, (ctx->cfg.flags & TGNN_FLAG_SIDE_STREAM) != 0};
+  hipStream_t s2 = side.stream();
   SgdSet sgd_set, zero_set_;
   fill_param_set(d, p, grads, 2, sgd_set);  // time_w, time_b stay frozen
   fill_param_set(d, grads, nullptr, 0, zero_set_);
@@ -545,14 +681,14 @@ int32_t tgnn_train_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
   tm.begin(0);
   prologue(ctx, p, &bs, lr != 0.0f ? &sgd_set : nullptr, overwrite ? &zero_set_ : nullptr, out_loss, s);
   tm.end(0);
-  tm.begin(1);
-  build_roots(ctx, bs.total, s);
-  tm.end(1);
   tm.begin(2);
-  UniqPtrs uq{w.utag, w.epoch, w.uidx, w.ucount, w.ulist, w.ucnt};
-  sample_recent(d, g, w.root_node, w.root_t, w.root_gid, R, w.nbr, w.neid, w.nts, w.cnt, w.slot_gid, w.slot_node, &uq, s);
-  uniq_finalize(ctx, S, s);
+  sample_roots(ctx, g, R, s);
+  uniq_map(ctx, S, s);
   tm.end(2);
+  side.fork();
+  tm.begin(1, s2);
+  uniq_sort(ctx, S, s2);   // only the backward pass needs the row-sorted slot list
+  tm.end(1, s2);
 
   // UPDT once per distinct (replica, node) among the root and supporting nodes, from the pre-batch state
   const int U = S < d.maxU ? S : d.maxU;   // launch bound; the actual row count is *w.ucount on the device
@@ -581,6 +717,14 @@ int32_t tgnn_train_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
   gru_gates_fwd(d, U, w.ucount, w.gi, w.gh, w.Hm, w.has, w.gates, w.s_new, w.ds_row, s);
   tm.end(6);
 
+  // Last-event-wins write-back: needs s' and tau only, and every read of the stored state (the gather) is
+  // already queued before it, so it can run beside the rest of the step.
+  side.fork();
+  tm.begin(19, s2);
+  writeback_scatter(d, w.bs_dev, bs.total, st, w.winkey, w.epoch, w.s_new, d.ldh, w.tau, w.slot_row, nullptr, nullptr,
+                    nullptr, nullptr, out_winner, s2);
+  tm.end(19, s2);
+
   // attention + merge
   AttnAssembleArgs aa;
   memset(&aa, 0, sizeof(aa));
@@ -594,12 +738,14 @@ int32_t tgnn_train_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
   tm.begin(7);
   attn_assemble(aa, s);
   tm.end(7);
+  side.fork();
+  tm.begin(9, s2);
+  gemm_nt(w.Qin, d.ldq, w.Wq_p, d.ldq, p->bq, w.q, d.ldh, R, d.dO, d.ldq, d.ldh, false, s2);
+  tm.end(9, s2);
   tm.begin(8);
   gemm_nt(w.Cmat, d.ldc, w.Wkv_p, d.ldc, w.bkv_p, w.KV, d.ldkv, RK, 2 * d.dO, d.ldc, d.ldkv, false, s);
   tm.end(8);
-  tm.begin(9);
-  gemm_nt(w.Qin, d.ldq, w.Wq_p, d.ldq, p->bq, w.q, d.ldh, R, d.dO, d.ldq, d.ldh, false, s);
-  tm.end(9);
+  side.join();   // q (and, in passing, the write-back and the slot sort)
   tm.begin(10);
   attn_core_fwd(d, R, w.q, d.ldh, w.KV, d.ldkv, w.cnt, w.prob, w.Min, d.ldm, s);
   tm.end(10);
@@ -614,50 +760,57 @@ int32_t tgnn_train_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
   decoder_loss(d, w.bs_dev, bs.total, w.h1, d.ldh, p->dec_w2, p->dec_b2, w.logits, out_loss, w.dh1, grads->dec_w2, grads->dec_b2, s);
   tm.end(12);
 
-  // backward
+  // Backward.  The data-gradient chain stays on the caller's stream; each weight-gradient GEMM is started on
+  // the side stream as soon as its two operands exist (single-stream mode: all of them in one launch at the end).
   tm.begin(13);
   OutMap dec;
   memset(&dec, 0, sizeof(dec));
   dec.p[0][0] = grads->dec_ws; dec.p[0][1] = grads->dec_wd; dec.ld[0][0] = dec.ld[0][1] = d.dO;
   dec.n_split = 1 << 30; dec.k_split = d.dO; dec.bias[0] = grads->dec_b1;
-  TnBatch tn;   // every weight gradient of the step, launched as one kernel after the data gradients
+  TnBatch tn;
   tn.add(w.dh1, d.ldh, w.Adec, d.ldkv, B2, d.dO, 2 * d.dO, dec);
+  side.flush(tn);
   gemm_nt(w.dh1, d.ldh, w.WdecT, d.ldh, nullptr, w.dAdec, d.ldkv, B2, 2 * d.dO, d.ldh, d.ldkv, false, s);
   decoder_dz(d, w.bs_dev, bs.total, w.dAdec, d.ldkv, w.z, d.ldh, w.dz, s);
   tm.end(13);
   tm.begin(14);
-  attn_backward(ctx, grads, p, R, w.cnt, false, tn, s);
+  attn_backward(ctx, grads, p, R, w.cnt, false, tn, side, s);
   tm.end(14);
   tm.begin(15);
   seg_reduce(ctx, R, S, s);   // per-row sum of the gradients of the slots that share the row
   gru_gates_bwd(d, U, w.ucount, w.ds_row, w.gates, w.Hm, w.has, w.dgi, w.dgh, s);
   tm.end(15);
-  tm.begin(16);
   tn.add(w.dgi, d.ld3, w.X, d.ldx, U, 3 * d.dm, d.d_in, single_out(grads->gru_wih, d.d_in, grads->gru_bih), w.ucount);
   tn.add(w.dgh, d.ld3, w.Hm, d.ldh, U, 3 * d.dm, d.dm, single_out(grads->gru_whh, d.dm, grads->gru_bhh), w.ucount);
-  tn.launch(s);
-  tm.end(16);
+  if (side.on) {
+    side.flush(tn);
+  } else {
+    tm.begin(16);
+    tn.launch(s);
+    tm.end(16);
+  }
   tm.begin(17);
   gemm_nt(w.dgi, d.ld3, w.WihT_phi, d.ld3, nullptr, w.dphi_g, d.ldt, U, d.dt, d.ld3, d.ldt, false, s, w.ucount);
   time_grad(w.dphi_g, d.ldt, 0, w.msinX, d.ldt, w.delta, U, d.dt, p->time_b,
             w.tg_partial + (size_t)2 * TG_BLOCKS * 2 * d.dt, s, w.ucount);
   time_grad_finish(w.tg_partial, 3, d.dt, grads->time_w, grads->time_b, s);
   tm.end(17);
+  side.join();   // all weight gradients
 
   if (lr != 0.0f) {
     tm.begin(18);
     sgd_update(w.sgd_dev, sgd_set.cnt, lr, s);
     tm.end(18);
   }
-
-  tm.begin(19);
-  writeback_scatter(d, w.bs_dev, bs.total, st, w.winkey, w.epoch, w.s_new, d.ldh, w.tau, w.slot_row, nullptr, nullptr,
-                    nullptr, nullptr, out_winner, s);
-  tm.end(19);
+  if (!side.on) {
+    tm.begin(19);
+    writeback_scatter(d, w.bs_dev, bs.total, st, w.winkey, w.epoch, w.s_new, d.ldh, w.tau, w.slot_row, nullptr, nullptr,
+                      nullptr, nullptr, out_winner, s);
+    tm.end(19);
+  }
   if (out_logits)
     TGNN_HIP_CHECK(hipMemcpyAsync(out_logits, w.logits, sizeof(float) * B2, hipMemcpyDeviceToDevice, s));
   TGNN_LAUNCH_CHECK();
-  ctx->last_attn_roots = -1;
   return TGNN_OK;
 }
 

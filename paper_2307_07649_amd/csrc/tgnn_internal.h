@@ -42,7 +42,7 @@ struct BatchSet {
 // Device workspace.  S slots = R roots followed by R*k neighbour slots (slot R + r*k + j).
 struct Ws {
   // indices
-  int32_t *root_node, *root_gid, *root_batch;  // [R]
+  int32_t* root_node;                          // [R]
   double* root_t;                              // [R]
   int32_t *nbr, *neid, *cnt;                   // [R,k], [R,k], [R]
   double* nts;                                 // [R,k]
@@ -87,8 +87,33 @@ struct Profiler {
 };
 }  // namespace tgnn
 
+namespace tgnn {
+// A captured tgnn_train_step: every launch of the step recorded once into a HIP graph and replayed with one
+// call; only the prologue node's arguments (the batch descriptors) change between replays.
+constexpr int MAX_STEP_GRAPHS = 8;
+struct StepKey {
+  const void* ptr[64];
+  int32_t n[TGNN_MAX_BATCHES], rep[TGNN_MAX_BATCHES];
+  int32_t nb;
+  float lr;
+};
+struct StepGraph {
+  bool used = false;
+  StepKey key;
+  hipGraph_t graph = nullptr;
+  hipGraphExec_t exec = nullptr;
+  hipGraphNode_t prologue_node = nullptr;
+  unsigned long long last_use = 0;
+};
+}  // namespace tgnn
+
 struct tgnn_ctx {
   tgnn::Profiler prof;
+  hipStream_t side = nullptr;      // second stream for work that is off the critical path of a step
+  hipEvent_t fork_ev[16] = {};     // fork/join events between the caller's stream and `side`
+  int next_ev = 0;
+  tgnn::StepGraph graphs[tgnn::MAX_STEP_GRAPHS];   // captured steps, one per distinct call signature
+  unsigned long long graph_clock = 0;
   tgnn_config cfg;
   tgnn::Dims d;
   void* arena;
@@ -157,34 +182,51 @@ struct PackDesc {
   int rows, cols, zero_to, ldd;  // dst[r*ldd + c] = src[r*srs + c*scs] for c < cols, 0 for cols <= c < zero_to
   int srs, scs;
 };
-// One launch at the start of a call: packs the weights, optionally zeroes the gradient tensors in `zero`,
-// copies the batch descriptors and the SGD pointer table to the device, zeroes *loss, bumps the epoch.
-// bs / sgd / zero / loss may be NULL.
-void prologue(tgnn_ctx* ctx, const tgnn_params* p, const BatchSet* bs, const struct SgdSet* sgd,
-              const struct SgdSet* zero, float* loss, hipStream_t s);
-void fill_state(tgnn_ctx* ctx, tgnn_state* st, int replica, hipStream_t s);
 struct SgdSet {
   float* p[20];
   const float* g[20];
   int n[20];
   int cnt;
 };
+constexpr int MAX_PACK = 24;
+struct PrologueArgs {
+  PackDesc d[MAX_PACK];
+  int n_pack;
+  SgdSet zero;          // tensors to clear (cnt = 0: none)
+  BatchSet bs;          // copied to *bs_dev when bs_dev != NULL
+  BatchSet* bs_dev;
+  SgdSet sgd;           // copied to *sgd_dev when sgd_dev != NULL
+  SgdSet* sgd_dev;
+  float* loss;
+  unsigned long long* epoch;
+  int32_t* ucount;
+};
+void prologue_fill(tgnn_ctx* ctx, const tgnn_params* p, const BatchSet* bs, const SgdSet* sgd, const SgdSet* zero,
+                   float* loss, PrologueArgs& pa);
+dim3 prologue_grid(const PrologueArgs& pa);
+void* prologue_func();
+// One launch at the start of a call: packs the weights, optionally zeroes the gradient tensors in `zero`,
+// copies the batch descriptors and the SGD pointer table to the device, zeroes *loss, bumps the epoch.
+// bs / sgd / zero / loss may be NULL.
+void prologue(tgnn_ctx* ctx, const tgnn_params* p, const BatchSet* bs, const struct SgdSet* sgd,
+              const struct SgdSet* zero, float* loss, hipStream_t s);
+void fill_state(tgnn_ctx* ctx, tgnn_state* st, int replica, hipStream_t s);
 void sgd_update(const SgdSet* set_dev, int cnt, float lr, hipStream_t s);
 void zero_set(const SgdSet& set, hipStream_t s);
 void copy_f4(const void* src, void* dst, size_t n_float4, hipStream_t s);
 
 // ---- k_sample.hip -------------------------------------------------------------------
-// Roots of every batch (+ their slot ids) and the write-back arbitration marks of the positive endpoints.
-void build_roots(tgnn_ctx* ctx, int total, hipStream_t s);
 struct UniqPtrs {
   unsigned long long* utag;
   const unsigned long long* epoch;
   int32_t *uidx, *ucount, *ulist, *ucnt;
 };
-// slot_gid / slot_node / uq may be NULL (plain sampling)
-void sample_recent(const Dims& d, const tgnn_graph* g, const int32_t* node, const double* t, const int32_t* gid_base,
-                   int n_roots, int32_t* out_nbr, int32_t* out_eid, double* out_ts, int32_t* out_cnt,
-                   int32_t* slot_gid, int32_t* slot_node, const UniqPtrs* uq, hipStream_t s);
+// Fused step: roots of every batch (node, time, slot ids), write-back arbitration marks, neighbour sampling and
+// row claims in one launch; results go to the workspace.
+void sample_roots(tgnn_ctx* ctx, const tgnn_graph* g, int n_roots, hipStream_t s);
+// Plain sampling of caller-provided queries.
+void sample_recent(const Dims& d, const tgnn_graph* g, const int32_t* node, const double* t, int n_roots,
+                   int32_t* out_nbr, int32_t* out_eid, double* out_ts, int32_t* out_cnt, hipStream_t s);
 
 // ---- k_unique.hip -------------------------------------------------------------------
 // Claim (replica, node) `gid` for this step; the first claimant allocates the node's row.
@@ -199,7 +241,8 @@ __device__ __forceinline__ void uniq_claim(unsigned long long* utag, int32_t* ui
     ucnt[row] = 0;
   }
 }
-void uniq_finalize(tgnn_ctx* ctx, int S, hipStream_t s);   // slot -> row map and the row-sorted slot list
+void uniq_map(tgnn_ctx* ctx, int S, hipStream_t s);    // slot -> row map, slots per row
+void uniq_sort(tgnn_ctx* ctx, int S, hipStream_t s);   // row-sorted slot list (needed by seg_reduce only)
 void seg_reduce(tgnn_ctx* ctx, int R, int S, hipStream_t s);
 void expand_rows(tgnn_ctx* ctx, int S, const float* src, int ld, const double* src_d, float* dst, double* dst_d,
                  hipStream_t s);

@@ -21,6 +21,8 @@ PARAM_NAMES = ["time_w", "time_b", "gru_wih", "gru_whh", "gru_bih", "gru_bhh", "
                "wv", "bv", "wo", "bo", "dec_ws", "dec_wd", "dec_b1", "dec_w2", "dec_b2"]
 MAX_BATCHES = 16
 FLAG_OVERWRITE_GRADS = 1
+FLAG_SIDE_STREAM = 2
+FLAG_NO_GRAPH = 4
 
 
 class tgnn_config(C.Structure):

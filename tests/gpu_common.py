@@ -63,14 +63,17 @@ class OracleSide:
 
 
 class GpuSide:
-    def __init__(self, P, n_replicas=1, dt_source=0):
+    def __init__(self, P, n_replicas=1, dt_source=0, own_stream=True, flags=0):
+        """own_stream: run the steps on a stream of their own (the library then replays a captured HIP graph);
+        False = the NULL stream, where every launch is enqueued directly."""
         import torch
         from paper_2307_07649_amd import tgnn
         self.torch, self.tgnn = torch, tgnn
+        self.stream = torch.cuda.Stream() if own_stream else torch.cuda.default_stream()
         d = P["d"]
         self.P, self.d = P, d
         self.ctx = tgnn.Context(d.n_nodes, d.d_mem, d.d_time, d.d_edge, d.d_static, d.n_heads, d.k, d.batch,
-                                n_replicas=n_replicas, dt_source=dt_source)
+                                n_replicas=n_replicas, dt_source=dt_source, flags=flags)
         self.graph = tgnn.Graph(P["src"], P["dst"], P["ts"], d.n_nodes, P["efeat"])
         self.state = tgnn.State(d.n_nodes, d.d_mem, n_replicas, P["static"])
         self.params = tgnn.Params.from_numpy(P["params"])
@@ -82,10 +85,14 @@ class GpuSide:
         replicas = replicas if replicas is not None else list(range(len(batches)))
         bl = [tgnn.Batch(b["src"], b["dst"], b["neg"], b["eid"], b["t"], replica=r) for b, r in zip(batches, replicas)]
         tot = sum(b.n for b in bl)
-        logits = torch.empty(2 * tot, device="cuda"); win = torch.empty(2 * tot, dtype=torch.int32, device="cuda")
-        self.grads.zero_()
-        self.ctx.tgnn_train_step(self.graph, self.state, self.params, self.grads, bl, lr=lr, out_loss=self.loss,
-                                 out_logits=logits, out_winner=win)
+        if not hasattr(self, "_out") or self._out[0].numel() != 2 * tot:      # stable output buffers: same graph key
+            self._out = (torch.empty(2 * tot, device="cuda"), torch.empty(2 * tot, dtype=torch.int32, device="cuda"))
+        logits, win = self._out
+        torch.cuda.synchronize()
+        with torch.cuda.stream(self.stream):
+            self.grads.zero_()
+            self.ctx.tgnn_train_step(self.graph, self.state, self.params, self.grads, bl, lr=lr, out_loss=self.loss,
+                                     out_logits=logits, out_winner=win)
         torch.cuda.synchronize()
         if not want:
             return None

@@ -9,9 +9,9 @@ from gpu_common import GpuSide, OracleSide, batch_np, compare_state, compare_ste
 pytestmark = pytest.mark.gpu
 
 
-def run_sequence(P, n_steps, lr=0.0, check_at=(0,), dt_source=0, first=0):
+def run_sequence(P, n_steps, lr=0.0, check_at=(0,), dt_source=0, first=0, own_stream=True, flags=0):
     d = P["d"]
-    G = GpuSide(P, dt_source=dt_source); Or = OracleSide(P, dt_source=dt_source)
+    G = GpuSide(P, dt_source=dt_source, own_stream=own_stream, flags=flags); Or = OracleSide(P, dt_source=dt_source)
     errs = {}
     for s in range(n_steps):
         lo = (first + s) * d.batch; hi = min(lo + d.batch, P["E"])
@@ -43,6 +43,14 @@ def test_c0_50_batches_sgd():
 def test_c0_edge_time_variant():
     P = make_problem("C0")
     run_sequence(P, 12, check_at=(0, 11), dt_source=1)
+
+
+@pytest.mark.parametrize("own_stream,flags", [(False, 0), (True, 2), (True, 4), (True, 6)])
+def test_launch_modes_agree_with_the_oracle(own_stream, flags):
+    """NULL stream (direct launches); captured graph with the side stream; no graph; no graph with the side stream.
+    (The default, a captured single-stream graph, is what every other test runs.)"""
+    P = make_problem("C0", random_phase=True)
+    run_sequence(P, 12, lr=0.05, check_at=(0, 5, 11), own_stream=own_stream, flags=flags)
 
 
 @pytest.mark.parametrize("shape", [
