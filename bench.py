@@ -22,12 +22,12 @@ sys.path.insert(0, ROOT)
 PEAK_HBM_GBS = 8000.0
 PEAK_MFMA_F32_TFLOPS = 157.3
 
-STAGE_NAMES = ["prologue (pack weights, clear)", "roots + write-back arbitration", "sample + distinct-node rows",
+STAGE_NAMES = ["prologue (pack weights, clear)", "row-sorted slot list (for the backward row sums)", "roots + sample + distinct-node rows",
                "gather + time-encode (GRU input)", "GRU input projection (MFMA)", "GRU hidden projection (MFMA)",
                "GRU gates", "attention input assembly (gather)", "K/V projection (MFMA)", "query projection (MFMA)",
                "softmax attention", "merge layer (MFMA)", "decoder forward + loss", "decoder backward",
                "attention backward (MFMA + softmax)", "segmented gradient sum + GRU gates backward",
-               "GRU weight gradients (MFMA)", "time-encoding gradients", "SGD", "write-back scatter"]
+               "all weight gradients (grouped MFMA GEMM)", "time-encoding gradients", "SGD", "write-back scatter"]
 STAGE_ASSEMBLE, STAGE_KV = 7, 8
 
 

@@ -205,11 +205,12 @@ int32_t tgnn_train_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
 int32_t tgnn_zero_params(tgnn_ctx* ctx, tgnn_params* g, void* stream);
 
 /* Stage timing with HIP events on the call's own stream.  Stages of tgnn_train_step:
- *  0 prologue (pack weights, clear loss/grads)   1 roots + write-back arbitration   2 sample   3 gather + time-encode (GRU input)
- *  4 GRU input projection (MFMA)   5 GRU hidden projection (MFMA)   6 GRU gates   7 attention input assembly
- *  8 K/V projection (MFMA)   9 query projection   10 softmax attention   11 merge layer   12 decoder forward + loss
- *  13 decoder backward   14 attention backward (GEMMs + softmax)   15 GRU gates backward
- *  16 GRU weight gradients (MFMA)   17 time-encoding gradients of the mail   18 SGD   19 write-back scatter
+ *  0 prologue (pack weights, clear loss/grads)   1 row-sorted slot list   2 roots + sample + distinct-node rows
+ *  3 gather + time-encode (GRU input)   4 GRU input projection (MFMA)   5 GRU hidden projection (MFMA)   6 GRU gates
+ *  7 attention input assembly   8 K/V projection (MFMA)   9 query projection   10 softmax attention   11 merge layer
+ *  12 decoder forward + loss   13 decoder backward   14 attention backward (data-gradient GEMMs + softmax)
+ *  15 per-row gradient sums + GRU gates backward   16 all weight gradients (one grouped MFMA GEMM)
+ *  17 time-encoding gradients   18 SGD   19 write-back scatter
  * tgnn_profile_enable: time the stages whose bit is set in `stage_mask` in every following tgnn_train_step
  * (0 = off); each timed stage costs two event records per step.  At most 4096 steps are kept per stage;
  * enabling resets the record.  tgnn_profile_read: synchronises the recorded events and returns the number
