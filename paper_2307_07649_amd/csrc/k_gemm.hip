@@ -361,95 +361,132 @@ void gemm_nt(const float* A, int lda, const float* B, int ldb, const float* bias
 }
 
 // ------------------------------------------------------------------------------------------------
-// TN with accumulation: G[n, k] += sum_m D[m, n] * A[m, k].  Both operands are m-major, so a stage is
-// 32 rows of D (64 columns) and 32 rows of A (64 columns); 2 x 2 waves each own a 32 x 32 block of G.
-// The reduction over m is split over blockIdx.y; partial results are added with float atomics.
+// TN with accumulation: G[n, k] += sum_m D[m, n] * A[m, k], bias[n] += sum_m D[m, n].
+// Both operands are m-major, so a stage is 32 rows of D and of A in LDS, row-major.  The MFMA sums over four
+// m values per instruction (one per lane group), and which n (k) a lane feeds is free as long as the result
+// is read back the same way: lane (li, lg) reads TD consecutive floats D[m][n0 + TD*li ..] and TA consecutive
+// floats A[m][k0 + TA*li ..] with one LDS load each and issues TD*TA MFMAs from them, instruction (t, u)
+// covering the strided columns n = n0 + TD*i + t, k = k0 + TA*j + u.  A workgroup owns a (16 TD) x (16 TA)
+// tile of G (64 x 64 in the bulk, narrower pieces at the right and bottom edges so that little of the
+// tile is padding); its four waves split the 32 rows of a stage, and their partial tiles are added in LDS
+// before one float atomic per element goes to memory.  The reduction over m is split over workgroups.
+// The bias gradient rides along as column K of A, which the loader replaces by ones.
 // ------------------------------------------------------------------------------------------------
-constexpr int TT = 64;     // output tile edge
-constexpr int TN_P = 80;   // stage row pitch: rows 4 apart land 16 banks apart
+constexpr int TT = 64;     // bulk tile edge
+constexpr int TN_P = 80;   // stage row pitch in floats
 constexpr int TN_ROWS = 32;
 
-__global__ __launch_bounds__(256) void gemm_tn_kernel(TnGroup grp) {
-  // Several independent problems share one launch (all weight gradients of a step): find this workgroup's.
-  int pi = 0;
-  while (pi + 1 < grp.n && (int)blockIdx.x >= grp.p[pi + 1].wg_begin) ++pi;
-  const TnProblem& pr = grp.p[pi];
-  const float* __restrict__ D = pr.D;
-  const float* __restrict__ A = pr.A;
-  const int ldd = pr.ldd, lda = pr.lda, N = pr.N, K = pr.K, k_tiles = pr.k_tiles, tiles = pr.tiles, chunks = pr.chunks;
-  int M = pr.M, m_chunk = pr.m_chunk;
-  const OutMap& out = pr.out;
-  // All output tiles of one m-chunk read the same rows of D and A: keep them on one XCD (one L2).
-  const int local = (int)blockIdx.x - pr.wg_begin;
-  const int xcd = local & 7, slot = local >> 3;
-  const int chunk = (slot / tiles) * 8 + xcd, tile = slot % tiles;
-  if (chunk >= chunks) return;
-  if (pr.m_dev != nullptr) {  // row count known only on the device: split it evenly over the launched chunks
-    M = min(M, *pr.m_dev);
-    m_chunk = ((M + chunks - 1) / chunks + TN_ROWS - 1) / TN_ROWS * TN_ROWS;
-  }
-  if (chunk * m_chunk >= M) return;
-  __shared__ __attribute__((aligned(16))) float Ds[2][TN_ROWS * TN_P];
-  __shared__ __attribute__((aligned(16))) float Asm[2][TN_ROWS * TN_P];
+// A length is cut into 64-wide pieces plus at most two narrower ones (32 and/or 16 wide) for the remainder.
+__host__ __device__ inline int tn_pieces(int len) {
+  const int r = len % TT;
+  return len / TT + (r == 0 ? 0 : (r > 32 && r <= 48) ? 2 : 1);
+}
+__device__ __forceinline__ void tn_piece(int len, int idx, int& off, int& width) {
+  const int full = len / TT;
+  if (idx < full) { off = idx * TT; width = TT; return; }
+  const int r = len - full * TT;
+  off = full * TT;
+  if (r <= 16) width = 16;
+  else if (r <= 32) width = 32;
+  else if (r <= 48) { if (idx == full) width = 32; else { off += 32; width = 16; } }
+  else width = TT;
+}
+
+template <int TD> struct FragT;
+template <> struct FragT<1> { typedef float type; };
+template <> struct FragT<2> { typedef float type __attribute__((ext_vector_type(2))); };
+template <> struct FragT<4> { typedef float type __attribute__((ext_vector_type(4))); };
+template <int T> __device__ __forceinline__ float frag_get(const typename FragT<T>::type& f, int i) { return f[i]; }
+template <> __device__ __forceinline__ float frag_get<1>(const float& f, int) { return f; }
+
+template <int TD, int TA>
+__device__ __forceinline__ void tn_tile(const float* __restrict__ D, const float* __restrict__ A, int ldd, int lda, int N,
+                                        int K, float* p00, float* p01, float* p10, float* p11, int ld00, int ld01, int ld10,
+                                        int ld11, int n_split, int k_split, float* bias0, float* bias1, int M, int m_lo,
+                                        int m_hi, int n0, int k0, float* lds) {
+  const bool with_bias = bias0 != nullptr;   // column K of A reads as ones
+  float* Ds = lds;                          // [2][TN_ROWS * TN_P]
+  float* As = lds + 2 * TN_ROWS * TN_P;     // [2][TN_ROWS * TN_P]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int li = lane & 15, lg = lane >> 4;
-  const int wn = wave >> 1, wk = wave & 1;
-  const int n0 = (tile / k_tiles) * TT, k0 = (tile % k_tiles) * TT;
-  const int m_lo = chunk * m_chunk;
-  const int m_hi = min(M, m_lo + m_chunk);
-  const bool do_bias = (tile % k_tiles) == 0 && (out.bias[0] != nullptr);
 
-  floatx4 acc[2][2];
+  floatx4 acc[TD][TA];
 #pragma unroll
-  for (int a = 0; a < 2; ++a)
+  for (int t = 0; t < TD; ++t)
 #pragma unroll
-    for (int b = 0; b < 2; ++b) acc[a][b] = floatx4{0.f, 0.f, 0.f, 0.f};
-  float bsum = 0.f;
+    for (int u = 0; u < TA; ++u) acc[t][u] = floatx4{0.f, 0.f, 0.f, 0.f};
 
-  // This thread's float4s of a stage: rows lrow and lrow + 16.  Column offsets are clamped into the row
-  // (results of clamped columns are dropped at the end); rows >= m_hi are clamped and zeroed by a select.
-  const int lrow = tid >> 4, lc4 = (tid & 15) * 4;
-  const float* pd = D + min(n0 + lc4, ldd - 4);
-  const float* pa = A + min(k0 + lc4, lda - 4);
+  // Loader: float4 f of a stage is row f / (4 T), columns 4 (f % (4 T)) .. +3 of the tile.  Column offsets are
+  // clamped into the row (results of columns >= N or > K are dropped at the end); rows >= m_hi are clamped
+  // and D is zeroed there by a select.
+  constexpr int D_F4 = TN_ROWS * 4 * TD, A_F4 = TN_ROWS * 4 * TA;
+  constexpr int D_PER = (D_F4 + 255) / 256, A_PER = (A_F4 + 255) / 256;
+  int d_row[D_PER], a_row[A_PER], one_comp[A_PER];
+  const float* pd[D_PER];
+  const float* pa[A_PER];
+#pragma unroll
+  for (int u = 0; u < D_PER; ++u) {
+    const int f = min(tid + u * 256, D_F4 - 1);
+    d_row[u] = f / (4 * TD);
+    pd[u] = D + min(n0 + (f % (4 * TD)) * 4, ldd - 4);
+  }
+#pragma unroll
+  for (int u = 0; u < A_PER; ++u) {
+    const int f = min(tid + u * 256, A_F4 - 1);
+    a_row[u] = f / (4 * TA);
+    const int c = k0 + (f % (4 * TA)) * 4;
+    pa[u] = A + min(c, lda - 4);
+    one_comp[u] = (with_bias && K >= c && K < c + 4) ? K - c : -1;
+  }
+  // The fix-ups (zero rows, ones column) are applied when a register set is stored to LDS, one stage after
+  // its loads were issued, so that no instruction waits on a load in the stage that issued it.
   struct Regs {
-    floatx4 d[2], a[2];
+    floatx4 d[D_PER], a[A_PER];
+    int m;
   };
   Regs r0, r1;
   auto gload = [&](Regs& r, int m) __attribute__((always_inline)) {
+    r.m = m;
 #pragma unroll
-    for (int u = 0; u < 2; ++u) {
-      const int row = m + lrow + u * 16;
-      const size_t rr = (size_t)min(row, M - 1);
-      const floatx4 vd = *reinterpret_cast<const floatx4*>(pd + rr * ldd);
-      const floatx4 va = *reinterpret_cast<const floatx4*>(pa + rr * lda);
-      const bool ok = row < m_hi;
-      r.d[u] = ok ? vd : floatx4{0.f, 0.f, 0.f, 0.f};
-      r.a[u] = va;   // multiplied by the zeros of r.d when the row is out of range
-    }
+    for (int u = 0; u < D_PER; ++u)
+      r.d[u] = *reinterpret_cast<const floatx4*>(pd[u] + (size_t)min(m + d_row[u], M - 1) * ldd);
+#pragma unroll
+    for (int u = 0; u < A_PER; ++u)
+      r.a[u] = *reinterpret_cast<const floatx4*>(pa[u] + (size_t)min(m + a_row[u], M - 1) * lda);
   };
   auto sstore = [&](const Regs& r, int buf) __attribute__((always_inline)) {
 #pragma unroll
-    for (int u = 0; u < 2; ++u) {
-      *reinterpret_cast<floatx4*>(&Ds[buf][(lrow + u * 16) * TN_P + lc4]) = r.d[u];
-      *reinterpret_cast<floatx4*>(&Asm[buf][(lrow + u * 16) * TN_P + lc4]) = r.a[u];
+    for (int u = 0; u < D_PER; ++u) {
+      const int f = tid + u * 256;
+      const floatx4 v = r.m + d_row[u] < m_hi ? r.d[u] : floatx4{0.f, 0.f, 0.f, 0.f};
+      if (D_F4 % 256 == 0 || f < D_F4)
+        *reinterpret_cast<floatx4*>(&Ds[buf * TN_ROWS * TN_P + (f / (4 * TD)) * TN_P + (f % (4 * TD)) * 4]) = v;
+    }
+#pragma unroll
+    for (int u = 0; u < A_PER; ++u) {
+      const int f = tid + u * 256;
+      floatx4 v = r.a[u];   // rows out of range are multiplied by the zeros of D
+      v.x = one_comp[u] == 0 ? 1.f : v.x;
+      v.y = one_comp[u] == 1 ? 1.f : v.y;
+      v.z = one_comp[u] == 2 ? 1.f : v.z;
+      v.w = one_comp[u] == 3 ? 1.f : v.w;
+      if (A_F4 % 256 == 0 || f < A_F4)
+        *reinterpret_cast<floatx4*>(&As[buf * TN_ROWS * TN_P + (f / (4 * TA)) * TN_P + (f % (4 * TA)) * 4]) = v;
     }
   };
+  typedef typename FragT<TD>::type FD;
+  typedef typename FragT<TA>::type FA;
   auto compute = [&](int buf) __attribute__((always_inline)) {
 #pragma unroll
-    for (int q = 0; q < TN_ROWS / 4; ++q) {
-      const int mm = q * 4 + lg;
-      const float a0 = Ds[buf][mm * TN_P + wn * 32 + li];
-      const float a1 = Ds[buf][mm * TN_P + wn * 32 + 16 + li];
-      const float b0 = Asm[buf][mm * TN_P + wk * 32 + li];
-      const float b1 = Asm[buf][mm * TN_P + wk * 32 + 16 + li];
-      acc[0][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(a0, b0, acc[0][0], 0, 0, 0);
-      acc[0][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(a0, b1, acc[0][1], 0, 0, 0);
-      acc[1][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(a1, b0, acc[1][0], 0, 0, 0);
-      acc[1][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(a1, b1, acc[1][1], 0, 0, 0);
-    }
-    if (do_bias && tid < TT) {
+    for (int q = 0; q < 2; ++q) {   // this wave's rows 8 wave .. 8 wave + 7, four per MFMA
+      const int mm = wave * 8 + q * 4 + lg;
+      const FD df = *reinterpret_cast<const FD*>(&Ds[buf * TN_ROWS * TN_P + mm * TN_P + TD * li]);
+      const FA af = *reinterpret_cast<const FA*>(&As[buf * TN_ROWS * TN_P + mm * TN_P + TA * li]);
 #pragma unroll
-      for (int mm = 0; mm < TN_ROWS; ++mm) bsum += Ds[buf][mm * TN_P + tid];
+      for (int t = 0; t < TD; ++t)
+#pragma unroll
+        for (int u = 0; u < TA; ++u)
+          acc[t][u] = __builtin_amdgcn_mfma_f32_16x16x4f32(frag_get<TD>(df, t), frag_get<TA>(af, u), acc[t][u], 0, 0, 0);
     }
   };
 
@@ -483,58 +520,140 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(TnGroup grp) {
     }
   }
 
+  // Add the four waves' partial tiles in LDS (two tiles of 16 TD x 16 TA, written by waves 0/1, then added to
+  // by waves 2/3), then one atomic per element.  acc[t][u][v] of lane (li, lg) is n = TD (4 lg + v) + t,
+  // k = TA li + u of the tile.
+  constexpr int TW = 16 * TA, TILE = 16 * TD * TW;
+  __syncthreads();   // every wave is done reading the stage buffers
+  float* red = lds + (wave & 1) * TILE;
+  if (wave < 2) {
 #pragma unroll
-  for (int a = 0; a < 2; ++a)
+    for (int t = 0; t < TD; ++t)
 #pragma unroll
-    for (int b = 0; b < 2; ++b) {
-      const int k = k0 + wk * 32 + b * 16 + li;
-      if (k >= K) continue;
-      const int ks = k >= out.k_split ? 1 : 0;
-      const int kk = k - (ks ? out.k_split : 0);
+      for (int u = 0; u < TA; ++u)
 #pragma unroll
-      for (int v = 0; v < 4; ++v) {
-        const int n = n0 + wn * 32 + a * 16 + lg * 4 + v;
-        if (n >= N) continue;
-        const int ns = n >= out.n_split ? 1 : 0;
-        const int nn = n - (ns ? out.n_split : 0);
-        atomicAdd(out.p[ns][ks] + (size_t)nn * out.ld[ns][ks] + kk, acc[a][b][v]);
-      }
-    }
-  if (do_bias && tid < TT) {
-    const int n = n0 + tid;
-    if (n < N) {
-      const int ns = n >= out.n_split ? 1 : 0;
-      atomicAdd(out.bias[ns] + (n - (ns ? out.n_split : 0)), bsum);
+        for (int v = 0; v < 4; ++v) red[(TD * (4 * lg + v) + t) * TW + TA * li + u] = acc[t][u][v];
+  }
+  __syncthreads();
+  if (wave >= 2) {
+#pragma unroll
+    for (int t = 0; t < TD; ++t)
+#pragma unroll
+      for (int u = 0; u < TA; ++u)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) red[(TD * (4 * lg + v) + t) * TW + TA * li + u] += acc[t][u][v];
+  }
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < (TILE + 255) / 256; ++i) {
+    const int e = tid + i * 256;
+    if (TILE % 256 != 0 && e >= TILE) break;
+    const int n = n0 + e / TW, k = k0 + e % TW;
+    if (n >= N || k > K) continue;
+    const float x = lds[e] + lds[TILE + e];
+    // (selects instead of indexing: a dynamically indexed local array would live in scratch memory)
+    const bool ns = n >= n_split;
+    const int nn = n - (ns ? n_split : 0);
+    if (k == K) {
+      if (with_bias) atomicAdd((ns ? bias1 : bias0) + nn, x);
+    } else {
+      const bool ks = k >= k_split;
+      float* base = ns ? (ks ? p11 : p10) : (ks ? p01 : p00);
+      const int ld = ns ? (ks ? ld11 : ld10) : (ks ? ld01 : ld00);
+      atomicAdd(base + (size_t)nn * ld + (k - (ks ? k_split : 0)), x);
     }
   }
 }
 
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4))) void gemm_tn_kernel(TnGroup grp) {
+  // Several independent problems share one launch (all weight gradients of a step): find this workgroup's.
+  int pi = 0;
+#pragma unroll
+  for (int i = 1; i < TN_MAX_GROUP; ++i)
+    if (i < grp.n && (int)blockIdx.x >= grp.p[i].wg_begin) pi = i;
+  // The argument block is indexed through the kernel-argument segment itself (scalar loads at a computed
+  // offset); indexing the by-value parameter would make the compiler spill the whole block to scratch.
+  typedef const TnGroup __attribute__((address_space(4))) * GroupPtr;
+  const GroupPtr gp = (GroupPtr)__builtin_amdgcn_kernarg_segment_ptr();
+  const auto& q = gp->p[pi];
+  const int k_tiles = q.k_tiles, tiles = q.tiles, chunks = q.chunks, wg_begin = q.wg_begin, N = q.N, K = q.K;
+  int M = q.M, m_chunk = q.m_chunk;
+  const int* m_dev = q.m_dev;
+  float* const bias0 = q.out.bias[0];
+  // All output tiles of one m-chunk read the same rows of D and A: keep them on one XCD (one L2).
+  const int local = (int)blockIdx.x - wg_begin;
+  const int xcd = local & 7, slot = local >> 3;
+  const int chunk = (slot / tiles) * 8 + xcd, tile = slot % tiles;
+  if (chunk >= chunks) return;
+  if (m_dev != nullptr) {  // row count known only on the device: split it evenly over the launched chunks
+    M = min(M, *m_dev);
+    m_chunk = ((M + chunks - 1) / chunks + TN_ROWS - 1) / TN_ROWS * TN_ROWS;
+  }
+  if (chunk * m_chunk >= M) return;   // uniform for the workgroup, before any barrier
+  __shared__ __attribute__((aligned(16))) float lds[4 * TN_ROWS * TN_P];
+  const int m_lo = chunk * m_chunk;
+  const int m_hi = min(M, m_lo + m_chunk);
+  int n0, wn, k0, wk;
+  tn_piece(N, tile / k_tiles, n0, wn);
+  tn_piece(K + (bias0 != nullptr ? 1 : 0), tile % k_tiles, k0, wk);
+#define TGNN_TN_CASE(WN, WK)                                                                                          \
+  if (wn == WN && wk == WK) {                                                                                         \
+    tn_tile<WN / 16, WK / 16>(q.D, q.A, q.ldd, q.lda, N, K, q.out.p[0][0], q.out.p[0][1], q.out.p[1][0], q.out.p[1][1], \
+                              q.out.ld[0][0], q.out.ld[0][1], q.out.ld[1][0], q.out.ld[1][1], q.out.n_split,           \
+                              q.out.k_split, bias0, q.out.bias[1], M, m_lo, m_hi, n0, k0, lds);                        \
+    return;                                                                                                           \
+  }
+  TGNN_TN_CASE(64, 64) TGNN_TN_CASE(64, 32) TGNN_TN_CASE(64, 16)
+  TGNN_TN_CASE(32, 64) TGNN_TN_CASE(32, 32) TGNN_TN_CASE(32, 16)
+  TGNN_TN_CASE(16, 64) TGNN_TN_CASE(16, 32) TGNN_TN_CASE(16, 16)
+#undef TGNN_TN_CASE
+}
+
 void TnBatch::add(const float* D, int ldd, const float* A, int lda, int M, int N, int K, const OutMap& out,
                   const int* m_dev) {
-  if (M <= 0 || N <= 0 || K <= 0 || g.n >= TN_MAX_GROUP) return;
+  // the loader clamps column offsets to ld - 4 and reads whole float4s: pitches below 4 (or below the logical
+  // width) would send it out of bounds
+  if (M <= 0 || N <= 0 || K <= 0 || g.n >= TN_MAX_GROUP || ldd < 4 || lda < 4 || (ldd & 3) || (lda & 3) || N > ldd ||
+      K > lda)
+    return;
   TnProblem& p = g.p[g.n];
-  const int n_tiles = (N + TT - 1) / TT, k_tiles = (K + TT - 1) / TT;
-  const int tiles = n_tiles * k_tiles;
-  // enough m-chunks to give the chip a few workgroups per CU, at least 64 rows (two stages) each
-  int chunks = (1024 + tiles - 1) / tiles;
-  const int max_chunks = (M + 63) / 64;
-  if (chunks > max_chunks) chunks = max_chunks;
-  if (chunks < 1) chunks = 1;
-  int m_chunk = ((M + chunks - 1) / chunks + TN_ROWS - 1) / TN_ROWS * TN_ROWS;
-  chunks = (M + m_chunk - 1) / m_chunk;
-  if (m_dev != nullptr && chunks > 16) chunks = 16;   // the device-side row count is usually far below M
   p.D = D; p.ldd = ldd; p.A = A; p.lda = lda; p.M = M; p.N = N; p.K = K;
-  p.m_chunk = m_chunk; p.k_tiles = k_tiles; p.tiles = tiles; p.chunks = chunks;
-  p.wg_begin = total_wgs; p.m_dev = m_dev; p.out = out;
-  total_wgs += tiles * ((chunks + 7) & ~7);
+  p.k_tiles = tn_pieces(K + (out.bias[0] != nullptr ? 1 : 0));
+  p.tiles = tn_pieces(N) * p.k_tiles;
+  p.m_dev = m_dev; p.out = out;
   g.n++;
 }
 
+// Every workgroup ends with one float atomic per element of its tile, and the L2 retires roughly one such
+// element per clock and channel: the number of m-chunks is what the atomics cost.  So the launch as a whole
+// gets about as many workgroups as the chip holds at once, shared out over the problems in proportion to their
+// multiply work; a small problem gets a handful of chunks instead of dozens.
 void TnBatch::launch(hipStream_t s) {
   if (g.n == 0) return;
+  static const int target_wgs = getenv("TGNN_TN_WGS") ? atoi(getenv("TGNN_TN_WGS")) : 1024;
+  double work[TN_MAX_GROUP], total = 0.0;
+  int rows[TN_MAX_GROUP];
+  for (int i = 0; i < g.n; ++i) {
+    // a row count that lives on the device (distinct nodes of a step) is usually a small part of its bound
+    rows[i] = g.p[i].m_dev != nullptr ? (g.p[i].M + 7) / 8 : g.p[i].M;
+    work[i] = (double)rows[i] * g.p[i].tiles;
+    total += work[i];
+  }
+  int total_wgs = 0;
+  for (int i = 0; i < g.n; ++i) {
+    TnProblem& p = g.p[i];
+    int chunks = (int)(target_wgs * (work[i] / total) / p.tiles + 0.5);
+    const int max_chunks = (rows[i] + 63) / 64;   // at least two stages each
+    if (chunks > max_chunks) chunks = max_chunks;
+    if (chunks < 1) chunks = 1;
+    p.m_chunk = ((p.M + chunks - 1) / chunks + TN_ROWS - 1) / TN_ROWS * TN_ROWS;
+    if (p.m_dev == nullptr) chunks = (p.M + p.m_chunk - 1) / p.m_chunk;
+    p.chunks = chunks;
+    p.wg_begin = total_wgs;
+    total_wgs += p.tiles * ((chunks + 7) & ~7);
+  }
   hipLaunchKernelGGL(gemm_tn_kernel, dim3(total_wgs), dim3(256), 0, s, g);
   g.n = 0;
-  total_wgs = 0;
 }
 
 void gemm_tn_acc(const float* D, int ldd, const float* A, int lda, int M, int N, int K, const OutMap& out,

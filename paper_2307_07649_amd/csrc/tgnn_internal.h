@@ -165,7 +165,6 @@ struct TnGroup {
 };
 struct TnBatch {
   TnGroup g;
-  int total_wgs = 0;
   TnBatch() { g.n = 0; }
   void add(const float* D, int ldd, const float* A, int lda, int M, int N, int K, const OutMap& out,
            const int* m_dev = nullptr);
