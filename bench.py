@@ -24,24 +24,25 @@ PEAK_MFMA_F32_TFLOPS = 157.3
 
 STAGE_NAMES = ["prologue (pack weights, clear)", "row-sorted slot list (for the backward row sums)", "roots + sample + distinct-node rows",
                "gather + time-encode (GRU input)", "GRU input projection (MFMA)", "GRU hidden projection (MFMA)",
-               "GRU gates", "attention input assembly (gather)", "K/V projection (MFMA)", "query projection (MFMA)",
-               "softmax attention", "merge layer (MFMA)", "decoder forward + loss", "decoder backward",
-               "attention backward (MFMA + softmax)", "segmented gradient sum + GRU gates backward",
+               "GRU gates", "per-slot attention input {e | Phi} (gather)", "K/V projection of the slots (MFMA)",
+               "per-node projections K, V, q, merge (MFMA)", "softmax attention", "merge layer (MFMA)",
+               "decoder forward + loss", "decoder backward", "attention backward (MFMA + softmax)",
+               "per-node gradient sums + node projections backward + GRU gates backward",
                "all weight gradients (grouped MFMA GEMM)", "time-encoding gradients", "SGD", "write-back scatter"]
 STAGE_ASSEMBLE, STAGE_KV = 7, 8
 
 
 def flops_kv(d, n_roots):
-    """K and V projections of every neighbour slot: [R k, d_kv] x [d_kv, 2 d_o]."""
-    return 2.0 * n_roots * d.k * d.d_kv * 2 * d.d_out
+    """Executed flops of the per-slot K/V projection: [R k, d_e + d_t] x [d_e + d_t, 2 d_o].  (The node part of
+    the projection, d_x columns, is taken once per distinct node by another, much smaller GEMM.)"""
+    return 2.0 * n_roots * d.k * (d.d_edge + d.d_time) * 2 * d.d_out
 
 
 def assemble_bytes(d, n_roots):
-    """Attention input assembly: per neighbour slot read the s' row, the static row and the edge-feature row and
-    write the key/value input row, the -sin row and the time difference; per root the query / merge inputs."""
-    per_nbr = 4 * (d.d_mem + d.d_static + d.d_edge) + 4 * d.d_kv + 4 * d.d_time + 8 + 8
-    per_root = 4 * (d.d_mem + d.d_static) + 4 * d.d_q + 4 * d.d_x
-    return n_roots * (d.k * per_nbr + per_root)
+    """Per-slot attention input: per neighbour slot read the edge-feature row, the neighbour's event time and
+    update time, and write the {e | Phi} row, the -sin row and the time difference."""
+    per_nbr = 4 * d.d_edge + 4 * (d.d_edge + d.d_time) + 4 * d.d_time + 4 + 8 + 8 + 8
+    return n_roots * d.k * per_nbr
 
 
 def step_flops(d, B):
@@ -199,13 +200,13 @@ def main():
                                f"d_edge {d.d_edge}, d_static {d.d_static}, {d.n_heads} heads, k {d.k}, "
                                f"batch {d.batch} x {nrep} replica(s), 1 negative/event, SGD lr {args.lr}",
                    "events_per_step": ev_step, "final_loss": final_loss},
-        "roofline": {"bound": "mfma", "kernel": "gemm_nt_kernel: K/V projection of all neighbour slots "
-                                                "(fp32 MFMA 16x16x4), the longest kernel of the step",
+        "roofline": {"bound": "mfma", "kernel": "gemm_nt_kernel: K/V projection of the {e | Phi} rows of all "
+                                                "neighbour slots (fp32 MFMA 16x16x4), the longest forward kernel",
                      "achieved": kv_tflops, "peak": PEAK_MFMA_F32_TFLOPS, "unit": "TFLOP/s",
                      "frac": kv_tflops / PEAK_MFMA_F32_TFLOPS if kv_tflops else None,
                      "avg_launch_us": ms_m / n_m * 1e3 if n_m else None, "traffic": None},
-        "gather": {"bound": "hbm", "kernel": "attn_assemble_kernel: s' / static / edge-feature row gather + time "
-                                             "encoding into the key/value inputs",
+        "gather": {"bound": "hbm", "kernel": "assemble_ce_kernel: edge-feature row gather + time encoding into the "
+                                             "per-slot key/value inputs",
                    "achieved": asm_gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                    "frac": asm_gbs / PEAK_HBM_GBS if asm_gbs else None,
                    "avg_launch_us": ms_g / n_g * 1e3 if n_g else None},

@@ -7,16 +7,17 @@
 namespace tgnn {
 
 struct AttnShape {
-  int R, k, H, dO, dh, ldq, ldkv, ldm;
+  int R, k, H, dO, dh, ldq, ldkv, ldo;
 };
 
 // LDS floats per wave
 __host__ __device__ inline int attn_lds_floats(int k, int H, int dO) { return dO + k * (dO + 1) + 2 * H * k; }
 
 __global__ __launch_bounds__(256) void attn_fwd_kernel(AttnShape sh, const float* __restrict__ q,
+                                                       const int32_t* __restrict__ slot_row,
                                                        const float* __restrict__ KV,
                                                        const int32_t* __restrict__ cnt, float* __restrict__ prob,
-                                                       float* __restrict__ Min) {
+                                                       float* __restrict__ Omat) {
   extern __shared__ float lds[];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int r = blockIdx.x * 4 + wave;
@@ -27,14 +28,15 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(AttnShape sh, const float
   const int c = cnt[r];
   const int HK = sh.H * sh.k;
   float* pr = prob + (size_t)r * HK;
-  float* out = Min + (size_t)r * sh.ldm;
+  float* out = Omat + (size_t)r * sh.ldo;
   if (c == 0) {
     for (int p = lane; p < HK; p += 64) pr[p] = 0.f;
     for (int e = lane; e < sh.dO; e += 64) out[e] = 0.f;
     return;
   }
   const float scale = 1.0f / sqrtf((float)c);
-  for (int e = lane; e < sh.dO; e += 64) sq[e] = q[(size_t)r * sh.ldq + e];
+  const size_t qrow = slot_row != nullptr ? (size_t)slot_row[r] : (size_t)r;   // q is stored per distinct node
+  for (int e = lane; e < sh.dO; e += 64) sq[e] = q[qrow * sh.ldq + e];
   for (int j = 0; j < c; ++j) {
     const float* krow = KV + ((size_t)r * sh.k + j) * sh.ldkv;
     for (int e = lane; e < sh.dO; e += 64) sK[j * (sh.dO + 1) + e] = krow[e];
@@ -79,10 +81,11 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(AttnShape sh, const float
 }
 
 __global__ __launch_bounds__(256) void attn_bwd_kernel(AttnShape sh, const float* __restrict__ q,
+                                                       const int32_t* __restrict__ slot_row,
                                                        const float* __restrict__ KV,
                                                        const int32_t* __restrict__ cnt,
                                                        const float* __restrict__ prob,
-                                                       const float* __restrict__ dMin, float* __restrict__ dq,
+                                                       const float* __restrict__ dOmat, float* __restrict__ dq,
                                                        float* __restrict__ dKV) {
   extern __shared__ float lds[];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -99,11 +102,12 @@ __global__ __launch_bounds__(256) void attn_bwd_kernel(AttnShape sh, const float
     for (int e = lane; e < 2 * sh.dO; e += 64) row[e] = 0.f;
   }
   if (c == 0) {
-    for (int e = lane; e < sh.dO; e += 64) dq[(size_t)r * sh.ldq + e] = 0.f;
+    for (int e = lane; e < sh.dO; e += 64) dq[(size_t)r * sh.ldo + e] = 0.f;
     return;
   }
   const float scale = 1.0f / sqrtf((float)c);
-  for (int e = lane; e < sh.dO; e += 64) sdo[e] = dMin[(size_t)r * sh.ldm + e];
+  const size_t qrow = slot_row != nullptr ? (size_t)slot_row[r] : (size_t)r;
+  for (int e = lane; e < sh.dO; e += 64) sdo[e] = dOmat[(size_t)r * sh.ldo + e];
   for (int j = 0; j < c; ++j) {
     const float* vrow = KV + ((size_t)r * sh.k + j) * sh.ldkv + sh.dO;
     for (int e = lane; e < sh.dO; e += 64) sV[j * (sh.dO + 1) + e] = vrow[e];
@@ -143,7 +147,7 @@ __global__ __launch_bounds__(256) void attn_bwd_kernel(AttnShape sh, const float
   __builtin_amdgcn_s_waitcnt(0xc07f);
   for (int e = lane; e < sh.dO; e += 64) {
     const int h = e / sh.dh;
-    const float qe = q[(size_t)r * sh.ldq + e], doe = sdo[e];
+    const float qe = q[qrow * sh.ldq + e], doe = sdo[e];
     float dqe = 0.f;
     for (int j = 0; j < c; ++j) {
       const size_t row = ((size_t)r * sh.k + j) * sh.ldkv;
@@ -152,28 +156,30 @@ __global__ __launch_bounds__(256) void attn_bwd_kernel(AttnShape sh, const float
       dKV[row + e] = da * qe;
       dKV[row + sh.dO + e] = sa[h * sh.k + j] * doe;
     }
-    dq[(size_t)r * sh.ldq + e] = dqe;
+    dq[(size_t)r * sh.ldo + e] = dqe;
   }
 }
 
-static AttnShape shape_of(const Dims& d, int R, int ldq, int ldkv, int ldm) {
-  return AttnShape{R, d.k, d.H, d.dO, d.dO / d.H, ldq, ldkv, ldm};
+static AttnShape shape_of(const Dims& d, int R, int ldq, int ldkv, int ldo) {
+  return AttnShape{R, d.k, d.H, d.dO, d.dO / d.H, ldq, ldkv, ldo};
 }
 
-void attn_core_fwd(const Dims& d, int R, const float* q, int ldq, const float* KV, int ldkv, const int32_t* cnt,
-                   float* prob, float* Min, int ldm, hipStream_t s) {
+void attn_core_fwd(const Dims& d, int R, const float* q, int ldq, const int32_t* slot_row, const float* KV, int ldkv,
+                   const int32_t* cnt, float* prob, float* Omat, int ldo, hipStream_t s) {
   if (R <= 0) return;
   const size_t lds = 4 * sizeof(float) * attn_lds_floats(d.k, d.H, d.dO);
-  hipLaunchKernelGGL(attn_fwd_kernel, dim3((R + 3) / 4), dim3(256), lds, s, shape_of(d, R, ldq, ldkv, ldm), q, KV, cnt,
-                     prob, Min);
+  hipLaunchKernelGGL(attn_fwd_kernel, dim3((R + 3) / 4), dim3(256), lds, s, shape_of(d, R, ldq, ldkv, ldo), q, slot_row,
+                     KV, cnt, prob, Omat);
 }
 
-void attn_core_bwd(const Dims& d, int R, const float* q, int ldq, const float* KV, int ldkv, const int32_t* cnt,
-                   const float* prob, const float* dMin, int ldm, float* dq, float* dKV, hipStream_t s) {
+// dq and dOmat share the pitch ldo
+void attn_core_bwd(const Dims& d, int R, const float* q, int ldq, const int32_t* slot_row, const float* KV, int ldkv,
+                   const int32_t* cnt, const float* prob, const float* dOmat, int ldo, float* dq, float* dKV,
+                   hipStream_t s) {
   if (R <= 0) return;
   const size_t lds = 4 * sizeof(float) * attn_lds_floats(d.k, d.H, d.dO);
-  hipLaunchKernelGGL(attn_bwd_kernel, dim3((R + 3) / 4), dim3(256), lds, s, shape_of(d, R, ldq, ldkv, ldm), q, KV, cnt,
-                     prob, dMin, dq, dKV);
+  hipLaunchKernelGGL(attn_bwd_kernel, dim3((R + 3) / 4), dim3(256), lds, s, shape_of(d, R, ldq, ldkv, ldo), q, slot_row,
+                     KV, cnt, prob, dOmat, dq, dKV);
 }
 
 }  // namespace tgnn

@@ -142,22 +142,21 @@ void mask_dz(int R, int dO, const float* dz_in, int p_in, const float* z, int ld
   hipLaunchKernelGGL(mask_dz_kernel, dim3((R * dO + 255) / 256), dim3(256), 0, s, R, dO, dz_in, p_in, z, ldz, dz_out);
 }
 
-__global__ void attn_dx_out_kernel(int R, int RK, int dm, int dO, const float* __restrict__ dMin, int ldm,
-                                   const float* __restrict__ dQsub, const float* __restrict__ dCsub, int ldsub,
+__global__ void attn_dx_out_kernel(int R, int RK, int dm, const float* __restrict__ ds_row, int ldh,
                                    float* __restrict__ d_x_root, float* __restrict__ d_x_nbr) {
   const long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x;
   if (i >= (long long)(R + RK) * dm) return;
   const int row = (int)(i / dm), c = (int)(i - (long long)row * dm);
-  if (row < R) d_x_root[(size_t)row * dm + c] = dMin[(size_t)row * ldm + dO + c] + dQsub[(size_t)row * ldsub + c];
-  else d_x_nbr[(size_t)(row - R) * dm + c] = dCsub[(size_t)(row - R) * ldsub + c];
+  const float x = ds_row[(size_t)row * ldh + c];
+  if (row < R) d_x_root[(size_t)row * dm + c] = x;
+  else d_x_nbr[(size_t)(row - R) * dm + c] = x;
 }
 
-void attn_dx_out(int R, int RK, int dm, int dO, const float* dMin, int ldm, const float* dQsub, const float* dCsub,
-                 int ldsub, float* d_x_root, float* d_x_nbr, hipStream_t s) {
+void attn_dx_out(int R, int RK, int dm, const float* ds_row, int ldh, float* d_x_root, float* d_x_nbr, hipStream_t s) {
   const long long total = (long long)(R + RK) * dm;
   if (total <= 0) return;
-  hipLaunchKernelGGL(attn_dx_out_kernel, dim3((int)((total + 255) / 256)), dim3(256), 0, s, R, RK, dm, dO, dMin, ldm,
-                     dQsub, dCsub, ldsub, d_x_root, d_x_nbr);
+  hipLaunchKernelGGL(attn_dx_out_kernel, dim3((int)((total + 255) / 256)), dim3(256), 0, s, R, RK, dm, ds_row, ldh,
+                     d_x_root, d_x_nbr);
 }
 
 __global__ void zero_kernel(float* p, int n) {

@@ -1,5 +1,5 @@
 // Row gathers (Sec. 3.2.1: fetch node memory and cached mails of root and supporting nodes) fused with
-// the time encoding of the mail (Eq. 1-2), and the assembly of the attention inputs (Eq. 4-6).
+// the time encoding of the mail (Eq. 1-2), and the assembly of the per-slot attention inputs (Eq. 5-6).
 // One wavefront moves one row: 16-byte (or 8-byte) vector loads, every row a contiguous burst.
 #include "tgnn_internal.h"
 #include "device_math.h"
@@ -76,68 +76,74 @@ void gather_rows(const GatherArgs& a, hipStream_t s) {
   else hipLaunchKernelGGL(gather_kernel<1>, dim3(blocks), dim3(256), 0, s, a);
 }
 
-// Rows 0 .. R*k-1: key/value input {s'_w | static_w | e_vw | Phi(dt)} of neighbour slot (r, j);
-// rows R*k .. R*k+R-1: query input {s'_v | static_v | Phi(0)} and the x_v half of the merge input.
+// Per neighbour slot (r, j): the slot's own part of the key/value input of Eq. 5-6, {e_vw | Phi(dt)}.  The
+// node part {s'_w | static_w} is projected once per distinct node elsewhere, so it is not copied here.
+// One wavefront per slot row.
 template <int VEC>
-__global__ __launch_bounds__(256) void attn_assemble_kernel(AttnAssembleArgs a) {
+__global__ __launch_bounds__(256) void assemble_ce_kernel(CeArgs a) {
   const int lane = threadIdx.x & 63;
   const int wpb = blockDim.x >> 6;
   const int RK = a.R * a.k;
-  const int dx = a.dm + a.ds, dkv = dx + a.de + a.dt;
-  for (int row = blockIdx.x * wpb + (threadIdx.x >> 6); row < RK + a.R; row += gridDim.x * wpb) {
-    if (row < RK) {
-      const int r = row / a.k, j = row - r * a.k;
-      float* out = a.Cmat + (size_t)row * a.ldc;
-      if (j >= a.cnt[r]) {
-        wave_zero(out, a.ldc, lane);
-        if (lane == 0) a.dtk[row] = 0.0;
-        continue;
-      }
-      const int srow = a.slot_row ? a.slot_row[a.R + row] : row;
-      wave_copy<VEC>(out, a.s_nbr + (size_t)srow * a.p_s, a.dm, 0, lane);
-      if (a.ds) wave_copy<VEC>(out + a.dm, a.stat + (size_t)a.nbr[row] * a.ds, a.ds, 0, lane);
-      if (a.de) wave_copy<VEC>(out + dx, a.efeat + (size_t)(a.neid ? a.neid[row] : row) * a.de, a.de, 0, lane);
-      const double delta = a.dt_in ? a.dt_in[row]
-                                   : a.root_t[r] - (a.dt_source == 0 ? a.tau_nbr[srow] : a.nts[row]);
-      float* phi = out + dx + a.de;
-      float* ms = a.msin + (size_t)row * a.p_msin;
-      for (int c = lane; c < a.dt; c += 64) {
-        float sn, cs;
-        sincos_reduced(fma((double)a.time_w[c], delta, (double)a.time_b[c]), sn, cs);
-        phi[c] = cs;
-        ms[c] = -sn;
-      }
-      for (int c = dkv + lane; c < a.ldc; c += 64) out[c] = 0.f;
-      if (lane == 0) a.dtk[row] = delta;
-    } else {
-      const int r = row - RK;
-      const int v = a.ds ? a.root_node[r] : 0;
-      float* qi = a.Qin + (size_t)r * a.ldq;
-      float* mi = a.Min + (size_t)r * a.ldm + a.dO;
-      const float* sv = a.s_root + (size_t)(a.slot_row ? a.slot_row[r] : r) * a.p_s;
-      wave_copy<VEC>(qi, sv, a.dm, 0, lane);
-      wave_copy<VEC>(mi, sv, a.dm, 0, lane);
-      if (a.ds) {
-        wave_copy<VEC>(qi + a.dm, a.stat + (size_t)v * a.ds, a.ds, 0, lane);
-        wave_copy<VEC>(mi + a.dm, a.stat + (size_t)v * a.ds, a.ds, 0, lane);
-      }
-      for (int c = lane; c < a.dt; c += 64) qi[dx + c] = time_enc(0.0, a.time_w[c], a.time_b[c]);
-      for (int c = dx + a.dt + lane; c < a.ldq; c += 64) qi[c] = 0.f;
-      for (int c = a.dO + dx + lane; c < a.ldm; c += 64) a.Min[(size_t)r * a.ldm + c] = 0.f;
+  for (int row = blockIdx.x * wpb + (threadIdx.x >> 6); row < RK; row += gridDim.x * wpb) {
+    const int r = row / a.k, j = row - r * a.k;
+    float* out = a.CE + (size_t)row * a.ldce;
+    if (j >= a.cnt[r]) {
+      wave_zero(out, a.ldce, lane);
+      if (lane == 0) a.dtk[row] = 0.0;
+      continue;
     }
+    if (a.de) wave_copy<VEC>(out, a.efeat + (size_t)(a.neid ? a.neid[row] : row) * a.de, a.de, 0, lane);
+    double delta;
+    if (a.dt_in) delta = a.dt_in[row];
+    else if (a.dt_source != 0) delta = a.root_t[r] - a.nts[row];
+    else delta = a.root_t[r] - a.tau_nbr[a.slot_row ? a.slot_row[a.R + row] : row];
+    float* phi = out + a.de;
+    float* ms = a.msin + (size_t)row * a.p_msin;
+    for (int c = lane; c < a.dt; c += 64) {
+      float sn, cs;
+      sincos_reduced(fma((double)a.time_w[c], delta, (double)a.time_b[c]), sn, cs);
+      phi[c] = cs;
+      ms[c] = -sn;
+    }
+    for (int c = a.de + a.dt + lane; c < a.ldce; c += 64) out[c] = 0.f;
+    if (lane == 0) a.dtk[row] = delta;
   }
 }
 
-void attn_assemble(const AttnAssembleArgs& a, hipStream_t s) {
-  const int rows = a.R * a.k + a.R;
+void assemble_ce(const CeArgs& a, hipStream_t s) {
+  const int rows = a.R * a.k;
   if (rows <= 0) return;
-  const int vec = pick_vec({a.dm, a.ds ? a.ds : 4, a.de ? a.de : 4, a.dm + a.ds + a.de, a.dO, a.p_s,
-                            (long long)((uintptr_t)a.stat / 4), (long long)((uintptr_t)a.efeat / 4),
-                            (long long)((uintptr_t)a.s_root / 4), (long long)((uintptr_t)a.s_nbr / 4)});
+  const int vec = pick_vec({a.de ? a.de : 4, (long long)((uintptr_t)a.efeat / 4)});
   const int blocks = (rows + 3) / 4;
-  if (vec == 4) hipLaunchKernelGGL(attn_assemble_kernel<4>, dim3(blocks), dim3(256), 0, s, a);
-  else if (vec == 2) hipLaunchKernelGGL(attn_assemble_kernel<2>, dim3(blocks), dim3(256), 0, s, a);
-  else hipLaunchKernelGGL(attn_assemble_kernel<1>, dim3(blocks), dim3(256), 0, s, a);
+  if (vec == 4) hipLaunchKernelGGL(assemble_ce_kernel<4>, dim3(blocks), dim3(256), 0, s, a);
+  else if (vec == 2) hipLaunchKernelGGL(assemble_ce_kernel<2>, dim3(blocks), dim3(256), 0, s, a);
+  else hipLaunchKernelGGL(assemble_ce_kernel<1>, dim3(blocks), dim3(256), 0, s, a);
+}
+
+// Xrow[r] = x_root[r] (r < R); Xrow[R + r k + j] = x_nbr[r k + j] for j < cnt[r], zero otherwise; pad columns zero.
+__global__ __launch_bounds__(256) void stage_x_rows_kernel(int R, int k, int dx, const float* __restrict__ x_root,
+                                                           const float* __restrict__ x_nbr,
+                                                           const int32_t* __restrict__ cnt, float* __restrict__ Xrow,
+                                                           int ldxr) {
+  const int lane = threadIdx.x & 63;
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= R + R * k) return;
+  const float* src;
+  if (row < R) {
+    src = x_root + (size_t)row * dx;
+  } else {
+    const int sl = row - R, r = sl / k, j = sl - r * k;
+    src = j < cnt[r] ? x_nbr + (size_t)sl * dx : nullptr;
+  }
+  float* out = Xrow + (size_t)row * ldxr;
+  for (int c = lane; c < ldxr; c += 64) out[c] = (src != nullptr && c < dx) ? src[c] : 0.f;
+}
+
+void stage_x_rows(int R, int k, int dx, const float* x_root, const float* x_nbr, const int32_t* cnt, float* Xrow,
+                  int ldxr, hipStream_t s) {
+  const int rows = R + R * k;
+  if (rows <= 0) return;
+  hipLaunchKernelGGL(stage_x_rows_kernel, dim3((rows + 3) / 4), dim3(256), 0, s, R, k, dx, x_root, x_nbr, cnt, Xrow, ldxr);
 }
 
 }  // namespace tgnn

@@ -32,7 +32,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, (TN <= 5
                                                       const float* __restrict__ B, int ldb,
                                                       const float* __restrict__ bias, float* __restrict__ C, int ldc,
                                                       int M, int N, int Kp, int n_store, int relu,
-                                                      const int* __restrict__ m_dev, int col_tiles) {
+                                                      const int* __restrict__ m_dev, int col_tiles, RowAdd add) {
   constexpr int BM = 64, BN = 16 * TN;
   // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  The column tiles of one row tile
   // read the same rows of A, so they are given consecutive slots of one XCD.
@@ -141,6 +141,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, (TN <= 5
     }
   }
 
+  // rows this lane writes: m0 + wave * 16 + lg * 4 + v; their gather-add source rows (or -1)
+  int arow[4];
+#pragma unroll
+  for (int v = 0; v < 4; ++v) {
+    const int row = m0 + wave * 16 + lg * 4 + v;
+    arow[v] = -1;
+    if (add.src != nullptr && row < M) arow[v] = add.index != nullptr ? add.index[row] : row + add.row0;
+  }
 #pragma unroll
   for (int b = 0; b < TN; ++b) {
     const int col = n0 + b * 16 + li;
@@ -153,6 +161,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, (TN <= 5
         float x = 0.f;
         if (col < N) {
           x = acc[b][v] + bv;
+          if (arow[v] >= 0) x += add.src[(size_t)arow[v] * add.ld + col];
           if (relu) x = fmaxf(x, 0.f);
         }
         C[(size_t)row * ldc + col] = x;
@@ -163,166 +172,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, (TN <= 5
 
 template <int TN>
 static void launch_nt(const float* A, int lda, const float* B, int ldb, const float* bias, float* C, int ldc, int M,
-                      int N, int Kp, int n_store, bool relu, hipStream_t s, const int* m_dev) {
+                      int N, int Kp, int n_store, bool relu, hipStream_t s, const int* m_dev, const RowAdd& add) {
   constexpr int BM = 64, BN = 16 * TN;
   const int col_tiles = (n_store + BN - 1) / BN;
   const int row_tiles8 = ((M + BM - 1) / BM + 7) & ~7;
   hipLaunchKernelGGL((gemm_nt_kernel<TN>), dim3(col_tiles * row_tiles8), dim3(256), 0, s, A, lda, B, ldb, bias, C, ldc, M,
-                     N, Kp, n_store, relu ? 1 : 0, m_dev, col_tiles);
-}
-
-// ------------------------------------------------------------------------------------------------
-// NT with v_mfma_f32_32x32x2_f32 for problems with many rows: lane l supplies A[i = l%32][kk = l/32] and
-// B[kk = l/32][j = l%32]; accumulator v of 16 holds D[i = 8*(v/4) + 4*(l/32) + v%4][j = l%32].  Half the LDS
-// reads per flop of the 16x16 kernel and a higher sustained issue rate.  A workgroup is 4 waves stacked
-// along M (32 rows each, BM = 128) and 32*TNB columns; a stage is 16 k-columns = two 8-wide slabs, of which
-// lane half g reads k = 4g .. 4g+3 as one float4.  LDS rows are 16 floats = 4 chunks; chunk c of row r sits at
-// c ^ ((r >> 2) & 3), which makes both the operand reads and the stage stores bank-conflict free.
-// ------------------------------------------------------------------------------------------------
-typedef float floatx16 __attribute__((ext_vector_type(16)));
-constexpr int N32_BK = 16;
-__device__ __forceinline__ int n32_swz(int row, int chunk) { return row * N32_BK + ((chunk ^ ((row >> 2) & 3)) << 2); }
-
-template <int TNB>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, (TNB <= 2 ? 4 : 2)))) void gemm_nt32_kernel(
-    const float* __restrict__ A, int lda, const float* __restrict__ B, int ldb, const float* __restrict__ bias,
-    float* __restrict__ C, int ldc, int M, int N, int Kp, int n_store, int relu, const int* __restrict__ m_dev,
-    int col_tiles) {
-  constexpr int BM = 128, BN = 32 * TNB;
-  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-  const int row_tile = (slot / col_tiles) * 8 + xcd, col_tile = slot % col_tiles;
-  if (m_dev != nullptr) M = min(M, *m_dev);
-  if (row_tile * BM >= M) return;
-  constexpr int A_PER = BM * 4 / 256, B_F4 = BN * 4;
-  constexpr int B_PER = (B_F4 + 255) / 256;
-  __shared__ __attribute__((aligned(16))) float As[2][BM * N32_BK];
-  __shared__ __attribute__((aligned(16))) float Bs[2][BN * N32_BK];
-
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int li = lane & 31, lg = lane >> 5;
-  const int m0 = row_tile * BM, n0 = col_tile * BN;
-
-  floatx16 acc[TNB];
-#pragma unroll
-  for (int b = 0; b < TNB; ++b)
-#pragma unroll
-    for (int v = 0; v < 16; ++v) acc[b][v] = 0.f;
-
-  const float* pa[A_PER];
-  const float* pb[B_PER];
-#pragma unroll
-  for (int u = 0; u < A_PER; ++u) {
-    const int f = tid + u * 256;
-    pa[u] = A + (size_t)min(m0 + (f >> 2), M - 1) * lda + (f & 3) * 4;
-  }
-#pragma unroll
-  for (int u = 0; u < B_PER; ++u) {
-    const int f = min(tid + u * 256, B_F4 - 1);
-    pb[u] = B + (size_t)min(n0 + (f >> 2), N - 1) * ldb + (f & 3) * 4;
-  }
-  struct Regs {
-    floatx4 a[A_PER], b[B_PER];
-  };
-  Regs r0, r1;
-  auto gload = [&](Regs& r, int k0) __attribute__((always_inline)) {
-#pragma unroll
-    for (int u = 0; u < A_PER; ++u) r.a[u] = *reinterpret_cast<const floatx4*>(pa[u] + k0);
-#pragma unroll
-    for (int u = 0; u < B_PER; ++u) r.b[u] = *reinterpret_cast<const floatx4*>(pb[u] + k0);
-  };
-  auto sstore = [&](const Regs& r, int buf) __attribute__((always_inline)) {
-#pragma unroll
-    for (int u = 0; u < A_PER; ++u) {
-      const int f = tid + u * 256;
-      *reinterpret_cast<floatx4*>(&As[buf][n32_swz(f >> 2, f & 3)]) = r.a[u];
-    }
-#pragma unroll
-    for (int u = 0; u < B_PER; ++u) {
-      const int f = tid + u * 256;
-      if (B_F4 % 256 == 0 || f < B_F4) *reinterpret_cast<floatx4*>(&Bs[buf][n32_swz(f >> 2, f & 3)]) = r.b[u];
-    }
-  };
-  auto compute = [&](int buf) __attribute__((always_inline)) {
-#pragma unroll
-    for (int h = 0; h < 2; ++h) {  // two 8-wide k slabs per stage
-      const floatx4 a4 = *reinterpret_cast<const floatx4*>(&As[buf][n32_swz(wave * 32 + li, h * 2 + lg)]);
-      floatx4 b4[TNB];
-#pragma unroll
-      for (int b = 0; b < TNB; ++b)
-        b4[b] = *reinterpret_cast<const floatx4*>(&Bs[buf][n32_swz(b * 32 + li, h * 2 + lg)]);
-#pragma unroll
-      for (int b = 0; b < TNB; ++b) acc[b] = __builtin_amdgcn_mfma_f32_32x32x2f32(a4.x, b4[b].x, acc[b], 0, 0, 0);
-#pragma unroll
-      for (int b = 0; b < TNB; ++b) acc[b] = __builtin_amdgcn_mfma_f32_32x32x2f32(a4.y, b4[b].y, acc[b], 0, 0, 0);
-#pragma unroll
-      for (int b = 0; b < TNB; ++b) acc[b] = __builtin_amdgcn_mfma_f32_32x32x2f32(a4.z, b4[b].z, acc[b], 0, 0, 0);
-#pragma unroll
-      for (int b = 0; b < TNB; ++b) acc[b] = __builtin_amdgcn_mfma_f32_32x32x2f32(a4.w, b4[b].w, acc[b], 0, 0, 0);
-    }
-  };
-
-  const int nk = Kp / N32_BK;
-  gload(r0, 0);
-  gload(r1, nk > 1 ? N32_BK : 0);
-  sstore(r0, 0);
-  __syncthreads();
-  int kt = 0;
-  for (; kt + 3 < nk; kt += 2) {
-    gload(r0, (kt + 2) * N32_BK);
-    compute(0);
-    sstore(r1, 1);
-    __syncthreads();
-    gload(r1, (kt + 3) * N32_BK);
-    compute(1);
-    sstore(r0, 0);
-    __syncthreads();
-  }
-  const int rem = nk - kt;
-  if (rem == 3) gload(r0, (kt + 2) * N32_BK);
-  compute(0);
-  if (rem >= 2) {
-    sstore(r1, 1);
-    __syncthreads();
-    compute(1);
-    if (rem == 3) {
-      sstore(r0, 0);
-      __syncthreads();
-      compute(0);
-    }
-  }
-
-#pragma unroll
-  for (int b = 0; b < TNB; ++b) {
-    const int col = n0 + b * 32 + li;
-    if (col >= n_store) continue;
-    const float bv = (bias != nullptr && col < N) ? bias[col] : 0.f;
-#pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      const int row = m0 + wave * 32 + 8 * (v >> 2) + 4 * lg + (v & 3);
-      if (row < M) {
-        float x = 0.f;
-        if (col < N) {
-          x = acc[b][v] + bv;
-          if (relu) x = fmaxf(x, 0.f);
-        }
-        C[(size_t)row * ldc + col] = x;
-      }
-    }
-  }
-}
-
-template <int TNB>
-static void launch_nt32(const float* A, int lda, const float* B, int ldb, const float* bias, float* C, int ldc, int M,
-                        int N, int Kp, int n_store, bool relu, hipStream_t s, const int* m_dev) {
-  constexpr int BM = 128, BN = 32 * TNB;
-  const int col_tiles = (n_store + BN - 1) / BN;
-  const int row_tiles8 = ((M + BM - 1) / BM + 7) & ~7;
-  hipLaunchKernelGGL((gemm_nt32_kernel<TNB>), dim3(col_tiles * row_tiles8), dim3(256), 0, s, A, lda, B, ldb, bias, C, ldc,
-                     M, N, Kp, n_store, relu ? 1 : 0, m_dev, col_tiles);
+                     N, Kp, n_store, relu ? 1 : 0, m_dev, col_tiles, add);
 }
 
 void gemm_nt(const float* A, int lda, const float* B, int ldb, const float* bias, float* C, int ldc, int M, int N,
-             int Kp, int n_store, bool relu, hipStream_t s, const int* m_dev) {
+             int Kp, int n_store, bool relu, hipStream_t s, const int* m_dev, const RowAdd& add) {
   if (M <= 0 || N <= 0) return;
   if (n_store < N) n_store = N;
   // Column-tile width in 16-wide MFMA blocks, from sweeps on MI355X: problems of a few thousand rows want the
@@ -341,14 +200,8 @@ void gemm_nt(const float* A, int lda, const float* B, int ldb, const float* bias
     }
   }
   if (const char* e = getenv("TGNN_NT_TN")) best = atoi(e);
-  if (const char* e = getenv("TGNN_NT32")) {   // experiment switch: 32x32x2 kernel with the given column blocks
-    const int t = atoi(e);
-    if (t == 1) { launch_nt32<1>(A, lda, B, ldb, bias, C, ldc, M, N, Kp, n_store, relu, s, m_dev); return; }
-    if (t == 2) { launch_nt32<2>(A, lda, B, ldb, bias, C, ldc, M, N, Kp, n_store, relu, s, m_dev); return; }
-    if (t == 4) { launch_nt32<4>(A, lda, B, ldb, bias, C, ldc, M, N, Kp, n_store, relu, s, m_dev); return; }
-  }
 #define TGNN_NT_CASE(TNV) \
-  case TNV: launch_nt<TNV>(A, lda, B, ldb, bias, C, ldc, M, N, Kp, n_store, relu, s, m_dev); break;
+  case TNV: launch_nt<TNV>(A, lda, B, ldb, bias, C, ldc, M, N, Kp, n_store, relu, s, m_dev, add); break;
   switch (best) {
     TGNN_NT_CASE(10)
     TGNN_NT_CASE(7)

@@ -16,11 +16,13 @@ __device__ __forceinline__ float tanhf_(float x) {
 __global__ void gru_fwd_kernel(int n_max, const int* __restrict__ n_dev, int dm, int ldh, int ld3,
                                const float* __restrict__ gi, const float* __restrict__ gh,
                                const float* __restrict__ Hm, const int32_t* __restrict__ has,
-                               float* __restrict__ gates, float* __restrict__ s_new, float* __restrict__ ds_zero) {
+                               float* __restrict__ gates, float* __restrict__ x_out, int ld_x,
+                               const float* __restrict__ stat, int ds, const int32_t* __restrict__ gid, int N,
+                               float* __restrict__ zero_buf, int zero_w) {
   const int n = n_dev ? min(n_max, *n_dev) : n_max;
-  const long long total = (long long)n * dm;
-  for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < total;
-       i += (long long)gridDim.x * blockDim.x) {
+  const long long stride = (long long)gridDim.x * blockDim.x;
+  const long long first = blockIdx.x * (long long)blockDim.x + threadIdx.x;
+  for (long long i = first; i < (long long)n * dm; i += stride) {
     const int row = (int)(i / dm), c = (int)(i - (long long)row * dm);
     const float h = Hm[(size_t)row * ldh + c];
     float out = h;
@@ -38,18 +40,27 @@ __global__ void gru_fwd_kernel(int n_max, const int* __restrict__ n_dev, int dm,
       g[2 * ldh + c] = nn;
       g[3 * ldh + c] = hn;
     }
-    s_new[(size_t)row * ldh + c] = out;
-    if (ds_zero) ds_zero[(size_t)row * ldh + c] = 0.f;
+    x_out[(size_t)row * ld_x + c] = out;
+  }
+  if (stat != nullptr) {   // static node memory (Sec. 3.1) rides along as columns d_m .. d_m + d_s of the node row
+    for (long long i = first; i < (long long)n * ds; i += stride) {
+      const int row = (int)(i / ds), c = (int)(i - (long long)row * ds);
+      x_out[(size_t)row * ld_x + dm + c] = stat[(size_t)(gid[row] % N) * ds + c];
+    }
+  }
+  if (zero_buf != nullptr) {
+    for (long long i = first; i < (long long)n * zero_w; i += stride) zero_buf[i] = 0.f;
   }
 }
 
 void gru_gates_fwd(const Dims& d, int n, const int* n_dev, const float* gi, const float* gh, const float* Hm,
-                   const int32_t* has, float* gates, float* s_new, float* ds_zero, hipStream_t s) {
+                   const int32_t* has, float* gates, float* x_out, int ld_x, const float* stat, const int32_t* gid,
+                   float* zero_buf, int zero_w, hipStream_t s) {
   if (n <= 0) return;
   const long long total = (long long)n * d.dm;
   const int blocks = (int)((total + 255) / 256);
   hipLaunchKernelGGL(gru_fwd_kernel, dim3(blocks), dim3(256), 0, s, n, n_dev, d.dm, d.ldh, d.ld3, gi, gh, Hm, has, gates,
-                     s_new, ds_zero);
+                     x_out, ld_x, stat, d.ds, gid, d.N, zero_buf, zero_w);
 }
 
 // From the gradient reaching s' of a row to the gradients of the gate pre-activations.  The chain stops at
@@ -144,6 +155,47 @@ void time_grad(const float* dphi, int ld, int col0, const float* msin, int p_msi
   const int rpb = (((n + TG_BLOCKS - 1) / TG_BLOCKS) + 3) & ~3;
   hipLaunchKernelGGL(time_grad_kernel, dim3(TG_BLOCKS), dim3(256), 0, s, dphi, ld, col0, msin, p_msin, delta, n, n_dev,
                      rpb, dt, time_b, partial);
+}
+
+// The query's time encoding is Phi(0) = cos(time_b): its gradient, and that of the columns of W_q which
+// multiply it, need only the column sums of dq.
+// QPHI_BLOCKS blocks take a range of roots each and write one partial; the remaining partial slots of the
+// region are cleared (time_grad_finish adds all TG_BLOCKS of them).
+constexpr int QPHI_BLOCKS = 64;
+__global__ __launch_bounds__(256) void qphi_grad_kernel(const float* __restrict__ dq, int ld, int R, int dO,
+                                                        const float* __restrict__ wq, int dq_w, int dx, int dt,
+                                                        const float* __restrict__ time_b,
+                                                        float* __restrict__ partial, float* __restrict__ g_wq) {
+  __shared__ float colsum[256];
+  float* out = partial + (size_t)blockIdx.x * 2 * dt;
+  if (blockIdx.x >= QPHI_BLOCKS) {
+    for (int c = threadIdx.x; c < 2 * dt; c += blockDim.x) out[c] = 0.f;
+    return;
+  }
+  const int per = (R + QPHI_BLOCKS - 1) / QPHI_BLOCKS;
+  const int r0 = min(R, (int)blockIdx.x * per), r1 = min(R, r0 + per);
+  for (int n = threadIdx.x; n < dO; n += blockDim.x) {   // d_o <= 256
+    float a = 0.f;
+    for (int r = r0; r < r1; ++r) a += dq[(size_t)r * ld + n];
+    colsum[n] = a;
+  }
+  __syncthreads();
+  for (int c = threadIdx.x; c < dt; c += blockDim.x) {
+    float v = 0.f;
+    for (int n = 0; n < dO; ++n) v += colsum[n] * wq[(size_t)n * dq_w + dx + c];
+    float sn, cs;
+    sincos_reduced((double)time_b[c], sn, cs);
+    out[c] = 0.f;
+    out[dt + c] = -sn * v;
+    // weight gradient of the Phi(0) columns of W_q: (sum_r dq[r, n]) cos(time_b[c])
+    for (int n = 0; n < dO; ++n) atomicAdd(g_wq + (size_t)n * dq_w + dx + c, colsum[n] * cs);
+  }
+}
+
+void qphi_grad(const float* dq, int ld, int R, int dO, const float* wq, int dq_w, int dx, int dt, const float* time_b,
+               float* partial, float* g_wq, hipStream_t s) {
+  hipLaunchKernelGGL(qphi_grad_kernel, dim3(TG_BLOCKS), dim3(256), 0, s, dq, ld, R, dO, wq, dq_w, dx, dt, time_b, partial,
+                     g_wq);
 }
 
 // grid (ceil(2 dt / 32), TGF_SPLIT); block = 32 columns x 32 partial groups

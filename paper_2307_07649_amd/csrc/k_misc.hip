@@ -2,6 +2,7 @@
 #include <string.h>
 
 #include "tgnn_internal.h"
+#include "device_math.h"
 
 namespace tgnn {
 
@@ -34,11 +35,24 @@ __global__ void prologue_kernel(PrologueArgs a) {
       *a.epoch += 1ull;
       *a.ucount = 0;
     }
+  } else if (a.bq_out != nullptr) {
+    // the query's time encoding Phi(0) = cos(time_b) does not depend on the root: fold W_q Phi(0) into the
+    // bias.  One wavefront per output row, rows dealt over blocks 1 .. gridDim.x - 1 of this grid row.
+    const int lane = threadIdx.x & 63;
+    const int wv = (blockIdx.x - 1) * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    const int n_wv = (gridDim.x - 1) * (blockDim.x >> 6);
+    for (int n = wv; n < a.dO; n += n_wv) {
+      float acc = 0.f;
+      for (int c = lane; c < a.dt; c += 64) acc += a.wq[(size_t)n * a.dq + a.dx + c] * time_enc(0.0, 0.f, a.time_b[c]);
+      for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o);
+      if (lane == 0) a.bq_out[n] = a.bq[n] + acc;
+    }
   }
 }
 
-// Padded copies of the weights (row pitch = the pitch of the activation matrix they multiply) and the
-// transposed copies / column subsets that the data-gradient GEMMs read.
+// Padded copies of the weights (row pitch = the pitch of the activation matrix they multiply), split into
+// the blocks that multiply the node rows, the per-slot rows and the attention output, and the transposed
+// copies that the data-gradient GEMMs read.
 void prologue_fill(tgnn_ctx* ctx, const tgnn_params* p, const BatchSet* bs, const SgdSet* sgd, const SgdSet* zero,
                    float* loss, PrologueArgs& pa) {
   const Dims& d = ctx->d;
@@ -50,31 +64,41 @@ void prologue_fill(tgnn_ctx* ctx, const tgnn_params* p, const BatchSet* bs, cons
     pa.d[n++] = PackDesc{src, dst, rows, cols, zero_to, ldd, srs, scs};
   };
   if (p != nullptr) {
-    const int dO = d.dO, dm = d.dm;
+    const int dO = d.dO, dm = d.dm, dx = d.dx, dkv = d.dkv, dmrg = d.dO + d.dx, half = d.ldkv;
     add(p->gru_wih, w.Wih_p, 3 * dm, d.d_in, d.ldx, d.ldx, d.d_in, 1);
     add(p->gru_whh, w.Whh_p, 3 * dm, dm, d.ldh, d.ldh, dm, 1);
-    add(p->wk, w.Wkv_p, dO, d.dkv, d.ldc, d.ldc, d.dkv, 1);
-    add(p->wv, w.Wkv_p + (size_t)dO * d.ldc, dO, d.dkv, d.ldc, d.ldc, d.dkv, 1);
-    add(p->wq, w.Wq_p, dO, d.dq, d.ldq, d.ldq, d.dq, 1);
-    add(p->wo, w.Wo_p, dO, dO + d.dx, d.ldm, d.ldm, dO + d.dx, 1);
+    // node part of every projection of x = {s' | static}: rows {W_k ; W_v} then, from row `half`, {W_q ; W_o}
+    // (rows 2 d_o .. half stay zero); row pitch = the pitch of the node rows
+    add(p->wk, w.Wx, dO, dx, d.ldxr, d.ldxr, dkv, 1);
+    add(p->wv, w.Wx + (size_t)dO * d.ldxr, dO, dx, d.ldxr, d.ldxr, dkv, 1);
+    add(p->wq, w.Wx + (size_t)half * d.ldxr, dO, dx, d.ldxr, d.ldxr, d.dq, 1);
+    add(p->wo + dO, w.Wx + (size_t)(half + dO) * d.ldxr, dO, dx, d.ldxr, d.ldxr, dmrg, 1);
+    // its transpose, dynamic columns only: WxT[c, j] = Wx[j, c], c < d_m
+    add(p->wk, w.WxT, dm, dO, dO, d.ldp, 1, dkv);
+    add(p->wv, w.WxT + dO, dm, dO, dO, d.ldp, 1, dkv);
+    add(p->wq, w.WxT + half, dm, dO, dO, d.ldp, 1, d.dq);
+    add(p->wo + dO, w.WxT + half + dO, dm, dO, dO, d.ldp, 1, dmrg);
+    // per-slot part {e | Phi} of the key/value projections and the transpose of its Phi columns
+    add(p->wk + dx, w.Wce, dO, d.de + d.dt, d.ldce, d.ldce, dkv, 1);
+    add(p->wv + dx, w.Wce + (size_t)dO * d.ldce, dO, d.de + d.dt, d.ldce, d.ldce, dkv, 1);
+    add(p->wk + dx + d.de, w.WceT_phi, d.dt, dO, dO, d.ldkv, 1, dkv);
+    add(p->wv + dx + d.de, w.WceT_phi + dO, d.dt, dO, d.ldkv - dO, d.ldkv, 1, dkv);
+    // merge layer, attention-output columns, and their transpose
+    add(p->wo, w.Wo_o, dO, dO, d.ldh, d.ldh, dmrg, 1);
+    add(p->wo, w.WoT_o, dO, dO, d.ldh, d.ldh, 1, dmrg);
     // decoder input is {z_a | z_b}: weights side by side
     add(p->dec_ws, w.Wdec_p, dO, dO, dO, d.ldkv, dO, 1);
     add(p->dec_wd, w.Wdec_p + dO, dO, dO, d.ldkv - dO, d.ldkv, dO, 1);
     // transposes: XT[c, n] = X[n, c]
     add(p->dec_ws, w.WdecT, dO, dO, d.ldh, d.ldh, 1, dO);
     add(p->dec_wd, w.WdecT + (size_t)dO * d.ldh, dO, dO, d.ldh, d.ldh, 1, dO);
-    add(p->wo, w.WoT, dO + d.dx, dO, d.ldh, d.ldh, 1, dO + d.dx);
-    // columns of {W_k ; W_v} that multiply the dynamic memory (first d_m) and the time encoding (last d_t)
-    const int phi_kv = d.dx + d.de;
-    add(p->wk, w.WkvT_sub, dm, dO, dO, d.ldkv, 1, d.dkv);
-    add(p->wv, w.WkvT_sub + dO, dm, dO, d.ldkv - dO, d.ldkv, 1, d.dkv);
-    add(p->wk + phi_kv, w.WkvT_sub + (size_t)dm * d.ldkv, d.dt, dO, dO, d.ldkv, 1, d.dkv);
-    add(p->wv + phi_kv, w.WkvT_sub + (size_t)dm * d.ldkv + dO, d.dt, dO, d.ldkv - dO, d.ldkv, 1, d.dkv);
-    add(p->wq, w.WqT_sub, dm, dO, d.ldh, d.ldh, 1, d.dq);
-    add(p->wq + d.dx, w.WqT_sub + (size_t)dm * d.ldh, d.dt, dO, d.ldh, d.ldh, 1, d.dq);
     add(p->gru_wih + 2 * dm, w.WihT_phi, d.dt, 3 * dm, d.ld3, d.ld3, 1, d.d_in);
-    add(p->bk, w.bkv_p, 1, dO, dO, 2 * dO, 0, 1);
-    add(p->bv, w.bkv_p + dO, 1, dO, dO, 2 * dO, 0, 1);
+    // biases of the per-node projections: {b_k | b_v || b_q + W_q Phi(0) | b_o}
+    add(p->bk, w.bias_x, 1, dO, dO, d.ldp, 0, 1);
+    add(p->bv, w.bias_x + dO, 1, dO, dO, d.ldp, 0, 1);
+    add(p->bo, w.bias_x + half + dO, 1, dO, dO, d.ldp, 0, 1);
+    pa.bq = p->bq; pa.wq = p->wq; pa.time_b = p->time_b; pa.bq_out = w.bias_x + half;
+    pa.dO = dO; pa.dq = d.dq; pa.dx = dx; pa.dt = d.dt;
   }
   pa.n_pack = n;
   if (zero) pa.zero = *zero;

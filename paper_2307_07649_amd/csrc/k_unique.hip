@@ -1,7 +1,8 @@
 // Distinct-node bookkeeping of a step.  UPDT (Eq. 3) depends only on a node's stored state, so every slot
 // that refers to the same (replica, node) gets the same s'.  The step therefore evaluates the GRU once per
 // distinct node ("row") and lets slots point at rows; this is an exact shortcut of the per-reference
-// re-computation of Sec. 3.2.1.  The backward pass needs, per row, the sum of the gradients of its slots:
+// re-computation of Sec. 3.2.1.  The attention projections are linear in their input, so their node part
+// is taken per row as well.  The backward pass needs, per row, the sum of the gradients of its slots:
 // slots are counting-sorted by row and reduced in fixed chunks, so a node referenced thousands of times
 // (power-law graphs) costs a few dozen atomic row updates instead of thousands.
 #include "tgnn_internal.h"
@@ -99,20 +100,19 @@ void uniq_sort(tgnn_ctx* ctx, int S, hipStream_t s) {
   hipLaunchKernelGGL(uniq_fill_kernel, dim3((S + 255) / 256), dim3(256), 0, s, S, w.slot_row, w.cursor, w.sorted);
 }
 
-// ds_row[row, c] += sum over the row's slots of the gradient reaching s' of that slot:
-//   root slot r      : dMin[r, dO + c] + dQsub[r, c]     (merge layer + query)
-//   neighbour slot   : dCsub[slot - R, c]                (key/value input)
-// One wavefront owns SEG_CHUNK consecutive entries of the row-sorted slot list.
+// Per-row sums of the slot gradients that reach the per-node projections P = {K | V || q | merge}:
+//   neighbour slot s : dP[row, 0 .. 2 d_o)              += dKV[s - R]
+//   root slot r      : dP[row, half .. half + 2 d_o)     += {dq[r] | dz[r]}          (half = the pitch of dKV)
+// One wavefront owns SEG_CHUNK consecutive entries of the row-sorted slot list; runs of one row are summed
+// in registers and leave as one atomic row update per half.
 constexpr int SEG_CHUNK = 16;
-__global__ __launch_bounds__(256) void seg_reduce_kernel(int R, int dm, int dO, const int32_t* __restrict__ ucount,
+__global__ __launch_bounds__(256) void seg_reduce_kernel(int R, int dO, const int32_t* __restrict__ ucount,
                                                          const int32_t* __restrict__ rowptr,
                                                          const int32_t* __restrict__ sorted,
                                                          const int32_t* __restrict__ slot_row,
-                                                         const int32_t* __restrict__ has,
-                                                         const float* __restrict__ dMin, int ldm,
-                                                         const float* __restrict__ dQsub,
-                                                         const float* __restrict__ dCsub, int ldsub,
-                                                         float* __restrict__ ds_row, int ldh) {
+                                                         const float* __restrict__ dq, const float* __restrict__ dz,
+                                                         int ldh, const float* __restrict__ dKV, int ldkv,
+                                                         float* __restrict__ dP, int ldp) {
   const int lane = threadIdx.x & 63;
   const int chunk = blockIdx.x * 4 + (threadIdx.x >> 6);
   const int total = rowptr[*ucount];
@@ -124,51 +124,66 @@ __global__ __launch_bounds__(256) void seg_reduce_kernel(int R, int dm, int dO, 
   if (lane < n) {
     my_slot = sorted[p0 + lane];
     my_row = slot_row[my_slot];
-    if (!has[my_row]) my_row = -1;   // no mail consumed: s' is the stored memory, a constant
   }
-  // all row loads of the chunk are issued before any is consumed
-  float v[SEG_CHUNK][4];
-  int rows[SEG_CHUNK];
+  int slots[SEG_CHUNK], rows[SEG_CHUNK];
 #pragma unroll
   for (int i = 0; i < SEG_CHUNK; ++i) {
-    const int slot = __shfl(my_slot, i);
+    slots[i] = __shfl(my_slot, i);
     rows[i] = __shfl(my_row, i);
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const int c = lane + 64 * q;
-      float x = 0.f;
-      if (rows[i] >= 0 && c < dm) {
-        if (slot < R) x = dMin[(size_t)slot * ldm + dO + c] + dQsub[(size_t)slot * ldsub + c];
-        else x = dCsub[(size_t)(slot - R) * ldsub + c];
-      }
-      v[i][q] = x;
-    }
   }
-  float acc[4] = {0.f, 0.f, 0.f, 0.f};
-  int cur = -1;
+  for (int cb = 0; cb < 2 * dO; cb += 256) {   // 256 columns per pass, 4 per lane
+    // all row loads of the chunk are issued before any is consumed
+    float v[SEG_CHUNK][4];
 #pragma unroll
-  for (int i = 0; i < SEG_CHUNK; ++i) {
-    if (rows[i] != cur) {
-      if (cur >= 0) {
+    for (int i = 0; i < SEG_CHUNK; ++i) {
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int c = lane + 64 * q;
-          if (c < dm) atomicAdd(ds_row + (size_t)cur * ldh + c, acc[q]);
+      for (int q = 0; q < 4; ++q) {
+        const int c = cb + lane + 64 * q;
+        float x = 0.f;
+        if (rows[i] >= 0 && c < 2 * dO) {
+          const int slot = slots[i];
+          if (slot < R) x = c < dO ? dq[(size_t)slot * ldh + c] : dz[(size_t)slot * ldh + (c - dO)];
+          else x = dKV[(size_t)(slot - R) * ldkv + c];
+        }
+        v[i][q] = x;
+      }
+    }
+    float akv[4] = {0.f, 0.f, 0.f, 0.f}, aqm[4] = {0.f, 0.f, 0.f, 0.f};
+    bool any_kv = false, any_qm = false;
+    int cur = -1;
+    auto flush = [&]() __attribute__((always_inline)) {
+      if (cur < 0) return;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int c = cb + lane + 64 * q;
+        if (c < 2 * dO) {
+          if (any_kv) atomicAdd(dP + (size_t)cur * ldp + c, akv[q]);
+          if (any_qm) atomicAdd(dP + (size_t)cur * ldp + ldkv + c, aqm[q]);
         }
       }
+    };
 #pragma unroll
-      for (int q = 0; q < 4; ++q) acc[q] = 0.f;
-      cur = rows[i];
+    for (int i = 0; i < SEG_CHUNK; ++i) {
+      if (rows[i] != cur) {
+        flush();
+#pragma unroll
+        for (int q = 0; q < 4; ++q) akv[q] = aqm[q] = 0.f;
+        any_kv = any_qm = false;
+        cur = rows[i];
+      }
+      if (rows[i] >= 0) {
+        if (slots[i] < R) {
+          any_qm = true;
+#pragma unroll
+          for (int q = 0; q < 4; ++q) aqm[q] += v[i][q];
+        } else {
+          any_kv = true;
+#pragma unroll
+          for (int q = 0; q < 4; ++q) akv[q] += v[i][q];
+        }
+      }
     }
-#pragma unroll
-    for (int q = 0; q < 4; ++q) acc[q] += v[i][q];
-  }
-  if (cur >= 0) {
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const int c = lane + 64 * q;
-      if (c < dm) atomicAdd(ds_row + (size_t)cur * ldh + c, acc[q]);
-    }
+    flush();
   }
 }
 
@@ -176,8 +191,34 @@ void seg_reduce(tgnn_ctx* ctx, int R, int S, hipStream_t s) {
   const Dims& d = ctx->d;
   Ws& w = ctx->w;
   const int chunks = (S + SEG_CHUNK - 1) / SEG_CHUNK;
-  hipLaunchKernelGGL(seg_reduce_kernel, dim3((chunks + 3) / 4), dim3(256), 0, s, R, d.dm, d.dO, w.ucount, w.rowptr,
-                     w.sorted, w.slot_row, w.has, w.dMin, d.ldm, w.dQsub, w.dCsub, d.ldsub, w.ds_row, d.ldh);
+  hipLaunchKernelGGL(seg_reduce_kernel, dim3((chunks + 3) / 4), dim3(256), 0, s, R, d.dO, w.ucount, w.rowptr, w.sorted,
+                     w.slot_row, w.dq, w.dz, d.ldh, w.dKV, d.ldkv, w.dP, d.ldp);
+}
+
+// slot = row: dP[r] = {0 || dq[r] | dz[r]} for roots, dP[R + j] = {dKV[j] || 0} for neighbour slots
+__global__ void slots_to_dp_kernel(int R, int RK, int dO, const float* __restrict__ dq, const float* __restrict__ dz,
+                                   int ldh, const float* __restrict__ dKV, int ldkv, float* __restrict__ dP, int ldp) {
+  const long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x;
+  if (i >= (long long)(R + RK) * ldp) return;
+  const int row = (int)(i / ldp), c = (int)(i - (long long)row * ldp);
+  float x = 0.f;
+  if (row < R) {
+    const int cc = c - ldkv;
+    if (cc >= 0 && cc < dO) x = dq[(size_t)row * ldh + cc];
+    else if (cc >= dO && cc < 2 * dO) x = dz[(size_t)row * ldh + (cc - dO)];
+  } else if (c < 2 * dO) {
+    x = dKV[(size_t)(row - R) * ldkv + c];
+  }
+  dP[i] = x;
+}
+
+void slots_to_dp(tgnn_ctx* ctx, int R, int RK, hipStream_t s) {
+  const Dims& d = ctx->d;
+  Ws& w = ctx->w;
+  const long long total = (long long)(R + RK) * d.ldp;
+  if (total <= 0) return;
+  hipLaunchKernelGGL(slots_to_dp_kernel, dim3((int)((total + 255) / 256)), dim3(256), 0, s, R, RK, d.dO, w.dq, w.dz, d.ldh,
+                     w.dKV, d.ldkv, w.dP, d.ldp);
 }
 
 // debug: per-slot view of per-row data

@@ -94,30 +94,31 @@ static void layout(const Dims& d, Ws& w, Bump& b) {
   w.utag = b.take<unsigned long long>(NG); w.uidx = b.take<int32_t>(NG); w.ucount = b.take<int32_t>(1);
   w.ulist = b.take<int32_t>(U); w.slot_row = b.take<int32_t>(S); w.ucnt = b.take<int32_t>(U);
   w.rowptr = b.take<int32_t>(U + 1); w.cursor = b.take<int32_t>(U); w.sorted = b.take<int32_t>(S);
-  w.ds_row = b.take<float>(U * d.ldh);
+  w.ds_row = b.take<float>(S * d.ldh);
   w.bs_dev = b.take<BatchSet>(1);
   w.sgd_dev = b.take<SgdSet>(1);
   w.msinX = b.take<float>(S * d.ldt); w.msinC = b.take<float>(RK * d.ldt);
   w.tg_partial = b.take<float>((size_t)3 * TG_BLOCKS * 2 * d.dt);
   w.X = b.take<float>(S * d.ldx); w.Hm = b.take<float>(S * d.ldh);
   w.gi = b.take<float>(S * d.ld3); w.gh = b.take<float>(S * d.ld3);
-  w.gates = b.take<float>(S * 4 * d.ldh); w.s_new = b.take<float>(S * d.ldh);
+  w.gates = b.take<float>(S * 4 * d.ldh); w.Xrow = b.take<float>(S * d.ldxr);
   w.dgi = b.take<float>(S * d.ld3); w.dgh = b.take<float>(S * d.ld3); w.dphi_g = b.take<float>(S * d.ldt);
-  w.Cmat = b.take<float>(RK * d.ldc); w.Qin = b.take<float>(R * d.ldq); w.KV = b.take<float>(RK * d.ldkv);
-  w.q = b.take<float>(R * d.ldh); w.prob = b.take<float>(R * d.H * d.k); w.Min = b.take<float>(R * d.ldm);
-  w.z = b.take<float>(R * d.ldh);
-  w.dz = b.take<float>(R * d.ldh); w.dMin = b.take<float>(R * d.ldm); w.dq = b.take<float>(R * d.ldh);
-  w.dKV = b.take<float>(RK * d.ldkv); w.dCsub = b.take<float>(RK * d.ldsub); w.dQsub = b.take<float>(R * d.ldsub);
+  // node rows of a standalone attention call are its slots, so P / dP hold S rows (a step uses far fewer)
+  w.P = b.take<float>(S * d.ldp); w.dP = b.take<float>(S * d.ldp);
+  w.CE = b.take<float>(RK * d.ldce); w.KV = b.take<float>(RK * d.ldkv);
+  w.prob = b.take<float>(R * d.H * d.k); w.Omat = b.take<float>(R * d.ldh); w.z = b.take<float>(R * d.ldh);
+  w.dz = b.take<float>(R * d.ldh); w.dOmat = b.take<float>(R * d.ldh); w.dq = b.take<float>(R * d.ldh);
+  w.dKV = b.take<float>(RK * d.ldkv); w.dPhi = b.take<float>(RK * d.ldt);
   w.Adec = b.take<float>(B2 * d.ldkv); w.h1 = b.take<float>(B2 * d.ldh); w.dh1 = b.take<float>(B2 * d.ldh);
   w.dAdec = b.take<float>(B2 * d.ldkv); w.logits = b.take<float>(B2); w.dlogit = b.take<float>(B2);
   w.loss_acc = b.take<float>(TGNN_MAX_BATCHES);
   w.Wih_p = b.take<float>((size_t)3 * d.dm * d.ldx); w.Whh_p = b.take<float>((size_t)3 * d.dm * d.ldh);
-  w.Wkv_p = b.take<float>((size_t)2 * d.dO * d.ldc); w.Wq_p = b.take<float>((size_t)d.dO * d.ldq);
-  w.Wo_p = b.take<float>((size_t)d.dO * d.ldm); w.Wdec_p = b.take<float>((size_t)d.dO * d.ldkv);
-  w.bkv_p = b.take<float>((size_t)2 * d.dO);
-  w.WdecT = b.take<float>((size_t)2 * d.dO * d.ldh); w.WoT = b.take<float>((size_t)(d.dO + d.dx) * d.ldh);
-  w.WkvT_sub = b.take<float>((size_t)(d.dm + d.dt) * d.ldkv); w.WqT_sub = b.take<float>((size_t)(d.dm + d.dt) * d.ldh);
-  w.WihT_phi = b.take<float>((size_t)d.dt * d.ld3);
+  w.Wdec_p = b.take<float>((size_t)d.dO * d.ldkv);
+  w.Wx = b.take<float>((size_t)d.ldp * d.ldxr); w.bias_x = b.take<float>((size_t)d.ldp);
+  w.Wce = b.take<float>((size_t)2 * d.dO * d.ldce); w.Wo_o = b.take<float>((size_t)d.dO * d.ldh);
+  w.WdecT = b.take<float>((size_t)2 * d.dO * d.ldh); w.WihT_phi = b.take<float>((size_t)d.dt * d.ld3);
+  w.WxT = b.take<float>((size_t)d.dm * d.ldp); w.WceT_phi = b.take<float>((size_t)d.dt * d.ldkv);
+  w.WoT_o = b.take<float>((size_t)d.dO * d.ldh);
   b.take<char>(256);
 }
 
@@ -157,53 +158,6 @@ struct Side {
   }
 };
 
-// UPDT on n rows already staged in ws.X / ws.Hm / ws.has: projections (MFMA) + gates.
-static void gru_forward(tgnn_ctx* ctx, const tgnn_params* p, int n, hipStream_t s) {
-  const Dims& d = ctx->d; Ws& w = ctx->w;
-  gemm_nt(w.X, d.ldx, w.Wih_p, d.ldx, p->gru_bih, w.gi, d.ld3, n, 3 * d.dm, d.ldx, d.ld3, false, s);
-  gemm_nt(w.Hm, d.ldh, w.Whh_p, d.ldh, p->gru_bhh, w.gh, d.ld3, n, 3 * d.dm, d.ldh, d.ld3, false, s);
-  gru_gates_fwd(d, n, nullptr, w.gi, w.gh, w.Hm, w.has, w.gates, w.s_new, nullptr, s);
-}
-
-// Projections, per-root softmax attention and the merge layer from ws.Cmat / ws.Qin / ws.Min[:, dO:].
-static void attn_forward(tgnn_ctx* ctx, const tgnn_params* p, int R, const int32_t* cnt, hipStream_t s) {
-  const Dims& d = ctx->d; Ws& w = ctx->w;
-  const int RK = R * d.k;
-  gemm_nt(w.Cmat, d.ldc, w.Wkv_p, d.ldc, w.bkv_p, w.KV, d.ldkv, RK, 2 * d.dO, d.ldc, d.ldkv, false, s);
-  gemm_nt(w.Qin, d.ldq, w.Wq_p, d.ldq, p->bq, w.q, d.ldh, R, d.dO, d.ldq, d.ldh, false, s);
-  attn_core_fwd(d, R, w.q, d.ldh, w.KV, d.ldkv, cnt, w.prob, w.Min, d.ldm, s);
-  gemm_nt(w.Min, d.ldm, w.Wo_p, d.ldm, p->bo, w.z, d.ldh, R, d.dO, d.ldm, d.ldh, true, s);
-}
-
-// From ws.dz (already masked by the merge ReLU) down to ws.dMin / ws.dQsub / ws.dCsub, adding the
-// gradients of W_o, W_q, W_k, W_v, their biases and the time encoding.
-// Weight-gradient GEMMs are queued in `tn` (launched by the caller, later, as one grouped kernel).
-static void attn_backward(tgnn_ctx* ctx, tgnn_params* g, const tgnn_params* p, int R, const int32_t* cnt,
-                          bool finish_time_grad, TnBatch& tn, Side& side, hipStream_t s) {
-  const Dims& d = ctx->d; Ws& w = ctx->w;
-  const int RK = R * d.k;
-  tn.add(w.dz, d.ldh, w.Min, d.ldm, R, d.dO, d.dO + d.dx, single_out(g->wo, d.dO + d.dx, g->bo));
-  side.flush(tn);
-  gemm_nt(w.dz, d.ldh, w.WoT, d.ldh, nullptr, w.dMin, d.ldm, R, d.dO + d.dx, d.ldh, d.ldm, false, s);
-  attn_core_bwd(d, R, w.q, d.ldh, w.KV, d.ldkv, cnt, w.prob, w.dMin, d.ldm, w.dq, w.dKV, s);
-  OutMap kv;
-  memset(&kv, 0, sizeof(kv));
-  kv.p[0][0] = g->wk; kv.p[1][0] = g->wv; kv.ld[0][0] = kv.ld[1][0] = d.dkv;
-  kv.n_split = d.dO; kv.k_split = 1 << 30;
-  kv.bias[0] = g->bk; kv.bias[1] = g->bv;
-  tn.add(w.dKV, d.ldkv, w.Cmat, d.ldc, RK, 2 * d.dO, d.dkv, kv);
-  gemm_nt(w.dKV, d.ldkv, w.WkvT_sub, d.ldkv, nullptr, w.dCsub, d.ldsub, RK, d.dm + d.dt, d.ldkv, d.ldsub, false, s);
-  tn.add(w.dq, d.ldh, w.Qin, d.ldq, R, d.dO, d.dq, single_out(g->wq, d.dq, g->bq));
-  side.flush(tn);
-  gemm_nt(w.dq, d.ldh, w.WqT_sub, d.ldh, nullptr, w.dQsub, d.ldsub, R, d.dm + d.dt, d.ldh, d.ldsub, false, s);
-  const size_t tgp = (size_t)TG_BLOCKS * 2 * d.dt;
-  time_grad(w.dCsub, d.ldsub, d.dm, w.msinC, d.ldt, w.dtk, RK, d.dt, p->time_b, w.tg_partial, s);
-  time_grad(w.dQsub, d.ldsub, d.dm, nullptr, 0, nullptr, R, d.dt, p->time_b, w.tg_partial + tgp, s);
-  if (finish_time_grad) time_grad_finish(w.tg_partial, 2, d.dt, g->time_w, g->time_b, s);
-}
-
-static hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
-
 // Records a pair of events around a stage when its bit is set in the profiler mask.
 struct StageTimer {
   tgnn_ctx* c;
@@ -228,6 +182,87 @@ struct StageTimer {
     pr.count[st]++;
   }
 };
+
+// UPDT on n rows already staged in ws.X / ws.Hm / ws.has: projections (MFMA) + gates; s' goes to ws.Xrow.
+static void gru_forward(tgnn_ctx* ctx, const tgnn_params* p, int n, hipStream_t s) {
+  const Dims& d = ctx->d; Ws& w = ctx->w;
+  gemm_nt(w.X, d.ldx, w.Wih_p, d.ldx, p->gru_bih, w.gi, d.ld3, n, 3 * d.dm, d.ldx, d.ld3, false, s);
+  gemm_nt(w.Hm, d.ldh, w.Whh_p, d.ldh, p->gru_bhh, w.gh, d.ld3, n, 3 * d.dm, d.ldh, d.ld3, false, s);
+  gru_gates_fwd(d, n, nullptr, w.gi, w.gh, w.Hm, w.has, w.gates, w.Xrow, d.ldxr, nullptr, nullptr, nullptr, 0, s);
+}
+
+// Attention (Eq. 4-7) and the merge layer, from the node rows ws.Xrow [n_rows] and the per-slot rows ws.CE.
+// Every projection is linear in {x | e | Phi}, and x depends on the node only, so the x part of K, V, q and
+// of the merge layer is one small GEMM over the distinct node rows (ws.P); the per-slot GEMMs add the row of
+// their node in the epilogue.  slot_row maps root slot r and neighbour slot R + r k + j to node rows
+// (NULL: slot = row).  n_rows_dev (may be NULL): device-side row count.
+static void attn_forward(tgnn_ctx* ctx, const tgnn_params* p, int R, int n_rows, const int* n_rows_dev,
+                         const int32_t* slot_row, const int32_t* cnt, StageTimer* tm, hipStream_t s) {
+  const Dims& d = ctx->d; Ws& w = ctx->w;
+  const int RK = R * d.k;
+  if (tm) tm->begin(9);
+  gemm_nt(w.Xrow, d.ldxr, w.Wx, d.ldxr, w.bias_x, w.P, d.ldp, n_rows, d.ldkv + 2 * d.dO, d.ldxr, d.ldp, false, s,
+          n_rows_dev);
+  if (tm) { tm->end(9); tm->begin(8); }
+  RowAdd kv_add;
+  kv_add.src = w.P; kv_add.ld = d.ldp; kv_add.index = slot_row ? slot_row + R : nullptr; kv_add.row0 = R;
+  gemm_nt(w.CE, d.ldce, w.Wce, d.ldce, nullptr, w.KV, d.ldkv, RK, 2 * d.dO, d.ldce, d.ldkv, false, s, nullptr, kv_add);
+  if (tm) { tm->end(8); tm->begin(10); }
+  attn_core_fwd(d, R, w.P + d.ldkv, d.ldp, slot_row, w.KV, d.ldkv, cnt, w.prob, w.Omat, d.ldh, s);
+  if (tm) { tm->end(10); tm->begin(11); }
+  RowAdd m_add;
+  m_add.src = w.P + d.ldkv + d.dO; m_add.ld = d.ldp; m_add.index = slot_row; m_add.row0 = 0;
+  gemm_nt(w.Omat, d.ldh, w.Wo_o, d.ldh, nullptr, w.z, d.ldh, R, d.dO, d.ldh, d.ldh, true, s, nullptr, m_add);
+  if (tm) tm->end(11);
+}
+
+// From ws.dz (already masked by the merge ReLU) down to ws.dP (per-node projection gradients, not yet
+// reduced over slots), ws.dKV and ws.dq; queues the weight-gradient GEMMs of W_o (attention-output
+// columns) and of the {e | Phi} columns of W_k, W_v, and writes the time-encoding partial sums of the keys
+// and of the query into regions 0 and 1 of ws.tg_partial.
+static void attn_backward(tgnn_ctx* ctx, tgnn_params* g, const tgnn_params* p, int R, const int32_t* slot_row,
+                          const int32_t* cnt, TnBatch& tn, Side& side, hipStream_t s) {
+  const Dims& d = ctx->d; Ws& w = ctx->w;
+  const int RK = R * d.k;
+  tn.add(w.dz, d.ldh, w.Omat, d.ldh, R, d.dO, d.dO, single_out(g->wo, d.dO + d.dx, nullptr));
+  side.flush(tn);
+  gemm_nt(w.dz, d.ldh, w.WoT_o, d.ldh, nullptr, w.dOmat, d.ldh, R, d.dO, d.ldh, d.ldh, false, s);
+  attn_core_bwd(d, R, w.P + d.ldkv, d.ldp, slot_row, w.KV, d.ldkv, cnt, w.prob, w.dOmat, d.ldh, w.dq, w.dKV, s);
+  if (d.de + d.dt > 0) {
+    OutMap kv;
+    memset(&kv, 0, sizeof(kv));
+    kv.p[0][0] = g->wk + d.dx; kv.p[1][0] = g->wv + d.dx; kv.ld[0][0] = kv.ld[1][0] = d.dkv;
+    kv.n_split = d.dO; kv.k_split = 1 << 30;
+    tn.add(w.dKV, d.ldkv, w.CE, d.ldce, RK, 2 * d.dO, d.de + d.dt, kv);
+    side.flush(tn);
+  }
+  gemm_nt(w.dKV, d.ldkv, w.WceT_phi, d.ldkv, nullptr, w.dPhi, d.ldt, RK, d.dt, d.ldkv, d.ldt, false, s);
+  const size_t tgp = (size_t)TG_BLOCKS * 2 * d.dt;
+  time_grad(w.dPhi, d.ldt, 0, w.msinC, d.ldt, w.dtk, RK, d.dt, p->time_b, w.tg_partial, s);
+  qphi_grad(w.dq, d.ldh, R, d.dO, p->wq, d.dq, d.dx, d.dt, p->time_b, w.tg_partial + tgp, g->wq, s);
+}
+
+// After the per-row reduction into ws.dP: gradient reaching the node rows (ws.ds_row, dynamic columns) and
+// the weight gradients of the node part of W_k, W_v, W_q, W_o with all four biases.
+static void node_proj_backward(tgnn_ctx* ctx, tgnn_params* g, int n_rows, const int* n_rows_dev, TnBatch& tn,
+                               hipStream_t s) {
+  const Dims& d = ctx->d; Ws& w = ctx->w;
+  gemm_nt(w.dP, d.ldp, w.WxT, d.ldp, nullptr, w.ds_row, d.ldh, n_rows, d.dm, d.ldp, d.ldh, false, s, n_rows_dev);
+  OutMap kv;
+  memset(&kv, 0, sizeof(kv));
+  kv.p[0][0] = g->wk; kv.p[1][0] = g->wv; kv.ld[0][0] = kv.ld[1][0] = d.dkv;
+  kv.n_split = d.dO; kv.k_split = 1 << 30;
+  kv.bias[0] = g->bk; kv.bias[1] = g->bv;
+  tn.add(w.dP, d.ldp, w.Xrow, d.ldxr, n_rows, 2 * d.dO, d.dx, kv, n_rows_dev);
+  OutMap qm;
+  memset(&qm, 0, sizeof(qm));
+  qm.p[0][0] = g->wq; qm.ld[0][0] = d.dq; qm.p[1][0] = g->wo + d.dO; qm.ld[1][0] = d.dO + d.dx;
+  qm.n_split = d.dO; qm.k_split = 1 << 30;
+  qm.bias[0] = g->bq; qm.bias[1] = g->bo;
+  tn.add(w.dP + d.ldkv, d.ldp, w.Xrow, d.ldxr, n_rows, 2 * d.dO, d.dx, qm, n_rows_dev);
+}
+
+static hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
 
 static void fill_param_set(const Dims& d, const tgnn_params* p, const tgnn_params* g, int first, SgdSet& set) {
   memset(&set, 0, sizeof(set));
@@ -280,8 +315,8 @@ int32_t tgnn_create(const tgnn_config* cfg, tgnn_ctx** out) {
   d.N = cfg->n_nodes; d.dm = cfg->d_mem; d.dt = cfg->d_time; d.de = cfg->d_edge; d.ds = cfg->d_static;
   d.H = cfg->n_heads; d.k = cfg->k; d.nrep = cfg->n_replicas; d.maxB = cfg->max_batch; d.dt_source = cfg->dt_source;
   d.d_in = 2 * d.dm + d.dt + d.de; d.dx = d.dm + d.ds; d.dq = d.dx + d.dt; d.dkv = d.dx + d.de + d.dt; d.dO = d.dm;
-  d.ldx = padrow(d.d_in); d.ldh = padrow(d.dm); d.ld3 = padrow(3 * d.dm); d.ldc = padrow(d.dkv); d.ldq = padrow(d.dq);
-  d.ldkv = padrow(2 * d.dO); d.ldm = padrow(d.dO + d.dx); d.ldsub = padrow(d.dm + d.dt); d.ldt = padrow(d.dt);
+  d.ldx = padrow(d.d_in); d.ldh = padrow(d.dm); d.ld3 = padrow(3 * d.dm); d.ldxr = padrow(d.dx);
+  d.ldce = padrow(d.de + d.dt); d.ldkv = padrow(2 * d.dO); d.ldp = 2 * d.ldkv; d.ldt = padrow(d.dt);
   const int nb = d.nrep < TGNN_MAX_BATCHES ? d.nrep : TGNN_MAX_BATCHES;
   const long long maxEv = (long long)d.maxB * nb;
   if (maxEv * 3 * (1 + d.k) > 0x3fffffffLL) {
@@ -426,8 +461,8 @@ int32_t tgnn_gru_update(tgnn_ctx* ctx, const tgnn_params* p, int32_t n_slots, co
   if (ctx == nullptr) return set_error(TGNN_E_NULL_PTR, "ctx is NULL");
   if (int rc = check_params(p, "params")) return rc;
   const Dims& d = ctx->d; Ws& w = ctx->w;
-  if (n_slots < 0 || n_slots > d.maxU)
-    return set_error(TGNN_E_WORKSPACE, "n_slots = %d outside [0, %d] (workspace row capacity)", n_slots, d.maxU);
+  if (n_slots < 0 || n_slots > d.maxS)
+    return set_error(TGNN_E_WORKSPACE, "n_slots = %d outside [0, %d] (workspace row capacity)", n_slots, d.maxS);
   if (n_slots == 0) return TGNN_OK;
   REQ_PTR(mem); REQ_PTR(mail); REQ_PTR(mem_ts); REQ_PTR(mail_ts); REQ_PTR(has_mail); REQ_PTR(out_s_new); REQ_PTR(out_tau);
   if (d.de > 0) REQ_PTR(mail_efeat);
@@ -446,7 +481,7 @@ int32_t tgnn_gru_update(tgnn_ctx* ctx, const tgnn_params* p, int32_t n_slots, co
   a.n_slots = n_slots; a.dm = d.dm; a.dt = d.dt; a.de = d.de;
   gather_rows(a, s);
   gru_forward(ctx, p, n_slots, s);
-  TGNN_HIP_CHECK(hipMemcpy2DAsync(out_s_new, (size_t)d.dm * 4, w.s_new, (size_t)d.ldh * 4, (size_t)d.dm * 4, n_slots,
+  TGNN_HIP_CHECK(hipMemcpy2DAsync(out_s_new, (size_t)d.dm * 4, w.Xrow, (size_t)d.ldxr * 4, (size_t)d.dm * 4, n_slots,
                                   hipMemcpyDeviceToDevice, s));
   TGNN_LAUNCH_CHECK();
   return TGNN_OK;
@@ -466,16 +501,15 @@ int32_t tgnn_temporal_attn_fwd(tgnn_ctx* ctx, const tgnn_params* p, int32_t n_ro
   hipStream_t s = as_stream(stream);
   prologue(ctx, p, nullptr, nullptr, nullptr, nullptr, s);
   TGNN_HIP_CHECK(hipMemcpyAsync(w.cnt, cnt, sizeof(int32_t) * n_roots, hipMemcpyDeviceToDevice, s));
-  AttnAssembleArgs a;
+  stage_x_rows(n_roots, d.k, d.dx, x_root, x_nbr, cnt, w.Xrow, d.ldxr, s);
+  CeArgs a;
   memset(&a, 0, sizeof(a));
-  a.s_root = x_root; a.s_nbr = x_nbr; a.p_s = d.dx;
-  a.stat = nullptr; a.efeat = e_nbr; a.neid = nullptr; a.cnt = cnt; a.dt_in = dt_nbr;
+  a.efeat = e_nbr; a.neid = nullptr; a.cnt = cnt; a.dt_in = dt_nbr;
   a.time_w = p->time_w; a.time_b = p->time_b;
-  a.Cmat = w.Cmat; a.Qin = w.Qin; a.Min = w.Min; a.ldc = d.ldc; a.ldq = d.ldq; a.ldm = d.ldm; a.dtk = w.dtk;
-  a.msin = w.msinC; a.p_msin = d.ldt;
-  a.R = n_roots; a.k = d.k; a.dm = d.dx; a.ds = 0; a.de = d.de; a.dt = d.dt; a.dO = d.dO; a.dt_source = 0;
-  attn_assemble(a, s);
-  attn_forward(ctx, p, n_roots, w.cnt, s);
+  a.CE = w.CE; a.ldce = d.ldce; a.msin = w.msinC; a.p_msin = d.ldt; a.dtk = w.dtk;
+  a.R = n_roots; a.k = d.k; a.de = d.de; a.dt = d.dt; a.dt_source = 0;
+  assemble_ce(a, s);
+  attn_forward(ctx, p, n_roots, n_roots * (1 + d.k), nullptr, nullptr, w.cnt, nullptr, s);
   TGNN_HIP_CHECK(hipMemcpy2DAsync(out_z, (size_t)d.dO * 4, w.z, (size_t)d.ldh * 4, (size_t)d.dO * 4, n_roots,
                                   hipMemcpyDeviceToDevice, s));
   TGNN_LAUNCH_CHECK();
@@ -498,9 +532,13 @@ int32_t tgnn_temporal_attn_bwd(tgnn_ctx* ctx, const tgnn_params* p, int32_t n_ro
   mask_dz(n_roots, d.dO, dz, d.dO, w.z, d.ldh, w.dz, s);
   TnBatch tn;
   Side side{ctx, s, false};
-  attn_backward(ctx, grads, p, n_roots, w.cnt, true, tn, side, s);
+  const int RK = n_roots * d.k;
+  attn_backward(ctx, grads, p, n_roots, nullptr, w.cnt, tn, side, s);
+  time_grad_finish(w.tg_partial, 2, d.dt, grads->time_w, grads->time_b, s);
+  slots_to_dp(ctx, n_roots, RK, s);
+  node_proj_backward(ctx, grads, n_roots + RK, nullptr, tn, s);
   tn.launch(s);
-  attn_dx_out(n_roots, n_roots * d.k, d.dm, d.dO, w.dMin, d.ldm, w.dQsub, w.dCsub, d.ldsub, d_x_root, d_x_nbr, s);
+  attn_dx_out(n_roots, RK, d.dm, w.ds_row, d.ldh, d_x_root, d_x_nbr, s);
   TGNN_LAUNCH_CHECK();
   return TGNN_OK;
 }
@@ -714,44 +752,31 @@ static int enqueue_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
   gemm_nt(w.Hm, d.ldh, w.Whh_p, d.ldh, p->gru_bhh, w.gh, d.ld3, U, 3 * d.dm, d.ldh, d.ld3, false, s, w.ucount);
   tm.end(5);
   tm.begin(6);
-  gru_gates_fwd(d, U, w.ucount, w.gi, w.gh, w.Hm, w.has, w.gates, w.s_new, w.ds_row, s);
+  gru_gates_fwd(d, U, w.ucount, w.gi, w.gh, w.Hm, w.has, w.gates, w.Xrow, d.ldxr, d.ds ? st->stat : nullptr, w.ulist,
+                w.dP, d.ldp, s);
   tm.end(6);
 
   // Last-event-wins write-back: needs s' and tau only, and every read of the stored state (the gather) is
   // already queued before it, so it can run beside the rest of the step.
   side.fork();
   tm.begin(19, s2);
-  writeback_scatter(d, w.bs_dev, bs.total, st, w.winkey, w.epoch, w.s_new, d.ldh, w.tau, w.slot_row, nullptr, nullptr,
+  writeback_scatter(d, w.bs_dev, bs.total, st, w.winkey, w.epoch, w.Xrow, d.ldxr, w.tau, w.slot_row, nullptr, nullptr,
                     nullptr, nullptr, out_winner, s2);
   tm.end(19, s2);
 
   // attention + merge
-  AttnAssembleArgs aa;
+  CeArgs aa;
   memset(&aa, 0, sizeof(aa));
-  aa.s_root = w.s_new; aa.s_nbr = w.s_new; aa.p_s = d.ldh; aa.slot_row = w.slot_row;
-  aa.stat = st->stat; aa.efeat = g->efeat; aa.root_node = w.root_node; aa.nbr = w.nbr; aa.neid = w.neid; aa.cnt = w.cnt;
+  aa.efeat = g->efeat; aa.neid = w.neid; aa.cnt = w.cnt; aa.slot_row = w.slot_row;
   aa.root_t = w.root_t; aa.nts = w.nts; aa.tau_nbr = w.tau; aa.dt_in = nullptr;
   aa.time_w = p->time_w; aa.time_b = p->time_b;
-  aa.Cmat = w.Cmat; aa.Qin = w.Qin; aa.Min = w.Min; aa.ldc = d.ldc; aa.ldq = d.ldq; aa.ldm = d.ldm; aa.dtk = w.dtk;
-  aa.msin = w.msinC; aa.p_msin = d.ldt;
-  aa.R = R; aa.k = d.k; aa.dm = d.dm; aa.ds = d.ds; aa.de = d.de; aa.dt = d.dt; aa.dO = d.dO; aa.dt_source = d.dt_source;
+  aa.CE = w.CE; aa.ldce = d.ldce; aa.msin = w.msinC; aa.p_msin = d.ldt; aa.dtk = w.dtk;
+  aa.R = R; aa.k = d.k; aa.de = d.de; aa.dt = d.dt; aa.dt_source = d.dt_source;
   tm.begin(7);
-  attn_assemble(aa, s);
+  assemble_ce(aa, s);
   tm.end(7);
-  side.fork();
-  tm.begin(9, s2);
-  gemm_nt(w.Qin, d.ldq, w.Wq_p, d.ldq, p->bq, w.q, d.ldh, R, d.dO, d.ldq, d.ldh, false, s2);
-  tm.end(9, s2);
-  tm.begin(8);
-  gemm_nt(w.Cmat, d.ldc, w.Wkv_p, d.ldc, w.bkv_p, w.KV, d.ldkv, RK, 2 * d.dO, d.ldc, d.ldkv, false, s);
-  tm.end(8);
-  side.join();   // q (and, in passing, the write-back and the slot sort)
-  tm.begin(10);
-  attn_core_fwd(d, R, w.q, d.ldh, w.KV, d.ldkv, w.cnt, w.prob, w.Min, d.ldm, s);
-  tm.end(10);
-  tm.begin(11);
-  gemm_nt(w.Min, d.ldm, w.Wo_p, d.ldm, p->bo, w.z, d.ldh, R, d.dO, d.ldm, d.ldh, true, s);
-  tm.end(11);
+  attn_forward(ctx, p, R, U, w.ucount, w.slot_row, w.cnt, &tm, s);
+  side.join();   // in passing: the write-back and the slot sort
 
   // decoder + loss (also produces d loss / d hidden)
   tm.begin(12);
@@ -774,10 +799,11 @@ static int enqueue_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
   decoder_dz(d, w.bs_dev, bs.total, w.dAdec, d.ldkv, w.z, d.ldh, w.dz, s);
   tm.end(13);
   tm.begin(14);
-  attn_backward(ctx, grads, p, R, w.cnt, false, tn, side, s);
+  attn_backward(ctx, grads, p, R, w.slot_row, w.cnt, tn, side, s);
   tm.end(14);
   tm.begin(15);
-  seg_reduce(ctx, R, S, s);   // per-row sum of the gradients of the slots that share the row
+  seg_reduce(ctx, R, S, s);   // per-row sum of the slot gradients reaching the per-node projections
+  node_proj_backward(ctx, grads, U, w.ucount, tn, s);
   gru_gates_bwd(d, U, w.ucount, w.ds_row, w.gates, w.Hm, w.has, w.dgi, w.dgh, s);
   tm.end(15);
   tn.add(w.dgi, d.ld3, w.X, d.ldx, U, 3 * d.dm, d.d_in, single_out(grads->gru_wih, d.d_in, grads->gru_bih), w.ucount);
@@ -804,7 +830,7 @@ static int enqueue_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
   }
   if (!side.on) {
     tm.begin(19);
-    writeback_scatter(d, w.bs_dev, bs.total, st, w.winkey, w.epoch, w.s_new, d.ldh, w.tau, w.slot_row, nullptr, nullptr,
+    writeback_scatter(d, w.bs_dev, bs.total, st, w.winkey, w.epoch, w.Xrow, d.ldxr, w.tau, w.slot_row, nullptr, nullptr,
                       nullptr, nullptr, out_winner, s);
     tm.end(19);
   }
@@ -876,7 +902,7 @@ int32_t tgnn_debug_read(tgnn_ctx* ctx, int32_t what, void* dst, int64_t n_bytes,
     if (n_bytes < 0 || (size_t)n_bytes % unit != 0 || (size_t)n_bytes / unit > (size_t)d.maxS)
       return set_error(TGNN_E_OUT_OF_RANGE, "n_bytes is not a whole number of slots within capacity");
     const int n = (int)((size_t)n_bytes / unit);
-    if (what == 4) expand_rows(ctx, n, w.s_new, d.ldh, nullptr, static_cast<float*>(dst), nullptr, s);
+    if (what == 4) expand_rows(ctx, n, w.Xrow, d.ldxr, nullptr, static_cast<float*>(dst), nullptr, s);
     else expand_rows(ctx, n, nullptr, 0, w.tau, nullptr, static_cast<double*>(dst), s);
     TGNN_LAUNCH_CHECK();
     return TGNN_OK;

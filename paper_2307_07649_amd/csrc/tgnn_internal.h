@@ -20,11 +20,10 @@ struct Dims {
   int ldx;    // GRU input rows {mail | Phi | efeat}
   int ldh;    // rows of width d_m
   int ld3;    // rows of width 3 d_m
-  int ldc;    // key/value input rows {x_w | e | Phi}
-  int ldq;    // query input rows {x_v | Phi(0)}
+  int ldxr;   // node rows x = {s' | static}
+  int ldce;   // per-slot key/value input rows {e | Phi}
   int ldkv;   // rows of width 2 d_o  (K | V), also decoder input {z_a | z_b}
-  int ldm;    // merge input rows {h_v | x_v}
-  int ldsub;  // rows of width d_m + d_t (gradient wrt the dynamic and time-encoding columns)
+  int ldp;    // per-node projections {K | V || q | merge}: two halves of pitch ldkv
   int ldt;    // rows of width d_t
   int maxEv, maxR, maxRK, maxS, maxU;
 };
@@ -55,25 +54,34 @@ struct Ws {
   unsigned long long* utag;                    // [nrep*N] epoch of the last step that claimed the node
   int32_t *uidx, *ucount, *ulist;              // [nrep*N] row of a claimed node; [1] number of rows; [maxU] row -> gid
   int32_t *slot_row, *ucnt, *rowptr, *cursor, *sorted;  // [S] slot -> row; [maxU] slots per row; CSR of slots by row
-  float* ds_row;                               // [maxU, ldh] gradient reaching s' per row
+  float* ds_row;                               // [maxS, ldh] gradient reaching s' per row
   BatchSet* bs_dev;                            // device copy of the step's batch descriptors
   struct SgdSet* sgd_dev;                      // device copy of the parameter/gradient pointer table
   float *msinX, *msinC;                        // [S,ldt] [RK,ldt]  -sin of the time-encoding arguments
   float* tg_partial;                           // [3, TG_BLOCKS, 2, dt] partial time-encoding gradient sums
   // GRU
-  float *X, *Hm, *gi, *gh, *gates, *s_new;     // [S,ldx] [S,ldh] [S,ld3] [S,ld3] [S,4*ldh] [S,ldh]
+  float *X, *Hm, *gi, *gh, *gates;             // [S,ldx] [S,ldh] [S,ld3] [S,ld3] [S,4*ldh]
+  float* Xrow;                                 // [S,ldxr] x = {s' | static} per distinct node (row)
   float *dgi, *dgh, *dphi_g;                   // [S,ld3] [S,ld3] [S,ldh(dt)]
-  // attention
-  float *Cmat, *Qin, *KV, *q, *prob, *Min, *z; // [RK,ldc] [R,ldq] [RK,ldkv] [R,ldh] [R,H*k] [R,ldm] [R,ldh]
-  float *dz, *dMin, *dq, *dKV, *dCsub, *dQsub; // [R,ldh] [R,ldm] [R,ldh] [RK,ldkv] [RK,ldsub] [R,ldsub]
+  // attention.  The projections of x are taken once per distinct node (P), the projections of {e | Phi}
+  // per neighbour slot (CE); a slot's key/value is the sum of the two.
+  float *P, *dP;                               // [S,ldp]
+  float *CE, *KV, *prob, *Omat, *z;            // [RK,ldce] [RK,ldkv] [R,H*k] [R,ldh] [R,ldh]
+  float *dz, *dOmat, *dq, *dKV, *dPhi;         // [R,ldh] [R,ldh] [R,ldh] [RK,ldkv] [RK,ldt]
   // decoder
   float *Adec, *h1, *dh1, *dAdec, *logits, *dlogit;  // [2B,ldkv] [2B,ldh] [2B,ldh] [2B,ldkv] [2B] [2B]
   float* loss_acc;                                   // [TGNN_MAX_BATCHES] per-batch loss sums
   // standalone-call staging
   float *x_root_s, *x_nbr_s;                         // unused placeholders
   // packed weights
-  float *Wih_p, *Whh_p, *Wkv_p, *Wq_p, *Wo_p, *Wdec_p, *bkv_p;
-  float *WdecT, *WoT, *WkvT_sub, *WqT_sub, *WihT_phi;
+  float *Wih_p, *Whh_p, *Wdec_p;
+  float *Wx, *bias_x;       // [ldkv + 2 d_o, ldxr] rows {W_k ; W_v ; 0 ; W_q ; W_o} restricted to the x columns; [ldp]
+  float *Wce;               // [2 d_o, ldce] {W_k ; W_v} restricted to the {e | Phi} columns
+  float *Wo_o;              // [d_o, ldh] W_o restricted to the attention-output columns
+  float *WdecT, *WihT_phi;
+  float *WxT;               // [d_m, ldp]   transposed Wx, dynamic columns only
+  float *WceT_phi;          // [d_t, ldkv]  transposed Wce, time-encoding columns only
+  float *WoT_o;             // [d_o, ldh]   transposed Wo_o
 };
 
 }  // namespace tgnn
@@ -138,8 +146,16 @@ int set_error(int code, const char* fmt, ...);
 // C[m, n] = sum_k A[m, k] * B[n, k] + bias[n]  (m < M, n < N), optional ReLU; columns [N, n_store) of C are
 // set to zero.  Kp (multiple of 32) columns of A and B are read; B rows >= N and A rows >= M read as zero.
 // m_dev (device pointer, may be NULL): the number of valid rows is min(M, *m_dev); the grid is sized for M.
+// RowAdd (optional): row m of C additionally receives src[idx * ld + n] for n < N, with idx = index[m]
+// (index[m] < 0: nothing is added) or, without an index array, idx = m + row0.
+struct RowAdd {
+  const float* src = nullptr;
+  const int32_t* index = nullptr;
+  int ld = 0, row0 = 0;
+};
 void gemm_nt(const float* A, int lda, const float* B, int ldb, const float* bias, float* C, int ldc, int M,
-             int N, int Kp, int n_store, bool relu, hipStream_t s, const int* m_dev = nullptr);
+             int N, int Kp, int n_store, bool relu, hipStream_t s, const int* m_dev = nullptr,
+             const RowAdd& add = RowAdd());
 
 // Where the weight-gradient GEMM adds its result: element (n, k) goes to p[n >= n_split][k >= k_split]
 // (indices taken relative to the split) with row pitch ld[..][..]; column sums of D go to bias[n >= n_split].
@@ -187,7 +203,7 @@ struct SgdSet {
   int n[20];
   int cnt;
 };
-constexpr int MAX_PACK = 24;
+constexpr int MAX_PACK = 30;
 struct PrologueArgs {
   PackDesc d[MAX_PACK];
   int n_pack;
@@ -199,6 +215,10 @@ struct PrologueArgs {
   float* loss;
   unsigned long long* epoch;
   int32_t* ucount;
+  // bq_out[n] = bq[n] + sum_c wq[n, dx + c] * cos(time_b[c]): the query's time encoding Phi(0) is a constant
+  const float *bq, *wq, *time_b;
+  float* bq_out;
+  int dO, dq, dx, dt;
 };
 void prologue_fill(tgnn_ctx* ctx, const tgnn_params* p, const BatchSet* bs, const SgdSet* sgd, const SgdSet* zero,
                    float* loss, PrologueArgs& pa);
@@ -242,7 +262,10 @@ __device__ __forceinline__ void uniq_claim(unsigned long long* utag, int32_t* ui
 }
 void uniq_map(tgnn_ctx* ctx, int S, hipStream_t s);    // slot -> row map, slots per row
 void uniq_sort(tgnn_ctx* ctx, int S, hipStream_t s);   // row-sorted slot list (needed by seg_reduce only)
+// dP[row] += {dKV[slot] | 0} of the row's neighbour slots and {0 | dq[r] | dz[r]} of its root slots
 void seg_reduce(tgnn_ctx* ctx, int R, int S, hipStream_t s);
+// the same with slot = row (standalone attention call): plain stores, every row of dP written
+void slots_to_dp(tgnn_ctx* ctx, int R, int RK, hipStream_t s);
 void expand_rows(tgnn_ctx* ctx, int S, const float* src, int ld, const double* src_d, float* dst, double* dst_d,
                  hipStream_t s);
 
@@ -268,27 +291,37 @@ struct GatherArgs {
 };
 void gather_rows(const GatherArgs& a, hipStream_t s);
 
-struct AttnAssembleArgs {
-  const float *s_root, *s_nbr;  int p_s;  // dynamic rows of the roots [R, p_s] and of the neighbour slots [R*k, p_s]
-  const int32_t* slot_row;              // non-NULL: rows are s_root[slot_row[slot] * p_s] with slot = r or R + r*k + j,
-                                        // and tau_nbr is indexed by row as well
-  const float* stat;                    // [N, ds] or NULL
+// Per neighbour slot (r, j): CE row {e_vw | Phi(dt)} (Eq. 5-6 without the node part), -sin of the arguments,
+// and the time difference itself.
+struct CeArgs {
   const float* efeat;                   // [E, de], or [R*k, de] when neid == NULL
-  const int32_t *root_node, *nbr, *neid, *cnt;
-  const double *root_t, *nts, *tau_nbr; // tau_nbr [R*k]
+  const int32_t *neid, *cnt;
+  const int32_t* slot_row;              // non-NULL: tau_nbr is indexed by slot_row[R + slot]
+  const double *root_t, *nts, *tau_nbr;
   const double* dt_in;                  // non-NULL: time differences given directly [R*k]
   const float *time_w, *time_b;
-  float *Cmat, *Qin, *Min;  int ldc, ldq, ldm;
-  float* msin;  int p_msin;             // -sin of the key time-encoding arguments [R*k, p_msin]
+  float* CE;  int ldce;
+  float* msin;  int p_msin;             // [R*k, p_msin]
   double* dtk;
-  int R, k, dm, ds, de, dt, dO, dt_source;
+  int R, k, de, dt, dt_source;
 };
-void attn_assemble(const AttnAssembleArgs& a, hipStream_t s);
+void assemble_ce(const CeArgs& a, hipStream_t s);
+// Standalone attention call: node rows from the caller's x_root / x_nbr (rows of absent neighbours zeroed).
+void stage_x_rows(int R, int k, int dx, const float* x_root, const float* x_nbr, const int32_t* cnt, float* Xrow,
+                  int ldxr, hipStream_t s);
 
 // ---- k_gru.hip ----------------------------------------------------------------------
-// n_dev (device, may be NULL) caps the row count; ds_zero (may be NULL) [n, ldh] is cleared for the backward pass
+// n_dev (device, may be NULL) caps the row count.  s' goes to x_out [n, ld_x]; with stat != NULL the node's
+// static row stat[gid[row] % N] is appended (columns d_m .. d_m + d_s).  zero_buf (may be NULL) [n, zero_w]
+// is cleared for the backward pass.
 void gru_gates_fwd(const Dims& d, int n, const int* n_dev, const float* gi, const float* gh, const float* Hm,
-                   const int32_t* has, float* gates, float* s_new, float* ds_zero, hipStream_t s);
+                   const int32_t* has, float* gates, float* x_out, int ld_x, const float* stat, const int32_t* gid,
+                   float* zero_buf, int zero_w, hipStream_t s);
+// Gradient of the time-encoding phase through the query's Phi(0): per block of roots,
+// partial[block, 1, c] = -sin(time_b[c]) * sum_n (sum_r dq[r, n]) wq[n, dx + c]   (frequency part: 0); also
+// g_wq[n, dx + c] += (sum_r dq[r, n]) cos(time_b[c]), the weight gradient of the columns that multiply Phi(0).
+void qphi_grad(const float* dq, int ld, int R, int dO, const float* wq, int dq_w, int dx, int dt, const float* time_b,
+               float* partial, float* g_wq, hipStream_t s);
 // ds [n, ldh] = gradient reaching s' per row
 void gru_gates_bwd(const Dims& d, int n, const int* n_dev, const float* ds, const float* gates, const float* Hm,
                    const int32_t* has, float* dgi, float* dgh, hipStream_t s);
@@ -303,10 +336,12 @@ void time_grad(const float* dphi, int ld, int col0, const float* msin, int p_msi
 void time_grad_finish(const float* partial, int n_calls, int dt, float* g_w, float* g_b, hipStream_t s);
 
 // ---- k_attn.hip ---------------------------------------------------------------------
-void attn_core_fwd(const Dims& d, int R, const float* q, int ldq_, const float* KV, int ldkv, const int32_t* cnt,
-                   float* prob, float* Min, int ldm, hipStream_t s);
-void attn_core_bwd(const Dims& d, int R, const float* q, int ldq_, const float* KV, int ldkv, const int32_t* cnt,
-                   const float* prob, const float* dMin, int ldm, float* dq, float* dKV, hipStream_t s);
+// q of root r is q[qrow * ldq_ ...] with qrow = slot_row ? slot_row[r] : r.
+void attn_core_fwd(const Dims& d, int R, const float* q, int ldq_, const int32_t* slot_row, const float* KV, int ldkv,
+                   const int32_t* cnt, float* prob, float* Omat, int ldo, hipStream_t s);
+void attn_core_bwd(const Dims& d, int R, const float* q, int ldq_, const int32_t* slot_row, const float* KV, int ldkv,
+                   const int32_t* cnt, const float* prob, const float* dOmat, int ldo, float* dq, float* dKV,
+                   hipStream_t s);
 
 // ---- k_decoder.hip ------------------------------------------------------------------
 void decoder_assemble(const Dims& d, const BatchSet* bs, int total, const float* z, int ldz, float* Adec, int lda,
@@ -317,9 +352,8 @@ void decoder_dz(const Dims& d, const BatchSet* bs, int total, const float* dAdec
                 hipStream_t s);
 // dz_out[r, c] = z[r, c] > 0 ? dz_in[r, c] : 0   (dz_in pitch p_in)
 void mask_dz(int R, int dO, const float* dz_in, int p_in, const float* z, int ldz, float* dz_out, hipStream_t s);
-// d_x_root[r, c] = dMin[r, dO + c] + dQsub[r, c];  d_x_nbr[row, c] = dCsub[row, c]   (c < dm, outputs pitch dm)
-void attn_dx_out(int R, int RK, int dm, int dO, const float* dMin, int ldm, const float* dQsub, const float* dCsub,
-                 int ldsub, float* d_x_root, float* d_x_nbr, hipStream_t s);
+// d_x_root[r, c] = ds_row[r, c];  d_x_nbr[j, c] = ds_row[R + j, c]   (c < dm, outputs pitch dm)
+void attn_dx_out(int R, int RK, int dm, const float* ds_row, int ldh, float* d_x_root, float* d_x_nbr, hipStream_t s);
 void zero_f32(float* p, int n, hipStream_t s);
 
 // ---- k_writeback.hip ----------------------------------------------------------------
