@@ -96,6 +96,8 @@ def main():
     ap.add_argument("--events", type=int, default=None, help="shorten the event list (C4: default 2,000,000)")
     ap.add_argument("--lr", type=float, default=1e-4)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--side-stream", action="store_true", help="let the library fork independent work of a step onto its second stream")
+    ap.add_argument("--no-stage-events", action="store_true", help="do not time the two roofline kernels inside the timed region (the step then replays a captured HIP graph)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="first run the library's plain copy kernel on 256 MiB three times (reference for rocprofv3 --pmc "
                          "FETCH_SIZE / WRITE_SIZE readings)")
@@ -128,7 +130,7 @@ def main():
     d = P["d"]
     nrep = d.n_replicas
     ctx = tgnn.Context(d.n_nodes, d.d_mem, d.d_time, d.d_edge, d.d_static, d.n_heads, d.k, d.batch, n_replicas=nrep,
-                       flags=tgnn.FLAG_OVERWRITE_GRADS)
+                       flags=tgnn.FLAG_OVERWRITE_GRADS | (tgnn.FLAG_SIDE_STREAM if args.side_stream else 0))
     graph = tgnn.Graph(P["src"], P["dst"], P["ts"], d.n_nodes, P["efeat"])
     state = tgnn.State(d.n_nodes, d.d_mem, nrep, P["static"])
     params = tgnn.Params.from_numpy(P["params"])
@@ -162,7 +164,8 @@ def main():
     for s in range(args.warmup):
         run_step(s)
     torch.cuda.synchronize()
-    ctx.tgnn_profile_enable((1 << STAGE_ASSEMBLE) | (1 << STAGE_KV))
+    if not args.no_stage_events:
+        ctx.tgnn_profile_enable((1 << STAGE_ASSEMBLE) | (1 << STAGE_KV))
     ev = 0
     t0 = time.perf_counter()
     for s in range(args.warmup, args.warmup + args.steps):

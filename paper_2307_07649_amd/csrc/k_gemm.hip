@@ -478,9 +478,10 @@ void TnBatch::add(const float* D, int ldd, const float* A, int lda, int M, int N
 }
 
 // Every workgroup ends with one float atomic per element of its tile, and the L2 retires roughly one such
-// element per clock and channel: the number of m-chunks is what the atomics cost.  So the launch as a whole
-// gets about as many workgroups as the chip holds at once, shared out over the problems in proportion to their
-// multiply work; a small problem gets a handful of chunks instead of dozens.
+// element per clock and channel: the number of m-chunks is what the atomics cost.  So a small launch gets
+// about as many workgroups as the chip holds at once, shared out over the problems in proportion to their
+// multiply work (a small problem gets a handful of chunks instead of dozens); a large launch gets more,
+// about 16 stages each, so that the hardware dispatcher can balance them over several rounds.
 void TnBatch::launch(hipStream_t s) {
   if (g.n == 0) return;
   static const int target_wgs = getenv("TGNN_TN_WGS") ? atoi(getenv("TGNN_TN_WGS")) : 1024;
@@ -492,10 +493,12 @@ void TnBatch::launch(hipStream_t s) {
     work[i] = (double)rows[i] * g.p[i].tiles;
     total += work[i];
   }
+  double want = total / (16.0 * TN_ROWS);
+  if (want < target_wgs) want = target_wgs;
   int total_wgs = 0;
   for (int i = 0; i < g.n; ++i) {
     TnProblem& p = g.p[i];
-    int chunks = (int)(target_wgs * (work[i] / total) / p.tiles + 0.5);
+    int chunks = (int)(want * (work[i] / total) / p.tiles + 0.5);
     const int max_chunks = (rows[i] + 63) / 64;   // at least two stages each
     if (chunks > max_chunks) chunks = max_chunks;
     if (chunks < 1) chunks = 1;

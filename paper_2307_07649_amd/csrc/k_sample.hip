@@ -25,7 +25,7 @@ __global__ __launch_bounds__(256) void sample_kernel(const int64_t* __restrict__
   const int lane = threadIdx.x & 63;
   const int r = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
   if (r >= n_roots) return;  // whole wave leaves together
-  int node, rep_base = 0;
+  int node, rep_base = 0, root_gid = -1;
   double t;
   unsigned long long ep = 0ull;
   if (FUSED) {
@@ -39,14 +39,13 @@ __global__ __launch_bounds__(256) void sample_kernel(const int64_t* __restrict__
     t = bd.t[i];
     rep_base = bd.replica * N;
     ep = *uq.epoch;
+    root_gid = rep_base + node;
     if (lane == 0) {
-      const int gid = rep_base + node;
       root_node[r] = node;
       root_t[r] = t;
-      slot_gid[r] = gid;
+      slot_gid[r] = root_gid;
       slot_node[r] = node;
-      if (role < 2) atomicMax(winkey + gid, wb_key(ep, bd.ev_off + i, role));
-      uniq_claim(uq.utag, uq.uidx, uq.ucount, uq.ulist, uq.ucnt, gid, ep);
+      if (role < 2) atomicMax(winkey + root_gid, wb_key(ep, bd.ev_off + i, role));
     }
   } else {
     node = q_node[r];
@@ -78,15 +77,15 @@ __global__ __launch_bounds__(256) void sample_kernel(const int64_t* __restrict__
   const long long avail = pos - base;
   const int cnt = avail < k ? (int)avail : k;
   if (lane == 0) out_cnt[r] = cnt;
+  int nb = -1, ei = -1;
+  double ts = 0.0;
+  if (lane < cnt) {
+    const long long idx = pos - 1 - lane;
+    nb = g_nbr[idx];
+    ei = g_eid[idx];
+    ts = g_ts[idx];
+  }
   if (lane < k) {
-    int nb = -1, ei = -1;
-    double ts = 0.0;
-    if (lane < cnt) {
-      const long long idx = pos - 1 - lane;
-      nb = g_nbr[idx];
-      ei = g_eid[idx];
-      ts = g_ts[idx];
-    }
     const size_t o = (size_t)r * k + lane;
     out_nbr[o] = nb;
     out_eid[o] = ei;
@@ -94,8 +93,12 @@ __global__ __launch_bounds__(256) void sample_kernel(const int64_t* __restrict__
     if (FUSED) {
       slot_gid[(size_t)n_roots + o] = nb >= 0 ? rep_base + nb : -1;
       slot_node[(size_t)n_roots + o] = nb;
-      if (nb >= 0) uniq_claim(uq.utag, uq.uidx, uq.ucount, uq.ulist, uq.ucnt, rep_base + nb, ep);
     }
+  }
+  if (FUSED) {
+    // lanes 0 .. k-1 claim their neighbour, lane k (k < 64) the root itself: one row-counter atomic per wave
+    const int claim = lane < k ? (nb >= 0 ? rep_base + nb : -1) : (lane == k ? root_gid : -1);
+    uniq_claim(uq.utag, uq.uidx, uq.ucount, uq.ulist, uq.ucnt, claim, ep);
   }
 }
 

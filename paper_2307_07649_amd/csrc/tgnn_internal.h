@@ -248,13 +248,23 @@ void sample_recent(const Dims& d, const tgnn_graph* g, const int32_t* node, cons
                    int32_t* out_nbr, int32_t* out_eid, double* out_ts, int32_t* out_cnt, hipStream_t s);
 
 // ---- k_unique.hip -------------------------------------------------------------------
-// Claim (replica, node) `gid` for this step; the first claimant allocates the node's row.
+// Claim (replica, node) `gid` (or -1: nothing) for this step; the first claimant allocates the node's row.
+// Called by all lanes of a wavefront together: the lanes that won a claim take their row numbers from one
+// atomic on the shared row counter (thousands of waves adding to one address serialise in the L2).
 __device__ __forceinline__ void uniq_claim(unsigned long long* utag, int32_t* uidx, int32_t* ucount, int32_t* ulist,
                                            int32_t* ucnt, int gid, unsigned long long epoch) {
   // popular nodes are claimed thousands of times per step: look before touching the atomic unit
-  if (__atomic_load_n(utag + gid, __ATOMIC_RELAXED) >= epoch) return;
-  if (atomicMax(utag + gid, epoch) < epoch) {
-    const int row = atomicAdd(ucount, 1);
+  bool won = false;
+  if (gid >= 0 && __atomic_load_n(utag + gid, __ATOMIC_RELAXED) < epoch) won = atomicMax(utag + gid, epoch) < epoch;
+  const unsigned long long winners = __ballot(won);
+  if (winners == 0ull) return;
+  const int lane = threadIdx.x & 63;
+  const int leader = __ffsll((long long)winners) - 1;
+  int base = 0;
+  if (lane == leader) base = atomicAdd(ucount, __popcll(winners));
+  base = __shfl(base, leader);
+  if (won) {
+    const int row = base + __popcll(winners & ((1ull << lane) - 1ull));
     uidx[gid] = row;
     ulist[row] = gid;
     ucnt[row] = 0;
