@@ -158,44 +158,64 @@ void time_grad(const float* dphi, int ld, int col0, const float* msin, int p_msi
 }
 
 // The query's time encoding is Phi(0) = cos(time_b): its gradient, and that of the columns of W_q which
-// multiply it, need only the column sums of dq.
-// QPHI_BLOCKS blocks take a range of roots each and write one partial; the remaining partial slots of the
-// region are cleared (time_grad_finish adds all TG_BLOCKS of them).
-constexpr int QPHI_BLOCKS = 64;
+// multiply it, need only the column sums of dq over the roots:
+//   g_b[c]           += -sin(time_b[c]) * sum_n colsum[n] wq[n, dx + c]
+//   g_wq[n, dx + c]  += colsum[n] cos(time_b[c])
+// Blocks add their part of the column sums to a scratch vector; the block that finishes last (ticket
+// counter) turns the total into the two gradients and clears scratch and counter for the next call.
+constexpr int QPHI_BLOCKS = 256;
 __global__ __launch_bounds__(256) void qphi_grad_kernel(const float* __restrict__ dq, int ld, int R, int dO,
                                                         const float* __restrict__ wq, int dq_w, int dx, int dt,
-                                                        const float* __restrict__ time_b,
-                                                        float* __restrict__ partial, float* __restrict__ g_wq) {
-  __shared__ float colsum[256];
-  float* out = partial + (size_t)blockIdx.x * 2 * dt;
-  if (blockIdx.x >= QPHI_BLOCKS) {
-    for (int c = threadIdx.x; c < 2 * dt; c += blockDim.x) out[c] = 0.f;
-    return;
-  }
-  const int per = (R + QPHI_BLOCKS - 1) / QPHI_BLOCKS;
+                                                        const float* __restrict__ time_b, float* colsum,
+                                                        unsigned int* ticket, float* __restrict__ g_b,
+                                                        float* __restrict__ g_wq) {
+  __shared__ float part[4][256];
+  __shared__ bool last;
+  const int cx = threadIdx.x & 63, cy = threadIdx.x >> 6;
+  const int per = (R + gridDim.x - 1) / gridDim.x;
   const int r0 = min(R, (int)blockIdx.x * per), r1 = min(R, r0 + per);
-  for (int n = threadIdx.x; n < dO; n += blockDim.x) {   // d_o <= 256
+  for (int n0 = 0; n0 < dO; n0 += 64) {   // d_o <= 256
+    const int n = n0 + cx;
     float a = 0.f;
-    for (int r = r0; r < r1; ++r) a += dq[(size_t)r * ld + n];
-    colsum[n] = a;
+    if (n < dO)
+      for (int r = r0 + cy; r < r1; r += 4) a += dq[(size_t)r * ld + n];
+    part[cy][n0 + cx] = a;
   }
   __syncthreads();
+  if (r1 > r0)
+    for (int n = threadIdx.x; n < dO; n += blockDim.x) atomicAdd(colsum + n, part[0][n] + part[1][n] + part[2][n] + part[3][n]);
+  __threadfence();
+  __syncthreads();
+  if (threadIdx.x == 0) last = atomicAdd(ticket, 1u) == gridDim.x - 1;
+  __syncthreads();
+  if (!last) return;
+  __threadfence();
+  float* total = &part[0][0];
+  for (int n = threadIdx.x; n < dO; n += blockDim.x) {
+    total[n] = __hip_atomic_load(colsum + n, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(colsum + n, 0.f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+  if (threadIdx.x == 0) __hip_atomic_store(ticket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  __syncthreads();
   for (int c = threadIdx.x; c < dt; c += blockDim.x) {
-    float v = 0.f;
-    for (int n = 0; n < dO; ++n) v += colsum[n] * wq[(size_t)n * dq_w + dx + c];
     float sn, cs;
     sincos_reduced((double)time_b[c], sn, cs);
-    out[c] = 0.f;
-    out[dt + c] = -sn * v;
-    // weight gradient of the Phi(0) columns of W_q: (sum_r dq[r, n]) cos(time_b[c])
-    for (int n = 0; n < dO; ++n) atomicAdd(g_wq + (size_t)n * dq_w + dx + c, colsum[n] * cs);
+    float v = 0.f;
+    for (int n = 0; n < dO; ++n) {
+      v += total[n] * wq[(size_t)n * dq_w + dx + c];
+      atomicAdd(g_wq + (size_t)n * dq_w + dx + c, total[n] * cs);
+    }
+    atomicAdd(g_b + c, -sn * v);
   }
 }
 
 void qphi_grad(const float* dq, int ld, int R, int dO, const float* wq, int dq_w, int dx, int dt, const float* time_b,
-               float* partial, float* g_wq, hipStream_t s) {
-  hipLaunchKernelGGL(qphi_grad_kernel, dim3(TG_BLOCKS), dim3(256), 0, s, dq, ld, R, dO, wq, dq_w, dx, dt, time_b, partial,
-                     g_wq);
+               float* colsum, unsigned int* ticket, float* g_b, float* g_wq, hipStream_t s) {
+  if (R <= 0) return;
+  int blocks = (R + 15) / 16;
+  if (blocks > QPHI_BLOCKS) blocks = QPHI_BLOCKS;
+  hipLaunchKernelGGL(qphi_grad_kernel, dim3(blocks), dim3(256), 0, s, dq, ld, R, dO, wq, dq_w, dx, dt, time_b, colsum,
+                     ticket, g_b, g_wq);
 }
 
 // grid (ceil(2 dt / 32), TGF_SPLIT); block = 32 columns x 32 partial groups

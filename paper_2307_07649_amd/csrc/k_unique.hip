@@ -54,7 +54,8 @@ __global__ void uniq_map_kernel(int S, const int32_t* __restrict__ slot_gid, con
   wave_counted_add(ucnt, row, false);
 }
 
-// exclusive scan of ucnt[0 .. U) into rowptr[0 .. U] and cursor[0 .. U); one block
+// exclusive scan of ucnt[0 .. U) into rowptr[0 .. U] and cursor[0 .. U); one block.  Each thread owns a
+// contiguous range; its loads are issued eight at a time so that their latencies overlap.
 __global__ __launch_bounds__(1024) void uniq_scan_kernel(const int32_t* __restrict__ ucount,
                                                          const int32_t* __restrict__ ucnt,
                                                          int32_t* __restrict__ rowptr, int32_t* __restrict__ cursor) {
@@ -63,7 +64,13 @@ __global__ __launch_bounds__(1024) void uniq_scan_kernel(const int32_t* __restri
   const int per = (U + 1023) / 1024;
   const int lo = min(U, (int)threadIdx.x * per), hi = min(U, lo + per);
   int sum = 0;
-  for (int i = lo; i < hi; ++i) sum += ucnt[i];
+  for (int i = lo; i < hi; i += 8) {
+    int v[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) v[j] = i + j < hi ? ucnt[i + j] : 0;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) sum += v[j];
+  }
   part[threadIdx.x] = sum;
   __syncthreads();
   for (int off = 1; off < 1024; off <<= 1) {
@@ -73,10 +80,18 @@ __global__ __launch_bounds__(1024) void uniq_scan_kernel(const int32_t* __restri
     __syncthreads();
   }
   int run = part[threadIdx.x] - sum;
-  for (int i = lo; i < hi; ++i) {
-    rowptr[i] = run;
-    cursor[i] = run;
-    run += ucnt[i];
+  for (int i = lo; i < hi; i += 8) {
+    int v[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) v[j] = i + j < hi ? ucnt[i + j] : 0;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      if (i + j < hi) {
+        rowptr[i + j] = run;
+        cursor[i + j] = run;
+      }
+      run += v[j];
+    }
   }
   if (threadIdx.x == 1023) rowptr[U] = part[1023];
 }

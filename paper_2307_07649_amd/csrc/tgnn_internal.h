@@ -58,7 +58,8 @@ struct Ws {
   BatchSet* bs_dev;                            // device copy of the step's batch descriptors
   struct SgdSet* sgd_dev;                      // device copy of the parameter/gradient pointer table
   float *msinX, *msinC;                        // [S,ldt] [RK,ldt]  -sin of the time-encoding arguments
-  float* tg_partial;                           // [3, TG_BLOCKS, 2, dt] partial time-encoding gradient sums
+  float* tg_partial;                           // [2, TG_BLOCKS, 2, dt] partial time-encoding gradient sums
+  float* q_colsum;  unsigned int* q_ticket;    // [d_o], [1] scratch of qphi_grad (zero between calls)
   // GRU
   float *X, *Hm, *gi, *gh, *gates;             // [S,ldx] [S,ldh] [S,ld3] [S,ld3] [S,4*ldh]
   float* Xrow;                                 // [S,ldxr] x = {s' | static} per distinct node (row)
@@ -248,28 +249,6 @@ void sample_recent(const Dims& d, const tgnn_graph* g, const int32_t* node, cons
                    int32_t* out_nbr, int32_t* out_eid, double* out_ts, int32_t* out_cnt, hipStream_t s);
 
 // ---- k_unique.hip -------------------------------------------------------------------
-// Claim (replica, node) `gid` (or -1: nothing) for this step; the first claimant allocates the node's row.
-// Called by all lanes of a wavefront together: the lanes that won a claim take their row numbers from one
-// atomic on the shared row counter (thousands of waves adding to one address serialise in the L2).
-__device__ __forceinline__ void uniq_claim(unsigned long long* utag, int32_t* uidx, int32_t* ucount, int32_t* ulist,
-                                           int32_t* ucnt, int gid, unsigned long long epoch) {
-  // popular nodes are claimed thousands of times per step: look before touching the atomic unit
-  bool won = false;
-  if (gid >= 0 && __atomic_load_n(utag + gid, __ATOMIC_RELAXED) < epoch) won = atomicMax(utag + gid, epoch) < epoch;
-  const unsigned long long winners = __ballot(won);
-  if (winners == 0ull) return;
-  const int lane = threadIdx.x & 63;
-  const int leader = __ffsll((long long)winners) - 1;
-  int base = 0;
-  if (lane == leader) base = atomicAdd(ucount, __popcll(winners));
-  base = __shfl(base, leader);
-  if (won) {
-    const int row = base + __popcll(winners & ((1ull << lane) - 1ull));
-    uidx[gid] = row;
-    ulist[row] = gid;
-    ucnt[row] = 0;
-  }
-}
 void uniq_map(tgnn_ctx* ctx, int S, hipStream_t s);    // slot -> row map, slots per row
 void uniq_sort(tgnn_ctx* ctx, int S, hipStream_t s);   // row-sorted slot list (needed by seg_reduce only)
 // dP[row] += {dKV[slot] | 0} of the row's neighbour slots and {0 | dq[r] | dz[r]} of its root slots
@@ -327,19 +306,18 @@ void stage_x_rows(int R, int k, int dx, const float* x_root, const float* x_nbr,
 void gru_gates_fwd(const Dims& d, int n, const int* n_dev, const float* gi, const float* gh, const float* Hm,
                    const int32_t* has, float* gates, float* x_out, int ld_x, const float* stat, const int32_t* gid,
                    float* zero_buf, int zero_w, hipStream_t s);
-// Gradient of the time-encoding phase through the query's Phi(0): per block of roots,
-// partial[block, 1, c] = -sin(time_b[c]) * sum_n (sum_r dq[r, n]) wq[n, dx + c]   (frequency part: 0); also
-// g_wq[n, dx + c] += (sum_r dq[r, n]) cos(time_b[c]), the weight gradient of the columns that multiply Phi(0).
+// Gradients through the query's time encoding Phi(0) = cos(time_b), from the column sums of dq [R, ld]:
+// g_b[c] += -sin(time_b[c]) sum_n colsum[n] wq[n, dx + c] and g_wq[n, dx + c] += colsum[n] cos(time_b[c]).
+// colsum [d_o] and ticket [1] are scratch that is zero on entry and left zero.
 void qphi_grad(const float* dq, int ld, int R, int dO, const float* wq, int dq_w, int dx, int dt, const float* time_b,
-               float* partial, float* g_wq, hipStream_t s);
+               float* colsum, unsigned int* ticket, float* g_b, float* g_wq, hipStream_t s);
 // ds [n, ldh] = gradient reaching s' per row
 void gru_gates_bwd(const Dims& d, int n, const int* n_dev, const float* ds, const float* gates, const float* Hm,
                    const int32_t* has, float* dgi, float* dgh, hipStream_t s);
 // Time-encoding gradients in two stages.  time_grad: column sums of dPhi [n, ld] (dt columns from col0) times
 // the stored -sin(arg) [n, p_msin] (and times delta[n] for time_w) per block of rows, written to
-// partial[TG_BLOCKS, 2, dt] (always all TG_BLOCKS entries).  msin == NULL: delta = 0 for every row (the
-// query's Phi(0)); -sin(time_b[c]) is used and the time_w sums are zero.  time_grad_finish: adds the
-// partials of n_calls consecutive regions to g_w / g_b.
+// partial[TG_BLOCKS, 2, dt] (always all TG_BLOCKS entries).  time_grad_finish: adds the partials of n_calls
+// consecutive regions to g_w / g_b.
 constexpr int TG_BLOCKS = 1024;
 void time_grad(const float* dphi, int ld, int col0, const float* msin, int p_msin, const double* delta, int n, int dt,
                const float* time_b, float* partial, hipStream_t s, const int* n_dev = nullptr);
