@@ -39,9 +39,9 @@ def flops_kv(d, n_roots):
 
 
 def assemble_bytes(d, n_roots):
-    """Per-slot attention input: per neighbour slot read the edge-feature row, the neighbour's event time and
-    update time, and write the {e | Phi} row, the -sin row and the time difference."""
-    per_nbr = 4 * d.d_edge + 4 * (d.d_edge + d.d_time) + 4 * d.d_time + 4 + 8 + 8 + 8
+    """Per-slot attention input: per neighbour slot read the edge-feature row, its index and the neighbour's
+    update time, and write the {e | Phi} row and the time difference."""
+    per_nbr = 4 * d.d_edge + 4 * (d.d_edge + d.d_time) + 4 + 8 + 8
     return n_roots * d.k * per_nbr
 
 

@@ -104,14 +104,17 @@ void gru_gates_bwd(const Dims& d, int n, const int* n_dev, const float* ds, cons
                      dgh);
 }
 
-// Time-encoding gradients: g_b[c] += sum_n dphi[n, col0 + c] * msin[n, c] ;  g_w[c] += sum_n dphi * msin * delta_n.
+// Time-encoding gradients of Phi(delta)_c = cos(w_c delta + b_c):
+//   g_b[c] += sum_n dphi[n, col0 + c] * (-sin(w_c delta_n + b_c)),   g_w[c] += the same terms times delta_n.
+// The sine is evaluated again here (the argument is formed exactly as in the forward kernels) rather than
+// stored by the forward pass: a [rows, d_t] matrix written and read back costs more than the arithmetic.
 // Stage 1 (time_grad): a block owns a contiguous range of rows and writes its column sums to a partial
 // buffer [TG_BLOCKS, 2, dt] (no atomics: hundreds of blocks adding to the same 2*dt addresses serialise).
-// Stage 2 (time_grad_finish): one block adds all partials of the step to the gradient tensors.
+// Stage 2 (time_grad_finish): adds all partials of the step to the gradient tensors.
 __global__ __launch_bounds__(256) void time_grad_kernel(const float* __restrict__ dphi, int ld, int col0,
-                                                        const float* __restrict__ msin, int p_msin,
                                                         const double* __restrict__ delta, int n_max,
                                                         const int* __restrict__ n_dev, int rows_per_block, int dt,
+                                                        const float* __restrict__ time_w,
                                                         const float* __restrict__ time_b,
                                                         float* __restrict__ partial) {
   __shared__ float sw[4][64], sb[4][64];
@@ -124,18 +127,15 @@ __global__ __launch_bounds__(256) void time_grad_kernel(const float* __restrict_
     const int c = c0 + cx;
     float aw = 0.f, ab = 0.f;
     if (c < dt) {
-      if (msin != nullptr) {
-#pragma unroll 8
-        for (int r = r0 + cy; r < r1; r += 4) {
-          const float t = dphi[(size_t)r * ld + col0 + c] * msin[(size_t)r * p_msin + c];
-          ab += t;
-          aw += t * (float)delta[r];
-        }
-      } else {
+      const double w = (double)time_w[c], b = (double)time_b[c];
+#pragma unroll 4
+      for (int r = r0 + cy; r < r1; r += 4) {
+        const double dl = delta[r];
         float sn, cs;
-        sincos_reduced((double)time_b[c], sn, cs);
-#pragma unroll 8
-        for (int r = r0 + cy; r < r1; r += 4) ab -= dphi[(size_t)r * ld + col0 + c] * sn;
+        sincos_reduced(fma(w, dl, b), sn, cs);
+        const float t = -dphi[(size_t)r * ld + col0 + c] * sn;
+        ab += t;
+        aw += t * (float)dl;
       }
     }
     sw[cy][cx] = aw;
@@ -149,12 +149,12 @@ __global__ __launch_bounds__(256) void time_grad_kernel(const float* __restrict_
   }
 }
 
-void time_grad(const float* dphi, int ld, int col0, const float* msin, int p_msin, const double* delta, int n, int dt,
+void time_grad(const float* dphi, int ld, int col0, const double* delta, int n, int dt, const float* time_w,
                const float* time_b, float* partial, hipStream_t s, const int* n_dev) {
   if (n <= 0) return;
   const int rpb = (((n + TG_BLOCKS - 1) / TG_BLOCKS) + 3) & ~3;
-  hipLaunchKernelGGL(time_grad_kernel, dim3(TG_BLOCKS), dim3(256), 0, s, dphi, ld, col0, msin, p_msin, delta, n, n_dev,
-                     rpb, dt, time_b, partial);
+  hipLaunchKernelGGL(time_grad_kernel, dim3(TG_BLOCKS), dim3(256), 0, s, dphi, ld, col0, delta, n, n_dev, rpb, dt, time_w,
+                     time_b, partial);
 }
 
 // The query's time encoding is Phi(0) = cos(time_b): its gradient, and that of the columns of W_q which

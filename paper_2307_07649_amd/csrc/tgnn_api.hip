@@ -97,7 +97,6 @@ static void layout(const Dims& d, Ws& w, Bump& b) {
   w.ds_row = b.take<float>(S * d.ldh);
   w.bs_dev = b.take<BatchSet>(1);
   w.sgd_dev = b.take<SgdSet>(1);
-  w.msinX = b.take<float>(S * d.ldt); w.msinC = b.take<float>(RK * d.ldt);
   w.tg_partial = b.take<float>((size_t)2 * TG_BLOCKS * 2 * d.dt);
   w.q_colsum = b.take<float>(256); w.q_ticket = b.take<unsigned int>(1);
   w.X = b.take<float>(S * d.ldx); w.Hm = b.take<float>(S * d.ldh);
@@ -238,7 +237,7 @@ static void attn_backward(tgnn_ctx* ctx, tgnn_params* g, const tgnn_params* p, i
     side.flush(tn);
   }
   gemm_nt(w.dKV, d.ldkv, w.WceT_phi, d.ldkv, nullptr, w.dPhi, d.ldt, RK, d.dt, d.ldkv, d.ldt, false, s);
-  time_grad(w.dPhi, d.ldt, 0, w.msinC, d.ldt, w.dtk, RK, d.dt, p->time_b, w.tg_partial, s);
+  time_grad(w.dPhi, d.ldt, 0, w.dtk, RK, d.dt, p->time_w, p->time_b, w.tg_partial, s);
   qphi_grad(w.dq, d.ldh, R, d.dO, p->wq, d.dq, d.dx, d.dt, p->time_b, w.q_colsum, w.q_ticket, g->time_b, g->wq, s);
 }
 
@@ -506,7 +505,7 @@ int32_t tgnn_temporal_attn_fwd(tgnn_ctx* ctx, const tgnn_params* p, int32_t n_ro
   memset(&a, 0, sizeof(a));
   a.efeat = e_nbr; a.neid = nullptr; a.cnt = cnt; a.dt_in = dt_nbr;
   a.time_w = p->time_w; a.time_b = p->time_b;
-  a.CE = w.CE; a.ldce = d.ldce; a.msin = w.msinC; a.p_msin = d.ldt; a.dtk = w.dtk;
+  a.CE = w.CE; a.ldce = d.ldce; a.dtk = w.dtk;
   a.R = n_roots; a.k = d.k; a.de = d.de; a.dt = d.dt; a.dt_source = 0;
   assemble_ce(a, s);
   attn_forward(ctx, p, n_roots, n_roots * (1 + d.k), nullptr, nullptr, w.cnt, nullptr, s);
@@ -737,7 +736,6 @@ static int enqueue_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
   a.o_mem = w.Hm; a.p_mem = d.ldh; a.z_mem = d.ldh - d.dm;
   a.o_mail = w.X; a.p_mail = d.ldx;
   a.o_phi = w.X + 2 * d.dm; a.p_phi = d.ldx;
-  a.o_msin = w.msinX; a.p_msin = d.ldt;
   a.o_ef = w.X + 2 * d.dm + d.dt; a.p_ef = d.ldx; a.z_ef = d.ldx - d.d_in;
   a.o_tau = w.tau; a.o_delta = w.delta; a.o_has = w.has;
   a.time_w = p->time_w; a.time_b = p->time_b;
@@ -770,7 +768,7 @@ static int enqueue_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
   aa.efeat = g->efeat; aa.neid = w.neid; aa.cnt = w.cnt; aa.slot_row = w.slot_row;
   aa.root_t = w.root_t; aa.nts = w.nts; aa.tau_nbr = w.tau; aa.dt_in = nullptr;
   aa.time_w = p->time_w; aa.time_b = p->time_b;
-  aa.CE = w.CE; aa.ldce = d.ldce; aa.msin = w.msinC; aa.p_msin = d.ldt; aa.dtk = w.dtk;
+  aa.CE = w.CE; aa.ldce = d.ldce; aa.dtk = w.dtk;
   aa.R = R; aa.k = d.k; aa.de = d.de; aa.dt = d.dt; aa.dt_source = d.dt_source;
   tm.begin(7);
   assemble_ce(aa, s);
@@ -817,8 +815,8 @@ static int enqueue_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
   }
   tm.begin(17);
   gemm_nt(w.dgi, d.ld3, w.WihT_phi, d.ld3, nullptr, w.dphi_g, d.ldt, U, d.dt, d.ld3, d.ldt, false, s, w.ucount);
-  time_grad(w.dphi_g, d.ldt, 0, w.msinX, d.ldt, w.delta, U, d.dt, p->time_b,
-            w.tg_partial + (size_t)TG_BLOCKS * 2 * d.dt, s, w.ucount);
+  time_grad(w.dphi_g, d.ldt, 0, w.delta, U, d.dt, p->time_w, p->time_b, w.tg_partial + (size_t)TG_BLOCKS * 2 * d.dt, s,
+            w.ucount);
   time_grad_finish(w.tg_partial, 2, d.dt, grads->time_w, grads->time_b, s);
   tm.end(17);
   side.join();   // all weight gradients

@@ -57,7 +57,6 @@ struct Ws {
   float* ds_row;                               // [maxS, ldh] gradient reaching s' per row
   BatchSet* bs_dev;                            // device copy of the step's batch descriptors
   struct SgdSet* sgd_dev;                      // device copy of the parameter/gradient pointer table
-  float *msinX, *msinC;                        // [S,ldt] [RK,ldt]  -sin of the time-encoding arguments
   float* tg_partial;                           // [2, TG_BLOCKS, 2, dt] partial time-encoding gradient sums
   float* q_colsum;  unsigned int* q_ticket;    // [d_o], [1] scratch of qphi_grad (zero between calls)
   // GRU
@@ -270,7 +269,6 @@ struct GatherArgs {
   int gid_add;              // added to every non-negative slot_gid entry (replica offset)
   // destinations (pitches in floats)
   float *o_mem, *o_mail, *o_ef, *o_phi;  // o_phi NULL: no time encoding
-  float* o_msin;  int p_msin;            // -sin of the time-encoding argument (for the backward pass), may be NULL
   int p_mem, p_mail, p_ef, p_phi;
   int z_mem, z_mail, z_ef, z_phi;  // number of zero floats to append after each segment (row padding)
   double *o_mem_ts, *o_mail_ts, *o_tau, *o_delta;
@@ -280,8 +278,8 @@ struct GatherArgs {
 };
 void gather_rows(const GatherArgs& a, hipStream_t s);
 
-// Per neighbour slot (r, j): CE row {e_vw | Phi(dt)} (Eq. 5-6 without the node part), -sin of the arguments,
-// and the time difference itself.
+// Per neighbour slot (r, j): CE row {e_vw | Phi(dt)} (Eq. 5-6 without the node part) and the time difference
+// itself (kept for the backward pass).
 struct CeArgs {
   const float* efeat;                   // [E, de], or [R*k, de] when neid == NULL
   const int32_t *neid, *cnt;
@@ -290,7 +288,6 @@ struct CeArgs {
   const double* dt_in;                  // non-NULL: time differences given directly [R*k]
   const float *time_w, *time_b;
   float* CE;  int ldce;
-  float* msin;  int p_msin;             // [R*k, p_msin]
   double* dtk;
   int R, k, de, dt, dt_source;
 };
@@ -315,11 +312,11 @@ void qphi_grad(const float* dq, int ld, int R, int dO, const float* wq, int dq_w
 void gru_gates_bwd(const Dims& d, int n, const int* n_dev, const float* ds, const float* gates, const float* Hm,
                    const int32_t* has, float* dgi, float* dgh, hipStream_t s);
 // Time-encoding gradients in two stages.  time_grad: column sums of dPhi [n, ld] (dt columns from col0) times
-// the stored -sin(arg) [n, p_msin] (and times delta[n] for time_w) per block of rows, written to
+// -sin(time_w[c] delta[n] + time_b[c]) (and times delta[n] for time_w) per block of rows, written to
 // partial[TG_BLOCKS, 2, dt] (always all TG_BLOCKS entries).  time_grad_finish: adds the partials of n_calls
 // consecutive regions to g_w / g_b.
 constexpr int TG_BLOCKS = 1024;
-void time_grad(const float* dphi, int ld, int col0, const float* msin, int p_msin, const double* delta, int n, int dt,
+void time_grad(const float* dphi, int ld, int col0, const double* delta, int n, int dt, const float* time_w,
                const float* time_b, float* partial, hipStream_t s, const int* n_dev = nullptr);
 void time_grad_finish(const float* partial, int n_calls, int dt, float* g_w, float* g_b, hipStream_t s);
 
