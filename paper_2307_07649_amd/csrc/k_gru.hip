@@ -161,16 +161,11 @@ void time_grad(const float* dphi, int ld, int col0, const double* delta, int n, 
 // multiply it, need only the column sums of dq over the roots:
 //   g_b[c]           += -sin(time_b[c]) * sum_n colsum[n] wq[n, dx + c]
 //   g_wq[n, dx + c]  += colsum[n] cos(time_b[c])
-// Blocks add their part of the column sums to a scratch vector; the block that finishes last (ticket
-// counter) turns the total into the two gradients and clears scratch and counter for the next call.
-constexpr int QPHI_BLOCKS = 256;
-__global__ __launch_bounds__(256) void qphi_grad_kernel(const float* __restrict__ dq, int ld, int R, int dO,
-                                                        const float* __restrict__ wq, int dq_w, int dx, int dt,
-                                                        const float* __restrict__ time_b, float* colsum,
-                                                        unsigned int* ticket, float* __restrict__ g_b,
-                                                        float* __restrict__ g_wq) {
+// qphi_colsum: QPHI_BLOCKS blocks each write the column sums of their range of roots to q_part[block, d_o].
+// time_grad_finish adds them up and applies the two formulas (extra grid rows of that kernel).
+__global__ __launch_bounds__(256) void qphi_colsum_kernel(const float* __restrict__ dq, int ld, int R, int dO,
+                                                          float* __restrict__ q_part) {
   __shared__ float part[4][256];
-  __shared__ bool last;
   const int cx = threadIdx.x & 63, cy = threadIdx.x >> 6;
   const int per = (R + gridDim.x - 1) / gridDim.x;
   const int r0 = min(R, (int)blockIdx.x * per), r1 = min(R, r0 + per);
@@ -182,48 +177,49 @@ __global__ __launch_bounds__(256) void qphi_grad_kernel(const float* __restrict_
     part[cy][n0 + cx] = a;
   }
   __syncthreads();
-  if (r1 > r0)
-    for (int n = threadIdx.x; n < dO; n += blockDim.x) atomicAdd(colsum + n, part[0][n] + part[1][n] + part[2][n] + part[3][n]);
-  __threadfence();
-  __syncthreads();
-  if (threadIdx.x == 0) last = atomicAdd(ticket, 1u) == gridDim.x - 1;
-  __syncthreads();
-  if (!last) return;
-  __threadfence();
-  float* total = &part[0][0];
-  for (int n = threadIdx.x; n < dO; n += blockDim.x) {
-    total[n] = __hip_atomic_load(colsum + n, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    __hip_atomic_store(colsum + n, 0.f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  }
-  if (threadIdx.x == 0) __hip_atomic_store(ticket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  __syncthreads();
-  for (int c = threadIdx.x; c < dt; c += blockDim.x) {
-    float sn, cs;
-    sincos_reduced((double)time_b[c], sn, cs);
-    float v = 0.f;
-    for (int n = 0; n < dO; ++n) {
-      v += total[n] * wq[(size_t)n * dq_w + dx + c];
-      atomicAdd(g_wq + (size_t)n * dq_w + dx + c, total[n] * cs);
-    }
-    atomicAdd(g_b + c, -sn * v);
-  }
+  for (int n = threadIdx.x; n < dO; n += blockDim.x)
+    q_part[(size_t)blockIdx.x * dO + n] = part[0][n] + part[1][n] + part[2][n] + part[3][n];
 }
 
-void qphi_grad(const float* dq, int ld, int R, int dO, const float* wq, int dq_w, int dx, int dt, const float* time_b,
-               float* colsum, unsigned int* ticket, float* g_b, float* g_wq, hipStream_t s) {
-  if (R <= 0) return;
-  int blocks = (R + 15) / 16;
-  if (blocks > QPHI_BLOCKS) blocks = QPHI_BLOCKS;
-  hipLaunchKernelGGL(qphi_grad_kernel, dim3(blocks), dim3(256), 0, s, dq, ld, R, dO, wq, dq_w, dx, dt, time_b, colsum,
-                     ticket, g_b, g_wq);
+void qphi_colsum(const float* dq, int ld, int R, int dO, float* q_part, hipStream_t s) {
+  hipLaunchKernelGGL(qphi_colsum_kernel, dim3(QPHI_BLOCKS), dim3(256), 0, s, dq, ld, R, dO, q_part);
 }
 
-// grid (ceil(2 dt / 32), TGF_SPLIT); block = 32 columns x 32 partial groups
+// grid (ceil(2 dt / 32), TGF_SPLIT + q_rows); block = 32 columns x 32 partial groups.  Rows y < TGF_SPLIT add
+// the time_grad partials; rows y >= TGF_SPLIT (present when q.part != NULL) take 1024 consecutive (n, c) pairs
+// of the query's Phi(0) gradients each.
 constexpr int TGF_SPLIT = 8;
 __global__ __launch_bounds__(1024) void time_grad_finish_kernel(const float* __restrict__ partial, int n_partials,
                                                                 int dt, float* __restrict__ g_w,
-                                                                float* __restrict__ g_b) {
+                                                                float* __restrict__ g_b, QPhi q) {
   __shared__ float red[32][33];
+  if (blockIdx.y >= TGF_SPLIT) {
+    if (blockIdx.x != 0) return;
+    __shared__ float gb[1024];   // per-thread contribution to g_b[c], summed over the block's n per c below
+    const int i = (blockIdx.y - TGF_SPLIT) * 1024 + threadIdx.x;
+    const int n = i / dt, c = i - n * dt;
+    float contrib = 0.f;
+    if (n < q.dO) {
+      float cs_n = 0.f;
+      for (int b = 0; b < QPHI_BLOCKS; ++b) cs_n += q.part[(size_t)b * q.dO + n];
+      float sn, cs;
+      sincos_reduced((double)q.time_b[c], sn, cs);
+      atomicAdd(q.g_wq + (size_t)n * q.dq_w + q.dx + c, cs_n * cs);
+      contrib = -sn * cs_n * q.wq[(size_t)n * q.dq_w + q.dx + c];
+    }
+    gb[threadIdx.x] = contrib;
+    __syncthreads();
+    // pairs are numbered n * dt + c: thread t < dt sums the entries of this block whose c equals
+    // (first c of the block + t) mod dt
+    if ((int)threadIdx.x < dt) {
+      const int first = (blockIdx.y - TGF_SPLIT) * 1024;
+      const int c0 = (first + threadIdx.x) % dt;
+      float acc = 0.f;
+      for (int t = threadIdx.x; t < 1024; t += dt) acc += gb[t];
+      atomicAdd(g_b + c0, acc);
+    }
+    return;
+  }
   const int cx = threadIdx.x & 31, cy = threadIdx.x >> 5;
   const int c = blockIdx.x * 32 + cx;
   float acc = 0.f;
@@ -241,9 +237,12 @@ __global__ __launch_bounds__(1024) void time_grad_finish_kernel(const float* __r
   }
 }
 
-void time_grad_finish(const float* partial, int n_calls, int dt, float* g_w, float* g_b, hipStream_t s) {
-  hipLaunchKernelGGL(time_grad_finish_kernel, dim3((2 * dt + 31) / 32, TGF_SPLIT), dim3(1024), 0, s, partial,
-                     n_calls * TG_BLOCKS, dt, g_w, g_b);
+void time_grad_finish(const float* partial, int n_calls, int dt, float* g_w, float* g_b, const QPhi* q, hipStream_t s) {
+  QPhi qq;
+  if (q != nullptr) qq = *q;
+  const int q_rows = qq.part != nullptr ? (qq.dO * dt + 1023) / 1024 : 0;
+  hipLaunchKernelGGL(time_grad_finish_kernel, dim3((2 * dt + 31) / 32, TGF_SPLIT + q_rows), dim3(1024), 0, s, partial,
+                     n_calls * TG_BLOCKS, dt, g_w, g_b, qq);
 }
 
 }  // namespace tgnn

@@ -98,7 +98,7 @@ static void layout(const Dims& d, Ws& w, Bump& b) {
   w.bs_dev = b.take<BatchSet>(1);
   w.sgd_dev = b.take<SgdSet>(1);
   w.tg_partial = b.take<float>((size_t)2 * TG_BLOCKS * 2 * d.dt);
-  w.q_colsum = b.take<float>(256); w.q_ticket = b.take<unsigned int>(1);
+  w.q_part = b.take<float>((size_t)QPHI_BLOCKS * d.dO);
   w.X = b.take<float>(S * d.ldx); w.Hm = b.take<float>(S * d.ldh);
   w.gi = b.take<float>(S * d.ld3); w.gh = b.take<float>(S * d.ld3);
   w.gates = b.take<float>(S * 4 * d.ldh); w.Xrow = b.take<float>(S * d.ldxr);
@@ -218,8 +218,8 @@ static void attn_forward(tgnn_ctx* ctx, const tgnn_params* p, int R, int n_rows,
 
 // From ws.dz (already masked by the merge ReLU) down to ws.dP (per-node projection gradients, not yet
 // reduced over slots), ws.dKV and ws.dq; queues the weight-gradient GEMMs of W_o (attention-output
-// columns) and of the {e | Phi} columns of W_k, W_v, adds the gradients through the query's Phi(0), and writes
-// the time-encoding partial sums of the keys into region 0 of ws.tg_partial.
+// columns) and of the {e | Phi} columns of W_k, W_v, and writes the time-encoding partial sums of the keys into
+// region 0 of ws.tg_partial and the column sums of dq into ws.q_part (both consumed by time_grad_finish).
 static void attn_backward(tgnn_ctx* ctx, tgnn_params* g, const tgnn_params* p, int R, const int32_t* slot_row,
                           const int32_t* cnt, TnBatch& tn, Side& side, hipStream_t s) {
   const Dims& d = ctx->d; Ws& w = ctx->w;
@@ -238,7 +238,7 @@ static void attn_backward(tgnn_ctx* ctx, tgnn_params* g, const tgnn_params* p, i
   }
   gemm_nt(w.dKV, d.ldkv, w.WceT_phi, d.ldkv, nullptr, w.dPhi, d.ldt, RK, d.dt, d.ldkv, d.ldt, false, s);
   time_grad(w.dPhi, d.ldt, 0, w.dtk, RK, d.dt, p->time_w, p->time_b, w.tg_partial, s);
-  qphi_grad(w.dq, d.ldh, R, d.dO, p->wq, d.dq, d.dx, d.dt, p->time_b, w.q_colsum, w.q_ticket, g->time_b, g->wq, s);
+  qphi_colsum(w.dq, d.ldh, R, d.dO, w.q_part, s);
 }
 
 // After the per-row reduction into ws.dP: gradient reaching the node rows (ws.ds_row, dynamic columns) and
@@ -533,7 +533,11 @@ int32_t tgnn_temporal_attn_bwd(tgnn_ctx* ctx, const tgnn_params* p, int32_t n_ro
   Side side{ctx, s, false};
   const int RK = n_roots * d.k;
   attn_backward(ctx, grads, p, n_roots, nullptr, w.cnt, tn, side, s);
-  time_grad_finish(w.tg_partial, 1, d.dt, grads->time_w, grads->time_b, s);
+  {
+    QPhi qp;
+    qp.part = w.q_part; qp.wq = p->wq; qp.time_b = p->time_b; qp.g_wq = grads->wq; qp.dO = d.dO; qp.dq_w = d.dq; qp.dx = d.dx;
+    time_grad_finish(w.tg_partial, 1, d.dt, grads->time_w, grads->time_b, &qp, s);
+  }
   slots_to_dp(ctx, n_roots, RK, s);
   node_proj_backward(ctx, grads, n_roots + RK, nullptr, tn, s);
   tn.launch(s);
@@ -817,7 +821,11 @@ static int enqueue_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
   gemm_nt(w.dgi, d.ld3, w.WihT_phi, d.ld3, nullptr, w.dphi_g, d.ldt, U, d.dt, d.ld3, d.ldt, false, s, w.ucount);
   time_grad(w.dphi_g, d.ldt, 0, w.delta, U, d.dt, p->time_w, p->time_b, w.tg_partial + (size_t)TG_BLOCKS * 2 * d.dt, s,
             w.ucount);
-  time_grad_finish(w.tg_partial, 2, d.dt, grads->time_w, grads->time_b, s);
+  {
+    QPhi qp;
+    qp.part = w.q_part; qp.wq = p->wq; qp.time_b = p->time_b; qp.g_wq = grads->wq; qp.dO = d.dO; qp.dq_w = d.dq; qp.dx = d.dx;
+    time_grad_finish(w.tg_partial, 2, d.dt, grads->time_w, grads->time_b, &qp, s);
+  }
   tm.end(17);
   side.join();   // all weight gradients
 

@@ -58,7 +58,7 @@ struct Ws {
   BatchSet* bs_dev;                            // device copy of the step's batch descriptors
   struct SgdSet* sgd_dev;                      // device copy of the parameter/gradient pointer table
   float* tg_partial;                           // [2, TG_BLOCKS, 2, dt] partial time-encoding gradient sums
-  float* q_colsum;  unsigned int* q_ticket;    // [d_o], [1] scratch of qphi_grad (zero between calls)
+  float* q_part;                               // [QPHI_BLOCKS, d_o] column sums of dq per block of roots
   // GRU
   float *X, *Hm, *gi, *gh, *gates;             // [S,ldx] [S,ldh] [S,ld3] [S,ld3] [S,4*ldh]
   float* Xrow;                                 // [S,ldxr] x = {s' | static} per distinct node (row)
@@ -305,9 +305,16 @@ void gru_gates_fwd(const Dims& d, int n, const int* n_dev, const float* gi, cons
                    float* zero_buf, int zero_w, hipStream_t s);
 // Gradients through the query's time encoding Phi(0) = cos(time_b), from the column sums of dq [R, ld]:
 // g_b[c] += -sin(time_b[c]) sum_n colsum[n] wq[n, dx + c] and g_wq[n, dx + c] += colsum[n] cos(time_b[c]).
-// colsum [d_o] and ticket [1] are scratch that is zero on entry and left zero.
-void qphi_grad(const float* dq, int ld, int R, int dO, const float* wq, int dq_w, int dx, int dt, const float* time_b,
-               float* colsum, unsigned int* ticket, float* g_b, float* g_wq, hipStream_t s);
+// qphi_colsum writes per-block column sums to q_part [QPHI_BLOCKS, d_o]; time_grad_finish (given a QPhi)
+// turns them into the two gradients.
+constexpr int QPHI_BLOCKS = 64;
+struct QPhi {
+  const float* part = nullptr;   // NULL: no query part
+  const float *wq = nullptr, *time_b = nullptr;
+  float* g_wq = nullptr;
+  int dO = 0, dq_w = 0, dx = 0;
+};
+void qphi_colsum(const float* dq, int ld, int R, int dO, float* q_part, hipStream_t s);
 // ds [n, ldh] = gradient reaching s' per row
 void gru_gates_bwd(const Dims& d, int n, const int* n_dev, const float* ds, const float* gates, const float* Hm,
                    const int32_t* has, float* dgi, float* dgh, hipStream_t s);
@@ -318,7 +325,7 @@ void gru_gates_bwd(const Dims& d, int n, const int* n_dev, const float* ds, cons
 constexpr int TG_BLOCKS = 1024;
 void time_grad(const float* dphi, int ld, int col0, const double* delta, int n, int dt, const float* time_w,
                const float* time_b, float* partial, hipStream_t s, const int* n_dev = nullptr);
-void time_grad_finish(const float* partial, int n_calls, int dt, float* g_w, float* g_b, hipStream_t s);
+void time_grad_finish(const float* partial, int n_calls, int dt, float* g_w, float* g_b, const QPhi* q, hipStream_t s);
 
 // ---- k_attn.hip ---------------------------------------------------------------------
 // q of root r is q[qrow * ldq_ ...] with qrow = slot_row ? slot_row[r] : r.
