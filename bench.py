@@ -22,6 +22,11 @@ sys.path.insert(0, ROOT)
 PEAK_HBM_GBS = 8000.0
 PEAK_MFMA_F32_TFLOPS = 157.3
 
+# HBM bytes per launch (read + written) from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised in
+# profiles/train_step_C1_hbm_traffic.md (counter units scaled by the copy-kernel calibration described there).
+# Counters cannot be read from inside this script, so the figures are the recorded ones, for C1 only.
+MEASURED_TRAFFIC_BYTES = {"C1": {"kv_projection": 41.0e6, "assemble_ce": 27.2e6}}
+
 STAGE_NAMES = ["prologue (pack weights, clear)", "row-sorted slot list (for the backward row sums)", "roots + sample + distinct-node rows",
                "gather + time-encode (GRU input)", "GRU input projection (MFMA)", "GRU hidden projection (MFMA)",
                "GRU gates", "per-slot attention input {e | Phi} (gather)", "K/V projection of the slots (MFMA)",
@@ -207,12 +212,14 @@ def main():
                                                 "neighbour slots (fp32 MFMA 16x16x4), the longest forward kernel",
                      "achieved": kv_tflops, "peak": PEAK_MFMA_F32_TFLOPS, "unit": "TFLOP/s",
                      "frac": kv_tflops / PEAK_MFMA_F32_TFLOPS if kv_tflops else None,
-                     "avg_launch_us": ms_m / n_m * 1e3 if n_m else None, "traffic": None},
+                     "avg_launch_us": ms_m / n_m * 1e3 if n_m else None,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(name, {}).get("kv_projection")},
         "gather": {"bound": "hbm", "kernel": "assemble_ce_kernel: edge-feature row gather + time encoding into the "
                                              "per-slot key/value inputs",
                    "achieved": asm_gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                    "frac": asm_gbs / PEAK_HBM_GBS if asm_gbs else None,
-                   "avg_launch_us": ms_g / n_g * 1e3 if n_g else None},
+                   "avg_launch_us": ms_g / n_g * 1e3 if n_g else None,
+                   "traffic": MEASURED_TRAFFIC_BYTES.get(name, {}).get("assemble_ce")},
         "step_model": {"flops_per_step_per_slot_updt": step_flops(d, ev_step), "bytes_per_step": step_bytes(d, ev_step),
                        "note": "flops counted with UPDT per slot as the method states it; the library evaluates "
                                "UPDT once per distinct node, so executed flops are lower"},
