@@ -41,7 +41,7 @@ void decoder_assemble(const Dims& d, const BatchSet* bs, int total, const float*
 
 // Per row: logit, loss term, d(loss)/d(logit), gradient into the hidden layer; per block: partial sums of
 // the w2 / b2 gradients.  loss = mean over batches of (1 / 2n_b) sum softplus(-+logit).
-constexpr int DL_ROWS = 4;  // rows per block: one per wave
+constexpr int DL_ROWS = 16;  // rows per block (the block ends with one atomic per column and two on scalars)
 __global__ __launch_bounds__(256) void dec_loss_kernel(const BatchSet* __restrict__ bsp, int dO, const float* __restrict__ h1, int ldh,
                                                        const float* __restrict__ w2, const float* __restrict__ b2,
                                                        float* __restrict__ logits, float* __restrict__ out_loss,

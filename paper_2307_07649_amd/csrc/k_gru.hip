@@ -163,26 +163,32 @@ void time_grad(const float* dphi, int ld, int col0, const double* delta, int n, 
 //   g_wq[n, dx + c]  += colsum[n] cos(time_b[c])
 // qphi_colsum: QPHI_BLOCKS blocks each write the column sums of their range of roots to q_part[block, d_o].
 // time_grad_finish adds them up and applies the two formulas (extra grid rows of that kernel).
-__global__ __launch_bounds__(256) void qphi_colsum_kernel(const float* __restrict__ dq, int ld, int R, int dO,
-                                                          float* __restrict__ q_part) {
-  __shared__ float part[4][256];
-  const int cx = threadIdx.x & 63, cy = threadIdx.x >> 6;
+__global__ __launch_bounds__(1024) void qphi_colsum_kernel(const float* __restrict__ dq, int ld, int R, int dO,
+                                                           float* __restrict__ q_part) {
+  __shared__ float part[16][256];
+  const int cx = threadIdx.x & 63, cy = threadIdx.x >> 6;   // 16 row groups x 64 columns
   const int per = (R + gridDim.x - 1) / gridDim.x;
   const int r0 = min(R, (int)blockIdx.x * per), r1 = min(R, r0 + per);
   for (int n0 = 0; n0 < dO; n0 += 64) {   // d_o <= 256
     const int n = n0 + cx;
     float a = 0.f;
-    if (n < dO)
-      for (int r = r0 + cy; r < r1; r += 4) a += dq[(size_t)r * ld + n];
+    if (n < dO) {
+#pragma unroll 4
+      for (int r = r0 + cy; r < r1; r += 16) a += dq[(size_t)r * ld + n];
+    }
     part[cy][n0 + cx] = a;
   }
   __syncthreads();
-  for (int n = threadIdx.x; n < dO; n += blockDim.x)
-    q_part[(size_t)blockIdx.x * dO + n] = part[0][n] + part[1][n] + part[2][n] + part[3][n];
+  for (int n = threadIdx.x; n < dO; n += blockDim.x) {
+    float t = 0.f;
+#pragma unroll
+    for (int g = 0; g < 16; ++g) t += part[g][n];
+    q_part[(size_t)blockIdx.x * dO + n] = t;
+  }
 }
 
 void qphi_colsum(const float* dq, int ld, int R, int dO, float* q_part, hipStream_t s) {
-  hipLaunchKernelGGL(qphi_colsum_kernel, dim3(QPHI_BLOCKS), dim3(256), 0, s, dq, ld, R, dO, q_part);
+  hipLaunchKernelGGL(qphi_colsum_kernel, dim3(QPHI_BLOCKS), dim3(1024), 0, s, dq, ld, R, dO, q_part);
 }
 
 // grid (ceil(2 dt / 32), TGF_SPLIT + q_rows); block = 32 columns x 32 partial groups.  Rows y < TGF_SPLIT add
