@@ -10,6 +10,9 @@ struct AttnShape {
   int R, k, H, dO, dh, ldq, ldkv, ldo;
 };
 
+constexpr int ROWS_IN_FLIGHT = 5;   // neighbour rows whose loads are issued together
+constexpr int MAX_E = 4;            // d_o <= 256: columns lane, lane + 64, lane + 128, lane + 192
+
 // LDS floats per wave
 __host__ __device__ inline int attn_lds_floats(int k, int H, int dO) { return dO + k * (dO + 1) + 2 * H * k; }
 
@@ -37,9 +40,29 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(AttnShape sh, const float
   const float scale = 1.0f / sqrtf((float)c);
   const size_t qrow = slot_row != nullptr ? (size_t)slot_row[r] : (size_t)r;   // q is stored per distinct node
   for (int e = lane; e < sh.dO; e += 64) sq[e] = q[qrow * sh.ldq + e];
-  for (int j = 0; j < c; ++j) {
-    const float* krow = KV + ((size_t)r * sh.k + j) * sh.ldkv;
-    for (int e = lane; e < sh.dO; e += 64) sK[j * (sh.dO + 1) + e] = krow[e];
+  // key rows: the loads of ROWS_IN_FLIGHT rows are issued before any is stored (a wave has few neighbours in
+  // flight on its SIMD, so serialised row loads would each cost a full memory latency)
+  for (int j0 = 0; j0 < c; j0 += ROWS_IN_FLIGHT) {
+    float kreg[ROWS_IN_FLIGHT][MAX_E];
+#pragma unroll
+    for (int jj = 0; jj < ROWS_IN_FLIGHT; ++jj) {
+      const float* krow = KV + ((size_t)r * sh.k + min(j0 + jj, c - 1)) * sh.ldkv;
+#pragma unroll
+      for (int u = 0; u < MAX_E; ++u) {
+        const int e = lane + 64 * u;
+        kreg[jj][u] = e < sh.dO ? krow[e] : 0.f;
+      }
+    }
+#pragma unroll
+    for (int jj = 0; jj < ROWS_IN_FLIGHT; ++jj) {
+      if (j0 + jj < c) {
+#pragma unroll
+        for (int u = 0; u < MAX_E; ++u) {
+          const int e = lane + 64 * u;
+          if (e < sh.dO) sK[(j0 + jj) * (sh.dO + 1) + e] = kreg[jj][u];
+        }
+      }
+    }
   }
   __builtin_amdgcn_wave_barrier();
   __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): LDS writes of this wave are visible to all its lanes
@@ -75,7 +98,15 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(AttnShape sh, const float
   for (int e = lane; e < sh.dO; e += 64) {
     const int h = e / sh.dh;
     float o = 0.f;
-    for (int j = 0; j < c; ++j) o += sa[HK + h * sh.k + j] * KV[((size_t)r * sh.k + j) * sh.ldkv + sh.dO + e];
+    for (int j0 = 0; j0 < c; j0 += ROWS_IN_FLIGHT) {
+      float vreg[ROWS_IN_FLIGHT];
+#pragma unroll
+      for (int jj = 0; jj < ROWS_IN_FLIGHT; ++jj)
+        vreg[jj] = KV[((size_t)r * sh.k + min(j0 + jj, c - 1)) * sh.ldkv + sh.dO + e];
+#pragma unroll
+      for (int jj = 0; jj < ROWS_IN_FLIGHT; ++jj)
+        if (j0 + jj < c) o += sa[HK + h * sh.k + j0 + jj] * vreg[jj];
+    }
     out[e] = o;
   }
 }
@@ -108,9 +139,27 @@ __global__ __launch_bounds__(256) void attn_bwd_kernel(AttnShape sh, const float
   const float scale = 1.0f / sqrtf((float)c);
   const size_t qrow = slot_row != nullptr ? (size_t)slot_row[r] : (size_t)r;
   for (int e = lane; e < sh.dO; e += 64) sdo[e] = dOmat[(size_t)r * sh.ldo + e];
-  for (int j = 0; j < c; ++j) {
-    const float* vrow = KV + ((size_t)r * sh.k + j) * sh.ldkv + sh.dO;
-    for (int e = lane; e < sh.dO; e += 64) sV[j * (sh.dO + 1) + e] = vrow[e];
+  for (int j0 = 0; j0 < c; j0 += ROWS_IN_FLIGHT) {
+    float vreg[ROWS_IN_FLIGHT][MAX_E];
+#pragma unroll
+    for (int jj = 0; jj < ROWS_IN_FLIGHT; ++jj) {
+      const float* vrow = KV + ((size_t)r * sh.k + min(j0 + jj, c - 1)) * sh.ldkv + sh.dO;
+#pragma unroll
+      for (int u = 0; u < MAX_E; ++u) {
+        const int e = lane + 64 * u;
+        vreg[jj][u] = e < sh.dO ? vrow[e] : 0.f;
+      }
+    }
+#pragma unroll
+    for (int jj = 0; jj < ROWS_IN_FLIGHT; ++jj) {
+      if (j0 + jj < c) {
+#pragma unroll
+        for (int u = 0; u < MAX_E; ++u) {
+          const int e = lane + 64 * u;
+          if (e < sh.dO) sV[(j0 + jj) * (sh.dO + 1) + e] = vreg[jj][u];
+        }
+      }
+    }
   }
   for (int p = lane; p < HK; p += 64) sa[p] = prob[(size_t)r * HK + p];
   __builtin_amdgcn_wave_barrier();
@@ -149,12 +198,21 @@ __global__ __launch_bounds__(256) void attn_bwd_kernel(AttnShape sh, const float
     const int h = e / sh.dh;
     const float qe = q[qrow * sh.ldq + e], doe = sdo[e];
     float dqe = 0.f;
-    for (int j = 0; j < c; ++j) {
-      const size_t row = ((size_t)r * sh.k + j) * sh.ldkv;
-      const float da = sa[HK + h * sh.k + j];
-      dqe += da * KV[row + e];
-      dKV[row + e] = da * qe;
-      dKV[row + sh.dO + e] = sa[h * sh.k + j] * doe;
+    for (int j0 = 0; j0 < c; j0 += ROWS_IN_FLIGHT) {
+      float kreg[ROWS_IN_FLIGHT];
+#pragma unroll
+      for (int jj = 0; jj < ROWS_IN_FLIGHT; ++jj) kreg[jj] = KV[((size_t)r * sh.k + min(j0 + jj, c - 1)) * sh.ldkv + e];
+#pragma unroll
+      for (int jj = 0; jj < ROWS_IN_FLIGHT; ++jj) {
+        const int j = j0 + jj;
+        if (j < c) {
+          const size_t row = ((size_t)r * sh.k + j) * sh.ldkv;
+          const float da = sa[HK + h * sh.k + j];
+          dqe += da * kreg[jj];
+          dKV[row + e] = da * qe;
+          dKV[row + sh.dO + e] = sa[h * sh.k + j] * doe;
+        }
+      }
     }
     dq[(size_t)r * sh.ldo + e] = dqe;
   }
