@@ -11,6 +11,7 @@
 #include <stdlib.h>
 
 #include "tgnn_internal.h"
+#include "device_math.h"
 
 namespace tgnn {
 
@@ -32,8 +33,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, (TN <= 5
                                                       const float* __restrict__ B, int ldb,
                                                       const float* __restrict__ bias, float* __restrict__ C, int ldc,
                                                       int M, int N, int Kp, int n_store, int relu,
-                                                      const int* __restrict__ m_dev, int col_tiles, RowAdd add) {
-  constexpr int BM = 64, BN = 16 * TN;
+                                                      const int* __restrict__ m_dev, int col_tiles, RowAdd add,
+                                                      TimeGradOut tg) {
+  constexpr int BM = NT_BM, BN = 16 * TN;
   // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  The column tiles of one row tile
   // read the same rows of A, so they are given consecutive slots of one XCD.
   const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
@@ -141,6 +143,53 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, (TN <= 5
     }
   }
 
+  if (tg.partial != nullptr) {
+    // Time-encoding gradient epilogue: the tile is not stored.  Each lane multiplies its 4 rows x TN columns
+    // by -sin(w_col delta_row + b_col) (the argument formed exactly as in the forward kernels), sums over its
+    // rows, then over the four lane groups (shuffles) and the four waves (LDS).
+    __syncthreads();   // all waves are done reading the last stage: the stage buffer becomes scratch
+    float* red = &As[0][0];   // [2][4 waves][BN]
+    double dl[4];
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      const int row = m0 + wave * 16 + lg * 4 + v;
+      dl[v] = row < M ? tg.delta[row] : 0.0;
+    }
+#pragma unroll
+    for (int b = 0; b < TN; ++b) {
+      const int col = n0 + b * 16 + li;
+      float sw = 0.f, sb = 0.f;
+      if (col < N) {
+        const double wv = (double)tg.w[col], bv = (double)tg.b[col];
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+          if (m0 + wave * 16 + lg * 4 + v < M) {
+            float sn, cs;
+            sincos_reduced(fma(wv, dl[v], bv), sn, cs);
+            const float t = -acc[b][v] * sn;
+            sb += t;
+            sw += t * (float)dl[v];
+          }
+        }
+      }
+      sw += __shfl_xor(sw, 16); sw += __shfl_xor(sw, 32);
+      sb += __shfl_xor(sb, 16); sb += __shfl_xor(sb, 32);
+      if (lg == 0) {
+        red[wave * BN + b * 16 + li] = sw;
+        red[(4 + wave) * BN + b * 16 + li] = sb;
+      }
+    }
+    __syncthreads();
+    for (int c = tid; c < BN; c += 256) {
+      const int col = n0 + c;
+      if (col < N) {
+        float* out = tg.partial + (size_t)row_tile * 2 * N;
+        out[col] = red[c] + red[BN + c] + red[2 * BN + c] + red[3 * BN + c];
+        out[N + col] = red[4 * BN + c] + red[5 * BN + c] + red[6 * BN + c] + red[7 * BN + c];
+      }
+    }
+    return;
+  }
   // rows this lane writes: m0 + wave * 16 + lg * 4 + v; their gather-add source rows (or -1)
   int arow[4];
 #pragma unroll
@@ -172,16 +221,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, (TN <= 5
 
 template <int TN>
 static void launch_nt(const float* A, int lda, const float* B, int ldb, const float* bias, float* C, int ldc, int M,
-                      int N, int Kp, int n_store, bool relu, hipStream_t s, const int* m_dev, const RowAdd& add) {
-  constexpr int BM = 64, BN = 16 * TN;
+                      int N, int Kp, int n_store, bool relu, hipStream_t s, const int* m_dev, const RowAdd& add,
+                      const TimeGradOut& tg) {
+  constexpr int BM = NT_BM, BN = 16 * TN;
   const int col_tiles = (n_store + BN - 1) / BN;
   const int row_tiles8 = ((M + BM - 1) / BM + 7) & ~7;
   hipLaunchKernelGGL((gemm_nt_kernel<TN>), dim3(col_tiles * row_tiles8), dim3(256), 0, s, A, lda, B, ldb, bias, C, ldc, M,
-                     N, Kp, n_store, relu ? 1 : 0, m_dev, col_tiles, add);
+                     N, Kp, n_store, relu ? 1 : 0, m_dev, col_tiles, add, tg);
 }
 
 void gemm_nt(const float* A, int lda, const float* B, int ldb, const float* bias, float* C, int ldc, int M, int N,
-             int Kp, int n_store, bool relu, hipStream_t s, const int* m_dev, const RowAdd& add) {
+             int Kp, int n_store, bool relu, hipStream_t s, const int* m_dev, const RowAdd& add, const TimeGradOut& tg) {
   if (M <= 0 || N <= 0) return;
   if (n_store < N) n_store = N;
   // Column-tile width in 16-wide MFMA blocks, from sweeps on MI355X: problems of a few thousand rows want the
@@ -201,7 +251,7 @@ void gemm_nt(const float* A, int lda, const float* B, int ldb, const float* bias
   }
   if (const char* e = getenv("TGNN_NT_TN")) best = atoi(e);
 #define TGNN_NT_CASE(TNV) \
-  case TNV: launch_nt<TNV>(A, lda, B, ldb, bias, C, ldc, M, N, Kp, n_store, relu, s, m_dev, add); break;
+  case TNV: launch_nt<TNV>(A, lda, B, ldb, bias, C, ldc, M, N, Kp, n_store, relu, s, m_dev, add, tg); break;
   switch (best) {
     TGNN_NT_CASE(10)
     TGNN_NT_CASE(7)

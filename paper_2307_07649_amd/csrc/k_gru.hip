@@ -104,59 +104,6 @@ void gru_gates_bwd(const Dims& d, int n, const int* n_dev, const float* ds, cons
                      dgh);
 }
 
-// Time-encoding gradients of Phi(delta)_c = cos(w_c delta + b_c):
-//   g_b[c] += sum_n dphi[n, col0 + c] * (-sin(w_c delta_n + b_c)),   g_w[c] += the same terms times delta_n.
-// The sine is evaluated again here (the argument is formed exactly as in the forward kernels) rather than
-// stored by the forward pass: a [rows, d_t] matrix written and read back costs more than the arithmetic.
-// Stage 1 (time_grad): a block owns a contiguous range of rows and writes its column sums to a partial
-// buffer [TG_BLOCKS, 2, dt] (no atomics: hundreds of blocks adding to the same 2*dt addresses serialise).
-// Stage 2 (time_grad_finish): adds all partials of the step to the gradient tensors.
-__global__ __launch_bounds__(256) void time_grad_kernel(const float* __restrict__ dphi, int ld, int col0,
-                                                        const double* __restrict__ delta, int n_max,
-                                                        const int* __restrict__ n_dev, int rows_per_block, int dt,
-                                                        const float* __restrict__ time_w,
-                                                        const float* __restrict__ time_b,
-                                                        float* __restrict__ partial) {
-  __shared__ float sw[4][64], sb[4][64];
-  const int n = n_dev ? min(n_max, *n_dev) : n_max;
-  const int cx = threadIdx.x & 63, cy = threadIdx.x >> 6;
-  const int r0 = min(n, (int)blockIdx.x * rows_per_block);
-  const int r1 = min(n, r0 + rows_per_block);
-  float* out = partial + (size_t)blockIdx.x * 2 * dt;
-  for (int c0 = 0; c0 < dt; c0 += 64) {
-    const int c = c0 + cx;
-    float aw = 0.f, ab = 0.f;
-    if (c < dt) {
-      const double w = (double)time_w[c], b = (double)time_b[c];
-#pragma unroll 4
-      for (int r = r0 + cy; r < r1; r += 4) {
-        const double dl = delta[r];
-        float sn, cs;
-        sincos_reduced(fma(w, dl, b), sn, cs);
-        const float t = -dphi[(size_t)r * ld + col0 + c] * sn;
-        ab += t;
-        aw += t * (float)dl;
-      }
-    }
-    sw[cy][cx] = aw;
-    sb[cy][cx] = ab;
-    __syncthreads();
-    if (cy == 0 && c < dt) {
-      out[c] = sw[0][cx] + sw[1][cx] + sw[2][cx] + sw[3][cx];
-      out[dt + c] = sb[0][cx] + sb[1][cx] + sb[2][cx] + sb[3][cx];
-    }
-    __syncthreads();
-  }
-}
-
-void time_grad(const float* dphi, int ld, int col0, const double* delta, int n, int dt, const float* time_w,
-               const float* time_b, float* partial, hipStream_t s, const int* n_dev) {
-  if (n <= 0) return;
-  const int rpb = (((n + TG_BLOCKS - 1) / TG_BLOCKS) + 3) & ~3;
-  hipLaunchKernelGGL(time_grad_kernel, dim3(TG_BLOCKS), dim3(256), 0, s, dphi, ld, col0, delta, n, n_dev, rpb, dt, time_w,
-                     time_b, partial);
-}
-
 // The query's time encoding is Phi(0) = cos(time_b): its gradient, and that of the columns of W_q which
 // multiply it, need only the column sums of dq over the roots:
 //   g_b[c]           += -sin(time_b[c]) * sum_n colsum[n] wq[n, dx + c]
@@ -191,13 +138,16 @@ void qphi_colsum(const float* dq, int ld, int R, int dO, float* q_part, hipStrea
   hipLaunchKernelGGL(qphi_colsum_kernel, dim3(QPHI_BLOCKS), dim3(1024), 0, s, dq, ld, R, dO, q_part);
 }
 
-// grid (ceil(2 dt / 32), TGF_SPLIT + q_rows); block = 32 columns x 32 partial groups.  Rows y < TGF_SPLIT add
-// the time_grad partials; rows y >= TGF_SPLIT (present when q.part != NULL) take 1024 consecutive (n, c) pairs
-// of the query's Phi(0) gradients each.
+// Time-encoding gradients, last stage: the NT GEMMs that produce the gradient reaching Phi write, per 64-row
+// tile, the column sums of its products with -sin(arg) (and with -sin(arg) delta) instead of the matrix itself;
+// this kernel adds the tiles of up to two such launches (keys, mails) to g_w / g_b.
+// grid (ceil(2 dt / 32), TGF_SPLIT + q_rows); block = 32 columns x 32 tile groups.  Rows y < TGF_SPLIT add the
+// tile sums; rows y >= TGF_SPLIT (present when q.part != NULL) take 1024 consecutive (n, c) pairs of the
+// query's Phi(0) gradients each.
 constexpr int TGF_SPLIT = 8;
-__global__ __launch_bounds__(1024) void time_grad_finish_kernel(const float* __restrict__ partial, int n_partials,
-                                                                int dt, float* __restrict__ g_w,
-                                                                float* __restrict__ g_b, QPhi q) {
+__global__ __launch_bounds__(1024) void time_grad_finish_kernel(TgRegion r0, TgRegion r1, int dt,
+                                                                float* __restrict__ g_w, float* __restrict__ g_b,
+                                                                QPhi q) {
   __shared__ float red[32][33];
   if (blockIdx.y >= TGF_SPLIT) {
     if (blockIdx.x != 0) return;
@@ -230,8 +180,15 @@ __global__ __launch_bounds__(1024) void time_grad_finish_kernel(const float* __r
   const int c = blockIdx.x * 32 + cx;
   float acc = 0.f;
   if (c < 2 * dt) {
+#pragma unroll
+    for (int reg = 0; reg < 2; ++reg) {
+      const TgRegion& r = reg == 0 ? r0 : r1;
+      if (r.partial == nullptr) continue;
+      const int rows = r.rows_dev != nullptr ? min(r.rows, *r.rows_dev) : r.rows;
+      const int tiles = (rows + NT_BM - 1) / NT_BM;
 #pragma unroll 4
-    for (int b = blockIdx.y * 32 + cy; b < n_partials; b += 32 * TGF_SPLIT) acc += partial[(size_t)b * 2 * dt + c];
+      for (int b = blockIdx.y * 32 + cy; b < tiles; b += 32 * TGF_SPLIT) acc += r.partial[(size_t)b * 2 * dt + c];
+    }
   }
   red[cy][cx] = acc;
   __syncthreads();
@@ -243,12 +200,13 @@ __global__ __launch_bounds__(1024) void time_grad_finish_kernel(const float* __r
   }
 }
 
-void time_grad_finish(const float* partial, int n_calls, int dt, float* g_w, float* g_b, const QPhi* q, hipStream_t s) {
+void time_grad_finish(const TgRegion& r0, const TgRegion& r1, int dt, float* g_w, float* g_b, const QPhi* q,
+                      hipStream_t s) {
   QPhi qq;
   if (q != nullptr) qq = *q;
   const int q_rows = qq.part != nullptr ? (qq.dO * dt + 1023) / 1024 : 0;
-  hipLaunchKernelGGL(time_grad_finish_kernel, dim3((2 * dt + 31) / 32, TGF_SPLIT + q_rows), dim3(1024), 0, s, partial,
-                     n_calls * TG_BLOCKS, dt, g_w, g_b, qq);
+  hipLaunchKernelGGL(time_grad_finish_kernel, dim3((2 * dt + 31) / 32, TGF_SPLIT + q_rows), dim3(1024), 0, s, r0, r1, dt,
+                     g_w, g_b, qq);
 }
 
 }  // namespace tgnn

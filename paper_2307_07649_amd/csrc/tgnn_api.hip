@@ -97,18 +97,19 @@ static void layout(const Dims& d, Ws& w, Bump& b) {
   w.ds_row = b.take<float>(S * d.ldh);
   w.bs_dev = b.take<BatchSet>(1);
   w.sgd_dev = b.take<SgdSet>(1);
-  w.tg_partial = b.take<float>((size_t)2 * TG_BLOCKS * 2 * d.dt);
+  w.tg_keys = b.take<float>(((RK + NT_BM - 1) / NT_BM) * 2 * (size_t)d.dt);
+  w.tg_mail = b.take<float>(((S + NT_BM - 1) / NT_BM) * 2 * (size_t)d.dt);
   w.q_part = b.take<float>((size_t)QPHI_BLOCKS * d.dO);
   w.X = b.take<float>(S * d.ldx); w.Hm = b.take<float>(S * d.ldh);
   w.gi = b.take<float>(S * d.ld3); w.gh = b.take<float>(S * d.ld3);
   w.gates = b.take<float>(S * 4 * d.ldh); w.Xrow = b.take<float>(S * d.ldxr);
-  w.dgi = b.take<float>(S * d.ld3); w.dgh = b.take<float>(S * d.ld3); w.dphi_g = b.take<float>(S * d.ldt);
+  w.dgi = b.take<float>(S * d.ld3); w.dgh = b.take<float>(S * d.ld3);
   // node rows of a standalone attention call are its slots, so P / dP hold S rows (a step uses far fewer)
   w.P = b.take<float>(S * d.ldp); w.dP = b.take<float>(S * d.ldp);
   w.CE = b.take<float>(RK * d.ldce); w.KV = b.take<float>(RK * d.ldkv);
   w.prob = b.take<float>(R * d.H * d.k); w.Omat = b.take<float>(R * d.ldh); w.z = b.take<float>(R * d.ldh);
   w.dz = b.take<float>(R * d.ldh); w.dOmat = b.take<float>(R * d.ldh); w.dq = b.take<float>(R * d.ldh);
-  w.dKV = b.take<float>(RK * d.ldkv); w.dPhi = b.take<float>(RK * d.ldt);
+  w.dKV = b.take<float>(RK * d.ldkv);
   w.Adec = b.take<float>(B2 * d.ldkv); w.h1 = b.take<float>(B2 * d.ldh); w.dh1 = b.take<float>(B2 * d.ldh);
   w.dAdec = b.take<float>(B2 * d.ldkv); w.logits = b.take<float>(B2); w.dlogit = b.take<float>(B2);
   w.loss_acc = b.take<float>(TGNN_MAX_BATCHES);
@@ -219,7 +220,7 @@ static void attn_forward(tgnn_ctx* ctx, const tgnn_params* p, int R, int n_rows,
 // From ws.dz (already masked by the merge ReLU) down to ws.dP (per-node projection gradients, not yet
 // reduced over slots), ws.dKV and ws.dq; queues the weight-gradient GEMMs of W_o (attention-output
 // columns) and of the {e | Phi} columns of W_k, W_v, and writes the time-encoding partial sums of the keys into
-// region 0 of ws.tg_partial and the column sums of dq into ws.q_part (both consumed by time_grad_finish).
+// ws.tg_keys and the column sums of dq into ws.q_part (both consumed by time_grad_finish).
 static void attn_backward(tgnn_ctx* ctx, tgnn_params* g, const tgnn_params* p, int R, const int32_t* slot_row,
                           const int32_t* cnt, TnBatch& tn, Side& side, hipStream_t s) {
   const Dims& d = ctx->d; Ws& w = ctx->w;
@@ -236,8 +237,12 @@ static void attn_backward(tgnn_ctx* ctx, tgnn_params* g, const tgnn_params* p, i
     tn.add(w.dKV, d.ldkv, w.CE, d.ldce, RK, 2 * d.dO, d.de + d.dt, kv);
     side.flush(tn);
   }
-  gemm_nt(w.dKV, d.ldkv, w.WceT_phi, d.ldkv, nullptr, w.dPhi, d.ldt, RK, d.dt, d.ldkv, d.ldt, false, s);
-  time_grad(w.dPhi, d.ldt, 0, w.dtk, RK, d.dt, p->time_w, p->time_b, w.tg_partial, s);
+  {  // gradient reaching the keys' Phi, reduced to per-tile time-encoding gradient sums inside the GEMM
+    TimeGradOut tg;
+    tg.delta = w.dtk; tg.w = p->time_w; tg.b = p->time_b; tg.partial = w.tg_keys;
+    gemm_nt(w.dKV, d.ldkv, w.WceT_phi, d.ldkv, nullptr, nullptr, d.ldt, RK, d.dt, d.ldkv, d.ldt, false, s, nullptr, RowAdd(),
+            tg);
+  }
   qphi_colsum(w.dq, d.ldh, R, d.dO, w.q_part, s);
 }
 
@@ -536,7 +541,9 @@ int32_t tgnn_temporal_attn_bwd(tgnn_ctx* ctx, const tgnn_params* p, int32_t n_ro
   {
     QPhi qp;
     qp.part = w.q_part; qp.wq = p->wq; qp.time_b = p->time_b; qp.g_wq = grads->wq; qp.dO = d.dO; qp.dq_w = d.dq; qp.dx = d.dx;
-    time_grad_finish(w.tg_partial, 1, d.dt, grads->time_w, grads->time_b, &qp, s);
+    TgRegion keys;
+    keys.partial = w.tg_keys; keys.rows = RK;
+    time_grad_finish(keys, TgRegion(), d.dt, grads->time_w, grads->time_b, &qp, s);
   }
   slots_to_dp(ctx, n_roots, RK, s);
   node_proj_backward(ctx, grads, n_roots + RK, nullptr, tn, s);
@@ -818,13 +825,18 @@ static int enqueue_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
     tm.end(16);
   }
   tm.begin(17);
-  gemm_nt(w.dgi, d.ld3, w.WihT_phi, d.ld3, nullptr, w.dphi_g, d.ldt, U, d.dt, d.ld3, d.ldt, false, s, w.ucount);
-  time_grad(w.dphi_g, d.ldt, 0, w.delta, U, d.dt, p->time_w, p->time_b, w.tg_partial + (size_t)TG_BLOCKS * 2 * d.dt, s,
-            w.ucount);
+  {  // gradient reaching the mails' Phi, reduced the same way
+    TimeGradOut tg;
+    tg.delta = w.delta; tg.w = p->time_w; tg.b = p->time_b; tg.partial = w.tg_mail;
+    gemm_nt(w.dgi, d.ld3, w.WihT_phi, d.ld3, nullptr, nullptr, d.ldt, U, d.dt, d.ld3, d.ldt, false, s, w.ucount, RowAdd(), tg);
+  }
   {
     QPhi qp;
     qp.part = w.q_part; qp.wq = p->wq; qp.time_b = p->time_b; qp.g_wq = grads->wq; qp.dO = d.dO; qp.dq_w = d.dq; qp.dx = d.dx;
-    time_grad_finish(w.tg_partial, 2, d.dt, grads->time_w, grads->time_b, &qp, s);
+    TgRegion keys, mail;
+    keys.partial = w.tg_keys; keys.rows = RK;
+    mail.partial = w.tg_mail; mail.rows = U; mail.rows_dev = w.ucount;
+    time_grad_finish(keys, mail, d.dt, grads->time_w, grads->time_b, &qp, s);
   }
   tm.end(17);
   side.join();   // all weight gradients

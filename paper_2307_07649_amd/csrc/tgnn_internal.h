@@ -57,17 +57,17 @@ struct Ws {
   float* ds_row;                               // [maxS, ldh] gradient reaching s' per row
   BatchSet* bs_dev;                            // device copy of the step's batch descriptors
   struct SgdSet* sgd_dev;                      // device copy of the parameter/gradient pointer table
-  float* tg_partial;                           // [2, TG_BLOCKS, 2, dt] partial time-encoding gradient sums
+  float *tg_keys, *tg_mail;                    // [ceil(RK/64), 2, dt], [ceil(S/64), 2, dt] per-tile time-encoding gradient sums
   float* q_part;                               // [QPHI_BLOCKS, d_o] column sums of dq per block of roots
   // GRU
   float *X, *Hm, *gi, *gh, *gates;             // [S,ldx] [S,ldh] [S,ld3] [S,ld3] [S,4*ldh]
   float* Xrow;                                 // [S,ldxr] x = {s' | static} per distinct node (row)
-  float *dgi, *dgh, *dphi_g;                   // [S,ld3] [S,ld3] [S,ldh(dt)]
+  float *dgi, *dgh;                            // [S,ld3] [S,ld3]
   // attention.  The projections of x are taken once per distinct node (P), the projections of {e | Phi}
   // per neighbour slot (CE); a slot's key/value is the sum of the two.
   float *P, *dP;                               // [S,ldp]
   float *CE, *KV, *prob, *Omat, *z;            // [RK,ldce] [RK,ldkv] [R,H*k] [R,ldh] [R,ldh]
-  float *dz, *dOmat, *dq, *dKV, *dPhi;         // [R,ldh] [R,ldh] [R,ldh] [RK,ldkv] [RK,ldt]
+  float *dz, *dOmat, *dq, *dKV;                // [R,ldh] [R,ldh] [R,ldh] [RK,ldkv]
   // decoder
   float *Adec, *h1, *dh1, *dAdec, *logits, *dlogit;  // [2B,ldkv] [2B,ldh] [2B,ldh] [2B,ldkv] [2B] [2B]
   float* loss_acc;                                   // [TGNN_MAX_BATCHES] per-batch loss sums
@@ -153,9 +153,19 @@ struct RowAdd {
   const int32_t* index = nullptr;
   int ld = 0, row0 = 0;
 };
+// TimeGradOut (optional): C is not written.  Instead C[m, n] is taken as the gradient reaching the time encoding
+// Phi(delta[m])_n = cos(w[n] delta[m] + b[n]) and each 64-row tile writes the column sums of its part of
+//   dL/dw[n] = sum_m C[m, n] (-sin(w[n] delta[m] + b[n])) delta[m],   dL/db[n] = the same without the factor delta[m]
+// to partial[row tile, {w, b}, N]; time_grad_finish adds the tiles up.  Row tiles beyond the rows are not written.
+constexpr int NT_BM = 64;
+struct TimeGradOut {
+  const double* delta = nullptr;
+  const float *w = nullptr, *b = nullptr;
+  float* partial = nullptr;
+};
 void gemm_nt(const float* A, int lda, const float* B, int ldb, const float* bias, float* C, int ldc, int M,
              int N, int Kp, int n_store, bool relu, hipStream_t s, const int* m_dev = nullptr,
-             const RowAdd& add = RowAdd());
+             const RowAdd& add = RowAdd(), const TimeGradOut& tg = TimeGradOut());
 
 // Where the weight-gradient GEMM adds its result: element (n, k) goes to p[n >= n_split][k >= k_split]
 // (indices taken relative to the split) with row pitch ld[..][..]; column sums of D go to bias[n >= n_split].
@@ -318,14 +328,16 @@ void qphi_colsum(const float* dq, int ld, int R, int dO, float* q_part, hipStrea
 // ds [n, ldh] = gradient reaching s' per row
 void gru_gates_bwd(const Dims& d, int n, const int* n_dev, const float* ds, const float* gates, const float* Hm,
                    const int32_t* has, float* dgi, float* dgh, hipStream_t s);
-// Time-encoding gradients in two stages.  time_grad: column sums of dPhi [n, ld] (dt columns from col0) times
-// -sin(time_w[c] delta[n] + time_b[c]) (and times delta[n] for time_w) per block of rows, written to
-// partial[TG_BLOCKS, 2, dt] (always all TG_BLOCKS entries).  time_grad_finish: adds the partials of n_calls
-// consecutive regions to g_w / g_b.
-constexpr int TG_BLOCKS = 1024;
-void time_grad(const float* dphi, int ld, int col0, const double* delta, int n, int dt, const float* time_w,
-               const float* time_b, float* partial, hipStream_t s, const int* n_dev = nullptr);
-void time_grad_finish(const float* partial, int n_calls, int dt, float* g_w, float* g_b, const QPhi* q, hipStream_t s);
+// Adds the per-tile partial sums written by gemm_nt (TimeGradOut) to g_w / g_b: up to two regions of
+// [tiles, 2, dt]; a region's tile count is ceil(min(rows, *rows_dev) / NT_BM) (rows_dev may be NULL).  With a QPhi
+// it also finishes the gradients through the query's Phi(0).
+struct TgRegion {
+  const float* partial = nullptr;
+  int rows = 0;
+  const int* rows_dev = nullptr;
+};
+void time_grad_finish(const TgRegion& r0, const TgRegion& r1, int dt, float* g_w, float* g_b, const QPhi* q,
+                      hipStream_t s);
 
 // ---- k_attn.hip ---------------------------------------------------------------------
 // q of root r is q[qrow * ldq_ ...] with qrow = slot_row ? slot_row[r] : r.
