@@ -11,26 +11,23 @@ namespace tgnn {
 
 // Adds 1 to counter[key] for every lane with key >= 0 and returns the value before this lane's increment.
 // Lanes of a wavefront that share a key are merged into one atomic (power-law graphs put thousands of
-// slots on one node, and atomics on one address serialise).  The grouping loop uses only cross-lane ALU
-// operations; the atomics of all group leaders are then issued together, so the wave pays one round trip.
+// slots on one node, and atomics on one address serialise).  Every lane of the wavefront must call it.
+// The set of lanes that share lane j's key is the ballot of (key == key of lane j); 64 such ballots, each
+// written into lane j's registers, give every lane its set without a data-dependent loop.  The atomics of all
+// group leaders are then issued together, so the wave pays one round trip.
 __device__ __forceinline__ int wave_counted_add(int32_t* counter, int key, bool want_result) {
   const int lane = threadIdx.x & 63;
-  bool pending = key >= 0;
-  int leader = lane, count = 0, rank = 0;
-  while (true) {
-    const unsigned long long todo = __ballot(pending);
-    if (todo == 0ull) break;
-    const int first = __ffsll((long long)todo) - 1;
-    const int k = __shfl(key, first);
-    const bool mine = pending && key == k;
-    const unsigned long long same = __ballot(mine);
-    if (mine) {
-      leader = first;
-      count = __popcll(same);
-      rank = __popcll(same & ((1ull << lane) - 1ull));
-      pending = false;
-    }
+  unsigned lo = 0u, hi = 0u;
+#pragma unroll
+  for (int j = 0; j < 64; ++j) {
+    const int kj = __builtin_amdgcn_readlane(key, j);
+    const unsigned long long m = __ballot(key == kj);
+    lo = lane == j ? (unsigned)m : lo;
+    hi = lane == j ? (unsigned)(m >> 32) : hi;
   }
+  const int count = __popc(lo) + __popc(hi);
+  const int rank = __builtin_amdgcn_mbcnt_hi(hi, __builtin_amdgcn_mbcnt_lo(lo, 0u));   // set members below this lane
+  const int leader = lo != 0u ? __ffs((int)lo) - 1 : 32 + __ffs((int)hi) - 1;
   int base = 0;
   if (key >= 0 && leader == lane) {
     if (want_result) base = atomicAdd(counter + key, count);
