@@ -1,7 +1,11 @@
 // Link-prediction decoder and binary cross-entropy (self-supervision by temporal edges with one sampled
 // negative destination per event, Sec. 2.1 / 3.2.2).  logit(a, b) = w2 . ReLU(W_s z_a + W_d z_b + b1) + b2.
+// The hidden layer is linear in {z_a | z_b} before its ReLU, so the two products are taken once per root
+// (one MFMA GEMM, Pdec = z {W_s ; W_d}^T) and a pair only adds two rows: the source's W_s z is shared by its
+// true and its negative pair.  Backward, the pair kernel leaves per root the gradient of its row of Pdec; the
+// GEMM that maps it back to z applies the ReLU gate of the merge layer in its epilogue.
 // Row layout of the 2n pairs of batch b (events before it: off): rows 2*off + i are the true pairs
-// (src_i, dst_i), rows 2*off + n + i the pairs (src_i, neg_i).  The hidden layer is an MFMA GEMM.
+// (src_i, dst_i), rows 2*off + n + i the pairs (src_i, neg_i); roots 3*off + {0, n, 2n} + i are src, dst, neg.
 #include "tgnn_internal.h"
 #include "device_math.h"
 
@@ -13,76 +17,91 @@ __device__ __forceinline__ int batch_of_row(const BatchSet& bs, int row, int mul
   return b;
 }
 
-template <int VEC>
-__global__ __launch_bounds__(256) void dec_assemble_kernel(const BatchSet* __restrict__ bsp, int dO, const float* __restrict__ z, int ldz,
-                                                           float* __restrict__ Adec, int lda) {
-  const BatchSet& bs = *bsp;
-  const int lane = threadIdx.x & 63;
-  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (row >= 2 * bs.total) return;
-  const int b = batch_of_row(bs, row, 2);
-  const int off = bs.b[b].ev_off, n = bs.b[b].n;
-  const int local = row - 2 * off;
-  const bool neg = local >= n;
-  const int i = neg ? local - n : local;
-  const int ra = 3 * off + i, rb = 3 * off + (neg ? 2 * n : n) + i;
-  float* out = Adec + (size_t)row * lda;
-  wave_copy<VEC>(out, z + (size_t)ra * ldz, dO, 0, lane);
-  wave_copy<VEC>(out + dO, z + (size_t)rb * ldz, dO, lda - 2 * dO, lane);
-}
-
-void decoder_assemble(const Dims& d, const BatchSet* bs, int total, const float* z, int ldz, float* Adec, int lda,
-                      hipStream_t s) {
-  if (total <= 0) return;
-  const int blocks = (2 * total + 3) / 4;
-  if (d.dO % 4 == 0) hipLaunchKernelGGL(dec_assemble_kernel<4>, dim3(blocks), dim3(256), 0, s, bs, d.dO, z, ldz, Adec, lda);
-  else hipLaunchKernelGGL(dec_assemble_kernel<1>, dim3(blocks), dim3(256), 0, s, bs, d.dO, z, ldz, Adec, lda);
-}
-
-// Per row: logit, loss term, d(loss)/d(logit), gradient into the hidden layer; per block: partial sums of
-// the w2 / b2 gradients.  loss = mean over batches of (1 / 2n_b) sum softplus(-+logit).
-constexpr int DL_ROWS = 16;  // rows per block (the block ends with one atomic per column and two on scalars)
-__global__ __launch_bounds__(256) void dec_loss_kernel(const BatchSet* __restrict__ bsp, int dO, const float* __restrict__ h1, int ldh,
-                                                       const float* __restrict__ w2, const float* __restrict__ b2,
-                                                       float* __restrict__ logits, float* __restrict__ out_loss,
-                                                       float* __restrict__ dh1, float* __restrict__ g_w2,
+// One wavefront per event (both of its pairs), at most DP_BLOCKS blocks of four wavefronts which stride over
+// the events (every block ends with one atomic per column of w2: more blocks would queue up there).  Per pair: hidden layer, logit,
+// loss term, d(loss)/d(logit); per root: gradient of its Pdec row ({W_s part | W_d part}: a source receives
+// the sum of its two pairs in the first half, a destination its pair in the second half, the other halves
+// are zero); per block: partial sums of the w2 / b2 gradients and of the loss.
+// loss = mean over batches of (1 / 2n_b) sum softplus(-+logit).
+constexpr int DP_BLOCKS = 256;
+__global__ __launch_bounds__(256) void dec_pair_kernel(const BatchSet* __restrict__ bsp, int dO,
+                                                       const float* __restrict__ Pdec, int ldp,
+                                                       const float* __restrict__ b1, const float* __restrict__ w2,
+                                                       const float* __restrict__ b2, float* __restrict__ logits,
+                                                       float* __restrict__ out_loss, float* __restrict__ h1, int ldh,
+                                                       float* __restrict__ dPdec, float* __restrict__ g_w2,
                                                        float* __restrict__ g_b2) {
   __shared__ float red[4][260];
   const BatchSet& bs = *bsp;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int rows = 2 * bs.total;
   float gw[4] = {0.f, 0.f, 0.f, 0.f};  // columns lane, lane+64, lane+128, lane+192
   float gb = 0.f, lsum = 0.f;
-  for (int u = 0; u < DL_ROWS / 4; ++u) {
-    const int row = blockIdx.x * DL_ROWS + u * 4 + wave;
-    if (row >= rows) break;
-    const int b = batch_of_row(bs, row, 2);
-    const int n = bs.b[b].n;
-    const bool pos = (row - 2 * bs.b[b].ev_off) < n;
-    const float* hr = h1 + (size_t)row * ldh;
-    float acc = 0.f;
-    for (int c = lane; c < dO; c += 64) acc += hr[c] * w2[c];
-    for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o);
-    const float l = acc + b2[0];
-    const float x = pos ? -l : l;                        // loss term softplus(x)
-    const float sp = fmaxf(x, 0.f) + log1pf(expf(-fabsf(x)));
-    const float sig = 1.0f / (1.0f + expf(-l));
-    const float inv = 1.0f / (2.0f * (float)n);
-    const float dl = (sig - (pos ? 1.0f : 0.0f)) * inv;  // d(sum_b loss_b) / d logit
-    if (lane == 0) {
-      logits[row] = l;
-      lsum += sp * inv / (float)bs.nb;
-      gb += dl;
+  float bb[4], ww[4];
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const int c = lane + 64 * q;
+    bb[q] = c < dO ? b1[c] : 0.f;
+    ww[q] = c < dO ? w2[c] : 0.f;
+  }
+  const float b2v = b2[0];
+  for (int ev = blockIdx.x * 4 + wave; ev < bs.total; ev += gridDim.x * 4) {
+    const int b = batch_of_row(bs, ev, 1);
+    const int off = bs.b[b].ev_off, n = bs.b[b].n;
+    const int i = ev - off;
+    const size_t ra = (size_t)(3 * off + i) * ldp, rb = ra + (size_t)n * ldp, rc = rb + (size_t)n * ldp;
+    float hp[4], hn[4];
+    float ap = 0.f, an = 0.f;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int c = lane + 64 * q;
+      hp[q] = hn[q] = 0.f;
+      if (c < dO) {
+        const float ps = Pdec[ra + c] + bb[q];
+        hp[q] = fmaxf(ps + Pdec[rb + dO + c], 0.f);
+        hn[q] = fmaxf(ps + Pdec[rc + dO + c], 0.f);
+      }
+      ap += hp[q] * ww[q];
+      an += hn[q] * ww[q];
     }
-    int q = 0;
-    for (int c = lane; c < dO; c += 64, ++q) {
-      const float h = hr[c];
-      dh1[(size_t)row * ldh + c] = h > 0.f ? dl * w2[c] : 0.f;
-      gw[q] += dl * h;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+      ap += __shfl_xor(ap, o);
+      an += __shfl_xor(an, o);
+    }
+    const float lp = ap + b2v, ln = an + b2v;
+    const float inv = 1.0f / (2.0f * (float)n);
+    // loss terms softplus(-lp) and softplus(ln)
+    const float spp = fmaxf(-lp, 0.f) + log1pf(expf(-fabsf(lp)));
+    const float spn = fmaxf(ln, 0.f) + log1pf(expf(-fabsf(ln)));
+    const float dlp = (1.0f / (1.0f + expf(-lp)) - 1.0f) * inv;   // d(sum_b loss_b) / d logit
+    const float dln = (1.0f / (1.0f + expf(-ln))) * inv;
+    const int row_p = 2 * off + i, row_n = row_p + n;
+    if (lane == 0) {
+      logits[row_p] = lp;
+      logits[row_n] = ln;
+      lsum += (spp + spn) * inv / (float)bs.nb;
+      gb += dlp + dln;
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int c = lane + 64 * q;
+      if (c < dO) {
+        const float dhp = hp[q] > 0.f ? dlp * ww[q] : 0.f;
+        const float dhn = hn[q] > 0.f ? dln * ww[q] : 0.f;
+        h1[(size_t)row_p * ldh + c] = hp[q];
+        h1[(size_t)row_n * ldh + c] = hn[q];
+        dPdec[ra + c] = dhp + dhn;
+        dPdec[ra + dO + c] = 0.f;
+        dPdec[rb + c] = 0.f;
+        dPdec[rb + dO + c] = dhp;
+        dPdec[rc + c] = 0.f;
+        dPdec[rc + dO + c] = dhn;
+        gw[q] += dlp * hp[q] + dln * hn[q];
+      }
     }
   }
-  int q = 0;
-  for (int c = lane; c < dO; c += 64, ++q) red[wave][c] = gw[q];
+#pragma unroll
+  for (int q = 0; q < 4; ++q) red[wave][lane + 64 * q] = gw[q];
   if (lane == 0) { red[wave][256] = gb; red[wave][257] = lsum; }
   __syncthreads();
   if (wave == 0) {
@@ -94,39 +113,12 @@ __global__ __launch_bounds__(256) void dec_loss_kernel(const BatchSet* __restric
   }
 }
 
-void decoder_loss(const Dims& d, const BatchSet* bs, int total, const float* h1, int ldh, const float* w2, const float* b2,
-                  float* logits, float* out_loss, float* dh1, float* g_w2, float* g_b2, hipStream_t s) {
+void decoder_pairs(const Dims& d, const BatchSet* bs, int total, const float* Pdec, int ldp, const float* b1,
+                   const float* w2, const float* b2, float* logits, float* out_loss, float* h1, float* dPdec,
+                   float* g_w2, float* g_b2, hipStream_t s) {
   if (total <= 0) return;
-  hipLaunchKernelGGL(dec_loss_kernel, dim3((2 * total + DL_ROWS - 1) / DL_ROWS), dim3(256), 0, s, bs, d.dO, h1, ldh,
-                     w2, b2, logits, out_loss, dh1, g_w2, g_b2);
-}
-
-// dz (already multiplied by the ReLU mask of the merge layer) per root from the decoder-input gradient.
-__global__ void dec_dz_kernel(const BatchSet* __restrict__ bsp, int dO, const float* __restrict__ dA, int lda, const float* __restrict__ z,
-                              int ldz, float* __restrict__ dz) {
-  const BatchSet& bs = *bsp;
-  const long long total = 3LL * bs.total * dO;
-  for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < total;
-       i += (long long)gridDim.x * blockDim.x) {
-    const int root = (int)(i / dO), c = (int)(i - (long long)root * dO);
-    const int b = batch_of_row(bs, root, 3);
-    const int off = bs.b[b].ev_off, n = bs.b[b].n;
-    const int local = root - 3 * off;
-    const int role = local / n, ev = local - role * n;
-    const size_t prow = (size_t)(2 * off + ev) * lda, nrow = (size_t)(2 * off + n + ev) * lda;
-    float g;
-    if (role == 0) g = dA[prow + c] + dA[nrow + c];
-    else if (role == 1) g = dA[prow + dO + c];
-    else g = dA[nrow + dO + c];
-    dz[(size_t)root * ldz + c] = z[(size_t)root * ldz + c] > 0.f ? g : 0.f;
-  }
-}
-
-void decoder_dz(const Dims& d, const BatchSet* bs, int total_ev, const float* dAdec, int lda, const float* z, int ldz,
-                float* dz, hipStream_t s) {
-  if (total_ev <= 0) return;
-  const long long total = 3LL * total_ev * d.dO;
-  hipLaunchKernelGGL(dec_dz_kernel, dim3((int)((total + 255) / 256)), dim3(256), 0, s, bs, d.dO, dAdec, lda, z, ldz, dz);
+  hipLaunchKernelGGL(dec_pair_kernel, dim3(std::min((total + 3) / 4, DP_BLOCKS)), dim3(256), 0, s, bs, d.dO, Pdec, ldp, b1,
+                     w2, b2, logits, out_loss, h1, d.ldh, dPdec, g_w2, g_b2);
 }
 
 __global__ void mask_dz_kernel(int R, int dO, const float* __restrict__ dz_in, int p_in, const float* __restrict__ z,

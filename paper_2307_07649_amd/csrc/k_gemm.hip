@@ -212,6 +212,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, (TN <= 5
           x = acc[b][v] + bv;
           if (arow[v] >= 0) x += add.src[(size_t)arow[v] * add.ld + col];
           if (relu) x = fmaxf(x, 0.f);
+          if (add.gate != nullptr && !(add.gate[(size_t)row * add.ld_gate + col] > 0.f)) x = 0.f;
         }
         C[(size_t)row * ldc + col] = x;
       }
@@ -307,7 +308,7 @@ __device__ __forceinline__ void tn_tile(const float* __restrict__ D, const float
                                         int K, float* p00, float* p01, float* p10, float* p11, int ld00, int ld01, int ld10,
                                         int ld11, int n_split, int k_split, float* bias0, float* bias1, int M, int m_lo,
                                         int m_hi, int n0, int k0, float* lds) {
-  const bool with_bias = bias0 != nullptr;   // column K of A reads as ones
+  const bool with_bias = bias0 != nullptr || bias1 != nullptr;   // column K of A reads as ones
   float* Ds = lds;                          // [2][TN_ROWS * TN_P]
   float* As = lds + 2 * TN_ROWS * TN_P;     // [2][TN_ROWS * TN_P]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -458,7 +459,8 @@ __device__ __forceinline__ void tn_tile(const float* __restrict__ D, const float
     const bool ns = n >= n_split;
     const int nn = n - (ns ? n_split : 0);
     if (k == K) {
-      if (with_bias) atomicAdd((ns ? bias1 : bias0) + nn, x);
+      float* const bias = ns ? bias1 : bias0;
+      if (bias != nullptr) atomicAdd(bias + nn, x);
     } else {
       const bool ks = k >= k_split;
       float* base = ns ? (ks ? p11 : p10) : (ks ? p01 : p00);
@@ -483,6 +485,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4))) voi
   int M = q.M, m_chunk = q.m_chunk;
   const int* m_dev = q.m_dev;
   float* const bias0 = q.out.bias[0];
+  const bool with_bias = bias0 != nullptr || q.out.bias[1] != nullptr;
   // All output tiles of one m-chunk read the same rows of D and A: keep them on one XCD (one L2).
   const int local = (int)blockIdx.x - wg_begin;
   const int xcd = local & 7, slot = local >> 3;
@@ -498,7 +501,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4))) voi
   const int m_hi = min(M, m_lo + m_chunk);
   int n0, wn, k0, wk;
   tn_piece(N, tile / k_tiles, n0, wn);
-  tn_piece(K + (bias0 != nullptr ? 1 : 0), tile % k_tiles, k0, wk);
+  tn_piece(K + (with_bias ? 1 : 0), tile % k_tiles, k0, wk);
 #define TGNN_TN_CASE(WN, WK)                                                                                          \
   if (wn == WN && wk == WK) {                                                                                         \
     tn_tile<WN / 16, WK / 16>(q.D, q.A, q.ldd, q.lda, N, K, q.out.p[0][0], q.out.p[0][1], q.out.p[1][0], q.out.p[1][1], \
@@ -521,7 +524,7 @@ void TnBatch::add(const float* D, int ldd, const float* A, int lda, int M, int N
     return;
   TnProblem& p = g.p[g.n];
   p.D = D; p.ldd = ldd; p.A = A; p.lda = lda; p.M = M; p.N = N; p.K = K;
-  p.k_tiles = tn_pieces(K + (out.bias[0] != nullptr ? 1 : 0));
+  p.k_tiles = tn_pieces(K + (out.bias[0] != nullptr || out.bias[1] != nullptr ? 1 : 0));
   p.tiles = tn_pieces(N) * p.k_tiles;
   p.m_dev = m_dev; p.out = out;
   g.n++;

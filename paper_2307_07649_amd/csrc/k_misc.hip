@@ -86,12 +86,12 @@ void prologue_fill(tgnn_ctx* ctx, const tgnn_params* p, const BatchSet* bs, cons
     // merge layer, attention-output columns, and their transpose
     add(p->wo, w.Wo_o, dO, dO, d.ldh, d.ldh, dmrg, 1);
     add(p->wo, w.WoT_o, dO, dO, d.ldh, d.ldh, 1, dmrg);
-    // decoder input is {z_a | z_b}: weights side by side
-    add(p->dec_ws, w.Wdec_p, dO, dO, dO, d.ldkv, dO, 1);
-    add(p->dec_wd, w.Wdec_p + dO, dO, dO, d.ldkv - dO, d.ldkv, dO, 1);
-    // transposes: XT[c, n] = X[n, c]
-    add(p->dec_ws, w.WdecT, dO, dO, d.ldh, d.ldh, 1, dO);
-    add(p->dec_wd, w.WdecT + (size_t)dO * d.ldh, dO, dO, d.ldh, d.ldh, 1, dO);
+    // decoder hidden layer per root: rows {W_s ; W_d}; and for the way back, side by side and transposed:
+    // WdecT[c, j] = W_s[j, c], WdecT[c, d_o + j] = W_d[j, c]
+    add(p->dec_ws, w.Wdec_p, dO, dO, d.ldh, d.ldh, dO, 1);
+    add(p->dec_wd, w.Wdec_p + (size_t)dO * d.ldh, dO, dO, d.ldh, d.ldh, dO, 1);
+    add(p->dec_ws, w.WdecT, dO, dO, dO, d.ldkv, 1, dO);
+    add(p->dec_wd, w.WdecT + dO, dO, dO, d.ldkv - dO, d.ldkv, 1, dO);
     add(p->gru_wih + 2 * dm, w.WihT_phi, d.dt, 3 * dm, d.ld3, d.ld3, 1, d.d_in);
     // biases of the per-node projections: {b_k | b_v || b_q + W_q Phi(0) | b_o}
     add(p->bk, w.bias_x, 1, dO, dO, d.ldp, 0, 1);

@@ -51,46 +51,63 @@ __global__ void uniq_map_kernel(int S, const int32_t* __restrict__ slot_gid, con
   wave_counted_add(ucnt, row, false);
 }
 
-// exclusive scan of ucnt[0 .. U) into rowptr[0 .. U] and cursor[0 .. U); one block.  Each thread owns a
-// contiguous range; its loads are issued eight at a time so that their latencies overlap.
+// exclusive scan of ucnt[0 .. U) into rowptr[0 .. U] and cursor[0 .. U); one block of 16 wavefronts.  Each
+// wavefront owns a contiguous range (a multiple of 256 elements) and walks it 256 elements at a time: a lane
+// reads four consecutive counts, the wavefront scans the lane sums with shuffles.  The arrays must be
+// 16-byte aligned.
+__device__ __forceinline__ int4 scan_load4(const int32_t* __restrict__ p, int i, int hi) {
+  if (i + 3 < hi) return *reinterpret_cast<const int4*>(p + i);
+  int4 v = make_int4(0, 0, 0, 0);
+  if (i < hi) v.x = p[i];
+  if (i + 1 < hi) v.y = p[i + 1];
+  if (i + 2 < hi) v.z = p[i + 2];
+  return v;
+}
+__device__ __forceinline__ void scan_store4(int32_t* __restrict__ p, int i, int hi, const int4& v) {
+  if (i + 3 < hi) {
+    *reinterpret_cast<int4*>(p + i) = v;
+    return;
+  }
+  if (i < hi) p[i] = v.x;
+  if (i + 1 < hi) p[i + 1] = v.y;
+  if (i + 2 < hi) p[i + 2] = v.z;
+}
 __global__ __launch_bounds__(1024) void uniq_scan_kernel(const int32_t* __restrict__ ucount,
                                                          const int32_t* __restrict__ ucnt,
                                                          int32_t* __restrict__ rowptr, int32_t* __restrict__ cursor) {
-  __shared__ int part[1024];
+  __shared__ int wsum[16];
   const int U = *ucount;
-  const int per = (U + 1023) / 1024;
-  const int lo = min(U, (int)threadIdx.x * per), hi = min(U, lo + per);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int per = ((U + 16 * 256 - 1) / (16 * 256)) * 256;
+  const int lo = min(U, wave * per), hi = min(U, lo + per);
   int sum = 0;
-  for (int i = lo; i < hi; i += 8) {
-    int v[8];
-#pragma unroll
-    for (int j = 0; j < 8; ++j) v[j] = i + j < hi ? ucnt[i + j] : 0;
-#pragma unroll
-    for (int j = 0; j < 8; ++j) sum += v[j];
+  for (int i = lo + lane * 4; i < hi; i += 256) {
+    const int4 v = scan_load4(ucnt, i, hi);
+    sum += v.x + v.y + v.z + v.w;
   }
-  part[threadIdx.x] = sum;
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) sum += __shfl_xor(sum, off);
+  if (lane == 0) wsum[wave] = sum;
   __syncthreads();
-  for (int off = 1; off < 1024; off <<= 1) {
-    int v = threadIdx.x >= off ? part[threadIdx.x - off] : 0;
-    __syncthreads();
-    part[threadIdx.x] += v;
-    __syncthreads();
-  }
-  int run = part[threadIdx.x] - sum;
-  for (int i = lo; i < hi; i += 8) {
-    int v[8];
+  int run = 0;
+  for (int w = 0; w < wave; ++w) run += wsum[w];
+  for (int i0 = lo; i0 < hi; i0 += 256) {
+    const int i = i0 + lane * 4;
+    const int4 v = scan_load4(ucnt, i, hi);
+    const int t = v.x + v.y + v.z + v.w;
+    int inc = t;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) v[j] = i + j < hi ? ucnt[i + j] : 0;
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      if (i + j < hi) {
-        rowptr[i + j] = run;
-        cursor[i + j] = run;
-      }
-      run += v[j];
+    for (int off = 1; off < 64; off <<= 1) {
+      const int o = __shfl_up(inc, off);
+      if (lane >= off) inc += o;
     }
+    const int e = run + inc - t;
+    const int4 out = make_int4(e, e + v.x, e + v.x + v.y, e + v.x + v.y + v.z);
+    scan_store4(rowptr, i, hi, out);
+    scan_store4(cursor, i, hi, out);
+    run += __shfl(inc, 63);
   }
-  if (threadIdx.x == 1023) rowptr[U] = part[1023];
+  if (threadIdx.x == 1023) rowptr[U] = run;   // the last wavefront ends at U (or owns nothing): run is the total
 }
 
 __global__ void uniq_fill_kernel(int S, const int32_t* __restrict__ slot_row, int32_t* __restrict__ cursor,

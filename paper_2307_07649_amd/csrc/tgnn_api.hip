@@ -110,14 +110,14 @@ static void layout(const Dims& d, Ws& w, Bump& b) {
   w.prob = b.take<float>(R * d.H * d.k); w.Omat = b.take<float>(R * d.ldh); w.z = b.take<float>(R * d.ldh);
   w.dz = b.take<float>(R * d.ldh); w.dOmat = b.take<float>(R * d.ldh); w.dq = b.take<float>(R * d.ldh);
   w.dKV = b.take<float>(RK * d.ldkv);
-  w.Adec = b.take<float>(B2 * d.ldkv); w.h1 = b.take<float>(B2 * d.ldh); w.dh1 = b.take<float>(B2 * d.ldh);
-  w.dAdec = b.take<float>(B2 * d.ldkv); w.logits = b.take<float>(B2); w.dlogit = b.take<float>(B2);
+  w.Pdec = b.take<float>(R * d.ldkv); w.dPdec = b.take<float>(R * d.ldkv);
+  w.h1 = b.take<float>(B2 * d.ldh); w.logits = b.take<float>(B2);
   w.loss_acc = b.take<float>(TGNN_MAX_BATCHES);
   w.Wih_p = b.take<float>((size_t)3 * d.dm * d.ldx); w.Whh_p = b.take<float>((size_t)3 * d.dm * d.ldh);
-  w.Wdec_p = b.take<float>((size_t)d.dO * d.ldkv);
+  w.Wdec_p = b.take<float>((size_t)2 * d.dO * d.ldh);
   w.Wx = b.take<float>((size_t)d.ldp * d.ldxr); w.bias_x = b.take<float>((size_t)d.ldp);
   w.Wce = b.take<float>((size_t)2 * d.dO * d.ldce); w.Wo_o = b.take<float>((size_t)d.dO * d.ldh);
-  w.WdecT = b.take<float>((size_t)2 * d.dO * d.ldh); w.WihT_phi = b.take<float>((size_t)d.dt * d.ld3);
+  w.WdecT = b.take<float>((size_t)d.dO * d.ldkv); w.WihT_phi = b.take<float>((size_t)d.dt * d.ld3);
   w.WxT = b.take<float>((size_t)d.dm * d.ldp); w.WceT_phi = b.take<float>((size_t)d.dt * d.ldkv);
   w.WoT_o = b.take<float>((size_t)d.dO * d.ldh);
   b.take<char>(256);
@@ -789,9 +789,9 @@ static int enqueue_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
 
   // decoder + loss (also produces d loss / d hidden)
   tm.begin(12);
-  decoder_assemble(d, w.bs_dev, bs.total, w.z, d.ldh, w.Adec, d.ldkv, s);
-  gemm_nt(w.Adec, d.ldkv, w.Wdec_p, d.ldkv, p->dec_b1, w.h1, d.ldh, B2, d.dO, d.ldkv, d.ldh, true, s);
-  decoder_loss(d, w.bs_dev, bs.total, w.h1, d.ldh, p->dec_w2, p->dec_b2, w.logits, out_loss, w.dh1, grads->dec_w2, grads->dec_b2, s);
+  gemm_nt(w.z, d.ldh, w.Wdec_p, d.ldh, nullptr, w.Pdec, d.ldkv, R, 2 * d.dO, d.ldh, 2 * d.dO, false, s);
+  decoder_pairs(d, w.bs_dev, bs.total, w.Pdec, d.ldkv, p->dec_b1, p->dec_w2, p->dec_b2, w.logits, out_loss, w.h1, w.dPdec,
+                grads->dec_w2, grads->dec_b2, s);
   tm.end(12);
 
   // Backward.  The data-gradient chain stays on the caller's stream; each weight-gradient GEMM is started on
@@ -799,13 +799,16 @@ static int enqueue_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
   tm.begin(13);
   OutMap dec;
   memset(&dec, 0, sizeof(dec));
-  dec.p[0][0] = grads->dec_ws; dec.p[0][1] = grads->dec_wd; dec.ld[0][0] = dec.ld[0][1] = d.dO;
-  dec.n_split = 1 << 30; dec.k_split = d.dO; dec.bias[0] = grads->dec_b1;
+  dec.p[0][0] = grads->dec_ws; dec.p[1][0] = grads->dec_wd; dec.ld[0][0] = dec.ld[1][0] = d.dO;
+  dec.n_split = d.dO; dec.k_split = 1 << 30; dec.bias[1] = grads->dec_b1;   // every pair is in one W_d half
   TnBatch tn;
-  tn.add(w.dh1, d.ldh, w.Adec, d.ldkv, B2, d.dO, 2 * d.dO, dec);
+  tn.add(w.dPdec, d.ldkv, w.z, d.ldh, R, 2 * d.dO, d.dO, dec);
   side.flush(tn);
-  gemm_nt(w.dh1, d.ldh, w.WdecT, d.ldh, nullptr, w.dAdec, d.ldkv, B2, 2 * d.dO, d.ldh, d.ldkv, false, s);
-  decoder_dz(d, w.bs_dev, bs.total, w.dAdec, d.ldkv, w.z, d.ldh, w.dz, s);
+  {  // dz, gated by the ReLU of the merge layer
+    RowAdd gate;
+    gate.gate = w.z; gate.ld_gate = d.ldh;
+    gemm_nt(w.dPdec, d.ldkv, w.WdecT, d.ldkv, nullptr, w.dz, d.ldh, R, d.dO, d.ldkv, d.ldh, false, s, nullptr, gate);
+  }
   tm.end(13);
   tm.begin(14);
   attn_backward(ctx, grads, p, R, w.slot_row, w.cnt, tn, side, s);

@@ -69,7 +69,7 @@ struct Ws {
   float *CE, *KV, *prob, *Omat, *z;            // [RK,ldce] [RK,ldkv] [R,H*k] [R,ldh] [R,ldh]
   float *dz, *dOmat, *dq, *dKV;                // [R,ldh] [R,ldh] [R,ldh] [RK,ldkv]
   // decoder
-  float *Adec, *h1, *dh1, *dAdec, *logits, *dlogit;  // [2B,ldkv] [2B,ldh] [2B,ldh] [2B,ldkv] [2B] [2B]
+  float *Pdec, *dPdec, *h1, *logits;           // [R,ldkv] [R,ldkv] [2B,ldh] [2B]
   float* loss_acc;                                   // [TGNN_MAX_BATCHES] per-batch loss sums
   // standalone-call staging
   float *x_root_s, *x_nbr_s;                         // unused placeholders
@@ -147,11 +147,14 @@ int set_error(int code, const char* fmt, ...);
 // set to zero.  Kp (multiple of 32) columns of A and B are read; B rows >= N and A rows >= M read as zero.
 // m_dev (device pointer, may be NULL): the number of valid rows is min(M, *m_dev); the grid is sized for M.
 // RowAdd (optional): row m of C additionally receives src[idx * ld + n] for n < N, with idx = index[m]
-// (index[m] < 0: nothing is added) or, without an index array, idx = m + row0.
+// (index[m] < 0: nothing is added) or, without an index array, idx = m + row0.  gate (optional, applied
+// last): C[m, n] is set to zero where gate[m * ld_gate + n] is not positive (the ReLU gate of a stored output).
 struct RowAdd {
   const float* src = nullptr;
   const int32_t* index = nullptr;
   int ld = 0, row0 = 0;
+  const float* gate = nullptr;
+  int ld_gate = 0;
 };
 // TimeGradOut (optional): C is not written.  Instead C[m, n] is taken as the gradient reaching the time encoding
 // Phi(delta[m])_n = cos(w[n] delta[m] + b[n]) and each 64-row tile writes the column sums of its part of
@@ -348,13 +351,9 @@ void attn_core_bwd(const Dims& d, int R, const float* q, int ldq_, const int32_t
                    hipStream_t s);
 
 // ---- k_decoder.hip ------------------------------------------------------------------
-void decoder_assemble(const Dims& d, const BatchSet* bs, int total, const float* z, int ldz, float* Adec, int lda,
-                      hipStream_t s);
-void decoder_loss(const Dims& d, const BatchSet* bs, int total, const float* h1, int ldh, const float* w2, const float* b2,
-                  float* logits, float* out_loss, float* dh1, float* g_w2, float* g_b2, hipStream_t s);
-void decoder_dz(const Dims& d, const BatchSet* bs, int total, const float* dAdec, int lda, const float* z, int ldz, float* dz,
-                hipStream_t s);
-// dz_out[r, c] = z[r, c] > 0 ? dz_in[r, c] : 0   (dz_in pitch p_in)
+void decoder_pairs(const Dims& d, const BatchSet* bs, int total, const float* Pdec, int ldp, const float* b1,
+                   const float* w2, const float* b2, float* logits, float* out_loss, float* h1, float* dPdec,
+                   float* g_w2, float* g_b2, hipStream_t s);
 void mask_dz(int R, int dO, const float* dz_in, int p_in, const float* z, int ldz, float* dz_out, hipStream_t s);
 // d_x_root[r, c] = ds_row[r, c];  d_x_nbr[j, c] = ds_row[R + j, c]   (c < dm, outputs pitch dm)
 void attn_dx_out(int R, int RK, int dm, const float* ds_row, int ldh, float* d_x_root, float* d_x_nbr, hipStream_t s);
