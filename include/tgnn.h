@@ -45,12 +45,13 @@ extern "C" {
                                        HIP graph and replays that with one launch, updating only the batch
                                        descriptors.  Not used on the NULL (legacy default) stream, while the caller's stream is itself being captured
                                        or while stage timing is enabled. */
-#define TGNN_FLAG_SIDE_STREAM 2     /* tgnn_train_step moves work that is off the critical path (weight gradients,
-                                       write-back, slot sorting, the query projection) to a second stream of the
-                                       context, forked from and joined back into the caller's stream with events
-                                       inside the call.  Off by default: on MI355X the step is then bound by the host's
-                                       launch rate (measured), and captured graphs with parallel branches replay
-                                       slower than a linear one. */
+#define TGNN_FLAG_SIDE_STREAM 2     /* tgnn_train_step starts the bulk of the weight-gradient GEMMs (decoder, merge
+                                       layer, {e | Phi} columns of W_k / W_v) on a second stream of the context as
+                                       soon as their operands exist, beside the remaining chain of small backward
+                                       kernels; forked from and joined back into the caller's stream with one
+                                       event each inside the call.  Off by default: measured on MI355X the two
+                                       streams get in each other's way and the step takes a few per cent longer,
+                                       launched one by one and as a captured graph alike. */
 
 #define TGNN_MAX_K 32        /* neighbours per root */
 #define TGNN_MAX_BATCHES 16  /* mini-batches (memory replicas) per tgnn_train_step call */

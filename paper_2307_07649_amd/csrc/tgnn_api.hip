@@ -151,12 +151,6 @@ struct Side {
     (void)hipEventRecord(e, c->side);
     (void)hipStreamWaitEvent(main, e, 0);
   }
-  // weight-gradient problems queued so far: start them now on the side stream, or keep them queued
-  void flush(TnBatch& tn) {
-    if (!on) return;
-    fork();
-    tn.launch(c->side);
-  }
 };
 
 // Records a pair of events around a stage when its bit is set in the profiler mask.
@@ -226,7 +220,6 @@ static void attn_backward(tgnn_ctx* ctx, tgnn_params* g, const tgnn_params* p, i
   const Dims& d = ctx->d; Ws& w = ctx->w;
   const int RK = R * d.k;
   tn.add(w.dz, d.ldh, w.Omat, d.ldh, R, d.dO, d.dO, single_out(g->wo, d.dO + d.dx, nullptr));
-  side.flush(tn);
   gemm_nt(w.dz, d.ldh, w.WoT_o, d.ldh, nullptr, w.dOmat, d.ldh, R, d.dO, d.ldh, d.ldh, false, s);
   attn_core_bwd(d, R, w.P + d.ldkv, d.ldp, slot_row, w.KV, d.ldkv, cnt, w.prob, w.dOmat, d.ldh, w.dq, w.dKV, s);
   if (d.de + d.dt > 0) {
@@ -235,7 +228,10 @@ static void attn_backward(tgnn_ctx* ctx, tgnn_params* g, const tgnn_params* p, i
     kv.p[0][0] = g->wk + d.dx; kv.p[1][0] = g->wv + d.dx; kv.ld[0][0] = kv.ld[1][0] = d.dkv;
     kv.n_split = d.dO; kv.k_split = 1 << 30;
     tn.add(w.dKV, d.ldkv, w.CE, d.ldce, RK, 2 * d.dO, d.de + d.dt, kv);
-    side.flush(tn);
+  }
+  if (side.on) {   // the bulk of the weight-gradient work is known here: start it beside the rest of the chain
+    side.fork();
+    tn.launch(side.c->side);
   }
   {  // gradient reaching the keys' Phi, reduced to per-tile time-encoding gradient sums inside the GEMM
     TimeGradOut tg;
@@ -721,7 +717,6 @@ static int enqueue_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
 
   StageTimer tm{ctx, s};
   Side side{ctx, s, (ctx->cfg.flags & TGNN_FLAG_SIDE_STREAM) != 0};
-  hipStream_t s2 = side.stream();
   SgdSet sgd_set, zero_set_;
   fill_param_set(d, p, grads, 2, sgd_set);  // time_w, time_b stay frozen
   fill_param_set(d, grads, nullptr, 0, zero_set_);
@@ -733,10 +728,9 @@ static int enqueue_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
   sample_roots(ctx, g, R, s);
   uniq_map(ctx, S, s);
   tm.end(2);
-  side.fork();
-  tm.begin(1, s2);
-  uniq_sort(ctx, S, s2);   // only the backward pass needs the row-sorted slot list
-  tm.end(1, s2);
+  tm.begin(1);
+  uniq_sort(ctx, S, s);   // only the backward pass needs the row-sorted slot list
+  tm.end(1);
 
   // UPDT once per distinct (replica, node) among the root and supporting nodes, from the pre-batch state
   const int U = S < d.maxU ? S : d.maxU;   // launch bound; the actual row count is *w.ucount on the device
@@ -765,14 +759,6 @@ static int enqueue_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
                 w.dP, d.ldp, s);
   tm.end(6);
 
-  // Last-event-wins write-back: needs s' and tau only, and every read of the stored state (the gather) is
-  // already queued before it, so it can run beside the rest of the step.
-  side.fork();
-  tm.begin(19, s2);
-  writeback_scatter(d, w.bs_dev, bs.total, st, w.winkey, w.epoch, w.Xrow, d.ldxr, w.tau, w.slot_row, nullptr, nullptr,
-                    nullptr, nullptr, out_winner, s2);
-  tm.end(19, s2);
-
   // attention + merge
   CeArgs aa;
   memset(&aa, 0, sizeof(aa));
@@ -785,7 +771,6 @@ static int enqueue_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
   assemble_ce(aa, s);
   tm.end(7);
   attn_forward(ctx, p, R, U, w.ucount, w.slot_row, w.cnt, &tm, s);
-  side.join();   // in passing: the write-back and the slot sort
 
   // decoder + loss (also produces d loss / d hidden)
   tm.begin(12);
@@ -794,8 +779,9 @@ static int enqueue_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
                 grads->dec_w2, grads->dec_b2, s);
   tm.end(12);
 
-  // Backward.  The data-gradient chain stays on the caller's stream; each weight-gradient GEMM is started on
-  // the side stream as soon as its two operands exist (single-stream mode: all of them in one launch at the end).
+  // Backward.  The data-gradient chain stays on the caller's stream; the weight-gradient GEMMs are queued and
+  // leave in one launch at the end (side-stream mode: those known after the attention backward leave there,
+  // on the side stream).
   tm.begin(13);
   OutMap dec;
   memset(&dec, 0, sizeof(dec));
@@ -803,7 +789,6 @@ static int enqueue_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
   dec.n_split = d.dO; dec.k_split = 1 << 30; dec.bias[1] = grads->dec_b1;   // every pair is in one W_d half
   TnBatch tn;
   tn.add(w.dPdec, d.ldkv, w.z, d.ldh, R, 2 * d.dO, d.dO, dec);
-  side.flush(tn);
   {  // dz, gated by the ReLU of the merge layer
     RowAdd gate;
     gate.gate = w.z; gate.ld_gate = d.ldh;
@@ -820,13 +805,9 @@ static int enqueue_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
   tm.end(15);
   tn.add(w.dgi, d.ld3, w.X, d.ldx, U, 3 * d.dm, d.d_in, single_out(grads->gru_wih, d.d_in, grads->gru_bih), w.ucount);
   tn.add(w.dgh, d.ld3, w.Hm, d.ldh, U, 3 * d.dm, d.dm, single_out(grads->gru_whh, d.dm, grads->gru_bhh), w.ucount);
-  if (side.on) {
-    side.flush(tn);
-  } else {
-    tm.begin(16);
-    tn.launch(s);
-    tm.end(16);
-  }
+  tm.begin(16);
+  tn.launch(s);
+  tm.end(16);
   tm.begin(17);
   {  // gradient reaching the mails' Phi, reduced the same way
     TimeGradOut tg;
@@ -842,19 +823,17 @@ static int enqueue_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
     time_grad_finish(keys, mail, d.dt, grads->time_w, grads->time_b, &qp, s);
   }
   tm.end(17);
-  side.join();   // all weight gradients
+  side.join();   // the weight gradients started beside the chain
 
   if (lr != 0.0f) {
     tm.begin(18);
     sgd_update(w.sgd_dev, sgd_set.cnt, lr, s);
     tm.end(18);
   }
-  if (!side.on) {
-    tm.begin(19);
-    writeback_scatter(d, w.bs_dev, bs.total, st, w.winkey, w.epoch, w.Xrow, d.ldxr, w.tau, w.slot_row, nullptr, nullptr,
-                      nullptr, nullptr, out_winner, s);
-    tm.end(19);
-  }
+  tm.begin(19);
+  writeback_scatter(d, w.bs_dev, bs.total, st, w.winkey, w.epoch, w.Xrow, d.ldxr, w.tau, w.slot_row, nullptr, nullptr,
+                    nullptr, nullptr, out_winner, s);
+  tm.end(19);
   if (out_logits)
     TGNN_HIP_CHECK(hipMemcpyAsync(out_logits, w.logits, sizeof(float) * B2, hipMemcpyDeviceToDevice, s));
   TGNN_LAUNCH_CHECK();
