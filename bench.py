@@ -102,7 +102,10 @@ def main():
     ap.add_argument("--lr", type=float, default=1e-4)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--side-stream", action="store_true", help="let the library fork independent work of a step onto its second stream")
-    ap.add_argument("--no-stage-events", action="store_true", help="do not time the two roofline kernels inside the timed region (the step then replays a captured HIP graph)")
+    ap.add_argument("--no-stage-events", action="store_true", help="do not time the two roofline kernels inside the timed region (every step then replays a captured HIP graph)")
+    ap.add_argument("--event-every", type=int, default=8,
+                    help="inside the timed region, every N-th step is launched kernel by kernel with HIP events around "
+                         "the two roofline kernels; the other steps replay the captured HIP graph (1: every step)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="first run the library's plain copy kernel on 256 MiB three times (reference for rocprofv3 --pmc "
                          "FETCH_SIZE / WRITE_SIZE readings)")
@@ -166,21 +169,32 @@ def main():
     # a stream of its own: the library replays a captured HIP graph there (the NULL stream cannot be captured)
     torch.cuda.synchronize()
     torch.cuda.set_stream(torch.cuda.Stream())
+    roof_mask = 0 if args.no_stage_events else (1 << STAGE_ASSEMBLE) | (1 << STAGE_KV)
+    every = max(1, args.event_every)
+    ctx.tgnn_profile_enable(roof_mask)
+    ctx.tgnn_profile_every(2)             # warm up both launch modes
     for s in range(args.warmup):
         run_step(s)
     torch.cuda.synchronize()
-    if not args.no_stage_events:
-        ctx.tgnn_profile_enable((1 << STAGE_ASSEMBLE) | (1 << STAGE_KV))
+    ctx.tgnn_profile_enable(roof_mask)    # drops the warm-up's records
+    ctx.tgnn_profile_every(every)
     ev = 0
+    ev_timed_launches = 0                 # events of the steps whose roofline kernels were timed
+    n_timed_launches = 0
     t0 = time.perf_counter()
     for s in range(args.warmup, args.warmup + args.steps):
-        ev += run_step(s)
+        n = run_step(s)
+        ev += n
+        if roof_mask != 0 and (s - args.warmup) % every == 0:
+            ev_timed_launches += n
+            n_timed_launches += 1
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     final_loss = float(loss[0].item())
     n_g, ms_g = ctx.tgnn_profile_read(STAGE_ASSEMBLE)
     n_m, ms_m = ctx.tgnn_profile_read(STAGE_KV)
     ctx.tgnn_profile_enable(0)
+    ctx.tgnn_profile_every(1)
 
     # per-stage breakdown from a separate, untimed pass with every stage bracketed by events
     n_prof = min(args.steps, 64)
@@ -196,7 +210,7 @@ def main():
     ctx.tgnn_profile_enable(0)
 
     ev_step = ev / args.steps
-    R_avg = 3 * ev_step
+    R_avg = 3 * (ev_timed_launches / n_timed_launches if n_timed_launches else ev_step)   # roots per timed launch
     kv_tflops = flops_kv(d, R_avg) / (ms_m / n_m * 1e-3) / 1e12 if n_m else None
     asm_gbs = assemble_bytes(d, R_avg) / (ms_g / n_g * 1e-3) / 1e9 if n_g else None
     out = {

@@ -216,9 +216,13 @@ int32_t tgnn_zero_params(tgnn_ctx* ctx, tgnn_params* g, void* stream);
  * tgnn_profile_enable: time the stages whose bit is set in `stage_mask` in every following tgnn_train_step
  * (0 = off); each timed stage costs two event records per step.  At most 4096 steps are kept per stage;
  * enabling resets the record.  tgnn_profile_read: synchronises the recorded events and returns the number
- * of recorded launches of `stage` and their total duration in milliseconds.  HOST pointers. */
+ * of recorded launches of `stage` and their total duration in milliseconds.  HOST pointers.
+ * tgnn_profile_every: with a non-zero mask, only every `n`-th tgnn_train_step (the first one after this call,
+ * then every n-th; n >= 1, default 1) is timed; the steps between run as if the mask were zero, i.e. they may
+ * replay the captured graph.  Keeps the mask and the record. */
 #define TGNN_N_STAGES 20
 int32_t tgnn_profile_enable(tgnn_ctx* ctx, uint32_t stage_mask);
+int32_t tgnn_profile_every(tgnn_ctx* ctx, int32_t n);
 int32_t tgnn_profile_read(tgnn_ctx* ctx, int32_t stage, int32_t* out_count, double* out_total_ms);
 
 /* A plain streaming copy kernel (dst[i] = src[i], 16-byte words; n_bytes % 16 == 0; buffers must not overlap).

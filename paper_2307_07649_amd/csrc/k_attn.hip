@@ -117,7 +117,7 @@ __global__ __launch_bounds__(256) void attn_bwd_kernel(AttnShape sh, const float
                                                        const int32_t* __restrict__ cnt,
                                                        const float* __restrict__ prob,
                                                        const float* __restrict__ dOmat, float* __restrict__ dq,
-                                                       float* __restrict__ dKV) {
+                                                       float* __restrict__ dKV, float* __restrict__ q_part) {
   extern __shared__ float lds[];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int r = blockIdx.x * 4 + wave;
@@ -215,6 +215,8 @@ __global__ __launch_bounds__(256) void attn_bwd_kernel(AttnShape sh, const float
       }
     }
     dq[(size_t)r * sh.ldo + e] = dqe;
+    // column sums of dq over the roots, spread over QPHI_BLOCKS partial rows to keep the atomics apart
+    if (q_part != nullptr) atomicAdd(q_part + (size_t)(blockIdx.x & (QPHI_BLOCKS - 1)) * sh.dO + e, dqe);
   }
 }
 
@@ -233,11 +235,11 @@ void attn_core_fwd(const Dims& d, int R, const float* q, int ldq, const int32_t*
 // dq and dOmat share the pitch ldo
 void attn_core_bwd(const Dims& d, int R, const float* q, int ldq, const int32_t* slot_row, const float* KV, int ldkv,
                    const int32_t* cnt, const float* prob, const float* dOmat, int ldo, float* dq, float* dKV,
-                   hipStream_t s) {
+                   float* q_part, hipStream_t s) {
   if (R <= 0) return;
   const size_t lds = 4 * sizeof(float) * attn_lds_floats(d.k, d.H, d.dO);
   hipLaunchKernelGGL(attn_bwd_kernel, dim3((R + 3) / 4), dim3(256), lds, s, shape_of(d, R, ldq, ldkv, ldo), q, slot_row,
-                     KV, cnt, prob, dOmat, dq, dKV);
+                     KV, cnt, prob, dOmat, dq, dKV, q_part);
 }
 
 }  // namespace tgnn

@@ -34,7 +34,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, (TN <= 5
                                                       const float* __restrict__ bias, float* __restrict__ C, int ldc,
                                                       int M, int N, int Kp, int n_store, int relu,
                                                       const int* __restrict__ m_dev, int col_tiles, RowAdd add,
-                                                      TimeGradOut tg) {
+                                                      TimeGradOut tg, GruBwdOut gb) {
   constexpr int BM = NT_BM, BN = 16 * TN;
   // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  The column tiles of one row tile
   // read the same rows of A, so they are given consecutive slots of one XCD.
@@ -190,6 +190,38 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, (TN <= 5
     }
     return;
   }
+  if (gb.dgi != nullptr) {
+    // GRU gates backward epilogue: acc is the gradient reaching s' = (1 - z) n + z h.
+#pragma unroll
+    for (int b = 0; b < TN; ++b) {
+      const int col = n0 + b * 16 + li;
+      if (col >= N) continue;
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const int row = m0 + wave * 16 + lg * 4 + v;
+        if (row >= M) continue;
+        float drp = 0.f, dzp = 0.f, dnp = 0.f, dnr = 0.f;
+        if (gb.has[row]) {
+          const float ds = acc[b][v];
+          const float* g = gb.gates + (size_t)row * 4 * gb.ldh;
+          const float r = g[col], z = g[gb.ldh + col], nn = g[2 * gb.ldh + col], hn = g[3 * gb.ldh + col];
+          const float h = gb.Hm[(size_t)row * gb.ldh + col];
+          const float dn = ds * (1.0f - z);
+          const float dz = ds * (h - nn);
+          dnp = dn * (1.0f - nn * nn);
+          const float dr = dnp * hn;
+          dzp = dz * z * (1.0f - z);
+          drp = dr * r * (1.0f - r);
+          dnr = dnp * r;
+        }
+        float* a = gb.dgi + (size_t)row * gb.ld3;
+        float* h_ = gb.dgh + (size_t)row * gb.ld3;
+        a[col] = drp; a[gb.dm + col] = dzp; a[2 * gb.dm + col] = dnp;
+        h_[col] = drp; h_[gb.dm + col] = dzp; h_[2 * gb.dm + col] = dnr;
+      }
+    }
+    return;
+  }
   // rows this lane writes: m0 + wave * 16 + lg * 4 + v; their gather-add source rows (or -1)
   int arow[4];
 #pragma unroll
@@ -223,16 +255,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, (TN <= 5
 template <int TN>
 static void launch_nt(const float* A, int lda, const float* B, int ldb, const float* bias, float* C, int ldc, int M,
                       int N, int Kp, int n_store, bool relu, hipStream_t s, const int* m_dev, const RowAdd& add,
-                      const TimeGradOut& tg) {
+                      const TimeGradOut& tg, const GruBwdOut& gb) {
   constexpr int BM = NT_BM, BN = 16 * TN;
   const int col_tiles = (n_store + BN - 1) / BN;
   const int row_tiles8 = ((M + BM - 1) / BM + 7) & ~7;
   hipLaunchKernelGGL((gemm_nt_kernel<TN>), dim3(col_tiles * row_tiles8), dim3(256), 0, s, A, lda, B, ldb, bias, C, ldc, M,
-                     N, Kp, n_store, relu ? 1 : 0, m_dev, col_tiles, add, tg);
+                     N, Kp, n_store, relu ? 1 : 0, m_dev, col_tiles, add, tg, gb);
 }
 
 void gemm_nt(const float* A, int lda, const float* B, int ldb, const float* bias, float* C, int ldc, int M, int N,
-             int Kp, int n_store, bool relu, hipStream_t s, const int* m_dev, const RowAdd& add, const TimeGradOut& tg) {
+             int Kp, int n_store, bool relu, hipStream_t s, const int* m_dev, const RowAdd& add, const TimeGradOut& tg,
+             const GruBwdOut& gb) {
   if (M <= 0 || N <= 0) return;
   if (n_store < N) n_store = N;
   // Column-tile width in 16-wide MFMA blocks, from sweeps on MI355X: problems of a few thousand rows want the
@@ -252,7 +285,7 @@ void gemm_nt(const float* A, int lda, const float* B, int ldb, const float* bias
   }
   if (const char* e = getenv("TGNN_NT_TN")) best = atoi(e);
 #define TGNN_NT_CASE(TNV) \
-  case TNV: launch_nt<TNV>(A, lda, B, ldb, bias, C, ldc, M, N, Kp, n_store, relu, s, m_dev, add, tg); break;
+  case TNV: launch_nt<TNV>(A, lda, B, ldb, bias, C, ldc, M, N, Kp, n_store, relu, s, m_dev, add, tg, gb); break;
   switch (best) {
     TGNN_NT_CASE(10)
     TGNN_NT_CASE(7)

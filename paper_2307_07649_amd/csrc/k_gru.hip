@@ -1,5 +1,6 @@
-// Element-wise parts of UPDT = GRU cell (Eq. 3): gates forward and backward, and the gradients of the
-// time-encoding parameters.  The matrix products live in k_gemm.hip.
+// Element-wise parts of UPDT = GRU cell (Eq. 3): gates forward, and the last stage of the gradients of the
+// time-encoding parameters.  The matrix products live in k_gemm.hip; the gates' backward pass is an epilogue
+// of the product that yields the gradient reaching s'.
 #include "tgnn_internal.h"
 #include "device_math.h"
 
@@ -63,81 +64,12 @@ void gru_gates_fwd(const Dims& d, int n, const int* n_dev, const float* gi, cons
                      x_out, ld_x, stat, d.ds, gid, d.N, zero_buf, zero_w);
 }
 
-// From the gradient reaching s' of a row to the gradients of the gate pre-activations.  The chain stops at
-// the stored memory and mails, which are constants of the step (Sec. 2.1: no back-propagation through time).
-__global__ void gru_bwd_kernel(int n_max, const int* __restrict__ n_dev, int dm, int ldh, int ld3,
-                               const float* __restrict__ ds_row, const float* __restrict__ gates,
-                               const float* __restrict__ Hm, const int32_t* __restrict__ has,
-                               float* __restrict__ dgi, float* __restrict__ dgh) {
-  const int n = n_dev ? min(n_max, *n_dev) : n_max;
-  const long long total = (long long)n * dm;
-  for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < total;
-       i += (long long)gridDim.x * blockDim.x) {
-    const int row = (int)(i / dm), c = (int)(i - (long long)row * dm);
-    float drp = 0.f, dzp = 0.f, dnp = 0.f, dnr = 0.f;
-    if (has[row]) {
-      const float ds = ds_row[(size_t)row * ldh + c];
-      const float* g = gates + (size_t)row * 4 * ldh;
-      const float r = g[c], z = g[ldh + c], nn = g[2 * ldh + c], hn = g[3 * ldh + c];
-      const float h = Hm[(size_t)row * ldh + c];
-      const float dn = ds * (1.0f - z);
-      const float dz = ds * (h - nn);
-      dnp = dn * (1.0f - nn * nn);
-      const float dr = dnp * hn;
-      dzp = dz * z * (1.0f - z);
-      drp = dr * r * (1.0f - r);
-      dnr = dnp * r;
-    }
-    float* a = dgi + (size_t)row * ld3;
-    float* b = dgh + (size_t)row * ld3;
-    a[c] = drp; a[dm + c] = dzp; a[2 * dm + c] = dnp;
-    b[c] = drp; b[dm + c] = dzp; b[2 * dm + c] = dnr;
-  }
-}
-
-void gru_gates_bwd(const Dims& d, int n, const int* n_dev, const float* ds, const float* gates, const float* Hm,
-                   const int32_t* has, float* dgi, float* dgh, hipStream_t s) {
-  if (n <= 0) return;
-  const long long total = (long long)n * d.dm;
-  const int blocks = (int)((total + 255) / 256);
-  hipLaunchKernelGGL(gru_bwd_kernel, dim3(blocks), dim3(256), 0, s, n, n_dev, d.dm, d.ldh, d.ld3, ds, gates, Hm, has, dgi,
-                     dgh);
-}
-
 // The query's time encoding is Phi(0) = cos(time_b): its gradient, and that of the columns of W_q which
 // multiply it, need only the column sums of dq over the roots:
 //   g_b[c]           += -sin(time_b[c]) * sum_n colsum[n] wq[n, dx + c]
 //   g_wq[n, dx + c]  += colsum[n] cos(time_b[c])
-// qphi_colsum: QPHI_BLOCKS blocks each write the column sums of their range of roots to q_part[block, d_o].
-// time_grad_finish adds them up and applies the two formulas (extra grid rows of that kernel).
-__global__ __launch_bounds__(1024) void qphi_colsum_kernel(const float* __restrict__ dq, int ld, int R, int dO,
-                                                           float* __restrict__ q_part) {
-  __shared__ float part[16][256];
-  const int cx = threadIdx.x & 63, cy = threadIdx.x >> 6;   // 16 row groups x 64 columns
-  const int per = (R + gridDim.x - 1) / gridDim.x;
-  const int r0 = min(R, (int)blockIdx.x * per), r1 = min(R, r0 + per);
-  for (int n0 = 0; n0 < dO; n0 += 64) {   // d_o <= 256
-    const int n = n0 + cx;
-    float a = 0.f;
-    if (n < dO) {
-#pragma unroll 4
-      for (int r = r0 + cy; r < r1; r += 16) a += dq[(size_t)r * ld + n];
-    }
-    part[cy][n0 + cx] = a;
-  }
-  __syncthreads();
-  for (int n = threadIdx.x; n < dO; n += blockDim.x) {
-    float t = 0.f;
-#pragma unroll
-    for (int g = 0; g < 16; ++g) t += part[g][n];
-    q_part[(size_t)blockIdx.x * dO + n] = t;
-  }
-}
-
-void qphi_colsum(const float* dq, int ld, int R, int dO, float* q_part, hipStream_t s) {
-  hipLaunchKernelGGL(qphi_colsum_kernel, dim3(QPHI_BLOCKS), dim3(1024), 0, s, dq, ld, R, dO, q_part);
-}
-
+// The attention backward kernel adds each root's dq to one of QPHI_BLOCKS partial rows q_part[., d_o] (cleared
+// beforehand); time_grad_finish adds the rows up and applies the two formulas (extra grid rows of that kernel).
 // Time-encoding gradients, last stage: the NT GEMMs that produce the gradient reaching Phi write, per 64-row
 // tile, the column sums of its products with -sin(arg) (and with -sin(arg) delta) instead of the matrix itself;
 // this kernel adds the tiles of up to two such launches (keys, mails) to g_w / g_b.

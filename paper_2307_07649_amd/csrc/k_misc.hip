@@ -30,6 +30,7 @@ __global__ void prologue_kernel(PrologueArgs a) {
       int* dst = reinterpret_cast<int*>(a.sgd_dev);
       for (int i = threadIdx.x; i < (int)(sizeof(SgdSet) / sizeof(int)); i += blockDim.x) dst[i] = src[i];
     }
+    for (int i = threadIdx.x; i < a.q_part_n; i += blockDim.x) a.q_part[i] = 0.f;
     if (threadIdx.x == 0) {
       if (a.loss) *a.loss = 0.f;
       *a.epoch += 1ull;
@@ -107,6 +108,7 @@ void prologue_fill(tgnn_ctx* ctx, const tgnn_params* p, const BatchSet* bs, cons
   pa.loss = loss;
   pa.epoch = w.epoch;
   pa.ucount = w.ucount;
+  pa.q_part = w.q_part; pa.q_part_n = QPHI_BLOCKS * d.dO;
 }
 
 dim3 prologue_grid(const PrologueArgs& pa) { return dim3(32, pa.n_pack + pa.zero.cnt + 1); }

@@ -157,7 +157,7 @@ struct Side {
 struct StageTimer {
   tgnn_ctx* c;
   hipStream_t s;
-  bool on(int st) const { return (c->prof.mask >> st) & 1u && c->prof.count[st] < PROF_RING; }
+  bool on(int st) const { return (c->prof.active >> st) & 1u && c->prof.count[st] < PROF_RING; }
   void begin(int st, hipStream_t on_stream) { hipStream_t keep = s; s = on_stream; begin(st); s = keep; }
   void end(int st, hipStream_t on_stream) { hipStream_t keep = s; s = on_stream; end(st); s = keep; }
   void begin(int st) {
@@ -214,14 +214,15 @@ static void attn_forward(tgnn_ctx* ctx, const tgnn_params* p, int R, int n_rows,
 // From ws.dz (already masked by the merge ReLU) down to ws.dP (per-node projection gradients, not yet
 // reduced over slots), ws.dKV and ws.dq; queues the weight-gradient GEMMs of W_o (attention-output
 // columns) and of the {e | Phi} columns of W_k, W_v, and writes the time-encoding partial sums of the keys into
-// ws.tg_keys and the column sums of dq into ws.q_part (both consumed by time_grad_finish).
+// ws.tg_keys and adds the column sums of dq to ws.q_part, which the caller cleared (both consumed by
+// time_grad_finish).
 static void attn_backward(tgnn_ctx* ctx, tgnn_params* g, const tgnn_params* p, int R, const int32_t* slot_row,
                           const int32_t* cnt, TnBatch& tn, Side& side, hipStream_t s) {
   const Dims& d = ctx->d; Ws& w = ctx->w;
   const int RK = R * d.k;
   tn.add(w.dz, d.ldh, w.Omat, d.ldh, R, d.dO, d.dO, single_out(g->wo, d.dO + d.dx, nullptr));
   gemm_nt(w.dz, d.ldh, w.WoT_o, d.ldh, nullptr, w.dOmat, d.ldh, R, d.dO, d.ldh, d.ldh, false, s);
-  attn_core_bwd(d, R, w.P + d.ldkv, d.ldp, slot_row, w.KV, d.ldkv, cnt, w.prob, w.dOmat, d.ldh, w.dq, w.dKV, s);
+  attn_core_bwd(d, R, w.P + d.ldkv, d.ldp, slot_row, w.KV, d.ldkv, cnt, w.prob, w.dOmat, d.ldh, w.dq, w.dKV, w.q_part, s);
   if (d.de + d.dt > 0) {
     OutMap kv;
     memset(&kv, 0, sizeof(kv));
@@ -239,15 +240,22 @@ static void attn_backward(tgnn_ctx* ctx, tgnn_params* g, const tgnn_params* p, i
     gemm_nt(w.dKV, d.ldkv, w.WceT_phi, d.ldkv, nullptr, nullptr, d.ldt, RK, d.dt, d.ldkv, d.ldt, false, s, nullptr, RowAdd(),
             tg);
   }
-  qphi_colsum(w.dq, d.ldh, R, d.dO, w.q_part, s);
 }
 
 // After the per-row reduction into ws.dP: gradient reaching the node rows (ws.ds_row, dynamic columns) and
 // the weight gradients of the node part of W_k, W_v, W_q, W_o with all four biases.
+// through_gru: the gradient is not stored in ws.ds_row but carried on, in the same launch, to the gradients of
+// the GRU gate pre-activations (ws.dgi, ws.dgh).
 static void node_proj_backward(tgnn_ctx* ctx, tgnn_params* g, int n_rows, const int* n_rows_dev, TnBatch& tn,
-                               hipStream_t s) {
+                               bool through_gru, hipStream_t s) {
   const Dims& d = ctx->d; Ws& w = ctx->w;
-  gemm_nt(w.dP, d.ldp, w.WxT, d.ldp, nullptr, w.ds_row, d.ldh, n_rows, d.dm, d.ldp, d.ldh, false, s, n_rows_dev);
+  GruBwdOut gb;
+  if (through_gru) {
+    gb.gates = w.gates; gb.Hm = w.Hm; gb.has = w.has; gb.dgi = w.dgi; gb.dgh = w.dgh;
+    gb.dm = d.dm; gb.ldh = d.ldh; gb.ld3 = d.ld3;
+  }
+  gemm_nt(w.dP, d.ldp, w.WxT, d.ldp, nullptr, w.ds_row, d.ldh, n_rows, d.dm, d.ldp, d.ldh, false, s, n_rows_dev, RowAdd(),
+          TimeGradOut(), gb);
   OutMap kv;
   memset(&kv, 0, sizeof(kv));
   kv.p[0][0] = g->wk; kv.p[1][0] = g->wv; kv.ld[0][0] = kv.ld[1][0] = d.dkv;
@@ -530,6 +538,7 @@ int32_t tgnn_temporal_attn_bwd(tgnn_ctx* ctx, const tgnn_params* p, int32_t n_ro
   REQ_PTR(dz); REQ_PTR(d_x_root); REQ_PTR(d_x_nbr);
   hipStream_t s = as_stream(stream);
   mask_dz(n_roots, d.dO, dz, d.dO, w.z, d.ldh, w.dz, s);
+  zero_f32(w.q_part, QPHI_BLOCKS * d.dO, s);
   TnBatch tn;
   Side side{ctx, s, false};
   const int RK = n_roots * d.k;
@@ -542,7 +551,7 @@ int32_t tgnn_temporal_attn_bwd(tgnn_ctx* ctx, const tgnn_params* p, int32_t n_ro
     time_grad_finish(keys, TgRegion(), d.dt, grads->time_w, grads->time_b, &qp, s);
   }
   slots_to_dp(ctx, n_roots, RK, s);
-  node_proj_backward(ctx, grads, n_roots + RK, nullptr, tn, s);
+  node_proj_backward(ctx, grads, n_roots + RK, nullptr, tn, false, s);
   tn.launch(s);
   attn_dx_out(n_roots, RK, d.dm, w.ds_row, d.ldh, d_x_root, d_x_nbr, s);
   TGNN_LAUNCH_CHECK();
@@ -628,7 +637,9 @@ int32_t tgnn_train_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
   ctx->last_attn_roots = -1;
 
   // the legacy default stream (NULL) cannot be captured
-  bool use_graph = (ctx->cfg.flags & TGNN_FLAG_NO_GRAPH) == 0 && ctx->prof.mask == 0 && s != nullptr;
+  Profiler& pr = ctx->prof;
+  pr.active = pr.mask != 0 && pr.calls++ % pr.every == 0 ? pr.mask : 0;
+  bool use_graph = (ctx->cfg.flags & TGNN_FLAG_NO_GRAPH) == 0 && pr.active == 0 && s != nullptr;
   if (use_graph) {
     hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
     if (hipStreamIsCapturing(s, &cs) != hipSuccess || cs != hipStreamCaptureStatusNone) use_graph = false;
@@ -800,8 +811,7 @@ static int enqueue_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
   tm.end(14);
   tm.begin(15);
   seg_reduce(ctx, R, S, s);   // per-row sum of the slot gradients reaching the per-node projections
-  node_proj_backward(ctx, grads, U, w.ucount, tn, s);
-  gru_gates_bwd(d, U, w.ucount, w.ds_row, w.gates, w.Hm, w.has, w.dgi, w.dgh, s);
+  node_proj_backward(ctx, grads, U, w.ucount, tn, true, s);
   tm.end(15);
   tn.add(w.dgi, d.ld3, w.X, d.ldx, U, 3 * d.dm, d.d_in, single_out(grads->gru_wih, d.d_in, grads->gru_bih), w.ucount);
   tn.add(w.dgh, d.ld3, w.Hm, d.ldh, U, 3 * d.dm, d.dm, single_out(grads->gru_whh, d.dm, grads->gru_bhh), w.ucount);
@@ -862,7 +872,17 @@ int32_t tgnn_debug_copy(void* dst, const void* src, int64_t n_bytes, void* strea
 int32_t tgnn_profile_enable(tgnn_ctx* ctx, uint32_t stage_mask) {
   if (ctx == nullptr) return set_error(TGNN_E_NULL_PTR, "ctx is NULL");
   ctx->prof.mask = stage_mask;
+  ctx->prof.active = 0;
+  ctx->prof.calls = 0;
   for (int i = 0; i < TGNN_N_STAGES; ++i) ctx->prof.count[i] = 0;
+  return TGNN_OK;
+}
+
+int32_t tgnn_profile_every(tgnn_ctx* ctx, int32_t n) {
+  if (ctx == nullptr) return set_error(TGNN_E_NULL_PTR, "ctx is NULL");
+  if (n < 1) return set_error(TGNN_E_INVALID_ARG, "n = %d must be at least 1", n);
+  ctx->prof.every = n;
+  ctx->prof.calls = 0;
   return TGNN_OK;
 }
 

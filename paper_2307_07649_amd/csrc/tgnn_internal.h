@@ -89,7 +89,9 @@ struct Ws {
 namespace tgnn {
 constexpr int PROF_RING = 4096;
 struct Profiler {
-  uint32_t mask = 0;
+  uint32_t mask = 0;     // stages to time
+  uint32_t active = 0;   // the mask in effect for the tgnn_train_step being enqueued (0 between timed steps)
+  int every = 1, calls = 0;
   hipEvent_t* ev[TGNN_N_STAGES][2] = {};  // lazily created rings
   int count[TGNN_N_STAGES] = {};
 };
@@ -166,9 +168,21 @@ struct TimeGradOut {
   const float *w = nullptr, *b = nullptr;
   float* partial = nullptr;
 };
+// GruBwdOut (optional): C is not written.  C[m, n] (n < d_m) is taken as the gradient reaching s' of node row m
+// and turned into the gradients of the GRU gate pre-activations (Eq. 3), written to dgi / dgh [M, ld3] as
+// {r | z | n} blocks of d_m columns; rows with has[m] == 0 (no mail: s' = s) get zeros.  gates holds
+// {r | z | n | W_hn h + b_hn} per row in blocks of ldh columns, Hm the stored memory (pitch ldh).
+struct GruBwdOut {
+  const float* gates = nullptr;
+  const float* Hm = nullptr;
+  const int32_t* has = nullptr;
+  float *dgi = nullptr, *dgh = nullptr;
+  int dm = 0, ldh = 0, ld3 = 0;
+};
 void gemm_nt(const float* A, int lda, const float* B, int ldb, const float* bias, float* C, int ldc, int M,
              int N, int Kp, int n_store, bool relu, hipStream_t s, const int* m_dev = nullptr,
-             const RowAdd& add = RowAdd(), const TimeGradOut& tg = TimeGradOut());
+             const RowAdd& add = RowAdd(), const TimeGradOut& tg = TimeGradOut(),
+             const GruBwdOut& gb = GruBwdOut());
 
 // Where the weight-gradient GEMM adds its result: element (n, k) goes to p[n >= n_split][k >= k_split]
 // (indices taken relative to the split) with row pitch ld[..][..]; column sums of D go to bias[n >= n_split].
@@ -232,6 +246,8 @@ struct PrologueArgs {
   const float *bq, *wq, *time_b;
   float* bq_out;
   int dO, dq, dx, dt;
+  float* q_part;        // cleared (q_part_n floats)
+  int q_part_n;
 };
 void prologue_fill(tgnn_ctx* ctx, const tgnn_params* p, const BatchSet* bs, const SgdSet* sgd, const SgdSet* zero,
                    float* loss, PrologueArgs& pa);
@@ -318,7 +334,7 @@ void gru_gates_fwd(const Dims& d, int n, const int* n_dev, const float* gi, cons
                    float* zero_buf, int zero_w, hipStream_t s);
 // Gradients through the query's time encoding Phi(0) = cos(time_b), from the column sums of dq [R, ld]:
 // g_b[c] += -sin(time_b[c]) sum_n colsum[n] wq[n, dx + c] and g_wq[n, dx + c] += colsum[n] cos(time_b[c]).
-// qphi_colsum writes per-block column sums to q_part [QPHI_BLOCKS, d_o]; time_grad_finish (given a QPhi)
+// The attention backward kernel adds them to q_part [QPHI_BLOCKS, d_o]; time_grad_finish (given a QPhi)
 // turns them into the two gradients.
 constexpr int QPHI_BLOCKS = 64;
 struct QPhi {
@@ -327,10 +343,6 @@ struct QPhi {
   float* g_wq = nullptr;
   int dO = 0, dq_w = 0, dx = 0;
 };
-void qphi_colsum(const float* dq, int ld, int R, int dO, float* q_part, hipStream_t s);
-// ds [n, ldh] = gradient reaching s' per row
-void gru_gates_bwd(const Dims& d, int n, const int* n_dev, const float* ds, const float* gates, const float* Hm,
-                   const int32_t* has, float* dgi, float* dgh, hipStream_t s);
 // Adds the per-tile partial sums written by gemm_nt (TimeGradOut) to g_w / g_b: up to two regions of
 // [tiles, 2, dt]; a region's tile count is ceil(min(rows, *rows_dev) / NT_BM) (rows_dev may be NULL).  With a QPhi
 // it also finishes the gradients through the query's Phi(0).
@@ -347,7 +359,7 @@ void time_grad_finish(const TgRegion& r0, const TgRegion& r1, int dt, float* g_w
 void attn_core_fwd(const Dims& d, int R, const float* q, int ldq_, const int32_t* slot_row, const float* KV, int ldkv,
                    const int32_t* cnt, float* prob, float* Omat, int ldo, hipStream_t s);
 void attn_core_bwd(const Dims& d, int R, const float* q, int ldq_, const int32_t* slot_row, const float* KV, int ldkv,
-                   const int32_t* cnt, const float* prob, const float* dOmat, int ldo, float* dq, float* dKV,
+                   const int32_t* cnt, const float* prob, const float* dOmat, int ldo, float* dq, float* dKV, float* q_part,
                    hipStream_t s);
 
 // ---- k_decoder.hip ------------------------------------------------------------------

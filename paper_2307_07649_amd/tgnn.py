@@ -69,6 +69,7 @@ _SIGS = {
     "tgnn_debug_copy": (_I, [_P, _P, C.c_int64, _P]),
     "tgnn_zero_params": (_I, [_P, C.POINTER(tgnn_params), _P]),
     "tgnn_profile_enable": (_I, [_P, C.c_uint32]),
+    "tgnn_profile_every": (_I, [_P, _I]),
     "tgnn_profile_read": (_I, [_P, _I, C.POINTER(_I), C.POINTER(C.c_double)]),
 }
 EXPORTS = list(_SIGS)
@@ -279,6 +280,9 @@ class Context:
 
     def tgnn_profile_enable(self, stage_mask: int):
         _check(_lib.tgnn_profile_enable(self.h, stage_mask))
+
+    def tgnn_profile_every(self, n: int):
+        _check(_lib.tgnn_profile_every(self.h, n))
 
     def tgnn_profile_read(self, stage: int):
         cnt = _I(0); ms = C.c_double(0.0)
