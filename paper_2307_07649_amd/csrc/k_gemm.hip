@@ -10,6 +10,8 @@
 // buffers, so a workgroup waits for memory only when the chip has nothing else resident to run.
 #include <stdlib.h>
 
+#include <algorithm>
+
 #include "tgnn_internal.h"
 #include "device_math.h"
 
@@ -299,19 +301,23 @@ void gemm_nt(const float* A, int lda, const float* B, int ldb, const float* bias
 
 // ------------------------------------------------------------------------------------------------
 // TN with accumulation: G[n, k] += sum_m D[m, n] * A[m, k], bias[n] += sum_m D[m, n].
-// Both operands are m-major, so a stage is 32 rows of D and of A in LDS, row-major.  The MFMA sums over four
-// m values per instruction (one per lane group), and which n (k) a lane feeds is free as long as the result
-// is read back the same way: lane (li, lg) reads TD consecutive floats D[m][n0 + TD*li ..] and TA consecutive
-// floats A[m][k0 + TA*li ..] with one LDS load each and issues TD*TA MFMAs from them, instruction (t, u)
-// covering the strided columns n = n0 + TD*i + t, k = k0 + TA*j + u.  A workgroup owns a (16 TD) x (16 TA)
-// tile of G (64 x 64 in the bulk, narrower pieces at the right and bottom edges so that little of the
-// tile is padding); its four waves split the 32 rows of a stage, and their partial tiles are added in LDS
-// before one float atomic per element goes to memory.  The reduction over m is split over workgroups.
+// Both operands are m-major.  The MFMA sums over four m values per instruction (one per lane group), and
+// which n (k) a lane feeds is free as long as the result is read back the same way: lane (li, lg) takes TD
+// consecutive floats D[m][n0 + TD*li ..] and TA consecutive floats A[m][k0 + TA*li ..] of row m = 4 step + lg
+// and issues TD*TA MFMAs from them, instruction (t, u) covering the strided columns n = n0 + TD*i + t,
+// k = k0 + TA*j + u.  Those two runs are one vector load each straight from global memory (a lane group reads
+// one contiguous piece of a row), and no element is used by more than one wavefront, so nothing is staged in
+// LDS and the main loop has no barrier: every wavefront streams its own rows, several steps of loads ahead.
+// A workgroup of TN_W wavefronts owns a (16 TD) x (16 TA) tile of G (64 x 64 in the bulk, narrower pieces
+// at the right and bottom edges so that little of the tile is padding) over a chunk of the rows; its
+// wavefronts take the 4-row steps of the chunk in turn, and their partial tiles are added in LDS before one
+// float atomic per element goes to memory.  The reduction over m is split over workgroups.
 // The bias gradient rides along as column K of A, which the loader replaces by ones.
 // ------------------------------------------------------------------------------------------------
-constexpr int TT = 64;     // bulk tile edge
-constexpr int TN_P = 80;   // stage row pitch in floats
-constexpr int TN_ROWS = 32;
+constexpr int TT = 64;        // bulk tile edge
+constexpr int TN_W = 8;       // wavefronts per workgroup
+constexpr int TN_AHEAD = 4;   // 4-row steps whose loads a wavefront keeps in flight
+constexpr int TN_ROWS = 32;   // row chunks are multiples of this
 
 // A length is cut into 64-wide pieces plus at most two narrower ones (32 and/or 16 wide) for the remainder.
 __host__ __device__ inline int tn_pieces(int len) {
@@ -335,16 +341,49 @@ template <> struct FragT<2> { typedef float type __attribute__((ext_vector_type(
 template <> struct FragT<4> { typedef float type __attribute__((ext_vector_type(4))); };
 template <int T> __device__ __forceinline__ float frag_get(const typename FragT<T>::type& f, int i) { return f[i]; }
 template <> __device__ __forceinline__ float frag_get<1>(const float& f, int) { return f; }
+template <int T> __device__ __forceinline__ void frag_set(typename FragT<T>::type& f, int i, float x) { f[i] = x; }
+template <> __device__ __forceinline__ void frag_set<1>(float& f, int, float x) { f = x; }
+template <int T> __device__ __forceinline__ typename FragT<T>::type frag_zero() {
+  typename FragT<T>::type f;
+#pragma unroll
+  for (int i = 0; i < T; ++i) frag_set<T>(f, i, 0.f);
+  return f;
+}
+
+// One global load of T floats per lane, issued without a wait; tn_wait_loads<N> then waits until at most N of
+// the loads issued so far are pending and ties the registers to that wait, so that no use can move above it.
+template <int T> __device__ __forceinline__ void tn_issue_load(typename FragT<T>::type& r, const float* p);
+template <> __device__ __forceinline__ void tn_issue_load<4>(FragT<4>::type& r, const float* p) {
+  asm volatile("global_load_dwordx4 %0, %1, off" : "=&v"(r) : "v"(p) : "memory");
+}
+template <> __device__ __forceinline__ void tn_issue_load<2>(FragT<2>::type& r, const float* p) {
+  asm volatile("global_load_dwordx2 %0, %1, off" : "=&v"(r) : "v"(p) : "memory");
+}
+template <> __device__ __forceinline__ void tn_issue_load<1>(float& r, const float* p) {
+  asm volatile("global_load_dword %0, %1, off" : "=&v"(r) : "v"(p) : "memory");
+}
+template <int N, class FD, class FA> __device__ __forceinline__ void tn_wait_loads(FD& d, FA& a) {
+  asm volatile("s_waitcnt vmcnt(%2)" : "+v"(d), "+v"(a) : "n"(N));
+}
+
+// Where partial-tile element (t, u, v) of lane (li, lg) lives in a reduction buffer: element-major, lane-minor
+// (stores of one instruction touch 64 consecutive words), with the lane rotated by 16 u so that the final
+// pass, which walks a row of the tile (li and u vary, lg fixed), also touches 64 different words.
+template <int TA>
+__device__ __forceinline__ int tn_slot(int t, int u, int v, int li, int lg) {
+  return ((t * TA + u) * 4 + v) * 64 + ((lg * 16 + li + 16 * u) & 63);
+}
 
 template <int TD, int TA>
 __device__ __forceinline__ void tn_tile(const float* __restrict__ D, const float* __restrict__ A, int ldd, int lda, int N,
                                         int K, float* p00, float* p01, float* p10, float* p11, int ld00, int ld01, int ld10,
                                         int ld11, int n_split, int k_split, float* bias0, float* bias1, int M, int m_lo,
                                         int m_hi, int n0, int k0, float* lds) {
+  typedef typename FragT<TD>::type FD;
+  typedef typename FragT<TA>::type FA;
   const bool with_bias = bias0 != nullptr || bias1 != nullptr;   // column K of A reads as ones
-  float* Ds = lds;                          // [2][TN_ROWS * TN_P]
-  float* As = lds + 2 * TN_ROWS * TN_P;     // [2][TN_ROWS * TN_P]
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform: loop bounds stay scalar
   const int li = lane & 15, lg = lane >> 4;
 
   floatx4 acc[TD][TA];
@@ -353,141 +392,110 @@ __device__ __forceinline__ void tn_tile(const float* __restrict__ D, const float
 #pragma unroll
     for (int u = 0; u < TA; ++u) acc[t][u] = floatx4{0.f, 0.f, 0.f, 0.f};
 
-  // Loader: float4 f of a stage is row f / (4 T), columns 4 (f % (4 T)) .. +3 of the tile.  Column offsets are
-  // clamped into the row (results of columns >= N or > K are dropped at the end); rows >= m_hi are clamped
-  // and D is zeroed there by a select.
-  constexpr int D_F4 = TN_ROWS * 4 * TD, A_F4 = TN_ROWS * 4 * TA;
-  constexpr int D_PER = (D_F4 + 255) / 256, A_PER = (A_F4 + 255) / 256;
-  int d_row[D_PER], a_row[A_PER], one_comp[A_PER];
-  const float* pd[D_PER];
-  const float* pa[A_PER];
-#pragma unroll
-  for (int u = 0; u < D_PER; ++u) {
-    const int f = min(tid + u * 256, D_F4 - 1);
-    d_row[u] = f / (4 * TD);
-    pd[u] = D + min(n0 + (f % (4 * TD)) * 4, ldd - 4);
-  }
-#pragma unroll
-  for (int u = 0; u < A_PER; ++u) {
-    const int f = min(tid + u * 256, A_F4 - 1);
-    a_row[u] = f / (4 * TA);
-    const int c = k0 + (f % (4 * TA)) * 4;
-    pa[u] = A + min(c, lda - 4);
-    one_comp[u] = (with_bias && K >= c && K < c + 4) ? K - c : -1;
-  }
-  // The fix-ups (zero rows, ones column) are applied when a register set is stored to LDS, one stage after
-  // its loads were issued, so that no instruction waits on a load in the stage that issued it.
-  struct Regs {
-    floatx4 d[D_PER], a[A_PER];
-    int m;
+  // Column offsets are clamped into the row (results of columns >= N or > K are dropped at the end); rows
+  // >= m_hi are clamped and D is zeroed there by a select when the step is used.
+  const int c_nom = k0 + TA * li;
+  const float* pd = D + min(n0 + TD * li, ldd - TD);
+  const float* pa = A + min(c_nom, lda - TA);
+  const int one_comp = (with_bias && K >= c_nom && K < c_nom + TA) ? K - c_nom : -1;
+  const int n_steps = (m_hi - m_lo + 3) >> 2;
+
+  // The loads are issued as inline assembly and waited for by count: left to itself the compiler sinks them
+  // next to their uses and the wavefront then waits out the full memory latency at every step.  Loads return in
+  // order, so when slot p is needed only the loads of the other TN_AHEAD - 1 slots (two each) may be pending.
+  FD fd[TN_AHEAD];
+  FA fa[TN_AHEAD];
+  auto issue = [&](int step, FD& d, FA& a) __attribute__((always_inline)) {
+    const size_t m = (size_t)min(m_lo + 4 * step + lg, M - 1);
+    tn_issue_load<TD>(d, pd + m * ldd);
+    tn_issue_load<TA>(a, pa + m * lda);
   };
-  Regs r0, r1;
-  auto gload = [&](Regs& r, int m) __attribute__((always_inline)) {
-    r.m = m;
+  auto use = [&](int step, FD d, FA a) __attribute__((always_inline)) {
+    if (m_lo + 4 * step + lg >= m_hi) d = frag_zero<TD>();   // rows out of range: zeros times whatever A holds
+    if (one_comp >= 0) {
 #pragma unroll
-    for (int u = 0; u < D_PER; ++u)
-      r.d[u] = *reinterpret_cast<const floatx4*>(pd[u] + (size_t)min(m + d_row[u], M - 1) * ldd);
-#pragma unroll
-    for (int u = 0; u < A_PER; ++u)
-      r.a[u] = *reinterpret_cast<const floatx4*>(pa[u] + (size_t)min(m + a_row[u], M - 1) * lda);
-  };
-  auto sstore = [&](const Regs& r, int buf) __attribute__((always_inline)) {
-#pragma unroll
-    for (int u = 0; u < D_PER; ++u) {
-      const int f = tid + u * 256;
-      const floatx4 v = r.m + d_row[u] < m_hi ? r.d[u] : floatx4{0.f, 0.f, 0.f, 0.f};
-      if (D_F4 % 256 == 0 || f < D_F4)
-        *reinterpret_cast<floatx4*>(&Ds[buf * TN_ROWS * TN_P + (f / (4 * TD)) * TN_P + (f % (4 * TD)) * 4]) = v;
+      for (int u = 0; u < TA; ++u)
+        if (one_comp == u) frag_set<TA>(a, u, 1.f);
     }
 #pragma unroll
-    for (int u = 0; u < A_PER; ++u) {
-      const int f = tid + u * 256;
-      floatx4 v = r.a[u];   // rows out of range are multiplied by the zeros of D
-      v.x = one_comp[u] == 0 ? 1.f : v.x;
-      v.y = one_comp[u] == 1 ? 1.f : v.y;
-      v.z = one_comp[u] == 2 ? 1.f : v.z;
-      v.w = one_comp[u] == 3 ? 1.f : v.w;
-      if (A_F4 % 256 == 0 || f < A_F4)
-        *reinterpret_cast<floatx4*>(&As[buf * TN_ROWS * TN_P + (f / (4 * TA)) * TN_P + (f % (4 * TA)) * 4]) = v;
-    }
-  };
-  typedef typename FragT<TD>::type FD;
-  typedef typename FragT<TA>::type FA;
-  auto compute = [&](int buf) __attribute__((always_inline)) {
+    for (int t = 0; t < TD; ++t)
 #pragma unroll
-    for (int q = 0; q < 2; ++q) {   // this wave's rows 8 wave .. 8 wave + 7, four per MFMA
-      const int mm = wave * 8 + q * 4 + lg;
-      const FD df = *reinterpret_cast<const FD*>(&Ds[buf * TN_ROWS * TN_P + mm * TN_P + TD * li]);
-      const FA af = *reinterpret_cast<const FA*>(&As[buf * TN_ROWS * TN_P + mm * TN_P + TA * li]);
-#pragma unroll
-      for (int t = 0; t < TD; ++t)
-#pragma unroll
-        for (int u = 0; u < TA; ++u)
-          acc[t][u] = __builtin_amdgcn_mfma_f32_16x16x4f32(frag_get<TD>(df, t), frag_get<TA>(af, u), acc[t][u], 0, 0, 0);
-    }
+      for (int u = 0; u < TA; ++u)
+        acc[t][u] = __builtin_amdgcn_mfma_f32_16x16x4f32(frag_get<TD>(d, t), frag_get<TA>(a, u), acc[t][u], 0, 0, 0);
   };
 
-  const int nst = (m_hi - m_lo + TN_ROWS - 1) / TN_ROWS;   // >= 1 by construction of the grid
-  gload(r0, m_lo);
-  gload(r1, m_lo + TN_ROWS);
-  sstore(r0, 0);
+  // Steps are not dealt out in advance beyond the first TN_AHEAD per wavefront: a wavefront that is done with a
+  // step claims the next free one from a counter in LDS.  The wavefronts of a workgroup share their SIMDs
+  // unevenly (the oldest wins the MFMA pipe), and with a fixed split the youngest would still be at work, alone
+  // and unable to hide its load latency, long after the others had reached the barrier below.
+  int* next_step = reinterpret_cast<int*>(lds + (TN_W / 2) * TT * TT);
+  if (tid == 0) *next_step = TN_W * TN_AHEAD;
   __syncthreads();
-  int st = 0;
-  for (; st + 3 < nst; st += 2) {
-    gload(r0, m_lo + (st + 2) * TN_ROWS);
-    compute(0);
-    sstore(r1, 1);
-    __syncthreads();
-    gload(r1, m_lo + (st + 3) * TN_ROWS);
-    compute(1);
-    sstore(r0, 0);
-    __syncthreads();
+  auto claim = [&]() __attribute__((always_inline)) {
+    int v = 0;
+    if (lane == 0) v = atomicAdd(next_step, 1);
+    return __builtin_amdgcn_readfirstlane(v);
+  };
+  int sidx[TN_AHEAD];   // the step each slot holds; claims only grow, so a slot past the end means all later are
+#pragma unroll
+  for (int p = 0; p < TN_AHEAD; ++p) {
+    sidx[p] = wave + p * TN_W;
+    issue(sidx[p], fd[p], fa[p]);   // past the end: clamped rows, unused
   }
-  const int rem = nst - st;
-  if (rem == 3) gload(r0, m_lo + (st + 2) * TN_ROWS);
-  compute(0);
-  if (rem >= 2) {
-    sstore(r1, 1);
-    __syncthreads();
-    compute(1);
-    if (rem == 3) {
-      sstore(r0, 0);
-      __syncthreads();
-      compute(0);
-    }
+  int nxt = claim();
+  static_assert(TN_AHEAD == 4, "the loop below is written out for four slots");
+#define TGNN_TN_SUBSTEP(P)                                   \
+  {                                                          \
+    tn_wait_loads<2 * (TN_AHEAD - 1)>(fd[P], fa[P]);         \
+    if (sidx[P] < n_steps) use(sidx[P], fd[P], fa[P]);       \
+    sidx[P] = nxt;                                           \
+    issue(nxt, fd[P], fa[P]);                                \
+    nxt = claim();                                           \
   }
+  // slot 0 holds the oldest claim: once that is past the end, so are the others
+  while (sidx[0] < n_steps) {
+    TGNN_TN_SUBSTEP(0) TGNN_TN_SUBSTEP(1) TGNN_TN_SUBSTEP(2) TGNN_TN_SUBSTEP(3)
+  }
+#undef TGNN_TN_SUBSTEP
+  // every issued load has to land before its registers are given to anything else
+#pragma unroll
+  for (int p = 0; p < TN_AHEAD; ++p) tn_wait_loads<0>(fd[p], fa[p]);
 
-  // Add the four waves' partial tiles in LDS (two tiles of 16 TD x 16 TA, written by waves 0/1, then added to
-  // by waves 2/3), then one atomic per element.  acc[t][u][v] of lane (li, lg) is n = TD (4 lg + v) + t,
-  // k = TA li + u of the tile.
-  constexpr int TW = 16 * TA, TILE = 16 * TD * TW;
-  __syncthreads();   // every wave is done reading the stage buffers
-  float* red = lds + (wave & 1) * TILE;
-  if (wave < 2) {
+  // Add the wavefronts' partial tiles in LDS: the lower half of the wavefronts store theirs into a buffer
+  // each, the upper half add theirs on top, then every thread sums the buffers for its elements and issues
+  // one atomic per element.  acc[t][u][v] of lane (li, lg) is n = TD (4 lg + v) + t, k = TA li + u of the tile.
+  constexpr int TW = 16 * TA, TILE = 16 * TD * TW, NB = TN_W / 2;
+  float* red = lds + (wave % NB) * TILE;
+  if (wave < NB) {
 #pragma unroll
     for (int t = 0; t < TD; ++t)
 #pragma unroll
       for (int u = 0; u < TA; ++u)
 #pragma unroll
-        for (int v = 0; v < 4; ++v) red[(TD * (4 * lg + v) + t) * TW + TA * li + u] = acc[t][u][v];
+        for (int v = 0; v < 4; ++v) red[tn_slot<TA>(t, u, v, li, lg)] = acc[t][u][v];
   }
   __syncthreads();
-  if (wave >= 2) {
+  if (wave >= NB) {
 #pragma unroll
     for (int t = 0; t < TD; ++t)
 #pragma unroll
       for (int u = 0; u < TA; ++u)
 #pragma unroll
-        for (int v = 0; v < 4; ++v) red[(TD * (4 * lg + v) + t) * TW + TA * li + u] += acc[t][u][v];
+        for (int v = 0; v < 4; ++v) red[tn_slot<TA>(t, u, v, li, lg)] += acc[t][u][v];
   }
   __syncthreads();
+  constexpr int NT = 64 * TN_W;
 #pragma unroll
-  for (int i = 0; i < (TILE + 255) / 256; ++i) {
-    const int e = tid + i * 256;
-    if (TILE % 256 != 0 && e >= TILE) break;
-    const int n = n0 + e / TW, k = k0 + e % TW;
+  for (int i = 0; i < (TILE + NT - 1) / NT; ++i) {
+    const int e = tid + i * NT;
+    if (TILE % NT != 0 && e >= TILE) break;
+    const int tn = e / TW, tk = e % TW;           // position in the tile
+    const int n = n0 + tn, k = k0 + tk;
     if (n >= N || k > K) continue;
-    const float x = lds[e] + lds[TILE + e];
+    const int slot = tn_slot<TA>(tn % TD, tk % TA, (tn / TD) & 3, tk / TA, tn / (4 * TD));
+    float x = 0.f;
+#pragma unroll
+    for (int b = 0; b < NB; ++b) x += lds[b * TILE + slot];
     // (selects instead of indexing: a dynamically indexed local array would live in scratch memory)
     const bool ns = n >= n_split;
     const int nn = n - (ns ? n_split : 0);
@@ -503,33 +511,34 @@ __device__ __forceinline__ void tn_tile(const float* __restrict__ D, const float
   }
 }
 
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 4))) void gemm_tn_kernel(TnGroup grp) {
+__global__ __launch_bounds__(64 * TN_W) void gemm_tn_kernel(TnGroup grp) {
   // Several independent problems share one launch (all weight gradients of a step): find this workgroup's.
-  int pi = 0;
-#pragma unroll
-  for (int i = 1; i < TN_MAX_GROUP; ++i)
-    if (i < grp.n && (int)blockIdx.x >= grp.p[i].wg_begin) pi = i;
   // The argument block is indexed through the kernel-argument segment itself (scalar loads at a computed
   // offset); indexing the by-value parameter would make the compiler spill the whole block to scratch.
   typedef const TnGroup __attribute__((address_space(4))) * GroupPtr;
   const GroupPtr gp = (GroupPtr)__builtin_amdgcn_kernarg_segment_ptr();
+  const int xcd = blockIdx.x & 7, pos = blockIdx.x >> 3;
+  int pi = -1, local = 0, v = 0;
+  for (int i = 0; i < gp->n; ++i) {
+    const int vi = (xcd + gp->p[i].rot) & 7;
+    const int cnt = gp->p[i].chunks > vi ? gp->p[i].tiles * ((gp->p[i].chunks - vi + 7) >> 3) : 0;
+    const int begin = gp->p[i].lane_begin[xcd];
+    if (pos >= begin && pos < begin + cnt) { pi = i; local = pos - begin; v = vi; }
+  }
+  if (pi < 0) return;   // this XCD's queue is shorter than the longest one
   const auto& q = gp->p[pi];
-  const int k_tiles = q.k_tiles, tiles = q.tiles, chunks = q.chunks, wg_begin = q.wg_begin, N = q.N, K = q.K;
+  const int k_tiles = q.k_tiles, tiles = q.tiles, chunks = q.chunks, N = q.N, K = q.K;
   int M = q.M, m_chunk = q.m_chunk;
   const int* m_dev = q.m_dev;
   float* const bias0 = q.out.bias[0];
   const bool with_bias = bias0 != nullptr || q.out.bias[1] != nullptr;
-  // All output tiles of one m-chunk read the same rows of D and A: keep them on one XCD (one L2).
-  const int local = (int)blockIdx.x - wg_begin;
-  const int xcd = local & 7, slot = local >> 3;
-  const int chunk = (slot / tiles) * 8 + xcd, tile = slot % tiles;
-  if (chunk >= chunks) return;
+  const int chunk = (local / tiles) * 8 + v, tile = local % tiles;
   if (m_dev != nullptr) {  // row count known only on the device: split it evenly over the launched chunks
     M = min(M, *m_dev);
     m_chunk = ((M + chunks - 1) / chunks + TN_ROWS - 1) / TN_ROWS * TN_ROWS;
   }
   if (chunk * m_chunk >= M) return;   // uniform for the workgroup, before any barrier
-  __shared__ __attribute__((aligned(16))) float lds[4 * TN_ROWS * TN_P];
+  __shared__ __attribute__((aligned(16))) float lds[(TN_W / 2) * TT * TT + 4];   // reduction buffers + step counter
   const int m_lo = chunk * m_chunk;
   const int m_hi = min(M, m_lo + m_chunk);
   int n0, wn, k0, wk;
@@ -563,38 +572,69 @@ void TnBatch::add(const float* D, int ldd, const float* A, int lda, int M, int N
   g.n++;
 }
 
-// Every workgroup ends with one float atomic per element of its tile, and the L2 retires roughly one such
-// element per clock and channel: the number of m-chunks is what the atomics cost.  So a small launch gets
-// about as many workgroups as the chip holds at once, shared out over the problems in proportion to their
-// multiply work (a small problem gets a handful of chunks instead of dozens); a large launch gets more,
-// about 16 stages each, so that the hardware dispatcher can balance them over several rounds.
-void TnBatch::launch(hipStream_t s) {
-  if (g.n == 0) return;
-  static const int target_wgs = getenv("TGNN_TN_WGS") ? atoi(getenv("TGNN_TN_WGS")) : 1024;
-  double work[TN_MAX_GROUP], total = 0.0;
-  int rows[TN_MAX_GROUP];
-  for (int i = 0; i < g.n; ++i) {
-    // a row count that lives on the device (distinct nodes of a step) is usually a small part of its bound
-    rows[i] = g.p[i].m_dev != nullptr ? (g.p[i].M + 7) / 8 : g.p[i].M;
-    work[i] = (double)rows[i] * g.p[i].tiles;
-    total += work[i];
-  }
-  double want = total / (16.0 * TN_ROWS);
-  if (want < target_wgs) want = target_wgs;
-  int total_wgs = 0;
+// Chunking and placement.  A workgroup's life is a first wait for data, its share of the rows at the pace of
+// the MFMA pipes it shares, and a reduction with one float atomic per tile element; a launch takes as long
+// as the number of rounds the chip needs to hold all workgroups times the life of one.  So a small launch
+// (all weight gradients of a step on a few thousand rows) gets the largest number of row chunks with which
+// no XCD queue exceeds TN_WGS_PER_XCD workgroups, and a large one gets chunks of TN_MAX_ROWS rows and runs
+// in rounds.  An XCD holds 64 workgroups at once (two per compute unit); workgroups with narrow edge tiles
+// finish early, and a queue one and a half times that long measured best on MI355X for the weight gradients
+// of a 600-event step.  All problems of a launch use the same chunk length.
+constexpr int TN_MAX_ROWS = 1024;
+constexpr int TN_WGS_PER_XCD = 96;
+
+// Chunks of `rows_per_chunk` rows for every problem, then the placement on the eight XCDs: problems in order
+// of decreasing size, each rotated so that the XCDs which receive one chunk more than the others are the least
+// loaded ones so far.  Returns the length of the longest XCD queue.
+static int tn_place(TnGroup& g, const int* rows, int rows_per_chunk) {
   for (int i = 0; i < g.n; ++i) {
     TnProblem& p = g.p[i];
-    int chunks = (int)(want * (work[i] / total) / p.tiles + 0.5);
-    const int max_chunks = (rows[i] + 63) / 64;   // at least two stages each
-    if (chunks > max_chunks) chunks = max_chunks;
-    if (chunks < 1) chunks = 1;
+    int chunks = (rows[i] + rows_per_chunk - 1) / rows_per_chunk;
     p.m_chunk = ((p.M + chunks - 1) / chunks + TN_ROWS - 1) / TN_ROWS * TN_ROWS;
     if (p.m_dev == nullptr) chunks = (p.M + p.m_chunk - 1) / p.m_chunk;
     p.chunks = chunks;
-    p.wg_begin = total_wgs;
-    total_wgs += p.tiles * ((chunks + 7) & ~7);
   }
-  hipLaunchKernelGGL(gemm_tn_kernel, dim3(total_wgs), dim3(256), 0, s, g);
+  int order[TN_MAX_GROUP], load[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  for (int i = 0; i < g.n; ++i) order[i] = i;
+  std::sort(order, order + g.n, [&](int a, int b) { return g.p[a].tiles * g.p[a].chunks > g.p[b].tiles * g.p[b].chunks; });
+  for (int oi = 0; oi < g.n; ++oi) {
+    TnProblem& p = g.p[order[oi]];
+    int cnt[8];
+    for (int v = 0; v < 8; ++v) cnt[v] = p.chunks > v ? p.tiles * ((p.chunks - v + 7) / 8) : 0;
+    int best_rot = 0, best_max = 1 << 30;
+    for (int r = 0; r < 8; ++r) {
+      int mx = 0;
+      for (int x = 0; x < 8; ++x) mx = std::max(mx, load[x] + cnt[(x + r) & 7]);
+      if (mx < best_max) { best_max = mx; best_rot = r; }
+    }
+    p.rot = best_rot;
+    for (int x = 0; x < 8; ++x) {
+      p.lane_begin[x] = load[x];
+      load[x] += cnt[(x + best_rot) & 7];
+    }
+  }
+  return *std::max_element(load, load + 8);
+}
+
+void TnBatch::launch(hipStream_t s) {
+  if (g.n == 0) return;
+  static const int per_xcd = getenv("TGNN_TN_WGS") ? atoi(getenv("TGNN_TN_WGS")) / 8 : TN_WGS_PER_XCD;
+  static const int max_rows = getenv("TGNN_TN_RPW") ? atoi(getenv("TGNN_TN_RPW")) : TN_MAX_ROWS;
+  int rows[TN_MAX_GROUP];
+  // a row count that lives on the device (distinct nodes of a step) is usually a small part of its bound
+  for (int i = 0; i < g.n; ++i) rows[i] = g.p[i].m_dev != nullptr ? (g.p[i].M + 7) / 8 : g.p[i].M;
+  // smallest chunk length (in units of TN_ROWS) whose placement fits the chip at once, by bisection
+  int lo = 4, hi = max_rows / TN_ROWS;   // lo: at least four steps per wavefront; hi: taken if nothing smaller fits
+  int longest = tn_place(g, rows, hi * TN_ROWS);
+  if (longest <= per_xcd) {
+    while (lo < hi) {
+      const int mid = (lo + hi) / 2;
+      if (tn_place(g, rows, mid * TN_ROWS) <= per_xcd) hi = mid; else lo = mid + 1;
+    }
+    longest = tn_place(g, rows, hi * TN_ROWS);
+  }
+  const int total_wgs = 8 * longest;
+  hipLaunchKernelGGL(gemm_tn_kernel, dim3(total_wgs), dim3(64 * TN_W), 0, s, g);
   g.n = 0;
 }
 

@@ -198,7 +198,12 @@ struct TnProblem {
   const float* A;
   const int* m_dev;
   int ldd, lda, M, N, K;
-  int m_chunk, k_tiles, tiles, chunks, wg_begin;
+  int m_chunk, k_tiles, tiles, chunks;
+  // Placement of the workgroups (one per chunk and tile).  Workgroup b of the launch runs on XCD b % 8; the
+  // workgroups of XCD x form a queue of their own (position b / 8), in which this problem's start at
+  // lane_begin[x].  XCD x works on the chunks v, v + 8, ... with v = (x + rot) % 8, all tiles of a chunk in a
+  // row, so that the rows of a chunk are fetched into one L2 only.
+  int rot, lane_begin[8];
   OutMap out;
 };
 constexpr int TN_MAX_GROUP = 8;
