@@ -115,9 +115,29 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, (TN <= 5
   // Kp is a multiple of the stage depth.  Stage s lives in register set s & 1 until it is stored to LDS
   // buffer s & 1; loads run two stages ahead of the MFMAs.
   const int nk = Kp / NT_BK;
+  // rows this lane writes: m0 + wave * 16 + lg * 4 + v.  Their gather-add source rows (or -1), and then the
+  // values to add, are fetched now: two dependent loads that would otherwise sit between the last MFMA and
+  // the stores.
+  int arow[4] = {-1, -1, -1, -1};
+  if (add.src != nullptr) {
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      const int row = m0 + wave * 16 + lg * 4 + v;
+      if (row < M) arow[v] = add.index != nullptr ? add.index[row] : row + add.row0;
+    }
+  }
   gload(r0, 0);
   gload(r1, nk > 1 ? NT_BK : 0);
   sstore(r0, 0);
+  float addv[TN][4], bv[TN];
+#pragma unroll
+  for (int b = 0; b < TN; ++b) {
+    const int col = n0 + b * 16 + li;
+    bv[b] = (bias != nullptr && col < N) ? bias[col] : 0.f;
+#pragma unroll
+    for (int v = 0; v < 4; ++v)
+      addv[b][v] = (add.src != nullptr && arow[v] >= 0 && col < N) ? add.src[(size_t)arow[v] * add.ld + col] : 0.f;
+  }
   __syncthreads();
   int kt = 0;
   for (; kt + 3 < nk; kt += 2) {
@@ -224,27 +244,18 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, (TN <= 5
     }
     return;
   }
-  // rows this lane writes: m0 + wave * 16 + lg * 4 + v; their gather-add source rows (or -1)
-  int arow[4];
-#pragma unroll
-  for (int v = 0; v < 4; ++v) {
-    const int row = m0 + wave * 16 + lg * 4 + v;
-    arow[v] = -1;
-    if (add.src != nullptr && row < M) arow[v] = add.index != nullptr ? add.index[row] : row + add.row0;
-  }
 #pragma unroll
   for (int b = 0; b < TN; ++b) {
     const int col = n0 + b * 16 + li;
     if (col >= n_store) continue;
-    const float bv = (bias != nullptr && col < N) ? bias[col] : 0.f;
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
       const int row = m0 + wave * 16 + lg * 4 + v;
       if (row < M) {
         float x = 0.f;
         if (col < N) {
-          x = acc[b][v] + bv;
-          if (arow[v] >= 0) x += add.src[(size_t)arow[v] * add.ld + col];
+          x = acc[b][v] + bv[b];
+          x += addv[b][v];
           if (relu) x = fmaxf(x, 0.f);
           if (add.gate != nullptr && !(add.gate[(size_t)row * add.ld_gate + col] > 0.f)) x = 0.f;
         }
