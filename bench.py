@@ -28,12 +28,13 @@ PEAK_MFMA_F32_TFLOPS = 157.3
 MEASURED_TRAFFIC_BYTES = {"C1": {"kv_projection": 41.0e6, "assemble_ce": 27.2e6}}
 
 STAGE_NAMES = ["prologue (pack weights, clear)", "row-sorted slot list (for the backward row sums)", "roots + sample + distinct-node rows",
-               "gather + time-encode (GRU input)", "GRU input projection (MFMA)", "GRU hidden projection (MFMA)",
+               "gather + time-encode (GRU input)", "GRU input + hidden projections (MFMA, one launch)", "(unused)",
                "GRU gates", "per-slot attention input {e | Phi} (gather)", "K/V projection of the slots (MFMA)",
                "per-node projections K, V, q, merge (MFMA)", "softmax attention", "merge layer (MFMA)",
                "decoder forward + loss", "decoder backward", "attention backward (MFMA + softmax)",
                "per-node gradient sums + node projections backward + GRU gates backward",
-               "all weight gradients (grouped MFMA GEMM)", "time-encoding gradients", "SGD", "write-back scatter"]
+               "all weight gradients (grouped MFMA GEMM)", "time-encoding gradients (two MFMA GEMMs in one launch + final sums)",
+               "SGD", "write-back scatter"]
 STAGE_ASSEMBLE, STAGE_KV = 7, 8
 
 

@@ -207,12 +207,13 @@ int32_t tgnn_zero_params(tgnn_ctx* ctx, tgnn_params* g, void* stream);
 
 /* Stage timing with HIP events on the call's own stream.  Stages of tgnn_train_step:
  *  0 prologue (pack weights, clear loss/grads)   1 row-sorted slot list   2 roots + sample + distinct-node rows
- *  3 gather + time-encode (GRU input)   4 GRU input projection (MFMA)   5 GRU hidden projection (MFMA)   6 GRU gates
+ *  3 gather + time-encode (GRU input)   4 GRU input and hidden projections (MFMA, one launch)   5 (unused)   6 GRU gates
  *  7 per-slot attention input {e | Phi}   8 K/V projection of the slots (MFMA)   9 per-node projections (MFMA)
  *  10 softmax attention   11 merge layer   12 decoder forward + loss   13 decoder backward
- *  14 attention backward (data-gradient GEMMs + softmax + time-encoding partial sums)
+ *  14 attention backward (data-gradient GEMM + softmax)
  *  15 per-node gradient sums + node projections backward + GRU gates backward
- *  16 all weight gradients (one grouped MFMA GEMM)   17 time-encoding gradients   18 SGD   19 write-back scatter
+ *  16 all weight gradients (one grouped MFMA GEMM)   17 time-encoding gradients (GEMMs onto Phi of keys and mails
+ *  with the reduction in their epilogue, one launch; final sums)   18 SGD   19 write-back scatter
  * tgnn_profile_enable: time the stages whose bit is set in `stage_mask` in every following tgnn_train_step
  * (0 = off); each timed stage costs two event records per step.  At most 4096 steps are kept per stage;
  * enabling resets the record.  tgnn_profile_read: synchronises the recorded events and returns the number

@@ -11,6 +11,7 @@
 #include <stdlib.h>
 
 #include <algorithm>
+#include <cstring>
 
 #include "tgnn_internal.h"
 #include "device_math.h"
@@ -31,16 +32,34 @@ constexpr int NT_P = 32;
 __device__ __forceinline__ int nt_swz(int row, int chunk) { return row * NT_P + ((chunk ^ ((row >> 1) & 7)) << 2); }
 
 template <int TN>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, (TN <= 5 ? 4 : 2)))) void gemm_nt_kernel(const float* __restrict__ A, int lda,
-                                                      const float* __restrict__ B, int ldb,
-                                                      const float* __restrict__ bias, float* __restrict__ C, int ldc,
-                                                      int M, int N, int Kp, int n_store, int relu,
-                                                      const int* __restrict__ m_dev, int col_tiles, RowAdd add,
-                                                      TimeGradOut tg, GruBwdOut gb) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, (TN <= 5 ? 4 : 2)))) void gemm_nt_kernel(NtGroup grp) {
   constexpr int BM = NT_BM, BN = 16 * TN;
+  // Up to two independent problems share a launch; the second one's workgroups follow the first one's.
+  // The argument block is read through the kernel-argument segment (scalar loads at a computed offset).
+  typedef const NtGroup __attribute__((address_space(4))) * GroupPtr;
+  const GroupPtr gp = (GroupPtr)__builtin_amdgcn_kernarg_segment_ptr();
+  const int pi = (gp->n > 1 && (int)blockIdx.x >= gp->p[1].wg_begin) ? 1 : 0;
+  const auto& q = gp->p[pi];
+  const float* __restrict__ A = q.A;
+  const float* __restrict__ B = q.B;
+  const float* __restrict__ bias = q.bias;
+  float* __restrict__ C = q.C;
+  const int lda = q.lda, ldb = q.ldb, ldc = q.ldc, N = q.N, Kp = q.Kp, n_store = q.n_store, relu = q.relu;
+  const int col_tiles = q.col_tiles;
+  int M = q.M;
+  const int* m_dev = q.m_dev;
+  RowAdd add;
+  add.src = q.add.src; add.index = q.add.index; add.ld = q.add.ld; add.row0 = q.add.row0;
+  add.gate = q.add.gate; add.ld_gate = q.add.ld_gate;
+  TimeGradOut tg;
+  tg.delta = q.tg.delta; tg.w = q.tg.w; tg.b = q.tg.b; tg.partial = q.tg.partial;
+  GruBwdOut gb;
+  gb.gates = q.gb.gates; gb.Hm = q.gb.Hm; gb.has = q.gb.has; gb.dgi = q.gb.dgi; gb.dgh = q.gb.dgh;
+  gb.dm = q.gb.dm; gb.ldh = q.gb.ldh; gb.ld3 = q.gb.ld3;
   // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  The column tiles of one row tile
   // read the same rows of A, so they are given consecutive slots of one XCD.
-  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int block = (int)blockIdx.x - q.wg_begin;   // wg_begin is a multiple of 8
+  const int xcd = block & 7, slot = block >> 3;
   const int row_tile = (slot / col_tiles) * 8 + xcd, col_tile = slot % col_tiles;
   if (m_dev != nullptr) M = min(M, *m_dev);
   if (row_tile * BM >= M) return;   // uniform for the workgroup, before any barrier
@@ -265,25 +284,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, (TN <= 5
   }
 }
 
-template <int TN>
-static void launch_nt(const float* A, int lda, const float* B, int ldb, const float* bias, float* C, int ldc, int M,
-                      int N, int Kp, int n_store, bool relu, hipStream_t s, const int* m_dev, const RowAdd& add,
-                      const TimeGradOut& tg, const GruBwdOut& gb) {
-  constexpr int BM = NT_BM, BN = 16 * TN;
-  const int col_tiles = (n_store + BN - 1) / BN;
-  const int row_tiles8 = ((M + BM - 1) / BM + 7) & ~7;
-  hipLaunchKernelGGL((gemm_nt_kernel<TN>), dim3(col_tiles * row_tiles8), dim3(256), 0, s, A, lda, B, ldb, bias, C, ldc, M,
-                     N, Kp, n_store, relu ? 1 : 0, m_dev, col_tiles, add, tg, gb);
-}
-
-void gemm_nt(const float* A, int lda, const float* B, int ldb, const float* bias, float* C, int ldc, int M, int N,
-             int Kp, int n_store, bool relu, hipStream_t s, const int* m_dev, const RowAdd& add, const TimeGradOut& tg,
-             const GruBwdOut& gb) {
-  if (M <= 0 || N <= 0) return;
-  if (n_store < N) n_store = N;
-  // Column-tile width in 16-wide MFMA blocks, from sweeps on MI355X: problems of a few thousand rows want the
-  // narrowest tiles (many short workgroups, all resident at once), tens of thousands of rows want 2 blocks,
-  // and only beyond that do wider tiles (less re-reading of A) pay off.
+// Column-tile width in 16-wide MFMA blocks, from sweeps on MI355X: problems of a few thousand rows want the
+// narrowest tiles (many short workgroups, all resident at once), tens of thousands of rows want 2 blocks,
+// and only beyond that do wider tiles (less re-reading of A) pay off.
+static int nt_tile_blocks(int M, int n_store) {
   const int nb = (n_store + 15) / 16;
   int best = 1;
   if (M > 4096 && M <= 65536) {
@@ -297,17 +301,42 @@ void gemm_nt(const float* A, int lda, const float* B, int ldb, const float* bias
     }
   }
   if (const char* e = getenv("TGNN_NT_TN")) best = atoi(e);
+  return best;
+}
+
+void gemm_nt_group(const NtProblem* probs, int n, hipStream_t s) {
+  NtGroup g;
+  memset(&g, 0, sizeof(g));
+  int tn = 0, total = 0;
+  for (int i = 0; i < n && g.n < 2; ++i) {
+    NtProblem p = probs[i];
+    if (p.M <= 0 || p.N <= 0) continue;
+    if (p.n_store < p.N) p.n_store = p.N;
+    if (tn == 0) tn = nt_tile_blocks(p.M, p.n_store);   // the first problem decides the tile width
+    p.col_tiles = (p.n_store + 16 * tn - 1) / (16 * tn);
+    p.wg_begin = total;
+    total += p.col_tiles * (((p.M + NT_BM - 1) / NT_BM + 7) & ~7);
+    g.p[g.n++] = p;
+  }
+  if (g.n == 0) return;
 #define TGNN_NT_CASE(TNV) \
-  case TNV: launch_nt<TNV>(A, lda, B, ldb, bias, C, ldc, M, N, Kp, n_store, relu, s, m_dev, add, tg, gb); break;
-  switch (best) {
-    TGNN_NT_CASE(10)
+  case TNV: hipLaunchKernelGGL((gemm_nt_kernel<TNV>), dim3(total), dim3(256), 0, s, g); break;
+  switch (tn) {
     TGNN_NT_CASE(7)
     TGNN_NT_CASE(5)
     TGNN_NT_CASE(4)
     TGNN_NT_CASE(2)
+    default:
     TGNN_NT_CASE(1)
   }
 #undef TGNN_NT_CASE
+}
+
+void gemm_nt(const float* A, int lda, const float* B, int ldb, const float* bias, float* C, int ldc, int M, int N,
+             int Kp, int n_store, bool relu, hipStream_t s, const int* m_dev, const RowAdd& add, const TimeGradOut& tg,
+             const GruBwdOut& gb) {
+  const NtProblem p = nt_problem(A, lda, B, ldb, bias, C, ldc, M, N, Kp, n_store, relu, m_dev, add, tg, gb);
+  gemm_nt_group(&p, 1, s);
 }
 
 // ------------------------------------------------------------------------------------------------

@@ -11,9 +11,23 @@ __global__ void prologue_kernel(PrologueArgs a) {
   if (y < a.n_pack) {
     const PackDesc d = a.d[y];
     const int total = d.rows * d.zero_to;
-    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < total; i += gridDim.x * blockDim.x) {
-      const int r = i / d.zero_to, c = i - r * d.zero_to;
-      d.dst[(size_t)r * d.ldd + c] = c < d.cols ? d.src[(size_t)r * d.srs + (size_t)c * d.scs] : 0.f;
+    const float* __restrict__ src = d.src;
+    float* __restrict__ dst = d.dst;
+    const int stride = gridDim.x * blockDim.x;
+    // four elements per pass, their loads issued together
+    for (int i0 = blockIdx.x * blockDim.x + threadIdx.x; i0 < total; i0 += 4 * stride) {
+      float v[4];
+      int off[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int i = i0 + j * stride;
+        const int r = i / d.zero_to, c = i - r * d.zero_to;
+        off[j] = i < total ? r * d.ldd + c : -1;
+        v[j] = (i < total && c < d.cols) ? src[(size_t)r * d.srs + (size_t)c * d.scs] : 0.f;
+      }
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        if (off[j] >= 0) dst[off[j]] = v[j];
     }
   } else if (y < a.n_pack + a.zero.cnt) {
     float* p = a.zero.p[y - a.n_pack];

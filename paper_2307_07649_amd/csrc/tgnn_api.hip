@@ -181,8 +181,10 @@ struct StageTimer {
 // UPDT on n rows already staged in ws.X / ws.Hm / ws.has: projections (MFMA) + gates; s' goes to ws.Xrow.
 static void gru_forward(tgnn_ctx* ctx, const tgnn_params* p, int n, hipStream_t s) {
   const Dims& d = ctx->d; Ws& w = ctx->w;
-  gemm_nt(w.X, d.ldx, w.Wih_p, d.ldx, p->gru_bih, w.gi, d.ld3, n, 3 * d.dm, d.ldx, d.ld3, false, s);
-  gemm_nt(w.Hm, d.ldh, w.Whh_p, d.ldh, p->gru_bhh, w.gh, d.ld3, n, 3 * d.dm, d.ldh, d.ld3, false, s);
+  const NtProblem pr[2] = {
+      nt_problem(w.X, d.ldx, w.Wih_p, d.ldx, p->gru_bih, w.gi, d.ld3, n, 3 * d.dm, d.ldx, d.ld3, false),
+      nt_problem(w.Hm, d.ldh, w.Whh_p, d.ldh, p->gru_bhh, w.gh, d.ld3, n, 3 * d.dm, d.ldh, d.ld3, false)};
+  gemm_nt_group(pr, 2, s);
   gru_gates_fwd(d, n, nullptr, w.gi, w.gh, w.Hm, w.has, w.gates, w.Xrow, d.ldxr, nullptr, nullptr, nullptr, 0, s);
 }
 
@@ -216,8 +218,19 @@ static void attn_forward(tgnn_ctx* ctx, const tgnn_params* p, int R, int n_rows,
 // columns) and of the {e | Phi} columns of W_k, W_v, and writes the time-encoding partial sums of the keys into
 // ws.tg_keys and adds the column sums of dq to ws.q_part, which the caller cleared (both consumed by
 // time_grad_finish).
+// The product that carries dKV on to the keys' time encoding, with the reduction to per-tile time-encoding
+// gradient sums (ws.tg_keys) as its epilogue.
+static NtProblem keys_phi_problem(tgnn_ctx* ctx, const tgnn_params* p, int RK) {
+  const Dims& d = ctx->d; Ws& w = ctx->w;
+  TimeGradOut tg;
+  tg.delta = w.dtk; tg.w = p->time_w; tg.b = p->time_b; tg.partial = w.tg_keys;
+  return nt_problem(w.dKV, d.ldkv, w.WceT_phi, d.ldkv, nullptr, nullptr, d.ldt, RK, d.dt, d.ldkv, d.ldt, false, nullptr,
+                    RowAdd(), tg);
+}
+
+// phi_now: launch that product here; otherwise the caller launches it (together with another one).
 static void attn_backward(tgnn_ctx* ctx, tgnn_params* g, const tgnn_params* p, int R, const int32_t* slot_row,
-                          const int32_t* cnt, TnBatch& tn, Side& side, hipStream_t s) {
+                          const int32_t* cnt, TnBatch& tn, Side& side, bool phi_now, hipStream_t s) {
   const Dims& d = ctx->d; Ws& w = ctx->w;
   const int RK = R * d.k;
   tn.add(w.dz, d.ldh, w.Omat, d.ldh, R, d.dO, d.dO, single_out(g->wo, d.dO + d.dx, nullptr));
@@ -234,11 +247,9 @@ static void attn_backward(tgnn_ctx* ctx, tgnn_params* g, const tgnn_params* p, i
     side.fork();
     tn.launch(side.c->side);
   }
-  {  // gradient reaching the keys' Phi, reduced to per-tile time-encoding gradient sums inside the GEMM
-    TimeGradOut tg;
-    tg.delta = w.dtk; tg.w = p->time_w; tg.b = p->time_b; tg.partial = w.tg_keys;
-    gemm_nt(w.dKV, d.ldkv, w.WceT_phi, d.ldkv, nullptr, nullptr, d.ldt, RK, d.dt, d.ldkv, d.ldt, false, s, nullptr, RowAdd(),
-            tg);
+  if (phi_now) {
+    const NtProblem pr = keys_phi_problem(ctx, p, RK);
+    gemm_nt_group(&pr, 1, s);
   }
 }
 
@@ -542,7 +553,7 @@ int32_t tgnn_temporal_attn_bwd(tgnn_ctx* ctx, const tgnn_params* p, int32_t n_ro
   TnBatch tn;
   Side side{ctx, s, false};
   const int RK = n_roots * d.k;
-  attn_backward(ctx, grads, p, n_roots, nullptr, w.cnt, tn, side, s);
+  attn_backward(ctx, grads, p, n_roots, nullptr, w.cnt, tn, side, true, s);
   {
     QPhi qp;
     qp.part = w.q_part; qp.wq = p->wq; qp.time_b = p->time_b; qp.g_wq = grads->wq; qp.dO = d.dO; qp.dq_w = d.dq; qp.dx = d.dx;
@@ -760,11 +771,13 @@ static int enqueue_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
   gather_rows(a, s);
   tm.end(3);
   tm.begin(4);
-  gemm_nt(w.X, d.ldx, w.Wih_p, d.ldx, p->gru_bih, w.gi, d.ld3, U, 3 * d.dm, d.ldx, d.ld3, false, s, w.ucount);
+  {  // W_ih x and W_hh h are independent: one launch
+    const NtProblem pr[2] = {
+        nt_problem(w.X, d.ldx, w.Wih_p, d.ldx, p->gru_bih, w.gi, d.ld3, U, 3 * d.dm, d.ldx, d.ld3, false, w.ucount),
+        nt_problem(w.Hm, d.ldh, w.Whh_p, d.ldh, p->gru_bhh, w.gh, d.ld3, U, 3 * d.dm, d.ldh, d.ld3, false, w.ucount)};
+    gemm_nt_group(pr, 2, s);
+  }
   tm.end(4);
-  tm.begin(5);
-  gemm_nt(w.Hm, d.ldh, w.Whh_p, d.ldh, p->gru_bhh, w.gh, d.ld3, U, 3 * d.dm, d.ldh, d.ld3, false, s, w.ucount);
-  tm.end(5);
   tm.begin(6);
   gru_gates_fwd(d, U, w.ucount, w.gi, w.gh, w.Hm, w.has, w.gates, w.Xrow, d.ldxr, d.ds ? st->stat : nullptr, w.ulist,
                 w.dP, d.ldp, s);
@@ -807,7 +820,7 @@ static int enqueue_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
   }
   tm.end(13);
   tm.begin(14);
-  attn_backward(ctx, grads, p, R, w.slot_row, w.cnt, tn, side, s);
+  attn_backward(ctx, grads, p, R, w.slot_row, w.cnt, tn, side, false, s);
   tm.end(14);
   tm.begin(15);
   seg_reduce(ctx, R, S, s);   // per-row sum of the slot gradients reaching the per-node projections
@@ -819,10 +832,13 @@ static int enqueue_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
   tn.launch(s);
   tm.end(16);
   tm.begin(17);
-  {  // gradient reaching the mails' Phi, reduced the same way
+  {  // gradients reaching the time encodings of the keys and of the mails, each reduced inside its GEMM: one launch
     TimeGradOut tg;
     tg.delta = w.delta; tg.w = p->time_w; tg.b = p->time_b; tg.partial = w.tg_mail;
-    gemm_nt(w.dgi, d.ld3, w.WihT_phi, d.ld3, nullptr, nullptr, d.ldt, U, d.dt, d.ld3, d.ldt, false, s, w.ucount, RowAdd(), tg);
+    const NtProblem pr[2] = {
+        keys_phi_problem(ctx, p, RK),
+        nt_problem(w.dgi, d.ld3, w.WihT_phi, d.ld3, nullptr, nullptr, d.ldt, U, d.dt, d.ld3, d.ldt, false, w.ucount, RowAdd(), tg)};
+    gemm_nt_group(pr, 2, s);
   }
   {
     QPhi qp;

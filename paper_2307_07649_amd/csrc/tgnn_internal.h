@@ -183,6 +183,33 @@ void gemm_nt(const float* A, int lda, const float* B, int ldb, const float* bias
              int N, int Kp, int n_store, bool relu, hipStream_t s, const int* m_dev = nullptr,
              const RowAdd& add = RowAdd(), const TimeGradOut& tg = TimeGradOut(),
              const GruBwdOut& gb = GruBwdOut());
+// The same product as a record, so that two independent ones can share a launch (gemm_nt_group: the tile
+// width is chosen for the first problem; col_tiles and wg_begin are filled in by the launcher).
+struct NtProblem {
+  const float *A, *B, *bias;
+  float* C;
+  int lda, ldb, ldc, M, N, Kp, n_store, relu;
+  const int* m_dev;
+  int col_tiles, wg_begin;
+  RowAdd add;
+  TimeGradOut tg;
+  GruBwdOut gb;
+};
+struct NtGroup {
+  NtProblem p[2];
+  int n;
+};
+inline NtProblem nt_problem(const float* A, int lda, const float* B, int ldb, const float* bias, float* C, int ldc, int M,
+                            int N, int Kp, int n_store, bool relu, const int* m_dev = nullptr,
+                            const RowAdd& add = RowAdd(), const TimeGradOut& tg = TimeGradOut(),
+                            const GruBwdOut& gb = GruBwdOut()) {
+  NtProblem p;
+  p.A = A; p.B = B; p.bias = bias; p.C = C; p.lda = lda; p.ldb = ldb; p.ldc = ldc; p.M = M; p.N = N; p.Kp = Kp;
+  p.n_store = n_store; p.relu = relu ? 1 : 0; p.m_dev = m_dev; p.col_tiles = 0; p.wg_begin = 0;
+  p.add = add; p.tg = tg; p.gb = gb;
+  return p;
+}
+void gemm_nt_group(const NtProblem* probs, int n, hipStream_t s);
 
 // Where the weight-gradient GEMM adds its result: element (n, k) goes to p[n >= n_split][k >= k_split]
 // (indices taken relative to the split) with row pitch ld[..][..]; column sums of D go to bias[n >= n_split].
