@@ -34,7 +34,7 @@ STAGE_NAMES = ["prologue (pack weights, clear)", "row-sorted slot list (for the 
                "decoder forward + loss", "decoder backward", "attention backward (MFMA + softmax)",
                "per-node gradient sums + node projections backward + GRU gates backward",
                "all weight gradients (grouped MFMA GEMM)", "time-encoding gradients (two MFMA GEMMs in one launch + final sums)",
-               "SGD", "write-back scatter"]
+               "(unused)", "write-back scatter + SGD (one launch)"]
 STAGE_ASSEMBLE, STAGE_KV = 7, 8
 
 

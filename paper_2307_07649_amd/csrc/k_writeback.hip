@@ -48,7 +48,19 @@ template <int VEC>
 __global__ __launch_bounds__(256) void wb_scatter_kernel(const BatchSet* __restrict__ bsp, int N, int dm, WbPtrs w,
                                                          const unsigned long long* __restrict__ winkey,
                                                          const unsigned long long* __restrict__ epoch,
-                                                         int32_t* __restrict__ out_winner) {
+                                                         int32_t* __restrict__ out_winner, int wb_blocks,
+                                                         const SgdSet* __restrict__ sgd, float lr) {
+  if ((int)blockIdx.x >= wb_blocks) {
+    // The SGD update of the step shares the launch (it touches parameters and gradients only): 64 blocks per
+    // tensor, p -= lr * g.
+    const int extra = blockIdx.x - wb_blocks;
+    const int t = extra >> 6, x = extra & 63;
+    float* p = sgd->p[t];
+    const float* g = sgd->g[t];
+    const int n = sgd->n[t];
+    for (int i = x * 256 + threadIdx.x; i < n; i += 64 * 256) p[i] -= lr * g[i];
+    return;
+  }
   const BatchSet& bs = *bsp;
   const int lane = threadIdx.x & 63;
   int b, i, role;
@@ -86,15 +98,22 @@ __global__ __launch_bounds__(256) void wb_scatter_kernel(const BatchSet* __restr
 void writeback_scatter(const Dims& d, const BatchSet* bs, int total, const tgnn_state* st,
                        const unsigned long long* winkey, const unsigned long long* epoch, const float* s_new, int p_s,
                        const double* tau, const int32_t* slot_row, const float* s_src, const float* s_dst,
-                       const double* tau_src, const double* tau_dst, int32_t* out_winner, hipStream_t s) {
-  if (total <= 0) return;
+                       const double* tau_src, const double* tau_dst, int32_t* out_winner, hipStream_t s,
+                       const SgdSet* sgd_dev, int sgd_cnt, float lr) {
+  if (total <= 0) {
+    if (sgd_dev != nullptr && sgd_cnt > 0) sgd_update(sgd_dev, sgd_cnt, lr, s);
+    return;
+  }
   WbPtrs w{st->mem, st->mail, st->mem_ts, st->mail_ts, st->mail_eid, s_new, s_src, s_dst, tau, tau_src, tau_dst,
            slot_row, p_s};
   const int blocks = (2 * total + 3) / 4;
+  const int grid = blocks + (sgd_dev != nullptr ? 64 * sgd_cnt : 0);
   if (d.dm % 4 == 0 && p_s % 4 == 0)
-    hipLaunchKernelGGL(wb_scatter_kernel<4>, dim3(blocks), dim3(256), 0, s, bs, d.N, d.dm, w, winkey, epoch, out_winner);
+    hipLaunchKernelGGL(wb_scatter_kernel<4>, dim3(grid), dim3(256), 0, s, bs, d.N, d.dm, w, winkey, epoch, out_winner,
+                       blocks, sgd_dev, lr);
   else
-    hipLaunchKernelGGL(wb_scatter_kernel<1>, dim3(blocks), dim3(256), 0, s, bs, d.N, d.dm, w, winkey, epoch, out_winner);
+    hipLaunchKernelGGL(wb_scatter_kernel<1>, dim3(grid), dim3(256), 0, s, bs, d.N, d.dm, w, winkey, epoch, out_winner,
+                       blocks, sgd_dev, lr);
 }
 
 }  // namespace tgnn

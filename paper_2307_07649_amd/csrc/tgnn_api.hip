@@ -851,14 +851,10 @@ static int enqueue_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
   tm.end(17);
   side.join();   // the weight gradients started beside the chain
 
-  if (lr != 0.0f) {
-    tm.begin(18);
-    sgd_update(w.sgd_dev, sgd_set.cnt, lr, s);
-    tm.end(18);
-  }
+  // last-event-wins write-back of s', tau and the new mails, and the SGD update, in one launch
   tm.begin(19);
   writeback_scatter(d, w.bs_dev, bs.total, st, w.winkey, w.epoch, w.Xrow, d.ldxr, w.tau, w.slot_row, nullptr, nullptr,
-                    nullptr, nullptr, out_winner, s);
+                    nullptr, nullptr, out_winner, s, lr != 0.0f ? w.sgd_dev : nullptr, sgd_set.cnt, lr);
   tm.end(19);
   if (out_logits)
     TGNN_HIP_CHECK(hipMemcpyAsync(out_logits, w.logits, sizeof(float) * B2, hipMemcpyDeviceToDevice, s));

@@ -419,7 +419,8 @@ void writeback_mark(const Dims& d, const BatchSet* bs, int total, unsigned long 
 void writeback_scatter(const Dims& d, const BatchSet* bs, int total, const tgnn_state* st,
                        const unsigned long long* winkey, const unsigned long long* epoch, const float* s_new, int p_s,
                        const double* tau, const int32_t* slot_row, const float* s_src, const float* s_dst, const double* tau_src,
-                       const double* tau_dst, int32_t* out_winner, hipStream_t s);
+                       const double* tau_dst, int32_t* out_winner, hipStream_t s,
+                       const SgdSet* sgd_dev = nullptr, int sgd_cnt = 0, float lr = 0.f);
 // key of occurrence (event e = ev_off + i, role) in the step with epoch counter `epoch`
 __host__ __device__ inline unsigned long long wb_key(unsigned long long epoch, int e, int role) {
   return (epoch << 33) | (1ull + 2ull * (unsigned long long)e + (unsigned long long)role);
