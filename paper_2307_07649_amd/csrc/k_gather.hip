@@ -2,16 +2,25 @@
 // the time encoding of the mail (Eq. 1-2), and the assembly of the per-slot attention inputs (Eq. 5-6).
 // One wavefront moves one row: 16-byte (or 8-byte) vector loads, every row a contiguous burst.
 #include "tgnn_internal.h"
+#include "unique_device.h"
 #include "device_math.h"
 
 namespace tgnn {
 
 template <int VEC>
 __global__ __launch_bounds__(256) void gather_kernel(GatherArgs a) {
+  int block = blockIdx.x, n_blocks = gridDim.x;
+  if (a.scan.ucnt != nullptr) {   // block 0 is a passenger: the scan of the slot sort
+    if (block == 0) {
+      uniq_scan_block(a.scan);
+      return;
+    }
+    --block; --n_blocks;
+  }
   const int lane = threadIdx.x & 63;
   const int wpb = blockDim.x >> 6;
   const int n_slots = a.n_dev ? min(a.n_slots, *a.n_dev) : a.n_slots;
-  for (int s = blockIdx.x * wpb + (threadIdx.x >> 6); s < n_slots; s += gridDim.x * wpb) {
+  for (int s = block * wpb + (threadIdx.x >> 6); s < n_slots; s += n_blocks * wpb) {
     int gid = a.slot_gid ? a.slot_gid[s] : s;
     if (gid >= 0) gid += a.gid_add;
     float* o_mem = a.o_mem + (size_t)s * a.p_mem;
@@ -64,7 +73,7 @@ void gather_rows(const GatherArgs& a, hipStream_t s) {
                             (long long)((uintptr_t)a.o_mail / 4), (long long)((uintptr_t)a.o_ef / 4),
                             (long long)((uintptr_t)a.mem / 4), (long long)((uintptr_t)a.mail / 4),
                             (long long)((uintptr_t)a.efeat / 4)});
-  const int blocks = (a.n_slots + 3) / 4;
+  const int blocks = (a.n_slots + 3) / 4 + (a.scan.ucnt != nullptr ? 1 : 0);
   if (vec == 4) hipLaunchKernelGGL(gather_kernel<4>, dim3(blocks), dim3(256), 0, s, a);
   else if (vec == 2) hipLaunchKernelGGL(gather_kernel<2>, dim3(blocks), dim3(256), 0, s, a);
   else hipLaunchKernelGGL(gather_kernel<1>, dim3(blocks), dim3(256), 0, s, a);

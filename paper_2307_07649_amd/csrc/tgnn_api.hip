@@ -750,10 +750,6 @@ static int enqueue_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
   sample_roots(ctx, g, R, s);
   uniq_map(ctx, S, s);
   tm.end(2);
-  tm.begin(1);
-  uniq_sort(ctx, S, s);   // only the backward pass needs the row-sorted slot list
-  tm.end(1);
-
   // UPDT once per distinct (replica, node) among the root and supporting nodes, from the pre-batch state
   const int U = S < d.maxU ? S : d.maxU;   // launch bound; the actual row count is *w.ucount on the device
   GatherArgs a;
@@ -767,6 +763,7 @@ static int enqueue_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
   a.o_tau = w.tau; a.o_delta = w.delta; a.o_has = w.has;
   a.time_w = p->time_w; a.time_b = p->time_b;
   a.n_slots = U; a.dm = d.dm; a.dt = d.dt; a.de = d.de;
+  a.scan = sort_args(ctx, S);   // the scan of the slot sort rides along (only the backward pass needs the sort)
   tm.begin(3);
   gather_rows(a, s);
   tm.end(3);
@@ -780,7 +777,7 @@ static int enqueue_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
   tm.end(4);
   tm.begin(6);
   gru_gates_fwd(d, U, w.ucount, w.gi, w.gh, w.Hm, w.has, w.gates, w.Xrow, d.ldxr, d.ds ? st->stat : nullptr, w.ulist,
-                w.dP, d.ldp, s);
+                w.dP, d.ldp, s, sort_args(ctx, S));   // with the fill pass of the slot sort
   tm.end(6);
 
   // attention + merge

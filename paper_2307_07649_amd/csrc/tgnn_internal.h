@@ -310,7 +310,17 @@ void sample_recent(const Dims& d, const tgnn_graph* g, const int32_t* node, cons
 
 // ---- k_unique.hip -------------------------------------------------------------------
 void uniq_map(tgnn_ctx* ctx, int S, hipStream_t s);    // slot -> row map, slots per row
-void uniq_sort(tgnn_ctx* ctx, int S, hipStream_t s);   // row-sorted slot list (needed by seg_reduce only)
+// The row-sorted slot list (needed by seg_reduce only): an exclusive scan of the slots-per-row counts, then
+// every slot takes the next free position of its row.  Both ride in other launches (unique_device.h).
+struct SortArgs {
+  const int32_t* ucount = nullptr;   // device row count
+  const int32_t* ucnt = nullptr;     // NULL: nothing to do
+  int32_t *rowptr = nullptr, *cursor = nullptr;
+  int S = 0;
+  const int32_t* slot_row = nullptr;
+  int32_t* sorted = nullptr;
+};
+SortArgs sort_args(tgnn_ctx* ctx, int S);
 // dP[row] += {dKV[slot] | 0} of the row's neighbour slots and {0 | dq[r] | dz[r]} of its root slots
 void seg_reduce(tgnn_ctx* ctx, int R, int S, hipStream_t s);
 // the same with slot = row (standalone attention call): plain stores, every row of dP written
@@ -336,6 +346,7 @@ struct GatherArgs {
   int32_t* o_has;
   const float *time_w, *time_b;
   int n_slots, dm, dt, de;
+  SortArgs scan;            // scan.ucnt != NULL: block 0 of the launch runs the scan of the slot sort instead
 };
 void gather_rows(const GatherArgs& a, hipStream_t s);
 
@@ -363,7 +374,8 @@ void stage_x_rows(int R, int k, int dx, const float* x_root, const float* x_nbr,
 // is cleared for the backward pass.
 void gru_gates_fwd(const Dims& d, int n, const int* n_dev, const float* gi, const float* gh, const float* Hm,
                    const int32_t* has, float* gates, float* x_out, int ld_x, const float* stat, const int32_t* gid,
-                   float* zero_buf, int zero_w, hipStream_t s);
+                   float* zero_buf, int zero_w, hipStream_t s,
+                   const SortArgs& fill = SortArgs());
 // Gradients through the query's time encoding Phi(0) = cos(time_b), from the column sums of dq [R, ld]:
 // g_b[c] += -sin(time_b[c]) sum_n colsum[n] wq[n, dx + c] and g_wq[n, dx + c] += colsum[n] cos(time_b[c]).
 // The attention backward kernel adds them to q_part [QPHI_BLOCKS, d_o]; time_grad_finish (given a QPhi)
