@@ -28,9 +28,9 @@ PEAK_MFMA_F32_TFLOPS = 157.3
 MEASURED_TRAFFIC_BYTES = {"C1": {"kv_projection": 41.0e6, "assemble_ce": 27.2e6}}
 
 STAGE_NAMES = ["prologue (pack weights, clear)", "(unused)", "roots + sample + distinct-node rows",
-               "gather + time-encode (GRU input) + slot-sort scan", "GRU input + hidden projections (MFMA, one launch)", "(unused)",
-               "GRU gates + slot-sort fill", "per-slot attention input {e | Phi} (gather)", "K/V projection of the slots (MFMA)",
-               "per-node projections K, V, q, merge (MFMA)", "softmax attention", "merge layer (MFMA)",
+               "gather + time-encode (GRU input) + slot-to-row map", "GRU input + hidden projections (MFMA, one launch)", "(unused)",
+               "GRU gates + slot-sort scan", "per-slot attention input {e | Phi} (gather)", "K/V projection of the slots (MFMA)",
+               "per-node projections K, V, q, merge (MFMA)", "softmax attention + slot-sort fill", "merge layer (MFMA)",
                "decoder forward + loss", "decoder backward", "attention backward (MFMA + softmax)",
                "per-node gradient sums + node projections backward + GRU gates backward",
                "all weight gradients (grouped MFMA GEMM)", "time-encoding gradients (two MFMA GEMMs in one launch + final sums)",

@@ -3,6 +3,7 @@
 // H*k lanes, the per-head softmax runs over at most 32 values, and the weighted sums are taken with one
 // lane per output element.  The projections themselves (Eq. 4-6) are MFMA GEMMs.
 #include "tgnn_internal.h"
+#include "unique_device.h"
 
 namespace tgnn {
 
@@ -20,10 +21,19 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(AttnShape sh, const float
                                                        const int32_t* __restrict__ slot_row,
                                                        const float* __restrict__ KV,
                                                        const int32_t* __restrict__ cnt, float* __restrict__ prob,
-                                                       float* __restrict__ Omat) {
+                                                       float* __restrict__ Omat, SortArgs fill) {
   extern __shared__ float lds[];
+  int block = blockIdx.x;
+  if (fill.ucnt != nullptr) {   // the first blocks are passengers: the fill pass of the slot sort
+    const int fill_blocks = (fill.S + 255) / 256;
+    if (block < fill_blocks) {
+      uniq_fill_block(fill, block);
+      return;
+    }
+    block -= fill_blocks;
+  }
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int r = blockIdx.x * 4 + wave;
+  const int r = block * 4 + wave;
   if (r >= sh.R) return;
   float* sq = lds + (size_t)wave * attn_lds_floats(sh.k, sh.H, sh.dO);
   float* sK = sq + sh.dO;
@@ -225,11 +235,13 @@ static AttnShape shape_of(const Dims& d, int R, int ldq, int ldkv, int ldo) {
 }
 
 void attn_core_fwd(const Dims& d, int R, const float* q, int ldq, const int32_t* slot_row, const float* KV, int ldkv,
-                   const int32_t* cnt, float* prob, float* Omat, int ldo, hipStream_t s) {
+                   const int32_t* cnt, float* prob, float* Omat, int ldo, hipStream_t s,
+                   const SortArgs& fill) {
   if (R <= 0) return;
   const size_t lds = 4 * sizeof(float) * attn_lds_floats(d.k, d.H, d.dO);
-  hipLaunchKernelGGL(attn_fwd_kernel, dim3((R + 3) / 4), dim3(256), lds, s, shape_of(d, R, ldq, ldkv, ldo), q, slot_row,
-                     KV, cnt, prob, Omat);
+  const int fill_blocks = fill.ucnt != nullptr ? (fill.S + 255) / 256 : 0;
+  hipLaunchKernelGGL(attn_fwd_kernel, dim3((R + 3) / 4 + fill_blocks), dim3(256), lds, s, shape_of(d, R, ldq, ldkv, ldo), q,
+                     slot_row, KV, cnt, prob, Omat, fill);
 }
 
 // dq and dOmat share the pitch ldo

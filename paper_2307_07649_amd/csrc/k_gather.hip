@@ -10,12 +10,13 @@ namespace tgnn {
 template <int VEC>
 __global__ __launch_bounds__(256) void gather_kernel(GatherArgs a) {
   int block = blockIdx.x, n_blocks = gridDim.x;
-  if (a.scan.ucnt != nullptr) {   // block 0 is a passenger: the scan of the slot sort
-    if (block == 0) {
-      uniq_scan_block(a.scan);
+  if (a.map.ucnt != nullptr) {   // the first blocks are passengers: the slot -> row map
+    const int map_blocks = (a.map.S + (int)blockDim.x - 1) / (int)blockDim.x;
+    if (block < map_blocks) {
+      uniq_map_block(a.map, block);
       return;
     }
-    --block; --n_blocks;
+    block -= map_blocks; n_blocks -= map_blocks;
   }
   const int lane = threadIdx.x & 63;
   const int wpb = blockDim.x >> 6;
@@ -73,7 +74,7 @@ void gather_rows(const GatherArgs& a, hipStream_t s) {
                             (long long)((uintptr_t)a.o_mail / 4), (long long)((uintptr_t)a.o_ef / 4),
                             (long long)((uintptr_t)a.mem / 4), (long long)((uintptr_t)a.mail / 4),
                             (long long)((uintptr_t)a.efeat / 4)});
-  const int blocks = (a.n_slots + 3) / 4 + (a.scan.ucnt != nullptr ? 1 : 0);
+  const int blocks = (a.n_slots + 3) / 4 + (a.map.ucnt != nullptr ? (a.map.S + 255) / 256 : 0);
   if (vec == 4) hipLaunchKernelGGL(gather_kernel<4>, dim3(blocks), dim3(256), 0, s, a);
   else if (vec == 2) hipLaunchKernelGGL(gather_kernel<2>, dim3(blocks), dim3(256), 0, s, a);
   else hipLaunchKernelGGL(gather_kernel<1>, dim3(blocks), dim3(256), 0, s, a);

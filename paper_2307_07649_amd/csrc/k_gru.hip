@@ -20,14 +20,18 @@ __global__ void gru_fwd_kernel(int n_max, const int* __restrict__ n_dev, int dm,
                                const float* __restrict__ Hm, const int32_t* __restrict__ has,
                                float* __restrict__ gates, float* __restrict__ x_out, int ld_x,
                                const float* __restrict__ stat, int ds, const int32_t* __restrict__ gid, int N,
-                               float* __restrict__ zero_buf, int zero_w, int gru_blocks, SortArgs fill) {
-  if ((int)blockIdx.x >= gru_blocks) {   // passengers: the fill pass of the slot sort
-    uniq_fill_block(fill, blockIdx.x - gru_blocks);
-    return;
+                               float* __restrict__ zero_buf, int zero_w, int gru_blocks, SortArgs scan) {
+  int block = blockIdx.x;
+  if (scan.ucnt != nullptr) {   // block 0 is a passenger: the scan of the slot sort
+    if (block == 0) {
+      uniq_scan_block(scan);
+      return;
+    }
+    --block;
   }
   const int n = n_dev ? min(n_max, *n_dev) : n_max;
   const long long stride = (long long)gru_blocks * blockDim.x;
-  const long long first = blockIdx.x * (long long)blockDim.x + threadIdx.x;
+  const long long first = block * (long long)blockDim.x + threadIdx.x;
   for (long long i = first; i < (long long)n * dm; i += stride) {
     const int row = (int)(i / dm), c = (int)(i - (long long)row * dm);
     const float h = Hm[(size_t)row * ldh + c];
@@ -61,13 +65,13 @@ __global__ void gru_fwd_kernel(int n_max, const int* __restrict__ n_dev, int dm,
 
 void gru_gates_fwd(const Dims& d, int n, const int* n_dev, const float* gi, const float* gh, const float* Hm,
                    const int32_t* has, float* gates, float* x_out, int ld_x, const float* stat, const int32_t* gid,
-                   float* zero_buf, int zero_w, hipStream_t s, const SortArgs& fill) {
+                   float* zero_buf, int zero_w, hipStream_t s, const SortArgs& scan) {
   if (n <= 0) return;
   const long long total = (long long)n * d.dm;
   const int blocks = (int)((total + 255) / 256);
-  const int fill_blocks = fill.ucnt != nullptr ? (fill.S + 255) / 256 : 0;
-  hipLaunchKernelGGL(gru_fwd_kernel, dim3(blocks + fill_blocks), dim3(256), 0, s, n, n_dev, d.dm, d.ldh, d.ld3, gi, gh, Hm,
-                     has, gates, x_out, ld_x, stat, d.ds, gid, d.N, zero_buf, zero_w, blocks, fill);
+  const int scan_blocks = scan.ucnt != nullptr ? 1 : 0;
+  hipLaunchKernelGGL(gru_fwd_kernel, dim3(blocks + scan_blocks), dim3(256), 0, s, n, n_dev, d.dm, d.ldh, d.ld3, gi, gh, Hm,
+                     has, gates, x_out, ld_x, stat, d.ds, gid, d.N, zero_buf, zero_w, blocks, scan);
 }
 
 // The query's time encoding is Phi(0) = cos(time_b): its gradient, and that of the columns of W_q which

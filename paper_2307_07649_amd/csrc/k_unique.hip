@@ -10,29 +10,11 @@
 
 namespace tgnn {
 
-// slot -> row, and the number of slots per row
-__global__ void uniq_map_kernel(int S, const int32_t* __restrict__ slot_gid, const int32_t* __restrict__ uidx,
-                                int32_t* __restrict__ slot_row, int32_t* __restrict__ ucnt) {
-  const int s = blockIdx.x * blockDim.x + threadIdx.x;
-  int row = -1;
-  if (s < S) {
-    const int gid = slot_gid[s];
-    if (gid >= 0) row = uidx[gid];
-    slot_row[s] = row;
-  }
-  wave_counted_add(ucnt, row, false);
-}
-
-void uniq_map(tgnn_ctx* ctx, int S, hipStream_t s) {
-  Ws& w = ctx->w;
-  hipLaunchKernelGGL(uniq_map_kernel, dim3((S + 255) / 256), dim3(256), 0, s, S, w.slot_gid, w.uidx, w.slot_row, w.ucnt);
-}
-
 SortArgs sort_args(tgnn_ctx* ctx, int S) {
   Ws& w = ctx->w;
   SortArgs a;
   a.ucount = w.ucount; a.ucnt = w.ucnt; a.rowptr = w.rowptr; a.cursor = w.cursor;
-  a.S = S; a.slot_row = w.slot_row; a.sorted = w.sorted;
+  a.S = S; a.slot_gid = w.slot_gid; a.uidx = w.uidx; a.slot_row = w.slot_row; a.sorted = w.sorted;
   return a;
 }
 

@@ -194,7 +194,8 @@ static void gru_forward(tgnn_ctx* ctx, const tgnn_params* p, int n, hipStream_t 
 // their node in the epilogue.  slot_row maps root slot r and neighbour slot R + r k + j to node rows
 // (NULL: slot = row).  n_rows_dev (may be NULL): device-side row count.
 static void attn_forward(tgnn_ctx* ctx, const tgnn_params* p, int R, int n_rows, const int* n_rows_dev,
-                         const int32_t* slot_row, const int32_t* cnt, StageTimer* tm, hipStream_t s) {
+                         const int32_t* slot_row, const int32_t* cnt, StageTimer* tm, hipStream_t s,
+                         const SortArgs& fill = SortArgs()) {
   const Dims& d = ctx->d; Ws& w = ctx->w;
   const int RK = R * d.k;
   if (tm) tm->begin(9);
@@ -205,7 +206,7 @@ static void attn_forward(tgnn_ctx* ctx, const tgnn_params* p, int R, int n_rows,
   kv_add.src = w.P; kv_add.ld = d.ldp; kv_add.index = slot_row ? slot_row + R : nullptr; kv_add.row0 = R;
   gemm_nt(w.CE, d.ldce, w.Wce, d.ldce, nullptr, w.KV, d.ldkv, RK, 2 * d.dO, d.ldce, d.ldkv, false, s, nullptr, kv_add);
   if (tm) { tm->end(8); tm->begin(10); }
-  attn_core_fwd(d, R, w.P + d.ldkv, d.ldp, slot_row, w.KV, d.ldkv, cnt, w.prob, w.Omat, d.ldh, s);
+  attn_core_fwd(d, R, w.P + d.ldkv, d.ldp, slot_row, w.KV, d.ldkv, cnt, w.prob, w.Omat, d.ldh, s, fill);
   if (tm) { tm->end(10); tm->begin(11); }
   RowAdd m_add;
   m_add.src = w.P + d.ldkv + d.dO; m_add.ld = d.ldp; m_add.index = slot_row; m_add.row0 = 0;
@@ -748,7 +749,6 @@ static int enqueue_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
   tm.end(0);
   tm.begin(2);
   sample_roots(ctx, g, R, s);
-  uniq_map(ctx, S, s);
   tm.end(2);
   // UPDT once per distinct (replica, node) among the root and supporting nodes, from the pre-batch state
   const int U = S < d.maxU ? S : d.maxU;   // launch bound; the actual row count is *w.ucount on the device
@@ -763,7 +763,7 @@ static int enqueue_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
   a.o_tau = w.tau; a.o_delta = w.delta; a.o_has = w.has;
   a.time_w = p->time_w; a.time_b = p->time_b;
   a.n_slots = U; a.dm = d.dm; a.dt = d.dt; a.de = d.de;
-  a.scan = sort_args(ctx, S);   // the scan of the slot sort rides along (only the backward pass needs the sort)
+  a.map = sort_args(ctx, S);   // the slot -> row map rides along
   tm.begin(3);
   gather_rows(a, s);
   tm.end(3);
@@ -777,7 +777,7 @@ static int enqueue_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
   tm.end(4);
   tm.begin(6);
   gru_gates_fwd(d, U, w.ucount, w.gi, w.gh, w.Hm, w.has, w.gates, w.Xrow, d.ldxr, d.ds ? st->stat : nullptr, w.ulist,
-                w.dP, d.ldp, s, sort_args(ctx, S));   // with the fill pass of the slot sort
+                w.dP, d.ldp, s, sort_args(ctx, S));   // with the scan of the slot sort
   tm.end(6);
 
   // attention + merge
@@ -791,7 +791,8 @@ static int enqueue_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
   tm.begin(7);
   assemble_ce(aa, s);
   tm.end(7);
-  attn_forward(ctx, p, R, U, w.ucount, w.slot_row, w.cnt, &tm, s);
+  // (the fill pass of the slot sort, needed by the backward pass only, rides in the softmax-attention launch)
+  attn_forward(ctx, p, R, U, w.ucount, w.slot_row, w.cnt, &tm, s, sort_args(ctx, S));
 
   // decoder + loss (also produces d loss / d hidden)
   tm.begin(12);

@@ -309,15 +309,18 @@ void sample_recent(const Dims& d, const tgnn_graph* g, const int32_t* node, cons
                    int32_t* out_nbr, int32_t* out_eid, double* out_ts, int32_t* out_cnt, hipStream_t s);
 
 // ---- k_unique.hip -------------------------------------------------------------------
-void uniq_map(tgnn_ctx* ctx, int S, hipStream_t s);    // slot -> row map, slots per row
-// The row-sorted slot list (needed by seg_reduce only): an exclusive scan of the slots-per-row counts, then
-// every slot takes the next free position of its row.  Both ride in other launches (unique_device.h).
+// Slot -> row map and the row-sorted slot list (the latter needed by seg_reduce only).  Three small passes:
+// map (slot_row[s] = uidx[slot_gid[s]], slots counted per row), an exclusive scan of the counts, and the fill
+// (every slot takes the next free position of its row).  None gets a launch of its own in the training
+// step: they ride as extra blocks in the state-gather, GRU-gates and softmax-attention launches
+// (unique_device.h).  ucnt == NULL: nothing to do.
 struct SortArgs {
   const int32_t* ucount = nullptr;   // device row count
-  const int32_t* ucnt = nullptr;     // NULL: nothing to do
+  int32_t* ucnt = nullptr;           // slots per row
   int32_t *rowptr = nullptr, *cursor = nullptr;
   int S = 0;
-  const int32_t* slot_row = nullptr;
+  const int32_t *slot_gid = nullptr, *uidx = nullptr;
+  int32_t* slot_row = nullptr;
   int32_t* sorted = nullptr;
 };
 SortArgs sort_args(tgnn_ctx* ctx, int S);
@@ -346,7 +349,7 @@ struct GatherArgs {
   int32_t* o_has;
   const float *time_w, *time_b;
   int n_slots, dm, dt, de;
-  SortArgs scan;            // scan.ucnt != NULL: block 0 of the launch runs the scan of the slot sort instead
+  SortArgs map;             // map.ucnt != NULL: the first blocks of the launch run the slot -> row map instead
 };
 void gather_rows(const GatherArgs& a, hipStream_t s);
 
@@ -375,7 +378,7 @@ void stage_x_rows(int R, int k, int dx, const float* x_root, const float* x_nbr,
 void gru_gates_fwd(const Dims& d, int n, const int* n_dev, const float* gi, const float* gh, const float* Hm,
                    const int32_t* has, float* gates, float* x_out, int ld_x, const float* stat, const int32_t* gid,
                    float* zero_buf, int zero_w, hipStream_t s,
-                   const SortArgs& fill = SortArgs());
+                   const SortArgs& scan = SortArgs());
 // Gradients through the query's time encoding Phi(0) = cos(time_b), from the column sums of dq [R, ld]:
 // g_b[c] += -sin(time_b[c]) sum_n colsum[n] wq[n, dx + c] and g_wq[n, dx + c] += colsum[n] cos(time_b[c]).
 // The attention backward kernel adds them to q_part [QPHI_BLOCKS, d_o]; time_grad_finish (given a QPhi)
@@ -401,7 +404,8 @@ void time_grad_finish(const TgRegion& r0, const TgRegion& r1, int dt, float* g_w
 // ---- k_attn.hip ---------------------------------------------------------------------
 // q of root r is q[qrow * ldq_ ...] with qrow = slot_row ? slot_row[r] : r.
 void attn_core_fwd(const Dims& d, int R, const float* q, int ldq_, const int32_t* slot_row, const float* KV, int ldkv,
-                   const int32_t* cnt, float* prob, float* Omat, int ldo, hipStream_t s);
+                   const int32_t* cnt, float* prob, float* Omat, int ldo, hipStream_t s,
+                   const SortArgs& fill = SortArgs());
 void attn_core_bwd(const Dims& d, int R, const float* q, int ldq_, const int32_t* slot_row, const float* KV, int ldkv,
                    const int32_t* cnt, const float* prob, const float* dOmat, int ldo, float* dq, float* dKV, float* q_part,
                    hipStream_t s);

@@ -1,6 +1,6 @@
 // Device-side pieces of the counting sort of slots by node row (see k_unique.hip).  The scan and the fill
-// are small and off the critical path of the forward pass, so they do not get launches of their own: the scan
-// is one extra block of the state-gather launch, the fill a few extra blocks of the GRU-gates launch.
+// are small, so they do not get launches of their own in the training step: the map rides in the state-gather
+// launch, the scan (one block) in the GRU-gates launch, the fill in the softmax-attention launch.
 #pragma once
 #include "tgnn_internal.h"
 
@@ -91,6 +91,18 @@ __device__ __forceinline__ void uniq_scan_block(const SortArgs& a) {
   }
   // the last wavefront ends at U (or owns nothing): its running sum is the total
   if ((int)threadIdx.x == (int)blockDim.x - 1) a.rowptr[U] = run;
+}
+
+// slot -> row, and the number of slots per row; `block` counts the blocks that do this work
+__device__ __forceinline__ void uniq_map_block(const SortArgs& a, int block) {
+  const int s = block * blockDim.x + threadIdx.x;
+  int row = -1;
+  if (s < a.S) {
+    const int gid = a.slot_gid[s];
+    if (gid >= 0) row = a.uidx[gid];
+    a.slot_row[s] = row;
+  }
+  wave_counted_add(a.ucnt, row, false);
 }
 
 // slot s goes to the next free position of its row's range; `block` counts the blocks that do this work
