@@ -33,7 +33,7 @@ STAGE_NAMES = ["prologue (pack weights, clear)", "(unused)", "roots + sample + d
                "per-node projections K, V, q, merge (MFMA)", "softmax attention + slot-sort fill", "merge layer (MFMA)",
                "decoder forward + loss", "decoder backward", "attention backward (MFMA + softmax)",
                "per-node gradient sums + node projections backward + GRU gates backward",
-               "all weight gradients (grouped MFMA GEMM)", "time-encoding gradients (two MFMA GEMMs in one launch + final sums)",
+               "all weight gradients (grouped MFMA GEMM)", "time-encoding gradients (two MFMA GEMMs in one launch)",
                "(unused)", "write-back scatter + SGD (one launch)"]
 STAGE_ASSEMBLE, STAGE_KV = 7, 8
 

@@ -52,7 +52,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, (TN <= 5
   add.src = q.add.src; add.index = q.add.index; add.ld = q.add.ld; add.row0 = q.add.row0;
   add.gate = q.add.gate; add.ld_gate = q.add.ld_gate;
   TimeGradOut tg;
-  tg.delta = q.tg.delta; tg.w = q.tg.w; tg.b = q.tg.b; tg.partial = q.tg.partial;
+  tg.delta = q.tg.delta; tg.w = q.tg.w; tg.b = q.tg.b; tg.g_w = q.tg.g_w; tg.g_b = q.tg.g_b;
   GruBwdOut gb;
   gb.gates = q.gb.gates; gb.Hm = q.gb.Hm; gb.has = q.gb.has; gb.dgi = q.gb.dgi; gb.dgh = q.gb.dgh;
   gb.dm = q.gb.dm; gb.ldh = q.gb.ldh; gb.ld3 = q.gb.ld3;
@@ -184,7 +184,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, (TN <= 5
     }
   }
 
-  if (tg.partial != nullptr) {
+  if (tg.g_w != nullptr) {
     // Time-encoding gradient epilogue: the tile is not stored.  Each lane multiplies its 4 rows x TN columns
     // by -sin(w_col delta_row + b_col) (the argument formed exactly as in the forward kernels), sums over its
     // rows, then over the four lane groups (shuffles) and the four waves (LDS).
@@ -224,9 +224,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, (TN <= 5
     for (int c = tid; c < BN; c += 256) {
       const int col = n0 + c;
       if (col < N) {
-        float* out = tg.partial + (size_t)row_tile * 2 * N;
-        out[col] = red[c] + red[BN + c] + red[2 * BN + c] + red[3 * BN + c];
-        out[N + col] = red[4 * BN + c] + red[5 * BN + c] + red[6 * BN + c] + red[7 * BN + c];
+        atomicAdd(tg.g_w + col, red[c] + red[BN + c] + red[2 * BN + c] + red[3 * BN + c]);
+        atomicAdd(tg.g_b + col, red[4 * BN + c] + red[5 * BN + c] + red[6 * BN + c] + red[7 * BN + c]);
       }
     }
     return;

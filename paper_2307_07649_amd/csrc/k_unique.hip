@@ -7,6 +7,7 @@
 // (power-law graphs) costs a few dozen atomic row updates instead of thousands.
 #include "tgnn_internal.h"
 #include "unique_device.h"
+#include "qphi_device.h"
 
 namespace tgnn {
 
@@ -30,9 +31,18 @@ __global__ __launch_bounds__(256) void seg_reduce_kernel(int R, int dO, const in
                                                          const int32_t* __restrict__ slot_row,
                                                          const float* __restrict__ dq, const float* __restrict__ dz,
                                                          int ldh, const float* __restrict__ dKV, int ldkv,
-                                                         float* __restrict__ dP, int ldp) {
+                                                         float* __restrict__ dP, int ldp, QPhi qphi) {
+  int block = blockIdx.x;
+  if (qphi.part != nullptr) {   // the first blocks are passengers: gradients through the query's Phi(0)
+    const int nq = qphi_blocks(qphi);
+    if (block < nq) {
+      qphi_block(qphi, block);
+      return;
+    }
+    block -= nq;
+  }
   const int lane = threadIdx.x & 63;
-  const int chunk = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int chunk = block * 4 + (threadIdx.x >> 6);
   const int total = rowptr[*ucount];
   const int p0 = chunk * SEG_CHUNK;
   if (p0 >= total) return;
@@ -105,18 +115,29 @@ __global__ __launch_bounds__(256) void seg_reduce_kernel(int R, int dO, const in
   }
 }
 
-void seg_reduce(tgnn_ctx* ctx, int R, int S, hipStream_t s) {
+void seg_reduce(tgnn_ctx* ctx, int R, int S, const QPhi& qphi, hipStream_t s) {
   const Dims& d = ctx->d;
   Ws& w = ctx->w;
   const int chunks = (S + SEG_CHUNK - 1) / SEG_CHUNK;
-  hipLaunchKernelGGL(seg_reduce_kernel, dim3((chunks + 3) / 4), dim3(256), 0, s, R, d.dO, w.ucount, w.rowptr, w.sorted,
-                     w.slot_row, w.dq, w.dz, d.ldh, w.dKV, d.ldkv, w.dP, d.ldp);
+  hipLaunchKernelGGL(seg_reduce_kernel, dim3((chunks + 3) / 4 + qphi_blocks(qphi)), dim3(256), 0, s, R, d.dO, w.ucount,
+                     w.rowptr, w.sorted, w.slot_row, w.dq, w.dz, d.ldh, w.dKV, d.ldkv, w.dP, d.ldp, qphi);
 }
 
 // slot = row: dP[r] = {0 || dq[r] | dz[r]} for roots, dP[R + j] = {dKV[j] || 0} for neighbour slots
-__global__ void slots_to_dp_kernel(int R, int RK, int dO, const float* __restrict__ dq, const float* __restrict__ dz,
-                                   int ldh, const float* __restrict__ dKV, int ldkv, float* __restrict__ dP, int ldp) {
-  const long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x;
+__global__ __launch_bounds__(256) void slots_to_dp_kernel(int R, int RK, int dO, const float* __restrict__ dq,
+                                                          const float* __restrict__ dz, int ldh,
+                                                          const float* __restrict__ dKV, int ldkv,
+                                                          float* __restrict__ dP, int ldp, QPhi qphi) {
+  int block = blockIdx.x;
+  if (qphi.part != nullptr) {   // the first blocks are passengers: gradients through the query's Phi(0)
+    const int nq = qphi_blocks(qphi);
+    if (block < nq) {
+      qphi_block(qphi, block);
+      return;
+    }
+    block -= nq;
+  }
+  const long long i = block * (long long)blockDim.x + threadIdx.x;
   if (i >= (long long)(R + RK) * ldp) return;
   const int row = (int)(i / ldp), c = (int)(i - (long long)row * ldp);
   float x = 0.f;
@@ -130,13 +151,13 @@ __global__ void slots_to_dp_kernel(int R, int RK, int dO, const float* __restric
   dP[i] = x;
 }
 
-void slots_to_dp(tgnn_ctx* ctx, int R, int RK, hipStream_t s) {
+void slots_to_dp(tgnn_ctx* ctx, int R, int RK, const QPhi& qphi, hipStream_t s) {
   const Dims& d = ctx->d;
   Ws& w = ctx->w;
   const long long total = (long long)(R + RK) * d.ldp;
   if (total <= 0) return;
-  hipLaunchKernelGGL(slots_to_dp_kernel, dim3((int)((total + 255) / 256)), dim3(256), 0, s, R, RK, d.dO, w.dq, w.dz, d.ldh,
-                     w.dKV, d.ldkv, w.dP, d.ldp);
+  hipLaunchKernelGGL(slots_to_dp_kernel, dim3((int)((total + 255) / 256) + qphi_blocks(qphi)), dim3(256), 0, s, R, RK, d.dO,
+                     w.dq, w.dz, d.ldh, w.dKV, d.ldkv, w.dP, d.ldp, qphi);
 }
 
 // debug: per-slot view of per-row data

@@ -97,8 +97,6 @@ static void layout(const Dims& d, Ws& w, Bump& b) {
   w.ds_row = b.take<float>(S * d.ldh);
   w.bs_dev = b.take<BatchSet>(1);
   w.sgd_dev = b.take<SgdSet>(1);
-  w.tg_keys = b.take<float>(((RK + NT_BM - 1) / NT_BM) * 2 * (size_t)d.dt);
-  w.tg_mail = b.take<float>(((S + NT_BM - 1) / NT_BM) * 2 * (size_t)d.dt);
   w.q_part = b.take<float>((size_t)QPHI_BLOCKS * d.dO);
   w.X = b.take<float>(S * d.ldx); w.Hm = b.take<float>(S * d.ldh);
   w.gi = b.take<float>(S * d.ld3); w.gh = b.take<float>(S * d.ld3);
@@ -214,22 +212,30 @@ static void attn_forward(tgnn_ctx* ctx, const tgnn_params* p, int R, int n_rows,
   if (tm) tm->end(11);
 }
 
-// From ws.dz (already masked by the merge ReLU) down to ws.dP (per-node projection gradients, not yet
-// reduced over slots), ws.dKV and ws.dq; queues the weight-gradient GEMMs of W_o (attention-output
-// columns) and of the {e | Phi} columns of W_k, W_v, and writes the time-encoding partial sums of the keys into
-// ws.tg_keys and adds the column sums of dq to ws.q_part, which the caller cleared (both consumed by
-// time_grad_finish).
-// The product that carries dKV on to the keys' time encoding, with the reduction to per-tile time-encoding
-// gradient sums (ws.tg_keys) as its epilogue.
-static NtProblem keys_phi_problem(tgnn_ctx* ctx, const tgnn_params* p, int RK) {
+// The query's time encoding: what turns ws.q_part (column sums of dq) into gradients of W_q and time_b.
+static QPhi qphi_args(tgnn_ctx* ctx, const tgnn_params* p, tgnn_params* g) {
+  const Dims& d = ctx->d; Ws& w = ctx->w;
+  QPhi q;
+  q.part = w.q_part; q.wq = p->wq; q.time_b = p->time_b; q.g_wq = g->wq; q.g_b = g->time_b;
+  q.dO = d.dO; q.dq_w = d.dq; q.dx = d.dx; q.dt = d.dt;
+  return q;
+}
+
+// The product that carries dKV on to the keys' time encoding, with the reduction to the gradients of the
+// time-encoding parameters as its epilogue.
+static NtProblem keys_phi_problem(tgnn_ctx* ctx, const tgnn_params* p, tgnn_params* g, int RK) {
   const Dims& d = ctx->d; Ws& w = ctx->w;
   TimeGradOut tg;
-  tg.delta = w.dtk; tg.w = p->time_w; tg.b = p->time_b; tg.partial = w.tg_keys;
+  tg.delta = w.dtk; tg.w = p->time_w; tg.b = p->time_b; tg.g_w = g->time_w; tg.g_b = g->time_b;
   return nt_problem(w.dKV, d.ldkv, w.WceT_phi, d.ldkv, nullptr, nullptr, d.ldt, RK, d.dt, d.ldkv, d.ldt, false, nullptr,
                     RowAdd(), tg);
 }
 
-// phi_now: launch that product here; otherwise the caller launches it (together with another one).
+// From ws.dz (already masked by the merge ReLU) down to ws.dKV and ws.dq; queues the weight-gradient GEMMs of
+// W_o (attention-output columns) and of the {e | Phi} columns of W_k, W_v, and adds the column sums of dq to
+// ws.q_part, which the caller cleared (consumed by qphi_block in a later launch).
+// phi_now: launch the product onto the keys' time encoding here; otherwise the caller launches it (together
+// with another one).
 static void attn_backward(tgnn_ctx* ctx, tgnn_params* g, const tgnn_params* p, int R, const int32_t* slot_row,
                           const int32_t* cnt, TnBatch& tn, Side& side, bool phi_now, hipStream_t s) {
   const Dims& d = ctx->d; Ws& w = ctx->w;
@@ -249,7 +255,7 @@ static void attn_backward(tgnn_ctx* ctx, tgnn_params* g, const tgnn_params* p, i
     tn.launch(side.c->side);
   }
   if (phi_now) {
-    const NtProblem pr = keys_phi_problem(ctx, p, RK);
+    const NtProblem pr = keys_phi_problem(ctx, p, g, RK);
     gemm_nt_group(&pr, 1, s);
   }
 }
@@ -555,14 +561,7 @@ int32_t tgnn_temporal_attn_bwd(tgnn_ctx* ctx, const tgnn_params* p, int32_t n_ro
   Side side{ctx, s, false};
   const int RK = n_roots * d.k;
   attn_backward(ctx, grads, p, n_roots, nullptr, w.cnt, tn, side, true, s);
-  {
-    QPhi qp;
-    qp.part = w.q_part; qp.wq = p->wq; qp.time_b = p->time_b; qp.g_wq = grads->wq; qp.dO = d.dO; qp.dq_w = d.dq; qp.dx = d.dx;
-    TgRegion keys;
-    keys.partial = w.tg_keys; keys.rows = RK;
-    time_grad_finish(keys, TgRegion(), d.dt, grads->time_w, grads->time_b, &qp, s);
-  }
-  slots_to_dp(ctx, n_roots, RK, s);
+  slots_to_dp(ctx, n_roots, RK, qphi_args(ctx, p, grads), s);
   node_proj_backward(ctx, grads, n_roots + RK, nullptr, tn, false, s);
   tn.launch(s);
   attn_dx_out(n_roots, RK, d.dm, w.ds_row, d.ldh, d_x_root, d_x_nbr, s);
@@ -821,7 +820,8 @@ static int enqueue_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
   attn_backward(ctx, grads, p, R, w.slot_row, w.cnt, tn, side, false, s);
   tm.end(14);
   tm.begin(15);
-  seg_reduce(ctx, R, S, s);   // per-row sum of the slot gradients reaching the per-node projections
+  // per-row sum of the slot gradients reaching the per-node projections (the query's Phi(0) gradients ride along)
+  seg_reduce(ctx, R, S, qphi_args(ctx, p, grads), s);
   node_proj_backward(ctx, grads, U, w.ucount, tn, true, s);
   tm.end(15);
   tn.add(w.dgi, d.ld3, w.X, d.ldx, U, 3 * d.dm, d.d_in, single_out(grads->gru_wih, d.d_in, grads->gru_bih), w.ucount);
@@ -832,19 +832,11 @@ static int enqueue_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
   tm.begin(17);
   {  // gradients reaching the time encodings of the keys and of the mails, each reduced inside its GEMM: one launch
     TimeGradOut tg;
-    tg.delta = w.delta; tg.w = p->time_w; tg.b = p->time_b; tg.partial = w.tg_mail;
+    tg.delta = w.delta; tg.w = p->time_w; tg.b = p->time_b; tg.g_w = grads->time_w; tg.g_b = grads->time_b;
     const NtProblem pr[2] = {
-        keys_phi_problem(ctx, p, RK),
+        keys_phi_problem(ctx, p, grads, RK),
         nt_problem(w.dgi, d.ld3, w.WihT_phi, d.ld3, nullptr, nullptr, d.ldt, U, d.dt, d.ld3, d.ldt, false, w.ucount, RowAdd(), tg)};
     gemm_nt_group(pr, 2, s);
-  }
-  {
-    QPhi qp;
-    qp.part = w.q_part; qp.wq = p->wq; qp.time_b = p->time_b; qp.g_wq = grads->wq; qp.dO = d.dO; qp.dq_w = d.dq; qp.dx = d.dx;
-    TgRegion keys, mail;
-    keys.partial = w.tg_keys; keys.rows = RK;
-    mail.partial = w.tg_mail; mail.rows = U; mail.rows_dev = w.ucount;
-    time_grad_finish(keys, mail, d.dt, grads->time_w, grads->time_b, &qp, s);
   }
   tm.end(17);
   side.join();   // the weight gradients started beside the chain

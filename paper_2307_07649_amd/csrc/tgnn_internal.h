@@ -57,7 +57,6 @@ struct Ws {
   float* ds_row;                               // [maxS, ldh] gradient reaching s' per row
   BatchSet* bs_dev;                            // device copy of the step's batch descriptors
   struct SgdSet* sgd_dev;                      // device copy of the parameter/gradient pointer table
-  float *tg_keys, *tg_mail;                    // [ceil(RK/64), 2, dt], [ceil(S/64), 2, dt] per-tile time-encoding gradient sums
   float* q_part;                               // [QPHI_BLOCKS, d_o] column sums of dq per block of roots
   // GRU
   float *X, *Hm, *gi, *gh, *gates;             // [S,ldx] [S,ldh] [S,ld3] [S,ld3] [S,4*ldh]
@@ -159,14 +158,14 @@ struct RowAdd {
   int ld_gate = 0;
 };
 // TimeGradOut (optional): C is not written.  Instead C[m, n] is taken as the gradient reaching the time encoding
-// Phi(delta[m])_n = cos(w[n] delta[m] + b[n]) and each 64-row tile writes the column sums of its part of
+// Phi(delta[m])_n = cos(w[n] delta[m] + b[n]) and each 64-row tile adds the column sums of its part of
 //   dL/dw[n] = sum_m C[m, n] (-sin(w[n] delta[m] + b[n])) delta[m],   dL/db[n] = the same without the factor delta[m]
-// to partial[row tile, {w, b}, N]; time_grad_finish adds the tiles up.  Row tiles beyond the rows are not written.
+// to g_w[n] / g_b[n] (one float atomic each per tile and column).
 constexpr int NT_BM = 64;
 struct TimeGradOut {
   const double* delta = nullptr;
   const float *w = nullptr, *b = nullptr;
-  float* partial = nullptr;
+  float *g_w = nullptr, *g_b = nullptr;   // g_w != NULL switches the epilogue on
 };
 // GruBwdOut (optional): C is not written.  C[m, n] (n < d_m) is taken as the gradient reaching s' of node row m
 // and turned into the gradients of the GRU gate pre-activations (Eq. 3), written to dgi / dgh [M, ld3] as
@@ -309,6 +308,18 @@ void sample_recent(const Dims& d, const tgnn_graph* g, const int32_t* node, cons
                    int32_t* out_nbr, int32_t* out_eid, double* out_ts, int32_t* out_cnt, hipStream_t s);
 
 // ---- k_unique.hip -------------------------------------------------------------------
+// Gradients through the query's time encoding Phi(0) = cos(time_b), from the column sums of dq [R, ld]:
+// g_b[c] += -sin(time_b[c]) sum_n colsum[n] wq[n, dx + c] and g_wq[n, dx + c] += colsum[n] cos(time_b[c]).
+// The attention backward kernel adds them to q_part [QPHI_BLOCKS, d_o]; qphi_block (qphi_device.h), run as the
+// first qphi_blocks() blocks of a later 256-thread launch, turns them into the two gradients.
+constexpr int QPHI_BLOCKS = 64;
+struct QPhi {
+  const float* part = nullptr;   // NULL: no query part
+  const float *wq = nullptr, *time_b = nullptr;
+  float *g_wq = nullptr, *g_b = nullptr;
+  int dO = 0, dq_w = 0, dx = 0, dt = 0;
+};
+__host__ __device__ inline int qphi_blocks(const QPhi& q) { return q.part != nullptr ? (q.dO * q.dt + 255) / 256 : 0; }
 // Slot -> row map and the row-sorted slot list (the latter needed by seg_reduce only).  Three small passes:
 // map (slot_row[s] = uidx[slot_gid[s]], slots counted per row), an exclusive scan of the counts, and the fill
 // (every slot takes the next free position of its row).  None gets a launch of its own in the training
@@ -325,9 +336,9 @@ struct SortArgs {
 };
 SortArgs sort_args(tgnn_ctx* ctx, int S);
 // dP[row] += {dKV[slot] | 0} of the row's neighbour slots and {0 | dq[r] | dz[r]} of its root slots
-void seg_reduce(tgnn_ctx* ctx, int R, int S, hipStream_t s);
+void seg_reduce(tgnn_ctx* ctx, int R, int S, const QPhi& qphi, hipStream_t s);   // qphi: see QPhi (rides along)
 // the same with slot = row (standalone attention call): plain stores, every row of dP written
-void slots_to_dp(tgnn_ctx* ctx, int R, int RK, hipStream_t s);
+void slots_to_dp(tgnn_ctx* ctx, int R, int RK, const QPhi& qphi, hipStream_t s);
 void expand_rows(tgnn_ctx* ctx, int S, const float* src, int ld, const double* src_d, float* dst, double* dst_d,
                  hipStream_t s);
 
@@ -379,28 +390,6 @@ void gru_gates_fwd(const Dims& d, int n, const int* n_dev, const float* gi, cons
                    const int32_t* has, float* gates, float* x_out, int ld_x, const float* stat, const int32_t* gid,
                    float* zero_buf, int zero_w, hipStream_t s,
                    const SortArgs& scan = SortArgs());
-// Gradients through the query's time encoding Phi(0) = cos(time_b), from the column sums of dq [R, ld]:
-// g_b[c] += -sin(time_b[c]) sum_n colsum[n] wq[n, dx + c] and g_wq[n, dx + c] += colsum[n] cos(time_b[c]).
-// The attention backward kernel adds them to q_part [QPHI_BLOCKS, d_o]; time_grad_finish (given a QPhi)
-// turns them into the two gradients.
-constexpr int QPHI_BLOCKS = 64;
-struct QPhi {
-  const float* part = nullptr;   // NULL: no query part
-  const float *wq = nullptr, *time_b = nullptr;
-  float* g_wq = nullptr;
-  int dO = 0, dq_w = 0, dx = 0;
-};
-// Adds the per-tile partial sums written by gemm_nt (TimeGradOut) to g_w / g_b: up to two regions of
-// [tiles, 2, dt]; a region's tile count is ceil(min(rows, *rows_dev) / NT_BM) (rows_dev may be NULL).  With a QPhi
-// it also finishes the gradients through the query's Phi(0).
-struct TgRegion {
-  const float* partial = nullptr;
-  int rows = 0;
-  const int* rows_dev = nullptr;
-};
-void time_grad_finish(const TgRegion& r0, const TgRegion& r1, int dt, float* g_w, float* g_b, const QPhi* q,
-                      hipStream_t s);
-
 // ---- k_attn.hip ---------------------------------------------------------------------
 // q of root r is q[qrow * ldq_ ...] with qrow = slot_row ? slot_row[r] : r.
 void attn_core_fwd(const Dims& d, int R, const float* q, int ldq_, const int32_t* slot_row, const float* KV, int ldkv,
