@@ -34,8 +34,18 @@ STAGE_NAMES = ["prologue (pack weights, clear)", "(unused)", "roots + sample + d
                "decoder forward + loss", "decoder backward", "attention backward (MFMA + softmax)",
                "per-node gradient sums + node projections backward + GRU gates backward",
                "all weight gradients (grouped MFMA GEMM)", "time-encoding gradients (two MFMA GEMMs in one launch)",
-               "(unused)", "write-back scatter + SGD (one launch)"]
-STAGE_ASSEMBLE, STAGE_KV = 7, 8
+               "empty event bracket", "write-back scatter + SGD (one launch)"]
+STAGE_ASSEMBLE, STAGE_KV, STAGE_WGRAD, STAGE_EMPTY = 7, 8, 16, 18
+
+
+def flops_wgrad(d, n_roots, n_rows):
+    """Executed flops of the grouped weight-gradient launch, G += D^T A per problem (2 M N K each; bias gradients
+    are one more column): decoder hidden layer and merge layer over the roots, the {e | Phi} columns of W_k / W_v over
+    the neighbour slots, the node columns of W_k, W_v, W_q, W_o and the two GRU matrices over the distinct node rows."""
+    R, RK, U, dO = n_roots, n_roots * d.k, n_rows, d.d_out
+    macs = (R * 2 * dO * (dO + 1) + R * dO * dO + RK * 2 * dO * (d.d_edge + d.d_time)
+            + 2 * U * 2 * dO * (d.d_x + 1) + U * 3 * d.d_mem * (d.d_in + 1) + U * 3 * d.d_mem * (d.d_mem + 1))
+    return 2.0 * macs
 
 
 def flops_kv(d, n_roots):
@@ -170,7 +180,7 @@ def main():
     # a stream of its own: the library replays a captured HIP graph there (the NULL stream cannot be captured)
     torch.cuda.synchronize()
     torch.cuda.set_stream(torch.cuda.Stream())
-    roof_mask = 0 if args.no_stage_events else (1 << STAGE_ASSEMBLE) | (1 << STAGE_KV)
+    roof_mask = 0 if args.no_stage_events else (1 << STAGE_ASSEMBLE) | (1 << STAGE_KV) | (1 << STAGE_EMPTY)
     every = max(1, args.event_every)
     ctx.tgnn_profile_enable(roof_mask)
     ctx.tgnn_profile_every(2)             # warm up both launch modes
@@ -194,26 +204,43 @@ def main():
     final_loss = float(loss[0].item())
     n_g, ms_g = ctx.tgnn_profile_read(STAGE_ASSEMBLE)
     n_m, ms_m = ctx.tgnn_profile_read(STAGE_KV)
+    n_e, ms_e = ctx.tgnn_profile_read(STAGE_EMPTY)
     ctx.tgnn_profile_enable(0)
     ctx.tgnn_profile_every(1)
+    # A pair of HIP event records with nothing in between is itself several microseconds apart on this stack (the
+    # step records such an empty bracket, stage 18, on the same steps).  It is reported, not subtracted: part of it
+    # overlaps with a kernel's launch, so the difference would overstate the kernels.  The brackets are therefore
+    # upper bounds of the launch durations (rocprofv3's kernel trace shows about 3 us less).
+    bracket_us = ms_e / n_e * 1e3 if n_e else None
+    kv_us = ms_m / n_m * 1e3 if n_m else None
+    asm_us = ms_g / n_g * 1e3 if n_g else None
 
-    # per-stage breakdown from a separate, untimed pass with every stage bracketed by events
+    # per-stage breakdown from a separate, untimed pass with every stage bracketed by events; the number of distinct
+    # node rows of each of these steps is read back for the flops of the weight-gradient launch
     n_prof = min(args.steps, 64)
     ctx.tgnn_profile_enable((1 << len(STAGE_NAMES)) - 1)
-    for s in range(args.warmup + args.steps, args.warmup + args.steps + n_prof):
-        run_step(s)
+    rows_step = torch.zeros(n_prof, dtype=torch.int32, device="cuda")
+    ev_prof = 0
+    for i, s in enumerate(range(args.warmup + args.steps, args.warmup + args.steps + n_prof)):
+        ev_prof += run_step(s)
+        ctx.tgnn_debug_read(8, rows_step[i:i + 1])
     torch.cuda.synchronize()
     stages = {}
     for i, nm in enumerate(STAGE_NAMES):
         c, ms = ctx.tgnn_profile_read(i)
         if c:
             stages[nm] = round(ms / c * 1e3, 2)
+    n_w, ms_w = ctx.tgnn_profile_read(STAGE_WGRAD)
+    n_e2, ms_e2 = ctx.tgnn_profile_read(STAGE_EMPTY)
     ctx.tgnn_profile_enable(0)
+    rows_avg = float(rows_step.float().mean().item())
+    wgrad_us = ms_w / n_w * 1e3 if n_w else None
+    wgrad_tflops = flops_wgrad(d, 3 * ev_prof / n_prof, rows_avg) / (wgrad_us * 1e-6) / 1e12 if n_w else None
 
     ev_step = ev / args.steps
     R_avg = 3 * (ev_timed_launches / n_timed_launches if n_timed_launches else ev_step)   # roots per timed launch
-    kv_tflops = flops_kv(d, R_avg) / (ms_m / n_m * 1e-3) / 1e12 if n_m else None
-    asm_gbs = assemble_bytes(d, R_avg) / (ms_g / n_g * 1e-3) / 1e9 if n_g else None
+    kv_tflops = flops_kv(d, R_avg) / (kv_us * 1e-6) / 1e12 if n_m else None
+    asm_gbs = assemble_bytes(d, R_avg) / (asm_us * 1e-6) / 1e9 if n_g else None
     out = {
         "metric": "training events/sec (fwd+bwd+memory update) at 1 GPU",
         "value": ev / dt, "unit": "events/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -227,18 +254,27 @@ def main():
                                                 "neighbour slots (fp32 MFMA 16x16x4), the longest forward kernel",
                      "achieved": kv_tflops, "peak": PEAK_MFMA_F32_TFLOPS, "unit": "TFLOP/s",
                      "frac": kv_tflops / PEAK_MFMA_F32_TFLOPS if kv_tflops else None,
-                     "avg_launch_us": ms_m / n_m * 1e3 if n_m else None,
+                     "avg_launch_us": kv_us, "empty_event_bracket_us": bracket_us,
                      "traffic": MEASURED_TRAFFIC_BYTES.get(name, {}).get("kv_projection")},
+        "weight_gradients": {"bound": "mfma", "kernel": "gemm_tn_kernel: all weight gradients of the step in one grouped "
+                                                        "launch (fp32 MFMA 16x16x4), the longest kernel of the step; timed "
+                                                        "with HIP events in the untimed per-stage pass",
+                             "achieved": wgrad_tflops, "peak": PEAK_MFMA_F32_TFLOPS, "unit": "TFLOP/s",
+                             "frac": wgrad_tflops / PEAK_MFMA_F32_TFLOPS if wgrad_tflops else None,
+                             "avg_launch_us": wgrad_us, "empty_event_bracket_us": ms_e2 / n_e2 * 1e3 if n_e2 else None,
+                             "distinct_node_rows_per_step": rows_avg},
         "gather": {"bound": "hbm", "kernel": "assemble_ce_kernel: edge-feature row gather + time encoding into the "
                                              "per-slot key/value inputs",
                    "achieved": asm_gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                    "frac": asm_gbs / PEAK_HBM_GBS if asm_gbs else None,
-                   "avg_launch_us": ms_g / n_g * 1e3 if n_g else None,
+                   "avg_launch_us": asm_us, "empty_event_bracket_us": bracket_us,
                    "traffic": MEASURED_TRAFFIC_BYTES.get(name, {}).get("assemble_ce")},
         "step_model": {"flops_per_step_per_slot_updt": step_flops(d, ev_step), "bytes_per_step": step_bytes(d, ev_step),
                        "note": "flops counted with UPDT per slot as the method states it; the library evaluates "
                                "UPDT once per distinct node, so executed flops are lower"},
         "stages_us": stages,
+        "stages_us_note": "HIP-event brackets from an untimed pass launched kernel by kernel; every figure includes the "
+                          "cost of an empty bracket (listed as its own entry)",
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(P)

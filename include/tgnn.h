@@ -215,7 +215,8 @@ int32_t tgnn_zero_params(tgnn_ctx* ctx, tgnn_params* g, void* stream);
  *  15 per-node gradient sums (with the gradients through the query's Phi(0)) + node projections backward + GRU gates
  *  backward
  *  16 all weight gradients (one grouped MFMA GEMM)   17 time-encoding gradients (GEMMs onto Phi of keys and mails
- *  with the reduction in their epilogue, one launch)   18 (unused)   19 write-back scatter + SGD (one launch)
+ *  with the reduction in their epilogue, one launch)   18 nothing (two event records back to back: the
+ *  cost of a bracket by itself)   19 write-back scatter + SGD (one launch)
  * tgnn_profile_enable: time the stages whose bit is set in `stage_mask` in every following tgnn_train_step
  * (0 = off); each timed stage costs two event records per step.  At most 4096 steps are kept per stage;
  * enabling resets the record.  tgnn_profile_read: synchronises the recorded events and returns the number
@@ -234,7 +235,8 @@ int32_t tgnn_debug_copy(void* dst, const void* src, int64_t n_bytes, void* strea
 
 /* Debug/parity access to what the last tgnn_train_step left in the workspace.  `what`:
  * 0 nbr [R,k] i32, 1 eid [R,k] i32, 2 nts [R,k] f64, 3 cnt [R] i32, 4 s_new [R(1+k), d_m] f32,
- * 5 tau [R(1+k)] f64, 6 z [R, d_o] f32, 7 decoder hidden layer [2 sum n, d_o] f32.  Copies n_bytes (device to device) into dst on `stream`. */
+ * 5 tau [R(1+k)] f64, 6 z [R, d_o] f32, 7 decoder hidden layer [2 sum n, d_o] f32, 8 the number of distinct
+ * (replica, node) rows of the step [1] i32.  Copies n_bytes (device to device) into dst on `stream`. */
 int32_t tgnn_debug_read(tgnn_ctx* ctx, int32_t what, void* dst, int64_t n_bytes, void* stream);
 
 #ifdef __cplusplus

@@ -11,12 +11,16 @@ struct AttnShape {
   int R, k, H, dO, dh, ldq, ldkv, ldo;
 };
 
-constexpr int ROWS_IN_FLIGHT = 5;   // neighbour rows whose loads are issued together
+constexpr int ROWS_IN_FLIGHT = 10;  // neighbour rows whose loads are issued together (k = 10: all of them)
 constexpr int MAX_E = 4;            // d_o <= 256: columns lane, lane + 64, lane + 128, lane + 192
 
 // LDS floats per wave
 __host__ __device__ inline int attn_lds_floats(int k, int H, int dO) { return dO + k * (dO + 1) + 2 * H * k; }
 
+// A wavefront has few others on its SIMD to hide behind, so every dependent global load costs a full memory
+// latency.  Both kernels therefore issue everything they will need of the first ROWS_IN_FLIGHT neighbours
+// (with k = 10 that is everything) as one burst right after the two index loads: the query (or dO) row, the
+// key rows and the value rows; rows beyond the first batch are fetched batch by batch where they are used.
 __global__ __launch_bounds__(256) void attn_fwd_kernel(AttnShape sh, const float* __restrict__ q,
                                                        const int32_t* __restrict__ slot_row,
                                                        const float* __restrict__ KV,
@@ -39,6 +43,7 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(AttnShape sh, const float
   float* sK = sq + sh.dO;
   float* sa = sK + sh.k * (sh.dO + 1);
   const int c = cnt[r];
+  const size_t qrow = slot_row != nullptr ? (size_t)slot_row[r] : (size_t)r;   // q is stored per distinct node
   const int HK = sh.H * sh.k;
   float* pr = prob + (size_t)r * HK;
   float* out = Omat + (size_t)r * sh.ldo;
@@ -48,19 +53,48 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(AttnShape sh, const float
     return;
   }
   const float scale = 1.0f / sqrtf((float)c);
-  const size_t qrow = slot_row != nullptr ? (size_t)slot_row[r] : (size_t)r;   // q is stored per distinct node
-  for (int e = lane; e < sh.dO; e += 64) sq[e] = q[qrow * sh.ldq + e];
-  // key rows: the loads of ROWS_IN_FLIGHT rows are issued before any is stored (a wave has few neighbours in
-  // flight on its SIMD, so serialised row loads would each cost a full memory latency)
-  for (int j0 = 0; j0 < c; j0 += ROWS_IN_FLIGHT) {
-    float kreg[ROWS_IN_FLIGHT][MAX_E];
+  // the burst: q, and the key and value rows of the first batch
+  float qreg[MAX_E], kreg[ROWS_IN_FLIGHT][MAX_E], vreg[ROWS_IN_FLIGHT][MAX_E];
+#pragma unroll
+  for (int u = 0; u < MAX_E; ++u) {
+    const int e = lane + 64 * u;
+    qreg[u] = e < sh.dO ? q[qrow * sh.ldq + e] : 0.f;
+  }
+#pragma unroll
+  for (int jj = 0; jj < ROWS_IN_FLIGHT; ++jj) {
+    const float* krow = KV + ((size_t)r * sh.k + min(jj, c - 1)) * sh.ldkv;
+#pragma unroll
+    for (int u = 0; u < MAX_E; ++u) {
+      const int e = lane + 64 * u;
+      kreg[jj][u] = e < sh.dO ? krow[e] : 0.f;
+      vreg[jj][u] = e < sh.dO ? krow[sh.dO + e] : 0.f;
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < MAX_E; ++u) {
+    const int e = lane + 64 * u;
+    if (e < sh.dO) sq[e] = qreg[u];
+  }
+#pragma unroll
+  for (int jj = 0; jj < ROWS_IN_FLIGHT; ++jj) {
+    if (jj < c) {
+#pragma unroll
+      for (int u = 0; u < MAX_E; ++u) {
+        const int e = lane + 64 * u;
+        if (e < sh.dO) sK[jj * (sh.dO + 1) + e] = kreg[jj][u];
+      }
+    }
+  }
+  // key rows beyond the first batch
+  for (int j0 = ROWS_IN_FLIGHT; j0 < c; j0 += ROWS_IN_FLIGHT) {
+    float k2[ROWS_IN_FLIGHT][MAX_E];
 #pragma unroll
     for (int jj = 0; jj < ROWS_IN_FLIGHT; ++jj) {
       const float* krow = KV + ((size_t)r * sh.k + min(j0 + jj, c - 1)) * sh.ldkv;
 #pragma unroll
       for (int u = 0; u < MAX_E; ++u) {
         const int e = lane + 64 * u;
-        kreg[jj][u] = e < sh.dO ? krow[e] : 0.f;
+        k2[jj][u] = e < sh.dO ? krow[e] : 0.f;
       }
     }
 #pragma unroll
@@ -69,7 +103,7 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(AttnShape sh, const float
 #pragma unroll
         for (int u = 0; u < MAX_E; ++u) {
           const int e = lane + 64 * u;
-          if (e < sh.dO) sK[(j0 + jj) * (sh.dO + 1) + e] = kreg[jj][u];
+          if (e < sh.dO) sK[(j0 + jj) * (sh.dO + 1) + e] = k2[jj][u];
         }
       }
     }
@@ -105,19 +139,41 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(AttnShape sh, const float
   }
   __builtin_amdgcn_wave_barrier();
   __builtin_amdgcn_s_waitcnt(0xc07f);
-  for (int e = lane; e < sh.dO; e += 64) {
-    const int h = e / sh.dh;
-    float o = 0.f;
-    for (int j0 = 0; j0 < c; j0 += ROWS_IN_FLIGHT) {
-      float vreg[ROWS_IN_FLIGHT];
+  // weighted sums of the value rows: the first batch is in registers
+  float o[MAX_E];
 #pragma unroll
-      for (int jj = 0; jj < ROWS_IN_FLIGHT; ++jj)
-        vreg[jj] = KV[((size_t)r * sh.k + min(j0 + jj, c - 1)) * sh.ldkv + sh.dO + e];
+  for (int u = 0; u < MAX_E; ++u) {
+    const int e = lane + 64 * u;
+    const int h = min(e, sh.dO - 1) / sh.dh;
+    float acc = 0.f;
 #pragma unroll
-      for (int jj = 0; jj < ROWS_IN_FLIGHT; ++jj)
-        if (j0 + jj < c) o += sa[HK + h * sh.k + j0 + jj] * vreg[jj];
+    for (int jj = 0; jj < ROWS_IN_FLIGHT; ++jj)
+      if (jj < c) acc += sa[HK + h * sh.k + jj] * vreg[jj][u];
+    o[u] = acc;
+  }
+  for (int j0 = ROWS_IN_FLIGHT; j0 < c; j0 += ROWS_IN_FLIGHT) {
+    float v2[ROWS_IN_FLIGHT][MAX_E];
+#pragma unroll
+    for (int jj = 0; jj < ROWS_IN_FLIGHT; ++jj) {
+      const float* vrow = KV + ((size_t)r * sh.k + min(j0 + jj, c - 1)) * sh.ldkv + sh.dO;
+#pragma unroll
+      for (int u = 0; u < MAX_E; ++u) {
+        const int e = lane + 64 * u;
+        v2[jj][u] = e < sh.dO ? vrow[e] : 0.f;
+      }
     }
-    out[e] = o;
+#pragma unroll
+    for (int u = 0; u < MAX_E; ++u) {
+      const int h = min(lane + 64 * u, sh.dO - 1) / sh.dh;
+#pragma unroll
+      for (int jj = 0; jj < ROWS_IN_FLIGHT; ++jj)
+        if (j0 + jj < c) o[u] += sa[HK + h * sh.k + j0 + jj] * v2[jj][u];
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < MAX_E; ++u) {
+    const int e = lane + 64 * u;
+    if (e < sh.dO) out[e] = o[u];
   }
 }
 
@@ -136,6 +192,7 @@ __global__ __launch_bounds__(256) void attn_bwd_kernel(AttnShape sh, const float
   float* sV = sdo + sh.dO;
   float* sa = sV + sh.k * (sh.dO + 1);  // [0,HK): prob, [HK,2HK): d(score)
   const int c = cnt[r];
+  const size_t qrow = slot_row != nullptr ? (size_t)slot_row[r] : (size_t)r;
   const int HK = sh.H * sh.k;
   // rows of absent neighbours get zero gradients
   for (int j = c; j < sh.k; ++j) {
@@ -147,17 +204,50 @@ __global__ __launch_bounds__(256) void attn_bwd_kernel(AttnShape sh, const float
     return;
   }
   const float scale = 1.0f / sqrtf((float)c);
-  const size_t qrow = slot_row != nullptr ? (size_t)slot_row[r] : (size_t)r;
-  for (int e = lane; e < sh.dO; e += 64) sdo[e] = dOmat[(size_t)r * sh.ldo + e];
-  for (int j0 = 0; j0 < c; j0 += ROWS_IN_FLIGHT) {
-    float vreg[ROWS_IN_FLIGHT][MAX_E];
+  // the burst: dO and q rows, the softmax weights, and the key and value rows of the first batch
+  float doreg[MAX_E], qreg[MAX_E], kreg[ROWS_IN_FLIGHT][MAX_E], vreg[ROWS_IN_FLIGHT][MAX_E];
+#pragma unroll
+  for (int u = 0; u < MAX_E; ++u) {
+    const int e = lane + 64 * u;
+    doreg[u] = e < sh.dO ? dOmat[(size_t)r * sh.ldo + e] : 0.f;
+    qreg[u] = e < sh.dO ? q[qrow * sh.ldq + e] : 0.f;
+  }
+  for (int p = lane; p < HK; p += 64) sa[p] = prob[(size_t)r * HK + p];
+#pragma unroll
+  for (int jj = 0; jj < ROWS_IN_FLIGHT; ++jj) {
+    const float* krow = KV + ((size_t)r * sh.k + min(jj, c - 1)) * sh.ldkv;
+#pragma unroll
+    for (int u = 0; u < MAX_E; ++u) {
+      const int e = lane + 64 * u;
+      kreg[jj][u] = e < sh.dO ? krow[e] : 0.f;
+      vreg[jj][u] = e < sh.dO ? krow[sh.dO + e] : 0.f;
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < MAX_E; ++u) {
+    const int e = lane + 64 * u;
+    if (e < sh.dO) sdo[e] = doreg[u];
+  }
+#pragma unroll
+  for (int jj = 0; jj < ROWS_IN_FLIGHT; ++jj) {
+    if (jj < c) {
+#pragma unroll
+      for (int u = 0; u < MAX_E; ++u) {
+        const int e = lane + 64 * u;
+        if (e < sh.dO) sV[jj * (sh.dO + 1) + e] = vreg[jj][u];
+      }
+    }
+  }
+  // value rows beyond the first batch
+  for (int j0 = ROWS_IN_FLIGHT; j0 < c; j0 += ROWS_IN_FLIGHT) {
+    float v2[ROWS_IN_FLIGHT][MAX_E];
 #pragma unroll
     for (int jj = 0; jj < ROWS_IN_FLIGHT; ++jj) {
       const float* vrow = KV + ((size_t)r * sh.k + min(j0 + jj, c - 1)) * sh.ldkv + sh.dO;
 #pragma unroll
       for (int u = 0; u < MAX_E; ++u) {
         const int e = lane + 64 * u;
-        vreg[jj][u] = e < sh.dO ? vrow[e] : 0.f;
+        v2[jj][u] = e < sh.dO ? vrow[e] : 0.f;
       }
     }
 #pragma unroll
@@ -166,12 +256,11 @@ __global__ __launch_bounds__(256) void attn_bwd_kernel(AttnShape sh, const float
 #pragma unroll
         for (int u = 0; u < MAX_E; ++u) {
           const int e = lane + 64 * u;
-          if (e < sh.dO) sV[(j0 + jj) * (sh.dO + 1) + e] = vreg[jj][u];
+          if (e < sh.dO) sV[(j0 + jj) * (sh.dO + 1) + e] = v2[jj][u];
         }
       }
     }
   }
-  for (int p = lane; p < HK; p += 64) sa[p] = prob[(size_t)r * HK + p];
   __builtin_amdgcn_wave_barrier();
   __builtin_amdgcn_s_waitcnt(0xc07f);
   for (int p = lane; p < HK; p += 64) {
@@ -204,29 +293,61 @@ __global__ __launch_bounds__(256) void attn_bwd_kernel(AttnShape sh, const float
   for (int p = lane; p < HK; p += 64, ++it) sa[HK + p] = da_keep[it];
   __builtin_amdgcn_wave_barrier();
   __builtin_amdgcn_s_waitcnt(0xc07f);
-  for (int e = lane; e < sh.dO; e += 64) {
-    const int h = e / sh.dh;
-    const float qe = q[qrow * sh.ldq + e], doe = sdo[e];
-    float dqe = 0.f;
-    for (int j0 = 0; j0 < c; j0 += ROWS_IN_FLIGHT) {
-      float kreg[ROWS_IN_FLIGHT];
+  // dq, and the gradients of the key and value rows: the first batch of key rows is in registers
+  float dqe[MAX_E];
 #pragma unroll
-      for (int jj = 0; jj < ROWS_IN_FLIGHT; ++jj) kreg[jj] = KV[((size_t)r * sh.k + min(j0 + jj, c - 1)) * sh.ldkv + e];
+  for (int u = 0; u < MAX_E; ++u) {
+    const int e = lane + 64 * u;
+    const int h = min(e, sh.dO - 1) / sh.dh;
+    float acc = 0.f;
+#pragma unroll
+    for (int jj = 0; jj < ROWS_IN_FLIGHT; ++jj) {
+      if (jj < c && e < sh.dO) {
+        const size_t row = ((size_t)r * sh.k + jj) * sh.ldkv;
+        const float da = sa[HK + h * sh.k + jj];
+        acc += da * kreg[jj][u];
+        dKV[row + e] = da * qreg[u];
+        dKV[row + sh.dO + e] = sa[h * sh.k + jj] * doreg[u];
+      }
+    }
+    dqe[u] = acc;
+  }
+  for (int j0 = ROWS_IN_FLIGHT; j0 < c; j0 += ROWS_IN_FLIGHT) {
+    float k2[ROWS_IN_FLIGHT][MAX_E];
+#pragma unroll
+    for (int jj = 0; jj < ROWS_IN_FLIGHT; ++jj) {
+      const float* krow = KV + ((size_t)r * sh.k + min(j0 + jj, c - 1)) * sh.ldkv;
+#pragma unroll
+      for (int u = 0; u < MAX_E; ++u) {
+        const int e = lane + 64 * u;
+        k2[jj][u] = e < sh.dO ? krow[e] : 0.f;
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < MAX_E; ++u) {
+      const int e = lane + 64 * u;
+      const int h = min(e, sh.dO - 1) / sh.dh;
 #pragma unroll
       for (int jj = 0; jj < ROWS_IN_FLIGHT; ++jj) {
         const int j = j0 + jj;
-        if (j < c) {
+        if (j < c && e < sh.dO) {
           const size_t row = ((size_t)r * sh.k + j) * sh.ldkv;
           const float da = sa[HK + h * sh.k + j];
-          dqe += da * kreg[jj];
-          dKV[row + e] = da * qe;
-          dKV[row + sh.dO + e] = sa[h * sh.k + j] * doe;
+          dqe[u] += da * k2[jj][u];
+          dKV[row + e] = da * qreg[u];
+          dKV[row + sh.dO + e] = sa[h * sh.k + j] * doreg[u];
         }
       }
     }
-    dq[(size_t)r * sh.ldo + e] = dqe;
-    // column sums of dq over the roots, spread over QPHI_BLOCKS partial rows to keep the atomics apart
-    if (q_part != nullptr) atomicAdd(q_part + (size_t)(blockIdx.x & (QPHI_BLOCKS - 1)) * sh.dO + e, dqe);
+  }
+#pragma unroll
+  for (int u = 0; u < MAX_E; ++u) {
+    const int e = lane + 64 * u;
+    if (e < sh.dO) {
+      dq[(size_t)r * sh.ldo + e] = dqe[u];
+      // column sums of dq over the roots, spread over QPHI_BLOCKS partial rows to keep the atomics apart
+      if (q_part != nullptr) atomicAdd(q_part + (size_t)(blockIdx.x & (QPHI_BLOCKS - 1)) * sh.dO + e, dqe[u]);
+    }
   }
 }
 

@@ -841,6 +841,8 @@ static int enqueue_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
   tm.end(17);
   side.join();   // the weight gradients started beside the chain
 
+  tm.begin(18);   // nothing in between: what a pair of event records costs by itself
+  tm.end(18);
   // last-event-wins write-back of s', tau and the new mails, and the SGD update, in one launch
   tm.begin(19);
   writeback_scatter(d, w.bs_dev, bs.total, st, w.winkey, w.epoch, w.Xrow, d.ldxr, w.tau, w.slot_row, nullptr, nullptr,
@@ -914,6 +916,7 @@ int32_t tgnn_debug_read(tgnn_ctx* ctx, int32_t what, void* dst, int64_t n_bytes,
     case 1: src = w.neid; cap = sizeof(int32_t) * d.maxRK; break;
     case 2: src = w.nts; cap = sizeof(double) * d.maxRK; break;
     case 3: src = w.cnt; cap = sizeof(int32_t) * d.maxR; break;
+    case 8: src = w.ucount; cap = sizeof(int32_t); break;
     case 5: break;
     case 4: case 6: case 7: break;
     default: return set_error(TGNN_E_INVALID_ARG, "unknown item %d", what);
