@@ -16,6 +16,7 @@ SortArgs sort_args(tgnn_ctx* ctx, int S) {
   SortArgs a;
   a.ucount = w.ucount; a.ucnt = w.ucnt; a.rowptr = w.rowptr; a.cursor = w.cursor;
   a.S = S; a.slot_gid = w.slot_gid; a.uidx = w.uidx; a.slot_row = w.slot_row; a.sorted = w.sorted;
+  a.sorted_row = w.sorted_row; a.total = w.sort_total;
   return a;
 }
 
@@ -25,10 +26,9 @@ SortArgs sort_args(tgnn_ctx* ctx, int S) {
 // One wavefront owns SEG_CHUNK consecutive entries of the row-sorted slot list; runs of one row are summed
 // in registers and leave as one atomic row update per half.
 constexpr int SEG_CHUNK = 16;
-__global__ __launch_bounds__(256) void seg_reduce_kernel(int R, int dO, const int32_t* __restrict__ ucount,
-                                                         const int32_t* __restrict__ rowptr,
+__global__ __launch_bounds__(256) void seg_reduce_kernel(int R, int S, int dO, const int32_t* __restrict__ sort_total,
                                                          const int32_t* __restrict__ sorted,
-                                                         const int32_t* __restrict__ slot_row,
+                                                         const int32_t* __restrict__ sorted_row,
                                                          const float* __restrict__ dq, const float* __restrict__ dz,
                                                          int ldh, const float* __restrict__ dKV, int ldkv,
                                                          float* __restrict__ dP, int ldp, QPhi qphi) {
@@ -43,16 +43,17 @@ __global__ __launch_bounds__(256) void seg_reduce_kernel(int R, int dO, const in
   }
   const int lane = threadIdx.x & 63;
   const int chunk = block * 4 + (threadIdx.x >> 6);
-  const int total = rowptr[*ucount];
   const int p0 = chunk * SEG_CHUNK;
-  if (p0 >= total) return;
-  const int n = min(SEG_CHUNK, total - p0);
-  // lanes fetch the chunk's slot ids and rows in parallel; they are broadcast below
+  // lanes fetch the chunk's slot ids and rows in parallel, without waiting for the length of the list (entries
+  // past it are dropped below); they are broadcast afterwards
   int my_slot = -1, my_row = -1;
-  if (lane < n) {
+  if (lane < SEG_CHUNK && p0 + lane < S) {
     my_slot = sorted[p0 + lane];
-    my_row = slot_row[my_slot];
+    my_row = sorted_row[p0 + lane];
   }
+  const int total = *sort_total;
+  if (p0 >= total) return;
+  if (p0 + lane >= total) my_slot = my_row = -1;
   int slots[SEG_CHUNK], rows[SEG_CHUNK];
 #pragma unroll
   for (int i = 0; i < SEG_CHUNK; ++i) {
@@ -119,8 +120,8 @@ void seg_reduce(tgnn_ctx* ctx, int R, int S, const QPhi& qphi, hipStream_t s) {
   const Dims& d = ctx->d;
   Ws& w = ctx->w;
   const int chunks = (S + SEG_CHUNK - 1) / SEG_CHUNK;
-  hipLaunchKernelGGL(seg_reduce_kernel, dim3((chunks + 3) / 4 + qphi_blocks(qphi)), dim3(256), 0, s, R, d.dO, w.ucount,
-                     w.rowptr, w.sorted, w.slot_row, w.dq, w.dz, d.ldh, w.dKV, d.ldkv, w.dP, d.ldp, qphi);
+  hipLaunchKernelGGL(seg_reduce_kernel, dim3((chunks + 3) / 4 + qphi_blocks(qphi)), dim3(256), 0, s, R, S, d.dO,
+                     w.sort_total, w.sorted, w.sorted_row, w.dq, w.dz, d.ldh, w.dKV, d.ldkv, w.dP, d.ldp, qphi);
 }
 
 // slot = row: dP[r] = {0 || dq[r] | dz[r]} for roots, dP[R + j] = {dKV[j] || 0} for neighbour slots

@@ -94,6 +94,7 @@ static void layout(const Dims& d, Ws& w, Bump& b) {
   w.utag = b.take<unsigned long long>(NG); w.uidx = b.take<int32_t>(NG); w.ucount = b.take<int32_t>(1);
   w.ulist = b.take<int32_t>(U); w.slot_row = b.take<int32_t>(S); w.ucnt = b.take<int32_t>(U);
   w.rowptr = b.take<int32_t>(U + 1); w.cursor = b.take<int32_t>(U); w.sorted = b.take<int32_t>(S);
+  w.sorted_row = b.take<int32_t>(S); w.sort_total = b.take<int32_t>(1);
   w.ds_row = b.take<float>(S * d.ldh);
   w.bs_dev = b.take<BatchSet>(1);
   w.sgd_dev = b.take<SgdSet>(1);

@@ -54,6 +54,7 @@ struct Ws {
   unsigned long long* utag;                    // [nrep*N] epoch of the last step that claimed the node
   int32_t *uidx, *ucount, *ulist;              // [nrep*N] row of a claimed node; [1] number of rows; [maxU] row -> gid
   int32_t *slot_row, *ucnt, *rowptr, *cursor, *sorted;  // [S] slot -> row; [maxU] slots per row; CSR of slots by row
+  int32_t *sorted_row, *sort_total;            // [S] row of every sorted slot; [1] number of sorted slots
   float* ds_row;                               // [maxS, ldh] gradient reaching s' per row
   BatchSet* bs_dev;                            // device copy of the step's batch descriptors
   struct SgdSet* sgd_dev;                      // device copy of the parameter/gradient pointer table
@@ -332,7 +333,8 @@ struct SortArgs {
   int S = 0;
   const int32_t *slot_gid = nullptr, *uidx = nullptr;
   int32_t* slot_row = nullptr;
-  int32_t* sorted = nullptr;
+  int32_t *sorted = nullptr, *sorted_row = nullptr;   // the sorted slots and, beside them, their rows
+  int32_t* total = nullptr;                           // number of sorted slots (= rowptr[*ucount])
 };
 SortArgs sort_args(tgnn_ctx* ctx, int S);
 // dP[row] += {dKV[slot] | 0} of the row's neighbour slots and {0 | dq[r] | dz[r]} of its root slots

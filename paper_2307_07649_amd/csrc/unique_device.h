@@ -90,7 +90,10 @@ __device__ __forceinline__ void uniq_scan_block(const SortArgs& a) {
     run += __shfl(inc, 63);
   }
   // the last wavefront ends at U (or owns nothing): its running sum is the total
-  if ((int)threadIdx.x == (int)blockDim.x - 1) a.rowptr[U] = run;
+  if ((int)threadIdx.x == (int)blockDim.x - 1) {
+    a.rowptr[U] = run;
+    *a.total = run;
+  }
 }
 
 // slot -> row, and the number of slots per row; `block` counts the blocks that do this work
@@ -110,7 +113,10 @@ __device__ __forceinline__ void uniq_fill_block(const SortArgs& a, int block) {
   const int s = block * blockDim.x + threadIdx.x;
   const int row = s < a.S ? a.slot_row[s] : -1;
   const int pos = wave_counted_add(a.cursor, row, true);
-  if (row >= 0) a.sorted[pos] = s;
+  if (row >= 0) {
+    a.sorted[pos] = s;
+    a.sorted_row[pos] = row;
+  }
 }
 
 }  // namespace tgnn
