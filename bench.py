@@ -33,8 +33,8 @@ STAGE_NAMES = ["prologue (pack weights, clear)", "(unused)", "roots + sample + d
                "per-node projections K, V, q, merge (MFMA)", "softmax attention + slot-sort fill", "merge layer (MFMA)",
                "decoder forward + loss", "decoder backward", "attention backward (MFMA + softmax)",
                "per-node gradient sums + node projections backward + GRU gates backward",
-               "all weight gradients (grouped MFMA GEMM)", "time-encoding gradients (two MFMA GEMMs in one launch)",
-               "empty event bracket", "write-back scatter + SGD (one launch)"]
+               "all weight gradients (grouped MFMA GEMM)", "time-encoding gradients (two MFMA GEMMs) + write-back scatter + SGD (one launch)",
+               "empty event bracket", "(unused)"]
 STAGE_ASSEMBLE, STAGE_KV, STAGE_WGRAD, STAGE_EMPTY = 7, 8, 16, 18
 
 

@@ -215,8 +215,8 @@ int32_t tgnn_zero_params(tgnn_ctx* ctx, tgnn_params* g, void* stream);
  *  15 per-node gradient sums (with the gradients through the query's Phi(0)) + node projections backward + GRU gates
  *  backward
  *  16 all weight gradients (one grouped MFMA GEMM)   17 time-encoding gradients (GEMMs onto Phi of keys and mails
- *  with the reduction in their epilogue, one launch)   18 nothing (two event records back to back: the
- *  cost of a bracket by itself)   19 write-back scatter + SGD (one launch)
+ *  with the reduction in their epilogue) + write-back scatter + SGD, one launch   18 nothing (two event records back to back: the
+ *  cost of a bracket by itself)   19 (unused)
  * tgnn_profile_enable: time the stages whose bit is set in `stage_mask` in every following tgnn_train_step
  * (0 = off); each timed stage costs two event records per step.  At most 4096 steps are kept per stage;
  * enabling resets the record.  tgnn_profile_read: synchronises the recorded events and returns the number

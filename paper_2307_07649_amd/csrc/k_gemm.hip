@@ -15,6 +15,7 @@
 
 #include "tgnn_internal.h"
 #include "device_math.h"
+#include "writeback_device.h"
 
 namespace tgnn {
 
@@ -34,6 +35,10 @@ __device__ __forceinline__ int nt_swz(int row, int chunk) { return row * NT_P + 
 template <int TN>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, (TN <= 5 ? 4 : 2)))) void gemm_nt_kernel(NtGroup grp) {
   constexpr int BM = NT_BM, BN = 16 * TN;
+  if ((int)blockIdx.x >= grp.gemm_wgs) {   // passengers after the products' workgroups: write-back scatter + SGD
+    wb_sgd_block(grp.tail, blockIdx.x - grp.gemm_wgs);
+    return;
+  }
   // Up to two independent problems share a launch; the second one's workgroups follow the first one's.
   // The argument block is read through the kernel-argument segment (scalar loads at a computed offset).
   typedef const NtGroup __attribute__((address_space(4))) * GroupPtr;
@@ -303,9 +308,14 @@ static int nt_tile_blocks(int M, int n_store) {
   return best;
 }
 
-void gemm_nt_group(const NtProblem* probs, int n, hipStream_t s) {
+void gemm_nt_group(const NtProblem* probs, int n, hipStream_t s, const WbArgs* tail) {
   NtGroup g;
   memset(&g, 0, sizeof(g));
+  int tail_blocks = 0;
+  if (tail != nullptr) {
+    g.tail = *tail;
+    tail_blocks = wb_total_blocks(*tail);
+  }
   int tn = 0, total = 0;
   for (int i = 0; i < n && g.n < 2; ++i) {
     NtProblem p = probs[i];
@@ -317,7 +327,10 @@ void gemm_nt_group(const NtProblem* probs, int n, hipStream_t s) {
     total += p.col_tiles * (((p.M + NT_BM - 1) / NT_BM + 7) & ~7);
     g.p[g.n++] = p;
   }
-  if (g.n == 0) return;
+  if (g.n == 0 && tail_blocks == 0) return;
+  if (tn == 0) tn = 1;
+  g.gemm_wgs = total;
+  total += tail_blocks;
 #define TGNN_NT_CASE(TNV) \
   case TNV: hipLaunchKernelGGL((gemm_nt_kernel<TNV>), dim3(total), dim3(256), 0, s, g); break;
   switch (tn) {

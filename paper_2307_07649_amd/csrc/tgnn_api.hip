@@ -831,24 +831,23 @@ static int enqueue_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
   tn.launch(s);
   tm.end(16);
   tm.begin(17);
-  {  // gradients reaching the time encodings of the keys and of the mails, each reduced inside its GEMM: one launch
+  side.join();   // the weight gradients started beside the chain
+  tm.begin(18);   // nothing in between: what a pair of event records costs by itself
+  tm.end(18);
+  tm.begin(17);
+  {  // Last launch.  The gradients reaching the time encodings of the keys and of the mails, each reduced inside
+     // its GEMM; and, as passengers (they depend on nothing in this launch: the time-encoding parameters are
+     // not trained), the last-event-wins write-back of s', tau and the new mails and the SGD update.
     TimeGradOut tg;
     tg.delta = w.delta; tg.w = p->time_w; tg.b = p->time_b; tg.g_w = grads->time_w; tg.g_b = grads->time_b;
     const NtProblem pr[2] = {
         keys_phi_problem(ctx, p, grads, RK),
         nt_problem(w.dgi, d.ld3, w.WihT_phi, d.ld3, nullptr, nullptr, d.ldt, U, d.dt, d.ld3, d.ldt, false, w.ucount, RowAdd(), tg)};
-    gemm_nt_group(pr, 2, s);
+    const WbArgs wb = writeback_args(d, w.bs_dev, bs.total, st, w.winkey, w.epoch, w.Xrow, d.ldxr, w.tau, w.slot_row, nullptr,
+                                     nullptr, nullptr, nullptr, out_winner, lr != 0.0f ? w.sgd_dev : nullptr, sgd_set.cnt, lr);
+    gemm_nt_group(pr, 2, s, &wb);
   }
   tm.end(17);
-  side.join();   // the weight gradients started beside the chain
-
-  tm.begin(18);   // nothing in between: what a pair of event records costs by itself
-  tm.end(18);
-  // last-event-wins write-back of s', tau and the new mails, and the SGD update, in one launch
-  tm.begin(19);
-  writeback_scatter(d, w.bs_dev, bs.total, st, w.winkey, w.epoch, w.Xrow, d.ldxr, w.tau, w.slot_row, nullptr, nullptr,
-                    nullptr, nullptr, out_winner, s, lr != 0.0f ? w.sgd_dev : nullptr, sgd_set.cnt, lr);
-  tm.end(19);
   if (out_logits)
     TGNN_HIP_CHECK(hipMemcpyAsync(out_logits, w.logits, sizeof(float) * B2, hipMemcpyDeviceToDevice, s));
   TGNN_LAUNCH_CHECK();

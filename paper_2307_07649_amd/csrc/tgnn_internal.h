@@ -144,6 +144,38 @@ int set_error(int code, const char* fmt, ...);
   } while (0)
 #define TGNN_LAUNCH_CHECK() TGNN_HIP_CHECK(hipGetLastError())
 
+// Pointer table of the SGD update (and of "clear these tensors").
+struct SgdSet {
+  float* p[20];
+  const float* g[20];
+  int n[20];
+  int cnt;
+};
+
+// Last-event-wins write-back (k_writeback.hip) as a record, so that it can ride in another launch.
+struct WbPtrs {
+  float *mem, *mail;
+  double *mem_ts, *mail_ts;
+  int32_t* mail_eid;
+  const float *s_new, *s_src, *s_dst;
+  const double *tau, *tau_src, *tau_dst;
+  const int32_t* slot_row;
+  int p_s;
+};
+struct WbArgs {
+  const BatchSet* bs = nullptr;   // NULL: nothing to do
+  int N = 0, dm = 0, vec = 1;     // vec: 4 when rows can be copied 16 bytes at a time
+  WbPtrs w;
+  const unsigned long long* winkey = nullptr;
+  const unsigned long long* epoch = nullptr;
+  int32_t* out_winner = nullptr;
+  int wb_blocks = 0;              // blocks of 256 threads for the scatter ...
+  const SgdSet* sgd = nullptr;    // ... followed by 64 per tensor for the SGD update p -= lr * g (NULL: none)
+  int sgd_cnt = 0;
+  float lr = 0.f;
+};
+inline int wb_total_blocks(const WbArgs& a) { return a.bs != nullptr ? a.wb_blocks + (a.sgd != nullptr ? 64 * a.sgd_cnt : 0) : 0; }
+
 // ---- k_gemm.hip ---------------------------------------------------------------------
 // C[m, n] = sum_k A[m, k] * B[n, k] + bias[n]  (m < M, n < N), optional ReLU; columns [N, n_store) of C are
 // set to zero.  Kp (multiple of 32) columns of A and B are read; B rows >= N and A rows >= M read as zero.
@@ -198,6 +230,8 @@ struct NtProblem {
 struct NtGroup {
   NtProblem p[2];
   int n;
+  int gemm_wgs;   // workgroups of the products; the ones after them run `tail`
+  WbArgs tail;    // optional passenger: write-back scatter + SGD (wb_total_blocks(tail) blocks)
 };
 inline NtProblem nt_problem(const float* A, int lda, const float* B, int ldb, const float* bias, float* C, int ldc, int M,
                             int N, int Kp, int n_store, bool relu, const int* m_dev = nullptr,
@@ -209,7 +243,7 @@ inline NtProblem nt_problem(const float* A, int lda, const float* B, int ldb, co
   p.add = add; p.tg = tg; p.gb = gb;
   return p;
 }
-void gemm_nt_group(const NtProblem* probs, int n, hipStream_t s);
+void gemm_nt_group(const NtProblem* probs, int n, hipStream_t s, const WbArgs* tail = nullptr);
 
 // Where the weight-gradient GEMM adds its result: element (n, k) goes to p[n >= n_split][k >= k_split]
 // (indices taken relative to the split) with row pitch ld[..][..]; column sums of D go to bias[n >= n_split].
@@ -255,12 +289,6 @@ struct PackDesc {
   float* dst;
   int rows, cols, zero_to, ldd;  // dst[r*ldd + c] = src[r*srs + c*scs] for c < cols, 0 for cols <= c < zero_to
   int srs, scs;
-};
-struct SgdSet {
-  float* p[20];
-  const float* g[20];
-  int n[20];
-  int cnt;
 };
 constexpr int MAX_PACK = 30;
 struct PrologueArgs {
@@ -411,15 +439,6 @@ void attn_dx_out(int R, int RK, int dm, const float* ds_row, int ldh, float* d_x
 void zero_f32(float* p, int n, hipStream_t s);
 
 // ---- k_writeback.hip ----------------------------------------------------------------
-struct WbArgs {
-  float *mem, *mail;
-  double *mem_ts, *mail_ts;
-  int32_t* mail_eid;
-  unsigned long long* winkey;
-  const float *s_src, *s_dst;  int p_s;  // [n_occ/2 rows each] only in the standalone layout
-  const double *tau_src, *tau_dst;
-  int dm;
-};
 void writeback_mark(const Dims& d, const BatchSet* bs, int total, unsigned long long* winkey,
                     const unsigned long long* epoch, hipStream_t s);
 // Fused layout: s_new/tau indexed by root slot.  Standalone layout: separate src/dst arrays.
@@ -428,6 +447,11 @@ void writeback_scatter(const Dims& d, const BatchSet* bs, int total, const tgnn_
                        const double* tau, const int32_t* slot_row, const float* s_src, const float* s_dst, const double* tau_src,
                        const double* tau_dst, int32_t* out_winner, hipStream_t s,
                        const SgdSet* sgd_dev = nullptr, int sgd_cnt = 0, float lr = 0.f);
+// The same as a record (for a launch that carries it as a passenger); blocks of 256 threads.
+WbArgs writeback_args(const Dims& d, const BatchSet* bs, int total, const tgnn_state* st, const unsigned long long* winkey,
+                      const unsigned long long* epoch, const float* s_new, int p_s, const double* tau,
+                      const int32_t* slot_row, const float* s_src, const float* s_dst, const double* tau_src,
+                      const double* tau_dst, int32_t* out_winner, const SgdSet* sgd_dev, int sgd_cnt, float lr);
 // key of occurrence (event e = ev_off + i, role) in the step with epoch counter `epoch`
 __host__ __device__ inline unsigned long long wb_key(unsigned long long epoch, int e, int role) {
   return (epoch << 33) | (1ull + 2ull * (unsigned long long)e + (unsigned long long)role);
