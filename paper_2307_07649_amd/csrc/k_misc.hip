@@ -125,7 +125,7 @@ void prologue_fill(tgnn_ctx* ctx, const tgnn_params* p, const BatchSet* bs, cons
   pa.q_part = w.q_part; pa.q_part_n = QPHI_BLOCKS * d.dO;
 }
 
-dim3 prologue_grid(const PrologueArgs& pa) { return dim3(32, pa.n_pack + pa.zero.cnt + 1); }
+dim3 prologue_grid(const PrologueArgs& pa) { return dim3(96, pa.n_pack + pa.zero.cnt + 1); }
 void* prologue_func() { return reinterpret_cast<void*>(prologue_kernel); }
 
 void prologue(tgnn_ctx* ctx, const tgnn_params* p, const BatchSet* bs, const SgdSet* sgd, const SgdSet* zero,
