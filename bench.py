@@ -29,7 +29,7 @@ MEASURED_TRAFFIC_BYTES = {"C1": {"kv_projection": 40.9e6, "assemble_ce": 27.2e6}
 
 STAGE_NAMES = ["prologue (pack weights, clear)", "(unused)", "roots + sample + distinct-node rows",
                "gather + time-encode (GRU input) + slot-to-row map", "GRU input + hidden projections (MFMA, one launch)", "(unused)",
-               "GRU gates + slot-sort scan", "per-slot attention input {e | Phi} (gather)", "K/V projection of the slots (MFMA)",
+               "(unused)", "GRU gates + slot-sort scan + per-slot attention input {e | Phi} (gather), one launch", "K/V projection of the slots (MFMA)",
                "per-node projections K, V, q, merge (MFMA)", "softmax attention + slot-sort fill", "merge layer (MFMA)",
                "decoder forward + loss", "decoder backward", "attention backward (MFMA + softmax)",
                "per-node gradient sums + node projections backward + GRU gates backward",
@@ -59,6 +59,14 @@ def assemble_bytes(d, n_roots):
     update time, and write the {e | Phi} row and the time difference."""
     per_nbr = 4 * d.d_edge + 4 * (d.d_edge + d.d_time) + 4 + 8 + 8
     return n_roots * d.k * per_nbr
+
+
+def gates_bytes(d, n_rows):
+    """GRU gates, passenger of the same launch: per distinct node row read the two projections (6 d_m floats) and
+    the stored memory, write the four gate values, the node row {s' | static} and clear the row's gradient
+    accumulator (pitch 2 * pad32(2 d_o) floats)."""
+    pad32 = lambda x: (x + 31) // 32 * 32
+    return n_rows * 4 * (12 * d.d_mem + 2 * d.d_static + 2 * pad32(2 * d.d_out))
 
 
 def step_flops(d, B):
@@ -240,7 +248,7 @@ def main():
     ev_step = ev / args.steps
     R_avg = 3 * (ev_timed_launches / n_timed_launches if n_timed_launches else ev_step)   # roots per timed launch
     kv_tflops = flops_kv(d, R_avg) / (kv_us * 1e-6) / 1e12 if n_m else None
-    asm_gbs = assemble_bytes(d, R_avg) / (asm_us * 1e-6) / 1e9 if n_g else None
+    asm_gbs = (assemble_bytes(d, R_avg) + gates_bytes(d, rows_avg)) / (asm_us * 1e-6) / 1e9 if n_g else None
     out = {
         "metric": "training events/sec (fwd+bwd+memory update) at 1 GPU",
         "value": ev / dt, "unit": "events/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -264,7 +272,8 @@ def main():
                              "avg_launch_us": wgrad_us, "empty_event_bracket_us": ms_e2 / n_e2 * 1e3 if n_e2 else None,
                              "distinct_node_rows_per_step": rows_avg},
         "gather": {"bound": "hbm", "kernel": "assemble_ce_kernel: edge-feature row gather + time encoding into the "
-                                             "per-slot key/value inputs",
+                                             "per-slot key/value inputs; its first blocks carry the GRU gates of the "
+                                             "distinct node rows (bytes of both counted)",
                    "achieved": asm_gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                    "frac": asm_gbs / PEAK_HBM_GBS if asm_gbs else None,
                    "avg_launch_us": asm_us, "empty_event_bracket_us": bracket_us,

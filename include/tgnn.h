@@ -208,8 +208,8 @@ int32_t tgnn_zero_params(tgnn_ctx* ctx, tgnn_params* g, void* stream);
 /* Stage timing with HIP events on the call's own stream.  Stages of tgnn_train_step:
  *  0 prologue (pack weights, clear loss/grads)   1 (unused)   2 roots + sample + distinct-node rows (one kernel)
  *  3 gather + time-encode (GRU input; with the slot -> row map)   4 GRU input and hidden projections (MFMA,
- *  one launch)   5 (unused)   6 GRU gates (with the scan of the slot sort)
- *  7 per-slot attention input {e | Phi}   8 K/V projection of the slots (MFMA)   9 per-node projections (MFMA)
+ *  one launch)   5 (unused)   6 (unused)
+ *  7 GRU gates (with the scan of the slot sort) + per-slot attention input {e | Phi}, one launch   8 K/V projection of the slots (MFMA)   9 per-node projections (MFMA)
  *  10 softmax attention (with the fill pass of the slot sort)   11 merge layer   12 decoder forward + loss   13 decoder backward
  *  14 attention backward (data-gradient GEMM + softmax)
  *  15 per-node gradient sums (with the gradients through the query's Phi(0)) + node projections backward + GRU gates

@@ -3,6 +3,7 @@
 // One wavefront moves one row: 16-byte (or 8-byte) vector loads, every row a contiguous burst.
 #include "tgnn_internal.h"
 #include "unique_device.h"
+#include "gru_device.h"
 #include "device_math.h"
 
 namespace tgnn {
@@ -92,9 +93,18 @@ __global__ __launch_bounds__(256) void assemble_ce_kernel(CeArgs a) {
   extern __shared__ __attribute__((aligned(16))) float ce_lds[];   // [CE_ROWS][ldce] staging rows
   __shared__ int s_eid[CE_ROWS];       // edge-feature row, -1: absent neighbour
   __shared__ double s_delta[CE_ROWS];
+  int block = blockIdx.x;
+  {
+    const int gru_blocks = gru_total_blocks(a.gru);   // the first blocks are passengers: the GRU gates
+    if (block < gru_blocks) {
+      gru_fwd_block(a.gru, block);
+      return;
+    }
+    block -= gru_blocks;
+  }
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int RK = a.R * a.k;
-  const int row0 = blockIdx.x * CE_ROWS;
+  const int row0 = block * CE_ROWS;
   if (threadIdx.x < CE_ROWS) {
     const int row = row0 + threadIdx.x;
     int e = -1;
@@ -164,10 +174,19 @@ __global__ __launch_bounds__(256) void assemble_ce_kernel(CeArgs a) {
 // Fallback for rows too wide to stage CE_ROWS of them in LDS: one wavefront per row, direct stores.
 template <int VEC>
 __global__ __launch_bounds__(256) void assemble_ce_wide_kernel(CeArgs a) {
+  int block = blockIdx.x, n_blocks = gridDim.x;
+  {
+    const int gru_blocks = gru_total_blocks(a.gru);   // the first blocks are passengers: the GRU gates
+    if (block < gru_blocks) {
+      gru_fwd_block(a.gru, block);
+      return;
+    }
+    block -= gru_blocks; n_blocks -= gru_blocks;
+  }
   const int lane = threadIdx.x & 63;
   const int wpb = blockDim.x >> 6;
   const int RK = a.R * a.k;
-  for (int row = blockIdx.x * wpb + (threadIdx.x >> 6); row < RK; row += gridDim.x * wpb) {
+  for (int row = block * wpb + (threadIdx.x >> 6); row < RK; row += n_blocks * wpb) {
     const int r = row / a.k, j = row - r * a.k;
     float* out = a.CE + (size_t)row * a.ldce;
     if (j >= a.cnt[r]) {
@@ -188,15 +207,18 @@ __global__ __launch_bounds__(256) void assemble_ce_wide_kernel(CeArgs a) {
 
 void assemble_ce(const CeArgs& a, hipStream_t s) {
   const int rows = a.R * a.k;
-  if (rows <= 0) return;
+  if (rows <= 0) {
+    gru_gates_fwd(a.gru, s);
+    return;
+  }
   const int vec = pick_vec({a.de ? a.de : 4, (long long)((uintptr_t)a.efeat / 4)});
   const size_t lds = (size_t)CE_ROWS * a.ldce * sizeof(float);
   if (lds <= 48 * 1024) {
-    const int blocks = (rows + CE_ROWS - 1) / CE_ROWS;
+    const int blocks = (rows + CE_ROWS - 1) / CE_ROWS + gru_total_blocks(a.gru);
     if (vec == 4) hipLaunchKernelGGL(assemble_ce_kernel<4>, dim3(blocks), dim3(256), lds, s, a);
     else hipLaunchKernelGGL(assemble_ce_kernel<1>, dim3(blocks), dim3(256), lds, s, a);
   } else {
-    const int blocks = (rows + 3) / 4;
+    const int blocks = (rows + 3) / 4 + gru_total_blocks(a.gru);
     if (vec == 4) hipLaunchKernelGGL(assemble_ce_wide_kernel<4>, dim3(blocks), dim3(256), 0, s, a);
     else hipLaunchKernelGGL(assemble_ce_wide_kernel<1>, dim3(blocks), dim3(256), 0, s, a);
   }

@@ -184,7 +184,7 @@ static void gru_forward(tgnn_ctx* ctx, const tgnn_params* p, int n, hipStream_t 
       nt_problem(w.X, d.ldx, w.Wih_p, d.ldx, p->gru_bih, w.gi, d.ld3, n, 3 * d.dm, d.ldx, d.ld3, false),
       nt_problem(w.Hm, d.ldh, w.Whh_p, d.ldh, p->gru_bhh, w.gh, d.ld3, n, 3 * d.dm, d.ldh, d.ld3, false)};
   gemm_nt_group(pr, 2, s);
-  gru_gates_fwd(d, n, nullptr, w.gi, w.gh, w.Hm, w.has, w.gates, w.Xrow, d.ldxr, nullptr, nullptr, nullptr, 0, s);
+  gru_gates_fwd(gru_gates_args(d, n, nullptr, w.gi, w.gh, w.Hm, w.has, w.gates, w.Xrow, d.ldxr, nullptr, nullptr, nullptr, 0), s);
 }
 
 // Attention (Eq. 4-7) and the merge layer, from the node rows ws.Xrow [n_rows] and the per-slot rows ws.CE.
@@ -775,11 +775,6 @@ static int enqueue_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
     gemm_nt_group(pr, 2, s);
   }
   tm.end(4);
-  tm.begin(6);
-  gru_gates_fwd(d, U, w.ucount, w.gi, w.gh, w.Hm, w.has, w.gates, w.Xrow, d.ldxr, d.ds ? st->stat : nullptr, w.ulist,
-                w.dP, d.ldp, s, sort_args(ctx, S));   // with the scan of the slot sort
-  tm.end(6);
-
   // attention + merge
   CeArgs aa;
   memset(&aa, 0, sizeof(aa));
@@ -788,6 +783,10 @@ static int enqueue_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
   aa.time_w = p->time_w; aa.time_b = p->time_b;
   aa.CE = w.CE; aa.ldce = d.ldce; aa.dtk = w.dtk;
   aa.R = R; aa.k = d.k; aa.de = d.de; aa.dt = d.dt; aa.dt_source = d.dt_source;
+  // The GRU gates (with the scan of the slot sort) and the per-slot attention input do not depend on each other:
+  // one launch, the gates in its first blocks.
+  aa.gru = gru_gates_args(d, U, w.ucount, w.gi, w.gh, w.Hm, w.has, w.gates, w.Xrow, d.ldxr, d.ds ? st->stat : nullptr,
+                          w.ulist, w.dP, d.ldp, sort_args(ctx, S));
   tm.begin(7);
   assemble_ce(aa, s);
   tm.end(7);

@@ -372,6 +372,36 @@ void slots_to_dp(tgnn_ctx* ctx, int R, int RK, const QPhi& qphi, hipStream_t s);
 void expand_rows(tgnn_ctx* ctx, int S, const float* src, int ld, const double* src_d, float* dst, double* dst_d,
                  hipStream_t s);
 
+// ---- k_gru.hip ----------------------------------------------------------------------
+// GRU gates (Eq. 3) from the two projections gi = W_ih x + b_ih, gh = W_hh h + b_hh, as a record: blocks of 256
+// threads, gru_total_blocks() of them.  n_dev (device, may be NULL) caps the row count.  s' goes to
+// x_out [n, ld_x]; with stat != NULL the node's static row stat[gid[row] % N] is appended (columns d_m ..
+// d_m + d_s).  zero_buf (may be NULL) [n, zero_w] is cleared for the backward pass.  scan.ucnt != NULL: block 0
+// runs the scan of the slot sort instead.
+struct GruFwdArgs {
+  int n_max = 0;
+  const int* n_dev = nullptr;
+  int dm = 0, ldh = 0, ld3 = 0;
+  const float *gi = nullptr, *gh = nullptr, *Hm = nullptr;   // gi == NULL: nothing to do
+  const int32_t* has = nullptr;
+  float *gates = nullptr, *x_out = nullptr;
+  int ld_x = 0;
+  const float* stat = nullptr;
+  int ds = 0;
+  const int32_t* gid = nullptr;
+  int N = 0;
+  float* zero_buf = nullptr;
+  int zero_w = 0, gru_blocks = 0;
+  SortArgs scan;
+};
+__host__ __device__ inline int gru_total_blocks(const GruFwdArgs& a) {
+  return a.gi != nullptr ? a.gru_blocks + (a.scan.ucnt != nullptr ? 1 : 0) : 0;
+}
+GruFwdArgs gru_gates_args(const Dims& d, int n, const int* n_dev, const float* gi, const float* gh, const float* Hm,
+                          const int32_t* has, float* gates, float* x_out, int ld_x, const float* stat, const int32_t* gid,
+                          float* zero_buf, int zero_w, const SortArgs& scan = SortArgs());
+void gru_gates_fwd(const GruFwdArgs& a, hipStream_t s);
+
 // ---- k_gather.hip -------------------------------------------------------------------
 struct GatherArgs {
   // sources
@@ -406,20 +436,13 @@ struct CeArgs {
   float* CE;  int ldce;
   double* dtk;
   int R, k, de, dt, dt_source;
+  GruFwdArgs gru;                       // gru.gi != NULL: the first gru_total_blocks(gru) blocks of the launch run the GRU gates instead
 };
 void assemble_ce(const CeArgs& a, hipStream_t s);
 // Standalone attention call: node rows from the caller's x_root / x_nbr (rows of absent neighbours zeroed).
 void stage_x_rows(int R, int k, int dx, const float* x_root, const float* x_nbr, const int32_t* cnt, float* Xrow,
                   int ldxr, hipStream_t s);
 
-// ---- k_gru.hip ----------------------------------------------------------------------
-// n_dev (device, may be NULL) caps the row count.  s' goes to x_out [n, ld_x]; with stat != NULL the node's
-// static row stat[gid[row] % N] is appended (columns d_m .. d_m + d_s).  zero_buf (may be NULL) [n, zero_w]
-// is cleared for the backward pass.
-void gru_gates_fwd(const Dims& d, int n, const int* n_dev, const float* gi, const float* gh, const float* Hm,
-                   const int32_t* has, float* gates, float* x_out, int ld_x, const float* stat, const int32_t* gid,
-                   float* zero_buf, int zero_w, hipStream_t s,
-                   const SortArgs& scan = SortArgs());
 // ---- k_attn.hip ---------------------------------------------------------------------
 // q of root r is q[qrow * ldq_ ...] with qrow = slot_row ? slot_row[r] : r.
 void attn_core_fwd(const Dims& d, int R, const float* q, int ldq_, const int32_t* slot_row, const float* KV, int ldkv,
