@@ -32,8 +32,8 @@ STAGE_NAMES = ["prologue (pack weights, clear)", "(unused)", "roots + sample + d
                "(unused)", "GRU gates + slot-sort scan + per-slot attention input {e | Phi} (gather), one launch", "K/V projection of the slots (MFMA)",
                "per-node projections K, V, q, merge (MFMA)", "softmax attention + slot-sort fill", "merge layer (MFMA)",
                "decoder forward + loss", "decoder backward", "attention backward (MFMA + softmax)",
-               "per-node gradient sums + node projections backward + GRU gates backward",
-               "all weight gradients (grouped MFMA GEMM)", "time-encoding gradients (two MFMA GEMMs) + write-back scatter + SGD (one launch)",
+               "per-node gradient sums; node projections + GRU gates backward with the keys' time-encoding gradients (one launch)",
+               "all weight gradients (grouped MFMA GEMM)", "time-encoding gradients of the mails (MFMA) + write-back scatter + SGD (one launch)",
                "empty event bracket", "(unused)"]
 STAGE_ASSEMBLE, STAGE_KV, STAGE_WGRAD, STAGE_EMPTY = 7, 8, 16, 18
 

@@ -212,10 +212,10 @@ int32_t tgnn_zero_params(tgnn_ctx* ctx, tgnn_params* g, void* stream);
  *  7 GRU gates (with the scan of the slot sort) + per-slot attention input {e | Phi}, one launch   8 K/V projection of the slots (MFMA)   9 per-node projections (MFMA)
  *  10 softmax attention (with the fill pass of the slot sort)   11 merge layer   12 decoder forward + loss   13 decoder backward
  *  14 attention backward (data-gradient GEMM + softmax)
- *  15 per-node gradient sums (with the gradients through the query's Phi(0)) + node projections backward + GRU gates
- *  backward
- *  16 all weight gradients (one grouped MFMA GEMM)   17 time-encoding gradients (GEMMs onto Phi of keys and mails
- *  with the reduction in their epilogue) + write-back scatter + SGD, one launch   18 nothing (two event records back to back: the
+ *  15 per-node gradient sums (with the gradients through the query's Phi(0)) + node projections backward with GRU
+ *  gates backward, and the product onto the keys' time encoding with its reduction (one launch)
+ *  16 all weight gradients (one grouped MFMA GEMM)   17 time-encoding gradient of the mails (GEMM with the
+ *  reduction in its epilogue) + write-back scatter + SGD, one launch   18 nothing (two event records back to back: the
  *  cost of a bracket by itself)   19 (unused)
  * tgnn_profile_enable: time the stages whose bit is set in `stage_mask` in every following tgnn_train_step
  * (0 = off); each timed stage costs two event records per step.  At most 4096 steps are kept per stage;

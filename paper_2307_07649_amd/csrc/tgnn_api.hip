@@ -264,17 +264,24 @@ static void attn_backward(tgnn_ctx* ctx, tgnn_params* g, const tgnn_params* p, i
 // After the per-row reduction into ws.dP: gradient reaching the node rows (ws.ds_row, dynamic columns) and
 // the weight gradients of the node part of W_k, W_v, W_q, W_o with all four biases.
 // through_gru: the gradient is not stored in ws.ds_row but carried on, in the same launch, to the gradients of
-// the GRU gate pre-activations (ws.dgi, ws.dgh).
+// the GRU gate pre-activations (ws.dgi, ws.dgh).  `with` (may be NULL): an independent product to run in the
+// same launch.
 static void node_proj_backward(tgnn_ctx* ctx, tgnn_params* g, int n_rows, const int* n_rows_dev, TnBatch& tn,
-                               bool through_gru, hipStream_t s) {
+                               bool through_gru, hipStream_t s, const NtProblem* with = nullptr) {
   const Dims& d = ctx->d; Ws& w = ctx->w;
   GruBwdOut gb;
   if (through_gru) {
     gb.gates = w.gates; gb.Hm = w.Hm; gb.has = w.has; gb.dgi = w.dgi; gb.dgh = w.dgh;
     gb.dm = d.dm; gb.ldh = d.ldh; gb.ld3 = d.ld3;
   }
-  gemm_nt(w.dP, d.ldp, w.WxT, d.ldp, nullptr, w.ds_row, d.ldh, n_rows, d.dm, d.ldp, d.ldh, false, s, n_rows_dev, RowAdd(),
-          TimeGradOut(), gb);
+  const NtProblem mine = nt_problem(w.dP, d.ldp, w.WxT, d.ldp, nullptr, w.ds_row, d.ldh, n_rows, d.dm, d.ldp, d.ldh, false,
+                                    n_rows_dev, RowAdd(), TimeGradOut(), gb);
+  if (with != nullptr) {
+    const NtProblem pr[2] = {mine, *with};   // the few, long workgroups of this one start first
+    gemm_nt_group(pr, 2, s);
+  } else {
+    gemm_nt_group(&mine, 1, s);
+  }
   OutMap kv;
   memset(&kv, 0, sizeof(kv));
   kv.p[0][0] = g->wk; kv.p[1][0] = g->wv; kv.ld[0][0] = kv.ld[1][0] = d.dkv;
@@ -822,7 +829,10 @@ static int enqueue_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
   tm.begin(15);
   // per-row sum of the slot gradients reaching the per-node projections (the query's Phi(0) gradients ride along)
   seg_reduce(ctx, R, S, qphi_args(ctx, p, grads), s);
-  node_proj_backward(ctx, grads, U, w.ucount, tn, true, s);
+  {  // the product onto the keys' time encoding is independent of this chain: it shares the launch
+    const NtProblem keys_phi = keys_phi_problem(ctx, p, grads, RK);
+    node_proj_backward(ctx, grads, U, w.ucount, tn, true, s, &keys_phi);
+  }
   tm.end(15);
   tn.add(w.dgi, d.ld3, w.X, d.ldx, U, 3 * d.dm, d.d_in, single_out(grads->gru_wih, d.d_in, grads->gru_bih), w.ucount);
   tn.add(w.dgh, d.ld3, w.Hm, d.ldh, U, 3 * d.dm, d.dm, single_out(grads->gru_whh, d.dm, grads->gru_bhh), w.ucount);
@@ -834,17 +844,17 @@ static int enqueue_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
   tm.begin(18);   // nothing in between: what a pair of event records costs by itself
   tm.end(18);
   tm.begin(17);
-  {  // Last launch.  The gradients reaching the time encodings of the keys and of the mails, each reduced inside
-     // its GEMM; and, as passengers (they depend on nothing in this launch: the time-encoding parameters are
-     // not trained), the last-event-wins write-back of s', tau and the new mails and the SGD update.
+  {  // Last launch.  The gradient reaching the time encoding of the mails, reduced inside its GEMM (the keys'
+     // went with the node projections' backward); and, as passengers (they depend on nothing in this launch:
+     // the time-encoding parameters are not trained), the last-event-wins write-back of s', tau and the new
+     // mails and the SGD update.
     TimeGradOut tg;
     tg.delta = w.delta; tg.w = p->time_w; tg.b = p->time_b; tg.g_w = grads->time_w; tg.g_b = grads->time_b;
-    const NtProblem pr[2] = {
-        keys_phi_problem(ctx, p, grads, RK),
-        nt_problem(w.dgi, d.ld3, w.WihT_phi, d.ld3, nullptr, nullptr, d.ldt, U, d.dt, d.ld3, d.ldt, false, w.ucount, RowAdd(), tg)};
+    const NtProblem pr = nt_problem(w.dgi, d.ld3, w.WihT_phi, d.ld3, nullptr, nullptr, d.ldt, U, d.dt, d.ld3, d.ldt, false,
+                                    w.ucount, RowAdd(), tg);
     const WbArgs wb = writeback_args(d, w.bs_dev, bs.total, st, w.winkey, w.epoch, w.Xrow, d.ldxr, w.tau, w.slot_row, nullptr,
                                      nullptr, nullptr, nullptr, out_winner, lr != 0.0f ? w.sgd_dev : nullptr, sgd_set.cnt, lr);
-    gemm_nt_group(pr, 2, s, &wb);
+    gemm_nt_group(&pr, 1, s, &wb);
   }
   tm.end(17);
   if (out_logits)
