@@ -1,6 +1,8 @@
 // Row gathers (Sec. 3.2.1: fetch node memory and cached mails of root and supporting nodes) fused with
 // the time encoding of the mail (Eq. 1-2), and the assembly of the per-slot attention inputs (Eq. 5-6).
 // One wavefront moves one row: 16-byte (or 8-byte) vector loads, every row a contiguous burst.
+#include <algorithm>
+
 #include "tgnn_internal.h"
 #include "unique_device.h"
 #include "gru_device.h"
@@ -75,7 +77,10 @@ void gather_rows(const GatherArgs& a, hipStream_t s) {
                             (long long)((uintptr_t)a.o_mail / 4), (long long)((uintptr_t)a.o_ef / 4),
                             (long long)((uintptr_t)a.mem / 4), (long long)((uintptr_t)a.mail / 4),
                             (long long)((uintptr_t)a.efeat / 4)});
-  const int blocks = (a.n_slots + 3) / 4 + (a.map.ucnt != nullptr ? (a.map.S + 255) / 256 : 0);
+  // a row count that lives on the device is usually a small part of its bound: launch for an eighth of it (the
+  // waves stride over the rows, so more rows only mean more rounds)
+  const int rows_launched = a.n_dev != nullptr ? std::min(a.n_slots, std::max(512, (a.n_slots + 7) / 8)) : a.n_slots;
+  const int blocks = (rows_launched + 3) / 4 + (a.map.ucnt != nullptr ? (a.map.S + 255) / 256 : 0);
   if (vec == 4) hipLaunchKernelGGL(gather_kernel<4>, dim3(blocks), dim3(256), 0, s, a);
   else if (vec == 2) hipLaunchKernelGGL(gather_kernel<2>, dim3(blocks), dim3(256), 0, s, a);
   else hipLaunchKernelGGL(gather_kernel<1>, dim3(blocks), dim3(256), 0, s, a);

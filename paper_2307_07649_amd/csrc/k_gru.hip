@@ -1,6 +1,8 @@
 // Element-wise part of UPDT = GRU cell (Eq. 3): gates forward (gru_device.h), as a launch of its own.  In the
 // training step it rides in the launch that assembles the per-slot attention input instead.  The matrix products
 // live in k_gemm.hip; the gates' backward pass is an epilogue of the product that yields the gradient reaching s'.
+#include <algorithm>
+
 #include "tgnn_internal.h"
 #include "gru_device.h"
 
@@ -16,7 +18,10 @@ GruFwdArgs gru_gates_args(const Dims& d, int n, const int* n_dev, const float* g
   a.n_max = n; a.n_dev = n_dev; a.dm = d.dm; a.ldh = d.ldh; a.ld3 = d.ld3;
   a.gi = gi; a.gh = gh; a.Hm = Hm; a.has = has; a.gates = gates; a.x_out = x_out; a.ld_x = ld_x;
   a.stat = stat; a.ds = d.ds; a.gid = gid; a.N = d.N; a.zero_buf = zero_buf; a.zero_w = zero_w;
-  a.gru_blocks = (int)(((long long)n * d.dm + 255) / 256);
+  // a row count that lives on the device is usually a small part of its bound: launch for an eighth of it (the
+  // threads stride over the elements, so more rows only mean more rounds)
+  const int rows_launched = n_dev != nullptr ? std::min(n, std::max(512, (n + 7) / 8)) : n;
+  a.gru_blocks = (int)(((long long)rows_launched * d.dm + 255) / 256);
   a.scan = scan;
   return a;
 }
