@@ -70,3 +70,33 @@ def test_ragged_last_batch_and_single_event():
     run_sequence(P, 5, check_at=(0, 4))      # last batch has 5 events
     P = custom_problem(n_nodes=30, E=40, d_mem=16, d_time=8, d_edge=4, d_static=0, n_heads=2, k=5, batch=1)
     run_sequence(P, 40, check_at=(0, 39))
+
+
+def test_sampled_stage_timing_and_row_count():
+    """Stage timing on every 4th step (tgnn_profile_every): the timed steps are launched kernel by kernel, the others
+    replay the captured graph; both agree with the oracle, the record holds exactly the timed steps, and the
+    distinct-row count the step leaves behind (debug item 8) is the number of distinct nodes among the roots and
+    their sampled neighbours."""
+    import torch
+    P = make_problem("C0", random_phase=True)
+    d = P["d"]
+    G = GpuSide(P); Or = OracleSide(P)
+    G.ctx.tgnn_profile_enable((1 << 8) | (1 << 18))
+    G.ctx.tgnn_profile_every(4)
+    for s in range(9):                        # timed: steps 0, 4, 8
+        b = batch_np(P, s * d.batch, (s + 1) * d.batch)
+        g = G.step([b], lr=0.05, want=True)
+        o = Or.step([b], lr=0.05)
+        compare_step(g, o, label=f"step {s}")
+        out = o["outs"][0]
+        roots = np.concatenate([b["src"], b["dst"], b["neg"]])
+        nbr = out["nbr"][out["nbr"] >= 0]
+        rows = torch.zeros(1, dtype=torch.int32, device="cuda")
+        G.ctx.tgnn_debug_read(8, rows)
+        assert int(rows.item()) == len(np.unique(np.concatenate([roots, nbr]))), s
+    n_kv, ms_kv = G.ctx.tgnn_profile_read(8)
+    n_empty, ms_empty = G.ctx.tgnn_profile_read(18)
+    assert n_kv == 3 and n_empty == 3 and ms_kv > 0.0 and ms_empty >= 0.0
+    G.ctx.tgnn_profile_enable(0)
+    G.ctx.tgnn_profile_every(1)
+    compare_state(G.state_np(), Or.states[0], label="state")
