@@ -27,7 +27,7 @@ PEAK_MFMA_F32_TFLOPS = 157.3
 # Counters cannot be read from inside this script, so the figures are the recorded ones, for C1 only.
 MEASURED_TRAFFIC_BYTES = {"C1": {"kv_projection": 40.9e6, "assemble_ce": 33.8e6}}
 
-STAGE_NAMES = ["prologue (pack weights, clear)", "(unused)", "roots + sample + distinct-node rows",
+STAGE_NAMES = ["(unused)", "(unused)", "roots + sample + distinct-node rows + prologue (pack weights, clear), one launch",
                "gather + time-encode (GRU input) + slot-to-row map", "GRU input + hidden projections (MFMA, one launch)", "(unused)",
                "(unused)", "GRU gates + slot-sort scan + per-slot attention input {e | Phi} (gather), one launch", "K/V projection of the slots (MFMA)",
                "per-node projections K, V, q, merge (MFMA)", "softmax attention + slot-sort fill", "merge layer (MFMA)",

@@ -206,7 +206,8 @@ int32_t tgnn_train_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
 int32_t tgnn_zero_params(tgnn_ctx* ctx, tgnn_params* g, void* stream);
 
 /* Stage timing with HIP events on the call's own stream.  Stages of tgnn_train_step:
- *  0 prologue (pack weights, clear loss/grads)   1 (unused)   2 roots + sample + distinct-node rows (one kernel)
+ *  0 (unused)   1 (unused)   2 first launch: roots + sample + distinct-node rows, and the prologue (pack weights, clear
+ *  loss/grads, batch descriptors)
  *  3 gather + time-encode (GRU input; with the slot -> row map)   4 GRU input and hidden projections (MFMA,
  *  one launch)   5 (unused)   6 (unused)
  *  7 GRU gates (with the scan of the slot sort) + per-slot attention input {e | Phi}, one launch   8 K/V projection of the slots (MFMA)   9 per-node projections (MFMA)

@@ -12,6 +12,7 @@ namespace tgnn {
 
 template <int VEC>
 __global__ __launch_bounds__(256) void gather_kernel(GatherArgs a) {
+  if (a.epoch_bump != nullptr && blockIdx.x == 0 && threadIdx.x == 0) *a.epoch_bump += 1ull;   // nothing here reads it
   int block = blockIdx.x, n_blocks = gridDim.x;
   if (a.map.ucnt != nullptr) {   // the first blocks are passengers: the slot -> row map
     const int map_blocks = (a.map.S + (int)blockDim.x - 1) / (int)blockDim.x;

@@ -3,67 +3,11 @@
 
 #include "tgnn_internal.h"
 #include "device_math.h"
+#include "prologue_device.h"
 
 namespace tgnn {
 
-__global__ void prologue_kernel(PrologueArgs a) {
-  const int y = blockIdx.y;
-  if (y < a.n_pack) {
-    const PackDesc d = a.d[y];
-    const int total = d.rows * d.zero_to;
-    const float* __restrict__ src = d.src;
-    float* __restrict__ dst = d.dst;
-    const int stride = gridDim.x * blockDim.x;
-    // four elements per pass, their loads issued together
-    for (int i0 = blockIdx.x * blockDim.x + threadIdx.x; i0 < total; i0 += 4 * stride) {
-      float v[4];
-      int off[4];
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const int i = i0 + j * stride;
-        const int r = i / d.zero_to, c = i - r * d.zero_to;
-        off[j] = i < total ? r * d.ldd + c : -1;
-        v[j] = (i < total && c < d.cols) ? src[(size_t)r * d.srs + (size_t)c * d.scs] : 0.f;
-      }
-#pragma unroll
-      for (int j = 0; j < 4; ++j)
-        if (off[j] >= 0) dst[off[j]] = v[j];
-    }
-  } else if (y < a.n_pack + a.zero.cnt) {
-    float* p = a.zero.p[y - a.n_pack];
-    const int n = a.zero.n[y - a.n_pack];
-    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) p[i] = 0.f;
-  } else if (blockIdx.x == 0) {
-    if (a.bs_dev) {
-      const int* src = reinterpret_cast<const int*>(&a.bs);
-      int* dst = reinterpret_cast<int*>(a.bs_dev);
-      for (int i = threadIdx.x; i < (int)(sizeof(BatchSet) / sizeof(int)); i += blockDim.x) dst[i] = src[i];
-    }
-    if (a.sgd_dev) {
-      const int* src = reinterpret_cast<const int*>(&a.sgd);
-      int* dst = reinterpret_cast<int*>(a.sgd_dev);
-      for (int i = threadIdx.x; i < (int)(sizeof(SgdSet) / sizeof(int)); i += blockDim.x) dst[i] = src[i];
-    }
-    for (int i = threadIdx.x; i < a.q_part_n; i += blockDim.x) a.q_part[i] = 0.f;
-    if (threadIdx.x == 0) {
-      if (a.loss) *a.loss = 0.f;
-      *a.epoch += 1ull;
-      *a.ucount = 0;
-    }
-  } else if (a.bq_out != nullptr) {
-    // the query's time encoding Phi(0) = cos(time_b) does not depend on the root: fold W_q Phi(0) into the
-    // bias.  One wavefront per output row, rows dealt over blocks 1 .. gridDim.x - 1 of this grid row.
-    const int lane = threadIdx.x & 63;
-    const int wv = (blockIdx.x - 1) * (blockDim.x >> 6) + (threadIdx.x >> 6);
-    const int n_wv = (gridDim.x - 1) * (blockDim.x >> 6);
-    for (int n = wv; n < a.dO; n += n_wv) {
-      float acc = 0.f;
-      for (int c = lane; c < a.dt; c += 64) acc += a.wq[(size_t)n * a.dq + a.dx + c] * time_enc(0.0, 0.f, a.time_b[c]);
-      for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o);
-      if (lane == 0) a.bq_out[n] = a.bq[n] + acc;
-    }
-  }
-}
+__global__ void prologue_kernel(PrologueArgs a) { prologue_block(a, blockIdx.x, gridDim.x, blockIdx.y); }
 
 // Padded copies of the weights (row pitch = the pitch of the activation matrix they multiply), split into
 // the blocks that multiply the node rows, the per-slot rows and the attention output, and the transposed

@@ -1,30 +1,27 @@
 // Root construction and most-recent-neighbour sampling (Sec. 2.1 "most recent neighbors"; k = 10 in Sec. 4)
 // on the temporal CSR: one wavefront per query, a 64-ary search over the node's ascending time array
 // followed by one k-wide read of the newest entries below the query time.
+#include <string.h>
+
 #include "tgnn_internal.h"
+#include "prologue_device.h"
 
 namespace tgnn {
 
 // FUSED: the query of wave r is root r of the step's batches ([src | dst | neg] per batch); the wave also
 // records the root (node, time, slot ids), marks the write-back arbitration word of a positive endpoint
-// (last-event-wins: largest key survives) and claims rows for the root and its neighbours.
+// (last-event-wins: largest key survives) and claims rows for the root and its neighbours.  `bs` are the batch
+// descriptors (read from the kernel's argument block), `ep` the epoch of the step.
 // Otherwise the queries are the caller's (node, t) arrays.
+// `block` is the calling block's number among the sampling blocks; one wavefront per query.
 template <bool FUSED>
-__global__ __launch_bounds__(1024) void sample_kernel(const int64_t* __restrict__ indptr,
-                                                      const int32_t* __restrict__ g_nbr,
-                                                      const int32_t* __restrict__ g_eid,
-                                                      const double* __restrict__ g_ts, int N,
-                                                      const int32_t* __restrict__ q_node,
-                                                      const double* __restrict__ q_t, int n_roots, int k,
-                                                      int32_t* __restrict__ out_nbr, int32_t* __restrict__ out_eid,
-                                                      double* __restrict__ out_ts, int32_t* __restrict__ out_cnt,
-                                                      const BatchSet* __restrict__ bsp, int32_t* __restrict__ root_node,
-                                                      double* __restrict__ root_t, int32_t* __restrict__ slot_gid,
-                                                      int32_t* __restrict__ slot_node, unsigned long long* winkey,
-                                                      UniqPtrs uq) {
+__device__ __forceinline__ void sample_block(const SampleArgs& a, const BatchSet& bs, unsigned long long ep, int block) {
   __shared__ int blk_count, blk_base;
+  const UniqPtrs& uq = a.uq;
+  const int N = a.N, n_roots = a.n_roots, k = a.k;
   const int lane = threadIdx.x & 63;
-  const int r = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+  // (uniform per wavefront: the batch descriptors are then read with scalar loads)
+  const int r = block * (blockDim.x >> 6) + __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
   const bool active = r < n_roots;   // per wave; in the fused form idle waves still join the block barriers
   if (!FUSED && !active) return;
   if (FUSED) {
@@ -32,44 +29,42 @@ __global__ __launch_bounds__(1024) void sample_kernel(const int64_t* __restrict_
     __syncthreads();
   }
   int claim = -1;   // (replica, node) this lane wants a row for
-  unsigned long long ep = 0ull;
   if (active) {
     int node, rep_base = 0, root_gid = -1;
     double t;
     if (FUSED) {
-      const BatchSet& bs = *bsp;
       int b = 0;
       while (b + 1 < bs.nb && r >= 3 * bs.b[b + 1].ev_off) ++b;
-      const BatchDesc bd = bs.b[b];
-      const int local = r - 3 * bd.ev_off;
-      const int role = local / bd.n, i = local - role * bd.n;
-      node = (role == 0 ? bd.src : role == 1 ? bd.dst : bd.neg)[i];
-      t = bd.t[i];
-      rep_base = bd.replica * N;
-      ep = *uq.epoch;
+      const int ev_off = bs.b[b].ev_off, n = bs.b[b].n;
+      const int local = r - 3 * ev_off;
+      const int role = local / n, i = local - role * n;
+      const int32_t* nodes = role == 0 ? bs.b[b].src : role == 1 ? bs.b[b].dst : bs.b[b].neg;
+      node = nodes[i];
+      t = bs.b[b].t[i];
+      rep_base = bs.b[b].replica * N;
       root_gid = rep_base + node;
       if (lane == 0) {
-        root_node[r] = node;
-        root_t[r] = t;
-        slot_gid[r] = root_gid;
-        slot_node[r] = node;
-        if (role < 2) atomicMax(winkey + root_gid, wb_key(ep, bd.ev_off + i, role));
+        a.root_node[r] = node;
+        a.root_t[r] = t;
+        a.slot_gid[r] = root_gid;
+        a.slot_node[r] = node;
+        if (role < 2) atomicMax(a.winkey + root_gid, wb_key(ep, ev_off + i, role));
       }
     } else {
-      node = q_node[r];
-      t = q_t[r];
+      node = a.q_node[r];
+      t = a.q_t[r];
     }
     long long base = 0, lo = 0, hi = 0;
     if (node >= 0 && node < N) {
-      base = indptr[node];
+      base = a.indptr[node];
       lo = base;
-      hi = indptr[node + 1];
+      hi = a.indptr[node + 1];
     }
     // invariant: entries before lo are < t; entry hi (if inside the list) is >= t; answer in [lo, hi]
     while (hi - lo > 64) {
       const long long step = (hi - lo + 63) / 64;
       const long long idx = lo + (long long)(lane + 1) * step - 1;
-      const bool below = idx < hi && g_ts[idx] < t;
+      const bool below = idx < hi && a.g_ts[idx] < t;
       const int nb = __popcll(__ballot(below));
       const long long nlo = lo + (long long)nb * step;
       const long long nhi = lo + (long long)(nb + 1) * step - 1;
@@ -78,29 +73,29 @@ __global__ __launch_bounds__(1024) void sample_kernel(const int64_t* __restrict_
     }
     {
       const long long idx = lo + lane;
-      const bool below = idx < hi && g_ts[idx] < t;
+      const bool below = idx < hi && a.g_ts[idx] < t;
       lo += __popcll(__ballot(below));
     }
     const long long pos = lo;  // first entry with time >= t
     const long long avail = pos - base;
     const int cnt = avail < k ? (int)avail : k;
-    if (lane == 0) out_cnt[r] = cnt;
+    if (lane == 0) a.out_cnt[r] = cnt;
     int nb = -1, ei = -1;
     double ts = 0.0;
     if (lane < cnt) {
       const long long idx = pos - 1 - lane;
-      nb = g_nbr[idx];
-      ei = g_eid[idx];
-      ts = g_ts[idx];
+      nb = a.g_nbr[idx];
+      ei = a.g_eid[idx];
+      ts = a.g_ts[idx];
     }
     if (lane < k) {
       const size_t o = (size_t)r * k + lane;
-      out_nbr[o] = nb;
-      out_eid[o] = ei;
-      out_ts[o] = ts;
+      a.out_nbr[o] = nb;
+      a.out_eid[o] = ei;
+      a.out_ts[o] = ts;
       if (FUSED) {
-        slot_gid[(size_t)n_roots + o] = nb >= 0 ? rep_base + nb : -1;
-        slot_node[(size_t)n_roots + o] = nb;
+        a.slot_gid[(size_t)n_roots + o] = nb >= 0 ? rep_base + nb : -1;
+        a.slot_node[(size_t)n_roots + o] = nb;
       }
     }
     // lanes 0 .. k-1 claim their neighbour, lane k (k < 64) the root itself
@@ -128,25 +123,61 @@ __global__ __launch_bounds__(1024) void sample_kernel(const int64_t* __restrict_
   }
 }
 
-constexpr int SAMPLE_WAVES = 16;   // roots per block
+// plain sampling of the caller's queries
+__global__ __launch_bounds__(256) void sample_kernel(SampleArgs a, BatchSet none) { sample_block<false>(a, none, 0ull, blockIdx.x); }
 
-void sample_roots(tgnn_ctx* ctx, const tgnn_graph* g, int n_roots, hipStream_t s) {
-  if (n_roots <= 0) return;
+// The first launch of a training step: sampling blocks, then the prologue's blocks (see HeadArgs).
+__global__ __launch_bounds__(1024) void step_head_kernel(HeadArgs h) {
+  if ((int)blockIdx.x < h.sample_blocks) {
+    // the epoch counter still holds the previous step's value: nothing writes it during this launch
+    sample_block<true>(h.sa, h.pa.bs, *h.sa.uq.epoch + 1ull, blockIdx.x);
+    return;
+  }
+  const int pb = blockIdx.x - h.sample_blocks;
+  const int y = pb / h.pro_bx;
+  prologue_block(h.pa, pb - y * h.pro_bx, h.pro_bx, y);
+}
+
+static SampleArgs sample_args(const Dims& d, const tgnn_graph* g, int n_roots) {
+  SampleArgs a;
+  memset(&a, 0, sizeof(a));
+  a.indptr = g->indptr; a.g_nbr = g->nbr; a.g_eid = g->eid; a.g_ts = g->ts;
+  a.N = d.N; a.n_roots = n_roots; a.k = d.k;
+  return a;
+}
+
+void head_fill(tgnn_ctx* ctx, const tgnn_graph* g, int n_roots, const tgnn_params* p, const BatchSet* bs,
+               const SgdSet* sgd, const SgdSet* zero, float* loss, HeadArgs& h) {
   const Dims& d = ctx->d;
   Ws& w = ctx->w;
-  UniqPtrs uq{w.utag, w.epoch, w.uidx, w.ucount, w.ulist, w.ucnt};
-  hipLaunchKernelGGL(sample_kernel<true>, dim3((n_roots + SAMPLE_WAVES - 1) / SAMPLE_WAVES), dim3(64 * SAMPLE_WAVES), 0, s, g->indptr, g->nbr, g->eid, g->ts, d.N,
-                     nullptr, nullptr, n_roots, d.k, w.nbr, w.neid, w.nts, w.cnt, w.bs_dev, w.root_node, w.root_t,
-                     w.slot_gid, w.slot_node, w.winkey, uq);
+  h.sa = sample_args(d, g, n_roots);
+  h.sa.out_nbr = w.nbr; h.sa.out_eid = w.neid; h.sa.out_ts = w.nts; h.sa.out_cnt = w.cnt;
+  h.sa.root_node = w.root_node; h.sa.root_t = w.root_t; h.sa.slot_gid = w.slot_gid; h.sa.slot_node = w.slot_node;
+  h.sa.winkey = w.winkey;
+  h.sa.uq = UniqPtrs{w.utag, w.epoch, w.uidx, w.ucount, w.ulist, w.ucnt};
+  h.sample_blocks = (n_roots + SAMPLE_WAVES - 1) / SAMPLE_WAVES;
+  h.pro_bx = 24;   // 24 blocks of 1024 threads per grid row of the prologue
+  prologue_fill(ctx, p, bs, sgd, zero, loss, h.pa);
+  h.pa.head_of_step = 1;
+  h.pa.ucount_next = w.ucount_pair + (w.ucount == w.ucount_pair ? 1 : 0);
+}
+
+dim3 head_grid(const HeadArgs& h) { return dim3(h.sample_blocks + h.pro_bx * (h.pa.n_pack + h.pa.zero.cnt + 1)); }
+void* head_func() { return reinterpret_cast<void*>(step_head_kernel); }
+
+void step_head(const HeadArgs& h, hipStream_t s) {
+  hipLaunchKernelGGL(step_head_kernel, head_grid(h), dim3(64 * SAMPLE_WAVES), 0, s, h);
 }
 
 void sample_recent(const Dims& d, const tgnn_graph* g, const int32_t* node, const double* t, int n_roots,
                    int32_t* out_nbr, int32_t* out_eid, double* out_ts, int32_t* out_cnt, hipStream_t s) {
   if (n_roots <= 0) return;
-  UniqPtrs uq{};
-  hipLaunchKernelGGL(sample_kernel<false>, dim3((n_roots + 3) / 4), dim3(256), 0, s, g->indptr, g->nbr, g->eid, g->ts, d.N,
-                     node, t, n_roots, d.k, out_nbr, out_eid, out_ts, out_cnt, nullptr, nullptr, nullptr, nullptr, nullptr,
-                     nullptr, uq);
+  SampleArgs a = sample_args(d, g, n_roots);
+  a.q_node = node; a.q_t = t;
+  a.out_nbr = out_nbr; a.out_eid = out_eid; a.out_ts = out_ts; a.out_cnt = out_cnt;
+  BatchSet none;
+  memset(&none, 0, sizeof(none));
+  hipLaunchKernelGGL(sample_kernel, dim3((n_roots + 3) / 4), dim3(256), 0, s, a, none);
 }
 
 }  // namespace tgnn

@@ -91,7 +91,7 @@ static void layout(const Dims& d, Ws& w, Bump& b) {
   w.winkey = b.take<unsigned long long>((size_t)d.nrep * d.N);
   w.epoch = b.take<unsigned long long>(1);
   const size_t NG = (size_t)d.nrep * d.N, U = d.maxU;
-  w.utag = b.take<unsigned long long>(NG); w.uidx = b.take<int32_t>(NG); w.ucount = b.take<int32_t>(1);
+  w.utag = b.take<unsigned long long>(NG); w.uidx = b.take<int32_t>(NG); w.ucount_pair = b.take<int32_t>(2); w.ucount = w.ucount_pair;
   w.ulist = b.take<int32_t>(U); w.slot_row = b.take<int32_t>(S); w.ucnt = b.take<int32_t>(U);
   w.rowptr = b.take<int32_t>(U + 1); w.cursor = b.take<int32_t>(U); w.sorted = b.take<int32_t>(S);
   w.sorted_row = b.take<int32_t>(S); w.sort_total = b.take<int32_t>(1);
@@ -656,6 +656,11 @@ int32_t tgnn_train_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
   ctx->last_attn_roots = -1;
 
   // the legacy default stream (NULL) cannot be captured
+  // Training steps alternate between two row counters: each clears the one the next step will use (nothing
+  // else could do that before the first launch, which already counts rows).
+  ctx->w.ucount = ctx->w.ucount_pair + ctx->step_parity;
+  const int parity = ctx->step_parity;
+  ctx->step_parity ^= 1;
   Profiler& pr = ctx->prof;
   pr.active = pr.mask != 0 && pr.calls++ % pr.every == 0 ? pr.mask : 0;
   bool use_graph = (ctx->cfg.flags & TGNN_FLAG_NO_GRAPH) == 0 && pr.active == 0 && s != nullptr;
@@ -678,7 +683,7 @@ int32_t tgnn_train_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
     for (int i = 0; i < 19; ++i) { key.ptr[q++] = pp[i]; key.ptr[q++] = gg[i]; }
     key.ptr[q++] = out_loss; key.ptr[q++] = out_logits; key.ptr[q++] = out_winner; key.ptr[q++] = s;
     for (int b = 0; b < bs.nb; ++b) { key.n[b] = bs.b[b].n; key.rep[b] = bs.b[b].replica; }
-    key.nb = bs.nb; key.lr = lr;
+    key.nb = bs.nb; key.lr = lr; key.parity = parity;
   }
   StepGraph* hit = nullptr;
   StepGraph* victim = &ctx->graphs[0];
@@ -717,19 +722,19 @@ int32_t tgnn_train_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
     victim->used = true; victim->key = key; victim->graph = graph; victim->exec = exec; victim->prologue_node = roots[0];
     hit = victim;
   } else {
-    // same launches as the recorded step; only the prologue's argument block (batch descriptors) is new
+    // same launches as the recorded step; only the first launch's argument block (batch descriptors) is new
     SgdSet sgd_set, zero_set_;
     fill_param_set(d, p, grads, 2, sgd_set);
     fill_param_set(d, grads, nullptr, 0, zero_set_);
     const bool overwrite = (ctx->cfg.flags & TGNN_FLAG_OVERWRITE_GRADS) != 0;
-    PrologueArgs pa;
-    prologue_fill(ctx, p, &bs, lr != 0.0f ? &sgd_set : nullptr, overwrite ? &zero_set_ : nullptr, out_loss, pa);
-    void* kargs[1] = {&pa};
+    HeadArgs h;
+    head_fill(ctx, g, 3 * bs.total, p, &bs, lr != 0.0f ? &sgd_set : nullptr, overwrite ? &zero_set_ : nullptr, out_loss, h);
+    void* kargs[1] = {&h};
     hipKernelNodeParams np;
     memset(&np, 0, sizeof(np));
-    np.func = prologue_func();
-    np.gridDim = prologue_grid(pa);
-    np.blockDim = dim3(256);
+    np.func = head_func();
+    np.gridDim = head_grid(h);
+    np.blockDim = dim3(64 * SAMPLE_WAVES);
     np.kernelParams = kargs;
     TGNN_HIP_CHECK(hipGraphExecKernelNodeSetParams(hit->exec, hit->prologue_node, &np));
   }
@@ -751,11 +756,12 @@ static int enqueue_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
   fill_param_set(d, p, grads, 2, sgd_set);  // time_w, time_b stay frozen
   fill_param_set(d, grads, nullptr, 0, zero_set_);
   const bool overwrite = (ctx->cfg.flags & TGNN_FLAG_OVERWRITE_GRADS) != 0;
-  tm.begin(0);
-  prologue(ctx, p, &bs, lr != 0.0f ? &sgd_set : nullptr, overwrite ? &zero_set_ : nullptr, out_loss, s);
-  tm.end(0);
   tm.begin(2);
-  sample_roots(ctx, g, R, s);
+  {  // first launch: the sampler's blocks, then the prologue's
+    HeadArgs h;
+    head_fill(ctx, g, R, p, &bs, lr != 0.0f ? &sgd_set : nullptr, overwrite ? &zero_set_ : nullptr, out_loss, h);
+    step_head(h, s);
+  }
   tm.end(2);
   // UPDT once per distinct (replica, node) among the root and supporting nodes, from the pre-batch state
   const int U = S < d.maxU ? S : d.maxU;   // launch bound; the actual row count is *w.ucount on the device
@@ -771,6 +777,7 @@ static int enqueue_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
   a.time_w = p->time_w; a.time_b = p->time_b;
   a.n_slots = U; a.dm = d.dm; a.dt = d.dt; a.de = d.de;
   a.map = sort_args(ctx, S);   // the slot -> row map rides along
+  a.epoch_bump = w.epoch;      // the first launch worked with epoch + 1; from here on that is the epoch
   tm.begin(3);
   gather_rows(a, s);
   tm.end(3);

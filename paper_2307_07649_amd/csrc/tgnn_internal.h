@@ -53,6 +53,8 @@ struct Ws {
   // distinct (replica, node) rows of the step
   unsigned long long* utag;                    // [nrep*N] epoch of the last step that claimed the node
   int32_t *uidx, *ucount, *ulist;              // [nrep*N] row of a claimed node; [1] number of rows; [maxU] row -> gid
+  int32_t* ucount_pair;                        // [2] ucount points at one of them: training steps alternate, and
+                                               // each clears the counter of the next one
   int32_t *slot_row, *ucnt, *rowptr, *cursor, *sorted;  // [S] slot -> row; [maxU] slots per row; CSR of slots by row
   int32_t *sorted_row, *sort_total;            // [S] row of every sorted slot; [1] number of sorted slots
   float* ds_row;                               // [maxS, ldh] gradient reaching s' per row
@@ -104,7 +106,7 @@ constexpr int MAX_STEP_GRAPHS = 8;
 struct StepKey {
   const void* ptr[64];
   int32_t n[TGNN_MAX_BATCHES], rep[TGNN_MAX_BATCHES];
-  int32_t nb;
+  int32_t nb, parity;
   float lr;
 };
 struct StepGraph {
@@ -131,6 +133,7 @@ struct tgnn_ctx {
   tgnn::Ws w;
   int last_attn_roots;
   int device;
+  int step_parity = 0;             // which of the two row counters the next training step uses
 };
 
 namespace tgnn {
@@ -308,6 +311,11 @@ struct PrologueArgs {
   int dO, dq, dx, dt;
   float* q_part;        // cleared (q_part_n floats)
   int q_part_n;
+  // head_of_step: this runs inside the first launch of a training step, beside the sampler.  The sampler then
+  // works with epoch + 1 and with a row counter that is already zero, so neither is touched here; instead the
+  // row counter of the next step (ucount_next) is cleared.  Otherwise: epoch += 1, *ucount = 0.
+  int head_of_step;
+  int32_t* ucount_next;
 };
 void prologue_fill(tgnn_ctx* ctx, const tgnn_params* p, const BatchSet* bs, const SgdSet* sgd, const SgdSet* zero,
                    float* loss, PrologueArgs& pa);
@@ -329,9 +337,38 @@ struct UniqPtrs {
   const unsigned long long* epoch;
   int32_t *uidx, *ucount, *ulist, *ucnt;
 };
-// Fused step: roots of every batch (node, time, slot ids), write-back arbitration marks, neighbour sampling and
-// row claims in one launch; results go to the workspace.
-void sample_roots(tgnn_ctx* ctx, const tgnn_graph* g, int n_roots, hipStream_t s);
+// The first launch of a training step: roots of every batch (node, time, slot ids), write-back arbitration marks,
+// neighbour sampling and row claims (blocks 0 .. sample_blocks - 1, one wavefront per root, 1024 threads per
+// block), and, in the blocks after those, everything the prologue does (it depends on nothing the sampler does
+// and the other way round: the sampler takes the batch descriptors from the argument block and uses epoch + 1,
+// which a later launch makes official).
+struct SampleArgs {
+  const int64_t* indptr;
+  const int32_t *g_nbr, *g_eid;
+  const double* g_ts;
+  int N, n_roots, k;
+  const int32_t* q_node;   // caller's queries (plain sampling only)
+  const double* q_t;
+  int32_t *out_nbr, *out_eid;
+  double* out_ts;
+  int32_t* out_cnt;
+  int32_t* root_node;
+  double* root_t;
+  int32_t *slot_gid, *slot_node;
+  unsigned long long* winkey;
+  UniqPtrs uq;
+};
+struct HeadArgs {
+  SampleArgs sa;
+  int sample_blocks, pro_bx;   // pro_bx: prologue blocks per grid row
+  PrologueArgs pa;
+};
+constexpr int SAMPLE_WAVES = 16;   // roots per block in the first launch of a step
+void head_fill(tgnn_ctx* ctx, const tgnn_graph* g, int n_roots, const tgnn_params* p, const BatchSet* bs,
+               const struct SgdSet* sgd, const struct SgdSet* zero, float* loss, HeadArgs& h);
+dim3 head_grid(const HeadArgs& h);
+void* head_func();
+void step_head(const HeadArgs& h, hipStream_t s);
 // Plain sampling of caller-provided queries.
 void sample_recent(const Dims& d, const tgnn_graph* g, const int32_t* node, const double* t, int n_roots,
                    int32_t* out_nbr, int32_t* out_eid, double* out_ts, int32_t* out_cnt, hipStream_t s);
@@ -421,6 +458,7 @@ struct GatherArgs {
   const float *time_w, *time_b;
   int n_slots, dm, dt, de;
   SortArgs map;             // map.ucnt != NULL: the first blocks of the launch run the slot -> row map instead
+  unsigned long long* epoch_bump;   // may be NULL: *epoch_bump += 1 (the step's epoch becomes official here)
 };
 void gather_rows(const GatherArgs& a, hipStream_t s);
 
