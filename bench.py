@@ -30,8 +30,9 @@ MEASURED_TRAFFIC_BYTES = {"C1": {"kv_projection": 40.9e6, "assemble_ce": 33.8e6}
 STAGE_NAMES = ["(unused)", "(unused)", "roots + sample + distinct-node rows + prologue (pack weights, clear), one launch",
                "gather + time-encode (GRU input) + slot-to-row map", "GRU input + hidden projections (MFMA, one launch)", "(unused)",
                "(unused)", "GRU gates + slot-sort scan + per-slot attention input {e | Phi} (gather), one launch", "K/V projection of the slots (MFMA)",
-               "per-node projections K, V, q, merge (MFMA)", "softmax attention + slot-sort fill", "merge layer (MFMA)",
-               "decoder forward + loss", "decoder backward", "attention backward (MFMA + softmax)",
+               "per-node projections K, V, q, merge (MFMA)", "softmax attention + slot-sort fill", "merge layer (MFMA; only when the root chain does not fit)",
+               "root chain: merge layer, decoder + loss, their backward down to the attention output (MFMA, one launch)",
+               "decoder backward (only when the root chain does not fit)", "attention backward (softmax)",
                "per-node gradient sums; node projections + GRU gates backward with the keys' time-encoding gradients (one launch)",
                "all weight gradients (grouped MFMA GEMM)", "time-encoding gradients of the mails (MFMA) + write-back scatter + SGD (one launch)",
                "empty event bracket", "(unused)"]

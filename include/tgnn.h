@@ -211,8 +211,11 @@ int32_t tgnn_zero_params(tgnn_ctx* ctx, tgnn_params* g, void* stream);
  *  3 gather + time-encode (GRU input; with the slot -> row map)   4 GRU input and hidden projections (MFMA,
  *  one launch)   5 (unused)   6 (unused)
  *  7 GRU gates (with the scan of the slot sort) + per-slot attention input {e | Phi}, one launch   8 K/V projection of the slots (MFMA)   9 per-node projections (MFMA)
- *  10 softmax attention (with the fill pass of the slot sort)   11 merge layer   12 decoder forward + loss   13 decoder backward
- *  14 attention backward (data-gradient GEMM + softmax)
+ *  10 softmax attention (with the fill pass of the slot sort)
+ *  12 root chain: merge layer, decoder + loss and their backward pass down to the gradient of the attention
+ *  output, one launch (d_mem a multiple of 4 and <= 128; otherwise 11 merge layer, 12 decoder forward + loss,
+ *  13 decoder backward, and the attention-output gradient GEMM in 14)
+ *  14 attention backward (softmax)
  *  15 per-node gradient sums (with the gradients through the query's Phi(0)) + node projections backward with GRU
  *  gates backward, and the product onto the keys' time encoding with its reduction (one launch)
  *  16 all weight gradients (one grouped MFMA GEMM)   17 time-encoding gradient of the mails (GEMM with the

@@ -194,7 +194,7 @@ static void gru_forward(tgnn_ctx* ctx, const tgnn_params* p, int n, hipStream_t 
 // (NULL: slot = row).  n_rows_dev (may be NULL): device-side row count.
 static void attn_forward(tgnn_ctx* ctx, const tgnn_params* p, int R, int n_rows, const int* n_rows_dev,
                          const int32_t* slot_row, const int32_t* cnt, StageTimer* tm, hipStream_t s,
-                         const SortArgs& fill = SortArgs()) {
+                         const SortArgs& fill = SortArgs(), bool with_merge = true) {
   const Dims& d = ctx->d; Ws& w = ctx->w;
   const int RK = R * d.k;
   if (tm) tm->begin(9);
@@ -206,6 +206,10 @@ static void attn_forward(tgnn_ctx* ctx, const tgnn_params* p, int R, int n_rows,
   gemm_nt(w.CE, d.ldce, w.Wce, d.ldce, nullptr, w.KV, d.ldkv, RK, 2 * d.dO, d.ldce, d.ldkv, false, s, nullptr, kv_add);
   if (tm) { tm->end(8); tm->begin(10); }
   attn_core_fwd(d, R, w.P + d.ldkv, d.ldp, slot_row, w.KV, d.ldkv, cnt, w.prob, w.Omat, d.ldh, s, fill);
+  if (!with_merge) {   // the caller's next launch holds the merge layer
+    if (tm) tm->end(10);
+    return;
+  }
   if (tm) { tm->end(10); tm->begin(11); }
   RowAdd m_add;
   m_add.src = w.P + d.ldkv + d.dO; m_add.ld = d.ldp; m_add.index = slot_row; m_add.row0 = 0;
@@ -238,11 +242,12 @@ static NtProblem keys_phi_problem(tgnn_ctx* ctx, const tgnn_params* p, tgnn_para
 // phi_now: launch the product onto the keys' time encoding here; otherwise the caller launches it (together
 // with another one).
 static void attn_backward(tgnn_ctx* ctx, tgnn_params* g, const tgnn_params* p, int R, const int32_t* slot_row,
-                          const int32_t* cnt, TnBatch& tn, Side& side, bool phi_now, hipStream_t s) {
+                          const int32_t* cnt, TnBatch& tn, Side& side, bool phi_now, hipStream_t s,
+                          bool have_dOmat = false) {
   const Dims& d = ctx->d; Ws& w = ctx->w;
   const int RK = R * d.k;
   tn.add(w.dz, d.ldh, w.Omat, d.ldh, R, d.dO, d.dO, single_out(g->wo, d.dO + d.dx, nullptr));
-  gemm_nt(w.dz, d.ldh, w.WoT_o, d.ldh, nullptr, w.dOmat, d.ldh, R, d.dO, d.ldh, d.ldh, false, s);
+  if (!have_dOmat) gemm_nt(w.dz, d.ldh, w.WoT_o, d.ldh, nullptr, w.dOmat, d.ldh, R, d.dO, d.ldh, d.ldh, false, s);
   attn_core_bwd(d, R, w.P + d.ldkv, d.ldp, slot_row, w.KV, d.ldkv, cnt, w.prob, w.dOmat, d.ldh, w.dq, w.dKV, w.q_part, s);
   if (d.de + d.dt > 0) {
     OutMap kv;
@@ -805,33 +810,46 @@ static int enqueue_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
   assemble_ce(aa, s);
   tm.end(7);
   // (the fill pass of the slot sort, needed by the backward pass only, rides in the softmax-attention launch)
-  attn_forward(ctx, p, R, U, w.ucount, w.slot_row, w.cnt, &tm, s, sort_args(ctx, S));
+  // Merge layer, decoder + loss and their backward pass down to the attention output are local to an event's
+  // three roots: one launch when the layer width allows it.
+  const bool chain = root_chain_fits(d);
+  attn_forward(ctx, p, R, U, w.ucount, w.slot_row, w.cnt, &tm, s, sort_args(ctx, S), !chain);
 
-  // decoder + loss (also produces d loss / d hidden)
   tm.begin(12);
-  gemm_nt(w.z, d.ldh, w.Wdec_p, d.ldh, nullptr, w.Pdec, d.ldkv, R, 2 * d.dO, d.ldh, 2 * d.dO, false, s);
-  decoder_pairs(d, w.bs_dev, bs.total, w.Pdec, d.ldkv, p->dec_b1, p->dec_w2, p->dec_b2, w.logits, out_loss, w.h1, w.dPdec,
-                grads->dec_w2, grads->dec_b2, s);
+  if (chain) {
+    ChainArgs ca;
+    ca.dO = d.dO; ca.ldh = d.ldh; ca.ldkv = d.ldkv; ca.ldp = d.ldp;
+    ca.Omat = w.Omat; ca.P_o = w.P + d.ldkv + d.dO; ca.slot_row = w.slot_row;
+    ca.Wo_o = w.Wo_o; ca.Wdec_p = w.Wdec_p; ca.WdecT = w.WdecT; ca.WoT_o = w.WoT_o;
+    ca.b1 = p->dec_b1; ca.w2 = p->dec_w2; ca.b2 = p->dec_b2;
+    ca.z = w.z; ca.h1 = w.h1; ca.logits = w.logits; ca.dPdec = w.dPdec; ca.dz = w.dz; ca.dOmat = w.dOmat;
+    ca.loss = out_loss; ca.g_w2 = grads->dec_w2; ca.g_b2 = grads->dec_b2;
+    root_chain(ca, bs, s);
+  } else {   // decoder + loss (also produces d loss / d hidden)
+    gemm_nt(w.z, d.ldh, w.Wdec_p, d.ldh, nullptr, w.Pdec, d.ldkv, R, 2 * d.dO, d.ldh, 2 * d.dO, false, s);
+    decoder_pairs(d, w.bs_dev, bs.total, w.Pdec, d.ldkv, p->dec_b1, p->dec_w2, p->dec_b2, w.logits, out_loss, w.h1, w.dPdec,
+                  grads->dec_w2, grads->dec_b2, s);
+  }
   tm.end(12);
 
   // Backward.  The data-gradient chain stays on the caller's stream; the weight-gradient GEMMs are queued and
   // leave in one launch at the end (side-stream mode: those known after the attention backward leave there,
   // on the side stream).
-  tm.begin(13);
+  if (!chain) tm.begin(13);
   OutMap dec;
   memset(&dec, 0, sizeof(dec));
   dec.p[0][0] = grads->dec_ws; dec.p[1][0] = grads->dec_wd; dec.ld[0][0] = dec.ld[1][0] = d.dO;
   dec.n_split = d.dO; dec.k_split = 1 << 30; dec.bias[1] = grads->dec_b1;   // every pair is in one W_d half
   TnBatch tn;
   tn.add(w.dPdec, d.ldkv, w.z, d.ldh, R, 2 * d.dO, d.dO, dec);
-  {  // dz, gated by the ReLU of the merge layer
+  if (!chain) {  // dz, gated by the ReLU of the merge layer
     RowAdd gate;
     gate.gate = w.z; gate.ld_gate = d.ldh;
     gemm_nt(w.dPdec, d.ldkv, w.WdecT, d.ldkv, nullptr, w.dz, d.ldh, R, d.dO, d.ldkv, d.ldh, false, s, nullptr, gate);
+    tm.end(13);
   }
-  tm.end(13);
   tm.begin(14);
-  attn_backward(ctx, grads, p, R, w.slot_row, w.cnt, tn, side, false, s);
+  attn_backward(ctx, grads, p, R, w.slot_row, w.cnt, tn, side, false, s, chain);
   tm.end(14);
   tm.begin(15);
   // per-row sum of the slot gradients reaching the per-node projections (the query's Phi(0) gradients ride along)

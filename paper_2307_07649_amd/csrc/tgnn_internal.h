@@ -499,6 +499,23 @@ void mask_dz(int R, int dO, const float* dz_in, int p_in, const float* z, int ld
 void attn_dx_out(int R, int RK, int dm, const float* ds_row, int ldh, float* d_x_root, float* d_x_nbr, hipStream_t s);
 void zero_f32(float* p, int n, hipStream_t s);
 
+// ---- k_rootchain.hip ----------------------------------------------------------------
+// Merge layer, decoder with loss, and their backward pass down to the gradient of the attention output, for
+// the roots of a step in one launch.
+struct ChainArgs {
+  int nb, n[TGNN_MAX_BATCHES];   // batch sizes (events of batch b follow those of the batches before it); set by root_chain
+  int dO, ldh, ldkv, ldp;
+  const float* Omat;          // [R, ldh] attention output
+  const float* P_o;           // node part of the merge layer (bias included), row pitch ldp
+  const int32_t* slot_row;    // root slot -> node row (NULL: identity)
+  const float *Wo_o, *Wdec_p, *WdecT, *WoT_o;   // packed weight blocks
+  const float *b1, *w2, *b2;
+  float *z, *h1, *logits, *dPdec, *dz, *dOmat;
+  float *loss, *g_w2, *g_b2;
+};
+bool root_chain_fits(const Dims& d);
+void root_chain(ChainArgs a, const BatchSet& bs_host, hipStream_t s);
+
 // ---- k_writeback.hip ----------------------------------------------------------------
 void writeback_mark(const Dims& d, const BatchSet* bs, int total, unsigned long long* winkey,
                     const unsigned long long* epoch, hipStream_t s);

@@ -58,6 +58,11 @@ def test_launch_modes_agree_with_the_oracle(own_stream, flags):
     dict(n_nodes=40, E=900, d_mem=24, d_time=10, d_edge=0, d_static=0, n_heads=3, k=10, batch=100, ties=True),
     dict(n_nodes=300, E=800, d_mem=100, d_time=100, d_edge=186, d_static=0, n_heads=2, k=10, batch=64),
     dict(n_nodes=64, E=640, d_mem=32, d_time=16, d_edge=8, d_static=12, n_heads=4, k=32, batch=64),
+    # widths the one-launch root chain does not take (not a multiple of 4; wider than 128): separate launches
+    dict(n_nodes=45, E=400, d_mem=18, d_time=6, d_edge=5, d_static=0, n_heads=3, k=4, batch=41),
+    dict(n_nodes=60, E=300, d_mem=132, d_time=12, d_edge=7, d_static=0, n_heads=2, k=5, batch=50),
+    # the root chain at its widest (8 column blocks), ragged 16-event tiles
+    dict(n_nodes=60, E=300, d_mem=128, d_time=12, d_edge=7, d_static=3, n_heads=4, k=5, batch=50),
 ])
 def test_odd_shapes(shape):
     P = custom_problem(**shape)
