@@ -70,8 +70,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, (TN <= 5
   if (row_tile * BM >= M) return;   // uniform for the workgroup, before any barrier
   constexpr int A_PER = BM * 8 / 256, B_F4 = BN * 8;  // float4 loads per stage and thread
   constexpr int B_PER = (B_F4 + 255) / 256;
-  __shared__ __attribute__((aligned(16))) float As[2][BM * NT_P];
-  __shared__ __attribute__((aligned(16))) float Bs[2][BN * NT_P];
+  // two stage buffers of A and of B; the finished tile is staged in the same memory for its row-wise stores
+  __shared__ __attribute__((aligned(16))) float smem[2 * (BM + BN) * NT_P];
+  float (*As)[BM * NT_P] = reinterpret_cast<float (*)[BM * NT_P]>(smem);
+  float (*Bs)[BN * NT_P] = reinterpret_cast<float (*)[BN * NT_P]>(smem + 2 * BM * NT_P);
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int li = lane & 15, lg = lane >> 4;
@@ -236,55 +238,115 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, (TN <= 5
     return;
   }
   if (gb.dgi != nullptr) {
-    // GRU gates backward epilogue: acc is the gradient reaching s' = (1 - z) n + z h.
+    // GRU gates backward epilogue: acc is the gradient reaching s' = (1 - z) n + z h.  All loads first, then
+    // arithmetic and stores: a load between two stores would wait for the earlier store to complete.
+    bool hs[4];
 #pragma unroll
-    for (int b = 0; b < TN; ++b) {
-      const int col = n0 + b * 16 + li;
-      if (col >= N) continue;
+    for (int v = 0; v < 4; ++v) {
+      const int row = m0 + wave * 16 + lg * 4 + v;
+      hs[v] = row < M && gb.has[row] != 0;
+    }
+    constexpr int GB = TN < 2 ? TN : 2;   // column blocks per group (bounds the registers of wide tiles)
 #pragma unroll
-      for (int v = 0; v < 4; ++v) {
-        const int row = m0 + wave * 16 + lg * 4 + v;
-        if (row >= M) continue;
-        float drp = 0.f, dzp = 0.f, dnp = 0.f, dnr = 0.f;
-        if (gb.has[row]) {
-          const float ds = acc[b][v];
-          const float* g = gb.gates + (size_t)row * 4 * gb.ldh;
-          const float r = g[col], z = g[gb.ldh + col], nn = g[2 * gb.ldh + col], hn = g[3 * gb.ldh + col];
-          const float h = gb.Hm[(size_t)row * gb.ldh + col];
-          const float dn = ds * (1.0f - z);
-          const float dz = ds * (h - nn);
-          dnp = dn * (1.0f - nn * nn);
-          const float dr = dnp * hn;
-          dzp = dz * z * (1.0f - z);
-          drp = dr * r * (1.0f - r);
-          dnr = dnp * r;
+    for (int b0 = 0; b0 < TN; b0 += GB) {
+      float gr[GB][4], gz[GB][4], gn[GB][4], ghn[GB][4], gh[GB][4];
+#pragma unroll
+      for (int bb = 0; bb < GB; ++bb) {
+        const int col = n0 + (b0 + bb) * 16 + li;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+          const int row = m0 + wave * 16 + lg * 4 + v;
+          gr[bb][v] = gz[bb][v] = gn[bb][v] = ghn[bb][v] = gh[bb][v] = 0.f;
+          if (b0 + bb < TN && col < N && hs[v]) {
+            const float* g = gb.gates + (size_t)row * 4 * gb.ldh;
+            gr[bb][v] = g[col]; gz[bb][v] = g[gb.ldh + col]; gn[bb][v] = g[2 * gb.ldh + col];
+            ghn[bb][v] = g[3 * gb.ldh + col];
+            gh[bb][v] = gb.Hm[(size_t)row * gb.ldh + col];
+          }
         }
-        float* a = gb.dgi + (size_t)row * gb.ld3;
-        float* h_ = gb.dgh + (size_t)row * gb.ld3;
-        a[col] = drp; a[gb.dm + col] = dzp; a[2 * gb.dm + col] = dnp;
-        h_[col] = drp; h_[gb.dm + col] = dzp; h_[2 * gb.dm + col] = dnr;
+      }
+#pragma unroll
+      for (int bb = 0; bb < GB; ++bb) {
+        const int b = b0 + bb;
+        const int col = n0 + b * 16 + li;
+        if (b >= TN || col >= N) continue;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+          const int row = m0 + wave * 16 + lg * 4 + v;
+          if (row >= M) continue;
+          float drp = 0.f, dzp = 0.f, dnp = 0.f, dnr = 0.f;
+          if (hs[v]) {
+            const float ds = acc[b < TN ? b : 0][v];
+            const float r = gr[bb][v], z = gz[bb][v], nn = gn[bb][v], hn = ghn[bb][v], h = gh[bb][v];
+            const float dn = ds * (1.0f - z);
+            const float dz = ds * (h - nn);
+            dnp = dn * (1.0f - nn * nn);
+            const float dr = dnp * hn;
+            dzp = dz * z * (1.0f - z);
+            drp = dr * r * (1.0f - r);
+            dnr = dnp * r;
+          }
+          float* a = gb.dgi + (size_t)row * gb.ld3;
+          float* h_ = gb.dgh + (size_t)row * gb.ld3;
+          a[col] = drp; a[gb.dm + col] = dzp; a[2 * gb.dm + col] = dnp;
+          h_[col] = drp; h_[gb.dm + col] = dzp; h_[2 * gb.dm + col] = dnr;
+        }
       }
     }
     return;
   }
+  // A lane holds 4 rows x 16-column-strided pieces of the tile: stored from here, every instruction would write
+  // 64-byte pieces of four rows.  The tile goes through LDS instead and leaves as whole rows, 16 bytes per lane.
+  const bool rowwise = (n_store & 3) == 0 && (ldc & 3) == 0 && (reinterpret_cast<size_t>(C) & 15) == 0;
+  constexpr int CP = BN + 4;   // pitch = 4 mod 16 floats: the 4 x 16 lanes of a store hit 64 different banks
+  unsigned closed = 0u;   // bit 4 b + v: the gate of that element is closed (result 0)
+  if (add.gate != nullptr) {   // all gate values first: no load, and no wait for one, between the stores below
+#pragma unroll
+    for (int b = 0; b < TN; ++b) {
+      const int col = n0 + b * 16 + li;
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const int row = m0 + wave * 16 + lg * 4 + v;
+        if (col < N && row < M && !(add.gate[(size_t)row * add.ld_gate + col] > 0.f)) closed |= 1u << (4 * b + v);
+      }
+    }
+  }
 #pragma unroll
   for (int b = 0; b < TN; ++b) {
     const int col = n0 + b * 16 + li;
-    if (col >= n_store) continue;
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
       const int row = m0 + wave * 16 + lg * 4 + v;
-      if (row < M) {
-        float x = 0.f;
-        if (col < N) {
-          x = acc[b][v] + bv[b];
-          x += addv[b][v];
-          if (relu) x = fmaxf(x, 0.f);
-          if (add.gate != nullptr && !(add.gate[(size_t)row * add.ld_gate + col] > 0.f)) x = 0.f;
-        }
-        C[(size_t)row * ldc + col] = x;
+      const bool live = col < N && row < M && ((closed >> (4 * b + v)) & 1u) == 0u;
+      const float x = acc[b][v] + bv[b] + addv[b][v];
+      acc[b][v] = live ? (relu ? fmaxf(x, 0.f) : x) : 0.f;
+    }
+  }
+  if (!rowwise) {
+#pragma unroll
+    for (int b = 0; b < TN; ++b) {
+      const int col = n0 + b * 16 + li;
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const int row = m0 + wave * 16 + lg * 4 + v;
+        if (col < n_store && row < M) C[(size_t)row * ldc + col] = acc[b][v];
       }
     }
+    return;
+  }
+  __syncthreads();   // all waves are done reading the last stage
+#pragma unroll
+  for (int b = 0; b < TN; ++b)
+#pragma unroll
+    for (int v = 0; v < 4; ++v) smem[(wave * 16 + lg * 4 + v) * CP + b * 16 + li] = acc[b][v];
+  __syncthreads();
+  constexpr int F4_ROW = BN / 4, F4_ALL = BM * F4_ROW;
+#pragma unroll
+  for (int u = 0; u < (F4_ALL + 255) / 256; ++u) {
+    const int f = tid + u * 256;
+    const int r = f / F4_ROW, c = (f - r * F4_ROW) * 4;
+    if ((F4_ALL % 256 == 0 || f < F4_ALL) && m0 + r < M && n0 + c < n_store)
+      *reinterpret_cast<floatx4*>(C + (size_t)(m0 + r) * ldc + n0 + c) = *reinterpret_cast<const floatx4*>(&smem[r * CP + c]);
   }
 }
 
