@@ -123,7 +123,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--side-stream", action="store_true", help="let the library fork independent work of a step onto its second stream")
     ap.add_argument("--no-stage-events", action="store_true", help="do not time the two roofline kernels inside the timed region (every step then replays a captured HIP graph)")
-    ap.add_argument("--event-every", type=int, default=8,
+    ap.add_argument("--event-every", type=int, default=16,
                     help="inside the timed region, every N-th step is launched kernel by kernel with HIP events around "
                          "the two roofline kernels; the other steps replay the captured HIP graph (1: every step)")
     ap.add_argument("--calibrate-copy", action="store_true",
