@@ -28,7 +28,7 @@ constexpr int RC_PL = RC_MAXD + 4;       // LDS row pitch: 33 float4 chunks, so 
 // The B operands of a wavefront for one product: a lane's run [16 s + 4 lg, +4) of its weight row for every k
 // slab s; set 0 serves the sources, set 1 the destinations (products whose weights do not depend on the role
 // use set 0 for all three role blocks).  Two such sets alternate: the loads of the next product's weights
-// (they depend on nothing computed here) are issued before the current product's MFMAs.
+// (they depend on nothing computed here) are issued among the current product's MFMAs.
 template <int KS> struct RcSet {
   floatx4 w[2][KS];
 };
@@ -57,6 +57,8 @@ __device__ __forceinline__ void rc_load(RcSet<KS>& set, const RcWho& who, const 
 // PF != 0: the next product's weights (PF == 2: with a separate block for the destinations) are fetched into
 // `next` on the way, one k slab per k slab: the weight rows are 64-byte pieces of scattered lines, which the
 // vector memory path takes about as long to bring in as the MFMAs of a product take.
+// The MFMAs are unconditional (a wavefront without a column block skips the whole call): a wave-uniform `if`
+// around single MFMAs made the compiler branch around each of them and pad with s_nop, at twice the time.
 template <int KS, bool SPLIT, int PF>
 __device__ __forceinline__ void rc_mma(const RcSet<KS>& set, const RcWho& who, const float* T, int li, int lg,
                                        floatx4 (&acc)[RC_UNITS], RcSet<KS>& next, const float* __restrict__ Wn,
@@ -121,6 +123,8 @@ __global__ __launch_bounds__(64 * RC_WAVES) void root_chain_kernel(ChainArgs a) 
   // Order of the first loads (they return in order): the attention output, which the first product waits
   // for; its weights; the node rows of the roots this lane finishes.  Once those rows are known, the node part
   // of the merge layer, needed only after the first product's MFMAs.
+  // (all of a thread's pieces of the attention output are loaded before the first goes to LDS: a load -> store loop
+  // would pay one memory latency per pass)
   constexpr int OM_CHUNKS = 3 * RC_E * (RC_PL / 4), OM_PER = (OM_CHUNKS + 64 * RC_WAVES - 1) / (64 * RC_WAVES);
   floatx4 om[OM_PER];
 #pragma unroll
