@@ -12,7 +12,8 @@ struct AttnShape {
 };
 
 constexpr int ROWS_IN_FLIGHT = 10;  // neighbour rows whose loads are issued together (k = 10: all of them)
-constexpr int MAX_E = 4;            // d_o <= 256: columns lane, lane + 64, lane + 128, lane + 192
+// MAX_E (template parameter of both kernels): columns per lane, lane + 64 u for u < MAX_E; 2 for d_o <= 128, else 4
+// (d_o <= 256)
 
 // LDS floats per wave
 __host__ __device__ inline int attn_lds_floats(int k, int H, int dO) { return dO + k * (dO + 1) + 2 * H * k; }
@@ -21,6 +22,7 @@ __host__ __device__ inline int attn_lds_floats(int k, int H, int dO) { return dO
 // latency.  Both kernels therefore issue everything they will need of the first ROWS_IN_FLIGHT neighbours
 // (with k = 10 that is everything) as one burst right after the two index loads: the query (or dO) row, the
 // key rows and the value rows; rows beyond the first batch are fetched batch by batch where they are used.
+template <int MAX_E>
 __global__ __launch_bounds__(256) void attn_fwd_kernel(AttnShape sh, const float* __restrict__ q,
                                                        const int32_t* __restrict__ slot_row,
                                                        const float* __restrict__ KV,
@@ -177,6 +179,7 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(AttnShape sh, const float
   }
 }
 
+template <int MAX_E>
 __global__ __launch_bounds__(256) void attn_bwd_kernel(AttnShape sh, const float* __restrict__ q,
                                                        const int32_t* __restrict__ slot_row,
                                                        const float* __restrict__ KV,
@@ -361,8 +364,12 @@ void attn_core_fwd(const Dims& d, int R, const float* q, int ldq, const int32_t*
   if (R <= 0) return;
   const size_t lds = 4 * sizeof(float) * attn_lds_floats(d.k, d.H, d.dO);
   const int fill_blocks = fill.ucnt != nullptr ? (fill.S + 255) / 256 : 0;
-  hipLaunchKernelGGL(attn_fwd_kernel, dim3((R + 3) / 4 + fill_blocks), dim3(256), lds, s, shape_of(d, R, ldq, ldkv, ldo), q,
-                     slot_row, KV, cnt, prob, Omat, fill);
+  if (d.dO <= 128)
+    hipLaunchKernelGGL(attn_fwd_kernel<2>, dim3((R + 3) / 4 + fill_blocks), dim3(256), lds, s, shape_of(d, R, ldq, ldkv, ldo),
+                       q, slot_row, KV, cnt, prob, Omat, fill);
+  else
+    hipLaunchKernelGGL(attn_fwd_kernel<4>, dim3((R + 3) / 4 + fill_blocks), dim3(256), lds, s, shape_of(d, R, ldq, ldkv, ldo),
+                       q, slot_row, KV, cnt, prob, Omat, fill);
 }
 
 // dq and dOmat share the pitch ldo
@@ -371,8 +378,12 @@ void attn_core_bwd(const Dims& d, int R, const float* q, int ldq, const int32_t*
                    float* q_part, hipStream_t s) {
   if (R <= 0) return;
   const size_t lds = 4 * sizeof(float) * attn_lds_floats(d.k, d.H, d.dO);
-  hipLaunchKernelGGL(attn_bwd_kernel, dim3((R + 3) / 4), dim3(256), lds, s, shape_of(d, R, ldq, ldkv, ldo), q, slot_row,
-                     KV, cnt, prob, dOmat, dq, dKV, q_part);
+  if (d.dO <= 128)
+    hipLaunchKernelGGL(attn_bwd_kernel<2>, dim3((R + 3) / 4), dim3(256), lds, s, shape_of(d, R, ldq, ldkv, ldo), q, slot_row,
+                       KV, cnt, prob, dOmat, dq, dKV, q_part);
+  else
+    hipLaunchKernelGGL(attn_bwd_kernel<4>, dim3((R + 3) / 4), dim3(256), lds, s, shape_of(d, R, ldq, ldkv, ldo), q, slot_row,
+                       KV, cnt, prob, dOmat, dq, dKV, q_part);
 }
 
 }  // namespace tgnn
