@@ -25,7 +25,7 @@ PEAK_MFMA_F32_TFLOPS = 157.3
 # HBM bytes per launch (read + written) from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised in
 # profiles/train_step_C1_hbm_traffic.md (counter units scaled by the copy-kernel calibration described there).
 # Counters cannot be read from inside this script, so the figures are the recorded ones, for C1 only.
-MEASURED_TRAFFIC_BYTES = {"C1": {"kv_projection": 40.9e6, "assemble_ce": 33.8e6}}
+MEASURED_TRAFFIC_BYTES = {"C1": {"kv_projection": 41.0e6, "assemble_ce": 33.8e6}}
 
 STAGE_NAMES = ["(unused)", "(unused)", "roots + sample + distinct-node rows + prologue (pack weights, clear), one launch",
                "gather + time-encode (GRU input) + slot-to-row map", "GRU input + hidden projections (MFMA, one launch)", "(unused)",
