@@ -45,6 +45,10 @@ extern "C" {
                                        HIP graph and replays that with one launch, updating only the batch
                                        descriptors.  Not used on the NULL (legacy default) stream, while the caller's stream is itself being captured
                                        or while stage timing is enabled. */
+#define TGNN_FLAG_WIDE_ROOT_TILES 8  /* tgnn_train_step's root chain (merge layer, decoder, loss and their backward
+                                       pass in one launch) takes 16 events per workgroup whatever the size of the
+                                       step; by default steps of at most 1,280 events take 5 per workgroup.  Same
+                                       results up to the order of the sums over workgroups; for tests. */
 #define TGNN_FLAG_SIDE_STREAM 2     /* tgnn_train_step starts the bulk of the weight-gradient GEMMs (decoder, merge
                                        layer, {e | Phi} columns of W_k / W_v) on a second stream of the context as
                                        soon as their operands exist, beside the remaining chain of small backward

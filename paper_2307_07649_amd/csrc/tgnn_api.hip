@@ -824,7 +824,7 @@ static int enqueue_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
     ca.b1 = p->dec_b1; ca.w2 = p->dec_w2; ca.b2 = p->dec_b2;
     ca.z = w.z; ca.h1 = w.h1; ca.logits = w.logits; ca.dPdec = w.dPdec; ca.dz = w.dz; ca.dOmat = w.dOmat;
     ca.loss = out_loss; ca.g_w2 = grads->dec_w2; ca.g_b2 = grads->dec_b2;
-    root_chain(ca, bs, s);
+    root_chain(ca, bs, (ctx->cfg.flags & TGNN_FLAG_WIDE_ROOT_TILES) != 0, s);
   } else {   // decoder + loss (also produces d loss / d hidden)
     gemm_nt(w.z, d.ldh, w.Wdec_p, d.ldh, nullptr, w.Pdec, d.ldkv, R, 2 * d.dO, d.ldh, 2 * d.dO, false, s);
     decoder_pairs(d, w.bs_dev, bs.total, w.Pdec, d.ldkv, p->dec_b1, p->dec_w2, p->dec_b2, w.logits, out_loss, w.h1, w.dPdec,

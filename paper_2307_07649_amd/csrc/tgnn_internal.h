@@ -514,7 +514,8 @@ struct ChainArgs {
   float *loss, *g_w2, *g_b2;
 };
 bool root_chain_fits(const Dims& d);
-void root_chain(ChainArgs a, const BatchSet& bs_host, hipStream_t s);
+// force_wide: 16 events per workgroup whatever the size of the step (otherwise 5 when there are few events)
+void root_chain(ChainArgs a, const BatchSet& bs_host, bool force_wide, hipStream_t s);
 
 // ---- k_writeback.hip ----------------------------------------------------------------
 void writeback_mark(const Dims& d, const BatchSet* bs, int total, unsigned long long* winkey,

@@ -23,6 +23,7 @@ MAX_BATCHES = 16
 FLAG_OVERWRITE_GRADS = 1
 FLAG_SIDE_STREAM = 2
 FLAG_NO_GRAPH = 4
+FLAG_WIDE_ROOT_TILES = 8
 
 
 class tgnn_config(C.Structure):

@@ -45,9 +45,10 @@ def test_c0_edge_time_variant():
     run_sequence(P, 12, check_at=(0, 11), dt_source=1)
 
 
-@pytest.mark.parametrize("own_stream,flags", [(False, 0), (True, 2), (True, 4), (True, 6)])
+@pytest.mark.parametrize("own_stream,flags", [(False, 0), (True, 2), (True, 4), (True, 6), (True, 8)])
 def test_launch_modes_agree_with_the_oracle(own_stream, flags):
-    """NULL stream (direct launches); captured graph with the side stream; no graph; no graph with the side stream.
+    """NULL stream (direct launches); captured graph with the side stream; no graph; no graph with the side stream;
+    16 events per workgroup in the root chain (small steps take 5 by default).
     (The default, a captured single-stream graph, is what every other test runs.)"""
     P = make_problem("C0", random_phase=True)
     run_sequence(P, 12, lr=0.05, check_at=(0, 5, 11), own_stream=own_stream, flags=flags)
