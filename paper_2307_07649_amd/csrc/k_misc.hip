@@ -20,7 +20,7 @@ void prologue_fill(tgnn_ctx* ctx, const tgnn_params* p, const BatchSet* bs, cons
   memset(&pa, 0, sizeof(pa));
   int n = 0;
   auto add = [&](const float* src, float* dst, int rows, int cols, int zero_to, int ldd, int srs, int scs) {
-    pa.d[n++] = PackDesc{src, dst, rows, cols, zero_to, ldd, srs, scs};
+    pa.d[n++] = PackDesc{src, dst, rows, cols, zero_to, ldd, srs, scs, 0};
   };
   if (p != nullptr) {
     const int dO = d.dO, dm = d.dm, dx = d.dx, dkv = d.dkv, dmrg = d.dO + d.dx, half = d.ldkv;
@@ -52,6 +52,19 @@ void prologue_fill(tgnn_ctx* ctx, const tgnn_params* p, const BatchSet* bs, cons
     add(p->dec_ws, w.WdecT, dO, dO, dO, d.ldkv, 1, dO);
     add(p->dec_wd, w.WdecT + dO, dO, dO, d.ldkv - dO, d.ldkv, 1, dO);
     add(p->gru_wih + 2 * dm, w.WihT_phi, d.dt, 3 * dm, d.ld3, d.ld3, 1, d.d_in);
+    if (w.rc_pk != nullptr) {   // the root chain's copies, in MFMA B-operand order: [out column][k]
+      const int ks = (dO + 15) / 16;
+      const size_t blk = (size_t)ks * ks * 256;
+      auto add_mfma = [&](const float* src, int which, int srs, int scs) {
+        pa.d[n++] = PackDesc{src, w.rc_pk + which * blk, dO, dO, 0, 0, srs, scs, ks};
+      };
+      add_mfma(p->wo, 0, dmrg, 1);       // z column n      <- h columns k:      W_o[n, k]
+      add_mfma(p->dec_ws, 1, dO, 1);     // hidden column j <- z columns k:      W_s[j, k]
+      add_mfma(p->dec_wd, 2, dO, 1);
+      add_mfma(p->dec_ws, 3, 1, dO);     // dz column c     <- hidden gradient j: W_s[j, c]
+      add_mfma(p->dec_wd, 4, 1, dO);
+      add_mfma(p->wo, 5, 1, dmrg);       // dh column c     <- dz columns n:     W_o[n, c]
+    }
     // biases of the per-node projections: {b_k | b_v || b_q + W_q Phi(0) | b_o}
     add(p->bk, w.bias_x, 1, dO, dO, d.ldp, 0, 1);
     add(p->bv, w.bias_x + dO, 1, dO, dO, d.ldp, 0, 1);

@@ -11,7 +11,8 @@
 //   pairs  : hidden = ReLU(Pdec_src + Pdec_dst + b1), logit, loss, d/d(logit), d/d(hidden) -> dPdec per root
 //   dz     = gate_z(dPdec W_s) for sources, gate_z(dPdec W_d) for destinations
 //   dOmat  = dz W_oh
-// The weights are read from global memory (L2) as MFMA B operands, a lane's run of a weight row per 16-wide k slab.
+// The weights are read from global memory (L2) as MFMA B operands, from copies laid out in operand order (the
+// prologue writes them): 1 KB of contiguous memory per wavefront, column block and 16-wide k slab.
 // z, h1, dPdec ({W_s part | W_d part}, the unused half zero), dz and dOmat go to memory for the weight-gradient
 // products and the attention backward pass.
 #include "tgnn_internal.h"
@@ -54,30 +55,30 @@ template <int KS> struct RcSet {
   floatx4 w[2][KS];
 };
 
-// W: weight block with one row per output column; the destinations' block starts dst_off floats later
-// (SPLIT = false: one block for all roles).  cb: the wavefront's column block.
+// W0 (and W1 for the destinations when SPLIT): weight blocks in MFMA B-operand order: the lanes' float4 pieces of
+// column block cb and k slab s are the 1 KB at (cb KS + s) * 256 floats.
 template <int KS, bool SPLIT>
-__device__ __forceinline__ void rc_load(RcSet<KS>& set, int cb, const float* __restrict__ W, size_t dst_off, int ldw, int N,
-                                        int li, int lg) {
-  const float* p = W + (size_t)min(cb * 16 + li, N - 1) * ldw + lg * 4;
+__device__ __forceinline__ void rc_load(RcSet<KS>& set, int cb, const float* __restrict__ W0, const float* __restrict__ W1,
+                                        int lane) {
+  const float* p0 = W0 + ((size_t)cb * KS * 64 + lane) * 4;
 #pragma unroll
-  for (int s = 0; s < KS; ++s) set.w[0][s] = *reinterpret_cast<const floatx4*>(p + s * 16);
+  for (int s = 0; s < KS; ++s) set.w[0][s] = *reinterpret_cast<const floatx4*>(p0 + s * 256);
   if (SPLIT) {
+    const float* p1 = W1 + ((size_t)cb * KS * 64 + lane) * 4;
 #pragma unroll
-    for (int s = 0; s < KS; ++s) set.w[1][s] = *reinterpret_cast<const floatx4*>(p + dst_off + s * 16);
+    for (int s = 0; s < KS; ++s) set.w[1][s] = *reinterpret_cast<const floatx4*>(p1 + s * 256);
   }
 }
 
 // acc[j][v] = sum_k T[16 rb_j + li][k] W_j[col][k]  -> element (16 rb_j + 4 lg + v, 16 cb + li) of unit j.  The
 // units' accumulation chains are independent and interleaved, so an MFMA never waits for the one before it.
 // PF != 0: the next product's weights (PF == 2: with a separate block for the destinations) are fetched into
-// `next` on the way, one k slab per k slab: the weight rows are 64-byte pieces of scattered lines, which the
-// vector memory path takes about as long to bring in as the MFMAs of a product take.
+// `next` on the way, one k slab per k slab.
 // The MFMAs are unconditional (a wavefront without a column block skips the whole call): a wave-uniform `if`
 // around single MFMAs made the compiler branch around each of them and pad with s_nop, at twice the time.
 template <int KS, int E, bool SPLIT, int PF>
 __device__ __forceinline__ void rc_mma(const RcSet<KS>& set, int cb, const float* T, int li, int lg, floatx4 (&acc)[3],
-                                       RcSet<KS>& next, const float* __restrict__ Wn, size_t dst_off_n, int ldw_n, int N) {
+                                       RcSet<KS>& next, const float* __restrict__ Wn0, const float* __restrict__ Wn1) {
   typedef RcGeom<E> G;
   constexpr int NU = SPLIT ? G::NU_SPLIT : G::NU_SHARED;
   const float* pa[NU];
@@ -86,11 +87,13 @@ __device__ __forceinline__ void rc_mma(const RcSet<KS>& set, int cb, const float
     acc[j] = floatx4{0.f, 0.f, 0.f, 0.f};
     pa[j] = T + (G::template unit_rb<SPLIT>(j) * 16 + li) * RC_PL + lg * 4;
   }
-  const float* pn = PF ? Wn + (size_t)min(cb * 16 + li, N - 1) * ldw_n + lg * 4 : nullptr;
+  const int lane64 = lg * 16 + li;
+  const float* pn0 = PF ? Wn0 + ((size_t)cb * KS * 64 + lane64) * 4 : nullptr;
+  const float* pn1 = PF == 2 ? Wn1 + ((size_t)cb * KS * 64 + lane64) * 4 : nullptr;
 #pragma unroll
   for (int s = 0; s < KS; ++s) {
-    if (PF >= 1) next.w[0][s] = *reinterpret_cast<const floatx4*>(pn + s * 16);
-    if (PF == 2) next.w[1][s] = *reinterpret_cast<const floatx4*>(pn + dst_off_n + s * 16);
+    if (PF >= 1) next.w[0][s] = *reinterpret_cast<const floatx4*>(pn0 + s * 256);
+    if (PF == 2) next.w[1][s] = *reinterpret_cast<const floatx4*>(pn1 + s * 256);
     floatx4 a4[NU];
 #pragma unroll
     for (int j = 0; j < NU; ++j)
@@ -150,7 +153,7 @@ __global__ __launch_bounds__(64 * RC_WAVES) void root_chain_kernel(ChainArgs a) 
     if (c < dO) om[u] = *reinterpret_cast<const floatx4*>(a.Omat + (size_t)groot(lr) * ldh + c);
   }
   __builtin_amdgcn_sched_barrier(0);   // keep this issue order
-  rc_load<KS, false>(wa, cb, a.Wo_o, 0, ldh, dO, li, lg);
+  rc_load<KS, false>(wa, cb, a.Wo_pk, nullptr, lane);
   int prow[G::NB][4];
 #pragma unroll
   for (int j = 0; j < G::NB; ++j)
@@ -192,9 +195,9 @@ __global__ __launch_bounds__(64 * RC_WAVES) void root_chain_kernel(ChainArgs a) 
   floatx4 acc[3];
 
   // ---- z = ReLU(h W_oh^T + P_o[row]) ----
-  // next: Pdec, sources through W_s (rows 0 .. d_o-1 of the packed block), destinations through W_d
+  // next: Pdec, sources through W_s, destinations through W_d
   if (has_cb) {
-    rc_mma<KS, E, false, 2>(wa, cb, T0, li, lg, acc, wb, a.Wdec_p, (size_t)dO * ldh, ldh, dO);
+    rc_mma<KS, E, false, 2>(wa, cb, T0, li, lg, acc, wb, a.Ws_pk, a.Wd_pk);
 #pragma unroll
     for (int j = 0; j < G::NU_SHARED; ++j)
 #pragma unroll
@@ -208,9 +211,9 @@ __global__ __launch_bounds__(64 * RC_WAVES) void root_chain_kernel(ChainArgs a) 
   __syncthreads();
 
   // ---- Pdec ----
-  // next: dz; row c of the transposed block is {W_s[:, c] | W_d[:, c]}
+  // next: dz, through the transposed blocks
   if (has_cb) {
-    rc_mma<KS, E, true, 2>(wb, cb, T1, li, lg, acc, wa, a.WdecT, (size_t)dO, ldkv, dO);
+    rc_mma<KS, E, true, 2>(wb, cb, T1, li, lg, acc, wa, a.WsT_pk, a.WdT_pk);
 #pragma unroll
     for (int j = 0; j < G::NU_SPLIT; ++j)
 #pragma unroll
@@ -306,7 +309,7 @@ __global__ __launch_bounds__(64 * RC_WAVES) void root_chain_kernel(ChainArgs a) 
 
   // ---- dz = gate_z(dPdec {W_s | W_d}) ----
   if (has_cb) {
-    rc_mma<KS, E, true, 1>(wa, cb, T0, li, lg, acc, wb, a.WoT_o, 0, ldh, dO);
+    rc_mma<KS, E, true, 1>(wa, cb, T0, li, lg, acc, wb, a.WoT_pk, nullptr);
 #pragma unroll
     for (int j = 0; j < G::NU_SPLIT; ++j)
 #pragma unroll
@@ -324,7 +327,7 @@ __global__ __launch_bounds__(64 * RC_WAVES) void root_chain_kernel(ChainArgs a) 
 
   // ---- dOmat = dz W_oh ----
   if (has_cb) {
-    rc_mma<KS, E, false, 0>(wb, cb, T1, li, lg, acc, wa, nullptr, 0, 0, dO);
+    rc_mma<KS, E, false, 0>(wb, cb, T1, li, lg, acc, wa, nullptr, nullptr);
 #pragma unroll
     for (int j = 0; j < G::NU_SHARED; ++j)
 #pragma unroll

@@ -10,6 +10,16 @@ namespace tgnn {
 __device__ __forceinline__ void prologue_block(const PrologueArgs& a, int bx, int nbx, int y) {
   if (y < a.n_pack) {
     const PackDesc d = a.d[y];
+    if (d.mfma_ks > 0) {   // MFMA B-operand order
+      const int total = ((d.rows + 15) >> 4) * d.mfma_ks * 256;
+      for (int i = bx * blockDim.x + threadIdx.x; i < total; i += nbx * blockDim.x) {
+        const int slab = i >> 8, t = i & 255, lane = t >> 2, c = t & 3;
+        const int cb = slab / d.mfma_ks, s = slab - cb * d.mfma_ks;
+        const int row = cb * 16 + (lane & 15), k = s * 16 + (lane >> 4) * 4 + c;
+        d.dst[i] = (row < d.rows && k < d.cols) ? d.src[(size_t)row * d.srs + (size_t)k * d.scs] : 0.f;
+      }
+      return;
+    }
     const int total = d.rows * d.zero_to;
     const float* __restrict__ src = d.src;
     float* __restrict__ dst = d.dst;

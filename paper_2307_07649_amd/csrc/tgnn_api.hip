@@ -116,6 +116,10 @@ static void layout(const Dims& d, Ws& w, Bump& b) {
   w.Wdec_p = b.take<float>((size_t)2 * d.dO * d.ldh);
   w.Wx = b.take<float>((size_t)d.ldp * d.ldxr); w.bias_x = b.take<float>((size_t)d.ldp);
   w.Wce = b.take<float>((size_t)2 * d.dO * d.ldce); w.Wo_o = b.take<float>((size_t)d.dO * d.ldh);
+  {
+    const size_t ks = (size_t)(d.dO + 15) / 16;
+    w.rc_pk = root_chain_fits(d) ? b.take<float>(6 * ks * ks * 256) : nullptr;
+  }
   w.WdecT = b.take<float>((size_t)d.dO * d.ldkv); w.WihT_phi = b.take<float>((size_t)d.dt * d.ld3);
   w.WxT = b.take<float>((size_t)d.dm * d.ldp); w.WceT_phi = b.take<float>((size_t)d.dt * d.ldkv);
   w.WoT_o = b.take<float>((size_t)d.dO * d.ldh);
@@ -820,7 +824,11 @@ static int enqueue_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
     ChainArgs ca;
     ca.dO = d.dO; ca.ldh = d.ldh; ca.ldkv = d.ldkv; ca.ldp = d.ldp;
     ca.Omat = w.Omat; ca.P_o = w.P + d.ldkv + d.dO; ca.slot_row = w.slot_row;
-    ca.Wo_o = w.Wo_o; ca.Wdec_p = w.Wdec_p; ca.WdecT = w.WdecT; ca.WoT_o = w.WoT_o;
+    {
+      const size_t ks = (size_t)(d.dO + 15) / 16, blk = ks * ks * 256;
+      ca.Wo_pk = w.rc_pk; ca.Ws_pk = w.rc_pk + blk; ca.Wd_pk = w.rc_pk + 2 * blk; ca.WsT_pk = w.rc_pk + 3 * blk;
+      ca.WdT_pk = w.rc_pk + 4 * blk; ca.WoT_pk = w.rc_pk + 5 * blk;
+    }
     ca.b1 = p->dec_b1; ca.w2 = p->dec_w2; ca.b2 = p->dec_b2;
     ca.z = w.z; ca.h1 = w.h1; ca.logits = w.logits; ca.dPdec = w.dPdec; ca.dz = w.dz; ca.dOmat = w.dOmat;
     ca.loss = out_loss; ca.g_w2 = grads->dec_w2; ca.g_b2 = grads->dec_b2;

@@ -80,6 +80,7 @@ struct Ws {
   float *Wx, *bias_x;       // [ldkv + 2 d_o, ldxr] rows {W_k ; W_v ; 0 ; W_q ; W_o} restricted to the x columns; [ldp]
   float *Wce;               // [2 d_o, ldce] {W_k ; W_v} restricted to the {e | Phi} columns
   float *Wo_o;              // [d_o, ldh] W_o restricted to the attention-output columns
+  float *rc_pk;             // six [d_o, d_o] blocks in MFMA B-operand order for the root chain (NULL: it does not fit)
   float *WdecT, *WihT_phi;
   float *WxT;               // [d_m, ldp]   transposed Wx, dynamic columns only
   float *WceT_phi;          // [d_t, ldkv]  transposed Wce, time-encoding columns only
@@ -292,8 +293,13 @@ struct PackDesc {
   float* dst;
   int rows, cols, zero_to, ldd;  // dst[r*ldd + c] = src[r*srs + c*scs] for c < cols, 0 for cols <= c < zero_to
   int srs, scs;
+  // mfma_ks > 0: MFMA B-operand order instead (zero_to, ldd unused).  For column block cb (16 rows), k slab s < mfma_ks
+  // (16 columns), lane (li, lg) and c < 4:  dst[((cb * mfma_ks + s) * 64 + lg * 16 + li) * 4 + c] =
+  // src[(16 cb + li) * srs + (16 s + 4 lg + c) * scs], zero beyond rows / cols: a wavefront then reads the operand
+  // of one MFMA slab as 1 KB of contiguous memory.
+  int mfma_ks;
 };
-constexpr int MAX_PACK = 30;
+constexpr int MAX_PACK = 32;
 struct PrologueArgs {
   PackDesc d[MAX_PACK];
   int n_pack;
@@ -508,7 +514,9 @@ struct ChainArgs {
   const float* Omat;          // [R, ldh] attention output
   const float* P_o;           // node part of the merge layer (bias included), row pitch ldp
   const int32_t* slot_row;    // root slot -> node row (NULL: identity)
-  const float *Wo_o, *Wdec_p, *WdecT, *WoT_o;   // packed weight blocks
+  // weight blocks in MFMA B-operand order (see PackDesc): merge layer (attention-output columns), W_s, W_d, and
+  // their transposes
+  const float *Wo_pk, *Ws_pk, *Wd_pk, *WsT_pk, *WdT_pk, *WoT_pk;
   const float *b1, *w2, *b2;
   float *z, *h1, *logits, *dPdec, *dz, *dOmat;
   float *loss, *g_w2, *g_b2;
