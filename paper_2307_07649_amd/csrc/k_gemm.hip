@@ -366,7 +366,6 @@ static int nt_tile_blocks(int M, int n_store) {
       if (cost < best_cost - 1e-6f) { best_cost = cost; best = c; }
     }
   }
-  if (const char* e = getenv("TGNN_NT_TN")) best = atoi(e);
   return best;
 }
 
@@ -732,8 +731,8 @@ static int tn_place(TnGroup& g, const int* rows, int rows_per_chunk) {
 
 void TnBatch::launch(hipStream_t s) {
   if (g.n == 0) return;
-  static const int per_xcd = getenv("TGNN_TN_WGS") ? atoi(getenv("TGNN_TN_WGS")) / 8 : TN_WGS_PER_XCD;
-  static const int max_rows = getenv("TGNN_TN_RPW") ? atoi(getenv("TGNN_TN_RPW")) : TN_MAX_ROWS;
+  const int per_xcd = TN_WGS_PER_XCD;
+  const int max_rows = TN_MAX_ROWS;
   int rows[TN_MAX_GROUP];
   // a row count that lives on the device (distinct nodes of a step) is usually a small part of its bound
   for (int i = 0; i < g.n; ++i) rows[i] = g.p[i].m_dev != nullptr ? (g.p[i].M + 7) / 8 : g.p[i].M;
