@@ -186,7 +186,7 @@ __global__ __launch_bounds__(256) void attn_bwd_kernel(AttnShape sh, const float
                                                        const int32_t* __restrict__ cnt,
                                                        const float* __restrict__ prob,
                                                        const float* __restrict__ dOmat, float* __restrict__ dq,
-                                                       float* __restrict__ dKV, float* __restrict__ q_part) {
+                                                       float* __restrict__ dKV, float* __restrict__ q_part, AttnSums zs) {
   extern __shared__ float lds[];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int r = blockIdx.x * 4 + wave;
@@ -204,6 +204,14 @@ __global__ __launch_bounds__(256) void attn_bwd_kernel(AttnShape sh, const float
   }
   if (c == 0) {
     for (int e = lane; e < sh.dO; e += 64) dq[(size_t)r * sh.ldo + e] = 0.f;
+    if (zs.Zs != nullptr) {
+      if (zs.later) {
+        for (int p = lane; p < HK; p += 64) zs.ds_out[(size_t)r * HK + p] = 0.f;
+      } else {
+        for (int i = lane; i < sh.H * zs.dcp; i += 64) zs.Zs[(size_t)r * zs.ldz + i] = zs.Zp[(size_t)r * zs.ldz + i] = 0.f;
+      }
+      for (int e = lane; e < sh.dO; e += 64) zs.Qroot[(size_t)r * sh.ldo + e] = 0.f;
+    }
     return;
   }
   const float scale = 1.0f / sqrtf((float)c);
@@ -296,6 +304,56 @@ __global__ __launch_bounds__(256) void attn_bwd_kernel(AttnShape sh, const float
   for (int p = lane; p < HK; p += 64, ++it) sa[HK + p] = da_keep[it];
   __builtin_amdgcn_wave_barrier();
   __builtin_amdgcn_s_waitcnt(0xc07f);
+  if (zs.Zs != nullptr && zs.later) {
+    for (int p = lane; p < HK; p += 64) zs.ds_out[(size_t)r * HK + p] = sa[HK + p];
+#pragma unroll
+    for (int u = 0; u < MAX_E; ++u) {
+      const int e = lane + 64 * u;
+      if (e < sh.dO) zs.Qroot[(size_t)r * sh.ldo + e] = qreg[u];
+    }
+  } else if (zs.Zs != nullptr) {
+    // Per head, the sums of the slots' {e | Phi} rows weighted by the score gradients (Zs) and by the softmax
+    // weights (Zp): dK_j = ds_j q and dV_j = p_j dO per head, so the weight gradients sum_j dK_j CE_j^T and
+    // sum_j dV_j CE_j^T of a root are q Zs^T and dO Zp^T, products over roots instead of over slots.
+    for (int c0 = 0; c0 < zs.dcp; c0 += 64) {
+      const int cc = c0 + lane;
+      float as[TGNN_MAX_HEADS], ap[TGNN_MAX_HEADS];
+#pragma unroll
+      for (int h = 0; h < TGNN_MAX_HEADS; ++h) as[h] = ap[h] = 0.f;
+      for (int j0 = 0; j0 < c; j0 += ROWS_IN_FLIGHT) {
+        float ce[ROWS_IN_FLIGHT];
+#pragma unroll
+        for (int jj = 0; jj < ROWS_IN_FLIGHT; ++jj)
+          ce[jj] = (j0 + jj < c && cc < zs.dcols) ? zs.CE[((size_t)r * sh.k + j0 + jj) * zs.ldce + cc] : 0.f;
+#pragma unroll
+        for (int jj = 0; jj < ROWS_IN_FLIGHT; ++jj) {
+          if (j0 + jj < c) {
+#pragma unroll
+            for (int h = 0; h < TGNN_MAX_HEADS; ++h) {
+              if (h < sh.H) {
+                as[h] += sa[HK + h * sh.k + j0 + jj] * ce[jj];
+                ap[h] += sa[h * sh.k + j0 + jj] * ce[jj];
+              }
+            }
+          }
+        }
+      }
+      if (cc < zs.dcp) {
+#pragma unroll
+        for (int h = 0; h < TGNN_MAX_HEADS; ++h) {
+          if (h < sh.H) {
+            zs.Zs[(size_t)r * zs.ldz + h * zs.dcp + cc] = as[h];
+            zs.Zp[(size_t)r * zs.ldz + h * zs.dcp + cc] = ap[h];
+          }
+        }
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < MAX_E; ++u) {
+      const int e = lane + 64 * u;
+      if (e < sh.dO) zs.Qroot[(size_t)r * sh.ldo + e] = qreg[u];
+    }
+  }
   // dq, and the gradients of the key and value rows: the first batch of key rows is in registers
   float dqe[MAX_E];
 #pragma unroll
@@ -375,15 +433,15 @@ void attn_core_fwd(const Dims& d, int R, const float* q, int ldq, const int32_t*
 // dq and dOmat share the pitch ldo
 void attn_core_bwd(const Dims& d, int R, const float* q, int ldq, const int32_t* slot_row, const float* KV, int ldkv,
                    const int32_t* cnt, const float* prob, const float* dOmat, int ldo, float* dq, float* dKV,
-                   float* q_part, hipStream_t s) {
+                   float* q_part, hipStream_t s, const AttnSums& zs) {
   if (R <= 0) return;
   const size_t lds = 4 * sizeof(float) * attn_lds_floats(d.k, d.H, d.dO);
   if (d.dO <= 128)
     hipLaunchKernelGGL(attn_bwd_kernel<2>, dim3((R + 3) / 4), dim3(256), lds, s, shape_of(d, R, ldq, ldkv, ldo), q, slot_row,
-                       KV, cnt, prob, dOmat, dq, dKV, q_part);
+                       KV, cnt, prob, dOmat, dq, dKV, q_part, zs);
   else
     hipLaunchKernelGGL(attn_bwd_kernel<4>, dim3((R + 3) / 4), dim3(256), lds, s, shape_of(d, R, ldq, ldkv, ldo), q, slot_row,
-                       KV, cnt, prob, dOmat, dq, dKV, q_part);
+                       KV, cnt, prob, dOmat, dq, dKV, q_part, zs);
 }
 
 }  // namespace tgnn

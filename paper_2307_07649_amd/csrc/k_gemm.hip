@@ -491,7 +491,7 @@ template <int TD, int TA>
 __device__ __forceinline__ void tn_tile(const float* __restrict__ D, const float* __restrict__ A, int ldd, int lda, int N,
                                         int K, float* p00, float* p01, float* p10, float* p11, int ld00, int ld01, int ld10,
                                         int ld11, int n_split, int k_split, float* bias0, float* bias1, int M, int m_lo,
-                                        int m_hi, int n0, int k0, float* lds) {
+                                        int m_hi, int n0, int k0, float* lds, int head_n, int head_k, int head_cols) {
   typedef typename FragT<TD>::type FD;
   typedef typename FragT<TA>::type FA;
   const bool with_bias = bias0 != nullptr || bias1 != nullptr;   // column K of A reads as ones
@@ -609,6 +609,11 @@ __device__ __forceinline__ void tn_tile(const float* __restrict__ D, const float
     float x = 0.f;
 #pragma unroll
     for (int b = 0; b < NB; ++b) x += lds[b * TILE + slot];
+    if (head_k > 0) {   // per-head blocks: kept only where the head of D's column is the head of A's block
+      const int h = k / head_k, kk = k - h * head_k;
+      if (n / head_n == h && kk < head_cols) atomicAdd(p00 + (size_t)n * ld00 + kk, x);
+      continue;
+    }
     // (selects instead of indexing: a dynamically indexed local array would live in scratch memory)
     const bool ns = n >= n_split;
     const int nn = n - (ns ? n_split : 0);
@@ -657,11 +662,17 @@ __global__ __launch_bounds__(64 * TN_W) void gemm_tn_kernel(TnGroup grp) {
   int n0, wn, k0, wk;
   tn_piece(N, tile / k_tiles, n0, wn);
   tn_piece(K + (with_bias ? 1 : 0), tile % k_tiles, k0, wk);
+  if (q.out.head_k > 0) {   // a tile whose columns of D and of A share no head has nothing to add
+    const int hn_lo = n0 / q.out.head_n, hn_hi = (min(n0 + wn, N) - 1) / q.out.head_n;
+    const int hk_lo = k0 / q.out.head_k, hk_hi = (min(k0 + wk, K) - 1) / q.out.head_k;
+    if (hn_hi < hk_lo || hk_hi < hn_lo) return;   // uniform for the workgroup, before any barrier
+  }
 #define TGNN_TN_CASE(WN, WK)                                                                                          \
   if (wn == WN && wk == WK) {                                                                                         \
     tn_tile<WN / 16, WK / 16>(q.D, q.A, q.ldd, q.lda, N, K, q.out.p[0][0], q.out.p[0][1], q.out.p[1][0], q.out.p[1][1], \
                               q.out.ld[0][0], q.out.ld[0][1], q.out.ld[1][0], q.out.ld[1][1], q.out.n_split,           \
-                              q.out.k_split, bias0, q.out.bias[1], M, m_lo, m_hi, n0, k0, lds);                        \
+                              q.out.k_split, bias0, q.out.bias[1], M, m_lo, m_hi, n0, k0, lds, q.out.head_n,           \
+                              q.out.head_k, q.out.head_cols);                                                         \
     return;                                                                                                           \
   }
   TGNN_TN_CASE(64, 64) TGNN_TN_CASE(64, 32) TGNN_TN_CASE(64, 16)

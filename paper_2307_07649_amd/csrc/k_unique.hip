@@ -25,13 +25,79 @@ SortArgs sort_args(tgnn_ctx* ctx, int S) {
 //   root slot r      : dP[row, half .. half + 2 d_o)     += {dq[r] | dz[r]}          (half = the pitch of dKV)
 // One wavefront owns SEG_CHUNK consecutive entries of the row-sorted slot list; runs of one row are summed
 // in registers and leave as one atomic row update per half.
+// Per root and head: Zs = sum_j ds[h][j] CE_j and Zp = sum_j p[h][j] CE_j over the root's neighbour slots (see
+// AttnSums).  One wavefront per root, 16 bytes of a row per lane; a block is four roots.  HM: heads the
+// accumulators are laid out for.
+typedef float zsum_f4 __attribute__((ext_vector_type(4)));
+template <int HM>
+__device__ __forceinline__ void zsum_root(const AttnSums& a, int r, const float* wv, int lane) {
+  const int HK = a.H * a.k, n4 = a.dcp >> 2;
+  const int c = a.cnt[r];
+  constexpr int NJ = 10;   // rows whose loads are issued together
+  for (int f0 = 0; f0 < n4; f0 += 64) {
+    const int f = f0 + lane;
+    const bool on = f < n4;
+    zsum_f4 as[HM], ap[HM];
+#pragma unroll
+    for (int h = 0; h < HM; ++h) as[h] = ap[h] = zsum_f4{0.f, 0.f, 0.f, 0.f};
+    for (int j0 = 0; j0 < c; j0 += NJ) {
+      zsum_f4 ce[NJ];
+#pragma unroll
+      for (int jj = 0; jj < NJ; ++jj) {
+        ce[jj] = zsum_f4{0.f, 0.f, 0.f, 0.f};
+        if (on && j0 + jj < c)
+          ce[jj] = *reinterpret_cast<const zsum_f4*>(a.CE + ((size_t)r * a.k + j0 + jj) * a.ldce + 4 * f);
+      }
+#pragma unroll
+      for (int jj = 0; jj < NJ; ++jj) {
+        if (j0 + jj < c) {
+#pragma unroll
+          for (int h = 0; h < HM; ++h) {
+            if (h < a.H) {
+              as[h] += wv[h * a.k + j0 + jj] * ce[jj];
+              ap[h] += wv[HK + h * a.k + j0 + jj] * ce[jj];
+            }
+          }
+        }
+      }
+    }
+    if (on) {
+#pragma unroll
+      for (int h = 0; h < HM; ++h) {
+        if (h < a.H) {
+          *reinterpret_cast<zsum_f4*>(a.Zs + (size_t)r * a.ldz + h * a.dcp + 4 * f) = as[h];
+          *reinterpret_cast<zsum_f4*>(a.Zp + (size_t)r * a.ldz + h * a.dcp + 4 * f) = ap[h];
+        }
+      }
+    }
+  }
+}
+
+__device__ __forceinline__ void zsum_block(const AttnSums& a, int block) {
+  __shared__ float w_lds[4][2 * TGNN_MAX_HEADS * TGNN_MAX_K];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int r = block * 4 + wave;
+  if (r >= a.R) return;   // per wavefront; no block barrier below
+  const int HK = a.H * a.k;
+  float* wv = w_lds[wave];
+  for (int p = lane; p < HK; p += 64) {
+    wv[p] = a.ds_out[(size_t)r * HK + p];
+    wv[HK + p] = a.prob[(size_t)r * HK + p];
+  }
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_s_waitcnt(0xc07f);   // the wavefront's LDS writes are visible to all its lanes
+  __builtin_amdgcn_wave_barrier();
+  if (a.H <= 2) zsum_root<2>(a, r, wv, lane);
+  else zsum_root<TGNN_MAX_HEADS>(a, r, wv, lane);
+}
+
 constexpr int SEG_CHUNK = 16;
 __global__ __launch_bounds__(256) void seg_reduce_kernel(int R, int S, int dO, const int32_t* __restrict__ sort_total,
                                                          const int32_t* __restrict__ sorted,
                                                          const int32_t* __restrict__ sorted_row,
                                                          const float* __restrict__ dq, const float* __restrict__ dz,
                                                          int ldh, const float* __restrict__ dKV, int ldkv,
-                                                         float* __restrict__ dP, int ldp, QPhi qphi) {
+                                                         float* __restrict__ dP, int ldp, QPhi qphi, AttnSums zs) {
   int block = blockIdx.x;
   if (qphi.part != nullptr) {   // the first blocks are passengers: gradients through the query's Phi(0)
     const int nq = qphi_blocks(qphi);
@@ -40,6 +106,14 @@ __global__ __launch_bounds__(256) void seg_reduce_kernel(int R, int S, int dO, c
       return;
     }
     block -= nq;
+  }
+  {   // the last blocks, also passengers: the per-root sums for the weight gradients of the {e | Phi} columns
+      // (behind the row sums, which the next launch waits for the longest)
+    const int n_seg = ((S + SEG_CHUNK - 1) / SEG_CHUNK + 3) / 4;
+    if (block >= n_seg) {
+      if (block - n_seg < zsum_blocks(zs)) zsum_block(zs, block - n_seg);
+      return;
+    }
   }
   const int lane = threadIdx.x & 63;
   const int chunk = block * 4 + (threadIdx.x >> 6);
@@ -116,12 +190,12 @@ __global__ __launch_bounds__(256) void seg_reduce_kernel(int R, int S, int dO, c
   }
 }
 
-void seg_reduce(tgnn_ctx* ctx, int R, int S, const QPhi& qphi, hipStream_t s) {
+void seg_reduce(tgnn_ctx* ctx, int R, int S, const QPhi& qphi, hipStream_t s, const AttnSums& zs) {
   const Dims& d = ctx->d;
   Ws& w = ctx->w;
   const int chunks = (S + SEG_CHUNK - 1) / SEG_CHUNK;
-  hipLaunchKernelGGL(seg_reduce_kernel, dim3((chunks + 3) / 4 + qphi_blocks(qphi)), dim3(256), 0, s, R, S, d.dO,
-                     w.sort_total, w.sorted, w.sorted_row, w.dq, w.dz, d.ldh, w.dKV, d.ldkv, w.dP, d.ldp, qphi);
+  hipLaunchKernelGGL(seg_reduce_kernel, dim3((chunks + 3) / 4 + qphi_blocks(qphi) + zsum_blocks(zs)), dim3(256), 0, s, R, S,
+                     d.dO, w.sort_total, w.sorted, w.sorted_row, w.dq, w.dz, d.ldh, w.dKV, d.ldkv, w.dP, d.ldp, qphi, zs);
 }
 
 // slot = row: dP[r] = {0 || dq[r] | dz[r]} for roots, dP[R + j] = {dKV[j] || 0} for neighbour slots

@@ -109,6 +109,8 @@ static void layout(const Dims& d, Ws& w, Bump& b) {
   w.prob = b.take<float>(R * d.H * d.k); w.Omat = b.take<float>(R * d.ldh); w.z = b.take<float>(R * d.ldh);
   w.dz = b.take<float>(R * d.ldh); w.dOmat = b.take<float>(R * d.ldh); w.dq = b.take<float>(R * d.ldh);
   w.dKV = b.take<float>(RK * d.ldkv);
+  w.Zs = b.take<float>(R * d.ldz); w.Zp = b.take<float>(R * d.ldz); w.Qroot = b.take<float>(R * d.ldh);
+  w.dscore = b.take<float>(R * d.H * d.k);
   w.Pdec = b.take<float>(R * d.ldkv); w.dPdec = b.take<float>(R * d.ldkv);
   w.h1 = b.take<float>(B2 * d.ldh); w.logits = b.take<float>(B2);
   w.loss_acc = b.take<float>(TGNN_MAX_BATCHES);
@@ -247,13 +249,37 @@ static NtProblem keys_phi_problem(tgnn_ctx* ctx, const tgnn_params* p, tgnn_para
 // with another one).
 static void attn_backward(tgnn_ctx* ctx, tgnn_params* g, const tgnn_params* p, int R, const int32_t* slot_row,
                           const int32_t* cnt, TnBatch& tn, Side& side, bool phi_now, hipStream_t s,
-                          bool have_dOmat = false) {
+                          bool have_dOmat = false, AttnSums* sums_later = nullptr) {
   const Dims& d = ctx->d; Ws& w = ctx->w;
   const int RK = R * d.k;
   tn.add(w.dz, d.ldh, w.Omat, d.ldh, R, d.dO, d.dO, single_out(g->wo, d.dO + d.dx, nullptr));
   if (!have_dOmat) gemm_nt(w.dz, d.ldh, w.WoT_o, d.ldh, nullptr, w.dOmat, d.ldh, R, d.dO, d.ldh, d.ldh, false, s);
-  attn_core_bwd(d, R, w.P + d.ldkv, d.ldp, slot_row, w.KV, d.ldkv, cnt, w.prob, w.dOmat, d.ldh, w.dq, w.dKV, w.q_part, s);
-  if (d.de + d.dt > 0) {
+  // Weight gradients of the {e | Phi} columns of W_k, W_v: per head, dK_j = ds_j q and dV_j = p_j dO, so
+  // sum over slots of dK_j CE_j^T = sum over roots of q (sum_j ds_j CE_j)^T: the attention backward kernel leaves the
+  // inner sums per root and head, and the products run over R rows instead of R k.
+  const bool by_root = d.de + d.dt > 0;
+  AttnSums zs;
+  if (by_root) {
+    zs.CE = w.CE; zs.ldce = d.ldce; zs.dcols = d.de + d.dt; zs.dcp = d.dcp; zs.ldz = d.ldz;
+    zs.Zs = w.Zs; zs.Zp = w.Zp; zs.Qroot = w.Qroot;
+    if (sums_later != nullptr && !side.on) {   // the caller's next launch takes the sums (zsum_block); with the side
+                                               // stream the products that need them start before that launch
+      zs.later = true; zs.ds_out = w.dscore; zs.prob = w.prob; zs.cnt = cnt; zs.R = R; zs.k = d.k; zs.H = d.H;
+      *sums_later = zs;
+    }
+  }
+  attn_core_bwd(d, R, w.P + d.ldkv, d.ldp, slot_row, w.KV, d.ldkv, cnt, w.prob, w.dOmat, d.ldh, w.dq, w.dKV, w.q_part, s,
+                zs);
+  if (by_root) {
+    OutMap m;
+    memset(&m, 0, sizeof(m));
+    m.n_split = 1 << 30; m.k_split = 1 << 30;
+    m.head_n = d.dO / d.H; m.head_k = d.dcp; m.head_cols = d.de + d.dt;
+    m.p[0][0] = g->wk + d.dx; m.ld[0][0] = d.dkv;
+    tn.add(w.Qroot, d.ldh, w.Zs, d.ldz, R, d.dO, d.H * d.dcp, m);
+    m.p[0][0] = g->wv + d.dx;
+    tn.add(w.dOmat, d.ldh, w.Zp, d.ldz, R, d.dO, d.H * d.dcp, m);
+  } else if (d.de + d.dt > 0) {
     OutMap kv;
     memset(&kv, 0, sizeof(kv));
     kv.p[0][0] = g->wk + d.dx; kv.p[1][0] = g->wv + d.dx; kv.ld[0][0] = kv.ld[1][0] = d.dkv;
@@ -360,6 +386,7 @@ int32_t tgnn_create(const tgnn_config* cfg, tgnn_ctx** out) {
   d.d_in = 2 * d.dm + d.dt + d.de; d.dx = d.dm + d.ds; d.dq = d.dx + d.dt; d.dkv = d.dx + d.de + d.dt; d.dO = d.dm;
   d.ldx = padrow(d.d_in); d.ldh = padrow(d.dm); d.ld3 = padrow(3 * d.dm); d.ldxr = padrow(d.dx);
   d.ldce = padrow(d.de + d.dt); d.ldkv = padrow(2 * d.dO); d.ldp = 2 * d.ldkv; d.ldt = padrow(d.dt);
+  d.dcp = (d.de + d.dt + 3) & ~3; d.ldz = padrow(d.H * d.dcp);
   const int nb = d.nrep < TGNN_MAX_BATCHES ? d.nrep : TGNN_MAX_BATCHES;
   const long long maxEv = (long long)d.maxB * nb;
   if (maxEv * 3 * (1 + d.k) > 0x3fffffffLL) {
@@ -857,11 +884,12 @@ static int enqueue_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
     tm.end(13);
   }
   tm.begin(14);
-  attn_backward(ctx, grads, p, R, w.slot_row, w.cnt, tn, side, false, s, chain);
+  AttnSums sums;
+  attn_backward(ctx, grads, p, R, w.slot_row, w.cnt, tn, side, false, s, chain, &sums);
   tm.end(14);
   tm.begin(15);
   // per-row sum of the slot gradients reaching the per-node projections (the query's Phi(0) gradients ride along)
-  seg_reduce(ctx, R, S, qphi_args(ctx, p, grads), s);
+  seg_reduce(ctx, R, S, qphi_args(ctx, p, grads), s, sums);
   {  // the product onto the keys' time encoding is independent of this chain: it shares the launch
     const NtProblem keys_phi = keys_phi_problem(ctx, p, grads, RK);
     node_proj_backward(ctx, grads, U, w.ucount, tn, true, s, &keys_phi);

@@ -25,6 +25,8 @@ struct Dims {
   int ldkv;   // rows of width 2 d_o  (K | V), also decoder input {z_a | z_b}
   int ldp;    // per-node projections {K | V || q | merge}: two halves of pitch ldkv
   int ldt;    // rows of width d_t
+  int dcp;    // d_e + d_t rounded up to 4: a head's block of a row of Zs / Zp
+  int ldz;    // rows of width H * dcp
   int maxEv, maxR, maxRK, maxS, maxU;
 };
 
@@ -70,6 +72,8 @@ struct Ws {
   float *P, *dP;                               // [S,ldp]
   float *CE, *KV, *prob, *Omat, *z;            // [RK,ldce] [RK,ldkv] [R,H*k] [R,ldh] [R,ldh]
   float *dz, *dOmat, *dq, *dKV;                // [R,ldh] [R,ldh] [R,ldh] [RK,ldkv]
+  float *Zs, *Zp, *Qroot;                      // [R,ldz] x 2 (per head: sums of the slots' {e | Phi} rows), [R,ldh]
+  float *dscore;                               // [R,H*k] gradients of the attention scores
   // decoder
   float *Pdec, *dPdec, *h1, *logits;           // [R,ldkv] [R,ldkv] [2B,ldh] [2B]
   float* loss_acc;                                   // [TGNN_MAX_BATCHES] per-batch loss sums
@@ -251,11 +255,15 @@ void gemm_nt_group(const NtProblem* probs, int n, hipStream_t s, const WbArgs* t
 
 // Where the weight-gradient GEMM adds its result: element (n, k) goes to p[n >= n_split][k >= k_split]
 // (indices taken relative to the split) with row pitch ld[..][..]; column sums of D go to bias[n >= n_split].
+// head_k > 0 (then only p[0][0] is used): A holds one block of head_k columns per attention head and D's columns
+// belong to heads of head_n columns each; element (n, k) is kept only where both heads agree, and goes to
+// column k % head_k (dropped when >= head_cols) of row n.
 struct OutMap {
   float* p[2][2];
   int ld[2][2];
   int n_split, k_split;
   float* bias[2];
+  int head_n, head_k, head_cols;
 };
 // One weight-gradient problem G[n, k] += sum_m D[m, n] * A[m, k] and a group of them for one launch.
 struct TnProblem {
@@ -271,7 +279,7 @@ struct TnProblem {
   int rot, lane_begin[8];
   OutMap out;
 };
-constexpr int TN_MAX_GROUP = 8;
+constexpr int TN_MAX_GROUP = 10;
 struct TnGroup {
   TnProblem p[TN_MAX_GROUP];
   int n;
@@ -409,7 +417,25 @@ struct SortArgs {
 };
 SortArgs sort_args(tgnn_ctx* ctx, int S);
 // dP[row] += {dKV[slot] | 0} of the row's neighbour slots and {0 | dq[r] | dz[r]} of its root slots
-void seg_reduce(tgnn_ctx* ctx, int R, int S, const QPhi& qphi, hipStream_t s);   // qphi: see QPhi (rides along)
+// Optional extra outputs of the attention backward pass (Zs == NULL: none): per root and head, the sums of its
+// slots' {e | Phi} rows CE weighted by the score gradients (Zs) and by the softmax weights (Zp), rows of H blocks
+// of dcp floats (dcols of them used); and the root's query row (Qroot, pitch of dq).
+// later == true: the kernel only stores the score gradients (ds_out [R, H k]) and Qroot, and the sums are taken
+// by zsum_block in a later launch, where they are spread over more wavefronts.
+struct AttnSums {
+  const float* CE = nullptr;
+  int ldce = 0, dcols = 0, dcp = 0, ldz = 0;
+  float *Zs = nullptr, *Zp = nullptr, *Qroot = nullptr;
+  bool later = false;
+  float* ds_out = nullptr;
+  const float* prob = nullptr;   // softmax weights [R, H k] (for zsum_block)
+  const int32_t* cnt = nullptr;
+  int R = 0, k = 0, H = 0;
+};
+// blocks of 256 threads; one wavefront per root
+__host__ __device__ inline int zsum_blocks(const AttnSums& a) { return a.later && a.Zs != nullptr ? (a.R + 3) / 4 : 0; }
+// qphi, zs: ride along in the first blocks (see QPhi; AttnSums with later == true)
+void seg_reduce(tgnn_ctx* ctx, int R, int S, const QPhi& qphi, hipStream_t s, const AttnSums& zs = AttnSums());
 // the same with slot = row (standalone attention call): plain stores, every row of dP written
 void slots_to_dp(tgnn_ctx* ctx, int R, int RK, const QPhi& qphi, hipStream_t s);
 void expand_rows(tgnn_ctx* ctx, int S, const float* src, int ld, const double* src_d, float* dst, double* dst_d,
@@ -494,7 +520,7 @@ void attn_core_fwd(const Dims& d, int R, const float* q, int ldq_, const int32_t
                    const SortArgs& fill = SortArgs());
 void attn_core_bwd(const Dims& d, int R, const float* q, int ldq_, const int32_t* slot_row, const float* KV, int ldkv,
                    const int32_t* cnt, const float* prob, const float* dOmat, int ldo, float* dq, float* dKV, float* q_part,
-                   hipStream_t s);
+                   hipStream_t s, const AttnSums& zs = AttnSums());
 
 // ---- k_decoder.hip ------------------------------------------------------------------
 void decoder_pairs(const Dims& d, const BatchSet* bs, int total, const float* Pdec, int ldp, const float* b1,
