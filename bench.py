@@ -40,11 +40,13 @@ STAGE_ASSEMBLE, STAGE_KV, STAGE_WGRAD, STAGE_EMPTY = 7, 8, 16, 18
 
 
 def flops_wgrad(d, n_roots, n_rows):
-    """Executed flops of the grouped weight-gradient launch, G += D^T A per problem (2 M N K each; bias gradients
-    are one more column): decoder hidden layer and merge layer over the roots, the {e | Phi} columns of W_k / W_v over
-    the neighbour slots, the node columns of W_k, W_v, W_q, W_o and the two GRU matrices over the distinct node rows."""
-    R, RK, U, dO = n_roots, n_roots * d.k, n_rows, d.d_out
-    macs = (R * 2 * dO * (dO + 1) + R * dO * dO + RK * 2 * dO * (d.d_edge + d.d_time)
+    """Useful flops of the grouped weight-gradient launch, G += D^T A per problem (2 M N K each; bias gradients
+    are one more column): decoder hidden layer and merge layer over the roots, the {e | Phi} columns of W_k / W_v as
+    two products over the roots (a column of q / dO meets the d_e + d_t columns of its own head's block of the
+    per-root sums; the launch also runs the blocks of tiles that straddle a head boundary, which are not counted),
+    the node columns of W_k, W_v, W_q, W_o and the two GRU matrices over the distinct node rows."""
+    R, U, dO = n_roots, n_rows, d.d_out
+    macs = (R * 2 * dO * (dO + 1) + R * dO * dO + 2 * R * dO * (d.d_edge + d.d_time)
             + 2 * U * 2 * dO * (d.d_x + 1) + U * 3 * d.d_mem * (d.d_in + 1) + U * 3 * d.d_mem * (d.d_mem + 1))
     return 2.0 * macs
 
