@@ -119,9 +119,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, (TN <= 5
       if (B_F4 % 256 == 0 || f < B_F4) *reinterpret_cast<floatx4*>(&Bs[buf][nt_swz(f >> 3, f & 7)]) = r.b[u];
     }
   };
-  auto compute = [&](int buf) __attribute__((always_inline)) {
+  // the last stage stops after its first slab when the live columns end there
+  const int k_tail = q.k_live > 0 ? q.k_live - (Kp - NT_BK) : NT_BK;
+  const bool short_tail = k_tail > 0 && k_tail <= 16;
+  auto compute = [&](int buf, bool last = false) __attribute__((always_inline)) {
 #pragma unroll
     for (int h = 0; h < 2; ++h) {  // two 16-wide k slabs per stage
+      if (h == 1 && last && short_tail) break;
       const floatx4 a4 = *reinterpret_cast<const floatx4*>(&As[buf][nt_swz(wave * 16 + li, h * 4 + lg)]);
       floatx4 b4[TN];
 #pragma unroll
@@ -179,15 +183,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, (TN <= 5
   // 1, 2 or 3 stages remain: kt (in LDS 0), kt+1 (in set 1), kt+2 (not loaded yet)
   const int rem = nk - kt;
   if (rem == 3) gload(r0, (kt + 2) * NT_BK);
-  compute(0);
+  compute(0, rem == 1);
   if (rem >= 2) {
     sstore(r1, 1);
     __syncthreads();
-    compute(1);
+    compute(1, rem == 2);
     if (rem == 3) {
       sstore(r0, 0);
       __syncthreads();
-      compute(0);
+      compute(0, true);
     }
   }
 

@@ -187,8 +187,8 @@ struct StageTimer {
 static void gru_forward(tgnn_ctx* ctx, const tgnn_params* p, int n, hipStream_t s) {
   const Dims& d = ctx->d; Ws& w = ctx->w;
   const NtProblem pr[2] = {
-      nt_problem(w.X, d.ldx, w.Wih_p, d.ldx, p->gru_bih, w.gi, d.ld3, n, 3 * d.dm, d.ldx, d.ld3, false),
-      nt_problem(w.Hm, d.ldh, w.Whh_p, d.ldh, p->gru_bhh, w.gh, d.ld3, n, 3 * d.dm, d.ldh, d.ld3, false)};
+      nt_live(nt_problem(w.X, d.ldx, w.Wih_p, d.ldx, p->gru_bih, w.gi, d.ld3, n, 3 * d.dm, d.ldx, d.ld3, false), d.d_in),
+      nt_live(nt_problem(w.Hm, d.ldh, w.Whh_p, d.ldh, p->gru_bhh, w.gh, d.ld3, n, 3 * d.dm, d.ldh, d.ld3, false), d.dm)};
   gemm_nt_group(pr, 2, s);
   gru_gates_fwd(gru_gates_args(d, n, nullptr, w.gi, w.gh, w.Hm, w.has, w.gates, w.Xrow, d.ldxr, nullptr, nullptr, nullptr, 0), s);
 }
@@ -204,12 +204,15 @@ static void attn_forward(tgnn_ctx* ctx, const tgnn_params* p, int R, int n_rows,
   const Dims& d = ctx->d; Ws& w = ctx->w;
   const int RK = R * d.k;
   if (tm) tm->begin(9);
-  gemm_nt(w.Xrow, d.ldxr, w.Wx, d.ldxr, w.bias_x, w.P, d.ldp, n_rows, d.ldkv + 2 * d.dO, d.ldxr, d.ldp, false, s,
-          n_rows_dev);
+  const NtProblem node_part = nt_live(nt_problem(w.Xrow, d.ldxr, w.Wx, d.ldxr, w.bias_x, w.P, d.ldp, n_rows,
+                                                 d.ldkv + 2 * d.dO, d.ldxr, d.ldp, false, n_rows_dev), d.dx);
+  gemm_nt_group(&node_part, 1, s);
   if (tm) { tm->end(9); tm->begin(8); }
   RowAdd kv_add;
   kv_add.src = w.P; kv_add.ld = d.ldp; kv_add.index = slot_row ? slot_row + R : nullptr; kv_add.row0 = R;
-  gemm_nt(w.CE, d.ldce, w.Wce, d.ldce, nullptr, w.KV, d.ldkv, RK, 2 * d.dO, d.ldce, d.ldkv, false, s, nullptr, kv_add);
+  const NtProblem slot_part = nt_live(nt_problem(w.CE, d.ldce, w.Wce, d.ldce, nullptr, w.KV, d.ldkv, RK, 2 * d.dO, d.ldce,
+                                                 d.ldkv, false, nullptr, kv_add), d.de + d.dt);
+  gemm_nt_group(&slot_part, 1, s);
   if (tm) { tm->end(8); tm->begin(10); }
   attn_core_fwd(d, R, w.P + d.ldkv, d.ldp, slot_row, w.KV, d.ldkv, cnt, w.prob, w.Omat, d.ldh, s, fill);
   if (!with_merge) {   // the caller's next launch holds the merge layer
@@ -238,8 +241,8 @@ static NtProblem keys_phi_problem(tgnn_ctx* ctx, const tgnn_params* p, tgnn_para
   const Dims& d = ctx->d; Ws& w = ctx->w;
   TimeGradOut tg;
   tg.delta = w.dtk; tg.w = p->time_w; tg.b = p->time_b; tg.g_w = g->time_w; tg.g_b = g->time_b;
-  return nt_problem(w.dKV, d.ldkv, w.WceT_phi, d.ldkv, nullptr, nullptr, d.ldt, RK, d.dt, d.ldkv, d.ldt, false, nullptr,
-                    RowAdd(), tg);
+  return nt_live(nt_problem(w.dKV, d.ldkv, w.WceT_phi, d.ldkv, nullptr, nullptr, d.ldt, RK, d.dt, d.ldkv, d.ldt, false,
+                            nullptr, RowAdd(), tg), 2 * d.dO);
 }
 
 // From ws.dz (already masked by the merge ReLU) down to ws.dKV and ws.dq; queues the weight-gradient GEMMs of
@@ -309,8 +312,8 @@ static void node_proj_backward(tgnn_ctx* ctx, tgnn_params* g, int n_rows, const 
     gb.gates = w.gates; gb.Hm = w.Hm; gb.has = w.has; gb.dgi = w.dgi; gb.dgh = w.dgh;
     gb.dm = d.dm; gb.ldh = d.ldh; gb.ld3 = d.ld3;
   }
-  const NtProblem mine = nt_problem(w.dP, d.ldp, w.WxT, d.ldp, nullptr, w.ds_row, d.ldh, n_rows, d.dm, d.ldp, d.ldh, false,
-                                    n_rows_dev, RowAdd(), TimeGradOut(), gb);
+  const NtProblem mine = nt_live(nt_problem(w.dP, d.ldp, w.WxT, d.ldp, nullptr, w.ds_row, d.ldh, n_rows, d.dm, d.ldp, d.ldh,
+                                            false, n_rows_dev, RowAdd(), TimeGradOut(), gb), d.ldkv + 2 * d.dO);
   if (with != nullptr) {
     const NtProblem pr[2] = {mine, *with};   // the few, long workgroups of this one start first
     gemm_nt_group(pr, 2, s);
@@ -421,6 +424,9 @@ int32_t tgnn_create(const tgnn_config* cfg, tgnn_ctx** out) {
   e = hipStreamCreateWithFlags(&ctx->side, hipStreamNonBlocking);
   for (int i = 0; i < 16 && e == hipSuccess; ++i) e = hipEventCreateWithFlags(&ctx->fork_ev[i], hipEventDisableTiming);
   if (e != hipSuccess) {
+    for (int i = 0; i < 16; ++i)
+      if (ctx->fork_ev[i]) (void)hipEventDestroy(ctx->fork_ev[i]);
+    if (ctx->side) (void)hipStreamDestroy(ctx->side);
     (void)hipFree(ctx->arena);
     delete ctx;
     return set_error(TGNN_E_HIP, "stream/event creation failed: %s", hipGetErrorString(e));
@@ -820,8 +826,10 @@ static int enqueue_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
   tm.begin(4);
   {  // W_ih x and W_hh h are independent: one launch
     const NtProblem pr[2] = {
-        nt_problem(w.X, d.ldx, w.Wih_p, d.ldx, p->gru_bih, w.gi, d.ld3, U, 3 * d.dm, d.ldx, d.ld3, false, w.ucount),
-        nt_problem(w.Hm, d.ldh, w.Whh_p, d.ldh, p->gru_bhh, w.gh, d.ld3, U, 3 * d.dm, d.ldh, d.ld3, false, w.ucount)};
+        nt_live(nt_problem(w.X, d.ldx, w.Wih_p, d.ldx, p->gru_bih, w.gi, d.ld3, U, 3 * d.dm, d.ldx, d.ld3, false, w.ucount),
+                d.d_in),
+        nt_live(nt_problem(w.Hm, d.ldh, w.Whh_p, d.ldh, p->gru_bhh, w.gh, d.ld3, U, 3 * d.dm, d.ldh, d.ld3, false, w.ucount),
+                d.dm)};
     gemm_nt_group(pr, 2, s);
   }
   tm.end(4);
@@ -911,8 +919,8 @@ static int enqueue_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
      // mails and the SGD update.
     TimeGradOut tg;
     tg.delta = w.delta; tg.w = p->time_w; tg.b = p->time_b; tg.g_w = grads->time_w; tg.g_b = grads->time_b;
-    const NtProblem pr = nt_problem(w.dgi, d.ld3, w.WihT_phi, d.ld3, nullptr, nullptr, d.ldt, U, d.dt, d.ld3, d.ldt, false,
-                                    w.ucount, RowAdd(), tg);
+    const NtProblem pr = nt_live(nt_problem(w.dgi, d.ld3, w.WihT_phi, d.ld3, nullptr, nullptr, d.ldt, U, d.dt, d.ld3, d.ldt,
+                                            false, w.ucount, RowAdd(), tg), 3 * d.dm);
     const WbArgs wb = writeback_args(d, w.bs_dev, bs.total, st, w.winkey, w.epoch, w.Xrow, d.ldxr, w.tau, w.slot_row, nullptr,
                                      nullptr, nullptr, nullptr, out_winner, lr != 0.0f ? w.sgd_dev : nullptr, sgd_set.cnt, lr);
     gemm_nt_group(&pr, 1, s, &wb);

@@ -229,6 +229,7 @@ struct NtProblem {
   const float *A, *B, *bias;
   float* C;
   int lda, ldb, ldc, M, N, Kp, n_store, relu;
+  int k_live;   // columns >= k_live of A and B are padding (0: not stated); lets the last stage stop after 16 columns
   const int* m_dev;
   int col_tiles, wg_begin;
   RowAdd add;
@@ -247,10 +248,12 @@ inline NtProblem nt_problem(const float* A, int lda, const float* B, int ldb, co
                             const GruBwdOut& gb = GruBwdOut()) {
   NtProblem p;
   p.A = A; p.B = B; p.bias = bias; p.C = C; p.lda = lda; p.ldb = ldb; p.ldc = ldc; p.M = M; p.N = N; p.Kp = Kp;
-  p.n_store = n_store; p.relu = relu ? 1 : 0; p.m_dev = m_dev; p.col_tiles = 0; p.wg_begin = 0;
+  p.n_store = n_store; p.relu = relu ? 1 : 0; p.k_live = 0; p.m_dev = m_dev; p.col_tiles = 0; p.wg_begin = 0;
   p.add = add; p.tg = tg; p.gb = gb;
   return p;
 }
+// the same problem with its live column count stated
+inline NtProblem nt_live(NtProblem p, int k_live) { p.k_live = k_live; return p; }
 void gemm_nt_group(const NtProblem* probs, int n, hipStream_t s, const WbArgs* tail = nullptr);
 
 // Where the weight-gradient GEMM adds its result: element (n, k) goes to p[n >= n_split][k >= k_split]
