@@ -451,6 +451,8 @@ __device__ __forceinline__ void tn_piece(int len, int idx, int& off, int& width)
   else if (r <= 48) { if (idx == full) width = 32; else { off += 32; width = 16; } }
   else width = TT;
 }
+// Column window of D that one head of head_n columns is tiled over (its start is rounded down to 16 bytes).
+__host__ __device__ inline int tn_head_width(int head_n) { return head_n + 3; }
 
 template <int TD> struct FragT;
 template <> struct FragT<1> { typedef float type; };
@@ -492,10 +494,10 @@ __device__ __forceinline__ int tn_slot(int t, int u, int v, int li, int lg) {
 }
 
 template <int TD, int TA>
-__device__ __forceinline__ void tn_tile(const float* __restrict__ D, const float* __restrict__ A, int ldd, int lda, int N,
-                                        int K, float* p00, float* p01, float* p10, float* p11, int ld00, int ld01, int ld10,
-                                        int ld11, int n_split, int k_split, float* bias0, float* bias1, int M, int m_lo,
-                                        int m_hi, int n0, int k0, float* lds, int head_n, int head_k, int head_cols) {
+__device__ __forceinline__ void tn_tile(const float* __restrict__ D, const float* __restrict__ A, int ldd, int lda, int dw,
+                                        int aw, int n_lo, int N, int K, float* p00, float* p01, float* p10, float* p11,
+                                        int ld00, int ld01, int ld10, int ld11, int n_split, int k_split, float* bias0,
+                                        float* bias1, int M, int m_lo, int m_hi, int n0, int k0, float* lds) {
   typedef typename FragT<TD>::type FD;
   typedef typename FragT<TA>::type FA;
   const bool with_bias = bias0 != nullptr || bias1 != nullptr;   // column K of A reads as ones
@@ -512,16 +514,19 @@ __device__ __forceinline__ void tn_tile(const float* __restrict__ D, const float
   // Column offsets are clamped into the row (results of columns >= N or > K are dropped at the end); rows
   // >= m_hi are clamped and D is zeroed there by a select when the step is used.
   const int c_nom = k0 + TA * li;
-  const float* pd = D + min(n0 + TD * li, ldd - TD);
-  const float* pa = A + min(c_nom, lda - TA);
+  const float* pd = D + min(n0 + TD * li, dw - TD);   // dw, aw: columns that may be read from D, A (<= the pitch)
+  const float* pa = A + min(c_nom, aw - TA);
   const int one_comp = (with_bias && K >= c_nom && K < c_nom + TA) ? K - c_nom : -1;
   const int n_steps = (m_hi - m_lo + 3) >> 2;
 
   // The loads are issued as inline assembly and waited for by count: left to itself the compiler sinks them
   // next to their uses and the wavefront then waits out the full memory latency at every step.  Loads return in
   // order, so when slot p is needed only the loads of the other TN_AHEAD - 1 slots (two each) may be pending.
-  FD fd[TN_AHEAD];
-  FA fa[TN_AHEAD];
+  // 4-row steps whose loads a wavefront keeps in flight: a step of a narrow tile has few MFMAs to hide the
+  // memory latency behind, so more of them are kept in flight.
+  constexpr int AH = TD * TA >= 16 ? TN_AHEAD : TD * TA >= 8 ? TN_AHEAD + 2 : 2 * TN_AHEAD;
+  FD fd[AH];
+  FA fa[AH];
   auto issue = [&](int step, FD& d, FA& a) __attribute__((always_inline)) {
     const size_t m = (size_t)min(m_lo + 4 * step + lg, M - 1);
     tn_issue_load<TD>(d, pd + m * ldd);
@@ -546,37 +551,34 @@ __device__ __forceinline__ void tn_tile(const float* __restrict__ D, const float
   // unevenly (the oldest wins the MFMA pipe), and with a fixed split the youngest would still be at work, alone
   // and unable to hide its load latency, long after the others had reached the barrier below.
   int* next_step = reinterpret_cast<int*>(lds + (TN_W / 2) * TT * TT);
-  if (tid == 0) *next_step = TN_W * TN_AHEAD;
-  __syncthreads();
   auto claim = [&]() __attribute__((always_inline)) {
     int v = 0;
     if (lane == 0) v = atomicAdd(next_step, 1);
     return __builtin_amdgcn_readfirstlane(v);
   };
-  int sidx[TN_AHEAD];   // the step each slot holds; claims only grow, so a slot past the end means all later are
+  int sidx[AH];   // the step each slot holds; claims only grow, so a slot past the end means all later are
 #pragma unroll
-  for (int p = 0; p < TN_AHEAD; ++p) {
+  for (int p = 0; p < AH; ++p) {
     sidx[p] = wave + p * TN_W;
     issue(sidx[p], fd[p], fa[p]);   // past the end: clamped rows, unused
   }
+  if (tid == 0) *next_step = TN_W * AH;   // (after the first loads are on their way)
+  __syncthreads();
   int nxt = claim();
-  static_assert(TN_AHEAD == 4, "the loop below is written out for four slots");
-#define TGNN_TN_SUBSTEP(P)                                   \
-  {                                                          \
-    tn_wait_loads<2 * (TN_AHEAD - 1)>(fd[P], fa[P]);         \
-    if (sidx[P] < n_steps) use(sidx[P], fd[P], fa[P]);       \
-    sidx[P] = nxt;                                           \
-    issue(nxt, fd[P], fa[P]);                                \
-    nxt = claim();                                           \
-  }
   // slot 0 holds the oldest claim: once that is past the end, so are the others
   while (sidx[0] < n_steps) {
-    TGNN_TN_SUBSTEP(0) TGNN_TN_SUBSTEP(1) TGNN_TN_SUBSTEP(2) TGNN_TN_SUBSTEP(3)
+#pragma unroll
+    for (int p = 0; p < AH; ++p) {   // (unrolled: the slots are registers)
+      tn_wait_loads<2 * (AH - 1)>(fd[p], fa[p]);
+      if (sidx[p] < n_steps) use(sidx[p], fd[p], fa[p]);
+      sidx[p] = nxt;
+      issue(nxt, fd[p], fa[p]);
+      nxt = claim();
+    }
   }
-#undef TGNN_TN_SUBSTEP
   // every issued load has to land before its registers are given to anything else
 #pragma unroll
-  for (int p = 0; p < TN_AHEAD; ++p) tn_wait_loads<0>(fd[p], fa[p]);
+  for (int p = 0; p < AH; ++p) tn_wait_loads<0>(fd[p], fa[p]);
 
   // Add the wavefronts' partial tiles in LDS: the lower half of the wavefronts store theirs into a buffer
   // each, the upper half add theirs on top, then every thread sums the buffers for its elements and issues
@@ -608,16 +610,11 @@ __device__ __forceinline__ void tn_tile(const float* __restrict__ D, const float
     if (TILE % NT != 0 && e >= TILE) break;
     const int tn = e / TW, tk = e % TW;           // position in the tile
     const int n = n0 + tn, k = k0 + tk;
-    if (n >= N || k > K) continue;
+    if (n < n_lo || n >= N || k > K) continue;
     const int slot = tn_slot<TA>(tn % TD, tk % TA, (tn / TD) & 3, tk / TA, tn / (4 * TD));
     float x = 0.f;
 #pragma unroll
     for (int b = 0; b < NB; ++b) x += lds[b * TILE + slot];
-    if (head_k > 0) {   // per-head blocks: kept only where the head of D's column is the head of A's block
-      const int h = k / head_k, kk = k - h * head_k;
-      if (n / head_n == h && kk < head_cols) atomicAdd(p00 + (size_t)n * ld00 + kk, x);
-      continue;
-    }
     // (selects instead of indexing: a dynamically indexed local array would live in scratch memory)
     const bool ns = n >= n_split;
     const int nn = n - (ns ? n_split : 0);
@@ -633,6 +630,7 @@ __device__ __forceinline__ void tn_tile(const float* __restrict__ D, const float
   }
 }
 
+static_assert(sizeof(TnGroup) <= 4096, "the group travels as a kernel argument");
 __global__ __launch_bounds__(64 * TN_W) void gemm_tn_kernel(TnGroup grp) {
   // Several independent problems share one launch (all weight gradients of a step): find this workgroup's.
   // The argument block is indexed through the kernel-argument segment itself (scalar loads at a computed
@@ -640,43 +638,68 @@ __global__ __launch_bounds__(64 * TN_W) void gemm_tn_kernel(TnGroup grp) {
   typedef const TnGroup __attribute__((address_space(4))) * GroupPtr;
   const GroupPtr gp = (GroupPtr)__builtin_amdgcn_kernarg_segment_ptr();
   const int xcd = blockIdx.x & 7, pos = blockIdx.x >> 3;
-  int pi = -1, local = 0, v = 0;
-  for (int i = 0; i < gp->n; ++i) {
-    const int vi = (xcd + gp->p[i].rot) & 7;
-    const int cnt = gp->p[i].chunks > vi ? gp->p[i].tiles * ((gp->p[i].chunks - vi + 7) >> 3) : 0;
-    const int begin = gp->p[i].lane_begin[xcd];
-    if (pos >= begin && pos < begin + cnt) { pi = i; local = pos - begin; v = vi; }
-  }
-  if (pi < 0) return;   // this XCD's queue is shorter than the longest one
+  // (a loop over the problems with its scalar loads one after the other took 5 us before the first row was asked for)
+  typedef int int16v __attribute__((ext_vector_type(16)));
+  typedef unsigned uint4v __attribute__((ext_vector_type(4)));
+  const int16v qb = *reinterpret_cast<const int16v __attribute__((address_space(4)))*>(&gp->qbegin[xcd][0]);
+  const uint4v qp = *reinterpret_cast<const uint4v __attribute__((address_space(4)))*>(&gp->qprob[0]);
+  int slot = -1, begin = 0, end = 0;
+#pragma unroll
+  for (int t = 0; t < TN_MAX_GROUP; ++t)
+    if (pos >= qb[t]) { slot = t; begin = qb[t]; end = qb[t + 1]; }
+  if (slot < 0 || slot >= gp->n || pos >= end) return;   // this XCD's queue is shorter than the longest one
+  unsigned word = qp[0];
+#pragma unroll
+  for (int t = 1; t < 4; ++t)
+    if ((slot >> 2) == t) word = qp[t];
+  const int pi = (word >> (8 * (slot & 3))) & 255u;
+  const int local = pos - begin;
   const auto& q = gp->p[pi];
-  const int k_tiles = q.k_tiles, tiles = q.tiles, chunks = q.chunks, N = q.N, K = q.K;
+  const int v = (xcd + q.rot) & 7;
+  const int tiles = q.tiles, chunks = q.chunks, N = q.N, K = q.K;
   int M = q.M, m_chunk = q.m_chunk;
   const int* m_dev = q.m_dev;
   float* const bias0 = q.out.bias[0];
   const bool with_bias = bias0 != nullptr || q.out.bias[1] != nullptr;
-  const int chunk = (local / tiles) * 8 + v, tile = local % tiles;
+  const int chunk = (local / tiles) * 8 + v;
+  int tile = local % tiles;
   if (m_dev != nullptr) {  // row count known only on the device: split it evenly over the launched chunks
     M = min(M, *m_dev);
     m_chunk = ((M + chunks - 1) / chunks + TN_ROWS - 1) / TN_ROWS * TN_ROWS;
   }
   if (chunk * m_chunk >= M) return;   // uniform for the workgroup, before any barrier
   __shared__ __attribute__((aligned(16))) float lds[(TN_W / 2) * TT * TT + 4];   // reduction buffers + step counter
-  const int m_lo = chunk * m_chunk;
-  const int m_hi = min(M, m_lo + m_chunk);
-  int n0, wn, k0, wk;
-  tn_piece(N, tile / k_tiles, n0, wn);
-  tn_piece(K + (with_bias ? 1 : 0), tile % k_tiles, k0, wk);
-  if (q.out.head_k > 0) {   // a tile whose columns of D and of A share no head has nothing to add
-    const int hn_lo = n0 / q.out.head_n, hn_hi = (min(n0 + wn, N) - 1) / q.out.head_n;
-    const int hk_lo = k0 / q.out.head_k, hk_hi = (min(k0 + wk, K) - 1) / q.out.head_k;
-    if (hn_hi < hk_lo || hk_hi < hn_lo) return;   // uniform for the workgroup, before any barrier
+  int m_lo = chunk * m_chunk;
+  int m_hi = min(M, m_lo + m_chunk);
+  // A problem with per-head blocks is H problems of the same shape side by side: head h multiplies columns
+  // [h head_n, (h + 1) head_n) of D with columns [h head_k, h head_k + head_cols) of A.  Its column window of D
+  // starts at the 16-byte boundary below the head's first column; the columns in front are not written.
+  const float* Dp = q.D;
+  const float* Ap = q.A;
+  float* p00 = q.out.p[0][0];
+  int dw = q.ldd, aw = q.lda, n_lo = 0, n_hi = N, n_tiling = N, Kt = K;
+  if (q.out.head_k > 0) {
+    const int per_head = tiles / q.heads, h = tile / per_head;
+    tile -= h * per_head;
+    const int first = h * q.out.head_n, a0 = first & ~3;
+    Dp += a0; dw -= a0;
+    Ap += h * q.out.head_k; aw -= h * q.out.head_k;
+    p00 += (size_t)a0 * q.out.ld[0][0];
+    n_lo = first - a0; n_hi = n_lo + q.out.head_n;
+    n_tiling = tn_head_width(q.out.head_n);
+    Kt = q.out.head_cols;
   }
+  const int Kb = Kt + (with_bias ? 1 : 0);
+  const int k_tiles = tn_pieces(Kb);
+  const int np = tile / k_tiles, kp = tile - np * k_tiles;
+  int n0, wn, k0, wk;
+  tn_piece(n_tiling, np, n0, wn);
+  tn_piece(Kb, kp, k0, wk);
 #define TGNN_TN_CASE(WN, WK)                                                                                          \
   if (wn == WN && wk == WK) {                                                                                         \
-    tn_tile<WN / 16, WK / 16>(q.D, q.A, q.ldd, q.lda, N, K, q.out.p[0][0], q.out.p[0][1], q.out.p[1][0], q.out.p[1][1], \
-                              q.out.ld[0][0], q.out.ld[0][1], q.out.ld[1][0], q.out.ld[1][1], q.out.n_split,           \
-                              q.out.k_split, bias0, q.out.bias[1], M, m_lo, m_hi, n0, k0, lds, q.out.head_n,           \
-                              q.out.head_k, q.out.head_cols);                                                         \
+    tn_tile<WN / 16, WK / 16>(Dp, Ap, q.ldd, q.lda, dw, aw, n_lo, n_hi, Kt, p00, q.out.p[0][1], q.out.p[1][0],          \
+                              q.out.p[1][1], q.out.ld[0][0], q.out.ld[0][1], q.out.ld[1][0], q.out.ld[1][1],            \
+                              q.out.n_split, q.out.k_split, bias0, q.out.bias[1], M, m_lo, m_hi, n0, k0, lds);      \
     return;                                                                                                           \
   }
   TGNN_TN_CASE(64, 64) TGNN_TN_CASE(64, 32) TGNN_TN_CASE(64, 16)
@@ -694,8 +717,13 @@ void TnBatch::add(const float* D, int ldd, const float* A, int lda, int M, int N
     return;
   TnProblem& p = g.p[g.n];
   p.D = D; p.ldd = ldd; p.A = A; p.lda = lda; p.M = M; p.N = N; p.K = K;
-  p.k_tiles = tn_pieces(K + (out.bias[0] != nullptr || out.bias[1] != nullptr ? 1 : 0));
-  p.tiles = tn_pieces(N) * p.k_tiles;
+  if (out.head_k > 0) {   // H problems of head_n x head_cols side by side
+    p.heads = N / out.head_n;
+    p.tiles = p.heads * tn_pieces(tn_head_width(out.head_n)) * tn_pieces(out.head_cols);
+  } else {
+    p.heads = 1;
+    p.tiles = tn_pieces(N) * tn_pieces(K + (out.bias[0] != nullptr || out.bias[1] != nullptr ? 1 : 0));
+  }
   p.m_dev = m_dev; p.out = out;
   g.n++;
 }
@@ -706,10 +734,15 @@ void TnBatch::add(const float* D, int ldd, const float* A, int lda, int M, int N
 // (all weight gradients of a step on a few thousand rows) gets the largest number of row chunks with which
 // no XCD queue exceeds TN_WGS_PER_XCD workgroups, and a large one gets chunks of TN_MAX_ROWS rows and runs
 // in rounds.  An XCD holds 64 workgroups at once (two per compute unit); workgroups with narrow edge tiles
-// finish early, and a queue one and a half times that long measured best on MI355X for the weight gradients
-// of a 600-event step.  All problems of a launch use the same chunk length.
+// finish early, and queues of 72 to 88 measured best on MI355X for the weight gradients of a 600-event step
+// (64 and 96: a fifth slower).  All problems of a launch use the same chunk length.
+// What in-kernel timestamps say about such a launch: a workgroup sees its first rows 3 to 5 us after it starts
+// (argument block, device-side row count, then the rows: three dependent round trips), a wavefront then takes
+// 0.5 to 0.8 us per 4-row step whatever the tile width, because the loads of narrow tiles are 64- to 256-byte
+// pieces of four rows and the texture addresser, not the MFMA pipe, is what the 16 wavefronts of a compute unit
+// queue for; the reduction and the atomics take 2 to 3 us.
 constexpr int TN_MAX_ROWS = 1024;
-constexpr int TN_WGS_PER_XCD = 96;
+constexpr int TN_WGS_PER_XCD = 80;
 
 // Chunks of `rows_per_chunk` rows for every problem, then the placement on the eight XCDs: problems in order
 // of decreasing size, each rotated so that the XCDs which receive one chunk more than the others are the least
@@ -736,10 +769,16 @@ static int tn_place(TnGroup& g, const int* rows, int rows_per_chunk) {
       if (mx < best_max) { best_max = mx; best_rot = r; }
     }
     p.rot = best_rot;
+    g.qprob[oi] = (unsigned char)order[oi];
     for (int x = 0; x < 8; ++x) {
       p.lane_begin[x] = load[x];
+      g.qbegin[x][oi] = load[x];
       load[x] += cnt[(x + best_rot) & 7];
     }
+  }
+  for (int x = 0; x < 8; ++x) {
+    g.qbegin[x][g.n] = load[x];
+    for (int t = g.n + 1; t < 16; ++t) g.qbegin[x][t] = 0x7fffffff;
   }
   return *std::max_element(load, load + 8);
 }

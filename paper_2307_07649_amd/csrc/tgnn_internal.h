@@ -274,7 +274,8 @@ struct TnProblem {
   const float* A;
   const int* m_dev;
   int ldd, lda, M, N, K;
-  int m_chunk, k_tiles, tiles, chunks;
+  int m_chunk, tiles, chunks;   // tiles: workgroups per chunk of rows
+  int heads;                    // out.head_k > 0: number of per-head blocks (N / head_n), else 1
   // Placement of the workgroups (one per chunk and tile).  Workgroup b of the launch runs on XCD b % 8; the
   // workgroups of XCD x form a queue of their own (position b / 8), in which this problem's start at
   // lane_begin[x].  XCD x works on the chunks v, v + 8, ... with v = (x + rot) % 8, all tiles of a chunk in a
@@ -286,6 +287,11 @@ constexpr int TN_MAX_GROUP = 10;
 struct TnGroup {
   TnProblem p[TN_MAX_GROUP];
   int n;
+  // The XCD queues once more, in the form a workgroup reads with two scalar loads: the problems in placement
+  // order (qprob), and per XCD the queue position at which each of them starts, ascending, closed by the end of
+  // the queue and padded with INT_MAX (qbegin).
+  int qbegin[8][16];
+  unsigned char qprob[16];
 };
 struct TnBatch {
   TnGroup g;
