@@ -21,6 +21,12 @@ namespace tgnn {
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
+// A row count that an earlier kernel left in memory, read through the scalar cache (a third of the latency of a
+// vector load; nothing in these kernels writes it).
+__device__ __forceinline__ int load_count(const int* p) {
+  return *reinterpret_cast<const int __attribute__((address_space(4)))*>(reinterpret_cast<size_t>(p));
+}
+
 // ------------------------------------------------------------------------------------------------
 // NT: C = A * B^T.  One workgroup = 4 waves stacked along M (16 rows each); every wave spans the
 // whole 16*TN-wide column tile.  A stage is 32 k-columns.
@@ -66,7 +72,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, (TN <= 5
   const int block = (int)blockIdx.x - q.wg_begin;   // wg_begin is a multiple of 8
   const int xcd = block & 7, slot = block >> 3;
   const int row_tile = (slot / col_tiles) * 8 + xcd, col_tile = slot % col_tiles;
-  if (m_dev != nullptr) M = min(M, *m_dev);
+  if (m_dev != nullptr) M = min(M, load_count(m_dev));
   if (row_tile * BM >= M) return;   // uniform for the workgroup, before any barrier
   constexpr int A_PER = BM * 8 / 256, B_F4 = BN * 8;  // float4 loads per stage and thread
   constexpr int B_PER = (B_F4 + 255) / 256;
@@ -148,16 +154,24 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, (TN <= 5
   // rows this lane writes: m0 + wave * 16 + lg * 4 + v.  Their gather-add source rows (or -1), and then the
   // values to add, are fetched now: two dependent loads that would otherwise sit between the last MFMA and
   // the stores.
-  int arow[4] = {-1, -1, -1, -1};
-  if (add.src != nullptr) {
-#pragma unroll
-    for (int v = 0; v < 4; ++v) {
-      const int row = m0 + wave * 16 + lg * 4 + v;
-      if (row < M) arow[v] = add.index != nullptr ? add.index[row] : row + add.row0;
-    }
-  }
+  // The first two stages are asked for first; the index loads are four independent ones (clamped rows, no
+  // branch between them: one wait, not four).
   gload(r0, 0);
   gload(r1, nk > 1 ? NT_BK : 0);
+  int arow[4] = {-1, -1, -1, -1};
+  if (add.src != nullptr) {
+    const int row0 = m0 + wave * 16 + lg * 4;
+    if (add.index != nullptr) {
+      int idx[4];
+#pragma unroll
+      for (int v = 0; v < 4; ++v) idx[v] = add.index[min(row0 + v, M - 1)];
+#pragma unroll
+      for (int v = 0; v < 4; ++v) arow[v] = row0 + v < M ? idx[v] : -1;
+    } else {
+#pragma unroll
+      for (int v = 0; v < 4; ++v) arow[v] = row0 + v < M ? row0 + v + add.row0 : -1;
+    }
+  }
   sstore(r0, 0);
   float addv[TN][4], bv[TN];
 #pragma unroll
@@ -664,7 +678,7 @@ __global__ __launch_bounds__(64 * TN_W) void gemm_tn_kernel(TnGroup grp) {
   const int chunk = (local / tiles) * 8 + v;
   int tile = local % tiles;
   if (m_dev != nullptr) {  // row count known only on the device: split it evenly over the launched chunks
-    M = min(M, *m_dev);
+    M = min(M, load_count(m_dev));
     m_chunk = ((M + chunks - 1) / chunks + TN_ROWS - 1) / TN_ROWS * TN_ROWS;
   }
   if (chunk * m_chunk >= M) return;   // uniform for the workgroup, before any barrier
