@@ -29,24 +29,31 @@ SortArgs sort_args(tgnn_ctx* ctx, int S) {
 // AttnSums).  One wavefront per root, 16 bytes of a row per lane; a block is four roots.  HM: heads the
 // accumulators are laid out for.
 typedef float zsum_f4 __attribute__((ext_vector_type(4)));
-template <int HM>
+template <int HM, int NP>
 __device__ __forceinline__ void zsum_root(const AttnSums& a, int r, const float* wv, int lane) {
   const int HK = a.H * a.k, n4 = a.dcp >> 2;
   const int c = a.cnt[r];
   constexpr int NJ = 10;   // rows whose loads are issued together
-  for (int f0 = 0; f0 < n4; f0 += 64) {
-    const int f = f0 + lane;
-    const bool on = f < n4;
-    zsum_f4 as[HM], ap[HM];
+  // With NP = 2 a lane takes the 16-byte pieces f0 + lane and f0 + 64 + lane of every row: a row of 65 to 128
+  // pieces (C1: 68) is then one round trip to memory, not two with the second nearly empty.  (NP = 1: the
+  // accumulators for many heads leave no registers for that.)
+  for (int f0 = 0; f0 < n4; f0 += 64 * NP) {
+    const int fa = f0 + lane, fb = f0 + 64 + lane;
+    const bool on_a = fa < n4, on_b = NP > 1 && fb < n4;
+    zsum_f4 as[NP][HM], ap[NP][HM];
 #pragma unroll
-    for (int h = 0; h < HM; ++h) as[h] = ap[h] = zsum_f4{0.f, 0.f, 0.f, 0.f};
+    for (int h = 0; h < HM; ++h)
+#pragma unroll
+      for (int e = 0; e < NP; ++e) as[e][h] = ap[e][h] = zsum_f4{0.f, 0.f, 0.f, 0.f};
     for (int j0 = 0; j0 < c; j0 += NJ) {
-      zsum_f4 ce[NJ];
+      zsum_f4 ce[NP][NJ];
 #pragma unroll
       for (int jj = 0; jj < NJ; ++jj) {
-        ce[jj] = zsum_f4{0.f, 0.f, 0.f, 0.f};
-        if (on && j0 + jj < c)
-          ce[jj] = *reinterpret_cast<const zsum_f4*>(a.CE + ((size_t)r * a.k + j0 + jj) * a.ldce + 4 * f);
+#pragma unroll
+        for (int e = 0; e < NP; ++e) ce[e][jj] = zsum_f4{0.f, 0.f, 0.f, 0.f};
+        const float* row = a.CE + ((size_t)r * a.k + j0 + jj) * a.ldce;
+        if (on_a && j0 + jj < c) ce[0][jj] = *reinterpret_cast<const zsum_f4*>(row + 4 * fa);
+        if (NP > 1 && on_b && j0 + jj < c) ce[NP - 1][jj] = *reinterpret_cast<const zsum_f4*>(row + 4 * fb);
       }
 #pragma unroll
       for (int jj = 0; jj < NJ; ++jj) {
@@ -54,19 +61,29 @@ __device__ __forceinline__ void zsum_root(const AttnSums& a, int r, const float*
 #pragma unroll
           for (int h = 0; h < HM; ++h) {
             if (h < a.H) {
-              as[h] += wv[h * a.k + j0 + jj] * ce[jj];
-              ap[h] += wv[HK + h * a.k + j0 + jj] * ce[jj];
+              const float ws = wv[h * a.k + j0 + jj], wp = wv[HK + h * a.k + j0 + jj];
+#pragma unroll
+              for (int e = 0; e < NP; ++e) {
+                as[e][h] += ws * ce[e][jj];
+                ap[e][h] += wp * ce[e][jj];
+              }
             }
           }
         }
       }
     }
-    if (on) {
 #pragma unroll
-      for (int h = 0; h < HM; ++h) {
-        if (h < a.H) {
-          *reinterpret_cast<zsum_f4*>(a.Zs + (size_t)r * a.ldz + h * a.dcp + 4 * f) = as[h];
-          *reinterpret_cast<zsum_f4*>(a.Zp + (size_t)r * a.ldz + h * a.dcp + 4 * f) = ap[h];
+    for (int h = 0; h < HM; ++h) {
+      if (h < a.H) {
+        float* zs = a.Zs + (size_t)r * a.ldz + h * a.dcp;
+        float* zp = a.Zp + (size_t)r * a.ldz + h * a.dcp;
+        if (on_a) {
+          *reinterpret_cast<zsum_f4*>(zs + 4 * fa) = as[0][h];
+          *reinterpret_cast<zsum_f4*>(zp + 4 * fa) = ap[0][h];
+        }
+        if (NP > 1 && on_b) {
+          *reinterpret_cast<zsum_f4*>(zs + 4 * fb) = as[NP - 1][h];
+          *reinterpret_cast<zsum_f4*>(zp + 4 * fb) = ap[NP - 1][h];
         }
       }
     }
@@ -76,19 +93,24 @@ __device__ __forceinline__ void zsum_root(const AttnSums& a, int r, const float*
 __device__ __forceinline__ void zsum_block(const AttnSums& a, int block) {
   __shared__ float w_lds[4][2 * TGNN_MAX_HEADS * TGNN_MAX_K];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int r = block * 4 + wave;
-  if (r >= a.R) return;   // per wavefront; no block barrier below
   const int HK = a.H * a.k;
   float* wv = w_lds[wave];
-  for (int p = lane; p < HK; p += 64) {
-    wv[p] = a.ds_out[(size_t)r * HK + p];
-    wv[HK + p] = a.prob[(size_t)r * HK + p];
+  // ZSUM_PER_WAVE roots per wavefront, one after the other: the launch this rides in holds two blocks per compute
+  // unit, and with a block per four roots the last of them waited for a free place for half of the launch
+  for (int i = 0; i < ZSUM_PER_WAVE; ++i) {
+    const int r = (block * 4 + wave) * ZSUM_PER_WAVE + i;
+    if (r >= a.R) return;   // per wavefront; no block barrier below
+    for (int p = lane; p < HK; p += 64) {
+      wv[p] = a.ds_out[(size_t)r * HK + p];
+      wv[HK + p] = a.prob[(size_t)r * HK + p];
+    }
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_s_waitcnt(0xc07f);   // the wavefront's LDS writes are visible to all its lanes
+    __builtin_amdgcn_wave_barrier();
+    if (a.H <= 2) zsum_root<2, 2>(a, r, wv, lane);
+    else zsum_root<TGNN_MAX_HEADS, 1>(a, r, wv, lane);
+    __builtin_amdgcn_wave_barrier();   // all lanes are done reading wv before the next root overwrites it
   }
-  __builtin_amdgcn_wave_barrier();
-  __builtin_amdgcn_s_waitcnt(0xc07f);   // the wavefront's LDS writes are visible to all its lanes
-  __builtin_amdgcn_wave_barrier();
-  if (a.H <= 2) zsum_root<2>(a, r, wv, lane);
-  else zsum_root<TGNN_MAX_HEADS>(a, r, wv, lane);
 }
 
 constexpr int SEG_CHUNK = 16;

@@ -441,8 +441,11 @@ struct AttnSums {
   const int32_t* cnt = nullptr;
   int R = 0, k = 0, H = 0;
 };
-// blocks of 256 threads; one wavefront per root
-__host__ __device__ inline int zsum_blocks(const AttnSums& a) { return a.later && a.Zs != nullptr ? (a.R + 3) / 4 : 0; }
+// blocks of 256 threads; ZSUM_PER_WAVE roots per wavefront
+constexpr int ZSUM_PER_WAVE = 2;
+__host__ __device__ inline int zsum_blocks(const AttnSums& a) {
+  return a.later && a.Zs != nullptr ? (a.R + 4 * ZSUM_PER_WAVE - 1) / (4 * ZSUM_PER_WAVE) : 0;
+}
 // qphi, zs: ride along in the first blocks (see QPhi; AttnSums with later == true)
 void seg_reduce(tgnn_ctx* ctx, int R, int S, const QPhi& qphi, hipStream_t s, const AttnSums& zs = AttnSums());
 // the same with slot = row (standalone attention call): plain stores, every row of dP written
