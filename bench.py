@@ -125,6 +125,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--side-stream", action="store_true", help="let the library fork independent work of a step onto its second stream")
     ap.add_argument("--no-stage-events", action="store_true", help="do not time the two roofline kernels inside the timed region (every step then replays a captured HIP graph)")
+    ap.add_argument("--steps-per-call", type=int, default=4,
+                    help="consecutive training steps handed to the library per call (tgnn_train_steps; 1 = tgnn_train_step)")
     ap.add_argument("--event-every", type=int, default=16,
                     help="inside the timed region, every N-th step is launched kernel by kernel with HIP events around "
                          "the two roofline kernels; the other steps replay the captured HIP graph (1: every step)")
@@ -166,6 +168,7 @@ def main():
     params = tgnn.Params.from_numpy(P["params"])
     grads = tgnn.Params.zeros_like(params)
     loss = torch.zeros(4, device="cuda")
+    loss_steps = torch.zeros(tgnn.MAX_STEPS_PER_CALL, device="cuda")
 
     # every mini-batch of the epoch, resident on the device
     import synth
@@ -188,6 +191,35 @@ def main():
         ctx.tgnn_train_step(graph, state, params, grads, bl, lr=args.lr, out_loss=loss)
         return sum(b.n for b in bl)
 
+    per_call = max(1, min(args.steps_per_call, tgnn.MAX_STEPS_PER_CALL))
+    last_loss = [(loss, 0)]   # where the most recent step's loss is
+
+    def run_steps(s_lo, s_hi):
+        """Steps s_lo .. s_hi - 1, per_call of them per library call; a step at which a replica starts a new
+        epoch (memory reset) begins a group of its own.  Returns the events of every step."""
+        done = []
+        s = s_lo
+        while s < s_hi:
+            group = []
+            while s < s_hi and len(group) < per_call:
+                ms = [(s + r * shift) % M for r in range(nrep)]
+                if s > 0 and 0 in ms:
+                    if group:
+                        break
+                    for r in range(nrep):
+                        if ms[r] == 0:
+                            ctx.tgnn_state_reset(state, r)
+                group.append([batches[r][ms[r]] for r in range(nrep)])
+                s += 1
+            if len(group) == 1:
+                ctx.tgnn_train_step(graph, state, params, grads, group[0], lr=args.lr, out_loss=loss)
+                last_loss[0] = (loss, 0)
+            else:
+                ctx.tgnn_train_steps(graph, state, params, grads, group, lr=args.lr, out_loss=loss_steps)
+                last_loss[0] = (loss_steps, len(group) - 1)
+            done += [sum(b.n for b in bl) for bl in group]
+        return done
+
     # a stream of its own: the library replays a captured HIP graph there (the NULL stream cannot be captured)
     torch.cuda.synchronize()
     torch.cuda.set_stream(torch.cuda.Stream())
@@ -195,8 +227,7 @@ def main():
     every = max(1, args.event_every)
     ctx.tgnn_profile_enable(roof_mask)
     ctx.tgnn_profile_every(2)             # warm up both launch modes
-    for s in range(args.warmup):
-        run_step(s)
+    run_steps(0, args.warmup)
     torch.cuda.synchronize()
     ctx.tgnn_profile_enable(roof_mask)    # drops the warm-up's records
     ctx.tgnn_profile_every(every)
@@ -204,15 +235,15 @@ def main():
     ev_timed_launches = 0                 # events of the steps whose roofline kernels were timed
     n_timed_launches = 0
     t0 = time.perf_counter()
-    for s in range(args.warmup, args.warmup + args.steps):
-        n = run_step(s)
-        ev += n
-        if roof_mask != 0 and (s - args.warmup) % every == 0:
-            ev_timed_launches += n
-            n_timed_launches += 1
+    per_step = run_steps(args.warmup, args.warmup + args.steps)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
-    final_loss = float(loss[0].item())
+    assert len(per_step) == args.steps
+    ev = sum(per_step)
+    if roof_mask != 0:
+        timed = per_step[::every]             # the library times every `every`-th step, starting with the first
+        ev_timed_launches, n_timed_launches = sum(timed), len(timed)
+    final_loss = float(last_loss[0][0][last_loss[0][1]].item())
     n_g, ms_g = ctx.tgnn_profile_read(STAGE_ASSEMBLE)
     n_m, ms_m = ctx.tgnn_profile_read(STAGE_KV)
     n_e, ms_e = ctx.tgnn_profile_read(STAGE_EMPTY)
@@ -260,7 +291,7 @@ def main():
         "config": {"workload": f"{name}: {d.n_nodes} nodes, {P['E']} events, d_mem {d.d_mem}, d_time {d.d_time}, "
                                f"d_edge {d.d_edge}, d_static {d.d_static}, {d.n_heads} heads, k {d.k}, "
                                f"batch {d.batch} x {nrep} replica(s), 1 negative/event, SGD lr {args.lr}",
-                   "events_per_step": ev_step, "final_loss": final_loss},
+                   "events_per_step": ev_step, "steps_per_call": per_call, "final_loss": final_loss},
         "roofline": {"bound": "mfma", "kernel": "gemm_nt_kernel: K/V projection of the {e | Phi} rows of all "
                                                 "neighbour slots (fp32 MFMA 16x16x4), the longest forward kernel",
                      "achieved": kv_tflops, "peak": PEAK_MFMA_F32_TFLOPS, "unit": "TFLOP/s",

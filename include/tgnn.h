@@ -59,6 +59,7 @@ extern "C" {
 
 #define TGNN_MAX_K 32        /* neighbours per root */
 #define TGNN_MAX_BATCHES 16  /* mini-batches (memory replicas) per tgnn_train_step call */
+#define TGNN_MAX_STEPS_PER_CALL 8 /* consecutive training steps per tgnn_train_steps call */
 #define TGNN_MAX_HEADS 8
 
 typedef struct tgnn_ctx tgnn_ctx;
@@ -205,6 +206,22 @@ int32_t tgnn_memory_writeback(tgnn_ctx* ctx, tgnn_state* st, int32_t replica, co
 int32_t tgnn_train_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, const tgnn_params* p,
                         tgnn_params* grads, const tgnn_batch* batches, int32_t n_batches, float lr,
                         float* out_loss, float* out_logits, int32_t* out_winner, void* stream);
+
+/* n_steps consecutive training steps (Sec. 3.2.1: mini-batches are trained in chronological order, each step
+ * reading the memory the step before it wrote) in one call: the same sequence of launches, with the same results
+ * (up to the order of floating-point sums), as n_steps calls of tgnn_train_step with out_logits = out_winner = NULL.
+ * For callers that have the next mini-batches at hand: when all steps have the same batch sizes and replicas, the
+ * whole sequence is one recorded HIP graph and one launch, which saves the idle time between two graph launches
+ * (about 8 us each on MI355X); otherwise (and on the NULL stream, with TGNN_FLAG_NO_GRAPH or
+ * TGNN_FLAG_SIDE_STREAM, or while stage timing is enabled) the steps are issued one by one.
+ *   batches    host array [n_steps * n_batches]: step i uses batches[i * n_batches .. (i + 1) * n_batches);
+ *   out_loss   device array [n_steps]: the loss of every step;
+ *   grads, lr  as in tgnn_train_step, per step (without TGNN_FLAG_OVERWRITE_GRADS and with lr == 0 the gradients
+ *              of all steps add up).
+ * 1 <= n_steps <= TGNN_MAX_STEPS_PER_CALL, else TGNN_E_OUT_OF_RANGE; other errors as tgnn_train_step. */
+int32_t tgnn_train_steps(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, const tgnn_params* p,
+                         tgnn_params* grads, int32_t n_steps, const tgnn_batch* batches, int32_t n_batches,
+                         float lr, float* out_loss, void* stream);
 
 /* Sets every tensor of `g` (a gradient set laid out like the parameters) to zero with one kernel. */
 int32_t tgnn_zero_params(tgnn_ctx* ctx, tgnn_params* g, void* stream);

@@ -355,6 +355,9 @@ using namespace tgnn;
 static int enqueue_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, const tgnn_params* p, tgnn_params* grads,
                         const BatchSet& bs, float lr, float* out_loss, float* out_logits, int32_t* out_winner,
                         hipStream_t s);
+static int replay_steps(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, const tgnn_params* p, tgnn_params* grads,
+                        const BatchSet* sets, int n_steps, int parity, float lr, float* out_loss, float* out_logits,
+                        int32_t* out_winner, hipStream_t s);
 
 extern "C" {
 
@@ -675,9 +678,20 @@ int32_t tgnn_memory_writeback(tgnn_ctx* ctx, tgnn_state* st, int32_t replica, co
   return TGNN_OK;
 }
 
+// loss_in_array: out_loss is an element of tgnn_train_steps' loss array (checked there; only 4-byte aligned)
+static int train_step_impl(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, const tgnn_params* p, tgnn_params* grads,
+                           const tgnn_batch* batches, int32_t n_batches, float lr, float* out_loss, float* out_logits,
+                           int32_t* out_winner, void* stream, bool loss_in_array);
+
 int32_t tgnn_train_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, const tgnn_params* p, tgnn_params* grads,
                         const tgnn_batch* batches, int32_t n_batches, float lr, float* out_loss, float* out_logits,
                         int32_t* out_winner, void* stream) {
+  return train_step_impl(ctx, g, st, p, grads, batches, n_batches, lr, out_loss, out_logits, out_winner, stream, false);
+}
+
+static int train_step_impl(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, const tgnn_params* p, tgnn_params* grads,
+                           const tgnn_batch* batches, int32_t n_batches, float lr, float* out_loss, float* out_logits,
+                           int32_t* out_winner, void* stream, bool loss_in_array) {
   if (ctx == nullptr) return set_error(TGNN_E_NULL_PTR, "ctx is NULL");
   if (int rc = check_graph(ctx, g)) return rc;
   if (int rc = check_state(ctx, st)) return rc;
@@ -687,7 +701,8 @@ int32_t tgnn_train_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
   if (int rc = make_batchset(ctx, batches, n_batches, bs)) return rc;
   for (int b = 0; b < bs.nb; ++b)
     if (bs.b[b].n > 0) REQ_PTR(bs.b[b].neg);
-  REQ_PTR(out_loss); OPT_PTR(out_logits); OPT_PTR(out_winner);
+  if (!loss_in_array) REQ_PTR(out_loss);
+  OPT_PTR(out_logits); OPT_PTR(out_winner);
   if (!(lr == lr)) return set_error(TGNN_E_INVALID_ARG, "lr is NaN");
   hipStream_t s = as_stream(stream);
   if (bs.total == 0) {
@@ -712,6 +727,64 @@ int32_t tgnn_train_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
   }
   if (!use_graph) return enqueue_step(ctx, g, st, p, grads, bs, lr, out_loss, out_logits, out_winner, s);
 
+  return replay_steps(ctx, g, st, p, grads, &bs, 1, parity, lr, out_loss, out_logits, out_winner, s);
+}
+
+int32_t tgnn_train_steps(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, const tgnn_params* p, tgnn_params* grads,
+                         int32_t n_steps, const tgnn_batch* batches, int32_t n_batches, float lr, float* out_loss,
+                         void* stream) {
+  if (ctx == nullptr) return set_error(TGNN_E_NULL_PTR, "ctx is NULL");
+  if (n_steps < 1 || n_steps > TGNN_MAX_STEPS_PER_CALL)
+    return set_error(TGNN_E_OUT_OF_RANGE, "n_steps = %d outside [1, %d]", n_steps, TGNN_MAX_STEPS_PER_CALL);
+  if (batches == nullptr) return set_error(TGNN_E_NULL_PTR, "batches is NULL");
+  REQ_PTR(out_loss);
+  // one captured graph for all the steps when they have one shape and nothing stands in the way of replaying
+  // (see tgnn_train_step); otherwise the steps are issued one by one, with the same result
+  Profiler& pr = ctx->prof;
+  bool timed = false;   // stage timing is due on one of these steps (every pr.every-th call is timed)
+  if (pr.mask != 0)
+    for (int i = 0; i < n_steps; ++i) timed = timed || (pr.calls + i) % pr.every == 0;
+  bool together = n_steps > 1 && (ctx->cfg.flags & (TGNN_FLAG_NO_GRAPH | TGNN_FLAG_SIDE_STREAM)) == 0 && !timed &&
+                  stream != nullptr;
+  BatchSet sets[TGNN_MAX_STEPS_PER_CALL];
+  if (together) {
+    if (int rc = check_graph(ctx, g)) return rc;
+    if (int rc = check_state(ctx, st)) return rc;
+    if (int rc = check_params(p, "params")) return rc;
+    if (int rc = check_params(grads, "grads")) return rc;
+    if (!(lr == lr)) return set_error(TGNN_E_INVALID_ARG, "lr is NaN");
+    for (int i = 0; i < n_steps; ++i) {
+      if (int rc = make_batchset(ctx, batches + (size_t)i * n_batches, n_batches, sets[i])) return rc;
+      for (int b = 0; b < sets[i].nb; ++b) {
+        if (sets[i].b[b].n > 0) REQ_PTR(sets[i].b[b].neg);
+        if (sets[i].b[b].n != sets[0].b[b].n || sets[i].b[b].replica != sets[0].b[b].replica) together = false;
+      }
+    }
+    if (sets[0].total == 0) together = false;
+    hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(as_stream(stream), &cs) != hipSuccess || cs != hipStreamCaptureStatusNone) together = false;
+  }
+  if (!together) {
+    for (int i = 0; i < n_steps; ++i)
+      if (int rc = train_step_impl(ctx, g, st, p, grads, batches + (size_t)i * n_batches, n_batches, lr, out_loss + i,
+                                   nullptr, nullptr, stream, true))
+        return rc;
+    return TGNN_OK;
+  }
+  ctx->last_attn_roots = -1;
+  if (pr.mask != 0) pr.calls += n_steps;
+  pr.active = 0;
+  const int parity = ctx->step_parity;
+  ctx->step_parity ^= n_steps & 1;
+  return replay_steps(ctx, g, st, p, grads, sets, n_steps, parity, lr, out_loss, nullptr, nullptr, as_stream(stream));
+}
+
+// Replays (recording it first if need be) the HIP graph of n_steps consecutive training steps of one shape; step i
+// uses row counter (parity + i) & 1 and writes its loss to out_loss[i].
+static int replay_steps(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, const tgnn_params* p, tgnn_params* grads,
+                        const BatchSet* sets, int n_steps, int parity, float lr, float* out_loss, float* out_logits,
+                        int32_t* out_winner, hipStream_t s) {
+  const BatchSet& bs = sets[0];
   // look the call signature up among the captured steps
   StepKey key;
   memset(&key, 0, sizeof(key));
@@ -725,7 +798,7 @@ int32_t tgnn_train_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
     for (int i = 0; i < 19; ++i) { key.ptr[q++] = pp[i]; key.ptr[q++] = gg[i]; }
     key.ptr[q++] = out_loss; key.ptr[q++] = out_logits; key.ptr[q++] = out_winner; key.ptr[q++] = s;
     for (int b = 0; b < bs.nb; ++b) { key.n[b] = bs.b[b].n; key.rep[b] = bs.b[b].replica; }
-    key.nb = bs.nb; key.lr = lr; key.parity = parity;
+    key.nb = bs.nb; key.lr = lr; key.parity = parity; key.n_steps = n_steps;
   }
   StepGraph* hit = nullptr;
   StepGraph* victim = &ctx->graphs[0];
@@ -741,19 +814,50 @@ int32_t tgnn_train_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
       victim->used = false;
     }
     TGNN_HIP_CHECK(hipStreamBeginCapture(s, hipStreamCaptureModeThreadLocal));
-    const int rc = enqueue_step(ctx, g, st, p, grads, bs, lr, out_loss, out_logits, out_winner, s);
+    int rc = TGNN_OK;
+    for (int i = 0; i < n_steps && rc == TGNN_OK; ++i) {
+      ctx->w.ucount = ctx->w.ucount_pair + ((parity + i) & 1);
+      rc = enqueue_step(ctx, g, st, p, grads, sets[i], lr, out_loss + i, out_logits, out_winner, s);
+    }
     hipGraph_t graph = nullptr;
     const hipError_t ce = hipStreamEndCapture(s, &graph);
     if (rc != TGNN_OK) { if (graph) (void)hipGraphDestroy(graph); return rc; }
     if (ce != hipSuccess) return set_error(TGNN_E_HIP, "hipStreamEndCapture failed: %s", hipGetErrorString(ce));
-    hipGraphNode_t roots[4];
-    size_t n_roots = 4;
-    hipError_t e = hipGraphGetRootNodes(graph, roots, &n_roots);
-    hipGraphNodeType ty = hipGraphNodeTypeEmpty;
-    if (e == hipSuccess && n_roots == 1) e = hipGraphNodeGetType(roots[0], &ty);
-    if (e != hipSuccess || n_roots != 1 || ty != hipGraphNodeTypeKernel) {
+    // the recorded launches form a chain; the first launch of every step is found by its kernel
+    hipGraphNode_t node = nullptr, heads[TGNN_MAX_STEPS_PER_CALL];
+    int n_heads = 0;
+    size_t n_next = 1;
+    hipError_t e = hipGraphGetRootNodes(graph, &node, &n_next);
+    bool chain = e == hipSuccess && n_next == 1;
+    if (chain && n_steps == 1) {   // (with the side stream the graph forks further on: only its root is looked at)
+      hipGraphNodeType ty = hipGraphNodeTypeEmpty;
+      chain = hipGraphNodeGetType(node, &ty) == hipSuccess && ty == hipGraphNodeTypeKernel;
+      heads[n_heads++] = node;
+    }
+    for (int guard = 0; n_steps > 1 && chain && node != nullptr && guard < 4096; ++guard) {
+      hipGraphNodeType ty = hipGraphNodeTypeEmpty;
+      if (hipGraphNodeGetType(node, &ty) != hipSuccess) { chain = false; break; }
+      if (ty == hipGraphNodeTypeKernel) {
+        hipKernelNodeParams kp;
+        memset(&kp, 0, sizeof(kp));
+        if (hipGraphKernelNodeGetParams(node, &kp) != hipSuccess) { chain = false; break; }
+        if (kp.func == head_func()) {
+          if (n_heads == TGNN_MAX_STEPS_PER_CALL) { chain = false; break; }
+          heads[n_heads++] = node;
+        }
+      }
+      size_t n_dep = 0;
+      if (hipGraphNodeGetDependentNodes(node, nullptr, &n_dep) != hipSuccess || n_dep > 1) { chain = false; break; }
+      if (n_dep == 0) break;
+      hipGraphNode_t next = nullptr;
+      n_dep = 1;
+      if (hipGraphNodeGetDependentNodes(node, &next, &n_dep) != hipSuccess) { chain = false; break; }
+      node = next;
+    }
+    if (!chain || n_heads != n_steps || heads[0] == nullptr) {
       (void)hipGraphDestroy(graph);
-      return set_error(TGNN_E_HIP, "captured step has an unexpected shape (%zu root nodes)", n_roots);
+      return set_error(TGNN_E_HIP, "captured steps have an unexpected shape (%d first launches for %d steps)", n_heads,
+                       n_steps);
     }
     hipGraphExec_t exec = nullptr;
     e = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
@@ -761,24 +865,29 @@ int32_t tgnn_train_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
       (void)hipGraphDestroy(graph);
       return set_error(TGNN_E_HIP, "hipGraphInstantiate failed: %s", hipGetErrorString(e));
     }
-    victim->used = true; victim->key = key; victim->graph = graph; victim->exec = exec; victim->prologue_node = roots[0];
+    victim->used = true; victim->key = key; victim->graph = graph; victim->exec = exec;
+    for (int i = 0; i < n_steps; ++i) victim->head_node[i] = heads[i];
     hit = victim;
   } else {
-    // same launches as the recorded step; only the first launch's argument block (batch descriptors) is new
+    // same launches as the recorded steps; only the first launch's argument block (batch descriptors) of each is new
     SgdSet sgd_set, zero_set_;
     fill_param_set(d, p, grads, 2, sgd_set);
     fill_param_set(d, grads, nullptr, 0, zero_set_);
     const bool overwrite = (ctx->cfg.flags & TGNN_FLAG_OVERWRITE_GRADS) != 0;
-    HeadArgs h;
-    head_fill(ctx, g, 3 * bs.total, p, &bs, lr != 0.0f ? &sgd_set : nullptr, overwrite ? &zero_set_ : nullptr, out_loss, h);
-    void* kargs[1] = {&h};
-    hipKernelNodeParams np;
-    memset(&np, 0, sizeof(np));
-    np.func = head_func();
-    np.gridDim = head_grid(h);
-    np.blockDim = dim3(64 * SAMPLE_WAVES);
-    np.kernelParams = kargs;
-    TGNN_HIP_CHECK(hipGraphExecKernelNodeSetParams(hit->exec, hit->prologue_node, &np));
+    for (int i = 0; i < n_steps; ++i) {
+      ctx->w.ucount = ctx->w.ucount_pair + ((parity + i) & 1);
+      HeadArgs h;
+      head_fill(ctx, g, 3 * sets[i].total, p, &sets[i], lr != 0.0f ? &sgd_set : nullptr, overwrite ? &zero_set_ : nullptr,
+                out_loss + i, h);
+      void* kargs[1] = {&h};
+      hipKernelNodeParams np;
+      memset(&np, 0, sizeof(np));
+      np.func = head_func();
+      np.gridDim = head_grid(h);
+      np.blockDim = dim3(64 * SAMPLE_WAVES);
+      np.kernelParams = kargs;
+      TGNN_HIP_CHECK(hipGraphExecKernelNodeSetParams(hit->exec, hit->head_node[i], &np));
+    }
   }
   hit->last_use = ++ctx->graph_clock;
   TGNN_HIP_CHECK(hipGraphLaunch(hit->exec, s));

@@ -108,10 +108,11 @@ namespace tgnn {
 // A captured tgnn_train_step: every launch of the step recorded once into a HIP graph and replayed with one
 // call; only the prologue node's arguments (the batch descriptors) change between replays.
 constexpr int MAX_STEP_GRAPHS = 8;
+// (tgnn_train_steps records several consecutive steps of the same shape into one graph: one first-launch node each)
 struct StepKey {
   const void* ptr[64];
   int32_t n[TGNN_MAX_BATCHES], rep[TGNN_MAX_BATCHES];
-  int32_t nb, parity;
+  int32_t nb, parity, n_steps;
   float lr;
 };
 struct StepGraph {
@@ -119,7 +120,7 @@ struct StepGraph {
   StepKey key;
   hipGraph_t graph = nullptr;
   hipGraphExec_t exec = nullptr;
-  hipGraphNode_t prologue_node = nullptr;
+  hipGraphNode_t head_node[TGNN_MAX_STEPS_PER_CALL] = {};   // the first launch of every recorded step
   unsigned long long last_use = 0;
 };
 }  // namespace tgnn

@@ -20,6 +20,7 @@ _lib = C.CDLL(_LIB_PATH)
 PARAM_NAMES = ["time_w", "time_b", "gru_wih", "gru_whh", "gru_bih", "gru_bhh", "wq", "bq", "wk", "bk",
                "wv", "bv", "wo", "bo", "dec_ws", "dec_wd", "dec_b1", "dec_w2", "dec_b2"]
 MAX_BATCHES = 16
+MAX_STEPS_PER_CALL = 8
 FLAG_OVERWRITE_GRADS = 1
 FLAG_SIDE_STREAM = 2
 FLAG_NO_GRAPH = 4
@@ -66,6 +67,8 @@ _SIGS = {
     "tgnn_memory_writeback": (_I, [_P, C.POINTER(tgnn_state), _I, _P, _P, _P, _P, _I, _P, _P, _P, _P, _P, _P]),
     "tgnn_train_step": (_I, [_P, C.POINTER(tgnn_graph), C.POINTER(tgnn_state), C.POINTER(tgnn_params),
                              C.POINTER(tgnn_params), C.POINTER(tgnn_batch), _I, C.c_float, _P, _P, _P, _P]),
+    "tgnn_train_steps": (_I, [_P, C.POINTER(tgnn_graph), C.POINTER(tgnn_state), C.POINTER(tgnn_params),
+                              C.POINTER(tgnn_params), _I, C.POINTER(tgnn_batch), _I, C.c_float, _P, _P]),
     "tgnn_debug_read": (_I, [_P, _I, _P, C.c_int64, _P]),
     "tgnn_debug_copy": (_I, [_P, _P, C.c_int64, _P]),
     "tgnn_zero_params": (_I, [_P, C.POINTER(tgnn_params), _P]),
@@ -275,6 +278,14 @@ class Context:
         arr = (tgnn_batch * len(batches))(*[b.c for b in batches])
         _check(_lib.tgnn_train_step(self.h, C.byref(g.c), C.byref(st.c), C.byref(p.c), C.byref(grads.c), arr,
                                     len(batches), lr, _ptr(out_loss), _ptr(out_logits), _ptr(out_winner), _stream()))
+
+    def tgnn_train_steps(self, g: Graph, st: State, p: Params, grads: Params, steps, lr=0.0, out_loss=None):
+        """steps: a list of steps, each a list of Batch (the same number per step); out_loss: device array [len(steps)]."""
+        nb = len(steps[0])
+        flat = [b.c for step in steps for b in step]
+        arr = (tgnn_batch * len(flat))(*flat)
+        _check(_lib.tgnn_train_steps(self.h, C.byref(g.c), C.byref(st.c), C.byref(p.c), C.byref(grads.c), len(steps), arr,
+                                     nb, lr, _ptr(out_loss), _stream()))
 
     def tgnn_zero_params(self, grads: Params):
         _check(_lib.tgnn_zero_params(self.h, C.byref(grads.c), _stream()))

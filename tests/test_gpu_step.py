@@ -106,3 +106,42 @@ def test_sampled_stage_timing_and_row_count():
     G.ctx.tgnn_profile_enable(0)
     G.ctx.tgnn_profile_every(1)
     compare_state(G.state_np(), Or.states[0], label="state")
+
+
+@pytest.mark.parametrize("per_call,flags", [(4, 0), (3, 0), (8, 0), (4, 4)])
+def test_several_steps_per_call_agree_with_the_oracle(per_call, flags):
+    """tgnn_train_steps: groups of consecutive steps in one call (one recorded graph per group shape; flags = 4:
+    no graph, the steps are issued one by one inside the call), with SGD, against the oracle stepping one batch at a
+    time: the loss of every step, the memory, mails and parameters at the end.  24 batches of C0 end with a ragged
+    group when per_call does not divide them (3 -> whole groups, 8 -> whole groups, 4 -> whole groups; the last batch
+    of the sequence is shorter, so its group falls back to single steps)."""
+    import torch
+    from paper_2307_07649_amd import tgnn
+    from gpu_common import rel_err
+    P = make_problem("C0", random_phase=True)
+    d = P["d"]
+    n_total = 24
+    first = P["E"] // d.batch - n_total + 1          # the sequence ends with the ragged last batch of the graph
+    G = GpuSide(P, flags=flags | tgnn.FLAG_OVERWRITE_GRADS); Or = OracleSide(P)
+    spans = [((first + s) * d.batch, min((first + s + 1) * d.batch, P["E"])) for s in range(n_total)]
+    assert spans[-1][1] - spans[-1][0] < d.batch
+    o_loss = []
+    g_loss = []
+    losses = torch.zeros(per_call, device="cuda")
+    with torch.cuda.stream(G.stream):
+        for s0 in range(0, n_total, per_call):
+            grp = spans[s0:s0 + per_call]
+            steps = []
+            for lo, hi in grp:
+                b = batch_np(P, lo, hi)
+                steps.append([tgnn.Batch(b["src"], b["dst"], b["neg"], b["eid"], b["t"])])
+                o_loss.append(Or.step([b], lr=0.05)["loss"])
+            G.ctx.tgnn_train_steps(G.graph, G.state, G.params, G.grads, steps, lr=0.05, out_loss=losses)
+            torch.cuda.synchronize()
+            g_loss += [float(x) for x in losses[:len(grp)].cpu().numpy()]
+    assert len(g_loss) == n_total
+    for s, (a, b) in enumerate(zip(g_loss, o_loss)):
+        assert abs(a - b) <= 1e-4 * max(abs(b), 1e-30), (s, a, b)
+    compare_state(G.state_np(), Or.states[0], label="state")
+    for n, v in G.params.numpy().items():
+        assert rel_err(v, Or.p[n]) <= 1e-4, n
