@@ -210,10 +210,10 @@ int32_t tgnn_train_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
 /* n_steps consecutive training steps (Sec. 3.2.1: mini-batches are trained in chronological order, each step
  * reading the memory the step before it wrote) in one call: the same sequence of launches, with the same results
  * (up to the order of floating-point sums), as n_steps calls of tgnn_train_step with out_logits = out_winner = NULL.
- * For callers that have the next mini-batches at hand: when all steps have the same batch sizes and replicas, the
- * whole sequence is one recorded HIP graph and one launch, which saves the idle time between two graph launches
- * (about 8 us each on MI355X); otherwise (and on the NULL stream, with TGNN_FLAG_NO_GRAPH or
- * TGNN_FLAG_SIDE_STREAM, or while stage timing is enabled) the steps are issued one by one.
+ * For callers that have the next mini-batches at hand: every run of consecutive steps with the same batch sizes
+ * and replicas is one recorded HIP graph and one launch, which saves the idle time between two graph launches
+ * (about 8 us each on MI355X).  Steps on which stage timing is due, and all steps on the NULL stream or with
+ * TGNN_FLAG_NO_GRAPH or TGNN_FLAG_SIDE_STREAM, are issued one by one.
  *   batches    host array [n_steps * n_batches]: step i uses batches[i * n_batches .. (i + 1) * n_batches);
  *   out_loss   device array [n_steps]: the loss of every step;
  *   grads, lr  as in tgnn_train_step, per step (without TGNN_FLAG_OVERWRITE_GRADS and with lr == 0 the gradients

@@ -738,16 +738,16 @@ int32_t tgnn_train_steps(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, con
     return set_error(TGNN_E_OUT_OF_RANGE, "n_steps = %d outside [1, %d]", n_steps, TGNN_MAX_STEPS_PER_CALL);
   if (batches == nullptr) return set_error(TGNN_E_NULL_PTR, "batches is NULL");
   REQ_PTR(out_loss);
-  // one captured graph for all the steps when they have one shape and nothing stands in the way of replaying
-  // (see tgnn_train_step); otherwise the steps are issued one by one, with the same result
-  Profiler& pr = ctx->prof;
-  bool timed = false;   // stage timing is due on one of these steps (every pr.every-th call is timed)
-  if (pr.mask != 0)
-    for (int i = 0; i < n_steps; ++i) timed = timed || (pr.calls + i) % pr.every == 0;
-  bool together = n_steps > 1 && (ctx->cfg.flags & (TGNN_FLAG_NO_GRAPH | TGNN_FLAG_SIDE_STREAM)) == 0 && !timed &&
-                  stream != nullptr;
+  // Runs of consecutive steps of one shape on which no stage timing is due are replayed as one recorded graph each
+  // when nothing stands in the way of replaying (see tgnn_train_step); the other steps are issued one by one, with
+  // the same result.
+  bool can_replay = n_steps > 1 && (ctx->cfg.flags & (TGNN_FLAG_NO_GRAPH | TGNN_FLAG_SIDE_STREAM)) == 0 && stream != nullptr;
+  if (can_replay) {
+    hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(as_stream(stream), &cs) != hipSuccess || cs != hipStreamCaptureStatusNone) can_replay = false;
+  }
   BatchSet sets[TGNN_MAX_STEPS_PER_CALL];
-  if (together) {
+  if (can_replay) {
     if (int rc = check_graph(ctx, g)) return rc;
     if (int rc = check_state(ctx, st)) return rc;
     if (int rc = check_params(p, "params")) return rc;
@@ -755,28 +755,38 @@ int32_t tgnn_train_steps(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, con
     if (!(lr == lr)) return set_error(TGNN_E_INVALID_ARG, "lr is NaN");
     for (int i = 0; i < n_steps; ++i) {
       if (int rc = make_batchset(ctx, batches + (size_t)i * n_batches, n_batches, sets[i])) return rc;
-      for (int b = 0; b < sets[i].nb; ++b) {
+      for (int b = 0; b < sets[i].nb; ++b)
         if (sets[i].b[b].n > 0) REQ_PTR(sets[i].b[b].neg);
-        if (sets[i].b[b].n != sets[0].b[b].n || sets[i].b[b].replica != sets[0].b[b].replica) together = false;
-      }
     }
-    if (sets[0].total == 0) together = false;
-    hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
-    if (hipStreamIsCapturing(as_stream(stream), &cs) != hipSuccess || cs != hipStreamCaptureStatusNone) together = false;
   }
-  if (!together) {
-    for (int i = 0; i < n_steps; ++i)
+  Profiler& pr = ctx->prof;
+  auto same_shape = [&](int i, int j) {
+    for (int b = 0; b < sets[i].nb; ++b)
+      if (sets[i].b[b].n != sets[j].b[b].n || sets[i].b[b].replica != sets[j].b[b].replica) return false;
+    return true;
+  };
+  for (int i = 0; i < n_steps;) {
+    int run = 0;   // steps from i on that can share a graph: one shape, not empty, no stage timing due
+    if (can_replay && sets[i].total > 0)
+      while (i + run < n_steps && same_shape(i, i + run) && !(pr.mask != 0 && (pr.calls + run) % pr.every == 0)) ++run;
+    if (run >= 2) {
+      ctx->last_attn_roots = -1;
+      if (pr.mask != 0) pr.calls += run;
+      pr.active = 0;
+      const int parity = ctx->step_parity;
+      ctx->step_parity ^= run & 1;
+      if (int rc = replay_steps(ctx, g, st, p, grads, sets + i, run, parity, lr, out_loss + i, nullptr, nullptr,
+                                as_stream(stream)))
+        return rc;
+      i += run;
+    } else {
       if (int rc = train_step_impl(ctx, g, st, p, grads, batches + (size_t)i * n_batches, n_batches, lr, out_loss + i,
                                    nullptr, nullptr, stream, true))
         return rc;
-    return TGNN_OK;
+      i += 1;
+    }
   }
-  ctx->last_attn_roots = -1;
-  if (pr.mask != 0) pr.calls += n_steps;
-  pr.active = 0;
-  const int parity = ctx->step_parity;
-  ctx->step_parity ^= n_steps & 1;
-  return replay_steps(ctx, g, st, p, grads, sets, n_steps, parity, lr, out_loss, nullptr, nullptr, as_stream(stream));
+  return TGNN_OK;
 }
 
 // Replays (recording it first if need be) the HIP graph of n_steps consecutive training steps of one shape; step i
