@@ -105,3 +105,35 @@ def test_c4_full_graph_sampler():
     o = O.sample_recent(adj, qn, qt, 10)
     assert np.array_equal(cnt.cpu().numpy(), o[3]) and np.array_equal(eid.cpu().numpy(), o[1])
     assert np.array_equal(nbr.cpu().numpy(), o[0]) and np.array_equal(ts.cpu().numpy(), o[2])
+
+
+def test_c1_and_c3_four_steps_per_call():
+    """tgnn_train_steps at the benchmark's sizes, in the launch configuration bench.py times (groups of four steps,
+    SGD, gradients cleared inside the step): C1 for 12 batches and C3's eight replicas for 4 steps, against the
+    oracle stepping one step at a time: every step's loss, the final memory and mails, the final parameters."""
+    import torch
+    from paper_2307_07649_amd import tgnn
+    for name, n_ev, nrep, n_steps in (("C1", None, 1, 12), ("C3", 48_000, 8, 4)):
+        P = make_problem(name, n_events=n_ev)
+        d = P["d"]
+        G = GpuSide(P, n_replicas=nrep, flags=tgnn.FLAG_OVERWRITE_GRADS); Or = OracleSide(P, n_replicas=nrep)
+        spans = synth.batches_of(P["E"], d.batch)
+        M = len(spans); shift = -(-M // nrep)
+        losses = torch.zeros(4, device="cuda")
+        g_loss, o_loss = [], []
+        with torch.cuda.stream(G.stream):
+            for s0 in range(0, n_steps, 4):
+                steps = []
+                for s in range(s0, s0 + 4):
+                    bl = [batch_np(P, *spans[(s + r * shift) % M]) for r in range(nrep)]
+                    steps.append([tgnn.Batch(b["src"], b["dst"], b["neg"], b["eid"], b["t"], replica=r) for r, b in enumerate(bl)])
+                    o_loss.append(Or.step(bl, lr=1e-3)["loss"])
+                G.ctx.tgnn_train_steps(G.graph, G.state, G.params, G.grads, steps, lr=1e-3, out_loss=losses)
+                torch.cuda.synchronize()
+                g_loss += [float(x) for x in losses.cpu().numpy()]
+        for s, (a, b) in enumerate(zip(g_loss, o_loss)):
+            assert abs(a - b) <= 1e-4 * abs(b), (name, s, a, b)
+        for r in range(nrep):
+            compare_state(G.state_np(r), Or.states[r], label=f"{name} replica {r}")
+        for n, v in G.params.numpy().items():
+            assert rel_err(v, Or.p[n]) <= 1e-4, (name, n)
