@@ -4,13 +4,17 @@
 A step = one pass of the whole hot path over one mini-batch: sample -> gather -> time-encode -> GRU ->
 attention -> decoder/BCE forward and backward -> SGD -> last-event-wins write-back.  Inputs (graph, edge
 features, node state, weights, every mini-batch of the epoch) are resident in HBM before the clock starts.
-Prints one JSON line; see the design doc for the roofline and cpu_baseline fields.
+
+The headline (`value`) is the largest single-GPU configuration, C4: 16,682 nodes, the full 20,000,000-event list,
+14.9 GB of edge features, mini-batches of 4,000 events.  The same run measures the other four configurations
+(`configs`), and times the CPU oracle on the host cores (`cpu_baseline`).  Prints one JSON line.
 """
 from __future__ import annotations
 
 import argparse
 import json
 import os
+import re
 import sys
 import time
 
@@ -22,66 +26,77 @@ sys.path.insert(0, ROOT)
 PEAK_HBM_GBS = 8000.0
 PEAK_MFMA_F32_TFLOPS = 157.3
 
-# HBM bytes per launch (read + written) from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised in
-# profiles/train_step_C1_hbm_traffic.md (counter units scaled by the copy-kernel calibration described there).
-# Counters cannot be read from inside this script, so the figures are the recorded ones, for C1 only.
-MEASURED_TRAFFIC_BYTES = {"C1": {"kv_projection": 41.0e6, "assemble_ce": 33.8e6}}
-
-STAGE_NAMES = ["(unused)", "(unused)", "roots + sample + distinct-node rows + prologue (pack weights, clear), one launch",
-               "gather + time-encode (GRU input) + slot-to-row map", "GRU input + hidden projections (MFMA, one launch)", "(unused)",
-               "(unused)", "GRU gates + slot-sort scan + per-slot attention input {e | Phi} (gather), one launch", "K/V projection of the slots (MFMA)",
-               "per-node projections K, V, q, merge (MFMA)", "softmax attention + slot-sort fill", "merge layer (MFMA; only when the root chain does not fit)",
-               "root chain: merge layer, decoder + loss, their backward down to the attention output (MFMA, one launch)",
-               "decoder backward (only when the root chain does not fit)", "attention backward (softmax)",
-               "per-node gradient sums; node projections + GRU gates backward with the keys' time-encoding gradients (one launch)",
-               "all weight gradients (grouped MFMA GEMM)", "time-encoding gradients of the mails (MFMA) + write-back scatter + SGD (one launch)",
-               "empty event bracket", "(unused)"]
-STAGE_ASSEMBLE, STAGE_KV, STAGE_WGRAD, STAGE_EMPTY = 7, 8, 16, 18
-
-
-def flops_wgrad(d, n_roots, n_rows):
-    """Useful flops of the grouped weight-gradient launch, G += D^T A per problem (2 M N K each; bias gradients
-    are one more column): decoder hidden layer and merge layer over the roots, the {e | Phi} columns of W_k / W_v as
-    two products over the roots (a column of q / dO meets the d_e + d_t columns of its own head's block of the
-    per-root sums; the launch also runs the blocks of tiles that straddle a head boundary, which are not counted),
-    the node columns of W_k, W_v, W_q, W_o and the two GRU matrices over the distinct node rows."""
-    R, U, dO = n_roots, n_rows, d.d_out
-    macs = (R * 2 * dO * (dO + 1) + R * dO * dO + 2 * R * dO * (d.d_edge + d.d_time)
-            + 2 * U * 2 * dO * (d.d_x + 1) + U * 3 * d.d_mem * (d.d_in + 1) + U * 3 * d.d_mem * (d.d_mem + 1))
-    return 2.0 * macs
+STAGE_NAMES = {2: "roots + sample + distinct-node rows + prologue (pack weights, clear), one launch",
+               3: "state gather + time-encode (GRU input) + slot-to-row map",
+               4: "GRU input + hidden projections (MFMA, one launch)",
+               7: "GRU gates + slot-sort scan + per-slot attention input {e | Phi} (edge-feature gather), one launch",
+               8: "K/V projection of the slots (MFMA)",
+               9: "per-node projections K, V, q, merge (MFMA)",
+               10: "softmax attention + slot-sort fill",
+               11: "merge layer (MFMA; only when the root chain does not fit)",
+               12: "root chain: merge layer, decoder + loss, their backward down to the attention output (MFMA, one launch)",
+               13: "decoder backward (only when the root chain does not fit)",
+               14: "attention backward (softmax)",
+               15: "per-node gradient sums; node projections + GRU gates backward with the keys' time-encoding gradients",
+               16: "all weight gradients (grouped MFMA GEMM)",
+               17: "time-encoding gradients of the mails (MFMA) + write-back scatter + SGD (one launch)",
+               18: "empty event bracket"}
+STAGE_GATHER, STAGE_ASSEMBLE, STAGE_KV, STAGE_WGRAD, STAGE_EMPTY = 3, 7, 8, 16, 18
+N_STAGES = 20
 
 
-def flops_kv(d, n_roots):
-    """Executed flops of the per-slot K/V projection: [R k, d_e + d_t] x [d_e + d_t, 2 d_o].  (The node part of
-    the projection, d_x columns, is taken once per distinct node by another, much smaller GEMM.)"""
-    return 2.0 * n_roots * d.k * (d.d_edge + d.d_time) * 2 * d.d_out
-
-
-def assemble_bytes(d, n_roots):
-    """Per-slot attention input: per neighbour slot read the edge-feature row, its index and the neighbour's
-    update time, and write the {e | Phi} row and the time difference."""
-    per_nbr = 4 * d.d_edge + 4 * (d.d_edge + d.d_time) + 4 + 8 + 8
-    return n_roots * d.k * per_nbr
-
-
-def gates_bytes(d, n_rows):
-    """GRU gates, passenger of the same launch: per distinct node row read the two projections (6 d_m floats) and
-    the stored memory, write the four gate values, the node row {s' | static} and clear the row's gradient
-    accumulator (pitch 2 * pad32(2 d_o) floats)."""
-    pad32 = lambda x: (x + 31) // 32 * 32
-    return n_rows * 4 * (12 * d.d_mem + 2 * d.d_static + 2 * pad32(2 * d.d_out))
-
-
-def step_flops(d, B):
+# ---------------------------------------------------------------------------------------------------------
+# work models (documented in the design doc): what the method asks for per slot, and what the library executes
+# ---------------------------------------------------------------------------------------------------------
+def flops_per_slot_model(d, B):
+    """The method as stated: UPDT for every one of the 3B(1+k) slots, unsplit projections; fwd + bwd ~ 3x fwd."""
     R = 3 * B; RK = R * d.k; S = R + RK
     gru = S * 2 * (d.d_in + d.d_mem) * 3 * d.d_mem
     attn = R * 2 * d.d_q * d.d_out + RK * 2 * 2 * d.d_kv * d.d_out + RK * 4 * d.d_out
     merge = R * 2 * (d.d_out + d.d_x) * d.d_out
     dec = 2 * B * (4 * d.d_out ** 2 + 2 * d.d_out)
-    return 3.0 * (gru + attn + merge + dec)     # forward + backward ~ 3x forward
+    return 3.0 * (gru + attn + merge + dec)
 
 
-def step_bytes(d, B):
+def flops_wgrad(d, R, U):
+    """Useful flops of the grouped weight-gradient launch, G += D^T A per problem (2 M N K each; a bias gradient is
+    one more column): decoder hidden layer and merge layer over the roots, the {e | Phi} columns of W_k / W_v as two
+    products over the roots (per-root sums against the query / output gradient of the same head), the node columns
+    of W_k, W_v, W_q, W_o and the two GRU matrices over the distinct node rows."""
+    dO = d.d_out
+    macs = (R * 2 * dO * (dO + 1) + R * dO * dO + 2 * R * dO * (d.d_edge + d.d_time)
+            + 2 * U * 2 * dO * (d.d_x + 1) + U * 3 * d.d_mem * (d.d_in + 1) + U * 3 * d.d_mem * (d.d_mem + 1))
+    return 2.0 * macs
+
+
+def flops_kv(d, R):
+    """Executed flops of the per-slot K/V projection: [R k, d_e + d_t] x [d_e + d_t, 2 d_o]."""
+    return 2.0 * R * d.k * (d.d_edge + d.d_time) * 2 * d.d_out
+
+
+def flops_executed_model(d, B, U):
+    """What the library's kernels execute for a step with U distinct (replica, node) rows among its slots: UPDT and
+    the node part of every projection once per distinct row, the {e | Phi} part per neighbour slot, everything else
+    per root.  Forward and backward listed separately (no 3x rule)."""
+    R = 3 * B; RK = R * d.k; dO = d.d_out; dc = d.d_edge + d.d_time
+    fwd = (U * 2 * (d.d_in + d.d_mem) * 3 * d.d_mem          # GRU projections
+           + U * 2 * d.d_x * 4 * dO                          # node part of K, V, q, merge
+           + flops_kv(d, R)                                  # per-slot K/V
+           + RK * 4 * dO                                     # scores + weighted sum
+           + R * 2 * dO * dO + R * 2 * dO * 2 * dO           # merge (attention-output columns), decoder hidden layer
+           + 2 * B * 2 * dO)                                 # logits
+    bwd_data = (R * 2 * 2 * dO * dO + R * 2 * dO * dO        # dz, d(attention output)
+                + RK * 8 * dO                                # softmax backward: dP, dV, dq, dK
+                + 2 * RK * 2 * dc * d.n_heads                # per-root sums of {e | Phi} rows (two weightings per head)
+                + RK * 2 * 2 * dO * d.d_time                 # dKV onto the keys' time encoding
+                + U * 2 * 4 * dO * d.d_mem                   # node projections backward
+                + U * 2 * 3 * d.d_mem * d.d_time)            # GRU input gradient onto the mails' time encoding
+    return float(fwd + bwd_data + flops_wgrad(d, R, U))
+
+
+def bytes_per_slot_model(d, B):
+    """Algorithmic bytes of a step with nothing deduplicated: state + mail + edge-feature rows for every slot, edge
+    features of the neighbour slots, sampler lists, write-back rows."""
     R = 3 * B; RK = R * d.k; S = R + RK
     gather = S * (4 * d.d_mem + 8 * d.d_mem + 4 * d.d_edge + 4 * d.d_static + 20) + RK * 4 * d.d_edge
     sampler = R * (2 * d.k * 16 + 8 * 16)
@@ -89,78 +104,102 @@ def step_bytes(d, B):
     return float(gather + sampler + wb)
 
 
-def cpu_baseline(P, budget_s=15.0):
-    """The oracle as it stands, timed on the host cores on the first mini-batches of the same workload."""
+def assemble_bytes(d, R):
+    """Per-slot attention input launch: per neighbour slot read the edge-feature row, its index and the
+    neighbour's update time, and write the {e | Phi} row and the time difference."""
+    return R * d.k * (4 * d.d_edge + 4 * (d.d_edge + d.d_time) + 4 + 8 + 8)
+
+
+def gates_bytes(d, U):
+    """GRU gates, passenger of the same launch: per distinct node row read the two projections (6 d_m floats) and
+    the stored memory, write the four gate values, the node row {s' | static} and clear the row's gradient
+    accumulator (pitch 2 * pad32(2 d_o) floats)."""
+    pad32 = lambda x: (x + 31) // 32 * 32
+    return U * 4 * (12 * d.d_mem + 2 * d.d_static + 2 * pad32(2 * d.d_out))
+
+
+def state_gather_bytes(d, U):
+    """State gather launch (memory, mail, the mail's edge-feature row -> GRU input and hidden rows): per distinct node
+    row read 4 d_m + 8 d_m + 4 d_e + 20 bytes of state and write the same rows plus the time encoding."""
+    return U * (2 * (12 * d.d_mem + 4 * d.d_edge) + 4 * d.d_time + 28)
+
+
+def writeback_bytes(d, n_written):
+    """Write-back scatter: per written node read s'_self, s'_other and write mem (4 d_m), mail (8 d_m), two times and
+    the event id."""
+    return n_written * (8 * d.d_mem + 12 * d.d_mem + 20)
+
+
+def recorded_traffic(name, kernel):
+    """HBM bytes per launch from the committed rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE summary of this workload
+    (profiles/train_step_<name>_hbm_traffic.md, a line `traffic <kernel> <bytes>`); None when there is none.
+    Counters cannot be read from inside this script."""
+    path = os.path.join(ROOT, "profiles", f"train_step_{name}_hbm_traffic.md")
+    try:
+        for line in open(path):
+            m = re.match(r"\s*traffic\s+(\S+)\s+([0-9.eE+]+)", line)
+            if m and m.group(1) == kernel:
+                return float(m.group(2))
+    except OSError:
+        pass
+    return None
+
+
+# ---------------------------------------------------------------------------------------------------------
+# the oracle on the host cores
+# ---------------------------------------------------------------------------------------------------------
+def cpu_baseline(P, budget_s, threads):
+    """The oracle as it stands, on the first mini-batches of the workload from zero state.  Its event list is cut
+    after the last timed mini-batch: later events cannot precede any query of these batches, and the oracle's
+    sampler scans the list it is given once per root.  threads: BLAS threads (None = all)."""
     from oracle import tgnn_oracle as O
+    import threadpoolctl
     d = P["d"]
-    adj = O.build_adjacency(P["src"], P["dst"], P["ts"], d.n_nodes)
+    n_max = min(P["E"] // d.batch, 6)
+    cut = n_max * d.batch
+    graph = O.event_list(P["src"][:cut], P["dst"][:cut], P["ts"][:cut])
+    efeat = P["efeat_host"][np.arange(cut)] if "efeat_host" in P else P["efeat"][:cut]
     st = O.new_state(d.n_nodes, d.d_mem)
     p = O.to_f64(P["params"])
     ev = 0; steps = 0
-    t0 = time.perf_counter()
-    while time.perf_counter() - t0 < budget_s and (steps + 1) * d.batch <= P["E"]:
-        lo = steps * d.batch; hi = lo + d.batch
-        b = dict(src=P["src"][lo:hi], dst=P["dst"][lo:hi], neg=P["neg"][lo:hi], eid=np.arange(lo, hi), t=P["ts"][lo:hi])
-        O.train_step([st], adj, P["efeat"], P["static"], p, [b], d.k, d.n_heads, lr=1e-4)
-        ev += hi - lo; steps += 1
-    dt = time.perf_counter() - t0
-    try:
-        import threadpoolctl
-        cores = max([i.get("num_threads", 1) for i in threadpoolctl.threadpool_info()] + [1])
-    except Exception:
-        cores = os.cpu_count()
-    return dict(value=ev / dt, unit="events/s", cores=int(cores), kind="oracle",
-                sample=f"first {steps} mini-batches of {d.batch} events of {P['name']} from zero state "
-                       f"(fp64 numpy, {dt:.1f} s)")
+    with threadpoolctl.threadpool_limits(limits=threads):
+        used = max([i.get("num_threads", 1) for i in threadpoolctl.threadpool_info()] + [1])
+        t0 = time.perf_counter()
+        while steps < n_max and (steps == 0 or time.perf_counter() - t0 < budget_s):
+            lo = steps * d.batch; hi = lo + d.batch
+            b = dict(src=P["src"][lo:hi], dst=P["dst"][lo:hi], neg=P["neg"][lo:hi], eid=np.arange(lo, hi), t=P["ts"][lo:hi])
+            O.train_step([st], graph, efeat, P["static"], p, [b], d.k, d.n_heads, lr=1e-4)
+            ev += hi - lo; steps += 1
+        dt = time.perf_counter() - t0
+    return dict(value=ev / dt, unit="events/s", cores=int(used), kind="oracle",
+                sample=f"first {steps} mini-batch(es) of {d.batch} events of {P['name']} from zero state "
+                       f"(fp64 numpy, {dt:.1f} s, {used} BLAS thread(s))")
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=263)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--config", default="C1", choices=["C0", "C1", "C2", "C3", "C4"])
-    ap.add_argument("--events", type=int, default=None, help="shorten the event list (C4: default 2,000,000)")
-    ap.add_argument("--lr", type=float, default=1e-4)
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--side-stream", action="store_true", help="let the library fork independent work of a step onto its second stream")
-    ap.add_argument("--no-stage-events", action="store_true", help="do not time the two roofline kernels inside the timed region (every step then replays a captured HIP graph)")
-    ap.add_argument("--steps-per-call", type=int, default=4,
-                    help="consecutive training steps handed to the library per call (tgnn_train_steps; 1 = tgnn_train_step)")
-    ap.add_argument("--event-every", type=int, default=16,
-                    help="inside the timed region, every N-th step is launched kernel by kernel with HIP events around "
-                         "the two roofline kernels; the other steps replay the captured HIP graph (1: every step)")
-    ap.add_argument("--calibrate-copy", action="store_true",
-                    help="first run the library's plain copy kernel on 256 MiB three times (reference for rocprofv3 --pmc "
-                         "FETCH_SIZE / WRITE_SIZE readings)")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
-        sys.exit(2)
+# ---------------------------------------------------------------------------------------------------------
+# one configuration on the GPU
+# ---------------------------------------------------------------------------------------------------------
+def build_problem(name, n_events):
+    import synth
+    if name == "C4" and (n_events is None or n_events > 4_000_000):
+        # the edge-feature table of the full event list (14.9 GB) is drawn on the GPU, in chunks
+        from synth.device import HostRowView, device_normal_table
+        P = synth.make_problem(name, n_events=n_events, with_efeat=False)
+        P["efeat"] = device_normal_table(P["E"], P["d"].d_edge, seed=synth.CONFIGS[name]["seed"] + 1000)
+        P["efeat_host"] = HostRowView(P["efeat"])
+        P["efeat_where"] = "drawn on the GPU in 2^20-row chunks (seeded)"
+    else:
+        P = synth.make_problem(name, n_events=n_events)
+        P["efeat_where"] = "drawn on the host (seeded)"
+    return P
 
-    import torch
-    from paper_2307_07649_amd import tgnn
-    sys.path.insert(0, os.path.join(ROOT, "tests"))
-    from gpu_common import make_problem
 
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        sys.exit(3)
-
-    if args.calibrate_copy:
-        a = torch.ones(64 << 20, device="cuda"); b = torch.empty_like(a)      # 256 MiB each
-        for _ in range(3):
-            tgnn.tgnn_debug_copy(b, a)
-        torch.cuda.synchronize()
-        del a, b
-
-    name = args.config
-    n_events = args.events
-    if name == "C4" and n_events is None:
-        n_events = 2_000_000
-    P = make_problem(name, n_events=n_events)
-    d = P["d"]
-    nrep = d.n_replicas
+def run_config(tgnn, torch, P, args, detail):
+    """Warm-up, `args.steps` timed steps (replica r trains mini-batch (s + r * ceil(M / nrep)) mod M; a replica that
+    wraps to mini-batch 0 starts a new epoch with its memory and mails reset), then an untimed pass with every stage
+    bracketed by HIP events.  Returns the figures of the configuration."""
+    import synth
+    name = P["name"]; d = P["d"]; nrep = d.n_replicas
     ctx = tgnn.Context(d.n_nodes, d.d_mem, d.d_time, d.d_edge, d.d_static, d.n_heads, d.k, d.batch, n_replicas=nrep,
                        flags=tgnn.FLAG_OVERWRITE_GRADS | (tgnn.FLAG_SIDE_STREAM if args.side_stream else 0))
     graph = tgnn.Graph(P["src"], P["dst"], P["ts"], d.n_nodes, P["efeat"])
@@ -170,18 +209,17 @@ def main():
     loss = torch.zeros(4, device="cuda")
     loss_steps = torch.zeros(tgnn.MAX_STEPS_PER_CALL, device="cuda")
 
-    # every mini-batch of the epoch, resident on the device
-    import synth
+    # every mini-batch of the epoch, resident on the device: the event arrays are uploaded once and sliced
     spans = synth.batches_of(P["E"], d.batch)
     M = len(spans)
-    eid_all = np.arange(P["E"], dtype=np.int32)
-    batches = [[tgnn.Batch(P["src"][lo:hi], P["dst"][lo:hi], P["neg"][lo:hi], eid_all[lo:hi], P["ts"][lo:hi], replica=r)
-                for (lo, hi) in spans] for r in range(nrep)]
+    dsrc, ddst, dneg = (torch.from_numpy(np.ascontiguousarray(P[n], np.int32)).cuda() for n in ("src", "dst", "neg"))
+    deid = torch.arange(P["E"], dtype=torch.int32, device="cuda")
+    dts = torch.from_numpy(np.ascontiguousarray(P["ts"], np.float64)).cuda()
+    batches = [[tgnn.Batch(dsrc[lo:hi], ddst[lo:hi], dneg[lo:hi], deid[lo:hi], dts[lo:hi], replica=r) for (lo, hi) in spans]
+               for r in range(nrep)]
     shift = -(-M // nrep)
 
     def run_step(s):
-        """Step s: replica r trains mini-batch (s + r*shift) mod M; a replica that wraps to mini-batch 0 starts a
-        new epoch with its memory and mails reset."""
         bl = []
         for r in range(nrep):
             m = (s + r * shift) % M
@@ -192,7 +230,7 @@ def main():
         return sum(b.n for b in bl)
 
     per_call = max(1, min(args.steps_per_call, tgnn.MAX_STEPS_PER_CALL))
-    last_loss = [(loss, 0)]   # where the most recent step's loss is
+    last_loss = [(loss, 0)]
 
     def run_steps(s_lo, s_hi):
         """Steps s_lo .. s_hi - 1, per_call of them per library call; a step at which a replica starts a new
@@ -222,105 +260,211 @@ def main():
 
     # a stream of its own: the library replays a captured HIP graph there (the NULL stream cannot be captured)
     torch.cuda.synchronize()
-    torch.cuda.set_stream(torch.cuda.Stream())
-    roof_mask = 0 if args.no_stage_events else (1 << STAGE_ASSEMBLE) | (1 << STAGE_KV) | (1 << STAGE_EMPTY)
-    every = max(1, args.event_every)
-    ctx.tgnn_profile_enable(roof_mask)
-    ctx.tgnn_profile_every(2)             # warm up both launch modes
-    run_steps(0, args.warmup)
-    torch.cuda.synchronize()
-    ctx.tgnn_profile_enable(roof_mask)    # drops the warm-up's records
-    ctx.tgnn_profile_every(every)
-    ev = 0
-    ev_timed_launches = 0                 # events of the steps whose roofline kernels were timed
-    n_timed_launches = 0
-    t0 = time.perf_counter()
-    per_step = run_steps(args.warmup, args.warmup + args.steps)
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    assert len(per_step) == args.steps
-    ev = sum(per_step)
-    if roof_mask != 0:
-        timed = per_step[::every]             # the library times every `every`-th step, starting with the first
-        ev_timed_launches, n_timed_launches = sum(timed), len(timed)
-    final_loss = float(last_loss[0][0][last_loss[0][1]].item())
-    n_g, ms_g = ctx.tgnn_profile_read(STAGE_ASSEMBLE)
-    n_m, ms_m = ctx.tgnn_profile_read(STAGE_KV)
-    n_e, ms_e = ctx.tgnn_profile_read(STAGE_EMPTY)
-    ctx.tgnn_profile_enable(0)
-    ctx.tgnn_profile_every(1)
-    # A pair of HIP event records with nothing in between is itself several microseconds apart on this stack (the
-    # step records such an empty bracket, stage 18, on the same steps).  It is reported, not subtracted: part of it
-    # overlaps with a kernel's launch, so the difference would overstate the kernels.  The brackets are therefore
-    # upper bounds of the launch durations (rocprofv3's kernel trace shows about 3 us less).
-    bracket_us = ms_e / n_e * 1e3 if n_e else None
-    kv_us = ms_m / n_m * 1e3 if n_m else None
-    asm_us = ms_g / n_g * 1e3 if n_g else None
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        roof_mask = 0 if args.no_stage_events else ((1 << STAGE_ASSEMBLE) | (1 << STAGE_KV) | (1 << STAGE_WGRAD)
+                                                    | (1 << STAGE_GATHER) | (1 << STAGE_EMPTY))
+        every = max(1, args.event_every)
+        ctx.tgnn_profile_enable(roof_mask)
+        ctx.tgnn_profile_every(2)             # warm up both launch modes
+        run_steps(0, args.warmup)
+        torch.cuda.synchronize()
+        ctx.tgnn_profile_enable(roof_mask)    # drops the warm-up's records
+        ctx.tgnn_profile_every(every)
+        t0 = time.perf_counter()
+        per_step = run_steps(args.warmup, args.warmup + args.steps)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        assert len(per_step) == args.steps
+        ev = sum(per_step)
+        timed = per_step[::every] if roof_mask else []     # the library times every `every`-th step, from the first on
+        final_loss = float(last_loss[0][0][last_loss[0][1]].item())
+        live = {st: ctx.tgnn_profile_read(st) for st in (STAGE_GATHER, STAGE_ASSEMBLE, STAGE_KV, STAGE_WGRAD, STAGE_EMPTY)}
+        ctx.tgnn_profile_enable(0)
+        ctx.tgnn_profile_every(1)
 
-    # per-stage breakdown from a separate, untimed pass with every stage bracketed by events; the number of distinct
-    # node rows of each of these steps is read back for the flops of the weight-gradient launch
-    n_prof = min(args.steps, 64)
-    ctx.tgnn_profile_enable((1 << len(STAGE_NAMES)) - 1)
-    rows_step = torch.zeros(n_prof, dtype=torch.int32, device="cuda")
-    ev_prof = 0
-    for i, s in enumerate(range(args.warmup + args.steps, args.warmup + args.steps + n_prof)):
-        ev_prof += run_step(s)
-        ctx.tgnn_debug_read(8, rows_step[i:i + 1])
-    torch.cuda.synchronize()
-    stages = {}
-    for i, nm in enumerate(STAGE_NAMES):
-        c, ms = ctx.tgnn_profile_read(i)
-        if c:
-            stages[nm] = round(ms / c * 1e3, 2)
-    n_w, ms_w = ctx.tgnn_profile_read(STAGE_WGRAD)
-    n_e2, ms_e2 = ctx.tgnn_profile_read(STAGE_EMPTY)
-    ctx.tgnn_profile_enable(0)
+        # per-stage breakdown from a separate, untimed pass with every stage bracketed by events; the number of
+        # distinct node rows of each of these steps is read back for the executed-work model
+        n_prof = min(args.steps, 32)
+        ctx.tgnn_profile_enable((1 << N_STAGES) - 1)
+        rows_step = torch.zeros(n_prof, dtype=torch.int32, device="cuda")
+        ev_prof = 0
+        for i, s in enumerate(range(args.warmup + args.steps, args.warmup + args.steps + n_prof)):
+            ev_prof += run_step(s)
+            ctx.tgnn_debug_read(8, rows_step[i:i + 1])
+        torch.cuda.synchronize()
+        stages = {}
+        for i, nm in STAGE_NAMES.items():
+            c, ms = ctx.tgnn_profile_read(i)
+            if c:
+                stages[nm] = round(ms / c * 1e3, 2)
+        ctx.tgnn_profile_enable(0)
     rows_avg = float(rows_step.float().mean().item())
-    wgrad_us = ms_w / n_w * 1e3 if n_w else None
-    wgrad_tflops = flops_wgrad(d, 3 * ev_prof / n_prof, rows_avg) / (wgrad_us * 1e-6) / 1e12 if n_w else None
+
+    def us(stage):
+        n, ms = live[stage]
+        return ms / n * 1e3 if n else None
 
     ev_step = ev / args.steps
-    R_avg = 3 * (ev_timed_launches / n_timed_launches if n_timed_launches else ev_step)   # roots per timed launch
-    kv_tflops = flops_kv(d, R_avg) / (kv_us * 1e-6) / 1e12 if n_m else None
-    asm_gbs = (assemble_bytes(d, R_avg) + gates_bytes(d, rows_avg)) / (asm_us * 1e-6) / 1e9 if n_g else None
+    R_timed = 3 * (sum(timed) / len(timed) if timed else ev_step)      # roots per event-bracketed launch
+    kv_us, asm_us, wg_us, ga_us, empty_us = (us(s) for s in (STAGE_KV, STAGE_ASSEMBLE, STAGE_WGRAD, STAGE_GATHER, STAGE_EMPTY))
+    kv_tf = flops_kv(d, R_timed) / (kv_us * 1e-6) / 1e12 if kv_us else None
+    wg_tf = flops_wgrad(d, R_timed, rows_avg) / (wg_us * 1e-6) / 1e12 if wg_us else None
+    asm_gbs = (assemble_bytes(d, R_timed) + gates_bytes(d, rows_avg)) / (asm_us * 1e-6) / 1e9 if asm_us else None
+    ga_gbs = state_gather_bytes(d, rows_avg) / (ga_us * 1e-6) / 1e9 if ga_us else None
+    ms_step = dt / args.steps * 1e3
+    f_slot = flops_per_slot_model(d, ev_step); f_exec = flops_executed_model(d, ev_step, rows_avg)
+    b_slot = bytes_per_slot_model(d, ev_step)
+    res = {
+        "workload": f"{name}: {d.n_nodes} nodes, {P['E']} events, d_mem {d.d_mem}, d_time {d.d_time}, d_edge {d.d_edge}, "
+                    f"d_static {d.d_static}, {d.n_heads} heads, k {d.k}, batch {d.batch} x {nrep} replica(s), "
+                    f"1 negative/event, SGD lr {args.lr}; edge features {P['efeat_where']}",
+        "events_per_s": ev / dt, "ms_per_step": ms_step, "events_per_step": ev_step, "steps": args.steps,
+        "final_loss": final_loss, "distinct_node_rows_per_step": rows_avg,
+        "kv_gemm": {"tflops": kv_tf, "frac_of_mfma_peak": kv_tf / PEAK_MFMA_F32_TFLOPS if kv_tf else None, "avg_launch_us": kv_us},
+        "weight_gradients": {"tflops": wg_tf, "frac_of_mfma_peak": wg_tf / PEAK_MFMA_F32_TFLOPS if wg_tf else None,
+                             "avg_launch_us": wg_us},
+        "edge_feature_gather": {"gbs": asm_gbs, "frac_of_hbm_peak": asm_gbs / PEAK_HBM_GBS if asm_gbs else None,
+                                "avg_launch_us": asm_us},
+        "state_gather": {"gbs": ga_gbs, "frac_of_hbm_peak": ga_gbs / PEAK_HBM_GBS if ga_gbs else None, "avg_launch_us": ga_us},
+        "empty_event_bracket_us": empty_us,
+        "step_model": {
+            "flops_per_slot": f_slot, "flops_executed": f_exec, "bytes_per_slot": b_slot,
+            "step_frac_of_mfma_peak_per_slot_count": f_slot / (ms_step * 1e-3) / 1e12 / PEAK_MFMA_F32_TFLOPS,
+            "step_frac_of_mfma_peak_executed": f_exec / (ms_step * 1e-3) / 1e12 / PEAK_MFMA_F32_TFLOPS,
+            "step_frac_of_hbm_peak_per_slot_bytes": b_slot / (ms_step * 1e-3) / 1e9 / PEAK_HBM_GBS,
+            "note": "per_slot: UPDT and unsplit projections for every slot, as the method states it (3 x forward); "
+                    "executed: what the kernels run after the exact shortcuts (UPDT and node projections once per "
+                    "distinct node, weight gradients of the slot projections over the roots); the per-slot count is "
+                    "never achieved work, a fraction above 1 on it only says how much the shortcuts removed"},
+    }
+    if detail:
+        res["stages_us"] = stages
+        res["stages_us_note"] = ("HIP-event brackets from an untimed pass launched kernel by kernel; every figure includes "
+                                 "the cost of an empty bracket (listed as its own entry)")
+    # standalone write-back scatter (it rides inside the last launch of a step): 2 x batch occurrences per call
+    n_ev = d.batch
+    b0 = batches[0][min(M - 1, M // 2)]
+    if b0.n == n_ev:
+        s_src = torch.randn(n_ev, d.d_mem, device="cuda"); s_dst = torch.randn(n_ev, d.d_mem, device="cuda")
+        tau = torch.zeros(n_ev, dtype=torch.float64, device="cuda")
+        st2 = tgnn.State(d.n_nodes, d.d_mem, nrep, P["static"])
+        n_wb = 50
+        with torch.cuda.stream(stream):
+            for _ in range(5):
+                ctx.tgnn_memory_writeback(st2, 0, b0.src, b0.dst, b0.eid, b0.t, s_src, s_dst, tau, tau)
+            e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for _ in range(n_wb):
+                ctx.tgnn_memory_writeback(st2, 0, b0.src, b0.dst, b0.eid, b0.t, s_src, s_dst, tau, tau)
+            e1.record(stream)
+            torch.cuda.synchronize()
+        n_written = int(torch.unique(torch.cat([b0.src, b0.dst])).numel())
+        call_us = e0.elapsed_time(e1) / n_wb * 1e3
+        res["writeback_standalone"] = {
+            "occurrences": 2 * n_ev, "nodes_written": n_written, "avg_call_us": call_us,
+            "gbs": writeback_bytes(d, n_written) / (call_us * 1e-6) / 1e9,
+            "note": "tgnn_memory_writeback alone: three small launches (descriptors, arbitration marks, scatter) per call, "
+                    "timed back to back on one stream; bytes = rows read and written for the winners"}
+    ctx.close()
+    return res
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=400)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", default="all", choices=["all", "C0", "C1", "C2", "C3", "C4"],
+                    help="all (default): the headline is C4 and the other four configurations are measured in the same "
+                         "run; Cn: only that configuration, which is then the headline")
+    ap.add_argument("--events", type=int, default=None, help="shorten the event list of the headline configuration")
+    ap.add_argument("--lr", type=float, default=1e-4)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-budget", type=float, default=10.0, help="seconds of oracle time per cpu_baseline leg")
+    ap.add_argument("--side-stream", action="store_true", help="let the library fork independent work of a step onto its second stream")
+    ap.add_argument("--no-stage-events", action="store_true", help="do not time kernels inside the timed region (every step then replays a captured HIP graph)")
+    ap.add_argument("--steps-per-call", type=int, default=4,
+                    help="consecutive training steps handed to the library per call (tgnn_train_steps; 1 = tgnn_train_step)")
+    ap.add_argument("--event-every", type=int, default=16,
+                    help="inside the timed region, every N-th step is launched kernel by kernel with HIP events around "
+                         "the roofline kernels; the other steps replay the captured HIP graph (1: every step)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="first run the library's plain copy kernel on 256 MiB three times (reference for rocprofv3 --pmc "
+                         "FETCH_SIZE / WRITE_SIZE readings)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2307_07649_amd import tgnn
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+
+    if args.calibrate_copy:
+        a = torch.ones(64 << 20, device="cuda"); b = torch.empty_like(a)      # 256 MiB each
+        for _ in range(3):
+            tgnn.tgnn_debug_copy(b, a)
+        torch.cuda.synchronize()
+        del a, b
+
+    head = "C4" if args.config == "all" else args.config
+    others = [c for c in ("C0", "C1", "C2", "C3") if args.config == "all"]
+    configs = {}
+    for name in others:
+        P = build_problem(name, None)
+        configs[name] = run_config(tgnn, torch, P, args, detail=False)
+        print(f"bench.py: {name} {configs[name]['events_per_s']:.0f} events/s", file=sys.stderr, flush=True)
+        del P
+    P = build_problem(head, args.events)
+    print(f"bench.py: {head} inputs ready", file=sys.stderr, flush=True)
+    res = run_config(tgnn, torch, P, args, detail=True)
+    configs[head] = {k: v for k, v in res.items() if k not in ("stages_us", "stages_us_note")}
+
+    d = P["d"]
+    wg, kv = res["weight_gradients"], res["kv_gemm"]
+    # the dominant kernel: the longer of the two MFMA launches of the step
+    if (wg["avg_launch_us"] or 0) >= (kv["avg_launch_us"] or 0):
+        dom = dict(kernel="gemm_tn_kernel: all weight gradients of the step in one grouped launch (fp32 MFMA 16x16x4), "
+                          "useful flops of its eight products", key="weight_gradients", tag="gemm_tn")
+    else:
+        dom = dict(kernel="gemm_nt_kernel: K/V projection of the {e | Phi} rows of all neighbour slots (fp32 MFMA 16x16x4)",
+                   key="kv_gemm", tag="kv_projection")
+    dk = res[dom["key"]]
     out = {
         "metric": "training events/sec (fwd+bwd+memory update) at 1 GPU",
-        "value": ev / dt, "unit": "events/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": dt / args.steps * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "value": res["events_per_s"], "unit": "events/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": res["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": f"{name}: {d.n_nodes} nodes, {P['E']} events, d_mem {d.d_mem}, d_time {d.d_time}, "
-                               f"d_edge {d.d_edge}, d_static {d.d_static}, {d.n_heads} heads, k {d.k}, "
-                               f"batch {d.batch} x {nrep} replica(s), 1 negative/event, SGD lr {args.lr}",
-                   "events_per_step": ev_step, "steps_per_call": per_call, "final_loss": final_loss},
-        "roofline": {"bound": "mfma", "kernel": "gemm_nt_kernel: K/V projection of the {e | Phi} rows of all "
-                                                "neighbour slots (fp32 MFMA 16x16x4), the longest forward kernel",
-                     "achieved": kv_tflops, "peak": PEAK_MFMA_F32_TFLOPS, "unit": "TFLOP/s",
-                     "frac": kv_tflops / PEAK_MFMA_F32_TFLOPS if kv_tflops else None,
-                     "avg_launch_us": kv_us, "empty_event_bracket_us": bracket_us,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(name, {}).get("kv_projection")},
-        "weight_gradients": {"bound": "mfma", "kernel": "gemm_tn_kernel: all weight gradients of the step in one grouped "
-                                                        "launch (fp32 MFMA 16x16x4), the longest kernel of the step; timed "
-                                                        "with HIP events in the untimed per-stage pass",
-                             "achieved": wgrad_tflops, "peak": PEAK_MFMA_F32_TFLOPS, "unit": "TFLOP/s",
-                             "frac": wgrad_tflops / PEAK_MFMA_F32_TFLOPS if wgrad_tflops else None,
-                             "avg_launch_us": wgrad_us, "empty_event_bracket_us": ms_e2 / n_e2 * 1e3 if n_e2 else None,
-                             "distinct_node_rows_per_step": rows_avg},
-        "gather": {"bound": "hbm", "kernel": "assemble_ce_kernel: edge-feature row gather + time encoding into the "
-                                             "per-slot key/value inputs; its first blocks carry the GRU gates of the "
-                                             "distinct node rows (bytes of both counted)",
-                   "achieved": asm_gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                   "frac": asm_gbs / PEAK_HBM_GBS if asm_gbs else None,
-                   "avg_launch_us": asm_us, "empty_event_bracket_us": bracket_us,
-                   "traffic": MEASURED_TRAFFIC_BYTES.get(name, {}).get("assemble_ce")},
-        "step_model": {"flops_per_step_per_slot_updt": step_flops(d, ev_step), "bytes_per_step": step_bytes(d, ev_step),
-                       "note": "flops counted with UPDT per slot as the method states it; the library evaluates "
-                               "UPDT once per distinct node, so executed flops are lower"},
-        "stages_us": stages,
-        "stages_us_note": "HIP-event brackets from an untimed pass launched kernel by kernel; every figure includes the "
-                          "cost of an empty bracket (listed as its own entry)",
+        "config": {"workload": res["workload"], "events_per_step": res["events_per_step"],
+                   "steps_per_call": args.steps_per_call, "final_loss": res["final_loss"]},
+        "roofline": {"bound": "mfma", "kernel": dom["kernel"], "achieved": dk["tflops"], "peak": PEAK_MFMA_F32_TFLOPS,
+                     "unit": "TFLOP/s", "frac": dk["frac_of_mfma_peak"], "avg_launch_us": dk["avg_launch_us"],
+                     "empty_event_bracket_us": res["empty_event_bracket_us"],
+                     "traffic": recorded_traffic(head, dom["tag"])},
+        "gather": {"bound": "hbm", "kernel": "assemble_ce_kernel: edge-feature row gather + time encoding into the per-slot "
+                                             "key/value inputs; its first blocks carry the GRU gates of the distinct node "
+                                             "rows (bytes of both counted)",
+                   "achieved": res["edge_feature_gather"]["gbs"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                   "frac": res["edge_feature_gather"]["frac_of_hbm_peak"],
+                   "avg_launch_us": res["edge_feature_gather"]["avg_launch_us"],
+                   "traffic": recorded_traffic(head, "assemble_ce")},
+        "state_gather": dict(res["state_gather"], bound="hbm", peak=PEAK_HBM_GBS,
+                             kernel="gather_kernel: memory, mail and the mail's edge-feature row of every distinct node "
+                                    "into the GRU input"),
+        "writeback": res.get("writeback_standalone"),
+        "kv_gemm": kv, "weight_gradients": wg,
+        "step_model": res["step_model"],
+        "configs": configs,
+        "stages_us": res.get("stages_us"), "stages_us_note": res.get("stages_us_note"),
     }
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(P)
+        allc = cpu_baseline(P, args.cpu_budget, None)
+        one = cpu_baseline(P, args.cpu_budget, 1)
+        out["cpu_baseline"] = dict(allc, single_thread=one, host_cores=os.cpu_count())
     print(json.dumps(out))
 
 

@@ -28,9 +28,12 @@ Where the paper is silent the readings are (they are listed with reasons in the 
   loss = mean binary cross-entropy over B positive and B negative pairs; a mail row stores
   {s'_self || s'_other} and the event id, Phi and e_uv are looked up when the mail is consumed.
 
-Parity pins (tests/test_oracle_*.py): brute-force neighbour scan, closed forms of the time
-encoding, a library GRU cell and its limits, attention special cases, ln 2 loss, central
-finite differences for every parameter tensor, brute-force last-writer-wins write-back.
+Parity pins (tests/test_oracle_*.py): hand-written neighbour lists and a pure-Python event scan
+for the sampler (and the indexed form against the scan); closed forms of the time encoding, on the
+function and on the values the step feeds to the GRU, the keys and the query (hand-built states
+with known time differences and non-zero phases); a library GRU cell and its limits; attention
+special cases; ln 2 loss; central finite differences for every parameter tensor; brute-force
+last-writer-wins write-back.
 The step as a whole is "parity unpinned" against the paper, which prints no worked example.
 """
 from __future__ import annotations
@@ -61,9 +64,37 @@ def to_f64(params):
 # --------------------------------------------------------------------------------------
 # most-recent-neighbour sampling (Sec. 2.1: "most recent neighbors"; k = 10 in Sec. 4)
 # --------------------------------------------------------------------------------------
+def sample_recent(src, dst, ts, q_node, q_t, k):
+    """The definition, as a scan of the raw chronological event list.  Every event (u, v, t) is incident
+    to both endpoints; for a query (node, t_q) the candidates are the incident events with time strictly
+    below t_q, ordered by (time, event id); the last min(k, #) of them are returned, most recent first.
+    An event with u = v = node is incident to the node once as a source and once as a destination, so it
+    is listed twice.  Padding: nbr = eid = -1, time = 0.
+    src, dst, ts: the whole event list, ts non-decreasing (then event-id order is (time, id) order)."""
+    src = np.asarray(src, np.int64); dst = np.asarray(dst, np.int64); ts = np.asarray(ts, F)
+    R = len(q_node)
+    nbr = np.full((R, k), -1, np.int64); ne = np.full((R, k), -1, np.int64)
+    nts = np.zeros((R, k), F); cnt = np.zeros(R, np.int64)
+    for r in range(R):
+        v = q_node[r]
+        as_src = np.flatnonzero(src == v)                     # events leaving v: the other endpoint is dst
+        as_dst = np.flatnonzero(dst == v)                     # events entering v: the other endpoint is src
+        e = np.concatenate([as_src, as_dst])
+        other = np.concatenate([dst[as_src], src[as_dst]])
+        keep = ts[e] < q_t[r]                                 # strictly earlier than the query
+        e, other = e[keep], other[keep]
+        order = np.argsort(e, kind="stable")                  # (time, event id) order = event-id order
+        e, other = e[order], other[order]
+        c = min(k, len(e))
+        if c:
+            nbr[r, :c] = other[::-1][:c]; ne[r, :c] = e[::-1][:c]; nts[r, :c] = ts[e[::-1][:c]]
+        cnt[r] = c
+    return nbr, ne, nts, cnt
+
+
 def build_adjacency(src, dst, ts, n_nodes):
-    """Every event is incident to both endpoints.  Per node, incident events ordered by
-    (time, event id).  Returns (indptr, other, eid, time) in that order."""
+    """Per-node lists of incident events ordered by (time, event id): an index over the event list for
+    graphs on which the scan above would take hours.  Returns (indptr, other, eid, time)."""
     src = np.asarray(src, np.int64); dst = np.asarray(dst, np.int64); ts = np.asarray(ts, F)
     E = src.shape[0]
     node = np.concatenate([src, dst]); other = np.concatenate([dst, src])
@@ -76,9 +107,9 @@ def build_adjacency(src, dst, ts, n_nodes):
     return indptr, other, eid, tt
 
 
-def sample_recent(adj, q_node, q_t, k):
-    """For each query (node, t): the min(k, #) incident events with time strictly below t that come
-    last in (time, event id) order, listed most recent first.  Padding: nbr = eid = -1, time = 0."""
+def sample_recent_indexed(adj, q_node, q_t, k):
+    """Same result as sample_recent, read off the per-node lists of build_adjacency (the tests hold the
+    two against each other).  Used only where the event list is too long to scan once per query."""
     indptr, other, eid, tt = adj
     R = len(q_node)
     nbr = np.full((R, k), -1, np.int64); ne = np.full((R, k), -1, np.int64)
@@ -92,6 +123,11 @@ def sample_recent(adj, q_node, q_t, k):
     return nbr, ne, nts, cnt
 
 
+def event_list(src, dst, ts):
+    """The graph argument of forward_backward / train_step: the raw event list (neighbours by scan)."""
+    return dict(src=np.asarray(src, np.int64), dst=np.asarray(dst, np.int64), ts=np.asarray(ts, F))
+
+
 # --------------------------------------------------------------------------------------
 # time encoding Phi (Eq. 1-2, 5-6)
 # --------------------------------------------------------------------------------------
@@ -99,6 +135,13 @@ def time_encode(delta, w, b):
     """Phi(delta)_c = cos(w_c * delta + b_c).  delta: [...]; returns [..., d_time]."""
     delta = np.asarray(delta, F)
     return np.cos(delta[..., None] * w + b)
+
+
+def time_encode_darg(delta, w, b):
+    """d Phi(delta)_c / d(w_c delta + b_c) = -sin(w_c delta + b_c): what the backward pass multiplies by
+    (times delta for the gradient of w_c, times 1 for that of b_c)."""
+    delta = np.asarray(delta, F)
+    return -np.sin(delta[..., None] * w + b)
 
 
 # --------------------------------------------------------------------------------------
@@ -131,8 +174,7 @@ def updt_slots(state, efeat, p, slot_node):
     me = state["mail_eid"][w]
     has = valid & (me >= 0)
     delta = np.where(has, state["mail_ts"][w] - state["mem_ts"][w], 0.0)
-    arg = delta[:, None] * p["time_w"] + p["time_b"]
-    phi = np.cos(arg)
+    phi = time_encode(delta, p["time_w"], p["time_b"])
     d_e = efeat.shape[1]
     ef = efeat[np.where(has, me, 0)].astype(F) if d_e else np.zeros((len(w), 0), F)
     x = np.concatenate([state["mail"][w], phi, ef], axis=1)
@@ -140,7 +182,7 @@ def updt_slots(state, efeat, p, slot_node):
     hnew, c = gru_cell(x, h, p["gru_wih"], p["gru_whh"], p["gru_bih"], p["gru_bhh"], want_cache=True)
     s_new = np.where(has[:, None], hnew, h) * valid[:, None]
     tau = np.where(has, state["mail_ts"][w], state["mem_ts"][w]) * valid
-    c.update(x=x, h=h, has=has, delta=delta, arg=arg)
+    c.update(x=x, h=h, has=has, delta=delta)
     return s_new, tau, c
 
 
@@ -154,11 +196,10 @@ def attention_fwd(p, x_root, x_nbr, e_nbr, dt_nbr, cnt, n_heads):
     z = ReLU(W_o {h_v || x_v} + b_o)."""
     R, k, _ = x_nbr.shape
     d_o = p["wq"].shape[0]
-    phi0 = np.broadcast_to(np.cos(p["time_b"]), (R, p["time_b"].shape[0]))
+    phi0 = time_encode(np.zeros(R), p["time_w"], p["time_b"])          # the query's own time difference is 0
     q_in = np.concatenate([x_root, phi0], axis=1)
     q = q_in @ p["wq"].T + p["bq"]
-    arg = dt_nbr[..., None] * p["time_w"] + p["time_b"]
-    c_in = np.concatenate([x_nbr, e_nbr, np.cos(arg)], axis=2)
+    c_in = np.concatenate([x_nbr, e_nbr, time_encode(dt_nbr, p["time_w"], p["time_b"])], axis=2)
     K = c_in @ p["wk"].T + p["bk"]
     V = c_in @ p["wv"].T + p["bv"]
     mask = np.arange(k)[None, :] < cnt[:, None]
@@ -176,19 +217,22 @@ def attention_fwd(p, x_root, x_nbr, e_nbr, dt_nbr, cnt, n_heads):
     m_in = np.concatenate([o, x_root], axis=1)
     zpre = m_in @ p["wo"].T + p["bo"]
     z = np.maximum(zpre, 0.0)
-    cache = dict(q_in=q_in, q=q, c_in=c_in, arg=arg, K=K, V=V, pr=pr, scale=scale, mask=mask, o=o,
+    cache = dict(q_in=q_in, q=q, c_in=c_in, K=K, V=V, pr=pr, scale=scale, mask=mask, o=o,
                  m_in=m_in, zpre=zpre, dt=dt_nbr)
     return z, cache
 
 
-def attention_bwd(p, cache, dz, n_heads):
-    """Reverse mode through attention_fwd.  Returns (param grads, d x_root, d x_nbr)."""
+def attention_bwd(p, cache, dz, n_heads, gate_z=None):
+    """Reverse mode through attention_fwd.  Returns (param grads, d x_root, d x_nbr).
+    gate_z (bool [R, d_o], optional): the ReLU gate of the merge layer to differentiate through instead of
+    zpre > 0 -- for a comparison with an implementation that decided a pre-activation within rounding of zero
+    the other way (the decision is then taken once, in that implementation's precision)."""
     g = {}
     q_in, c_in, K, V, pr, scale, mask = (cache[n] for n in ("q_in", "c_in", "K", "V", "pr", "scale", "mask"))
     R, k, d_kv = c_in.shape
     d_o = p["wq"].shape[0]; dh = d_o // n_heads
     d_x = q_in.shape[1] - p["time_b"].shape[0]
-    dzpre = dz * (cache["zpre"] > 0)
+    dzpre = dz * ((cache["zpre"] > 0) if gate_z is None else gate_z)
     g["wo"] = dzpre.T @ cache["m_in"]; g["bo"] = dzpre.sum(0)
     dm_in = dzpre @ p["wo"]
     do = dm_in[:, :d_o]; dx_root = dm_in[:, d_o:].copy()
@@ -205,17 +249,27 @@ def attention_bwd(p, cache, dz, n_heads):
     dK = dK * mk; dV = dV * mk
     cf = c_in.reshape(R * k, d_kv) * mask.reshape(R * k, 1)
     g["wk"] = dK.reshape(R * k, d_o).T @ cf; g["bk"] = dK.sum((0, 1))
+    # Not gradients: for the four tensors fed by the score gradients da only, the same sums over magnitudes, with
+    # |da| taken before the cancellation inside the softmax's backward pass, pr (|dpr| + sum pr |dpr|).  The softmax is
+    # invariant to a shift of all scores of a root, so the exact gradient of bk is zero, and with identical keys
+    # those of wq, bq, wk vanish too; these sums are the scale the rounding error of such a result lives on.
+    da_mag = pr * (np.abs(dpr) + (pr * np.abs(dpr)).sum(axis=2, keepdims=True)) * scale[:, None, None]
+    dq_mag = np.einsum("rhj,rjhd->rhd", da_mag, np.abs(Kh)).reshape(R, d_o)
+    dK_mag = np.einsum("rhj,rhd->rjhd", da_mag, np.abs(qh)).reshape(R, k, d_o) * mk
+    cache["abs_terms"] = dict(wq=dq_mag.T @ np.abs(q_in), bq=dq_mag.sum(0),
+                              wk=dK_mag.reshape(R * k, d_o).T @ np.abs(cf), bk=dK_mag.sum((0, 1)))
     g["wv"] = dV.reshape(R * k, d_o).T @ cf; g["bv"] = dV.sum((0, 1))
     dc = dK @ p["wk"] + dV @ p["wv"]                         # [R, k, d_kv]
     dx_nbr = dc[:, :, :d_x]
     dphi = dc[:, :, d_kv - p["time_b"].shape[0]:] * mk
-    msin = -np.sin(cache["arg"])
+    msin = time_encode_darg(cache["dt"], p["time_w"], p["time_b"])
     g["time_w"] = (dphi * msin * cache["dt"][..., None]).sum((0, 1))
     g["time_b"] = (dphi * msin).sum((0, 1))
     g["wq"] = dq.T @ q_in; g["bq"] = dq.sum(0)
     dq_in = dq @ p["wq"]
     dx_root += dq_in[:, :d_x]
-    g["time_b"] = g["time_b"] + (dq_in[:, d_x:] * (-np.sin(p["time_b"]))).sum(0)   # Phi(0): d/dw = 0
+    g["time_b"] = g["time_b"] + (dq_in[:, d_x:] * time_encode_darg(np.zeros(R), p["time_w"], p["time_b"])).sum(0)
+    # (Phi(0) does not depend on w)
     return g, dx_root, dx_nbr
 
 
@@ -239,12 +293,14 @@ def decoder_loss(p, z_src, z_dst, z_neg):
     return loss, logits, dict(a=a, b=b, hpre=hpre, h1=h1, y=y)
 
 
-def decoder_bwd(p, cache, logits, loss_scale=1.0):
+def decoder_bwd(p, cache, logits, loss_scale=1.0, gate_h=None):
+    """gate_h (bool [2B, d_o], optional): the ReLU gate of the hidden layer to use instead of hpre > 0 (see
+    attention_bwd)."""
     B2 = logits.shape[0]; B = B2 // 2
     g = {}
     dl = (_sigmoid(logits) - cache["y"]) / B2 * loss_scale
     g["dec_w2"] = cache["h1"].T @ dl; g["dec_b2"] = np.array([dl.sum()])
-    dh = dl[:, None] * p["dec_w2"][None, :] * (cache["hpre"] > 0)
+    dh = dl[:, None] * p["dec_w2"][None, :] * ((cache["hpre"] > 0) if gate_h is None else gate_h)
     g["dec_ws"] = dh.T @ cache["a"]; g["dec_wd"] = dh.T @ cache["b"]; g["dec_b1"] = dh.sum(0)
     da = dh @ p["dec_ws"]; db = dh @ p["dec_wd"]
     return g, da[:B] + da[B:], db[:B], db[B:]
@@ -277,16 +333,21 @@ def writeback(state, src, dst, eid, t, s_src, s_dst, tau_src, tau_dst):
 # --------------------------------------------------------------------------------------
 # one training step on one mini-batch
 # --------------------------------------------------------------------------------------
-def forward_backward(state, adj, efeat, static, p, batch, k, n_heads, dt_source=0, loss_scale=1.0,
-                     want_grads=True):
-    """batch = dict(src, dst, neg, eid, t).  Returns dict(loss, logits, grads, nbr, neid, nts, cnt,
-    s_new, tau, z).  Does not modify `state`."""
+def forward_backward(state, graph, efeat, static, p, batch, k, n_heads, dt_source=0, loss_scale=1.0,
+                     want_grads=True, relu_gates=None):
+    """graph = event_list(src, dst, ts): neighbours by the scan of sample_recent (a build_adjacency tuple
+    instead selects sample_recent_indexed).  batch = dict(src, dst, neg, eid, t).  Returns dict(loss,
+    logits, grads, nbr, neid, nts, cnt, s_new, tau, z, ...).  Does not modify `state`.
+    relu_gates = (gate_z, gate_h), optional: see attention_bwd / decoder_bwd."""
     src, dst, neg = (np.asarray(batch[n], np.int64) for n in ("src", "dst", "neg"))
     t = np.asarray(batch["t"], F)
     B = len(src); R = 3 * B
     d_m = state["mem"].shape[1]; d_t = p["time_w"].shape[0]
     root_node = np.concatenate([src, dst, neg]); root_t = np.concatenate([t, t, t])
-    nbr, neid, nts, cnt = sample_recent(adj, root_node, root_t, k)
+    if isinstance(graph, dict):
+        nbr, neid, nts, cnt = sample_recent(graph["src"], graph["dst"], graph["ts"], root_node, root_t, k)
+    else:
+        nbr, neid, nts, cnt = sample_recent_indexed(graph, root_node, root_t, k)
     slot_node = np.concatenate([root_node, nbr.reshape(-1)])
     s_new, tau, gc = updt_slots(state, efeat, p, slot_node)
 
@@ -305,12 +366,13 @@ def forward_backward(state, adj, efeat, static, p, batch, k, n_heads, dt_source=
     z, ac = attention_fwd(p, x_root, x_nbr, e_nbr, dt_nbr, cnt, n_heads)
     loss, logits, dc = decoder_loss(p, z[:B], z[B:2 * B], z[2 * B:])
     out = dict(loss=loss, logits=logits, nbr=nbr, neid=neid, nts=nts, cnt=cnt, s_new=s_new, tau=tau, z=z,
-               dt_nbr=dt_nbr, zpre=ac["zpre"], hpre=dc["hpre"])
+               dt_nbr=dt_nbr, zpre=ac["zpre"], hpre=dc["hpre"], gru_x=gc["x"], q_in=ac["q_in"], c_in=ac["c_in"])
     if not want_grads:
         return out
 
-    g, dzs, dzd, dzn = decoder_bwd(p, dc, logits, loss_scale)
-    ga, dx_root, dx_nbr = attention_bwd(p, ac, np.concatenate([dzs, dzd, dzn], 0), n_heads)
+    gate_z, gate_h = relu_gates if relu_gates is not None else (None, None)
+    g, dzs, dzd, dzn = decoder_bwd(p, dc, logits, loss_scale, gate_h)
+    ga, dx_root, dx_nbr = attention_bwd(p, ac, np.concatenate([dzs, dzd, dzn], 0), n_heads, gate_z)
     g.update(ga)
     # gradient reaching s' of every slot; it stops at the stored memory and mails (no BPTT)
     ds = np.concatenate([dx_root[:, :d_m], dx_nbr[:, :, :d_m].reshape(R * k, d_m)], 0)
@@ -325,10 +387,11 @@ def forward_backward(state, adj, efeat, static, p, batch, k, n_heads, dt_source=
     g["gru_wih"] = dgi.T @ x; g["gru_bih"] = dgi.sum(0)
     g["gru_whh"] = dgh.T @ h; g["gru_bhh"] = dgh.sum(0)
     dphi = (dgi @ p["gru_wih"])[:, 2 * d_m:2 * d_m + d_t]
-    msin = -np.sin(gc["arg"])
+    msin = time_encode_darg(gc["delta"], p["time_w"], p["time_b"])
     g["time_w"] = g["time_w"] + (dphi * msin * gc["delta"][:, None]).sum(0)
     g["time_b"] = g["time_b"] + (dphi * msin).sum(0)
     out["grads"] = {n: g[n] for n in PARAM_NAMES}
+    out["abs_terms"] = ac["abs_terms"]
     return out
 
 
@@ -345,15 +408,21 @@ def sgd(p, grads, lr):
             p[n] -= lr * grads[n]
 
 
-def train_step(states, adj, efeat, static, p, batches, k, n_heads, lr=0.0, dt_source=0):
-    """One step over len(batches) memory replicas that share one weight set (memory parallelism,
-    Sec. 3.2.3): replica i advances states[i] on batches[i]; gradients are summed, the loss is the
-    mean of the per-batch losses; then one SGD update and the write-backs."""
-    outs = [forward_backward(states[i], adj, efeat, static, p, batches[i], k, n_heads, dt_source)
-            for i in range(len(batches))]
+def apply_step(states, p, batches, outs, lr=0.0):
+    """Second half of a step, from the per-batch results `outs` of forward_backward: gradients summed over the
+    batches (memory parallelism, Sec. 3.2.3: one weight set), loss averaged, the write-backs, one SGD update."""
     grads = {n: sum(o["grads"][n] for o in outs) for n in PARAM_NAMES}
     loss = float(np.mean([o["loss"] for o in outs]))
     wins = [apply_writeback(states[i], batches[i], outs[i]) for i in range(len(batches))]
     if lr:
         sgd(p, grads, lr)
-    return dict(loss=loss, grads=grads, outs=outs, winners=wins)
+    return dict(loss=loss, grads=grads, outs=outs, winners=wins,
+                abs_terms={n: sum(o["abs_terms"][n] for o in outs) for n in outs[0]["abs_terms"]})
+
+
+def train_step(states, graph, efeat, static, p, batches, k, n_heads, lr=0.0, dt_source=0):
+    """One step over len(batches) memory replicas that share one weight set: replica i advances states[i] on
+    batches[i], everything computed from the pre-step state and weights."""
+    outs = [forward_backward(states[i], graph, efeat, static, p, batches[i], k, n_heads, dt_source)
+            for i in range(len(batches))]
+    return apply_step(states, p, batches, outs, lr)

@@ -5,6 +5,7 @@ features, negative destinations, static embeddings, initial weights).  It contai
 of the model's arithmetic: no sampling, no time encoding, no GRU, no attention.
 """
 from .graphs import CONFIGS, ModelDims, dims_of, gen_graph, gen_negatives, gen_params, gen_static, batches_of
+from .problems import make_problem, custom_problem, batch_np
 
 __all__ = ["CONFIGS", "ModelDims", "dims_of", "gen_graph", "gen_negatives", "gen_params",
-           "gen_static", "batches_of"]
+           "gen_static", "batches_of", "make_problem", "custom_problem", "batch_np"]

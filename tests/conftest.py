@@ -28,3 +28,10 @@ def pytest_collection_modifyitems(config, items):
     for it in items:
         if "gpu" in it.keywords:
             it.add_marker(skip)
+
+
+def pytest_sessionfinish(session, exitstatus):
+    """The measured per-tensor errors of every GPU-vs-oracle step comparison of the session, one JSON line each."""
+    gc = sys.modules.get("gpu_common")
+    if gc is not None and gc.ERR_LOG:
+        gc.dump_err_log(os.path.join(ROOT, "gpurun_out", "parity_errors.jsonl"))

@@ -4,7 +4,8 @@ graph: sampled neighbours and winners bit-exact on every checked step, logits / 
 import numpy as np
 import pytest
 
-from gpu_common import GpuSide, OracleSide, batch_np, compare_state, compare_step, make_problem, rel_err
+from gpu_common import (GpuSide, OracleSide, batch_np, compare_state, compare_step, make_problem, rel_err,
+                        spot_check_sampler)
 import synth
 
 pytestmark = pytest.mark.gpu
@@ -19,11 +20,15 @@ def run(P, n_steps, lr, check_at, first=0):
         b = batch_np(P, lo, hi)
         want = s in check_at
         g = G.step([b], lr=lr, want=want)
-        o = Or.step([b], lr=lr)
+        o = Or.step([b], lr=lr, gpu=g)
         if want:
-            out[s] = compare_step(g, o, label=f"{P['name']} step {s}")
+            out[s] = compare_step(g, o, label=f"{P['name']} lr {lr} step {first + s}")
+            if not Or.scan:      # the oracle read its neighbours off the index: scan the event list for sampled roots
+                spot_check_sampler(P, g, [b], seed=s)
     compare_state(G.state_np(), Or.states[0], label=P["name"])
-    assert sum(1 for e in out.values() if e["relu_tie_flips"] == 0) >= max(1, len(out) - 1), out
+    if lr:
+        for n, v in G.params.numpy().items():
+            assert rel_err(v, Or.p[n]) <= 1e-4, n
     return out
 
 
@@ -39,9 +44,19 @@ def test_c1_last_ragged_batch():
     run(P, 3, lr=0.0, check_at=(0, 2), first=M - 3)          # the epoch's last mini-batch has 274 events
 
 
-def test_c2_static_memory_20_batches():
+@pytest.mark.parametrize("lr", [0.0, 1e-3])
+def test_c2_static_memory_50_batches(lr):
+    """The enhanced model (static + dynamic memory) on the first 100 mini-batches' worth of the C2 recipe: 50
+    consecutive batches without and with SGD."""
     P = make_problem("C2", n_events=60_000)
-    run(P, 20, lr=0.0, check_at=(0, 19))
+    run(P, 50, lr=lr, check_at=(0, 1, 25, 49))
+
+
+def test_c2_full_size_late_in_the_stream():
+    """C2 at its full 672,447 events, four batches from event 540,000 on (long neighbour lists, 463 MB of edge
+    features); the oracle reads its neighbours off the index, sampled roots are scanned."""
+    P = make_problem("C2")
+    run(P, 4, lr=1e-3, check_at=(0, 2, 3), first=900)
 
 
 def test_c3_eight_replicas_time_shifted():
@@ -54,8 +69,8 @@ def test_c3_eight_replicas_time_shifted():
     for s in range(6):
         bl = [batch_np(P, *spans[(s + r * shift) % M]) for r in range(nrep)]
         g = G.step(bl, lr=1e-3)
-        o = Or.step(bl, lr=1e-3)
-        compare_step(g, o, label=f"C3 step {s}")
+        o = Or.step(bl, lr=1e-3, gpu=g)
+        compare_step(g, o, label=f"C3 lr 1e-3 step {s}")
     for r in range(nrep):
         compare_state(G.state_np(r), Or.states[r], label=f"C3 replica {r}")
     for n, v in G.params.numpy().items():
@@ -71,7 +86,7 @@ def test_c3_replica_subset_and_order():
         reps = [5, 0, 7]                                     # any subset, any order; others stay untouched
         bl = [batch_np(P, *spans[s + 3 * i]) for i in range(3)]
         g = G.step(bl, replicas=reps)
-        o = Or.step(bl, replicas=reps)
+        o = Or.step(bl, replicas=reps, gpu=g)
         compare_step(g, o, label=f"subset step {s}")
     for r in range(8):
         compare_state(G.state_np(r), Or.states[r], label=f"replica {r}")
@@ -84,13 +99,57 @@ def test_c4_shape_three_batches():
     run(P, 4, lr=0.0, check_at=(1, 3))
 
 
+_C4 = {}
+
+
+def c4_full():
+    """The full 20,000,000-event C4 problem, built once per session: event list from the seeded host recipe, the
+    14.9 GB edge-feature table drawn on the GPU (seeded) and read by the oracle through a row view, and the
+    oracle's index over the event list."""
+    if not _C4:
+        from synth.device import HostRowView, device_normal_table
+        from oracle import tgnn_oracle as O
+        P = make_problem("C4", with_efeat=False)
+        P["efeat"] = device_normal_table(P["E"], P["d"].d_edge, seed=synth.CONFIGS["C4"]["seed"] + 1000)
+        P["efeat_host"] = HostRowView(P["efeat"])
+        _C4["P"] = P
+        _C4["adj"] = O.build_adjacency(P["src"], P["dst"], P["ts"], P["d"].n_nodes)
+    return _C4["P"], _C4["adj"]
+
+
+@pytest.mark.slow
+def test_c4_full_size_fused_steps_late_in_the_stream():
+    """Three consecutive fused steps of 4,000 events on the full graph from event 16,000,000 on: event ids are
+    beyond 2^31 / d_e, so the edge-feature row offsets pass 2^31 elements and 2^32 bytes; neighbour lists are at
+    their longest.  Indices and winners bit-exact, logits / gradients / s' of all slots / memory within 1e-4, SGD
+    on."""
+    P, adj = c4_full()
+    d = P["d"]
+    assert (16_000_000 * d.d_edge) > 2 ** 31
+    G = GpuSide(P); Or = OracleSide(P)
+    Or.adj = adj; Or.scan = False
+    first = 4000
+    for s in range(3):
+        lo = (first + s) * d.batch
+        b = batch_np(P, lo, lo + d.batch)
+        g = G.step([b], lr=1e-3)
+        o = Or.step([b], lr=1e-3, gpu=g)
+        compare_step(g, o, label=f"C4 full lr 1e-3 step {first + s}")
+        spot_check_sampler(P, g, [b], n=16, seed=s)
+        assert g["neid"].max() > 11_600_000
+    compare_state(G.state_np(), Or.states[0], label="C4 full")
+    for n, v in G.params.numpy().items():
+        assert rel_err(v, Or.p[n]) <= 1e-4, n
+
+
 @pytest.mark.slow
 def test_c4_full_graph_sampler():
     """Sampler on the full 20,000,000-event graph (node degrees up to millions) against the oracle."""
     import torch
     from paper_2307_07649_amd import tgnn
     from oracle import tgnn_oracle as O
-    g = synth.gen_graph("C4", with_efeat=False)
+    P, adj_full = c4_full()
+    g = P
     n = synth.CONFIGS["C4"]["n_nodes"]
     ctx = tgnn.Context(n, 8, 4, 0, 0, 1, 10, 40_000)
     graph = tgnn.Graph(g["src"], g["dst"], g["ts"], n, None)
@@ -101,10 +160,13 @@ def test_c4_full_graph_sampler():
     qt = g["ts"][ev].copy()
     qt[::7] = rng.uniform(0, 1.4e5, len(qt[::7]))
     nbr, eid, ts, cnt = ctx.tgnn_sample_recent(graph, torch.from_numpy(qn).cuda(), torch.from_numpy(qt).cuda())
-    adj = O.build_adjacency(g["src"], g["dst"], g["ts"], n)
-    o = O.sample_recent(adj, qn, qt, 10)
+    o = O.sample_recent_indexed(adj_full, qn, qt, 10)
     assert np.array_equal(cnt.cpu().numpy(), o[3]) and np.array_equal(eid.cpu().numpy(), o[1])
     assert np.array_equal(nbr.cpu().numpy(), o[0]) and np.array_equal(ts.cpu().numpy(), o[2])
+    pick = rng.choice(Q, 24, replace=False)               # the scan of the whole event list for sampled queries
+    sc = O.sample_recent(g["src"], g["dst"], g["ts"], qn[pick], qt[pick], 10)
+    for a, b in zip(sc, o):
+        assert np.array_equal(a, b[pick])
 
 
 def test_c1_and_c3_four_steps_per_call():

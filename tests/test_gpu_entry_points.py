@@ -5,7 +5,7 @@ import pytest
 import torch
 
 import synth
-from gpu_common import TOL, OracleSide, batch_np, custom_problem, make_problem, rel_err
+from gpu_common import FP32_EPS, TOL, OracleSide, batch_np, custom_problem, make_problem, rel_err
 from oracle import tgnn_oracle as O
 
 pytestmark = pytest.mark.gpu
@@ -56,8 +56,7 @@ def test_sample_recent(case):
     ev = rng.integers(0, P["E"], n // 2)                         # half the queries sit exactly on event times
     qn[:n // 2] = P["src"][ev]; qt[:n // 2] = P["ts"][ev]
     nbr, eid, ts, cnt = ctx.tgnn_sample_recent(graph, dev(qn), dev(qt))
-    adj = O.build_adjacency(P["src"], P["dst"], P["ts"], d.n_nodes)
-    o_nbr, o_eid, o_ts, o_cnt = O.sample_recent(adj, qn, qt, d.k)
+    o_nbr, o_eid, o_ts, o_cnt = O.sample_recent(P["src"], P["dst"], P["ts"], qn, qt, d.k)     # the scan of the event list
     assert np.array_equal(cnt.cpu().numpy(), o_cnt)
     assert np.array_equal(nbr.cpu().numpy(), o_nbr) and np.array_equal(eid.cpu().numpy(), o_eid)
     assert np.array_equal(ts.cpu().numpy(), o_ts)
@@ -170,9 +169,14 @@ def test_temporal_attention_fwd_bwd(shape):
     assert rel_err(d_root.cpu().numpy(), dxr[:, :d_m]) <= TOL
     assert rel_err(d_nbr.cpu().numpy().reshape(R, k, d_m), dxn[:, :, :d_m] * mask[..., None]) <= TOL
     gg = grads.numpy()
-    gmax = max(np.abs(v).max() for v in g.values())
-    for n in ("wq", "bq", "wk", "bk", "wv", "bv", "wo", "bo", "time_w", "time_b"):
-        assert rel_err(gg[n], g[n], floor=1e-3 * gmax) <= TOL, n
+    errs = {}
+    for n in ("wq", "bq", "wk", "bk", "wv", "bv", "wo", "bo", "time_w", "time_b"):      # each against its own largest entry
+        # (the four tensors fed only by the score gradients: plus 16 fp32 roundings of their summed summand
+        #  magnitudes -- the key bias is exactly zero in exact arithmetic; see gpu_common.compare_step)
+        floor = 16 * FP32_EPS * float(cache["abs_terms"][n].max()) if n in cache["abs_terms"] else 0.0
+        errs[n] = float(np.abs(gg[n] - g[n]).max() / (np.abs(g[n]).max() + floor / TOL))
+    print(shape, {n: "%.2e" % v for n, v in errs.items()})
+    assert all(v <= TOL for v in errs.values()), errs
     for n in ("gru_wih", "dec_ws", "dec_w2"):
         assert not gg[n].any()
     # a second backward call adds to the gradients (+= semantics)

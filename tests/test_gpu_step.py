@@ -18,7 +18,7 @@ def run_sequence(P, n_steps, lr=0.0, check_at=(0,), dt_source=0, first=0, own_st
         b = batch_np(P, lo, hi)
         want = s in check_at or s == n_steps - 1
         g = G.step([b], lr=lr, want=want)
-        o = Or.step([b], lr=lr)
+        o = Or.step([b], lr=lr, gpu=g)
         if want:
             errs[s] = compare_step(g, o, label=f"step {s}")
     e = compare_state(G.state_np(), Or.states[0], label="state")
@@ -71,6 +71,18 @@ def test_odd_shapes(shape):
     run_sequence(P, min(n, 8), check_at=(0, 3))
 
 
+def test_self_loop_events_and_negative_equal_to_the_true_destination():
+    """A quarter of the events have destination = source (the node is listed twice in its own neighbour list, and
+    of the two occurrences in the event the destination one wins the write-back, its mail holding its own s' twice);
+    a quarter of the negative destinations are the true destination."""
+    P = custom_problem(n_nodes=40, E=1200, d_mem=32, d_time=16, d_edge=8, d_static=4, n_heads=2, k=6, batch=100,
+                       self_loops=0.25, neg_is_dst=0.25)
+    assert (P["src"] == P["dst"]).sum() > 100 and (P["neg"] == P["dst"]).sum() > 100
+    errs, _ = run_sequence(P, 12, lr=0.02, check_at=(0, 1, 5, 11))
+    # 16 events per workgroup in the root chain as well
+    run_sequence(P, 6, lr=0.0, check_at=(0, 5), flags=8)
+
+
 def test_ragged_last_batch_and_single_event():
     P = custom_problem(n_nodes=30, E=205, d_mem=16, d_time=8, d_edge=4, d_static=0, n_heads=2, k=5, batch=50)
     run_sequence(P, 5, check_at=(0, 4))      # last batch has 5 events
@@ -92,7 +104,7 @@ def test_sampled_stage_timing_and_row_count():
     for s in range(9):                        # timed: steps 0, 4, 8
         b = batch_np(P, s * d.batch, (s + 1) * d.batch)
         g = G.step([b], lr=0.05, want=True)
-        o = Or.step([b], lr=0.05)
+        o = Or.step([b], lr=0.05, gpu=g)
         compare_step(g, o, label=f"step {s}")
         out = o["outs"][0]
         roots = np.concatenate([b["src"], b["dst"], b["neg"]])

@@ -20,7 +20,7 @@ def tiny_problem(seed=0, n=40, E=400, d_m=6, d_t=4, d_e=3, d_s=2, H=2, k=3, B=12
     p = O.to_f64(synth.gen_params(d, seed=seed, random_phase=True))
     p["time_w"] = rng.uniform(0.05, 1.0, d_t)
     neg = rng.integers(0, n, E)
-    adj = O.build_adjacency(src, dst, ts, n)
+    adj = O.event_list(src, dst, ts)          # neighbours by the plain scan of the event list
     return dict(src=src, dst=dst, ts=ts, efeat=efeat, static=static, d=d, p=p, neg=neg, adj=adj)
 
 
@@ -153,3 +153,69 @@ def test_sgd_freezes_time_encoding():
     res = O.train_step([st], P["adj"], P["efeat"], P["static"], P["p"], [batch_of(P, 72, 84)], d.k, d.n_heads, lr=0.1)
     assert np.array_equal(P["p"]["time_w"], p0["time_w"]) and np.array_equal(P["p"]["time_b"], p0["time_b"])
     np.testing.assert_allclose(P["p"]["wk"], p0["wk"] - 0.1 * res["grads"]["wk"], rtol=0, atol=1e-15)
+
+
+def _hand_built_step(dt_source=0, mail_ts0=5.0):
+    """Four nodes, two events, a state written out by hand so that every time difference of the step is known:
+         event 0: 1 -> 2 at t = 2          event 1: 0 -> 1 at t = 7 (the batch; negative destination: node 3)
+         node 0: memory updated at 4, mail of time mail_ts0 (default 5)   -> mail difference 1
+         node 1: memory updated at 1, mail of time 6                      -> mail difference 5
+         node 2: memory updated at 2.5, mail of time 6                    -> used memory is as of 6
+       Root 1 (node 1 at t = 7) has one earlier event, event 0, with neighbour 2: key difference 7 - 6 = 1
+       (memory-time reading) or 7 - 2 = 5 (edge-time reading).  Roots 0 and 3 have no earlier event."""
+    d = synth.ModelDims(n_nodes=4, d_mem=2, d_time=3, d_edge=1, d_static=0, n_heads=1, k=2, batch=1)
+    p = O.to_f64(synth.gen_params(d, seed=11))
+    p["time_w"] = np.array([np.pi / 2, np.pi, 0.25]); p["time_b"] = np.array([np.pi / 2, 0.0, 1.0])
+    rng = np.random.default_rng(0)
+    st = O.new_state(4, 2)
+    st["mem"][:] = rng.standard_normal((4, 2)); st["mail"][:] = rng.standard_normal((4, 4))
+    st["mem_ts"][:] = [4.0, 1.0, 2.5, 0.0]; st["mail_ts"][:] = [mail_ts0, 6.0, 6.0, 0.0]
+    st["mail_eid"][:] = [0, 0, 0, -1]
+    g = O.event_list([1, 0], [2, 1], [2.0, 7.0])
+    efeat = np.array([[0.5], [-0.25]], np.float32)
+    bt = dict(src=np.array([0]), dst=np.array([1]), neg=np.array([3]), eid=np.array([1]), t=np.array([7.0]))
+    return O.forward_backward(st, g, efeat, None, p, bt, d.k, d.n_heads, dt_source), d
+
+
+def test_time_encoding_inside_the_step_hand_values():
+    """Eq. 1-2 and 5-6 as the step evaluates them, against values worked out by hand with non-zero phases and
+    time differences whose sign matters: w = (pi/2, pi, 1/4), b = (pi/2, 0, 1)."""
+    fb, d = _hand_built_step()
+    assert fb["nbr"].tolist() == [[-1, -1], [2, -1], [-1, -1]]
+    phi_gru = fb["gru_x"][:, 2 * d.d_mem:2 * d.d_mem + d.d_time]
+    # slot 0 = root node 0: mail time - memory time = 1: cos(pi/2 + pi/2) = -1, cos(pi) = -1, cos(1.25)
+    np.testing.assert_allclose(phi_gru[0], [-1.0, -1.0, 0.3153223623952687], atol=1e-15)
+    # slot 1 = root node 1: difference 5: cos(3 pi) = -1, cos(5 pi) = -1, cos(2.25)
+    np.testing.assert_allclose(phi_gru[1], [-1.0, -1.0, -0.6281736227227391], atol=1e-14)
+    # slot 2 = negative root node 3, no mail: difference taken as 0 (and the cell is not applied)
+    np.testing.assert_allclose(phi_gru[2], [0.0, 1.0, 0.5403023058681398], atol=1e-15)
+    # key of root 1's neighbour: query time 7 - time of the neighbour's memory as used (its mail time 6) = 1
+    phi_key = fb["c_in"][1, 0, d.d_x + d.d_edge:]
+    np.testing.assert_allclose(phi_key, [-1.0, -1.0, 0.3153223623952687], atol=1e-15)
+    assert fb["c_in"][1, 0, d.d_x] == 0.5                                  # its edge feature: event 0
+    # the query encodes a time difference of zero: cos(b) = (0, 1, cos 1)
+    np.testing.assert_allclose(fb["q_in"][:, d.d_x:], np.tile([0.0, 1.0, 0.5403023058681398], (3, 1)), atol=1e-15)
+    # edge-time reading: 7 - 2 = 5
+    fb1, _ = _hand_built_step(dt_source=1)
+    np.testing.assert_allclose(fb1["c_in"][1, 0, d.d_x + d.d_edge:], [-1.0, -1.0, -0.6281736227227391], atol=1e-14)
+    # the mail's edge feature sits after the time encoding in the GRU input (Eq. 1-2 order)
+    assert fb["gru_x"][0, -1] == 0.5
+
+
+def test_half_period_flips_the_sign_through_the_step():
+    fb_a, d = _hand_built_step(mail_ts0=5.0)      # difference 1
+    fb_b, _ = _hand_built_step(mail_ts0=6.0)      # difference 2: half a period of w = pi, a quarter of w = pi/2
+    c = 2 * d.d_mem
+    assert abs(fb_a["gru_x"][0, c + 1] + fb_b["gru_x"][0, c + 1]) < 1e-15 and abs(fb_a["gru_x"][0, c + 1] + 1.0) < 1e-15
+    np.testing.assert_allclose(fb_b["gru_x"][0, c], np.cos(np.pi + np.pi / 2), atol=1e-15)   # ~ 0: a quarter period on
+    assert np.abs(fb_a["s_new"][0] - fb_b["s_new"][0]).max() > 1e-3     # and the updated memory of node 0 follows
+
+
+def test_time_encoding_derivative_by_finite_differences():
+    w = np.array([0.3, 2.0, 0.0]); b = np.array([0.4, -1.0, 0.7])
+    for delta in (0.0, 1.7, 13.0):
+        h = 1e-6
+        fd_b = (O.time_encode(delta, w, b + h) - O.time_encode(delta, w, b - h)) / (2 * h)
+        np.testing.assert_allclose(O.time_encode_darg(delta, w, b), fd_b, atol=1e-9)
+        fd_w = (O.time_encode(delta, w + h, b) - O.time_encode(delta, w - h, b)) / (2 * h)
+        np.testing.assert_allclose(O.time_encode_darg(delta, w, b) * delta, fd_w, atol=1e-8)
