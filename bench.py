@@ -29,19 +29,22 @@ PEAK_MFMA_F32_TFLOPS = 157.3
 STAGE_NAMES = {2: "roots + sample + distinct-node rows + prologue (pack weights, clear), one launch",
                3: "state gather + time-encode (GRU input) + slot-to-row map",
                4: "GRU input + hidden projections (MFMA, one launch)",
-               7: "GRU gates + slot-sort scan + per-slot attention input {e | Phi} (edge-feature gather), one launch",
-               8: "K/V projection of the slots (MFMA)",
+               6: "GRU gates + slot-sort scan",
                9: "per-node projections K, V, q, merge (MFMA)",
-               10: "softmax attention + slot-sort fill",
+               8: "per-node score vectors U = q W_k^c (MFMA)",
+               10: "attention forward: edge-feature gather, time encoding, scores, softmax, weighted sums (+ slot-sort fill)",
+               7: "attention output = node part + Zp W_v^c^T (MFMA)",
                11: "merge layer (MFMA; only when the root chain does not fit)",
                12: "root chain: merge layer, decoder + loss, their backward down to the attention output (MFMA, one launch)",
                13: "decoder backward (only when the root chain does not fit)",
-               14: "attention backward (softmax)",
-               15: "per-node gradient sums; node projections + GRU gates backward with the keys' time-encoding gradients",
-               16: "all weight gradients (grouped MFMA GEMM)",
+               19: "G = dO W_v^c per root (MFMA)",
+               14: "attention backward: edge-feature gather, time encoding, softmax backward, per-root sums",
+               5: "dq = node part + Zs W_k^c^T (MFMA)",
+               15: "per-node gradient sums; node projections + GRU gates backward",
+               16: "all weight gradients + time-encoding gradients of the keys (grouped MFMA GEMM)",
                17: "time-encoding gradients of the mails (MFMA) + write-back scatter + SGD (one launch)",
                18: "empty event bracket"}
-STAGE_GATHER, STAGE_ASSEMBLE, STAGE_KV, STAGE_WGRAD, STAGE_EMPTY = 3, 7, 8, 16, 18
+STAGE_GATHER, STAGE_ATTN_FWD, STAGE_ATTN_BWD, STAGE_WGRAD, STAGE_EMPTY = 3, 10, 14, 16, 18
 N_STAGES = 20
 
 
@@ -69,26 +72,27 @@ def flops_wgrad(d, R, U):
     return 2.0 * macs
 
 
-def flops_kv(d, R):
-    """Executed flops of the per-slot K/V projection: [R k, d_e + d_t] x [d_e + d_t, 2 d_o]."""
-    return 2.0 * R * d.k * (d.d_edge + d.d_time) * 2 * d.d_out
-
-
 def flops_executed_model(d, B, U):
     """What the library's kernels execute for a step with U distinct (replica, node) rows among its slots: UPDT and
-    the node part of every projection once per distinct row, the {e | Phi} part per neighbour slot, everything else
-    per root.  Forward and backward listed separately (no 3x rule)."""
-    R = 3 * B; RK = R * d.k; dO = d.d_out; dc = d.d_edge + d.d_time
+    the node part of every projection once per distinct row; the slots' own inputs {e | Phi} only meet per-root
+    vectors (two dot products and two weighted sums of width H (d_e + d_t) per slot and direction); four products of
+    width H (d_e + d_t) per root or node row tie those vectors to the weights; everything else per root.  Forward and
+    backward listed separately (no 3x rule).  The products over H dcp columns are counted dense (as executed: the
+    block-diagonal weights carry their zero blocks)."""
+    R = 3 * B; RK = R * d.k; dO = d.d_out; dc = d.d_edge + d.d_time; Hdc = d.n_heads * dc
     fwd = (U * 2 * (d.d_in + d.d_mem) * 3 * d.d_mem          # GRU projections
            + U * 2 * d.d_x * 4 * dO                          # node part of K, V, q, merge
-           + flops_kv(d, R)                                  # per-slot K/V
-           + RK * 4 * dO                                     # scores + weighted sum
+           + U * 2 * dO * Hdc                                # U = q W_k^c
+           + RK * (2 * Hdc + 2 * dO) * 2                     # scores (u . c, q . Pk) and weighted sums (Zp, node part)
+           + R * 2 * Hdc * dO                                # attention output from Zp
            + R * 2 * dO * dO + R * 2 * dO * 2 * dO           # merge (attention-output columns), decoder hidden layer
            + 2 * B * 2 * dO)                                 # logits
     bwd_data = (R * 2 * 2 * dO * dO + R * 2 * dO * dO        # dz, d(attention output)
-                + RK * 8 * dO                                # softmax backward: dP, dV, dq, dK
-                + 2 * RK * 2 * dc * d.n_heads                # per-root sums of {e | Phi} rows (two weightings per head)
-                + RK * 2 * 2 * dO * d.d_time                 # dKV onto the keys' time encoding
+                + R * 2 * dO * Hdc                           # G = dO W_v^c
+                + RK * (2 * Hdc + 2 * dO) * 2                # dp (g . c, dO . Pv) and the sums Zs, dq (node part)
+                + RK * 4 * d.n_heads * d.d_time              # gradient reaching the keys' time encoding
+                + RK * 4 * dO                                # gradients of the neighbour rows' K and V, formed where summed
+                + R * 2 * Hdc * dO                           # dq from Zs
                 + U * 2 * 4 * dO * d.d_mem                   # node projections backward
                 + U * 2 * 3 * d.d_mem * d.d_time)            # GRU input gradient onto the mails' time encoding
     return float(fwd + bwd_data + flops_wgrad(d, R, U))
@@ -104,18 +108,20 @@ def bytes_per_slot_model(d, B):
     return float(gather + sampler + wb)
 
 
-def assemble_bytes(d, R):
-    """Per-slot attention input launch: per neighbour slot read the edge-feature row, its index and the
-    neighbour's update time, and write the {e | Phi} row and the time difference."""
-    return R * d.k * (4 * d.d_edge + 4 * (d.d_edge + d.d_time) + 4 + 8 + 8)
+def attn_fwd_bytes(d, R, slots):
+    """Attention forward launch, algorithmic bytes: per valid neighbour slot the edge-feature row, its index, the node
+    row index, the neighbour's update time and the node's K and V rows; per root its q and U rows in, its softmax
+    weights, node part of the output, per-head sums Zp and time differences out."""
+    Hdcp = d.n_heads * ((d.d_edge + d.d_time + 3) // 4 * 4)
+    per_slot = 4 * d.d_edge + 4 + 4 + 8 + 8 * d.d_out
+    per_root = 4 * d.d_out + 4 * Hdcp + 4 + (4 * d.n_heads * d.k + 4 * d.d_out + 4 * Hdcp + 8 * d.k)
+    return slots * per_slot + R * per_root
 
 
-def gates_bytes(d, U):
-    """GRU gates, passenger of the same launch: per distinct node row read the two projections (6 d_m floats) and
-    the stored memory, write the four gate values, the node row {s' | static} and clear the row's gradient
-    accumulator (pitch 2 * pad32(2 d_o) floats)."""
-    pad32 = lambda x: (x + 31) // 32 * 32
-    return U * 4 * (12 * d.d_mem + 2 * d.d_static + 2 * pad32(2 * d.d_out))
+def attn_edge_bytes(d, slots):
+    """Of those, the bytes that are a true HBM gather: the edge-feature rows (the table does not fit any cache on
+    the large configuration; the node rows and per-root rows were written by the launches just before)."""
+    return slots * 4 * d.d_edge
 
 
 def state_gather_bytes(d, U):
@@ -262,7 +268,7 @@ def run_config(tgnn, torch, P, args, detail):
     torch.cuda.synchronize()
     stream = torch.cuda.Stream()
     with torch.cuda.stream(stream):
-        roof_mask = 0 if args.no_stage_events else ((1 << STAGE_ASSEMBLE) | (1 << STAGE_KV) | (1 << STAGE_WGRAD)
+        roof_mask = 0 if args.no_stage_events else ((1 << STAGE_ATTN_FWD) | (1 << STAGE_ATTN_BWD) | (1 << STAGE_WGRAD)
                                                     | (1 << STAGE_GATHER) | (1 << STAGE_EMPTY))
         every = max(1, args.event_every)
         ctx.tgnn_profile_enable(roof_mask)
@@ -279,7 +285,7 @@ def run_config(tgnn, torch, P, args, detail):
         ev = sum(per_step)
         timed = per_step[::every] if roof_mask else []     # the library times every `every`-th step, from the first on
         final_loss = float(last_loss[0][0][last_loss[0][1]].item())
-        live = {st: ctx.tgnn_profile_read(st) for st in (STAGE_GATHER, STAGE_ASSEMBLE, STAGE_KV, STAGE_WGRAD, STAGE_EMPTY)}
+        live = {st: ctx.tgnn_profile_read(st) for st in (STAGE_GATHER, STAGE_ATTN_FWD, STAGE_ATTN_BWD, STAGE_WGRAD, STAGE_EMPTY)}
         ctx.tgnn_profile_enable(0)
         ctx.tgnn_profile_every(1)
 
@@ -288,10 +294,15 @@ def run_config(tgnn, torch, P, args, detail):
         n_prof = min(args.steps, 32)
         ctx.tgnn_profile_enable((1 << N_STAGES) - 1)
         rows_step = torch.zeros(n_prof, dtype=torch.int32, device="cuda")
+        cnt_buf = torch.zeros(3 * d.batch * nrep, dtype=torch.int32, device="cuda")
         ev_prof = 0
+        slots_prof = 0.0
         for i, s in enumerate(range(args.warmup + args.steps, args.warmup + args.steps + n_prof)):
-            ev_prof += run_step(s)
+            n_ev = run_step(s)
+            ev_prof += n_ev
             ctx.tgnn_debug_read(8, rows_step[i:i + 1])
+            ctx.tgnn_debug_read(3, cnt_buf[:3 * n_ev])          # sampled neighbours per root
+            slots_prof += float(cnt_buf[:3 * n_ev].sum().item())
         torch.cuda.synchronize()
         stages = {}
         for i, nm in STAGE_NAMES.items():
@@ -307,10 +318,11 @@ def run_config(tgnn, torch, P, args, detail):
 
     ev_step = ev / args.steps
     R_timed = 3 * (sum(timed) / len(timed) if timed else ev_step)      # roots per event-bracketed launch
-    kv_us, asm_us, wg_us, ga_us, empty_us = (us(s) for s in (STAGE_KV, STAGE_ASSEMBLE, STAGE_WGRAD, STAGE_GATHER, STAGE_EMPTY))
-    kv_tf = flops_kv(d, R_timed) / (kv_us * 1e-6) / 1e12 if kv_us else None
+    slots_per_root = slots_prof / (3 * ev_prof)                        # valid neighbour slots per root (measured)
+    af_us, ab_us, wg_us, ga_us, empty_us = (us(s) for s in (STAGE_ATTN_FWD, STAGE_ATTN_BWD, STAGE_WGRAD, STAGE_GATHER, STAGE_EMPTY))
     wg_tf = flops_wgrad(d, R_timed, rows_avg) / (wg_us * 1e-6) / 1e12 if wg_us else None
-    asm_gbs = (assemble_bytes(d, R_timed) + gates_bytes(d, rows_avg)) / (asm_us * 1e-6) / 1e9 if asm_us else None
+    af_bytes = attn_fwd_bytes(d, R_timed, R_timed * slots_per_root)
+    af_gbs = af_bytes / (af_us * 1e-6) / 1e9 if af_us else None
     ga_gbs = state_gather_bytes(d, rows_avg) / (ga_us * 1e-6) / 1e9 if ga_us else None
     ms_step = dt / args.steps * 1e3
     f_slot = flops_per_slot_model(d, ev_step); f_exec = flops_executed_model(d, ev_step, rows_avg)
@@ -321,11 +333,13 @@ def run_config(tgnn, torch, P, args, detail):
                     f"1 negative/event, SGD lr {args.lr}; edge features {P['efeat_where']}",
         "events_per_s": ev / dt, "ms_per_step": ms_step, "events_per_step": ev_step, "steps": args.steps,
         "final_loss": final_loss, "distinct_node_rows_per_step": rows_avg,
-        "kv_gemm": {"tflops": kv_tf, "frac_of_mfma_peak": kv_tf / PEAK_MFMA_F32_TFLOPS if kv_tf else None, "avg_launch_us": kv_us},
         "weight_gradients": {"tflops": wg_tf, "frac_of_mfma_peak": wg_tf / PEAK_MFMA_F32_TFLOPS if wg_tf else None,
                              "avg_launch_us": wg_us},
-        "edge_feature_gather": {"gbs": asm_gbs, "frac_of_hbm_peak": asm_gbs / PEAK_HBM_GBS if asm_gbs else None,
-                                "avg_launch_us": asm_us},
+        "attention_fwd": {"gbs": af_gbs, "frac_of_hbm_peak": af_gbs / PEAK_HBM_GBS if af_gbs else None,
+                          "avg_launch_us": af_us, "bytes_per_launch": af_bytes,
+                          "edge_feature_bytes_per_launch": attn_edge_bytes(d, R_timed * slots_per_root),
+                          "valid_slots_per_root": slots_per_root},
+        "attention_bwd": {"avg_launch_us": ab_us},
         "state_gather": {"gbs": ga_gbs, "frac_of_hbm_peak": ga_gbs / PEAK_HBM_GBS if ga_gbs else None, "avg_launch_us": ga_us},
         "empty_event_bracket_us": empty_us,
         "step_model": {
@@ -335,8 +349,9 @@ def run_config(tgnn, torch, P, args, detail):
             "step_frac_of_hbm_peak_per_slot_bytes": b_slot / (ms_step * 1e-3) / 1e9 / PEAK_HBM_GBS,
             "note": "per_slot: UPDT and unsplit projections for every slot, as the method states it (3 x forward); "
                     "executed: what the kernels run after the exact shortcuts (UPDT and node projections once per "
-                    "distinct node, weight gradients of the slot projections over the roots); the per-slot count is "
-                    "never achieved work, a fraction above 1 on it only says how much the shortcuts removed"},
+                    "distinct node; the slots' own inputs meet per-root vectors instead of being projected; weight "
+                    "gradients of the slot projections over the roots); the per-slot count is never achieved work, a "
+                    "fraction above 1 on it only says how much the shortcuts removed"},
     }
     if detail:
         res["stages_us"] = stages
@@ -425,15 +440,10 @@ def main():
     configs[head] = {k: v for k, v in res.items() if k not in ("stages_us", "stages_us_note")}
 
     d = P["d"]
-    wg, kv = res["weight_gradients"], res["kv_gemm"]
-    # the dominant kernel: the longer of the two MFMA launches of the step
-    if (wg["avg_launch_us"] or 0) >= (kv["avg_launch_us"] or 0):
-        dom = dict(kernel="gemm_tn_kernel: all weight gradients of the step in one grouped launch (fp32 MFMA 16x16x4), "
-                          "useful flops of its eight products", key="weight_gradients", tag="gemm_tn")
-    else:
-        dom = dict(kernel="gemm_nt_kernel: K/V projection of the {e | Phi} rows of all neighbour slots (fp32 MFMA 16x16x4)",
-                   key="kv_gemm", tag="kv_projection")
-    dk = res[dom["key"]]
+    wg = res["weight_gradients"]
+    dom = dict(kernel="gemm_tn_kernel: all weight gradients of the step in one grouped launch (fp32 MFMA 16x16x4), the "
+                      "longest launch of the step; useful flops of its nine products", tag="gemm_tn")
+    dk = wg
     out = {
         "metric": "training events/sec (fwd+bwd+memory update) at 1 GPU",
         "value": res["events_per_s"], "unit": "events/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -445,18 +455,18 @@ def main():
                      "unit": "TFLOP/s", "frac": dk["frac_of_mfma_peak"], "avg_launch_us": dk["avg_launch_us"],
                      "empty_event_bracket_us": res["empty_event_bracket_us"],
                      "traffic": recorded_traffic(head, dom["tag"])},
-        "gather": {"bound": "hbm", "kernel": "assemble_ce_kernel: edge-feature row gather + time encoding into the per-slot "
-                                             "key/value inputs; its first blocks carry the GRU gates of the distinct node "
-                                             "rows (bytes of both counted)",
-                   "achieved": res["edge_feature_gather"]["gbs"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                   "frac": res["edge_feature_gather"]["frac_of_hbm_peak"],
-                   "avg_launch_us": res["edge_feature_gather"]["avg_launch_us"],
-                   "traffic": recorded_traffic(head, "assemble_ce")},
+        "gather": {"bound": "hbm", "kernel": "fattn_fwd_fast_kernel: per root, gathers the edge-feature rows and node rows of its "
+                                             "k neighbour slots, forms the time encoding, scores, softmax and weighted sums "
+                                             "in registers",
+                   "achieved": res["attention_fwd"]["gbs"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                   "frac": res["attention_fwd"]["frac_of_hbm_peak"],
+                   "avg_launch_us": res["attention_fwd"]["avg_launch_us"],
+                   "traffic": recorded_traffic(head, "fattn_fwd")},
         "state_gather": dict(res["state_gather"], bound="hbm", peak=PEAK_HBM_GBS,
                              kernel="gather_kernel: memory, mail and the mail's edge-feature row of every distinct node "
                                     "into the GRU input"),
         "writeback": res.get("writeback_standalone"),
-        "kv_gemm": kv, "weight_gradients": wg,
+        "weight_gradients": wg,
         "step_model": res["step_model"],
         "configs": configs,
         "stages_us": res.get("stages_us"), "stages_us_note": res.get("stages_us_note"),

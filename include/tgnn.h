@@ -49,6 +49,8 @@ extern "C" {
                                        pass in one launch) takes 16 events per workgroup whatever the size of the
                                        step; by default steps of at most 1,280 events take 5 per workgroup.  Same
                                        results up to the order of the sums over workgroups; for tests. */
+#define TGNN_FLAG_GENERIC_ATTN 16    /* the attention kernels take their generic code path (any k, widths and number of
+                                       heads) also where the shape fits the register-resident one; for tests */
 #define TGNN_FLAG_SIDE_STREAM 2     /* tgnn_train_step starts the bulk of the weight-gradient GEMMs (decoder, merge
                                        layer, {e | Phi} columns of W_k / W_v) on a second stream of the context as
                                        soon as their operands exist, beside the remaining chain of small backward
@@ -169,7 +171,8 @@ int32_t tgnn_gru_update(tgnn_ctx* ctx, const tgnn_params* p, int32_t n_slots, co
  * e_nbr [n_roots*k, d_e]; dt_nbr [n_roots*k] double (time difference of Eq. 5-6); cnt [n_roots] valid
  * neighbours per root (the first cnt of each k).  q = W_q{x_v || Phi(0)} + b_q; K, V from
  * {x_w || e_vw || Phi(dt)}; per head softmax(q K^T / sqrt(cnt)) V; out_z [n_roots, d_o] =
- * ReLU(W_o{h_v || x_v} + b_o).  Activations are kept in the context for tgnn_temporal_attn_bwd. */
+ * ReLU(W_o{h_v || x_v} + b_o).  Activations are kept in the context for tgnn_temporal_attn_bwd, which also reads
+ * e_nbr again: it must stay unchanged until then. */
 int32_t tgnn_temporal_attn_fwd(tgnn_ctx* ctx, const tgnn_params* p, int32_t n_roots, const float* x_root,
                                const float* x_nbr, const float* e_nbr, const double* dt_nbr,
                                const int32_t* cnt, float* out_z, void* stream);
@@ -226,22 +229,22 @@ int32_t tgnn_train_steps(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, con
 /* Sets every tensor of `g` (a gradient set laid out like the parameters) to zero with one kernel. */
 int32_t tgnn_zero_params(tgnn_ctx* ctx, tgnn_params* g, void* stream);
 
-/* Stage timing with HIP events on the call's own stream.  Stages of tgnn_train_step:
- *  0 (unused)   1 (unused)   2 first launch: roots + sample + distinct-node rows, and the prologue (pack weights, clear
- *  loss/grads, batch descriptors)
- *  3 gather + time-encode (GRU input; with the slot -> row map)   4 GRU input and hidden projections (MFMA,
- *  one launch)   5 (unused)   6 (unused)
- *  7 GRU gates (with the scan of the slot sort) + per-slot attention input {e | Phi}, one launch   8 K/V projection of the slots (MFMA)   9 per-node projections (MFMA)
- *  10 softmax attention (with the fill pass of the slot sort)
- *  12 root chain: merge layer, decoder + loss and their backward pass down to the gradient of the attention
- *  output, one launch (d_mem a multiple of 4 and <= 128; otherwise 11 merge layer, 12 decoder forward + loss,
- *  13 decoder backward, and the attention-output gradient GEMM in 14)
- *  14 attention backward (softmax)
+/* Stage timing with HIP events on the call's own stream.  Stages of tgnn_train_step (launches, in step order):
+ *  2 first launch: roots + sample + distinct-node rows, and the prologue (pack weights, clear loss/grads, batch
+ *    descriptors)   3 state gather + time-encode (GRU input; with the slot -> row map)   4 GRU input and hidden
+ *    projections (MFMA, one launch)   6 GRU gates (with the scan of the slot sort)
+ *  9 per-node projections K, V, q, merge (MFMA)   8 per-node score vectors U = q W_k^c (MFMA)
+ *  10 attention forward: gathers the slots' edge features, time encoding, scores, softmax, weighted sums (with the fill
+ *    pass of the slot sort)   7 attention output = node part + Zp (W_v^c)^T (MFMA)
+ *  12 root chain: merge layer, decoder + loss and their backward pass down to the gradient of the attention output,
+ *    one launch (d_mem a multiple of 4 and <= 128; otherwise 11 merge layer, 12 decoder forward + loss, 13 decoder
+ *    backward, and the attention-output gradient GEMM)
+ *  19 G = dO W_v^c per root (MFMA)   14 attention backward   5 dq = node part + Zs (W_k^c)^T (MFMA)
  *  15 per-node gradient sums (with the gradients through the query's Phi(0)) + node projections backward with GRU
- *  gates backward, and the product onto the keys' time encoding with its reduction (one launch)
- *  16 all weight gradients (one grouped MFMA GEMM)   17 time-encoding gradient of the mails (GEMM with the
- *  reduction in its epilogue) + write-back scatter + SGD, one launch   18 nothing (two event records back to back: the
- *  cost of a bracket by itself)   19 (unused)
+ *    gates backward
+ *  16 all weight gradients and the time-encoding gradients of the keys (one grouped MFMA GEMM)   17 time-encoding
+ *    gradient of the mails (GEMM with the reduction in its epilogue) + write-back scatter + SGD, one launch
+ *  18 nothing (two event records back to back: the cost of a bracket by itself)   0, 1 unused
  * tgnn_profile_enable: time the stages whose bit is set in `stage_mask` in every following tgnn_train_step
  * (0 = off); each timed stage costs two event records per step.  At most 4096 steps are kept per stage;
  * enabling resets the record.  tgnn_profile_read: synchronises the recorded events and returns the number

@@ -1,447 +1,691 @@
-// Softmax attention over the k sampled neighbours of one root (Eq. 7), forward and backward.
-// One wavefront per root: the k key (or value) rows are staged in LDS, the H*k scores are computed by
-// H*k lanes, the per-head softmax runs over at most 32 values, and the weighted sums are taken with one
-// lane per output element.  The projections themselves (Eq. 4-6) are MFMA GEMMs.
+// Temporal attention over the k sampled neighbours of one root (Eq. 4-7), forward and backward, without ever
+// forming a key or value row.
+//
+// A neighbour slot's key is K_j = Pk[w_j] + W_k^c c_j with c_j = {e_vw | Phi(dt_j)} the slot's own input and
+// Pk[w_j] the projection of the neighbour node's row {s' | static} (taken once per distinct node by an MFMA
+// GEMM).  A head's score is therefore
+//     q_h . K_jh = q_h . Pk_h[w_j] + u_h . c_j            with u_h = (W_k^c)_h^T q_h   (per node row: U, one GEMM)
+// and its output
+//     sum_j p_jh V_jh = sum_j p_jh Pv_h[w_j] + (W_v^c)_h zp_h     with zp_h = sum_j p_jh c_j   (Zp; one GEMM over roots)
+// so the per-slot work is two short dot products and two weighted sums of c_j, done here on the vector ALUs, one
+// wavefront per root, with c_j put together in registers: the edge-feature row is gathered straight from the
+// table and the time encoding is evaluated in place.  Nothing of size (slots x width) goes to memory.
+// The backward pass has the same shape: with g_h = (W_v^c)_h^T dO_h (G, one GEMM over roots)
+//     dp_jh = dO_h . Pv_h[w_j] + g_h . c_j,   ds_jh = p_jh (dp_jh - sum_j p_jh dp_jh) / sqrt(|N_v|)
+//     dq_h = sum_j ds_jh Pk_h[w_j] + (W_k^c)_h zs_h            with zs_h = sum_j ds_jh c_j   (Zs; one GEMM over roots)
+// the weight gradients of W_k^c, W_v^c are products over roots of q, dO with Zs, Zp, the gradient reaching the key's
+// time encoding is d Phi_j = sum_h ds_jh u_h + p_jh g_h (time columns), reduced per root against -sin(.) here (Y)
+// and over the roots by the weight-gradient launch, and the gradients of the neighbour rows' projections are
+// dK_j = ds_j q, dV_j = p_j dO, formed where they are summed per node row.
 #include "tgnn_internal.h"
+#include "device_math.h"
 #include "unique_device.h"
 
 namespace tgnn {
 
-struct AttnShape {
-  int R, k, H, dO, dh, ldq, ldkv, ldo;
+// LDS floats per wavefront: softmax weights and score gradients
+__host__ __device__ inline int fattn_lds_floats(int k, int H) { return 2 * H * k; }
+
+__device__ __forceinline__ float wave_sum(float x) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o);
+  return x;
+}
+
+__device__ __forceinline__ void wave_lds_sync() {
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0): this wavefront's LDS writes are visible to all its lanes
+  __builtin_amdgcn_wave_barrier();
+}
+
+// slot (r, j): edge-feature row index, node row, time difference of Eq. 5-6
+__device__ __forceinline__ void slot_ids(const FusedAttn& a, int r, int j, int c, int& e, int& row, double& dt,
+                                         bool forward) {
+  e = -1; row = 0; dt = 0.0;
+  const int s = r * a.k + j;
+  if (j < c) {
+    e = a.neid != nullptr ? a.neid[s] : s;
+    row = a.slot_row != nullptr ? a.slot_row[a.R + s] : a.R + s;
+    if (!forward) dt = a.dtk[s];
+    else if (a.dt_in != nullptr) dt = a.dt_in[s];
+    else if (a.dt_source != 0) dt = a.root_t[r] - a.nts[s];
+    else dt = a.root_t[r] - a.tau[row];
+  }
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// Fast path: k <= KR neighbours, d_e <= 64 NE and d_t <= 64 NT columns, d_o <= 128, at most two heads.  A lane
+// owns edge-feature columns lane + 64 m and time columns lane + 64 m of every slot; everything a root needs is
+// asked for in one burst after the index loads (a wavefront has few others on its SIMD to hide behind).
+// ---------------------------------------------------------------------------------------------------------
+constexpr int FA_KR = 10, FA_NE = 3, FA_NT = 2, FA_HM = 2, FA_E = 2;
+
+struct SlotRegs {
+  float ce[FA_KR][FA_NE];   // edge-feature columns
+  float ct[FA_KR][FA_NT];   // time-encoding columns (cos)
+  float pk[FA_KR][FA_E];    // node part of the key
+  float pv[FA_KR][FA_E];    // node part of the value
 };
 
-constexpr int ROWS_IN_FLIGHT = 10;  // neighbour rows whose loads are issued together (k = 10: all of them)
-// MAX_E (template parameter of both kernels): columns per lane, lane + 64 u for u < MAX_E; 2 for d_o <= 128, else 4
-// (d_o <= 256)
+template <bool BWD>
+__device__ __forceinline__ void fast_load_slots(const FusedAttn& a, int lane, int c, const int (&e_j)[FA_KR],
+                                                const int (&row_j)[FA_KR], const double (&dt_j)[FA_KR], SlotRegs& s,
+                                                float (&st)[FA_KR][FA_NT]) {
+#pragma unroll
+  for (int j = 0; j < FA_KR; ++j) {
+    const bool on = j < c;
+    const float* erow = a.efeat + (size_t)(on ? e_j[j] : 0) * a.de;
+#pragma unroll
+    for (int m = 0; m < FA_NE; ++m) {
+      const int col = lane + 64 * m;
+      s.ce[j][m] = (on && col < a.de) ? erow[col] : 0.f;
+    }
+    const float* prow = a.P + (size_t)(on ? row_j[j] : 0) * a.ldp;
+#pragma unroll
+    for (int u = 0; u < FA_E; ++u) {
+      const int e = lane + 64 * u;
+      s.pk[j][u] = (on && e < a.dO) ? prow[e] : 0.f;
+      s.pv[j][u] = (on && e < a.dO) ? prow[a.dO + e] : 0.f;
+    }
+  }
+  // time encoding of every slot, evaluated in place (Eq. 5-6); the backward pass also needs the sine
+#pragma unroll
+  for (int m = 0; m < FA_NT; ++m) {
+    const int tc = lane + 64 * m;
+    const bool live = tc < a.dt;
+    const double w = live ? (double)a.time_w[tc] : 0.0, b = live ? (double)a.time_b[tc] : 0.0;
+#pragma unroll
+    for (int j = 0; j < FA_KR; ++j) {
+      float sn = 0.f, cs = 0.f;
+      if (live && j < c) sincos_reduced(fma(w, dt_j[j], b), sn, cs);
+      s.ct[j][m] = cs;
+      if (BWD) st[j][m] = sn;
+    }
+  }
+}
 
-// LDS floats per wave
-__host__ __device__ inline int attn_lds_floats(int k, int H, int dO) { return dO + k * (dO + 1) + 2 * H * k; }
+// the per-head rows u_h (or g_h): edge-feature and time columns of head h's block of a row of pitch ldz
+struct HeadRow {
+  float e[FA_HM][FA_NE], t[FA_HM][FA_NT];
+};
+__device__ __forceinline__ void load_head_row(const FusedAttn& a, const float* row, int lane, HeadRow& h) {
+#pragma unroll
+  for (int hh = 0; hh < FA_HM; ++hh) {
+    const float* blk = row + hh * a.dcp;
+#pragma unroll
+    for (int m = 0; m < FA_NE; ++m) {
+      const int col = lane + 64 * m;
+      h.e[hh][m] = (hh < a.H && col < a.de) ? blk[col] : 0.f;
+    }
+#pragma unroll
+    for (int m = 0; m < FA_NT; ++m) {
+      const int tc = lane + 64 * m;
+      h.t[hh][m] = (hh < a.H && tc < a.dt) ? blk[a.de + tc] : 0.f;
+    }
+  }
+}
 
-// A wavefront has few others on its SIMD to hide behind, so every dependent global load costs a full memory
-// latency.  Both kernels therefore issue everything they will need of the first ROWS_IN_FLIGHT neighbours
-// (with k = 10 that is everything) as one burst right after the two index loads: the query (or dO) row, the
-// key rows and the value rows; rows beyond the first batch are fetched batch by batch where they are used.
-template <int MAX_E>
-__global__ __launch_bounds__(256) void attn_fwd_kernel(AttnShape sh, const float* __restrict__ q,
-                                                       const int32_t* __restrict__ slot_row,
-                                                       const float* __restrict__ KV,
-                                                       const int32_t* __restrict__ cnt, float* __restrict__ prob,
-                                                       float* __restrict__ Omat, SortArgs fill) {
+// store a root's per-head sums (Zp or Zs): head h's block holds d_e + d_t values, padded with zeros to dcp
+__device__ __forceinline__ void store_head_row(const FusedAttn& a, float* row, int lane, const HeadRow& h) {
+  const int pad = a.dcp - a.de - a.dt;
+#pragma unroll
+  for (int hh = 0; hh < FA_HM; ++hh) {
+    if (hh >= a.H) break;
+    float* blk = row + hh * a.dcp;
+#pragma unroll
+    for (int m = 0; m < FA_NE; ++m) {
+      const int col = lane + 64 * m;
+      if (col < a.de) blk[col] = h.e[hh][m];
+    }
+#pragma unroll
+    for (int m = 0; m < FA_NT; ++m) {
+      const int tc = lane + 64 * m;
+      if (tc < a.dt + pad) blk[a.de + tc] = tc < a.dt ? h.t[hh][m] : 0.f;
+    }
+  }
+}
+
+__device__ __forceinline__ void zero_head_rows(const FusedAttn& a, float* row, int lane) {
+  for (int i = lane; i < a.H * a.dcp; i += 64) row[i] = 0.f;
+}
+
+// per-head softmax over the c valid scores in sa[0 .. HK): weights to sa[HK ..) and to prob
+__device__ __forceinline__ void softmax_heads(float* sa, int HK, int k, int c, int lane, float* pr) {
+  for (int p = lane; p < HK; p += 64) {
+    const int h = p / k, j = p - h * k;
+    float v = 0.f;
+    if (j < c) {
+      float mx = -INFINITY;
+      for (int jj = 0; jj < c; ++jj) mx = fmaxf(mx, sa[h * k + jj]);
+      float den = 0.f;
+      for (int jj = 0; jj < c; ++jj) den += expf(sa[h * k + jj] - mx);
+      v = expf(sa[p] - mx) / den;
+    }
+    sa[HK + p] = v;
+    pr[p] = v;
+  }
+}
+
+__global__ __launch_bounds__(256) void fattn_fwd_fast_kernel(FusedAttn a) {
   extern __shared__ float lds[];
   int block = blockIdx.x;
-  if (fill.ucnt != nullptr) {   // the first blocks are passengers: the fill pass of the slot sort
-    const int fill_blocks = (fill.S + 255) / 256;
+  if (a.fill.ucnt != nullptr) {   // the first blocks are passengers: the fill pass of the slot sort
+    const int fill_blocks = (a.fill.S + 255) / 256;
     if (block < fill_blocks) {
-      uniq_fill_block(fill, block);
+      uniq_fill_block(a.fill, block);
       return;
     }
     block -= fill_blocks;
   }
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int r = block * 4 + wave;
-  if (r >= sh.R) return;
-  float* sq = lds + (size_t)wave * attn_lds_floats(sh.k, sh.H, sh.dO);
-  float* sK = sq + sh.dO;
-  float* sa = sK + sh.k * (sh.dO + 1);
-  const int c = cnt[r];
-  const size_t qrow = slot_row != nullptr ? (size_t)slot_row[r] : (size_t)r;   // q is stored per distinct node
-  const int HK = sh.H * sh.k;
-  float* pr = prob + (size_t)r * HK;
-  float* out = Omat + (size_t)r * sh.ldo;
+  if (r >= a.R) return;
+  const int HK = a.H * a.k;
+  float* sa = lds + (size_t)wave * fattn_lds_floats(a.k, a.H);   // [0, HK): scores, [HK, 2 HK): softmax weights
+  const int c = a.cnt[r];
+  float* pr = a.prob + (size_t)r * HK;
+  float* out = a.Onode + (size_t)r * a.ldh;
+  int my_e, my_row;
+  double my_dt;
+  slot_ids(a, r, min(lane, a.k - 1), lane < a.k ? c : 0, my_e, my_row, my_dt, true);
+  if (lane < a.k) a.dtk[(size_t)r * a.k + lane] = my_dt;
   if (c == 0) {
     for (int p = lane; p < HK; p += 64) pr[p] = 0.f;
-    for (int e = lane; e < sh.dO; e += 64) out[e] = 0.f;
+    for (int e = lane; e < a.dO; e += 64) out[e] = 0.f;
+    zero_head_rows(a, a.Zp + (size_t)r * a.ldz, lane);
     return;
   }
+  const size_t qrow = a.slot_row != nullptr ? (size_t)a.slot_row[r] : (size_t)r;
   const float scale = 1.0f / sqrtf((float)c);
-  // the burst: q, and the key and value rows of the first batch
-  float qreg[MAX_E], kreg[ROWS_IN_FLIGHT][MAX_E], vreg[ROWS_IN_FLIGHT][MAX_E];
+  int e_j[FA_KR], row_j[FA_KR];
+  double dt_j[FA_KR];
 #pragma unroll
-  for (int u = 0; u < MAX_E; ++u) {
+  for (int j = 0; j < FA_KR; ++j) {
+    // (readlane: one value for the whole wavefront, kept in scalar registers)
+    e_j[j] = __builtin_amdgcn_readlane(my_e, j);
+    row_j[j] = __builtin_amdgcn_readlane(my_row, j);
+    dt_j[j] = __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(my_dt), j),
+                               __builtin_amdgcn_readlane(__double2loint(my_dt), j));
+  }
+  // the burst: the root's query and u rows, then every slot's columns
+  float qreg[FA_E];
+#pragma unroll
+  for (int u = 0; u < FA_E; ++u) {
     const int e = lane + 64 * u;
-    qreg[u] = e < sh.dO ? q[qrow * sh.ldq + e] : 0.f;
+    qreg[u] = e < a.dO ? a.P[qrow * a.ldp + a.off_q + e] : 0.f;
+  }
+  HeadRow ur;
+  load_head_row(a, a.U + qrow * a.ldz, lane, ur);
+  SlotRegs s;
+  float unused[FA_KR][FA_NT];
+  fast_load_slots<false>(a, lane, c, e_j, row_j, dt_j, s, unused);
+  // scores (Eq. 7): per slot and head, this lane's share of q . Pk + u . c, summed over the wavefront
+  float part[FA_KR][FA_HM];
+#pragma unroll
+  for (int j = 0; j < FA_KR; ++j) {
+#pragma unroll
+    for (int hh = 0; hh < FA_HM; ++hh) {
+      float acc = 0.f;
+#pragma unroll
+      for (int m = 0; m < FA_NE; ++m) acc += ur.e[hh][m] * s.ce[j][m];
+#pragma unroll
+      for (int m = 0; m < FA_NT; ++m) acc += ur.t[hh][m] * s.ct[j][m];
+#pragma unroll
+      for (int u = 0; u < FA_E; ++u) {
+        const int e = lane + 64 * u;
+        if (e < a.dO && e / a.dh == hh) acc += qreg[u] * s.pk[j][u];
+      }
+      part[j][hh] = acc;
+    }
   }
 #pragma unroll
-  for (int jj = 0; jj < ROWS_IN_FLIGHT; ++jj) {
-    const float* krow = KV + ((size_t)r * sh.k + min(jj, c - 1)) * sh.ldkv;
+  for (int o = 32; o > 0; o >>= 1)
 #pragma unroll
-    for (int u = 0; u < MAX_E; ++u) {
+    for (int j = 0; j < FA_KR; ++j)
+#pragma unroll
+      for (int hh = 0; hh < FA_HM; ++hh) part[j][hh] += __shfl_xor(part[j][hh], o);
+  float mine = -INFINITY;
+#pragma unroll
+  for (int j = 0; j < FA_KR; ++j)
+#pragma unroll
+    for (int hh = 0; hh < FA_HM; ++hh)
+      if (lane == hh * a.k + j && j < c && hh < a.H) mine = part[j][hh] * scale;
+  if (lane < HK) sa[lane] = mine;
+  wave_lds_sync();
+  softmax_heads(sa, HK, a.k, c, lane, pr);
+  wave_lds_sync();
+  // weighted sums: node part of the output, and the per-head sums of the slots' own inputs
+  float o[FA_E] = {0.f, 0.f};
+  HeadRow zp;
+#pragma unroll
+  for (int hh = 0; hh < FA_HM; ++hh) {
+#pragma unroll
+    for (int m = 0; m < FA_NE; ++m) zp.e[hh][m] = 0.f;
+#pragma unroll
+    for (int m = 0; m < FA_NT; ++m) zp.t[hh][m] = 0.f;
+  }
+#pragma unroll
+  for (int j = 0; j < FA_KR; ++j) {   // (slots j >= c hold zeros and zero weights: no branch, the loop stays unrolled)
+    float pj[FA_HM];
+#pragma unroll
+    for (int hh = 0; hh < FA_HM; ++hh) pj[hh] = (hh < a.H && j < a.k) ? sa[HK + hh * a.k + j] : 0.f;
+#pragma unroll
+    for (int u = 0; u < FA_E; ++u) {
       const int e = lane + 64 * u;
-      kreg[jj][u] = e < sh.dO ? krow[e] : 0.f;
-      vreg[jj][u] = e < sh.dO ? krow[sh.dO + e] : 0.f;
+      const int h = min(e, a.dO - 1) / a.dh;
+      o[u] += (h == 0 ? pj[0] : pj[FA_HM - 1]) * s.pv[j][u];
+    }
+#pragma unroll
+    for (int hh = 0; hh < FA_HM; ++hh) {
+#pragma unroll
+      for (int m = 0; m < FA_NE; ++m) zp.e[hh][m] += pj[hh] * s.ce[j][m];
+#pragma unroll
+      for (int m = 0; m < FA_NT; ++m) zp.t[hh][m] += pj[hh] * s.ct[j][m];
     }
   }
 #pragma unroll
-  for (int u = 0; u < MAX_E; ++u) {
+  for (int u = 0; u < FA_E; ++u) {
     const int e = lane + 64 * u;
-    if (e < sh.dO) sq[e] = qreg[u];
+    if (e < a.dO) out[e] = o[u];
   }
-#pragma unroll
-  for (int jj = 0; jj < ROWS_IN_FLIGHT; ++jj) {
-    if (jj < c) {
-#pragma unroll
-      for (int u = 0; u < MAX_E; ++u) {
-        const int e = lane + 64 * u;
-        if (e < sh.dO) sK[jj * (sh.dO + 1) + e] = kreg[jj][u];
-      }
-    }
-  }
-  // key rows beyond the first batch
-  for (int j0 = ROWS_IN_FLIGHT; j0 < c; j0 += ROWS_IN_FLIGHT) {
-    float k2[ROWS_IN_FLIGHT][MAX_E];
-#pragma unroll
-    for (int jj = 0; jj < ROWS_IN_FLIGHT; ++jj) {
-      const float* krow = KV + ((size_t)r * sh.k + min(j0 + jj, c - 1)) * sh.ldkv;
-#pragma unroll
-      for (int u = 0; u < MAX_E; ++u) {
-        const int e = lane + 64 * u;
-        k2[jj][u] = e < sh.dO ? krow[e] : 0.f;
-      }
-    }
-#pragma unroll
-    for (int jj = 0; jj < ROWS_IN_FLIGHT; ++jj) {
-      if (j0 + jj < c) {
-#pragma unroll
-        for (int u = 0; u < MAX_E; ++u) {
-          const int e = lane + 64 * u;
-          if (e < sh.dO) sK[(j0 + jj) * (sh.dO + 1) + e] = k2[jj][u];
-        }
-      }
-    }
-  }
-  __builtin_amdgcn_wave_barrier();
-  __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): LDS writes of this wave are visible to all its lanes
-  for (int p = lane; p < HK; p += 64) {
-    const int h = p / sh.k, j = p - h * sh.k;
-    float a = -INFINITY;
-    if (j < c) {
-      a = 0.f;
-      const float* qq = sq + h * sh.dh;
-      const float* kk = sK + j * (sh.dO + 1) + h * sh.dh;
-      for (int d = 0; d < sh.dh; ++d) a += qq[d] * kk[d];
-      a *= scale;
-    }
-    sa[p] = a;
-  }
-  __builtin_amdgcn_wave_barrier();
-  __builtin_amdgcn_s_waitcnt(0xc07f);
-  for (int p = lane; p < HK; p += 64) {
-    const int h = p / sh.k, j = p - h * sh.k;
-    float v = 0.f;
-    if (j < c) {
-      float mx = -INFINITY;
-      for (int jj = 0; jj < c; ++jj) mx = fmaxf(mx, sa[h * sh.k + jj]);
-      float den = 0.f;
-      for (int jj = 0; jj < c; ++jj) den += expf(sa[h * sh.k + jj] - mx);
-      v = expf(sa[p] - mx) / den;
-    }
-    sa[HK + p] = v;
-    pr[p] = v;
-  }
-  __builtin_amdgcn_wave_barrier();
-  __builtin_amdgcn_s_waitcnt(0xc07f);
-  // weighted sums of the value rows: the first batch is in registers
-  float o[MAX_E];
-#pragma unroll
-  for (int u = 0; u < MAX_E; ++u) {
-    const int e = lane + 64 * u;
-    const int h = min(e, sh.dO - 1) / sh.dh;
-    float acc = 0.f;
-#pragma unroll
-    for (int jj = 0; jj < ROWS_IN_FLIGHT; ++jj)
-      if (jj < c) acc += sa[HK + h * sh.k + jj] * vreg[jj][u];
-    o[u] = acc;
-  }
-  for (int j0 = ROWS_IN_FLIGHT; j0 < c; j0 += ROWS_IN_FLIGHT) {
-    float v2[ROWS_IN_FLIGHT][MAX_E];
-#pragma unroll
-    for (int jj = 0; jj < ROWS_IN_FLIGHT; ++jj) {
-      const float* vrow = KV + ((size_t)r * sh.k + min(j0 + jj, c - 1)) * sh.ldkv + sh.dO;
-#pragma unroll
-      for (int u = 0; u < MAX_E; ++u) {
-        const int e = lane + 64 * u;
-        v2[jj][u] = e < sh.dO ? vrow[e] : 0.f;
-      }
-    }
-#pragma unroll
-    for (int u = 0; u < MAX_E; ++u) {
-      const int h = min(lane + 64 * u, sh.dO - 1) / sh.dh;
-#pragma unroll
-      for (int jj = 0; jj < ROWS_IN_FLIGHT; ++jj)
-        if (j0 + jj < c) o[u] += sa[HK + h * sh.k + j0 + jj] * v2[jj][u];
-    }
-  }
-#pragma unroll
-  for (int u = 0; u < MAX_E; ++u) {
-    const int e = lane + 64 * u;
-    if (e < sh.dO) out[e] = o[u];
-  }
+  store_head_row(a, a.Zp + (size_t)r * a.ldz, lane, zp);
 }
 
-template <int MAX_E>
-__global__ __launch_bounds__(256) void attn_bwd_kernel(AttnShape sh, const float* __restrict__ q,
-                                                       const int32_t* __restrict__ slot_row,
-                                                       const float* __restrict__ KV,
-                                                       const int32_t* __restrict__ cnt,
-                                                       const float* __restrict__ prob,
-                                                       const float* __restrict__ dOmat, float* __restrict__ dq,
-                                                       float* __restrict__ dKV, float* __restrict__ q_part, AttnSums zs) {
+__global__ __launch_bounds__(256) void fattn_bwd_fast_kernel(FusedAttn a) {
   extern __shared__ float lds[];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int r = blockIdx.x * 4 + wave;
-  if (r >= sh.R) return;
-  float* sdo = lds + (size_t)wave * attn_lds_floats(sh.k, sh.H, sh.dO);
-  float* sV = sdo + sh.dO;
-  float* sa = sV + sh.k * (sh.dO + 1);  // [0,HK): prob, [HK,2HK): d(score)
-  const int c = cnt[r];
-  const size_t qrow = slot_row != nullptr ? (size_t)slot_row[r] : (size_t)r;
-  const int HK = sh.H * sh.k;
-  // rows of absent neighbours get zero gradients
-  for (int j = c; j < sh.k; ++j) {
-    float* row = dKV + ((size_t)r * sh.k + j) * sh.ldkv;
-    for (int e = lane; e < 2 * sh.dO; e += 64) row[e] = 0.f;
-  }
+  if (r >= a.R) return;
+  const int HK = a.H * a.k;
+  float* sa = lds + (size_t)wave * fattn_lds_floats(a.k, a.H);   // [0, HK): softmax weights, [HK, 2 HK): dp, then ds
+  const int c = a.cnt[r];
+  float* yrow = a.Y + (size_t)r * a.ldy;
   if (c == 0) {
-    for (int e = lane; e < sh.dO; e += 64) dq[(size_t)r * sh.ldo + e] = 0.f;
-    if (zs.Zs != nullptr) {
-      if (zs.later) {
-        for (int p = lane; p < HK; p += 64) zs.ds_out[(size_t)r * HK + p] = 0.f;
-      } else {
-        for (int i = lane; i < sh.H * zs.dcp; i += 64) zs.Zs[(size_t)r * zs.ldz + i] = zs.Zp[(size_t)r * zs.ldz + i] = 0.f;
-      }
-      for (int e = lane; e < sh.dO; e += 64) zs.Qroot[(size_t)r * sh.ldo + e] = 0.f;
-    }
+    for (int p = lane; p < HK; p += 64) a.dscore[(size_t)r * HK + p] = 0.f;
+    for (int e = lane; e < a.dO; e += 64) a.dqn[(size_t)r * a.ldh + e] = a.Qroot[(size_t)r * a.ldh + e] = 0.f;
+    zero_head_rows(a, a.Zs + (size_t)r * a.ldz, lane);
+    for (int i = lane; i < 2 * a.dt; i += 64) yrow[i] = 0.f;
     return;
   }
+  int my_e, my_row;
+  double my_dt;
+  slot_ids(a, r, min(lane, a.k - 1), lane < a.k ? c : 0, my_e, my_row, my_dt, false);
+  const size_t qrow = a.slot_row != nullptr ? (size_t)a.slot_row[r] : (size_t)r;
   const float scale = 1.0f / sqrtf((float)c);
-  // the burst: dO and q rows, the softmax weights, and the key and value rows of the first batch
-  float doreg[MAX_E], qreg[MAX_E], kreg[ROWS_IN_FLIGHT][MAX_E], vreg[ROWS_IN_FLIGHT][MAX_E];
+  int e_j[FA_KR], row_j[FA_KR];
+  double dt_j[FA_KR];
 #pragma unroll
-  for (int u = 0; u < MAX_E; ++u) {
+  for (int j = 0; j < FA_KR; ++j) {
+    // (readlane: one value for the whole wavefront, kept in scalar registers)
+    e_j[j] = __builtin_amdgcn_readlane(my_e, j);
+    row_j[j] = __builtin_amdgcn_readlane(my_row, j);
+    dt_j[j] = __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(my_dt), j),
+                               __builtin_amdgcn_readlane(__double2loint(my_dt), j));
+  }
+  float qreg[FA_E], doreg[FA_E];
+#pragma unroll
+  for (int u = 0; u < FA_E; ++u) {
     const int e = lane + 64 * u;
-    doreg[u] = e < sh.dO ? dOmat[(size_t)r * sh.ldo + e] : 0.f;
-    qreg[u] = e < sh.dO ? q[qrow * sh.ldq + e] : 0.f;
+    qreg[u] = e < a.dO ? a.P[qrow * a.ldp + a.off_q + e] : 0.f;
+    doreg[u] = e < a.dO ? a.dOmat[(size_t)r * a.ldh + e] : 0.f;
   }
-  for (int p = lane; p < HK; p += 64) sa[p] = prob[(size_t)r * HK + p];
+  if (lane < HK) sa[lane] = a.prob[(size_t)r * HK + lane];
+  HeadRow ur, gr;
+  load_head_row(a, a.U + qrow * a.ldz, lane, ur);
+  load_head_row(a, a.G + (size_t)r * a.ldz, lane, gr);
+  SlotRegs s;
+  float st[FA_KR][FA_NT];
+  fast_load_slots<true>(a, lane, c, e_j, row_j, dt_j, s, st);
+  // dp_jh = dO_h . V_jh = dO_h . Pv_h[w_j] + g_h . c_j
+  float part[FA_KR][FA_HM];
 #pragma unroll
-  for (int jj = 0; jj < ROWS_IN_FLIGHT; ++jj) {
-    const float* krow = KV + ((size_t)r * sh.k + min(jj, c - 1)) * sh.ldkv;
+  for (int j = 0; j < FA_KR; ++j) {
 #pragma unroll
-    for (int u = 0; u < MAX_E; ++u) {
-      const int e = lane + 64 * u;
-      kreg[jj][u] = e < sh.dO ? krow[e] : 0.f;
-      vreg[jj][u] = e < sh.dO ? krow[sh.dO + e] : 0.f;
-    }
-  }
+    for (int hh = 0; hh < FA_HM; ++hh) {
+      float acc = 0.f;
 #pragma unroll
-  for (int u = 0; u < MAX_E; ++u) {
-    const int e = lane + 64 * u;
-    if (e < sh.dO) sdo[e] = doreg[u];
-  }
+      for (int m = 0; m < FA_NE; ++m) acc += gr.e[hh][m] * s.ce[j][m];
 #pragma unroll
-  for (int jj = 0; jj < ROWS_IN_FLIGHT; ++jj) {
-    if (jj < c) {
+      for (int m = 0; m < FA_NT; ++m) acc += gr.t[hh][m] * s.ct[j][m];
 #pragma unroll
-      for (int u = 0; u < MAX_E; ++u) {
+      for (int u = 0; u < FA_E; ++u) {
         const int e = lane + 64 * u;
-        if (e < sh.dO) sV[jj * (sh.dO + 1) + e] = vreg[jj][u];
+        if (e < a.dO && e / a.dh == hh) acc += doreg[u] * s.pv[j][u];
       }
+      part[j][hh] = acc;
     }
   }
-  // value rows beyond the first batch
-  for (int j0 = ROWS_IN_FLIGHT; j0 < c; j0 += ROWS_IN_FLIGHT) {
-    float v2[ROWS_IN_FLIGHT][MAX_E];
 #pragma unroll
-    for (int jj = 0; jj < ROWS_IN_FLIGHT; ++jj) {
-      const float* vrow = KV + ((size_t)r * sh.k + min(j0 + jj, c - 1)) * sh.ldkv + sh.dO;
+  for (int o = 32; o > 0; o >>= 1)
 #pragma unroll
-      for (int u = 0; u < MAX_E; ++u) {
-        const int e = lane + 64 * u;
-        v2[jj][u] = e < sh.dO ? vrow[e] : 0.f;
-      }
-    }
+    for (int j = 0; j < FA_KR; ++j)
 #pragma unroll
-    for (int jj = 0; jj < ROWS_IN_FLIGHT; ++jj) {
-      if (j0 + jj < c) {
+      for (int hh = 0; hh < FA_HM; ++hh) part[j][hh] += __shfl_xor(part[j][hh], o);
+  float dp = 0.f;
 #pragma unroll
-        for (int u = 0; u < MAX_E; ++u) {
-          const int e = lane + 64 * u;
-          if (e < sh.dO) sV[(j0 + jj) * (sh.dO + 1) + e] = v2[jj][u];
-        }
-      }
-    }
-  }
-  __builtin_amdgcn_wave_barrier();
-  __builtin_amdgcn_s_waitcnt(0xc07f);
-  for (int p = lane; p < HK; p += 64) {
-    const int h = p / sh.k, j = p - h * sh.k;
-    float dp = 0.f;
+  for (int j = 0; j < FA_KR; ++j)
+#pragma unroll
+    for (int hh = 0; hh < FA_HM; ++hh)
+      if (lane == hh * a.k + j && j < c && hh < a.H) dp = part[j][hh];
+  if (lane < HK) sa[HK + lane] = dp;
+  wave_lds_sync();
+  float da = 0.f;
+  if (lane < HK) {   // softmax backward, scaled by 1 / sqrt(|N_v|)
+    const int h = lane / a.k, j = lane - h * a.k;
     if (j < c) {
-      const float* dd = sdo + h * sh.dh;
-      const float* vv = sV + j * (sh.dO + 1) + h * sh.dh;
-      for (int d = 0; d < sh.dh; ++d) dp += dd[d] * vv[d];
+      float sdot = 0.f;
+      for (int jj = 0; jj < c; ++jj) sdot += sa[h * a.k + jj] * sa[HK + h * a.k + jj];
+      da = sa[lane] * (sa[HK + lane] - sdot) * scale;
     }
-    sa[HK + p] = dp;
   }
-  __builtin_amdgcn_wave_barrier();
-  __builtin_amdgcn_s_waitcnt(0xc07f);
+  wave_lds_sync();
+  if (lane < HK) {
+    sa[HK + lane] = da;
+    a.dscore[(size_t)r * HK + lane] = da;
+  }
+  wave_lds_sync();
+  // per-root sums: dq (node part), Zs, and the time-encoding gradient against -sin(.)
+  float dq[FA_E] = {0.f, 0.f};
+  HeadRow zs;
+  float yw[FA_NT], yb[FA_NT];
+#pragma unroll
+  for (int hh = 0; hh < FA_HM; ++hh) {
+#pragma unroll
+    for (int m = 0; m < FA_NE; ++m) zs.e[hh][m] = 0.f;
+#pragma unroll
+    for (int m = 0; m < FA_NT; ++m) zs.t[hh][m] = 0.f;
+  }
+#pragma unroll
+  for (int m = 0; m < FA_NT; ++m) yw[m] = yb[m] = 0.f;
+#pragma unroll
+  for (int j = 0; j < FA_KR; ++j) {   // (slots j >= c hold zeros and zero weights: no branch, the loop stays unrolled)
+    float dsj[FA_HM], pj[FA_HM];
+#pragma unroll
+    for (int hh = 0; hh < FA_HM; ++hh) {
+      dsj[hh] = (hh < a.H && j < a.k) ? sa[HK + hh * a.k + j] : 0.f;
+      pj[hh] = (hh < a.H && j < a.k) ? sa[hh * a.k + j] : 0.f;
+    }
+#pragma unroll
+    for (int u = 0; u < FA_E; ++u) {
+      const int e = lane + 64 * u;
+      const int h = min(e, a.dO - 1) / a.dh;
+      dq[u] += (h == 0 ? dsj[0] : dsj[FA_HM - 1]) * s.pk[j][u];
+    }
+    const float dtf = (float)dt_j[j];
+#pragma unroll
+    for (int hh = 0; hh < FA_HM; ++hh) {
+#pragma unroll
+      for (int m = 0; m < FA_NE; ++m) zs.e[hh][m] += dsj[hh] * s.ce[j][m];
+#pragma unroll
+      for (int m = 0; m < FA_NT; ++m) zs.t[hh][m] += dsj[hh] * s.ct[j][m];
+    }
+#pragma unroll
+    for (int m = 0; m < FA_NT; ++m) {
+      float dphi = 0.f;
+#pragma unroll
+      for (int hh = 0; hh < FA_HM; ++hh) dphi += dsj[hh] * ur.t[hh][m] + pj[hh] * gr.t[hh][m];
+      const float t = -dphi * st[j][m];
+      yb[m] += t;
+      yw[m] += t * dtf;
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < FA_E; ++u) {
+    const int e = lane + 64 * u;
+    if (e < a.dO) {
+      a.dqn[(size_t)r * a.ldh + e] = dq[u];
+      a.Qroot[(size_t)r * a.ldh + e] = qreg[u];
+    }
+  }
+  store_head_row(a, a.Zs + (size_t)r * a.ldz, lane, zs);
+#pragma unroll
+  for (int m = 0; m < FA_NT; ++m) {
+    const int tc = lane + 64 * m;
+    if (tc < a.dt) {
+      yrow[tc] = yw[m];
+      yrow[a.dt + tc] = yb[m];
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// Generic path: any k <= TGNN_MAX_K, any widths, any number of heads.  Same arithmetic with plain loops: a
+// slot's columns are recomputed wherever they are needed instead of being kept in registers.
+// ---------------------------------------------------------------------------------------------------------
+// column `col` < d_e + d_t of slot input c_j; sn receives the sine of a time column (0 for an edge-feature column)
+__device__ __forceinline__ float slot_col(const FusedAttn& a, int e, double dt, int col, float& sn) {
+  sn = 0.f;
+  if (col < a.de) return a.efeat[(size_t)e * a.de + col];
+  float cs;
+  const int tc = col - a.de;
+  sincos_reduced(fma((double)a.time_w[tc], dt, (double)a.time_b[tc]), sn, cs);
+  return cs;
+}
+
+// per-wavefront LDS of the generic kernels: [0, HK) and [HK, 2 HK) as in the fast ones, then k slot ids, node rows
+// and time differences
+__host__ __device__ inline int gattn_lds_bytes(int k, int H) { return 2 * H * k * 4 + k * (4 + 4 + 8) + 8; }
+
+struct GenLds {
+  float* sa;
+  int *e, *row;
+  double* dt;
+};
+__device__ __forceinline__ GenLds gen_lds(char* base, int wave, int k, int H) {
+  char* p = base + (size_t)wave * gattn_lds_bytes(k, H);
+  GenLds g;
+  g.dt = reinterpret_cast<double*>(p);              // 8-byte aligned: the per-wave size is a multiple of 8
+  g.sa = reinterpret_cast<float*>(p + 8 * k);
+  g.e = reinterpret_cast<int*>(p + 8 * k + 8 * H * k);
+  g.row = g.e + k;
+  return g;
+}
+
+__global__ __launch_bounds__(256) void fattn_fwd_gen_kernel(FusedAttn a) {
+  extern __shared__ __attribute__((aligned(16))) char lds_raw[];
+  int block = blockIdx.x;
+  if (a.fill.ucnt != nullptr) {
+    const int fill_blocks = (a.fill.S + 255) / 256;
+    if (block < fill_blocks) {
+      uniq_fill_block(a.fill, block);
+      return;
+    }
+    block -= fill_blocks;
+  }
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int r = block * 4 + wave;
+  if (r >= a.R) return;
+  const int HK = a.H * a.k, dc = a.de + a.dt;
+  GenLds L = gen_lds(lds_raw, wave, a.k, a.H);
+  const int c = a.cnt[r];
+  float* pr = a.prob + (size_t)r * HK;
+  float* out = a.Onode + (size_t)r * a.ldh;
+  for (int j = lane; j < a.k; j += 64) {
+    int e, row;
+    double dt;
+    slot_ids(a, r, j, c, e, row, dt, true);
+    L.e[j] = e; L.row[j] = row; L.dt[j] = dt;
+    a.dtk[(size_t)r * a.k + j] = dt;
+  }
+  if (c == 0) {
+    for (int p = lane; p < HK; p += 64) pr[p] = 0.f;
+    for (int e = lane; e < a.dO; e += 64) out[e] = 0.f;
+    zero_head_rows(a, a.Zp + (size_t)r * a.ldz, lane);
+    return;
+  }
+  wave_lds_sync();
+  const size_t qrow = a.slot_row != nullptr ? (size_t)a.slot_row[r] : (size_t)r;
+  const float* qv = a.P + qrow * a.ldp + a.off_q;
+  const float* urow = a.U + qrow * a.ldz;
+  const float scale = 1.0f / sqrtf((float)c);
+  for (int j = 0; j < c; ++j) {
+    const float* prow = a.P + (size_t)L.row[j] * a.ldp;
+    for (int h = 0; h < a.H; ++h) {
+      float acc = 0.f;
+      for (int col = lane; col < dc; col += 64) {
+        float sn;
+        acc += urow[h * a.dcp + col] * slot_col(a, L.e[j], L.dt[j], col, sn);
+      }
+      for (int e = h * a.dh + lane; e < (h + 1) * a.dh; e += 64) acc += qv[e] * prow[e];
+      acc = wave_sum(acc);
+      if (lane == 0) L.sa[h * a.k + j] = acc * scale;
+    }
+  }
+  wave_lds_sync();
+  softmax_heads(L.sa, HK, a.k, c, lane, pr);
+  wave_lds_sync();
+  for (int e = lane; e < a.dO; e += 64) {
+    const int h = e / a.dh;
+    float acc = 0.f;
+    for (int j = 0; j < c; ++j) acc += L.sa[HK + h * a.k + j] * a.P[(size_t)L.row[j] * a.ldp + a.dO + e];
+    out[e] = acc;
+  }
+  float* zrow = a.Zp + (size_t)r * a.ldz;
+  for (int col = lane; col < a.dcp; col += 64) {
+    float acc[TGNN_MAX_HEADS];
+#pragma unroll
+    for (int h = 0; h < TGNN_MAX_HEADS; ++h) acc[h] = 0.f;
+    if (col < dc) {
+      for (int j = 0; j < c; ++j) {
+        float sn;
+        const float cv = slot_col(a, L.e[j], L.dt[j], col, sn);
+#pragma unroll
+        for (int h = 0; h < TGNN_MAX_HEADS; ++h)
+          if (h < a.H) acc[h] += L.sa[HK + h * a.k + j] * cv;
+      }
+    }
+#pragma unroll
+    for (int h = 0; h < TGNN_MAX_HEADS; ++h)
+      if (h < a.H) zrow[h * a.dcp + col] = acc[h];
+  }
+}
+
+__global__ __launch_bounds__(256) void fattn_bwd_gen_kernel(FusedAttn a) {
+  extern __shared__ __attribute__((aligned(16))) char lds_raw[];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int r = blockIdx.x * 4 + wave;
+  if (r >= a.R) return;
+  const int HK = a.H * a.k, dc = a.de + a.dt;
+  GenLds L = gen_lds(lds_raw, wave, a.k, a.H);
+  const int c = a.cnt[r];
+  float* yrow = a.Y + (size_t)r * a.ldy;
+  if (c == 0) {
+    for (int p = lane; p < HK; p += 64) a.dscore[(size_t)r * HK + p] = 0.f;
+    for (int e = lane; e < a.dO; e += 64) a.dqn[(size_t)r * a.ldh + e] = a.Qroot[(size_t)r * a.ldh + e] = 0.f;
+    zero_head_rows(a, a.Zs + (size_t)r * a.ldz, lane);
+    for (int i = lane; i < 2 * a.dt; i += 64) yrow[i] = 0.f;
+    return;
+  }
+  for (int j = lane; j < a.k; j += 64) {
+    int e, row;
+    double dt;
+    slot_ids(a, r, j, c, e, row, dt, false);
+    L.e[j] = e; L.row[j] = row; L.dt[j] = dt;
+  }
+  for (int p = lane; p < HK; p += 64) L.sa[p] = a.prob[(size_t)r * HK + p];
+  wave_lds_sync();
+  const size_t qrow = a.slot_row != nullptr ? (size_t)a.slot_row[r] : (size_t)r;
+  const float* qv = a.P + qrow * a.ldp + a.off_q;
+  const float* urow = a.U + qrow * a.ldz;
+  const float* grow = a.G + (size_t)r * a.ldz;
+  const float* dov = a.dOmat + (size_t)r * a.ldh;
+  const float scale = 1.0f / sqrtf((float)c);
+  for (int j = 0; j < c; ++j) {
+    const float* prow = a.P + (size_t)L.row[j] * a.ldp + a.dO;
+    for (int h = 0; h < a.H; ++h) {
+      float acc = 0.f;
+      for (int col = lane; col < dc; col += 64) {
+        float sn;
+        acc += grow[h * a.dcp + col] * slot_col(a, L.e[j], L.dt[j], col, sn);
+      }
+      for (int e = h * a.dh + lane; e < (h + 1) * a.dh; e += 64) acc += dov[e] * prow[e];
+      acc = wave_sum(acc);
+      if (lane == 0) L.sa[HK + h * a.k + j] = acc;
+    }
+  }
+  wave_lds_sync();
   float da_keep[(TGNN_MAX_HEADS * TGNN_MAX_K + 63) / 64];
   int it = 0;
   for (int p = lane; p < HK; p += 64, ++it) {
-    const int h = p / sh.k, j = p - h * sh.k;
+    const int h = p / a.k, j = p - h * a.k;
     float da = 0.f;
     if (j < c) {
       float sdot = 0.f;
-      for (int jj = 0; jj < c; ++jj) sdot += sa[h * sh.k + jj] * sa[HK + h * sh.k + jj];
-      da = sa[p] * (sa[HK + p] - sdot) * scale;
+      for (int jj = 0; jj < c; ++jj) sdot += L.sa[h * a.k + jj] * L.sa[HK + h * a.k + jj];
+      da = L.sa[p] * (L.sa[HK + p] - sdot) * scale;
     }
     da_keep[it] = da;
   }
-  __builtin_amdgcn_wave_barrier();
-  __builtin_amdgcn_s_waitcnt(0xc07f);
+  wave_lds_sync();
   it = 0;
-  for (int p = lane; p < HK; p += 64, ++it) sa[HK + p] = da_keep[it];
-  __builtin_amdgcn_wave_barrier();
-  __builtin_amdgcn_s_waitcnt(0xc07f);
-  if (zs.Zs != nullptr && zs.later) {
-    for (int p = lane; p < HK; p += 64) zs.ds_out[(size_t)r * HK + p] = sa[HK + p];
+  for (int p = lane; p < HK; p += 64, ++it) {
+    L.sa[HK + p] = da_keep[it];
+    a.dscore[(size_t)r * HK + p] = da_keep[it];
+  }
+  wave_lds_sync();
+  for (int e = lane; e < a.dO; e += 64) {
+    const int h = e / a.dh;
+    float acc = 0.f;
+    for (int j = 0; j < c; ++j) acc += L.sa[HK + h * a.k + j] * a.P[(size_t)L.row[j] * a.ldp + e];
+    a.dqn[(size_t)r * a.ldh + e] = acc;
+    a.Qroot[(size_t)r * a.ldh + e] = qv[e];
+  }
+  float* zrow = a.Zs + (size_t)r * a.ldz;
+  for (int col = lane; col < a.dcp; col += 64) {
+    float acc[TGNN_MAX_HEADS];
 #pragma unroll
-    for (int u = 0; u < MAX_E; ++u) {
-      const int e = lane + 64 * u;
-      if (e < sh.dO) zs.Qroot[(size_t)r * sh.ldo + e] = qreg[u];
-    }
-  } else if (zs.Zs != nullptr) {
-    // Per head, the sums of the slots' {e | Phi} rows weighted by the score gradients (Zs) and by the softmax
-    // weights (Zp): dK_j = ds_j q and dV_j = p_j dO per head, so the weight gradients sum_j dK_j CE_j^T and
-    // sum_j dV_j CE_j^T of a root are q Zs^T and dO Zp^T, products over roots instead of over slots.
-    for (int c0 = 0; c0 < zs.dcp; c0 += 64) {
-      const int cc = c0 + lane;
-      float as[TGNN_MAX_HEADS], ap[TGNN_MAX_HEADS];
-#pragma unroll
-      for (int h = 0; h < TGNN_MAX_HEADS; ++h) as[h] = ap[h] = 0.f;
-      for (int j0 = 0; j0 < c; j0 += ROWS_IN_FLIGHT) {
-        float ce[ROWS_IN_FLIGHT];
-#pragma unroll
-        for (int jj = 0; jj < ROWS_IN_FLIGHT; ++jj)
-          ce[jj] = (j0 + jj < c && cc < zs.dcols) ? zs.CE[((size_t)r * sh.k + j0 + jj) * zs.ldce + cc] : 0.f;
-#pragma unroll
-        for (int jj = 0; jj < ROWS_IN_FLIGHT; ++jj) {
-          if (j0 + jj < c) {
-#pragma unroll
-            for (int h = 0; h < TGNN_MAX_HEADS; ++h) {
-              if (h < sh.H) {
-                as[h] += sa[HK + h * sh.k + j0 + jj] * ce[jj];
-                ap[h] += sa[h * sh.k + j0 + jj] * ce[jj];
-              }
-            }
-          }
-        }
-      }
-      if (cc < zs.dcp) {
+    for (int h = 0; h < TGNN_MAX_HEADS; ++h) acc[h] = 0.f;
+    float yw = 0.f, yb = 0.f;
+    if (col < dc) {
+      for (int j = 0; j < c; ++j) {
+        float sn;
+        const float cv = slot_col(a, L.e[j], L.dt[j], col, sn);
+        float dphi = 0.f;
 #pragma unroll
         for (int h = 0; h < TGNN_MAX_HEADS; ++h) {
-          if (h < sh.H) {
-            zs.Zs[(size_t)r * zs.ldz + h * zs.dcp + cc] = as[h];
-            zs.Zp[(size_t)r * zs.ldz + h * zs.dcp + cc] = ap[h];
+          if (h < a.H) {
+            const float ds = L.sa[HK + h * a.k + j];
+            acc[h] += ds * cv;
+            dphi += ds * urow[h * a.dcp + col] + L.sa[h * a.k + j] * grow[h * a.dcp + col];
           }
         }
+        const float t = -dphi * sn;
+        yb += t;
+        yw += t * (float)L.dt[j];
       }
     }
 #pragma unroll
-    for (int u = 0; u < MAX_E; ++u) {
-      const int e = lane + 64 * u;
-      if (e < sh.dO) zs.Qroot[(size_t)r * sh.ldo + e] = qreg[u];
-    }
-  }
-  // dq, and the gradients of the key and value rows: the first batch of key rows is in registers
-  float dqe[MAX_E];
-#pragma unroll
-  for (int u = 0; u < MAX_E; ++u) {
-    const int e = lane + 64 * u;
-    const int h = min(e, sh.dO - 1) / sh.dh;
-    float acc = 0.f;
-#pragma unroll
-    for (int jj = 0; jj < ROWS_IN_FLIGHT; ++jj) {
-      if (jj < c && e < sh.dO) {
-        const size_t row = ((size_t)r * sh.k + jj) * sh.ldkv;
-        const float da = sa[HK + h * sh.k + jj];
-        acc += da * kreg[jj][u];
-        dKV[row + e] = da * qreg[u];
-        dKV[row + sh.dO + e] = sa[h * sh.k + jj] * doreg[u];
-      }
-    }
-    dqe[u] = acc;
-  }
-  for (int j0 = ROWS_IN_FLIGHT; j0 < c; j0 += ROWS_IN_FLIGHT) {
-    float k2[ROWS_IN_FLIGHT][MAX_E];
-#pragma unroll
-    for (int jj = 0; jj < ROWS_IN_FLIGHT; ++jj) {
-      const float* krow = KV + ((size_t)r * sh.k + min(j0 + jj, c - 1)) * sh.ldkv;
-#pragma unroll
-      for (int u = 0; u < MAX_E; ++u) {
-        const int e = lane + 64 * u;
-        k2[jj][u] = e < sh.dO ? krow[e] : 0.f;
-      }
-    }
-#pragma unroll
-    for (int u = 0; u < MAX_E; ++u) {
-      const int e = lane + 64 * u;
-      const int h = min(e, sh.dO - 1) / sh.dh;
-#pragma unroll
-      for (int jj = 0; jj < ROWS_IN_FLIGHT; ++jj) {
-        const int j = j0 + jj;
-        if (j < c && e < sh.dO) {
-          const size_t row = ((size_t)r * sh.k + j) * sh.ldkv;
-          const float da = sa[HK + h * sh.k + j];
-          dqe[u] += da * k2[jj][u];
-          dKV[row + e] = da * qreg[u];
-          dKV[row + sh.dO + e] = sa[h * sh.k + j] * doreg[u];
-        }
-      }
-    }
-  }
-#pragma unroll
-  for (int u = 0; u < MAX_E; ++u) {
-    const int e = lane + 64 * u;
-    if (e < sh.dO) {
-      dq[(size_t)r * sh.ldo + e] = dqe[u];
-      // column sums of dq over the roots, spread over QPHI_BLOCKS partial rows to keep the atomics apart
-      if (q_part != nullptr) atomicAdd(q_part + (size_t)(blockIdx.x & (QPHI_BLOCKS - 1)) * sh.dO + e, dqe[u]);
+    for (int h = 0; h < TGNN_MAX_HEADS; ++h)
+      if (h < a.H) zrow[h * a.dcp + col] = acc[h];
+    if (col >= a.de && col < dc) {
+      yrow[col - a.de] = yw;
+      yrow[a.dt + col - a.de] = yb;
     }
   }
 }
 
-static AttnShape shape_of(const Dims& d, int R, int ldq, int ldkv, int ldo) {
-  return AttnShape{R, d.k, d.H, d.dO, d.dO / d.H, ldq, ldkv, ldo};
+static bool fast_path(const FusedAttn& a) {
+  return !a.force_generic && a.k <= FA_KR && a.de <= 64 * FA_NE && a.dt <= 64 * FA_NT && a.dO <= 64 * FA_E &&
+         a.H <= FA_HM && a.H * a.k <= 64;
 }
 
-void attn_core_fwd(const Dims& d, int R, const float* q, int ldq, const int32_t* slot_row, const float* KV, int ldkv,
-                   const int32_t* cnt, float* prob, float* Omat, int ldo, hipStream_t s,
-                   const SortArgs& fill) {
-  if (R <= 0) return;
-  const size_t lds = 4 * sizeof(float) * attn_lds_floats(d.k, d.H, d.dO);
-  const int fill_blocks = fill.ucnt != nullptr ? (fill.S + 255) / 256 : 0;
-  if (d.dO <= 128)
-    hipLaunchKernelGGL(attn_fwd_kernel<2>, dim3((R + 3) / 4 + fill_blocks), dim3(256), lds, s, shape_of(d, R, ldq, ldkv, ldo),
-                       q, slot_row, KV, cnt, prob, Omat, fill);
+void fattn_fwd(const FusedAttn& a, hipStream_t s) {
+  if (a.R <= 0) return;
+  const int fill_blocks = a.fill.ucnt != nullptr ? (a.fill.S + 255) / 256 : 0;
+  const dim3 grid((a.R + 3) / 4 + fill_blocks);
+  if (fast_path(a))
+    hipLaunchKernelGGL(fattn_fwd_fast_kernel, grid, dim3(256), 4 * sizeof(float) * fattn_lds_floats(a.k, a.H), s, a);
   else
-    hipLaunchKernelGGL(attn_fwd_kernel<4>, dim3((R + 3) / 4 + fill_blocks), dim3(256), lds, s, shape_of(d, R, ldq, ldkv, ldo),
-                       q, slot_row, KV, cnt, prob, Omat, fill);
+    hipLaunchKernelGGL(fattn_fwd_gen_kernel, grid, dim3(256), 4 * gattn_lds_bytes(a.k, a.H), s, a);
 }
 
-// dq and dOmat share the pitch ldo
-void attn_core_bwd(const Dims& d, int R, const float* q, int ldq, const int32_t* slot_row, const float* KV, int ldkv,
-                   const int32_t* cnt, const float* prob, const float* dOmat, int ldo, float* dq, float* dKV,
-                   float* q_part, hipStream_t s, const AttnSums& zs) {
-  if (R <= 0) return;
-  const size_t lds = 4 * sizeof(float) * attn_lds_floats(d.k, d.H, d.dO);
-  if (d.dO <= 128)
-    hipLaunchKernelGGL(attn_bwd_kernel<2>, dim3((R + 3) / 4), dim3(256), lds, s, shape_of(d, R, ldq, ldkv, ldo), q, slot_row,
-                       KV, cnt, prob, dOmat, dq, dKV, q_part, zs);
+void fattn_bwd(const FusedAttn& a, hipStream_t s) {
+  if (a.R <= 0) return;
+  const dim3 grid((a.R + 3) / 4);
+  if (fast_path(a))
+    hipLaunchKernelGGL(fattn_bwd_fast_kernel, grid, dim3(256), 4 * sizeof(float) * fattn_lds_floats(a.k, a.H), s, a);
   else
-    hipLaunchKernelGGL(attn_bwd_kernel<4>, dim3((R + 3) / 4), dim3(256), lds, s, shape_of(d, R, ldq, ldkv, ldo), q, slot_row,
-                       KV, cnt, prob, dOmat, dq, dKV, q_part, zs);
+    hipLaunchKernelGGL(fattn_bwd_gen_kernel, grid, dim3(256), 4 * gattn_lds_bytes(a.k, a.H), s, a);
 }
 
 }  // namespace tgnn

@@ -87,149 +87,6 @@ void gather_rows(const GatherArgs& a, hipStream_t s) {
   else hipLaunchKernelGGL(gather_kernel<1>, dim3(blocks), dim3(256), 0, s, a);
 }
 
-// Per neighbour slot (r, j): the slot's own part of the key/value input of Eq. 5-6, {e_vw | Phi(dt)}.  The
-// node part {s'_w | static_w} is projected once per distinct node elsewhere, so it is not copied here.
-// A block takes CE_ROWS consecutive slot rows.  Their indices and time differences are fetched first by a
-// few lanes and shared through LDS, so that the row loads of a wave (CE_ROWS / 4 rows, all issued before
-// any is consumed) do not each wait behind their own chain of dependent index loads.  Each output row is put
-// together in LDS and leaves as one contiguous run of 16-byte stores.
-constexpr int CE_ROWS = 16;
-template <int VEC>
-__global__ __launch_bounds__(256) void assemble_ce_kernel(CeArgs a) {
-  extern __shared__ __attribute__((aligned(16))) float ce_lds[];   // [CE_ROWS][ldce] staging rows
-  __shared__ int s_eid[CE_ROWS];       // edge-feature row, -1: absent neighbour
-  __shared__ double s_delta[CE_ROWS];
-  int block = blockIdx.x;
-  {
-    const int gru_blocks = gru_total_blocks(a.gru);   // the first blocks are passengers: the GRU gates
-    if (block < gru_blocks) {
-      gru_fwd_block(a.gru, block);
-      return;
-    }
-    block -= gru_blocks;
-  }
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int RK = a.R * a.k;
-  const int row0 = block * CE_ROWS;
-  if (threadIdx.x < CE_ROWS) {
-    const int row = row0 + threadIdx.x;
-    int e = -1;
-    double delta = 0.0;
-    if (row < RK) {
-      const int r = row / a.k, j = row - r * a.k;
-      if (j < a.cnt[r]) {
-        e = a.neid ? a.neid[row] : row;
-        if (a.dt_in) delta = a.dt_in[row];
-        else if (a.dt_source != 0) delta = a.root_t[r] - a.nts[row];
-        else delta = a.root_t[r] - a.tau_nbr[a.slot_row ? a.slot_row[a.R + row] : row];
-      }
-      a.dtk[row] = delta;
-    }
-    s_eid[threadIdx.x] = e;
-    s_delta[threadIdx.x] = delta;
-  }
-  __syncthreads();
-  constexpr int PER = CE_ROWS / 4;   // rows per wave: local rows wave * PER + i
-  float* stage = ce_lds + (size_t)wave * PER * a.ldce;
-  // edge features: the loads of all PER rows of a pass are in flight together
-  constexpr int EW = VEC == 4 ? 4 : 1;   // floats per lane and load (d_e % EW == 0)
-  const int e_units = a.de / EW;
-  for (int u0 = 0; u0 < e_units; u0 += 64) {
-    const int u = u0 + lane;
-    float4 v4[PER];
-    float v1[PER];
-#pragma unroll
-    for (int i = 0; i < PER; ++i) {
-      const int e = s_eid[wave * PER + i];
-      v4[i] = make_float4(0.f, 0.f, 0.f, 0.f);
-      v1[i] = 0.f;
-      if (e >= 0 && u < e_units) {
-        if (VEC == 4) v4[i] = reinterpret_cast<const float4*>(a.efeat + (size_t)e * a.de)[u];
-        else v1[i] = a.efeat[(size_t)e * a.de + u];
-      }
-    }
-    if (u < e_units) {
-#pragma unroll
-      for (int i = 0; i < PER; ++i) {
-        if (VEC == 4) reinterpret_cast<float4*>(stage + (size_t)i * a.ldce)[u] = v4[i];
-        else stage[(size_t)i * a.ldce + u] = v1[i];
-      }
-    }
-  }
-  // time encoding and row padding
-#pragma unroll
-  for (int i = 0; i < PER; ++i) {
-    const bool present = s_eid[wave * PER + i] >= 0;
-    const double delta = s_delta[wave * PER + i];
-    float* srow = stage + (size_t)i * a.ldce;
-    for (int c = lane; c < a.dt; c += 64) srow[a.de + c] = present ? time_enc(delta, a.time_w[c], a.time_b[c]) : 0.f;
-    for (int c = a.de + a.dt + lane; c < a.ldce; c += 64) srow[c] = 0.f;
-  }
-  __builtin_amdgcn_wave_barrier();
-  __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0): this wave's LDS writes are visible to all its lanes
-#pragma unroll
-  for (int i = 0; i < PER; ++i) {
-    const int row = row0 + wave * PER + i;
-    if (row >= RK) break;
-    float4* out = reinterpret_cast<float4*>(a.CE + (size_t)row * a.ldce);
-    const float4* srow = reinterpret_cast<const float4*>(stage + (size_t)i * a.ldce);
-    for (int q = lane; q < a.ldce / 4; q += 64) out[q] = srow[q];
-  }
-}
-
-// Fallback for rows too wide to stage CE_ROWS of them in LDS: one wavefront per row, direct stores.
-template <int VEC>
-__global__ __launch_bounds__(256) void assemble_ce_wide_kernel(CeArgs a) {
-  int block = blockIdx.x, n_blocks = gridDim.x;
-  {
-    const int gru_blocks = gru_total_blocks(a.gru);   // the first blocks are passengers: the GRU gates
-    if (block < gru_blocks) {
-      gru_fwd_block(a.gru, block);
-      return;
-    }
-    block -= gru_blocks; n_blocks -= gru_blocks;
-  }
-  const int lane = threadIdx.x & 63;
-  const int wpb = blockDim.x >> 6;
-  const int RK = a.R * a.k;
-  for (int row = block * wpb + (threadIdx.x >> 6); row < RK; row += n_blocks * wpb) {
-    const int r = row / a.k, j = row - r * a.k;
-    float* out = a.CE + (size_t)row * a.ldce;
-    if (j >= a.cnt[r]) {
-      wave_zero(out, a.ldce, lane);
-      if (lane == 0) a.dtk[row] = 0.0;
-      continue;
-    }
-    if (a.de) wave_copy<VEC>(out, a.efeat + (size_t)(a.neid ? a.neid[row] : row) * a.de, a.de, 0, lane);
-    double delta;
-    if (a.dt_in) delta = a.dt_in[row];
-    else if (a.dt_source != 0) delta = a.root_t[r] - a.nts[row];
-    else delta = a.root_t[r] - a.tau_nbr[a.slot_row ? a.slot_row[a.R + row] : row];
-    for (int c = lane; c < a.dt; c += 64) out[a.de + c] = time_enc(delta, a.time_w[c], a.time_b[c]);
-    for (int c = a.de + a.dt + lane; c < a.ldce; c += 64) out[c] = 0.f;
-    if (lane == 0) a.dtk[row] = delta;
-  }
-}
-
-void assemble_ce(const CeArgs& a, hipStream_t s) {
-  const int rows = a.R * a.k;
-  if (rows <= 0) {
-    gru_gates_fwd(a.gru, s);
-    return;
-  }
-  const int vec = pick_vec({a.de ? a.de : 4, (long long)((uintptr_t)a.efeat / 4)});
-  const size_t lds = (size_t)CE_ROWS * a.ldce * sizeof(float);
-  if (lds <= 48 * 1024) {
-    const int blocks = (rows + CE_ROWS - 1) / CE_ROWS + gru_total_blocks(a.gru);
-    if (vec == 4) hipLaunchKernelGGL(assemble_ce_kernel<4>, dim3(blocks), dim3(256), lds, s, a);
-    else hipLaunchKernelGGL(assemble_ce_kernel<1>, dim3(blocks), dim3(256), lds, s, a);
-  } else {
-    const int blocks = (rows + 3) / 4 + gru_total_blocks(a.gru);
-    if (vec == 4) hipLaunchKernelGGL(assemble_ce_wide_kernel<4>, dim3(blocks), dim3(256), 0, s, a);
-    else hipLaunchKernelGGL(assemble_ce_wide_kernel<1>, dim3(blocks), dim3(256), 0, s, a);
-  }
-}
-
 // Xrow[r] = x_root[r] (r < R); Xrow[R + r k + j] = x_nbr[r k + j] for j < cnt[r], zero otherwise; pad columns zero.
 __global__ __launch_bounds__(256) void stage_x_rows_kernel(int R, int k, int dx, const float* __restrict__ x_root,
                                                            const float* __restrict__ x_nbr,

@@ -340,6 +340,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, (TN <= 5
       acc[b][v] = live ? (relu ? fmaxf(x, 0.f) : x) : 0.f;
     }
   }
+  if (q.colsum != nullptr) {   // column sums of the tile: a lane's four rows, then the four lane groups; one atomic per wave
+    float* cs = q.colsum + (size_t)((row_tile * 4 + wave) & (q.colsum_rows - 1)) * N;
+#pragma unroll
+    for (int b = 0; b < TN; ++b) {
+      float t = acc[b][0] + acc[b][1] + acc[b][2] + acc[b][3];
+      t += __shfl_xor(t, 16);
+      t += __shfl_xor(t, 32);
+      const int col = n0 + b * 16 + li;
+      if (lg == 0 && col < N) atomicAdd(cs + col, t);
+    }
+  }
   if (!rowwise) {
 #pragma unroll
     for (int b = 0; b < TN; ++b) {
@@ -726,8 +737,10 @@ void TnBatch::add(const float* D, int ldd, const float* A, int lda, int M, int N
                   const int* m_dev) {
   // the loader clamps column offsets to ld - 4 and reads whole float4s: pitches below 4 (or below the logical
   // width) would send it out of bounds
-  if (M <= 0 || N <= 0 || K <= 0 || g.n >= TN_MAX_GROUP || ldd < 4 || lda < 4 || (ldd & 3) || (lda & 3) || N > ldd ||
-      K > lda)
+  // (K == 0 with a bias output: column sums of D only; A is then any readable matrix of M rows)
+  const bool with_bias = out.bias[0] != nullptr || out.bias[1] != nullptr;
+  if (M <= 0 || N <= 0 || K < 0 || (K == 0 && !with_bias) || g.n >= TN_MAX_GROUP || ldd < 4 || lda < 4 || (ldd & 3) ||
+      (lda & 3) || N > ldd || K > lda)
     return;
   TnProblem& p = g.p[g.n];
   p.D = D; p.ldd = ldd; p.A = A; p.lda = lda; p.M = M; p.N = N; p.K = K;

@@ -20,7 +20,11 @@ void prologue_fill(tgnn_ctx* ctx, const tgnn_params* p, const BatchSet* bs, cons
   memset(&pa, 0, sizeof(pa));
   int n = 0;
   auto add = [&](const float* src, float* dst, int rows, int cols, int zero_to, int ldd, int srs, int scs) {
-    pa.d[n++] = PackDesc{src, dst, rows, cols, zero_to, ldd, srs, scs, 0};
+    pa.d[n++] = PackDesc{src, dst, rows, cols, zero_to, ldd, srs, scs, 0, 0, 0, 0, 0};
+  };
+  // block-diagonal over the heads: block h of `rows` x `cols` lands at rows h * brd, columns h * bcd of dst
+  auto add_bd = [&](const float* src, float* dst, int rows, int cols, int ldd, int srs, int scs, int brd, int bcd, int bsrc) {
+    pa.d[n++] = PackDesc{src, dst, rows, cols, 0, ldd, srs, scs, 0, d.H, brd, bcd, bsrc};
   };
   if (p != nullptr) {
     const int dO = d.dO, dm = d.dm, dx = d.dx, dkv = d.dkv, dmrg = d.dO + d.dx, half = d.ldkv;
@@ -37,11 +41,16 @@ void prologue_fill(tgnn_ctx* ctx, const tgnn_params* p, const BatchSet* bs, cons
     add(p->wv, w.WxT + dO, dm, dO, dO, d.ldp, 1, dkv);
     add(p->wq, w.WxT + half, dm, dO, dO, d.ldp, 1, d.dq);
     add(p->wo + dO, w.WxT + half + dO, dm, dO, dO, d.ldp, 1, dmrg);
-    // per-slot part {e | Phi} of the key/value projections and the transpose of its Phi columns
-    add(p->wk + dx, w.Wce, dO, d.de + d.dt, d.ldce, d.ldce, dkv, 1);
-    add(p->wv + dx, w.Wce + (size_t)dO * d.ldce, dO, d.de + d.dt, d.ldce, d.ldce, dkv, 1);
-    add(p->wk + dx + d.de, w.WceT_phi, d.dt, dO, dO, d.ldkv, 1, dkv);
-    add(p->wv + dx + d.de, w.WceT_phi + dO, d.dt, dO, d.ldkv - dO, d.ldkv, 1, dkv);
+    // {e | Phi} columns of W_k, W_v (the slots' own inputs), per head: head h owns output rows [h dh, (h + 1) dh)
+    if (d.de + d.dt > 0) {
+      const int dh = dO / d.H, dc = d.de + d.dt;
+      // row h dcp + c, column h dh + dd  <-  W[h dh + dd, d_x + c]
+      add_bd(p->wk + dx, w.WkcT, dc, dh, d.ldh, 1, dkv, d.dcp, dh, dh * dkv);
+      add_bd(p->wv + dx, w.WvcT, dc, dh, d.ldh, 1, dkv, d.dcp, dh, dh * dkv);
+      // row h dh + dd, column h dcp + c  <-  W[h dh + dd, d_x + c]
+      add_bd(p->wk + dx, w.Wkc, dh, dc, d.ldz, dkv, 1, dh, d.dcp, dh * dkv);
+      add_bd(p->wv + dx, w.Wvc, dh, dc, d.ldz, dkv, 1, dh, d.dcp, dh * dkv);
+    }
     // merge layer, attention-output columns, and their transpose
     add(p->wo, w.Wo_o, dO, dO, d.ldh, d.ldh, dmrg, 1);
     add(p->wo, w.WoT_o, dO, dO, d.ldh, d.ldh, 1, dmrg);
@@ -56,7 +65,7 @@ void prologue_fill(tgnn_ctx* ctx, const tgnn_params* p, const BatchSet* bs, cons
       const int ks = (dO + 15) / 16;
       const size_t blk = (size_t)ks * ks * 256;
       auto add_mfma = [&](const float* src, int which, int srs, int scs) {
-        pa.d[n++] = PackDesc{src, w.rc_pk + which * blk, dO, dO, 0, 0, srs, scs, ks};
+        pa.d[n++] = PackDesc{src, w.rc_pk + which * blk, dO, dO, 0, 0, srs, scs, ks, 0, 0, 0, 0};
       };
       add_mfma(p->wo, 0, dmrg, 1);       // z column n      <- h columns k:      W_o[n, k]
       add_mfma(p->dec_ws, 1, dO, 1);     // hidden column j <- z columns k:      W_s[j, k]

@@ -21,105 +21,25 @@ SortArgs sort_args(tgnn_ctx* ctx, int S) {
 }
 
 // Per-row sums of the slot gradients that reach the per-node projections P = {K | V || q | merge}:
-//   neighbour slot s : dP[row, 0 .. 2 d_o)              += dKV[s - R]
-//   root slot r      : dP[row, half .. half + 2 d_o)     += {dq[r] | dz[r]}          (half = the pitch of dKV)
+//   neighbour slot (r, j) : dP[row, 0 .. 2 d_o)          += {ds[r, h, j] q[r] | p[r, h, j] dO[r]}   (per head h: the
+//                           gradients of the slot's key and value rows, formed here instead of being stored)
+//   root slot r           : dP[row, half .. half + 2 d_o) += {dq[r] | dz[r]}          (half = the pitch of {K | V})
 // One wavefront owns SEG_CHUNK consecutive entries of the row-sorted slot list; runs of one row are summed
 // in registers and leave as one atomic row update per half.
-// Per root and head: Zs = sum_j ds[h][j] CE_j and Zp = sum_j p[h][j] CE_j over the root's neighbour slots (see
-// AttnSums).  One wavefront per root, 16 bytes of a row per lane; a block is four roots.  HM: heads the
-// accumulators are laid out for.
-typedef float zsum_f4 __attribute__((ext_vector_type(4)));
-template <int HM, int NP>
-__device__ __forceinline__ void zsum_root(const AttnSums& a, int r, const float* wv, int lane) {
-  const int HK = a.H * a.k, n4 = a.dcp >> 2;
-  const int c = a.cnt[r];
-  constexpr int NJ = 10;   // rows whose loads are issued together
-  // With NP = 2 a lane takes the 16-byte pieces f0 + lane and f0 + 64 + lane of every row: a row of 65 to 128
-  // pieces (C1: 68) is then one round trip to memory, not two with the second nearly empty.  (NP = 1: the
-  // accumulators for many heads leave no registers for that.)
-  for (int f0 = 0; f0 < n4; f0 += 64 * NP) {
-    const int fa = f0 + lane, fb = f0 + 64 + lane;
-    const bool on_a = fa < n4, on_b = NP > 1 && fb < n4;
-    zsum_f4 as[NP][HM], ap[NP][HM];
-#pragma unroll
-    for (int h = 0; h < HM; ++h)
-#pragma unroll
-      for (int e = 0; e < NP; ++e) as[e][h] = ap[e][h] = zsum_f4{0.f, 0.f, 0.f, 0.f};
-    for (int j0 = 0; j0 < c; j0 += NJ) {
-      zsum_f4 ce[NP][NJ];
-#pragma unroll
-      for (int jj = 0; jj < NJ; ++jj) {
-#pragma unroll
-        for (int e = 0; e < NP; ++e) ce[e][jj] = zsum_f4{0.f, 0.f, 0.f, 0.f};
-        const float* row = a.CE + ((size_t)r * a.k + j0 + jj) * a.ldce;
-        if (on_a && j0 + jj < c) ce[0][jj] = *reinterpret_cast<const zsum_f4*>(row + 4 * fa);
-        if (NP > 1 && on_b && j0 + jj < c) ce[NP - 1][jj] = *reinterpret_cast<const zsum_f4*>(row + 4 * fb);
-      }
-#pragma unroll
-      for (int jj = 0; jj < NJ; ++jj) {
-        if (j0 + jj < c) {
-#pragma unroll
-          for (int h = 0; h < HM; ++h) {
-            if (h < a.H) {
-              const float ws = wv[h * a.k + j0 + jj], wp = wv[HK + h * a.k + j0 + jj];
-#pragma unroll
-              for (int e = 0; e < NP; ++e) {
-                as[e][h] += ws * ce[e][jj];
-                ap[e][h] += wp * ce[e][jj];
-              }
-            }
-          }
-        }
-      }
-    }
-#pragma unroll
-    for (int h = 0; h < HM; ++h) {
-      if (h < a.H) {
-        float* zs = a.Zs + (size_t)r * a.ldz + h * a.dcp;
-        float* zp = a.Zp + (size_t)r * a.ldz + h * a.dcp;
-        if (on_a) {
-          *reinterpret_cast<zsum_f4*>(zs + 4 * fa) = as[0][h];
-          *reinterpret_cast<zsum_f4*>(zp + 4 * fa) = ap[0][h];
-        }
-        if (NP > 1 && on_b) {
-          *reinterpret_cast<zsum_f4*>(zs + 4 * fb) = as[NP - 1][h];
-          *reinterpret_cast<zsum_f4*>(zp + 4 * fb) = ap[NP - 1][h];
-        }
-      }
-    }
-  }
-}
-
-__device__ __forceinline__ void zsum_block(const AttnSums& a, int block) {
-  __shared__ float w_lds[4][2 * TGNN_MAX_HEADS * TGNN_MAX_K];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int HK = a.H * a.k;
-  float* wv = w_lds[wave];
-  // ZSUM_PER_WAVE roots per wavefront, one after the other: the launch this rides in holds two blocks per compute
-  // unit, and with a block per four roots the last of them waited for a free place for half of the launch
-  for (int i = 0; i < ZSUM_PER_WAVE; ++i) {
-    const int r = (block * 4 + wave) * ZSUM_PER_WAVE + i;
-    if (r >= a.R) return;   // per wavefront; no block barrier below
-    for (int p = lane; p < HK; p += 64) {
-      wv[p] = a.ds_out[(size_t)r * HK + p];
-      wv[HK + p] = a.prob[(size_t)r * HK + p];
-    }
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_s_waitcnt(0xc07f);   // the wavefront's LDS writes are visible to all its lanes
-    __builtin_amdgcn_wave_barrier();
-    if (a.H <= 2) zsum_root<2, 2>(a, r, wv, lane);
-    else zsum_root<TGNN_MAX_HEADS, 1>(a, r, wv, lane);
-    __builtin_amdgcn_wave_barrier();   // all lanes are done reading wv before the next root overwrites it
-  }
+// element c < 2 d_o of the gradient of neighbour slot `sl` (= r k + j)
+__device__ __forceinline__ float slot_grad(const SlotGrads& g, int sl, int c) {
+  const int r = sl / g.k, j = sl - r * g.k;
+  if (c < g.dO) return g.dscore[(size_t)r * g.H * g.k + (c / g.dh) * g.k + j] * g.Qroot[(size_t)r * g.ldh + c];
+  const int cc = c - g.dO;
+  return g.prob[(size_t)r * g.H * g.k + (cc / g.dh) * g.k + j] * g.dOmat[(size_t)r * g.ldh + cc];
 }
 
 constexpr int SEG_CHUNK = 16;
 __global__ __launch_bounds__(256) void seg_reduce_kernel(int R, int S, int dO, const int32_t* __restrict__ sort_total,
                                                          const int32_t* __restrict__ sorted,
                                                          const int32_t* __restrict__ sorted_row,
-                                                         const float* __restrict__ dq, const float* __restrict__ dz,
-                                                         int ldh, const float* __restrict__ dKV, int ldkv,
-                                                         float* __restrict__ dP, int ldp, QPhi qphi, AttnSums zs) {
+                                                         SlotGrads sg, int ldkv, float* __restrict__ dP, int ldp,
+                                                         QPhi qphi) {
   int block = blockIdx.x;
   if (qphi.part != nullptr) {   // the first blocks are passengers: gradients through the query's Phi(0)
     const int nq = qphi_blocks(qphi);
@@ -128,14 +48,6 @@ __global__ __launch_bounds__(256) void seg_reduce_kernel(int R, int S, int dO, c
       return;
     }
     block -= nq;
-  }
-  {   // the last blocks, also passengers: the per-root sums for the weight gradients of the {e | Phi} columns
-      // (behind the row sums, which the next launch waits for the longest)
-    const int n_seg = ((S + SEG_CHUNK - 1) / SEG_CHUNK + 3) / 4;
-    if (block >= n_seg) {
-      if (block - n_seg < zsum_blocks(zs)) zsum_block(zs, block - n_seg);
-      return;
-    }
   }
   const int lane = threadIdx.x & 63;
   const int chunk = block * 4 + (threadIdx.x >> 6);
@@ -150,49 +62,78 @@ __global__ __launch_bounds__(256) void seg_reduce_kernel(int R, int S, int dO, c
   const int total = *sort_total;
   if (p0 >= total) return;
   if (p0 + lane >= total) my_slot = my_row = -1;
-  int slots[SEG_CHUNK], rows[SEG_CHUNK];
+  // a neighbour slot's root and position among the root's neighbours: one division per slot, done by the lane that
+  // fetched it, not one per element
+  int my_r = 0, my_j = 0;
+  if (my_slot >= R) {
+    const int sl = my_slot - R;
+    my_r = sl / sg.k;
+    my_j = sl - my_r * sg.k;
+  }
+  int slots[SEG_CHUNK], rows[SEG_CHUNK], rr[SEG_CHUNK], jj[SEG_CHUNK];
 #pragma unroll
   for (int i = 0; i < SEG_CHUNK; ++i) {
-    slots[i] = __shfl(my_slot, i);
-    rows[i] = __shfl(my_row, i);
+    // (readlane: the values are the same for every lane, so they live in scalar registers)
+    slots[i] = __builtin_amdgcn_readlane(my_slot, i);
+    rows[i] = __builtin_amdgcn_readlane(my_row, i);
+    rr[i] = __builtin_amdgcn_readlane(my_r, i);
+    jj[i] = __builtin_amdgcn_readlane(my_j, i);
   }
-  for (int cb = 0; cb < 2 * dO; cb += 256) {   // 256 columns per pass, 4 per lane
-    // all row loads of the chunk are issued before any is consumed
-    float v[SEG_CHUNK][4];
+  const int HK = sg.H * sg.k;
+  for (int cb = 0; cb < dO; cb += 128) {   // 128 columns of each of the two sections per pass, 2 + 2 per lane
+    // this lane's columns (the same in the key / query section and in the value / merge section) and their head's
+    // offset into a root's score gradients and softmax weights
+    int ck[2], hoff[2];
+    bool live[2];
 #pragma unroll
-    for (int i = 0; i < SEG_CHUNK; ++i) {
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int c = cb + lane + 64 * q;
-        float x = 0.f;
-        if (rows[i] >= 0 && c < 2 * dO) {
-          const int slot = slots[i];
-          if (slot < R) x = c < dO ? dq[(size_t)slot * ldh + c] : dz[(size_t)slot * ldh + (c - dO)];
-          else x = dKV[(size_t)(slot - R) * ldkv + c];
-        }
-        v[i][q] = x;
-      }
+    for (int u = 0; u < 2; ++u) {
+      const int c = cb + lane + 64 * u;
+      live[u] = c < dO;
+      ck[u] = live[u] ? c : 0;
+      hoff[u] = (ck[u] / sg.dh) * sg.k;
     }
-    float akv[4] = {0.f, 0.f, 0.f, 0.f}, aqm[4] = {0.f, 0.f, 0.f, 0.f};
+    float aK[2] = {0.f, 0.f}, aV[2] = {0.f, 0.f}, aQ[2] = {0.f, 0.f}, aM[2] = {0.f, 0.f};
     bool any_kv = false, any_qm = false;
     int cur = -1;
     auto flush = [&]() __attribute__((always_inline)) {
       if (cur < 0) return;
+      float* row = dP + (size_t)cur * ldp;
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int c = cb + lane + 64 * q;
-        if (c < 2 * dO) {
-          if (any_kv) atomicAdd(dP + (size_t)cur * ldp + c, akv[q]);
-          if (any_qm) atomicAdd(dP + (size_t)cur * ldp + ldkv + c, aqm[q]);
+      for (int u = 0; u < 2; ++u) {
+        if (live[u]) {
+          if (any_kv) { atomicAdd(row + ck[u], aK[u]); atomicAdd(row + dO + ck[u], aV[u]); }
+          if (any_qm) { atomicAdd(row + ldkv + ck[u], aQ[u]); atomicAdd(row + ldkv + dO + ck[u], aM[u]); }
         }
       }
     };
+    // all row loads of the chunk are issued before any is consumed.  Which arrays a slot reads is uniform over the
+    // wavefront (a root slot: its dq and dz rows; a neighbour slot: its root's q and dO rows with the slot's score
+    // gradient and softmax weight per head: dK = ds q, dV = p dO)
+    float xa[SEG_CHUNK][2], xb[SEG_CHUNK][2], wa[SEG_CHUNK][2], wb[SEG_CHUNK][2];
+#pragma unroll
+    for (int i = 0; i < SEG_CHUNK; ++i) {
+      const bool on = rows[i] >= 0;
+      const bool root = slots[i] < R;
+      const size_t ro = (size_t)(root ? max(slots[i], 0) : rr[i]);
+      const float* pa = (root ? sg.dq : sg.Qroot) + ro * sg.ldh;
+      const float* pb = (root ? sg.dz : sg.dOmat) + ro * sg.ldh;
+      const float* qa = sg.dscore + ro * HK + jj[i];
+      const float* qb = sg.prob + ro * HK + jj[i];
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        const bool ld = on && live[u];
+        xa[i][u] = ld ? pa[ck[u]] : 0.f;
+        xb[i][u] = ld ? pb[ck[u]] : 0.f;
+        wa[i][u] = (ld && !root) ? qa[hoff[u]] : 1.f;
+        wb[i][u] = (ld && !root) ? qb[hoff[u]] : 1.f;
+      }
+    }
 #pragma unroll
     for (int i = 0; i < SEG_CHUNK; ++i) {
       if (rows[i] != cur) {
         flush();
 #pragma unroll
-        for (int q = 0; q < 4; ++q) akv[q] = aqm[q] = 0.f;
+        for (int u = 0; u < 2; ++u) aK[u] = aV[u] = aQ[u] = aM[u] = 0.f;
         any_kv = any_qm = false;
         cur = rows[i];
       }
@@ -200,11 +141,11 @@ __global__ __launch_bounds__(256) void seg_reduce_kernel(int R, int S, int dO, c
         if (slots[i] < R) {
           any_qm = true;
 #pragma unroll
-          for (int q = 0; q < 4; ++q) aqm[q] += v[i][q];
+          for (int u = 0; u < 2; ++u) { aQ[u] += xa[i][u]; aM[u] += xb[i][u]; }
         } else {
           any_kv = true;
 #pragma unroll
-          for (int q = 0; q < 4; ++q) akv[q] += v[i][q];
+          for (int u = 0; u < 2; ++u) { aK[u] += xa[i][u] * wa[i][u]; aV[u] += xb[i][u] * wb[i][u]; }
         }
       }
     }
@@ -212,18 +153,25 @@ __global__ __launch_bounds__(256) void seg_reduce_kernel(int R, int S, int dO, c
   }
 }
 
-void seg_reduce(tgnn_ctx* ctx, int R, int S, const QPhi& qphi, hipStream_t s, const AttnSums& zs) {
+static SlotGrads slot_grads(tgnn_ctx* ctx, int R) {
+  const Dims& d = ctx->d;
+  Ws& w = ctx->w;
+  SlotGrads g;
+  g.dscore = w.dscore; g.prob = w.prob; g.Qroot = w.Qroot; g.dOmat = w.dOmat; g.dq = w.dq; g.dz = w.dz;
+  g.R = R; g.k = d.k; g.H = d.H; g.dO = d.dO; g.dh = d.dO / d.H; g.ldh = d.ldh;
+  return g;
+}
+
+void seg_reduce(tgnn_ctx* ctx, int R, int S, const QPhi& qphi, hipStream_t s) {
   const Dims& d = ctx->d;
   Ws& w = ctx->w;
   const int chunks = (S + SEG_CHUNK - 1) / SEG_CHUNK;
-  hipLaunchKernelGGL(seg_reduce_kernel, dim3((chunks + 3) / 4 + qphi_blocks(qphi) + zsum_blocks(zs)), dim3(256), 0, s, R, S,
-                     d.dO, w.sort_total, w.sorted, w.sorted_row, w.dq, w.dz, d.ldh, w.dKV, d.ldkv, w.dP, d.ldp, qphi, zs);
+  hipLaunchKernelGGL(seg_reduce_kernel, dim3((chunks + 3) / 4 + qphi_blocks(qphi)), dim3(256), 0, s, R, S, d.dO,
+                     w.sort_total, w.sorted, w.sorted_row, slot_grads(ctx, R), d.ldkv, w.dP, d.ldp, qphi);
 }
 
 // slot = row: dP[r] = {0 || dq[r] | dz[r]} for roots, dP[R + j] = {dKV[j] || 0} for neighbour slots
-__global__ __launch_bounds__(256) void slots_to_dp_kernel(int R, int RK, int dO, const float* __restrict__ dq,
-                                                          const float* __restrict__ dz, int ldh,
-                                                          const float* __restrict__ dKV, int ldkv,
+__global__ __launch_bounds__(256) void slots_to_dp_kernel(int R, int RK, int dO, SlotGrads sg, int ldkv,
                                                           float* __restrict__ dP, int ldp, QPhi qphi) {
   int block = blockIdx.x;
   if (qphi.part != nullptr) {   // the first blocks are passengers: gradients through the query's Phi(0)
@@ -240,10 +188,10 @@ __global__ __launch_bounds__(256) void slots_to_dp_kernel(int R, int RK, int dO,
   float x = 0.f;
   if (row < R) {
     const int cc = c - ldkv;
-    if (cc >= 0 && cc < dO) x = dq[(size_t)row * ldh + cc];
-    else if (cc >= dO && cc < 2 * dO) x = dz[(size_t)row * ldh + (cc - dO)];
+    if (cc >= 0 && cc < dO) x = sg.dq[(size_t)row * sg.ldh + cc];
+    else if (cc >= dO && cc < 2 * dO) x = sg.dz[(size_t)row * sg.ldh + (cc - dO)];
   } else if (c < 2 * dO) {
-    x = dKV[(size_t)(row - R) * ldkv + c];
+    x = slot_grad(sg, row - R, c);
   }
   dP[i] = x;
 }
@@ -254,7 +202,7 @@ void slots_to_dp(tgnn_ctx* ctx, int R, int RK, const QPhi& qphi, hipStream_t s) 
   const long long total = (long long)(R + RK) * d.ldp;
   if (total <= 0) return;
   hipLaunchKernelGGL(slots_to_dp_kernel, dim3((int)((total + 255) / 256) + qphi_blocks(qphi)), dim3(256), 0, s, R, RK, d.dO,
-                     w.dq, w.dz, d.ldh, w.dKV, d.ldkv, w.dP, d.ldp, qphi);
+                     slot_grads(ctx, R), d.ldkv, w.dP, d.ldp, qphi);
 }
 
 // debug: per-slot view of per-row data

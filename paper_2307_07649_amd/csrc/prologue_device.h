@@ -20,6 +20,18 @@ __device__ __forceinline__ void prologue_block(const PrologueArgs& a, int bx, in
       }
       return;
     }
+    if (d.nblk > 0) {   // block-diagonal
+      const int per = d.rows * d.cols, total = d.nblk * per;
+      for (int i = bx * blockDim.x + threadIdx.x; i < total; i += nbx * blockDim.x) {
+        const int h = i / per, rc = i - h * per;
+        // consecutive threads walk whichever index is contiguous in the source
+        int r, c;
+        if (d.srs == 1) { c = rc / d.rows; r = rc - c * d.rows; }
+        else { r = rc / d.cols; c = rc - r * d.cols; }
+        d.dst[(size_t)(h * d.brd + r) * d.ldd + h * d.bcd + c] = d.src[(size_t)h * d.bsrc + (size_t)r * d.srs + (size_t)c * d.scs];
+      }
+      return;
+    }
     const int total = d.rows * d.zero_to;
     const float* __restrict__ src = d.src;
     float* __restrict__ dst = d.dst;

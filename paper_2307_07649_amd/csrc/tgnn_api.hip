@@ -105,11 +105,13 @@ static void layout(const Dims& d, Ws& w, Bump& b) {
   w.dgi = b.take<float>(S * d.ld3); w.dgh = b.take<float>(S * d.ld3);
   // node rows of a standalone attention call are its slots, so P / dP hold S rows (a step uses far fewer)
   w.P = b.take<float>(S * d.ldp); w.dP = b.take<float>(S * d.ldp);
-  w.CE = b.take<float>(RK * d.ldce); w.KV = b.take<float>(RK * d.ldkv);
-  w.prob = b.take<float>(R * d.H * d.k); w.Omat = b.take<float>(R * d.ldh); w.z = b.take<float>(R * d.ldh);
-  w.dz = b.take<float>(R * d.ldh); w.dOmat = b.take<float>(R * d.ldh); w.dq = b.take<float>(R * d.ldh);
-  w.dKV = b.take<float>(RK * d.ldkv);
+  w.Umat = b.take<float>(S * d.ldz);
+  w.prob = b.take<float>(R * d.H * d.k); w.Onode = b.take<float>(R * d.ldh); w.Omat = b.take<float>(R * d.ldh);
+  w.z = b.take<float>(R * d.ldh);
+  w.dz = b.take<float>(R * d.ldh); w.dOmat = b.take<float>(R * d.ldh); w.dqn = b.take<float>(R * d.ldh);
+  w.dq = b.take<float>(R * d.ldh); w.Gmat = b.take<float>(R * d.ldz);
   w.Zs = b.take<float>(R * d.ldz); w.Zp = b.take<float>(R * d.ldz); w.Qroot = b.take<float>(R * d.ldh);
+  w.Yt = b.take<float>(R * d.ldy);
   w.dscore = b.take<float>(R * d.H * d.k);
   w.Pdec = b.take<float>(R * d.ldkv); w.dPdec = b.take<float>(R * d.ldkv);
   w.h1 = b.take<float>(B2 * d.ldh); w.logits = b.take<float>(B2);
@@ -117,13 +119,15 @@ static void layout(const Dims& d, Ws& w, Bump& b) {
   w.Wih_p = b.take<float>((size_t)3 * d.dm * d.ldx); w.Whh_p = b.take<float>((size_t)3 * d.dm * d.ldh);
   w.Wdec_p = b.take<float>((size_t)2 * d.dO * d.ldh);
   w.Wx = b.take<float>((size_t)d.ldp * d.ldxr); w.bias_x = b.take<float>((size_t)d.ldp);
-  w.Wce = b.take<float>((size_t)2 * d.dO * d.ldce); w.Wo_o = b.take<float>((size_t)d.dO * d.ldh);
+  w.WkcT = b.take<float>((size_t)d.H * d.dcp * d.ldh + 32); w.WvcT = b.take<float>((size_t)d.H * d.dcp * d.ldh + 32);
+  w.Wkc = b.take<float>((size_t)d.dO * d.ldz); w.Wvc = b.take<float>((size_t)d.dO * d.ldz);
+  w.Wo_o = b.take<float>((size_t)d.dO * d.ldh);
   {
     const size_t ks = (size_t)(d.dO + 15) / 16;
     w.rc_pk = root_chain_fits(d) ? b.take<float>(6 * ks * ks * 256) : nullptr;
   }
   w.WdecT = b.take<float>((size_t)d.dO * d.ldkv); w.WihT_phi = b.take<float>((size_t)d.dt * d.ld3);
-  w.WxT = b.take<float>((size_t)d.dm * d.ldp); w.WceT_phi = b.take<float>((size_t)d.dt * d.ldkv);
+  w.WxT = b.take<float>((size_t)d.dm * d.ldp);
   w.WoT_o = b.take<float>((size_t)d.dO * d.ldh);
   b.take<char>(256);
 }
@@ -193,35 +197,68 @@ static void gru_forward(tgnn_ctx* ctx, const tgnn_params* p, int n, hipStream_t 
   gru_gates_fwd(gru_gates_args(d, n, nullptr, w.gi, w.gh, w.Hm, w.has, w.gates, w.Xrow, d.ldxr, nullptr, nullptr, nullptr, 0), s);
 }
 
-// Attention (Eq. 4-7) and the merge layer, from the node rows ws.Xrow [n_rows] and the per-slot rows ws.CE.
-// Every projection is linear in {x | e | Phi}, and x depends on the node only, so the x part of K, V, q and
-// of the merge layer is one small GEMM over the distinct node rows (ws.P); the per-slot GEMMs add the row of
-// their node in the epilogue.  slot_row maps root slot r and neighbour slot R + r k + j to node rows
-// (NULL: slot = row).  n_rows_dev (may be NULL): device-side row count.
-static void attn_forward(tgnn_ctx* ctx, const tgnn_params* p, int R, int n_rows, const int* n_rows_dev,
-                         const int32_t* slot_row, const int32_t* cnt, StageTimer* tm, hipStream_t s,
-                         const SortArgs& fill = SortArgs(), bool with_merge = true) {
+// What the attention kernels need to know about a call.  slot_row maps root slot r and neighbour slot R + r k + j
+// to node rows (NULL: slot = row).  efeat / neid / dt_in: see FusedAttn.
+struct AttnIn {
+  const int32_t* slot_row;
+  const int32_t* cnt;
+  const float* efeat;
+  const int32_t* neid;
+  const double* dt_in;
+  const tgnn_params* p;
+};
+
+static FusedAttn fused_args(tgnn_ctx* ctx, int R, const AttnIn& in) {
   const Dims& d = ctx->d; Ws& w = ctx->w;
-  const int RK = R * d.k;
+  FusedAttn a;
+  memset(&a, 0, sizeof(a));
+  a.R = R; a.k = d.k; a.H = d.H; a.dO = d.dO; a.dh = d.dO / d.H; a.de = d.de; a.dt = d.dt; a.dcp = d.dcp;
+  a.ldz = d.ldz; a.ldh = d.ldh; a.ldp = d.ldp; a.ldy = d.ldy; a.off_q = d.ldkv; a.dt_source = d.dt_source;
+  a.force_generic = (ctx->cfg.flags & TGNN_FLAG_GENERIC_ATTN) != 0;
+  a.P = w.P; a.U = w.Umat; a.slot_row = in.slot_row; a.cnt = in.cnt; a.efeat = in.efeat; a.neid = in.neid;
+  a.root_t = w.root_t; a.nts = w.nts; a.tau = w.tau; a.dt_in = in.dt_in;
+  a.time_w = in.p->time_w; a.time_b = in.p->time_b; a.dtk = w.dtk; a.prob = w.prob;
+  a.Onode = w.Onode; a.Zp = w.Zp; a.dOmat = w.dOmat; a.G = w.Gmat;
+  a.dscore = w.dscore; a.dqn = w.dqn; a.Zs = w.Zs; a.Y = w.Yt; a.Qroot = w.Qroot;
+  return a;
+}
+
+// Attention (Eq. 4-7) and the merge layer, from the node rows ws.Xrow [n_rows].  Every projection is linear in
+// {x | e | Phi}, and x depends on the node only, so the x part of K, V, q and of the merge layer is one GEMM over the
+// distinct node rows (ws.P).  The {e | Phi} part never becomes a key or value row (k_attn.hip): the scores need
+// U = q (W_k^c) per head (a second GEMM over the node rows), the output is the kernel's node part plus Zp (W_v^c)^T
+// (a GEMM over the roots).  n_rows_dev (may be NULL): device-side row count.
+static void attn_forward(tgnn_ctx* ctx, const tgnn_params* p, int R, int n_rows, const int* n_rows_dev, const AttnIn& in,
+                         StageTimer* tm, hipStream_t s, const SortArgs& fill = SortArgs(), bool with_merge = true) {
+  const Dims& d = ctx->d; Ws& w = ctx->w;
+  const bool slot_part = d.de + d.dt > 0;   // (always: d_t > 0)
   if (tm) tm->begin(9);
   const NtProblem node_part = nt_live(nt_problem(w.Xrow, d.ldxr, w.Wx, d.ldxr, w.bias_x, w.P, d.ldp, n_rows,
                                                  d.ldkv + 2 * d.dO, d.ldxr, d.ldp, false, n_rows_dev), d.dx);
   gemm_nt_group(&node_part, 1, s);
   if (tm) { tm->end(9); tm->begin(8); }
-  RowAdd kv_add;
-  kv_add.src = w.P; kv_add.ld = d.ldp; kv_add.index = slot_row ? slot_row + R : nullptr; kv_add.row0 = R;
-  const NtProblem slot_part = nt_live(nt_problem(w.CE, d.ldce, w.Wce, d.ldce, nullptr, w.KV, d.ldkv, RK, 2 * d.dO, d.ldce,
-                                                 d.ldkv, false, nullptr, kv_add), d.de + d.dt);
-  gemm_nt_group(&slot_part, 1, s);
-  if (tm) { tm->end(8); tm->begin(10); }
-  attn_core_fwd(d, R, w.P + d.ldkv, d.ldp, slot_row, w.KV, d.ldkv, cnt, w.prob, w.Omat, d.ldh, s, fill);
-  if (!with_merge) {   // the caller's next launch holds the merge layer
-    if (tm) tm->end(10);
-    return;
+  if (slot_part) {   // U = q (W_k^c)_h per head: A is the q section of P (its pad columns meet zero columns of the weights)
+    const NtProblem u = nt_live(nt_problem(w.P + d.ldkv, d.ldp, w.WkcT, d.ldh, nullptr, w.Umat, d.ldz, n_rows, d.H * d.dcp,
+                                           d.ldh, d.ldz, false, n_rows_dev), d.dO);
+    gemm_nt_group(&u, 1, s);
   }
-  if (tm) { tm->end(10); tm->begin(11); }
+  if (tm) { tm->end(8); tm->begin(10); }
+  FusedAttn fa = fused_args(ctx, R, in);
+  fa.fill = fill;
+  fattn_fwd(fa, s);
+  if (tm) { tm->end(10); tm->begin(7); }
+  {   // attention output = node part + Zp (W_v^c)^T
+    RowAdd add;
+    add.src = w.Onode; add.ld = d.ldh; add.index = nullptr; add.row0 = 0;
+    const NtProblem o = nt_live(nt_problem(w.Zp, d.ldz, w.Wvc, d.ldz, nullptr, w.Omat, d.ldh, R, d.dO, d.ldz, d.ldh, false,
+                                           nullptr, add), d.H * d.dcp);
+    gemm_nt_group(&o, 1, s);
+  }
+  if (tm) tm->end(7);
+  if (!with_merge) return;   // the caller's next launch holds the merge layer
+  if (tm) tm->begin(11);
   RowAdd m_add;
-  m_add.src = w.P + d.ldkv + d.dO; m_add.ld = d.ldp; m_add.index = slot_row; m_add.row0 = 0;
+  m_add.src = w.P + d.ldkv + d.dO; m_add.ld = d.ldp; m_add.index = in.slot_row; m_add.row0 = 0;
   gemm_nt(w.Omat, d.ldh, w.Wo_o, d.ldh, nullptr, w.z, d.ldh, R, d.dO, d.ldh, d.ldh, true, s, nullptr, m_add);
   if (tm) tm->end(11);
 }
@@ -235,67 +272,53 @@ static QPhi qphi_args(tgnn_ctx* ctx, const tgnn_params* p, tgnn_params* g) {
   return q;
 }
 
-// The product that carries dKV on to the keys' time encoding, with the reduction to the gradients of the
-// time-encoding parameters as its epilogue.
-static NtProblem keys_phi_problem(tgnn_ctx* ctx, const tgnn_params* p, tgnn_params* g, int RK) {
-  const Dims& d = ctx->d; Ws& w = ctx->w;
-  TimeGradOut tg;
-  tg.delta = w.dtk; tg.w = p->time_w; tg.b = p->time_b; tg.g_w = g->time_w; tg.g_b = g->time_b;
-  return nt_live(nt_problem(w.dKV, d.ldkv, w.WceT_phi, d.ldkv, nullptr, nullptr, d.ldt, RK, d.dt, d.ldkv, d.ldt, false,
-                            nullptr, RowAdd(), tg), 2 * d.dO);
-}
-
-// From ws.dz (already masked by the merge ReLU) down to ws.dKV and ws.dq; queues the weight-gradient GEMMs of
-// W_o (attention-output columns) and of the {e | Phi} columns of W_k, W_v, and adds the column sums of dq to
+// From ws.dz (already masked by the merge ReLU) down to ws.dq, ws.dscore and the per-root sums; queues the
+// weight-gradient GEMMs of W_o (attention-output columns) and of the {e | Phi} columns of W_k, W_v, and the column
+// sums that give the gradients of the time-encoding parameters through the keys; adds the column sums of dq to
 // ws.q_part, which the caller cleared (consumed by qphi_block in a later launch).
-// phi_now: launch the product onto the keys' time encoding here; otherwise the caller launches it (together
-// with another one).
-static void attn_backward(tgnn_ctx* ctx, tgnn_params* g, const tgnn_params* p, int R, const int32_t* slot_row,
-                          const int32_t* cnt, TnBatch& tn, Side& side, bool phi_now, hipStream_t s,
-                          bool have_dOmat = false, AttnSums* sums_later = nullptr) {
+static void attn_backward(tgnn_ctx* ctx, tgnn_params* g, const tgnn_params* p, int R, const AttnIn& in, TnBatch& tn,
+                          Side& side, hipStream_t s, StageTimer* tm, bool have_dOmat = false) {
   const Dims& d = ctx->d; Ws& w = ctx->w;
-  const int RK = R * d.k;
   tn.add(w.dz, d.ldh, w.Omat, d.ldh, R, d.dO, d.dO, single_out(g->wo, d.dO + d.dx, nullptr));
   if (!have_dOmat) gemm_nt(w.dz, d.ldh, w.WoT_o, d.ldh, nullptr, w.dOmat, d.ldh, R, d.dO, d.ldh, d.ldh, false, s);
-  // Weight gradients of the {e | Phi} columns of W_k, W_v: per head, dK_j = ds_j q and dV_j = p_j dO, so
-  // sum over slots of dK_j CE_j^T = sum over roots of q (sum_j ds_j CE_j)^T: the attention backward kernel leaves the
-  // inner sums per root and head, and the products run over R rows instead of R k.
-  const bool by_root = d.de + d.dt > 0;
-  AttnSums zs;
-  if (by_root) {
-    zs.CE = w.CE; zs.ldce = d.ldce; zs.dcols = d.de + d.dt; zs.dcp = d.dcp; zs.ldz = d.ldz;
-    zs.Zs = w.Zs; zs.Zp = w.Zp; zs.Qroot = w.Qroot;
-    if (sums_later != nullptr && !side.on) {   // the caller's next launch takes the sums (zsum_block); with the side
-                                               // stream the products that need them start before that launch
-      zs.later = true; zs.ds_out = w.dscore; zs.prob = w.prob; zs.cnt = cnt; zs.R = R; zs.k = d.k; zs.H = d.H;
-      *sums_later = zs;
-    }
+  if (tm) tm->begin(19);
+  {   // G = dO (W_v^c)_h per head
+    const NtProblem gm = nt_live(nt_problem(w.dOmat, d.ldh, w.WvcT, d.ldh, nullptr, w.Gmat, d.ldz, R, d.H * d.dcp, d.ldh,
+                                            d.ldz, false), d.dO);
+    gemm_nt_group(&gm, 1, s);
   }
-  attn_core_bwd(d, R, w.P + d.ldkv, d.ldp, slot_row, w.KV, d.ldkv, cnt, w.prob, w.dOmat, d.ldh, w.dq, w.dKV, w.q_part, s,
-                zs);
-  if (by_root) {
-    OutMap m;
-    memset(&m, 0, sizeof(m));
-    m.n_split = 1 << 30; m.k_split = 1 << 30;
-    m.head_n = d.dO / d.H; m.head_k = d.dcp; m.head_cols = d.de + d.dt;
-    m.p[0][0] = g->wk + d.dx; m.ld[0][0] = d.dkv;
-    tn.add(w.Qroot, d.ldh, w.Zs, d.ldz, R, d.dO, d.H * d.dcp, m);
-    m.p[0][0] = g->wv + d.dx;
-    tn.add(w.dOmat, d.ldh, w.Zp, d.ldz, R, d.dO, d.H * d.dcp, m);
-  } else if (d.de + d.dt > 0) {
-    OutMap kv;
-    memset(&kv, 0, sizeof(kv));
-    kv.p[0][0] = g->wk + d.dx; kv.p[1][0] = g->wv + d.dx; kv.ld[0][0] = kv.ld[1][0] = d.dkv;
-    kv.n_split = d.dO; kv.k_split = 1 << 30;
-    tn.add(w.dKV, d.ldkv, w.CE, d.ldce, RK, 2 * d.dO, d.de + d.dt, kv);
+  if (tm) { tm->end(19); tm->begin(14); }
+  fattn_bwd(fused_args(ctx, R, in), s);
+  if (tm) { tm->end(14); tm->begin(5); }
+  {   // dq = node part + Zs (W_k^c)^T, with its column sums over the roots (for the query's Phi(0))
+    RowAdd add;
+    add.src = w.dqn; add.ld = d.ldh; add.index = nullptr; add.row0 = 0;
+    NtProblem dq = nt_live(nt_problem(w.Zs, d.ldz, w.Wkc, d.ldz, nullptr, w.dq, d.ldh, R, d.dO, d.ldz, d.ldh, false, nullptr,
+                                      add), d.H * d.dcp);
+    dq.colsum = w.q_part; dq.colsum_rows = QPHI_BLOCKS;
+    gemm_nt_group(&dq, 1, s);
+  }
+  if (tm) tm->end(5);
+  // Weight gradients of the {e | Phi} columns of W_k, W_v: per head, dK_j = ds_j q and dV_j = p_j dO, so
+  // sum over slots of dK_j c_j^T = sum over roots of q Zs^T, and likewise dO Zp^T: products over R rows, not R k.
+  OutMap m;
+  memset(&m, 0, sizeof(m));
+  m.n_split = 1 << 30; m.k_split = 1 << 30;
+  m.head_n = d.dO / d.H; m.head_k = d.dcp; m.head_cols = d.de + d.dt;
+  m.p[0][0] = g->wk + d.dx; m.ld[0][0] = d.dkv;
+  tn.add(w.Qroot, d.ldh, w.Zs, d.ldz, R, d.dO, d.H * d.dcp, m);
+  m.p[0][0] = g->wv + d.dx;
+  tn.add(w.dOmat, d.ldh, w.Zp, d.ldz, R, d.dO, d.H * d.dcp, m);
+  {   // gradients of the time-encoding parameters through the keys: column sums of the per-root sums Y = {d/dw | d/db}
+    OutMap y;
+    memset(&y, 0, sizeof(y));
+    y.n_split = d.dt; y.k_split = 1 << 30;
+    y.bias[0] = g->time_w; y.bias[1] = g->time_b;
+    tn.add(w.Yt, d.ldy, w.Yt, d.ldy, R, 2 * d.dt, 0, y);
   }
   if (side.on) {   // the bulk of the weight-gradient work is known here: start it beside the rest of the chain
     side.fork();
     tn.launch(side.c->side);
-  }
-  if (phi_now) {
-    const NtProblem pr = keys_phi_problem(ctx, p, g, RK);
-    gemm_nt_group(&pr, 1, s);
   }
 }
 
@@ -391,8 +414,8 @@ int32_t tgnn_create(const tgnn_config* cfg, tgnn_ctx** out) {
   d.H = cfg->n_heads; d.k = cfg->k; d.nrep = cfg->n_replicas; d.maxB = cfg->max_batch; d.dt_source = cfg->dt_source;
   d.d_in = 2 * d.dm + d.dt + d.de; d.dx = d.dm + d.ds; d.dq = d.dx + d.dt; d.dkv = d.dx + d.de + d.dt; d.dO = d.dm;
   d.ldx = padrow(d.d_in); d.ldh = padrow(d.dm); d.ld3 = padrow(3 * d.dm); d.ldxr = padrow(d.dx);
-  d.ldce = padrow(d.de + d.dt); d.ldkv = padrow(2 * d.dO); d.ldp = 2 * d.ldkv; d.ldt = padrow(d.dt);
-  d.dcp = (d.de + d.dt + 3) & ~3; d.ldz = padrow(d.H * d.dcp);
+  d.ldkv = padrow(2 * d.dO); d.ldp = 2 * d.ldkv; d.ldt = padrow(d.dt);
+  d.dcp = (d.de + d.dt + 3) & ~3; d.ldz = padrow(d.H * d.dcp); d.ldy = padrow(2 * d.dt);
   const int nb = d.nrep < TGNN_MAX_BATCHES ? d.nrep : TGNN_MAX_BATCHES;
   const long long maxEv = (long long)d.maxB * nb;
   if (maxEv * 3 * (1 + d.k) > 0x3fffffffLL) {
@@ -581,14 +604,10 @@ int32_t tgnn_temporal_attn_fwd(tgnn_ctx* ctx, const tgnn_params* p, int32_t n_ro
   prologue(ctx, p, nullptr, nullptr, nullptr, nullptr, s);
   TGNN_HIP_CHECK(hipMemcpyAsync(w.cnt, cnt, sizeof(int32_t) * n_roots, hipMemcpyDeviceToDevice, s));
   stage_x_rows(n_roots, d.k, d.dx, x_root, x_nbr, cnt, w.Xrow, d.ldxr, s);
-  CeArgs a;
-  memset(&a, 0, sizeof(a));
-  a.efeat = e_nbr; a.neid = nullptr; a.cnt = cnt; a.dt_in = dt_nbr;
-  a.time_w = p->time_w; a.time_b = p->time_b;
-  a.CE = w.CE; a.ldce = d.ldce; a.dtk = w.dtk;
-  a.R = n_roots; a.k = d.k; a.de = d.de; a.dt = d.dt; a.dt_source = 0;
-  assemble_ce(a, s);
-  attn_forward(ctx, p, n_roots, n_roots * (1 + d.k), nullptr, nullptr, w.cnt, nullptr, s);
+  // the caller's rows have to stay as they are until the backward call (the slots' inputs are read again there)
+  ctx->last_attn = AttnCall{e_nbr, dt_nbr};
+  const AttnIn in{nullptr, w.cnt, e_nbr, nullptr, dt_nbr, p};
+  attn_forward(ctx, p, n_roots, n_roots * (1 + d.k), nullptr, in, nullptr, s);
   TGNN_HIP_CHECK(hipMemcpy2DAsync(out_z, (size_t)d.dO * 4, w.z, (size_t)d.ldh * 4, (size_t)d.dO * 4, n_roots,
                                   hipMemcpyDeviceToDevice, s));
   TGNN_LAUNCH_CHECK();
@@ -613,7 +632,8 @@ int32_t tgnn_temporal_attn_bwd(tgnn_ctx* ctx, const tgnn_params* p, int32_t n_ro
   TnBatch tn;
   Side side{ctx, s, false};
   const int RK = n_roots * d.k;
-  attn_backward(ctx, grads, p, n_roots, nullptr, w.cnt, tn, side, true, s);
+  const AttnIn in{nullptr, w.cnt, ctx->last_attn.e_nbr, nullptr, ctx->last_attn.dt_nbr, p};
+  attn_backward(ctx, grads, p, n_roots, in, tn, side, s, nullptr);
   slots_to_dp(ctx, n_roots, RK, qphi_args(ctx, p, grads), s);
   node_proj_backward(ctx, grads, n_roots + RK, nullptr, tn, false, s);
   tn.launch(s);
@@ -909,7 +929,7 @@ static int enqueue_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
                         const BatchSet& bs, float lr, float* out_loss, float* out_logits, int32_t* out_winner,
                         hipStream_t s) {
   const Dims& d = ctx->d; Ws& w = ctx->w;
-  const int R = 3 * bs.total, RK = R * d.k, S = R + RK, B2 = 2 * bs.total;
+  const int R = 3 * bs.total, S = R * (1 + d.k), B2 = 2 * bs.total;
 
   StageTimer tm{ctx, s};
   Side side{ctx, s, (ctx->cfg.flags & TGNN_FLAG_SIDE_STREAM) != 0};
@@ -952,26 +972,17 @@ static int enqueue_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
     gemm_nt_group(pr, 2, s);
   }
   tm.end(4);
-  // attention + merge
-  CeArgs aa;
-  memset(&aa, 0, sizeof(aa));
-  aa.efeat = g->efeat; aa.neid = w.neid; aa.cnt = w.cnt; aa.slot_row = w.slot_row;
-  aa.root_t = w.root_t; aa.nts = w.nts; aa.tau_nbr = w.tau; aa.dt_in = nullptr;
-  aa.time_w = p->time_w; aa.time_b = p->time_b;
-  aa.CE = w.CE; aa.ldce = d.ldce; aa.dtk = w.dtk;
-  aa.R = R; aa.k = d.k; aa.de = d.de; aa.dt = d.dt; aa.dt_source = d.dt_source;
-  // The GRU gates (with the scan of the slot sort) and the per-slot attention input do not depend on each other:
-  // one launch, the gates in its first blocks.
-  aa.gru = gru_gates_args(d, U, w.ucount, w.gi, w.gh, w.Hm, w.has, w.gates, w.Xrow, d.ldxr, d.ds ? st->stat : nullptr,
-                          w.ulist, w.dP, d.ldp, sort_args(ctx, S));
-  tm.begin(7);
-  assemble_ce(aa, s);
-  tm.end(7);
-  // (the fill pass of the slot sort, needed by the backward pass only, rides in the softmax-attention launch)
+  // The GRU gates (with the scan of the slot sort) -> node rows x = {s' | static}
+  tm.begin(6);
+  gru_gates_fwd(gru_gates_args(d, U, w.ucount, w.gi, w.gh, w.Hm, w.has, w.gates, w.Xrow, d.ldxr, d.ds ? st->stat : nullptr,
+                               w.ulist, w.dP, d.ldp, sort_args(ctx, S)), s);
+  tm.end(6);
+  // (the fill pass of the slot sort, needed by the backward pass only, rides in the attention launch)
   // Merge layer, decoder + loss and their backward pass down to the attention output are local to an event's
   // three roots: one launch when the layer width allows it.
   const bool chain = root_chain_fits(d);
-  attn_forward(ctx, p, R, U, w.ucount, w.slot_row, w.cnt, &tm, s, sort_args(ctx, S), !chain);
+  const AttnIn ain{w.slot_row, w.cnt, g->efeat, w.neid, nullptr, p};
+  attn_forward(ctx, p, R, U, w.ucount, ain, &tm, s, sort_args(ctx, S), !chain);
 
   tm.begin(12);
   if (chain) {
@@ -1010,17 +1021,11 @@ static int enqueue_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
     gemm_nt(w.dPdec, d.ldkv, w.WdecT, d.ldkv, nullptr, w.dz, d.ldh, R, d.dO, d.ldkv, d.ldh, false, s, nullptr, gate);
     tm.end(13);
   }
-  tm.begin(14);
-  AttnSums sums;
-  attn_backward(ctx, grads, p, R, w.slot_row, w.cnt, tn, side, false, s, chain, &sums);
-  tm.end(14);
+  attn_backward(ctx, grads, p, R, ain, tn, side, s, &tm, chain);
   tm.begin(15);
   // per-row sum of the slot gradients reaching the per-node projections (the query's Phi(0) gradients ride along)
-  seg_reduce(ctx, R, S, qphi_args(ctx, p, grads), s, sums);
-  {  // the product onto the keys' time encoding is independent of this chain: it shares the launch
-    const NtProblem keys_phi = keys_phi_problem(ctx, p, grads, RK);
-    node_proj_backward(ctx, grads, U, w.ucount, tn, true, s, &keys_phi);
-  }
+  seg_reduce(ctx, R, S, qphi_args(ctx, p, grads), s);
+  node_proj_backward(ctx, grads, U, w.ucount, tn, true, s);
   tm.end(15);
   tn.add(w.dgi, d.ld3, w.X, d.ldx, U, 3 * d.dm, d.d_in, single_out(grads->gru_wih, d.d_in, grads->gru_bih), w.ucount);
   tn.add(w.dgh, d.ld3, w.Hm, d.ldh, U, 3 * d.dm, d.dm, single_out(grads->gru_whh, d.dm, grads->gru_bhh), w.ucount);

@@ -21,12 +21,12 @@ struct Dims {
   int ldh;    // rows of width d_m
   int ld3;    // rows of width 3 d_m
   int ldxr;   // node rows x = {s' | static}
-  int ldce;   // per-slot key/value input rows {e | Phi}
   int ldkv;   // rows of width 2 d_o  (K | V), also decoder input {z_a | z_b}
   int ldp;    // per-node projections {K | V || q | merge}: two halves of pitch ldkv
   int ldt;    // rows of width d_t
-  int dcp;    // d_e + d_t rounded up to 4: a head's block of a row of Zs / Zp
+  int dcp;    // d_e + d_t rounded up to 4: a head's block of a row of U / G / Zs / Zp
   int ldz;    // rows of width H * dcp
+  int ldy;    // rows of width 2 d_t: a root's time-encoding gradient sums {d/dw | d/db}
   int maxEv, maxR, maxRK, maxS, maxU;
 };
 
@@ -49,7 +49,7 @@ struct Ws {
   double* nts;                                 // [R,k]
   int32_t *slot_gid, *slot_node, *has;         // [S]
   double *tau, *delta;                         // [S]
-  double* dtk;                                 // [R*k] time difference in the keys
+  double* dtk;                                 // [R*k] time difference in the keys (Eq. 5-6), kept for the backward pass
   unsigned long long* winkey;                  // [nrep*N] write-back arbitration: (epoch << 33) | occurrence key
   unsigned long long* epoch;                   // [1] bumped once per step, makes stale winkey entries lose
   // distinct (replica, node) rows of the step
@@ -67,27 +67,29 @@ struct Ws {
   float *X, *Hm, *gi, *gh, *gates;             // [S,ldx] [S,ldh] [S,ld3] [S,ld3] [S,4*ldh]
   float* Xrow;                                 // [S,ldxr] x = {s' | static} per distinct node (row)
   float *dgi, *dgh;                            // [S,ld3] [S,ld3]
-  // attention.  The projections of x are taken once per distinct node (P), the projections of {e | Phi}
-  // per neighbour slot (CE); a slot's key/value is the sum of the two.
+  // attention.  The projections of x = {s' | static} are taken once per distinct node (P); the slots' own
+  // inputs {e | Phi} never leave the attention kernels, which work with per-root vectors instead (k_attn.hip).
   float *P, *dP;                               // [S,ldp]
-  float *CE, *KV, *prob, *Omat, *z;            // [RK,ldce] [RK,ldkv] [R,H*k] [R,ldh] [R,ldh]
-  float *dz, *dOmat, *dq, *dKV;                // [R,ldh] [R,ldh] [R,ldh] [RK,ldkv]
+  float *Umat;                                 // [S,ldz] per node row and head: (W_k^c)_h^T q_h
+  float *prob, *Onode, *Omat, *z;              // [R,H*k] [R,ldh] node part of the attention output [R,ldh] [R,ldh]
+  float *dz, *dOmat, *dqn, *dq;                // [R,ldh] x 4 (dqn: node part of dq)
+  float *Gmat;                                 // [R,ldz] per root and head: (W_v^c)_h^T dO_h
   float *Zs, *Zp, *Qroot;                      // [R,ldz] x 2 (per head: sums of the slots' {e | Phi} rows), [R,ldh]
+  float *Yt;                                   // [R,ldy] per root: time-encoding gradient sums of its keys
   float *dscore;                               // [R,H*k] gradients of the attention scores
   // decoder
   float *Pdec, *dPdec, *h1, *logits;           // [R,ldkv] [R,ldkv] [2B,ldh] [2B]
   float* loss_acc;                                   // [TGNN_MAX_BATCHES] per-batch loss sums
-  // standalone-call staging
-  float *x_root_s, *x_nbr_s;                         // unused placeholders
   // packed weights
   float *Wih_p, *Whh_p, *Wdec_p;
   float *Wx, *bias_x;       // [ldkv + 2 d_o, ldxr] rows {W_k ; W_v ; 0 ; W_q ; W_o} restricted to the x columns; [ldp]
-  float *Wce;               // [2 d_o, ldce] {W_k ; W_v} restricted to the {e | Phi} columns
+  // {e | Phi} columns of W_k, W_v, block-diagonal over the heads (off-diagonal blocks stay zero):
+  float *WkcT, *WvcT;       // [H dcp, ldh]  row h dcp + c, column d of head h: W[d, d_x + c]   (U = q WkcT^T, G = dO WvcT^T)
+  float *Wkc, *Wvc;         // [d_o, ldz]    row d of head h, column h dcp + c: W[d, d_x + c]   (dq += Zs Wkc^T, O += Zp Wvc^T)
   float *Wo_o;              // [d_o, ldh] W_o restricted to the attention-output columns
   float *rc_pk;             // six [d_o, d_o] blocks in MFMA B-operand order for the root chain (NULL: it does not fit)
   float *WdecT, *WihT_phi;
   float *WxT;               // [d_m, ldp]   transposed Wx, dynamic columns only
-  float *WceT_phi;          // [d_t, ldkv]  transposed Wce, time-encoding columns only
   float *WoT_o;             // [d_o, ldh]   transposed Wo_o
 };
 
@@ -125,8 +127,17 @@ struct StepGraph {
 };
 }  // namespace tgnn
 
+namespace tgnn {
+// what the last tgnn_temporal_attn_fwd was given and tgnn_temporal_attn_bwd reads again
+struct AttnCall {
+  const float* e_nbr = nullptr;
+  const double* dt_nbr = nullptr;
+};
+}  // namespace tgnn
+
 struct tgnn_ctx {
   tgnn::Profiler prof;
+  tgnn::AttnCall last_attn;
   hipStream_t side = nullptr;      // second stream for work that is off the critical path of a step
   hipEvent_t fork_ev[16] = {};     // fork/join events between the caller's stream and `side`
   int next_ev = 0;
@@ -236,6 +247,10 @@ struct NtProblem {
   RowAdd add;
   TimeGradOut tg;
   GruBwdOut gb;
+  // optional: the column sums of the stored tile are added to colsum[(tile & (colsum_rows - 1)) * N + n]
+  // (colsum_rows partial rows, a power of two, keep the float atomics of different tiles apart)
+  float* colsum;
+  int colsum_rows;
 };
 struct NtGroup {
   NtProblem p[2];
@@ -250,7 +265,7 @@ inline NtProblem nt_problem(const float* A, int lda, const float* B, int ldb, co
   NtProblem p;
   p.A = A; p.B = B; p.bias = bias; p.C = C; p.lda = lda; p.ldb = ldb; p.ldc = ldc; p.M = M; p.N = N; p.Kp = Kp;
   p.n_store = n_store; p.relu = relu ? 1 : 0; p.k_live = 0; p.m_dev = m_dev; p.col_tiles = 0; p.wg_begin = 0;
-  p.add = add; p.tg = tg; p.gb = gb;
+  p.add = add; p.tg = tg; p.gb = gb; p.colsum = nullptr; p.colsum_rows = 1;
   return p;
 }
 // the same problem with its live column count stated
@@ -316,6 +331,9 @@ struct PackDesc {
   // src[(16 cb + li) * srs + (16 s + 4 lg + c) * scs], zero beyond rows / cols: a wavefront then reads the operand
   // of one MFMA slab as 1 KB of contiguous memory.
   int mfma_ks;
+  // nblk > 0: block-diagonal instead (zero_to, mfma_ks unused).  For block h < nblk, r < rows, c < cols:
+  // dst[(h * brd + r) * ldd + h * bcd + c] = src[h * bsrc + r * srs + c * scs]; nothing else is written.
+  int nblk, brd, bcd, bsrc;
 };
 constexpr int MAX_PACK = 32;
 struct PrologueArgs {
@@ -426,29 +444,16 @@ struct SortArgs {
   int32_t* total = nullptr;                           // number of sorted slots (= rowptr[*ucount])
 };
 SortArgs sort_args(tgnn_ctx* ctx, int S);
-// dP[row] += {dKV[slot] | 0} of the row's neighbour slots and {0 | dq[r] | dz[r]} of its root slots
-// Optional extra outputs of the attention backward pass (Zs == NULL: none): per root and head, the sums of its
-// slots' {e | Phi} rows CE weighted by the score gradients (Zs) and by the softmax weights (Zp), rows of H blocks
-// of dcp floats (dcols of them used); and the root's query row (Qroot, pitch of dq).
-// later == true: the kernel only stores the score gradients (ds_out [R, H k]) and Qroot, and the sums are taken
-// by zsum_block in a later launch, where they are spread over more wavefronts.
-struct AttnSums {
-  const float* CE = nullptr;
-  int ldce = 0, dcols = 0, dcp = 0, ldz = 0;
-  float *Zs = nullptr, *Zp = nullptr, *Qroot = nullptr;
-  bool later = false;
-  float* ds_out = nullptr;
-  const float* prob = nullptr;   // softmax weights [R, H k] (for zsum_block)
-  const int32_t* cnt = nullptr;
-  int R = 0, k = 0, H = 0;
+// Per-row sums of the slot gradients that reach the per-node projections: for a neighbour slot (r, j) the gradient
+// of its key / value rows is formed on the fly, dK = ds[r, h, j] q[r], dV = p[r, h, j] dO[r] per head h.
+struct SlotGrads {
+  const float *dscore, *prob;     // [R, H k]
+  const float *Qroot, *dOmat;     // [R, ldh]
+  const float *dq, *dz;           // [R, ldh] gradients of the root's own query row and of its merge-layer row
+  int R, k, H, dO, dh, ldh;
 };
-// blocks of 256 threads; ZSUM_PER_WAVE roots per wavefront
-constexpr int ZSUM_PER_WAVE = 2;
-__host__ __device__ inline int zsum_blocks(const AttnSums& a) {
-  return a.later && a.Zs != nullptr ? (a.R + 4 * ZSUM_PER_WAVE - 1) / (4 * ZSUM_PER_WAVE) : 0;
-}
-// qphi, zs: ride along in the first blocks (see QPhi; AttnSums with later == true)
-void seg_reduce(tgnn_ctx* ctx, int R, int S, const QPhi& qphi, hipStream_t s, const AttnSums& zs = AttnSums());
+// qphi: rides along in the first blocks (see QPhi)
+void seg_reduce(tgnn_ctx* ctx, int R, int S, const QPhi& qphi, hipStream_t s);
 // the same with slot = row (standalone attention call): plain stores, every row of dP written
 void slots_to_dp(tgnn_ctx* ctx, int R, int RK, const QPhi& qphi, hipStream_t s);
 void expand_rows(tgnn_ctx* ctx, int S, const float* src, int ld, const double* src_d, float* dst, double* dst_d,
@@ -507,33 +512,32 @@ struct GatherArgs {
 };
 void gather_rows(const GatherArgs& a, hipStream_t s);
 
-// Per neighbour slot (r, j): CE row {e_vw | Phi(dt)} (Eq. 5-6 without the node part) and the time difference
-// itself (kept for the backward pass).
-struct CeArgs {
-  const float* efeat;                   // [E, de], or [R*k, de] when neid == NULL
-  const int32_t *neid, *cnt;
-  const int32_t* slot_row;              // non-NULL: tau_nbr is indexed by slot_row[R + slot]
-  const double *root_t, *nts, *tau_nbr;
-  const double* dt_in;                  // non-NULL: time differences given directly [R*k]
-  const float *time_w, *time_b;
-  float* CE;  int ldce;
-  double* dtk;
-  int R, k, de, dt, dt_source;
-  GruFwdArgs gru;                       // gru.gi != NULL: the first gru_total_blocks(gru) blocks of the launch run the GRU gates instead
-};
-void assemble_ce(const CeArgs& a, hipStream_t s);
 // Standalone attention call: node rows from the caller's x_root / x_nbr (rows of absent neighbours zeroed).
 void stage_x_rows(int R, int k, int dx, const float* x_root, const float* x_nbr, const int32_t* cnt, float* Xrow,
                   int ldxr, hipStream_t s);
 
 // ---- k_attn.hip ---------------------------------------------------------------------
-// q of root r is q[qrow * ldq_ ...] with qrow = slot_row ? slot_row[r] : r.
-void attn_core_fwd(const Dims& d, int R, const float* q, int ldq_, const int32_t* slot_row, const float* KV, int ldkv,
-                   const int32_t* cnt, float* prob, float* Omat, int ldo, hipStream_t s,
-                   const SortArgs& fill = SortArgs());
-void attn_core_bwd(const Dims& d, int R, const float* q, int ldq_, const int32_t* slot_row, const float* KV, int ldkv,
-                   const int32_t* cnt, const float* prob, const float* dOmat, int ldo, float* dq, float* dKV, float* q_part,
-                   hipStream_t s, const AttnSums& zs = AttnSums());
+// Arguments of the attention kernels (Eq. 4-7 forward and backward; see k_attn.hip).  Root r's node row is
+// slot_row[r], neighbour slot (r, j)'s is slot_row[R + r k + j] (slot_row == NULL: row = slot).
+struct FusedAttn {
+  int R, k, H, dO, dh, de, dt, dcp, ldz, ldh, ldp, ldy, off_q, dt_source, force_generic;
+  const float* P;            // node rows {K | V || q | merge}, pitch ldp; q at column off_q
+  const float* U;            // [rows, ldz]
+  const int32_t *slot_row, *cnt;
+  const float* efeat;        // [E, d_e]; or [R k, d_e] when neid == NULL
+  const int32_t* neid;       // [R, k] edge-feature row of every slot
+  const double *root_t, *nts, *tau;   // query times [R], edge times [R, k], update times per node row
+  const double* dt_in;       // non-NULL: time differences given directly [R k]
+  const float *time_w, *time_b;
+  double* dtk;               // [R k] time differences: written by the forward pass, read by the backward pass
+  float* prob;               // [R, H k] softmax weights
+  float *Onode, *Zp;         // forward out: node part of the attention output [R, ldh], per-head sums [R, ldz]
+  const float *dOmat, *G;    // backward in: gradient of the attention output [R, ldh], G [R, ldz]
+  float *dscore, *dqn, *Zs, *Y, *Qroot;   // backward out
+  SortArgs fill;             // forward only, fill.ucnt != NULL: the first blocks run the fill pass of the slot sort
+};
+void fattn_fwd(const FusedAttn& a, hipStream_t s);
+void fattn_bwd(const FusedAttn& a, hipStream_t s);
 
 // ---- k_decoder.hip ------------------------------------------------------------------
 void decoder_pairs(const Dims& d, const BatchSet* bs, int total, const float* Pdec, int ldp, const float* b1,

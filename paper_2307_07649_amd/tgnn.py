@@ -25,6 +25,7 @@ FLAG_OVERWRITE_GRADS = 1
 FLAG_SIDE_STREAM = 2
 FLAG_NO_GRAPH = 4
 FLAG_WIDE_ROOT_TILES = 8
+FLAG_GENERIC_ATTN = 16
 
 
 class tgnn_config(C.Structure):

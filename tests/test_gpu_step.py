@@ -45,10 +45,11 @@ def test_c0_edge_time_variant():
     run_sequence(P, 12, check_at=(0, 11), dt_source=1)
 
 
-@pytest.mark.parametrize("own_stream,flags", [(False, 0), (True, 2), (True, 4), (True, 6), (True, 8)])
+@pytest.mark.parametrize("own_stream,flags", [(False, 0), (True, 2), (True, 4), (True, 6), (True, 8), (True, 16)])
 def test_launch_modes_agree_with_the_oracle(own_stream, flags):
     """NULL stream (direct launches); captured graph with the side stream; no graph; no graph with the side stream;
-    16 events per workgroup in the root chain (small steps take 5 by default).
+    16 events per workgroup in the root chain (small steps take 5 by default); the attention kernels' generic code
+    path on a shape that fits their register-resident one.
     (The default, a captured single-stream graph, is what every other test runs.)"""
     P = make_problem("C0", random_phase=True)
     run_sequence(P, 12, lr=0.05, check_at=(0, 5, 11), own_stream=own_stream, flags=flags)
@@ -64,6 +65,10 @@ def test_launch_modes_agree_with_the_oracle(own_stream, flags):
     dict(n_nodes=60, E=300, d_mem=132, d_time=12, d_edge=7, d_static=0, n_heads=2, k=5, batch=50),
     # the root chain at its widest (8 column blocks), ragged 16-event tiles
     dict(n_nodes=60, E=300, d_mem=128, d_time=12, d_edge=7, d_static=3, n_heads=4, k=5, batch=50),
+    # slot inputs wider than the attention kernels keep in registers (d_e > 192, d_t > 128), two heads, k = 10
+    dict(n_nodes=80, E=600, d_mem=32, d_time=130, d_edge=200, d_static=0, n_heads=2, k=10, batch=60),
+    # the register-resident attention path at its limits: d_e = 192, d_t = 128, d_o = 128, one head
+    dict(n_nodes=80, E=600, d_mem=128, d_time=128, d_edge=192, d_static=0, n_heads=1, k=10, batch=60),
 ])
 def test_odd_shapes(shape):
     P = custom_problem(**shape)
