@@ -63,6 +63,8 @@ extern "C" {
 #define TGNN_MAX_BATCHES 16  /* mini-batches (memory replicas) per tgnn_train_step call */
 #define TGNN_MAX_STEPS_PER_CALL 8 /* consecutive training steps per tgnn_train_steps call */
 #define TGNN_MAX_HEADS 8
+#define TGNN_NOALLOC_MAX_NODES 262144   /* tgnn_memory_writeback_noalloc: nodes its static scratch array covers (2 MiB) */
+#define TGNN_NOALLOC_MAX_EVENTS 1048576 /* ... and events per call */
 
 typedef struct tgnn_ctx tgnn_ctx;
 
@@ -193,6 +195,20 @@ int32_t tgnn_memory_writeback(tgnn_ctx* ctx, tgnn_state* st, int32_t replica, co
                               const int32_t* dst, const int32_t* eid, const double* t, int32_t n_events,
                               const float* s_new_src, const float* s_new_dst, const double* tau_src,
                               const double* tau_dst, int32_t* out_winner, void* stream);
+
+/* For callers that cannot allocate device memory -- code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc: tgnn_memory_writeback for ONE memory replica without a context.  It allocates nothing
+ * (no hipMalloc / hipFree, no allocating library call): the arbitration words live in a static device array of the
+ * library, 8 bytes per node, 2 MiB + 1 KiB per GPU, held until the process ends.  `st` describes the replica to write
+ * (arrays of n_nodes rows; st->stat is not used); all other arguments, the results and out_winner are as in
+ * tgnn_memory_writeback, bit for bit.  Three kernel launches on `stream`, no memset, no synchronisation.
+ * TGNN_E_OUT_OF_RANGE: n_nodes > TGNN_NOALLOC_MAX_NODES, n_events > TGNN_NOALLOC_MAX_EVENTS or a device ordinal >= 64.
+ * Every call on a GPU shares that GPU's array (it keeps the last call's contents; each call clears the words of its
+ * node range first): calls that overlap in time on one GPU, also from different streams or threads, race -- order them. */
+int32_t tgnn_memory_writeback_noalloc(int32_t n_nodes, int32_t d_mem, tgnn_state* st, const int32_t* src,
+                                      const int32_t* dst, const int32_t* eid, const double* t, int32_t n_events,
+                                      const float* s_new_src, const float* s_new_dst, const double* tau_src,
+                                      const double* tau_dst, int32_t* out_winner, void* stream);
 
 /* The whole step for n_batches mini-batches (one per memory replica, distinct replicas) that share one
  * weight set: sample -> gather -> UPDT for root and supporting nodes -> attention -> decoder ->

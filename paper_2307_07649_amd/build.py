@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libtgnn.so")
 SOURCES = ["tgnn_api.hip", "k_unique.hip", "k_gemm.hip", "k_misc.hip", "k_sample.hip", "k_gather.hip", "k_gru.hip", "k_attn.hip",
-           "k_decoder.hip", "k_writeback.hip", "k_rootchain.hip"]
+           "k_decoder.hip", "k_writeback.hip", "k_rootchain.hip", "k_static.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-munsafe-fp-atomics", "-ffp-contract=fast",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-function"]

@@ -66,6 +66,7 @@ _SIGS = {
     "tgnn_temporal_attn_fwd": (_I, [_P, C.POINTER(tgnn_params), _I, _P, _P, _P, _P, _P, _P, _P]),
     "tgnn_temporal_attn_bwd": (_I, [_P, C.POINTER(tgnn_params), _I, _P, C.POINTER(tgnn_params), _P, _P, _P]),
     "tgnn_memory_writeback": (_I, [_P, C.POINTER(tgnn_state), _I, _P, _P, _P, _P, _I, _P, _P, _P, _P, _P, _P]),
+    "tgnn_memory_writeback_noalloc": (_I, [_I, _I, C.POINTER(tgnn_state), _P, _P, _P, _P, _I, _P, _P, _P, _P, _P, _P]),
     "tgnn_train_step": (_I, [_P, C.POINTER(tgnn_graph), C.POINTER(tgnn_state), C.POINTER(tgnn_params),
                              C.POINTER(tgnn_params), C.POINTER(tgnn_batch), _I, C.c_float, _P, _P, _P, _P]),
     "tgnn_train_steps": (_I, [_P, C.POINTER(tgnn_graph), C.POINTER(tgnn_state), C.POINTER(tgnn_params),
@@ -122,6 +123,16 @@ def tgnn_debug_copy(dst, src):
     """dst[:] = src through the library's plain copy kernel (HBM-traffic counter calibration)."""
     assert dst.numel() * dst.element_size() == src.numel() * src.element_size()
     _check(_lib.tgnn_debug_copy(_ptr(dst), _ptr(src), src.numel() * src.element_size(), _stream()))
+
+
+def tgnn_memory_writeback_noalloc(st, src, dst, eid, t, s_src, s_dst, tau_src, tau_dst, out_winner):
+    """st: a State of one replica; out_winner: int32 device tensor [2 n] (preallocated by the caller: the call
+    itself allocates nothing)."""
+    n_nodes, d_mem = st.mem.shape
+    _check(_lib.tgnn_memory_writeback_noalloc(n_nodes, d_mem, C.byref(st.c), _ptr(src), _ptr(dst), _ptr(eid), _ptr(t),
+                                              src.numel(), _ptr(s_src), _ptr(s_dst), _ptr(tau_src), _ptr(tau_dst),
+                                              _ptr(out_winner), _stream()))
+    return out_winner
 
 
 class Graph:
