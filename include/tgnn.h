@@ -221,7 +221,11 @@ int32_t tgnn_memory_writeback_noalloc(int32_t n_nodes, int32_t d_mem, tgnn_state
  *   out_loss   device scalar, mean over the batches of loss_b;
  *   out_logits [2 * sum n] or NULL; batch b at offset 2 * (events before b): n positive then n negative;
  *   out_winner [2 * sum n] or NULL; as in tgnn_memory_writeback, per batch.
- * Each batches[b].n <= max_batch, n_batches <= min(n_replicas, TGNN_MAX_BATCHES). */
+ * Each batches[b].n <= max_batch, n_batches <= min(n_replicas, TGNN_MAX_BATCHES).
+ * Node ids in the batch arrays live on the device and cannot be validated by the host: an id outside [0, n_nodes) is
+ * computed as node 0 (no access leaves the arrays), is never written back, and is counted; the running count is item 9
+ * of tgnn_debug_read.  Event ids must lie in [0, graph.n_events), and the temporal CSR must be the one
+ * tgnn_build_tcsr produces for these n_nodes (not checked). */
 int32_t tgnn_train_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, const tgnn_params* p,
                         tgnn_params* grads, const tgnn_batch* batches, int32_t n_batches, float lr,
                         float* out_loss, float* out_logits, int32_t* out_winner, void* stream);
@@ -280,7 +284,8 @@ int32_t tgnn_debug_copy(void* dst, const void* src, int64_t n_bytes, void* strea
 /* Debug/parity access to what the last tgnn_train_step left in the workspace.  `what`:
  * 0 nbr [R,k] i32, 1 eid [R,k] i32, 2 nts [R,k] f64, 3 cnt [R] i32, 4 s_new [R(1+k), d_m] f32,
  * 5 tau [R(1+k)] f64, 6 z [R, d_o] f32, 7 decoder hidden layer [2 sum n, d_o] f32, 8 the number of distinct
- * (replica, node) rows of the step [1] i32.  Copies n_bytes (device to device) into dst on `stream`. */
+ * (replica, node) rows of the step [1] i32, 9 the number of batch node ids outside [0, n_nodes) seen by all training
+ * steps of the context so far [1] i32.  Copies n_bytes (device to device) into dst on `stream`. */
 int32_t tgnn_debug_read(tgnn_ctx* ctx, int32_t what, void* dst, int64_t n_bytes, void* stream);
 
 #ifdef __cplusplus

@@ -41,6 +41,10 @@ __device__ __forceinline__ void sample_block(const SampleArgs& a, const BatchSet
       const int32_t* nodes = role == 0 ? bs.b[b].src : role == 1 ? bs.b[b].dst : bs.b[b].neg;
       node = nodes[i];
       t = bs.b[b].t[i];
+      // an id outside [0, N) in the caller's batch arrays: the root is computed as node 0 (every index stays in
+      // range), takes no part in the write-back, and is counted for the caller to see
+      const bool bad = node < 0 || node >= N;
+      if (bad) node = 0;
       rep_base = bs.b[b].replica * N;
       root_gid = rep_base + node;
       if (lane == 0) {
@@ -48,7 +52,8 @@ __device__ __forceinline__ void sample_block(const SampleArgs& a, const BatchSet
         a.root_t[r] = t;
         a.slot_gid[r] = root_gid;
         a.slot_node[r] = node;
-        if (role < 2) atomicMax(a.winkey + root_gid, wb_key(ep, ev_off + i, role));
+        if (bad) atomicAdd(a.bad_ids, 1);
+        else if (role < 2) atomicMax(a.winkey + root_gid, wb_key(ep, ev_off + i, role));
       }
     } else {
       node = a.q_node[r];
@@ -153,7 +158,7 @@ void head_fill(tgnn_ctx* ctx, const tgnn_graph* g, int n_roots, const tgnn_param
   h.sa = sample_args(d, g, n_roots);
   h.sa.out_nbr = w.nbr; h.sa.out_eid = w.neid; h.sa.out_ts = w.nts; h.sa.out_cnt = w.cnt;
   h.sa.root_node = w.root_node; h.sa.root_t = w.root_t; h.sa.slot_gid = w.slot_gid; h.sa.slot_node = w.slot_node;
-  h.sa.winkey = w.winkey;
+  h.sa.winkey = w.winkey; h.sa.bad_ids = w.bad_ids;
   h.sa.uq = UniqPtrs{w.utag, w.epoch, w.uidx, w.ucount, w.ulist, w.ucnt};
   h.sample_blocks = (n_roots + SAMPLE_WAVES - 1) / SAMPLE_WAVES;
   h.pro_bx = 12;   // blocks of 1024 threads per grid row of the prologue (C1: 12 measured best of 2 .. 48; 24: +1.6 us per step)

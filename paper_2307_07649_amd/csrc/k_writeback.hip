@@ -16,6 +16,7 @@ __global__ void wb_mark_kernel(const BatchSet* __restrict__ bsp, int N, unsigned
   if (!occ_decode(bs, blockIdx.x * blockDim.x + threadIdx.x, b, i, role)) return;
   const BatchDesc& bd = bs.b[b];
   const int node = role ? bd.dst[i] : bd.src[i];
+  if (node < 0 || node >= N) return;   // an id outside the node range takes no part in the write-back
   atomicMax(winkey + (size_t)bd.replica * N + node, wb_key(*epoch, bd.ev_off + i, role));
 }
 

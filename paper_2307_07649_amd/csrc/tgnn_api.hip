@@ -90,6 +90,7 @@ static void layout(const Dims& d, Ws& w, Bump& b) {
   w.tau = b.take<double>(S); w.delta = b.take<double>(S); w.dtk = b.take<double>(RK);
   w.winkey = b.take<unsigned long long>((size_t)d.nrep * d.N);
   w.epoch = b.take<unsigned long long>(1);
+  w.bad_ids = b.take<int32_t>(1);
   const size_t NG = (size_t)d.nrep * d.N, U = d.maxU;
   w.utag = b.take<unsigned long long>(NG); w.uidx = b.take<int32_t>(NG); w.ucount_pair = b.take<int32_t>(2); w.ucount = w.ucount_pair;
   w.ulist = b.take<int32_t>(U); w.slot_row = b.take<int32_t>(S); w.ucnt = b.take<int32_t>(U);
@@ -650,16 +651,14 @@ static int make_batchset(const tgnn_ctx* ctx, const tgnn_batch* batches, int n_b
     return set_error(TGNN_E_INVALID_ARG, "n_batches = %d outside [1, %d]", n_batches, cap);
   memset(&bs, 0, sizeof(bs));
   int off = 0;
-  unsigned seen = 0;
   for (int b = 0; b < n_batches; ++b) {
     const tgnn_batch& tb = batches[b];
     if (tb.n < 0 || tb.n > d.maxB) return set_error(TGNN_E_OUT_OF_RANGE, "batch %d: n = %d outside [0, %d]", b, tb.n, d.maxB);
     if (tb.replica < 0 || tb.replica >= d.nrep)
       return set_error(TGNN_E_OUT_OF_RANGE, "batch %d: replica %d outside [0, %d)", b, tb.replica, d.nrep);
-    if (tb.replica < 32) {
-      if (seen & (1u << tb.replica)) return set_error(TGNN_E_INVALID_ARG, "replica %d appears twice in one step", tb.replica);
-      seen |= 1u << tb.replica;
-    }
+    for (int b2 = 0; b2 < b; ++b2)
+      if (batches[b2].replica == tb.replica)
+        return set_error(TGNN_E_INVALID_ARG, "replica %d appears twice in one step", tb.replica);
     if (tb.n > 0) {
       REQ_PTR(tb.src); REQ_PTR(tb.dst); REQ_PTR(tb.eid); REQ_PTR(tb.t);
     }
@@ -1119,6 +1118,7 @@ int32_t tgnn_debug_read(tgnn_ctx* ctx, int32_t what, void* dst, int64_t n_bytes,
     case 2: src = w.nts; cap = sizeof(double) * d.maxRK; break;
     case 3: src = w.cnt; cap = sizeof(int32_t) * d.maxR; break;
     case 8: src = w.ucount; cap = sizeof(int32_t); break;
+    case 9: src = w.bad_ids; cap = sizeof(int32_t); break;
     case 5: break;
     case 4: case 6: case 7: break;
     default: return set_error(TGNN_E_INVALID_ARG, "unknown item %d", what);

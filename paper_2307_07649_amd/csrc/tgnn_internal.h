@@ -52,6 +52,7 @@ struct Ws {
   double* dtk;                                 // [R*k] time difference in the keys (Eq. 5-6), kept for the backward pass
   unsigned long long* winkey;                  // [nrep*N] write-back arbitration: (epoch << 33) | occurrence key
   unsigned long long* epoch;                   // [1] bumped once per step, makes stale winkey entries lose
+  int32_t* bad_ids;                            // [1] batch node ids outside [0, N) seen by the steps so far
   // distinct (replica, node) rows of the step
   unsigned long long* utag;                    // [nrep*N] epoch of the last step that claimed the node
   int32_t *uidx, *ucount, *ulist;              // [nrep*N] row of a claimed node; [1] number of rows; [maxU] row -> gid
@@ -398,6 +399,7 @@ struct SampleArgs {
   double* root_t;
   int32_t *slot_gid, *slot_node;
   unsigned long long* winkey;
+  int32_t* bad_ids;        // counter of batch node ids outside [0, N) (fused form only)
   UniqPtrs uq;
 };
 struct HeadArgs {

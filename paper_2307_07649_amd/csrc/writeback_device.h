@@ -27,8 +27,9 @@ __device__ __forceinline__ void wb_scatter_block(const WbArgs& a, int block) {
   if (!occ_decode(bs, o, b, i, role)) return;
   const BatchDesc& bd = bs.b[b];
   const int node = role ? bd.dst[i] : bd.src[i];
-  const size_t gid = (size_t)bd.replica * a.N + node;
-  const bool win = a.winkey[gid] == wb_key(*a.epoch, bd.ev_off + i, role);
+  const bool in_range = node >= 0 && node < a.N;   // an id outside the node range is never written
+  const size_t gid = (size_t)bd.replica * a.N + (in_range ? node : 0);
+  const bool win = in_range && a.winkey[gid] == wb_key(*a.epoch, bd.ev_off + i, role);
   if (lane == 0 && a.out_winner) a.out_winner[o] = win ? 1 : 0;
   if (!win) return;
   const float *self_row, *other_row;

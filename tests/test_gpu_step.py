@@ -162,3 +162,32 @@ def test_several_steps_per_call_agree_with_the_oracle(per_call, flags):
     compare_state(G.state_np(), Or.states[0], label="state")
     for n, v in G.params.numpy().items():
         assert rel_err(v, Or.p[n]) <= 1e-4, n
+
+
+def test_node_ids_outside_the_range_are_counted_and_never_written():
+    """Batch node ids live on the device, where the host cannot validate them: an id outside [0, n_nodes) is computed
+    as node 0, wins no write-back, and is counted (tgnn_debug_read item 9); the rest of the step is unaffected in the
+    sense that every other occurrence is arbitrated and written as usual."""
+    import torch
+    P = custom_problem(n_nodes=50, E=300, d_mem=16, d_time=8, d_edge=4, d_static=0, n_heads=2, k=5, batch=60)
+    d = P["d"]
+    G = GpuSide(P)
+    for s in range(2):
+        G.step([batch_np(P, s * 60, (s + 1) * 60)], want=False)
+    b = {k_: v.copy() for k_, v in batch_np(P, 120, 180).items()}
+    b["src"][3] = d.n_nodes + 5; b["dst"][7] = -2; b["neg"][1] = 10 ** 6; b["dst"][11] = d.n_nodes
+    before = G.state_np()
+    g = G.step([b])
+    cnt = torch.zeros(1, dtype=torch.int32, device="cuda")
+    G.ctx.tgnn_debug_read(9, cnt)
+    assert int(cnt.item()) == 4
+    assert np.isfinite(g["loss"]) and np.all(np.isfinite(g["logits"]))
+    win = g["winner"]                                   # [src occurrences | dst occurrences]
+    assert win[3] == 0 and win[60 + 7] == 0 and win[60 + 11] == 0
+    after = G.state_np()
+    valid = np.concatenate([np.delete(b["src"], 3), np.delete(b["dst"], [7, 11])])
+    touched = np.zeros(d.n_nodes, bool); touched[valid] = True
+    assert win.sum() == touched.sum()
+    for name in before:
+        assert np.array_equal(before[name][~touched], after[name][~touched]), name
+    assert np.all(after["mail_eid"][touched] >= 120)
