@@ -63,6 +63,7 @@ extern "C" {
 #define TGNN_MAX_BATCHES 16  /* mini-batches (memory replicas) per tgnn_train_step call */
 #define TGNN_MAX_STEPS_PER_CALL 8 /* consecutive training steps per tgnn_train_steps call */
 #define TGNN_MAX_HEADS 8
+#define TGNN_MAX_NEG_SETS 8  /* negative-destination sets per event in tgnn_train_step_epoch_parallel */
 #define TGNN_NOALLOC_MAX_NODES 262144   /* tgnn_memory_writeback_noalloc: nodes its static scratch array covers (2 MiB) */
 #define TGNN_NOALLOC_MAX_EVENTS 1048576 /* ... and events per call */
 
@@ -75,6 +76,8 @@ typedef struct {
   int32_t dt_source;  /* time difference in the attention keys (Eq. 5-6): 0 = query time minus the update
                          time of the neighbour's memory as used (the paper's wording), 1 = minus the edge time */
   int32_t flags;      /* TGNN_FLAG_* bits */
+  int32_t max_neg_sets; /* largest number of negative-destination sets a step carries (tgnn_train_step_epoch_parallel);
+                           0 or 1: one, the plain step.  The workspace grows with it. */
 } tgnn_config;
 
 /* Temporal CSR: node v's incident events (both directions) are entries indptr[v] .. indptr[v+1]-1 of
@@ -229,6 +232,22 @@ int32_t tgnn_memory_writeback_noalloc(int32_t n_nodes, int32_t d_mem, tgnn_state
 int32_t tgnn_train_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, const tgnn_params* p,
                         tgnn_params* grads, const tgnn_batch* batches, int32_t n_batches, float lr,
                         float* out_loss, float* out_logits, int32_t* out_winner, void* stream);
+
+/* Epoch parallelism on one GPU (Sec. 3.2.2): the work of n_neg_sets trainers that train the SAME positive mini-batch
+ * with different sampled negative destinations, in one step.  The inputs of the positive roots (memory, mails,
+ * neighbours) are fetched, updated (UPDT) and embedded once and shared by all sets; every set adds its n negative roots
+ * and its n pairs (src_i, neg_{g,i}); memory and mails are written once (the paper: only the first trainer writes).
+ * batches[b].neg holds the sets one after the other, [n_neg_sets, n].  Roots per batch: [src | dst | neg set 0 | ... ].
+ *   loss       mean over the sets of each set's loss (1 / 2n) (sum softplus(-logit+) + sum softplus(logit-_g));
+ *   grads      gradient of the SUM of the sets' losses (what the trainers' gradient all-reduce would deliver), +=;
+ *   out_logits [(1 + n_neg_sets) * sum n] or NULL; per batch: n true pairs, then n pairs per set.
+ * n_neg_sets = 1 is tgnn_train_step.  1 <= n_neg_sets <= config.max_neg_sets <= TGNN_MAX_NEG_SETS, else
+ * TGNN_E_OUT_OF_RANGE.  The multi-GPU schedule staggers the sets over consecutive iterations (each trainer then sees
+ * weights one update newer); running them in one step is the same work at the same shapes with one weight set. */
+int32_t tgnn_train_step_epoch_parallel(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, const tgnn_params* p,
+                                       tgnn_params* grads, const tgnn_batch* batches, int32_t n_batches,
+                                       int32_t n_neg_sets, float lr, float* out_loss, float* out_logits,
+                                       int32_t* out_winner, void* stream);
 
 /* n_steps consecutive training steps (Sec. 3.2.1: mini-batches are trained in chronological order, each step
  * reading the memory the step before it wrote) in one call: the same sequence of launches, with the same results

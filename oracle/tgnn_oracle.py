@@ -282,28 +282,34 @@ def _softplus(x):
 
 def decoder_loss(p, z_src, z_dst, z_neg):
     """logit(a, b) = w2 . ReLU(W_s z_a + W_d z_b + b1) + b2 for the B true pairs and the B pairs with a
-    sampled negative destination; loss = mean of softplus(-logit+) and softplus(logit-) over 2B."""
+    sampled negative destination; loss = mean of softplus(-logit+) and softplus(logit-) over 2B.
+    z_neg may hold J sets of B negative destinations, [J B, d] (epoch parallelism, Sec. 3.2.2: J trainers share the
+    positive batch and differ in their negatives): logits are [B true | B per set], the loss is the mean over the
+    sets of each set's loss (the true pairs belong to every set)."""
     B = z_src.shape[0]
-    a = np.concatenate([z_src, z_src], 0); b = np.concatenate([z_dst, z_neg], 0)
+    J = z_neg.shape[0] // B if B else 1
+    a = np.concatenate([z_src] * (1 + J), 0); b = np.concatenate([z_dst, z_neg], 0)
     hpre = a @ p["dec_ws"].T + b @ p["dec_wd"].T + p["dec_b1"]
     h1 = np.maximum(hpre, 0.0)
     logits = h1 @ p["dec_w2"] + p["dec_b2"][0]
-    y = np.concatenate([np.ones(B), np.zeros(B)])
-    loss = (_softplus(-logits[:B]).sum() + _softplus(logits[B:]).sum()) / (2 * B) if B else 0.0
-    return loss, logits, dict(a=a, b=b, hpre=hpre, h1=h1, y=y)
+    y = np.concatenate([np.ones(B), np.zeros(J * B)])
+    loss = (_softplus(-logits[:B]).sum() + _softplus(logits[B:]).sum() / J) / (2 * B) if B else 0.0
+    return loss, logits, dict(a=a, b=b, hpre=hpre, h1=h1, y=y, J=J)
 
 
 def decoder_bwd(p, cache, logits, loss_scale=1.0, gate_h=None):
     """gate_h (bool [2B, d_o], optional): the ReLU gate of the hidden layer to use instead of hpre > 0 (see
     attention_bwd)."""
-    B2 = logits.shape[0]; B = B2 // 2
+    J = cache["J"]; B = logits.shape[0] // (1 + J)
     g = {}
-    dl = (_sigmoid(logits) - cache["y"]) / B2 * loss_scale
+    # gradient of the SUM of the J sets' losses (each a mean over its 2B pairs): a true pair is in every set
+    dl = (_sigmoid(logits) - cache["y"]) / (2 * B) * loss_scale
+    dl[:B] *= J
     g["dec_w2"] = cache["h1"].T @ dl; g["dec_b2"] = np.array([dl.sum()])
     dh = dl[:, None] * p["dec_w2"][None, :] * ((cache["hpre"] > 0) if gate_h is None else gate_h)
     g["dec_ws"] = dh.T @ cache["a"]; g["dec_wd"] = dh.T @ cache["b"]; g["dec_b1"] = dh.sum(0)
     da = dh @ p["dec_ws"]; db = dh @ p["dec_wd"]
-    return g, da[:B] + da[B:], db[:B], db[B:]
+    return g, da.reshape(1 + J, B, da.shape[1]).sum(0), db[:B], db[B:]
 
 
 # --------------------------------------------------------------------------------------
@@ -339,11 +345,12 @@ def forward_backward(state, graph, efeat, static, p, batch, k, n_heads, dt_sourc
     instead selects sample_recent_indexed).  batch = dict(src, dst, neg, eid, t).  Returns dict(loss,
     logits, grads, nbr, neid, nts, cnt, s_new, tau, z, ...).  Does not modify `state`.
     relu_gates = (gate_z, gate_h), optional: see attention_bwd / decoder_bwd."""
-    src, dst, neg = (np.asarray(batch[n], np.int64) for n in ("src", "dst", "neg"))
+    src, dst = (np.asarray(batch[n], np.int64) for n in ("src", "dst"))
+    neg = np.asarray(batch["neg"], np.int64).reshape(-1)        # J sets of B negative destinations, one after the other
     t = np.asarray(batch["t"], F)
-    B = len(src); R = 3 * B
+    B = len(src); J = len(neg) // B if B else 1; R = (2 + J) * B
     d_m = state["mem"].shape[1]; d_t = p["time_w"].shape[0]
-    root_node = np.concatenate([src, dst, neg]); root_t = np.concatenate([t, t, t])
+    root_node = np.concatenate([src, dst, neg]); root_t = np.concatenate([t] * (2 + J))
     if isinstance(graph, dict):
         nbr, neid, nts, cnt = sample_recent(graph["src"], graph["dst"], graph["ts"], root_node, root_t, k)
     else:

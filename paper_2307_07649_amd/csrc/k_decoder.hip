@@ -4,8 +4,9 @@
 // (one MFMA GEMM, Pdec = z {W_s ; W_d}^T) and a pair only adds two rows: the source's W_s z is shared by its
 // true and its negative pair.  Backward, the pair kernel leaves per root the gradient of its row of Pdec; the
 // GEMM that maps it back to z applies the ReLU gate of the merge layer in its epilogue.
-// Row layout of the 2n pairs of batch b (events before it: off): rows 2*off + i are the true pairs
-// (src_i, dst_i), rows 2*off + n + i the pairs (src_i, neg_i); roots 3*off + {0, n, 2n} + i are src, dst, neg.
+// Row layout of the (1 + J) n pairs of batch b (events before it: off; J negative sets): rows (1 + J) off + i are the
+// true pairs (src_i, dst_i), rows (1 + J) off + (1 + g) n + i the pairs (src_i, neg_{g,i}); roots (2 + J) off +
+// {0, n, 2n, ...} + i are src, dst, neg set 0, ...
 #include "tgnn_internal.h"
 #include "device_math.h"
 
@@ -44,59 +45,70 @@ __global__ __launch_bounds__(256) void dec_pair_kernel(const BatchSet* __restric
     ww[q] = c < dO ? w2[c] : 0.f;
   }
   const float b2v = b2[0];
+  const int nneg = bs.nneg;
   for (int ev = blockIdx.x * 4 + wave; ev < bs.total; ev += gridDim.x * 4) {
     const int b = batch_of_row(bs, ev, 1);
     const int off = bs.b[b].ev_off, n = bs.b[b].n;
     const int i = ev - off;
-    const size_t ra = (size_t)(3 * off + i) * ldp, rb = ra + (size_t)n * ldp, rc = rb + (size_t)n * ldp;
-    float hp[4], hn[4];
-    float ap = 0.f, an = 0.f;
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const int c = lane + 64 * q;
-      hp[q] = hn[q] = 0.f;
-      if (c < dO) {
-        const float ps = Pdec[ra + c] + bb[q];
-        hp[q] = fmaxf(ps + Pdec[rb + dO + c], 0.f);
-        hn[q] = fmaxf(ps + Pdec[rc + dO + c], 0.f);
-      }
-      ap += hp[q] * ww[q];
-      an += hn[q] * ww[q];
-    }
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-      ap += __shfl_xor(ap, o);
-      an += __shfl_xor(an, o);
-    }
-    const float lp = ap + b2v, ln = an + b2v;
+    const size_t ra = (size_t)((2 + nneg) * off + i) * ldp;   // the source's row; the partner of pair g is n (1 + g) rows on
     const float inv = 1.0f / (2.0f * (float)n);
-    // loss terms softplus(-lp) and softplus(ln)
-    const float spp = fmaxf(-lp, 0.f) + log1pf(expf(-fabsf(lp)));
-    const float spn = fmaxf(ln, 0.f) + log1pf(expf(-fabsf(ln)));
-    const float dlp = (1.0f / (1.0f + expf(-lp)) - 1.0f) * inv;   // d(sum_b loss_b) / d logit
-    const float dln = (1.0f / (1.0f + expf(-ln))) * inv;
-    const int row_p = 2 * off + i, row_n = row_p + n;
-    if (lane == 0) {
-      logits[row_p] = lp;
-      logits[row_n] = ln;
-      lsum += (spp + spn) * inv / (float)bs.nb;
-      gb += dlp + dln;
+    float ps[4], dsrc[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int c = lane + 64 * q;
+      ps[q] = c < dO ? Pdec[ra + c] + bb[q] : 0.f;
     }
+    float lterm = 0.f;
+    // pair 0 is the true pair (src, dst); pair 1 + g pairs the source with the negative destination of set g.  With
+    // nneg sets the step stands for nneg trainers that share the positive batch (Sec. 3.2.2): the loss is the mean of
+    // their losses, the gradient that of their sum, so the true pair counts nneg times in the gradient.
+    for (int pr = 0; pr <= nneg; ++pr) {
+      const size_t rb = ra + (size_t)(1 + pr) * n * ldp;
+      float h[4], acc = 0.f;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int c = lane + 64 * q;
+        h[q] = c < dO ? fmaxf(ps[q] + Pdec[rb + dO + c], 0.f) : 0.f;
+        acc += h[q] * ww[q];
+      }
+#pragma unroll
+      for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o);
+      const float lg = acc + b2v;
+      const float sgm = 1.0f / (1.0f + expf(-lg));
+      float dl, sp;
+      if (pr == 0) {   // softplus(-logit)
+        sp = fmaxf(-lg, 0.f) + log1pf(expf(-fabsf(lg)));
+        dl = (sgm - 1.0f) * inv * (float)nneg;
+      } else {         // softplus(logit), averaged over the sets in the loss
+        sp = (fmaxf(lg, 0.f) + log1pf(expf(-fabsf(lg)))) / (float)nneg;
+        dl = sgm * inv;
+      }
+      const int row = (1 + nneg) * off + pr * n + i;
+      if (lane == 0) {
+        logits[row] = lg;
+        gb += dl;
+      }
+      lterm += sp;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int c = lane + 64 * q;
+        if (c < dO) {
+          const float dh = h[q] > 0.f ? dl * ww[q] : 0.f;
+          h1[(size_t)row * ldh + c] = h[q];
+          dPdec[rb + c] = 0.f;
+          dPdec[rb + dO + c] = dh;
+          dsrc[q] += dh;
+          gw[q] += dl * h[q];
+        }
+      }
+    }
+    if (lane == 0) lsum += lterm * inv / (float)bs.nb;
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
       const int c = lane + 64 * q;
       if (c < dO) {
-        const float dhp = hp[q] > 0.f ? dlp * ww[q] : 0.f;
-        const float dhn = hn[q] > 0.f ? dln * ww[q] : 0.f;
-        h1[(size_t)row_p * ldh + c] = hp[q];
-        h1[(size_t)row_n * ldh + c] = hn[q];
-        dPdec[ra + c] = dhp + dhn;
+        dPdec[ra + c] = dsrc[q];
         dPdec[ra + dO + c] = 0.f;
-        dPdec[rb + c] = 0.f;
-        dPdec[rb + dO + c] = dhp;
-        dPdec[rc + c] = 0.f;
-        dPdec[rc + dO + c] = dhn;
-        gw[q] += dlp * hp[q] + dln * hn[q];
       }
     }
   }

@@ -34,11 +34,12 @@ __device__ __forceinline__ void sample_block(const SampleArgs& a, const BatchSet
     double t;
     if (FUSED) {
       int b = 0;
-      while (b + 1 < bs.nb && r >= 3 * bs.b[b + 1].ev_off) ++b;
+      const int n_roles = 2 + bs.nneg;
+      while (b + 1 < bs.nb && r >= n_roles * bs.b[b + 1].ev_off) ++b;
       const int ev_off = bs.b[b].ev_off, n = bs.b[b].n;
-      const int local = r - 3 * ev_off;
+      const int local = r - n_roles * ev_off;
       const int role = local / n, i = local - role * n;
-      const int32_t* nodes = role == 0 ? bs.b[b].src : role == 1 ? bs.b[b].dst : bs.b[b].neg;
+      const int32_t* nodes = role == 0 ? bs.b[b].src : role == 1 ? bs.b[b].dst : bs.b[b].neg + (size_t)(role - 2) * n;
       node = nodes[i];
       t = bs.b[b].t[i];
       // an id outside [0, N) in the caller's batch arrays: the root is computed as node 0 (every index stays in

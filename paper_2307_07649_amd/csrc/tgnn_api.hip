@@ -82,7 +82,7 @@ struct Bump {
 };
 
 static void layout(const Dims& d, Ws& w, Bump& b) {
-  const size_t R = d.maxR, RK = d.maxRK, S = d.maxS, B2 = 2 * (size_t)d.maxEv;
+  const size_t R = d.maxR, RK = d.maxRK, S = d.maxS, B2 = (1 + (size_t)d.maxNeg) * d.maxEv;
   w.root_node = b.take<int32_t>(R);
   w.root_t = b.take<double>(R);
   w.nbr = b.take<int32_t>(RK); w.neid = b.take<int32_t>(RK); w.cnt = b.take<int32_t>(R); w.nts = b.take<double>(RK);
@@ -404,6 +404,8 @@ int32_t tgnn_create(const tgnn_config* cfg, tgnn_ctx** out) {
   if (4LL * 4 * (cfg->d_mem + (long long)cfg->k * (cfg->d_mem + 1) + 2LL * cfg->n_heads * cfg->k) > 64 * 1024)
     return set_error(TGNN_E_UNSUPPORTED_DIM, "k * d_mem too large for the attention kernel's LDS staging");
   if (cfg->dt_source != 0 && cfg->dt_source != 1) return set_error(TGNN_E_INVALID_ARG, "dt_source must be 0 or 1");
+  if (cfg->max_neg_sets < 0 || cfg->max_neg_sets > TGNN_MAX_NEG_SETS)
+    return set_error(TGNN_E_OUT_OF_RANGE, "max_neg_sets = %d outside [0, %d]", cfg->max_neg_sets, TGNN_MAX_NEG_SETS);
   if ((long long)cfg->n_nodes * cfg->n_replicas > 0x7fffffffLL)
     return set_error(TGNN_E_OUT_OF_RANGE, "n_nodes * n_replicas exceeds int32");
 
@@ -419,11 +421,12 @@ int32_t tgnn_create(const tgnn_config* cfg, tgnn_ctx** out) {
   d.dcp = (d.de + d.dt + 3) & ~3; d.ldz = padrow(d.H * d.dcp); d.ldy = padrow(2 * d.dt);
   const int nb = d.nrep < TGNN_MAX_BATCHES ? d.nrep : TGNN_MAX_BATCHES;
   const long long maxEv = (long long)d.maxB * nb;
-  if (maxEv * 3 * (1 + d.k) > 0x3fffffffLL) {
+  d.maxNeg = cfg->max_neg_sets > 1 ? cfg->max_neg_sets : 1;
+  if (maxEv * (2 + d.maxNeg) * (1 + d.k) > 0x3fffffffLL) {
     delete ctx;
-    return set_error(TGNN_E_OUT_OF_RANGE, "max_batch * n_replicas * 3 * (1 + k) exceeds the slot index range");
+    return set_error(TGNN_E_OUT_OF_RANGE, "max_batch * n_replicas * (2 + max_neg_sets) * (1 + k) exceeds the slot index range");
   }
-  d.maxEv = (int)maxEv; d.maxR = 3 * d.maxEv; d.maxRK = d.maxR * d.k; d.maxS = d.maxR + d.maxRK;
+  d.maxEv = (int)maxEv; d.maxR = (2 + d.maxNeg) * d.maxEv; d.maxRK = d.maxR * d.k; d.maxS = d.maxR + d.maxRK;
   {  // distinct (replica, node) rows a step can touch
     const long long ng = (long long)d.nrep * d.N;
     d.maxU = (int)(ng < d.maxS ? ng : d.maxS);
@@ -643,7 +646,7 @@ int32_t tgnn_temporal_attn_bwd(tgnn_ctx* ctx, const tgnn_params* p, int32_t n_ro
   return TGNN_OK;
 }
 
-static int make_batchset(const tgnn_ctx* ctx, const tgnn_batch* batches, int n_batches, BatchSet& bs) {
+static int make_batchset(const tgnn_ctx* ctx, const tgnn_batch* batches, int n_batches, BatchSet& bs, int nneg = 1) {
   const Dims& d = ctx->d;
   if (batches == nullptr) return set_error(TGNN_E_NULL_PTR, "batches is NULL");
   const int cap = d.nrep < TGNN_MAX_BATCHES ? d.nrep : TGNN_MAX_BATCHES;
@@ -667,6 +670,7 @@ static int make_batchset(const tgnn_ctx* ctx, const tgnn_batch* batches, int n_b
   }
   bs.nb = n_batches;
   bs.total = off;
+  bs.nneg = nneg;
   return TGNN_OK;
 }
 
@@ -686,7 +690,7 @@ int32_t tgnn_memory_writeback(tgnn_ctx* ctx, tgnn_state* st, int32_t replica, co
   BatchSet bs;
   memset(&bs, 0, sizeof(bs));
   bs.b[0] = BatchDesc{src, dst, nullptr, eid, t, n_events, replica, 0};
-  bs.nb = 1; bs.total = n_events;
+  bs.nb = 1; bs.total = n_events; bs.nneg = 1;
   hipStream_t s = as_stream(stream);
   Ws& w = ctx->w;
   prologue(ctx, nullptr, &bs, nullptr, nullptr, nullptr, s);
@@ -700,7 +704,18 @@ int32_t tgnn_memory_writeback(tgnn_ctx* ctx, tgnn_state* st, int32_t replica, co
 // loss_in_array: out_loss is an element of tgnn_train_steps' loss array (checked there; only 4-byte aligned)
 static int train_step_impl(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, const tgnn_params* p, tgnn_params* grads,
                            const tgnn_batch* batches, int32_t n_batches, float lr, float* out_loss, float* out_logits,
-                           int32_t* out_winner, void* stream, bool loss_in_array);
+                           int32_t* out_winner, void* stream, bool loss_in_array, int nneg = 1);
+
+int32_t tgnn_train_step_epoch_parallel(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, const tgnn_params* p,
+                                       tgnn_params* grads, const tgnn_batch* batches, int32_t n_batches,
+                                       int32_t n_neg_sets, float lr, float* out_loss, float* out_logits,
+                                       int32_t* out_winner, void* stream) {
+  if (ctx == nullptr) return set_error(TGNN_E_NULL_PTR, "ctx is NULL");
+  if (n_neg_sets < 1 || n_neg_sets > ctx->d.maxNeg)
+    return set_error(TGNN_E_OUT_OF_RANGE, "n_neg_sets = %d outside [1, %d] (config.max_neg_sets)", n_neg_sets, ctx->d.maxNeg);
+  return train_step_impl(ctx, g, st, p, grads, batches, n_batches, lr, out_loss, out_logits, out_winner, stream, false,
+                         n_neg_sets);
+}
 
 int32_t tgnn_train_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, const tgnn_params* p, tgnn_params* grads,
                         const tgnn_batch* batches, int32_t n_batches, float lr, float* out_loss, float* out_logits,
@@ -710,14 +725,14 @@ int32_t tgnn_train_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
 
 static int train_step_impl(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, const tgnn_params* p, tgnn_params* grads,
                            const tgnn_batch* batches, int32_t n_batches, float lr, float* out_loss, float* out_logits,
-                           int32_t* out_winner, void* stream, bool loss_in_array) {
+                           int32_t* out_winner, void* stream, bool loss_in_array, int nneg) {
   if (ctx == nullptr) return set_error(TGNN_E_NULL_PTR, "ctx is NULL");
   if (int rc = check_graph(ctx, g)) return rc;
   if (int rc = check_state(ctx, st)) return rc;
   if (int rc = check_params(p, "params")) return rc;
   if (int rc = check_params(grads, "grads")) return rc;
   BatchSet bs;
-  if (int rc = make_batchset(ctx, batches, n_batches, bs)) return rc;
+  if (int rc = make_batchset(ctx, batches, n_batches, bs, nneg)) return rc;
   for (int b = 0; b < bs.nb; ++b)
     if (bs.b[b].n > 0) REQ_PTR(bs.b[b].neg);
   if (!loss_in_array) REQ_PTR(out_loss);
@@ -827,7 +842,7 @@ static int replay_steps(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
     for (int i = 0; i < 19; ++i) { key.ptr[q++] = pp[i]; key.ptr[q++] = gg[i]; }
     key.ptr[q++] = out_loss; key.ptr[q++] = out_logits; key.ptr[q++] = out_winner; key.ptr[q++] = s;
     for (int b = 0; b < bs.nb; ++b) { key.n[b] = bs.b[b].n; key.rep[b] = bs.b[b].replica; }
-    key.nb = bs.nb; key.lr = lr; key.parity = parity; key.n_steps = n_steps;
+    key.nb = bs.nb; key.lr = lr; key.parity = parity; key.n_steps = n_steps; key.nneg = bs.nneg;
   }
   StepGraph* hit = nullptr;
   StepGraph* victim = &ctx->graphs[0];
@@ -906,7 +921,7 @@ static int replay_steps(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
     for (int i = 0; i < n_steps; ++i) {
       ctx->w.ucount = ctx->w.ucount_pair + ((parity + i) & 1);
       HeadArgs h;
-      head_fill(ctx, g, 3 * sets[i].total, p, &sets[i], lr != 0.0f ? &sgd_set : nullptr, overwrite ? &zero_set_ : nullptr,
+      head_fill(ctx, g, (2 + sets[i].nneg) * sets[i].total, p, &sets[i], lr != 0.0f ? &sgd_set : nullptr, overwrite ? &zero_set_ : nullptr,
                 out_loss + i, h);
       void* kargs[1] = {&h};
       hipKernelNodeParams np;
@@ -928,7 +943,7 @@ static int enqueue_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
                         const BatchSet& bs, float lr, float* out_loss, float* out_logits, int32_t* out_winner,
                         hipStream_t s) {
   const Dims& d = ctx->d; Ws& w = ctx->w;
-  const int R = 3 * bs.total, S = R * (1 + d.k), B2 = 2 * bs.total;
+  const int R = (2 + bs.nneg) * bs.total, S = R * (1 + d.k), B2 = (1 + bs.nneg) * bs.total;
 
   StageTimer tm{ctx, s};
   Side side{ctx, s, (ctx->cfg.flags & TGNN_FLAG_SIDE_STREAM) != 0};
@@ -979,7 +994,7 @@ static int enqueue_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
   // (the fill pass of the slot sort, needed by the backward pass only, rides in the attention launch)
   // Merge layer, decoder + loss and their backward pass down to the attention output are local to an event's
   // three roots: one launch when the layer width allows it.
-  const bool chain = root_chain_fits(d);
+  const bool chain = root_chain_fits(d) && bs.nneg == 1;   // (the one-launch chain is laid out for three roots per event)
   const AttnIn ain{w.slot_row, w.cnt, g->efeat, w.neid, nullptr, p};
   attn_forward(ctx, p, R, U, w.ucount, ain, &tm, s, sort_args(ctx, S), !chain);
 
@@ -1136,7 +1151,7 @@ int32_t tgnn_debug_read(tgnn_ctx* ctx, int32_t what, void* dst, int64_t n_bytes,
   }
   if (what == 6 || what == 7) {  // pitched float rows -> dense [rows, d_m]
     const float* base = what == 6 ? w.z : w.h1;
-    const size_t max_rows = what == 6 ? (size_t)d.maxR : 2 * (size_t)d.maxEv;
+    const size_t max_rows = what == 6 ? (size_t)d.maxR : (1 + (size_t)d.maxNeg) * d.maxEv;
     const size_t row_b = sizeof(float) * d.dm;
     if (n_bytes < 0 || (size_t)n_bytes % row_b != 0 || (size_t)n_bytes / row_b > max_rows)
       return set_error(TGNN_E_OUT_OF_RANGE, "n_bytes is not a whole number of rows within capacity");

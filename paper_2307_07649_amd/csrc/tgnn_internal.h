@@ -27,6 +27,7 @@ struct Dims {
   int dcp;    // d_e + d_t rounded up to 4: a head's block of a row of U / G / Zs / Zp
   int ldz;    // rows of width H * dcp
   int ldy;    // rows of width 2 d_t: a root's time-encoding gradient sums {d/dw | d/db}
+  int maxNeg;   // negative sets a step may carry
   int maxEv, maxR, maxRK, maxS, maxU;
 };
 
@@ -35,9 +36,12 @@ struct BatchDesc {
   const double* t;
   int32_t n, replica, ev_off;
 };
+// Roots of batch b are [src | dst | neg set 0 | ... | neg set nneg-1], n each, starting at root (2 + nneg) * ev_off;
+// its pairs are [true pairs | pairs with neg set 0 | ...], starting at pair (1 + nneg) * ev_off.
 struct BatchSet {
   BatchDesc b[TGNN_MAX_BATCHES];
   int32_t nb, total;
+  int32_t nneg;   // negative destinations per event (sets of the epoch-parallel step, Sec. 3.2.2); 1 in the plain step
 };
 
 // Device workspace.  S slots = R roots followed by R*k neighbour slots (slot R + r*k + j).
@@ -115,7 +119,7 @@ constexpr int MAX_STEP_GRAPHS = 8;
 struct StepKey {
   const void* ptr[64];
   int32_t n[TGNN_MAX_BATCHES], rep[TGNN_MAX_BATCHES];
-  int32_t nb, parity, n_steps;
+  int32_t nb, parity, n_steps, nneg;
   float lr;
 };
 struct StepGraph {

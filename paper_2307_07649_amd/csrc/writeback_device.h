@@ -35,7 +35,7 @@ __device__ __forceinline__ void wb_scatter_block(const WbArgs& a, int block) {
   const float *self_row, *other_row;
   double tau;
   if (w.s_new) {  // fused layout: rows indexed by root slot [src | dst | neg] of the batch
-    size_t rs = (size_t)(3 * bd.ev_off + i), rd = (size_t)(3 * bd.ev_off + bd.n + i);
+    size_t rs = (size_t)((2 + bs.nneg) * bd.ev_off + i), rd = rs + (size_t)bd.n;
     if (w.slot_row) { rs = (size_t)w.slot_row[rs]; rd = (size_t)w.slot_row[rd]; }
     self_row = w.s_new + (role ? rd : rs) * w.p_s;
     other_row = w.s_new + (role ? rs : rd) * w.p_s;

@@ -30,7 +30,7 @@ FLAG_GENERIC_ATTN = 16
 
 class tgnn_config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("n_nodes", "d_mem", "d_time", "d_edge", "d_static", "n_heads", "k",
-                                         "max_batch", "n_replicas", "dt_source", "flags")]
+                                         "max_batch", "n_replicas", "dt_source", "flags", "max_neg_sets")]
 
 
 class tgnn_graph(C.Structure):
@@ -69,6 +69,8 @@ _SIGS = {
     "tgnn_memory_writeback_noalloc": (_I, [_I, _I, C.POINTER(tgnn_state), _P, _P, _P, _P, _I, _P, _P, _P, _P, _P, _P]),
     "tgnn_train_step": (_I, [_P, C.POINTER(tgnn_graph), C.POINTER(tgnn_state), C.POINTER(tgnn_params),
                              C.POINTER(tgnn_params), C.POINTER(tgnn_batch), _I, C.c_float, _P, _P, _P, _P]),
+    "tgnn_train_step_epoch_parallel": (_I, [_P, C.POINTER(tgnn_graph), C.POINTER(tgnn_state), C.POINTER(tgnn_params),
+                                            C.POINTER(tgnn_params), C.POINTER(tgnn_batch), _I, _I, C.c_float, _P, _P, _P, _P]),
     "tgnn_train_steps": (_I, [_P, C.POINTER(tgnn_graph), C.POINTER(tgnn_state), C.POINTER(tgnn_params),
                               C.POINTER(tgnn_params), _I, C.POINTER(tgnn_batch), _I, C.c_float, _P, _P]),
     "tgnn_debug_read": (_I, [_P, _I, _P, C.c_int64, _P]),
@@ -206,9 +208,9 @@ class Batch:
 
 class Context:
     def __init__(self, n_nodes, d_mem, d_time, d_edge, d_static, n_heads, k, max_batch, n_replicas=1, dt_source=0,
-                 flags=0):
+                 flags=0, max_neg_sets=1):
         self.cfg = tgnn_config(n_nodes, d_mem, d_time, d_edge, d_static, n_heads, k, max_batch, n_replicas, dt_source,
-                               flags)
+                               flags, max_neg_sets)
         self.h = _P()
         _check(_lib.tgnn_create(C.byref(self.cfg), C.byref(self.h)))
         self.d_x = d_mem + d_static
@@ -290,6 +292,14 @@ class Context:
         arr = (tgnn_batch * len(batches))(*[b.c for b in batches])
         _check(_lib.tgnn_train_step(self.h, C.byref(g.c), C.byref(st.c), C.byref(p.c), C.byref(grads.c), arr,
                                     len(batches), lr, _ptr(out_loss), _ptr(out_logits), _ptr(out_winner), _stream()))
+
+    def tgnn_train_step_epoch_parallel(self, g: Graph, st: State, p: Params, grads: Params, batches, n_neg_sets, lr=0.0,
+                                       out_loss=None, out_logits=None, out_winner=None):
+        """Each batch's `neg` holds n_neg_sets sets of n negative destinations, one after the other."""
+        arr = (tgnn_batch * len(batches))(*[b.c for b in batches])
+        _check(_lib.tgnn_train_step_epoch_parallel(self.h, C.byref(g.c), C.byref(st.c), C.byref(p.c), C.byref(grads.c), arr,
+                                                   len(batches), n_neg_sets, lr, _ptr(out_loss), _ptr(out_logits),
+                                                   _ptr(out_winner), _stream()))
 
     def tgnn_train_steps(self, g: Graph, st: State, p: Params, grads: Params, steps, lr=0.0, out_loss=None):
         """steps: a list of steps, each a list of Batch (the same number per step); out_loss: device array [len(steps)]."""

@@ -68,7 +68,7 @@ class OracleSide:
 
 
 class GpuSide:
-    def __init__(self, P, n_replicas=1, dt_source=0, own_stream=True, flags=0):
+    def __init__(self, P, n_replicas=1, dt_source=0, own_stream=True, flags=0, max_neg_sets=1):
         """own_stream: run the steps on a stream of their own (the library then replays a captured HIP graph);
         False = the NULL stream, where every launch is enqueued directly."""
         import torch
@@ -78,30 +78,37 @@ class GpuSide:
         d = P["d"]
         self.P, self.d = P, d
         self.ctx = tgnn.Context(d.n_nodes, d.d_mem, d.d_time, d.d_edge, d.d_static, d.n_heads, d.k, d.batch,
-                                n_replicas=n_replicas, dt_source=dt_source, flags=flags)
+                                n_replicas=n_replicas, dt_source=dt_source, flags=flags, max_neg_sets=max_neg_sets)
         self.graph = tgnn.Graph(P["src"], P["dst"], P["ts"], d.n_nodes, P["efeat"])
         self.state = tgnn.State(d.n_nodes, d.d_mem, n_replicas, P["static"])
         self.params = tgnn.Params.from_numpy(P["params"])
         self.grads = tgnn.Params.zeros_like(self.params)
         self.loss = torch.zeros(4, device="cuda")
 
-    def step(self, batches, replicas=None, lr=0.0, want=True):
+    def step(self, batches, replicas=None, lr=0.0, want=True, n_neg_sets=1):
+        """n_neg_sets > 1: every batch's "neg" holds that many sets, [J, n] (tgnn_train_step_epoch_parallel)."""
         torch, tgnn = self.torch, self.tgnn
+        J = n_neg_sets
         replicas = replicas if replicas is not None else list(range(len(batches)))
-        bl = [tgnn.Batch(b["src"], b["dst"], b["neg"], b["eid"], b["t"], replica=r) for b, r in zip(batches, replicas)]
+        bl = [tgnn.Batch(b["src"], b["dst"], np.asarray(b["neg"]).reshape(-1), b["eid"], b["t"], replica=r)
+              for b, r in zip(batches, replicas)]
         tot = sum(b.n for b in bl)
-        if not hasattr(self, "_out") or self._out[0].numel() != 2 * tot:      # stable output buffers: same graph key
-            self._out = (torch.empty(2 * tot, device="cuda"), torch.empty(2 * tot, dtype=torch.int32, device="cuda"))
+        if not hasattr(self, "_out") or self._out[0].numel() != (1 + J) * tot:      # stable output buffers: same graph key
+            self._out = (torch.empty((1 + J) * tot, device="cuda"), torch.empty(2 * tot, dtype=torch.int32, device="cuda"))
         logits, win = self._out
         torch.cuda.synchronize()
         with torch.cuda.stream(self.stream):
             self.grads.zero_()
-            self.ctx.tgnn_train_step(self.graph, self.state, self.params, self.grads, bl, lr=lr, out_loss=self.loss,
-                                     out_logits=logits, out_winner=win)
+            if J == 1:
+                self.ctx.tgnn_train_step(self.graph, self.state, self.params, self.grads, bl, lr=lr, out_loss=self.loss,
+                                         out_logits=logits, out_winner=win)
+            else:
+                self.ctx.tgnn_train_step_epoch_parallel(self.graph, self.state, self.params, self.grads, bl, J, lr=lr,
+                                                        out_loss=self.loss, out_logits=logits, out_winner=win)
         torch.cuda.synchronize()
         if not want:
             return None
-        R = 3 * tot; k = self.d.k
+        R = (2 + J) * tot; k = self.d.k
         out = dict(loss=float(self.loss[0].item()), logits=logits.cpu().numpy(), winner=win.cpu().numpy(),
                    grads=self.grads.numpy())
         dbg = self.ctx.tgnn_debug_read
@@ -112,7 +119,7 @@ class GpuSide:
         out["s_new"] = dbg(4, torch.empty(R * (1 + k), self.d.d_mem, device="cuda")).cpu().numpy()
         out["tau"] = dbg(5, torch.empty(R * (1 + k), dtype=torch.float64, device="cuda")).cpu().numpy()
         out["z"] = dbg(6, torch.empty(R, self.d.d_mem, device="cuda")).cpu().numpy()
-        out["h1"] = dbg(7, torch.empty(2 * tot, self.d.d_mem, device="cuda")).cpu().numpy()
+        out["h1"] = dbg(7, torch.empty((1 + J) * tot, self.d.d_mem, device="cuda")).cpu().numpy()
         torch.cuda.synchronize()
         return out
 
@@ -148,7 +155,7 @@ def compare_step(g, o_res, tol=TOL, check_grads=True, label=""):
     logits = np.concatenate([o["logits"] for o in outs])
     errs = dict(logits=rel_err(g["logits"], logits), z=rel_err(g["z"], np.concatenate([o["z"] for o in outs])))
     R = len(cnt)
-    n_roots = [3 * len(o["logits"]) // 2 for o in outs]
+    n_roots = [len(o["cnt"]) for o in outs]
     s_all = np.concatenate([o["s_new"][:r] for o, r in zip(outs, n_roots)] + [o["s_new"][r:] for o, r in zip(outs, n_roots)])
     tau_all = np.concatenate([o["tau"][:r] for o, r in zip(outs, n_roots)] + [o["tau"][r:] for o, r in zip(outs, n_roots)])
     assert g["s_new"].shape == s_all.shape, label

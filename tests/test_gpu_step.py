@@ -191,3 +191,34 @@ def test_node_ids_outside_the_range_are_counted_and_never_written():
     for name in before:
         assert np.array_equal(before[name][~touched], after[name][~touched]), name
     assert np.all(after["mail_eid"][touched] >= 120)
+
+
+@pytest.mark.parametrize("J,shape", [
+    (3, dict(n_nodes=60, E=900, d_mem=32, d_time=16, d_edge=8, d_static=4, n_heads=2, k=6, batch=100)),
+    (2, dict(n_nodes=300, E=1600, d_mem=100, d_time=100, d_edge=172, d_static=0, n_heads=2, k=10, batch=200)),
+    (8, dict(n_nodes=40, E=300, d_mem=18, d_time=6, d_edge=5, d_static=0, n_heads=3, k=4, batch=41)),
+])
+def test_epoch_parallel_step_against_the_oracle(J, shape):
+    """tgnn_train_step_epoch_parallel (Sec. 3.2.2): J negative sets per positive batch in one step, the positive roots'
+    inputs and embeddings shared, memory written once.  Against the oracle's step with the same J sets: indices and
+    winners bit-exact, logits of all (1 + J) n pairs, gradients, s' of all slots, memory and parameters within 1e-4."""
+    from gpu_common import rel_err
+    P = custom_problem(**shape)
+    d = P["d"]
+    rng = np.random.default_rng(5)
+    G = GpuSide(P, max_neg_sets=J); Or = OracleSide(P)
+    n_steps = min(P["E"] // d.batch, 7)
+    for s in range(n_steps):
+        b = batch_np(P, s * d.batch, (s + 1) * d.batch)
+        b["neg"] = rng.integers(0, d.n_nodes, (J, d.batch)).astype(np.int32)
+        g = G.step([b], lr=0.02, n_neg_sets=J)
+        o = Or.step([b], lr=0.02, gpu=g)
+        compare_step(g, o, label=f"epoch-parallel J={J} step {s}")
+    compare_state(G.state_np(), Or.states[0], label="state")
+    for n, v in G.params.numpy().items():
+        assert rel_err(v, Or.p[n]) <= 1e-4, n
+    # one set through the same entry point is the plain step
+    G1 = GpuSide(P, max_neg_sets=J); G2 = GpuSide(P)
+    b = batch_np(P, 0, d.batch)
+    a1 = G1.step([b], n_neg_sets=1); a2 = G2.step([b])
+    assert np.array_equal(a1["logits"], a2["logits"]) and np.array_equal(a1["winner"], a2["winner"])

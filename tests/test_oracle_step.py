@@ -219,3 +219,37 @@ def test_time_encoding_derivative_by_finite_differences():
         np.testing.assert_allclose(O.time_encode_darg(delta, w, b), fd_b, atol=1e-9)
         fd_w = (O.time_encode(delta, w + h, b) - O.time_encode(delta, w - h, b)) / (2 * h)
         np.testing.assert_allclose(O.time_encode_darg(delta, w, b) * delta, fd_w, atol=1e-8)
+
+
+def test_epoch_parallel_step_is_the_sum_of_its_trainers():
+    """Sec. 3.2.2: J trainers share one positive mini-batch and differ in their negative destinations.  One step with
+    J negative sets must give the mean of the J single-set losses and the sum of their gradients (each computed by the
+    plain step from the same state), the same sampled neighbours for the shared roots, and -- since only the positive
+    endpoints are written -- the same memory and mails."""
+    P = tiny_problem(seed=12, n=60)
+    d = P["d"]
+    st = warm_state(P, 8)
+    lo, hi = 8 * d.batch, 9 * d.batch
+    rng = np.random.default_rng(1)
+    J = 3
+    negs = rng.integers(0, d.n_nodes, (J, d.batch))
+    bt = batch_of(P, lo, hi)
+    singles = []
+    for g in range(J):
+        b1 = dict(bt, neg=negs[g])
+        singles.append(O.forward_backward(st, P["adj"], P["efeat"], P["static"], P["p"], b1, d.k, d.n_heads))
+    multi = O.forward_backward(st, P["adj"], P["efeat"], P["static"], P["p"], dict(bt, neg=negs), d.k, d.n_heads)
+    B = d.batch
+    assert multi["logits"].shape == ((1 + J) * B,) and multi["cnt"].shape == ((2 + J) * B,)
+    assert abs(multi["loss"] - np.mean([s_["loss"] for s_ in singles])) < 1e-14
+    for name in O.PARAM_NAMES:
+        np.testing.assert_allclose(multi["grads"][name], sum(s_["grads"][name] for s_ in singles), rtol=1e-11, atol=1e-15)
+    for g in range(J):
+        np.testing.assert_allclose(multi["logits"][:B], singles[g]["logits"][:B], atol=1e-14)
+        np.testing.assert_allclose(multi["logits"][(1 + g) * B:(2 + g) * B], singles[g]["logits"][B:], atol=1e-14)
+        assert np.array_equal(multi["nbr"][(2 + g) * B:(3 + g) * B], singles[g]["nbr"][2 * B:])
+    st_a = copy.deepcopy(st); st_b = copy.deepcopy(st)
+    O.apply_writeback(st_a, dict(bt, neg=negs), multi)
+    O.apply_writeback(st_b, dict(bt, neg=negs[0]), singles[0])
+    for key in st_a:
+        assert np.array_equal(st_a[key], st_b[key])
