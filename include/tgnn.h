@@ -249,6 +249,26 @@ int32_t tgnn_train_step_epoch_parallel(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_
                                        int32_t n_neg_sets, float lr, float* out_loss, float* out_logits,
                                        int32_t* out_winner, void* stream);
 
+/* Optimiser of the in-step update that tgnn_train_step (and its variants) apply when lr != 0.
+ *   kind 0  plain SGD, p -= lr g (the default);
+ *   kind 1  Adam: m = beta1 m + (1 - beta1) g, v = beta2 v + (1 - beta2) g^2, p -= lr (m / (1 - beta1^t)) /
+ *           (sqrt(v / (1 - beta2^t)) + eps), t = number of Adam steps so far on this context (kept on the device, starts
+ *           at 0 with this call).  m, v: moment tensors laid out like the parameters, caller-owned, zero on entry.
+ * The time-encoding parameters time_w, time_b stay frozen under both.  The learning rate is the `lr` of every step (the
+ * paper scales it linearly with the global batch size, Sec. 4: the caller's choice).  Takes effect from the next step;
+ * synchronises the device. */
+int32_t tgnn_set_optimizer(tgnn_ctx* ctx, int32_t kind, tgnn_params* m, tgnn_params* v, float beta1, float beta2, float eps);
+
+/* Co-trained static node memory (Sec. 3.1: the static memory as a learnable embedding table trained with the model
+ * instead of a frozen pre-trained one).  From the next step on, every training step also back-propagates into the
+ * static rows {static_w} of the nodes it touches (roots and supporting nodes):
+ *   grad_static [n_nodes, d_static] or NULL: the rows' gradients (of the sum of the batches' losses) are ADDED here;
+ *   lr_static: if nonzero, the touched rows of state.stat are updated in the step, stat[w] -= lr_static * g[w] (plain
+ *              sparse SGD on the table: no moments are kept for rows, whatever tgnn_set_optimizer selects).
+ * state.stat is then written by the library although the struct declares it const.  enable = 0 switches it off.
+ * TGNN_E_UNSUPPORTED_DIM when d_static == 0.  Synchronises the device. */
+int32_t tgnn_train_static(tgnn_ctx* ctx, int32_t enable, float* grad_static, float lr_static);
+
 /* n_steps consecutive training steps (Sec. 3.2.1: mini-batches are trained in chronological order, each step
  * reading the memory the step before it wrote) in one call: the same sequence of launches, with the same results
  * (up to the order of floating-point sums), as n_steps calls of tgnn_train_step with out_logits = out_winner = NULL.

@@ -398,6 +398,13 @@ def forward_backward(state, graph, efeat, static, p, batch, k, n_heads, dt_sourc
     g["time_w"] = g["time_w"] + (dphi * msin * gc["delta"][:, None]).sum(0)
     g["time_b"] = g["time_b"] + (dphi * msin).sum(0)
     out["grads"] = {n: g[n] for n in PARAM_NAMES}
+    if static is not None:
+        # co-trained static memory (Sec. 3.1): the static row of a node is an input of every slot that refers to the
+        # node, so its gradient is the sum over those slots of the gradient reaching the static columns of x
+        g_static = np.zeros(static.shape, F)
+        np.add.at(g_static, root_node, dx_root[:, d_m:])
+        np.add.at(g_static, nbr[valid], dx_nbr[valid][:, d_m:])
+        out["g_static"] = g_static
     out["abs_terms"] = ac["abs_terms"]
     return out
 
@@ -415,16 +422,48 @@ def sgd(p, grads, lr):
             p[n] -= lr * grads[n]
 
 
-def apply_step(states, p, batches, outs, lr=0.0):
+def adam_init(p):
+    """Adam's state: first and second moments (zero) and the step count."""
+    return dict(m={n: np.zeros_like(p[n]) for n in PARAM_NAMES}, v={n: np.zeros_like(p[n]) for n in PARAM_NAMES}, t=0)
+
+
+def adam(p, grads, st, lr, beta1=0.9, beta2=0.999, eps=1e-8):
+    """One Adam step with bias correction on every tensor except the time-encoding frequencies and phases:
+    m = b1 m + (1 - b1) g;  v = b2 v + (1 - b2) g^2;  p -= lr (m / (1 - b1^t)) / (sqrt(v / (1 - b2^t)) + eps)."""
+    st["t"] += 1
+    t = st["t"]
+    for n in PARAM_NAMES:
+        if n in FROZEN_IN_SGD:
+            continue
+        g = grads[n]
+        st["m"][n] = beta1 * st["m"][n] + (1.0 - beta1) * g
+        st["v"][n] = beta2 * st["v"][n] + (1.0 - beta2) * g * g
+        mhat = st["m"][n] / (1.0 - beta1 ** t)
+        vhat = st["v"][n] / (1.0 - beta2 ** t)
+        p[n] -= lr * mhat / (np.sqrt(vhat) + eps)
+
+
+def apply_step(states, p, batches, outs, lr=0.0, adam_state=None, adam_hyper=(0.9, 0.999, 1e-8), static=None,
+               lr_static=0.0):
     """Second half of a step, from the per-batch results `outs` of forward_backward: gradients summed over the
-    batches (memory parallelism, Sec. 3.2.3: one weight set), loss averaged, the write-backs, one SGD update."""
+    batches (memory parallelism, Sec. 3.2.3: one weight set), loss averaged, the write-backs, one optimiser update
+    (plain SGD, or Adam when adam_state is given).  static + lr_static: the co-trained static memory table (Sec. 3.1)
+    takes static -= lr_static * g_static (rows no slot referred to have zero gradient)."""
     grads = {n: sum(o["grads"][n] for o in outs) for n in PARAM_NAMES}
     loss = float(np.mean([o["loss"] for o in outs]))
     wins = [apply_writeback(states[i], batches[i], outs[i]) for i in range(len(batches))]
+    res = dict(loss=loss, grads=grads, outs=outs, winners=wins,
+               abs_terms={n: sum(o["abs_terms"][n] for o in outs) for n in outs[0]["abs_terms"]})
+    if "g_static" in outs[0]:
+        res["g_static"] = sum(o["g_static"] for o in outs)
     if lr:
-        sgd(p, grads, lr)
-    return dict(loss=loss, grads=grads, outs=outs, winners=wins,
-                abs_terms={n: sum(o["abs_terms"][n] for o in outs) for n in outs[0]["abs_terms"]})
+        if adam_state is not None:
+            adam(p, grads, adam_state, lr, *adam_hyper)
+        else:
+            sgd(p, grads, lr)
+    if static is not None and lr_static:
+        static -= (lr_static * res["g_static"]).astype(static.dtype)
+    return res
 
 
 def train_step(states, graph, efeat, static, p, batches, k, n_heads, lr=0.0, dt_source=0):

@@ -37,10 +37,11 @@ void prologue_fill(tgnn_ctx* ctx, const tgnn_params* p, const BatchSet* bs, cons
     add(p->wq, w.Wx + (size_t)half * d.ldxr, dO, dx, d.ldxr, d.ldxr, d.dq, 1);
     add(p->wo + dO, w.Wx + (size_t)(half + dO) * d.ldxr, dO, dx, d.ldxr, d.ldxr, dmrg, 1);
     // its transpose, dynamic columns only: WxT[c, j] = Wx[j, c], c < d_m
-    add(p->wk, w.WxT, dm, dO, dO, d.ldp, 1, dkv);
-    add(p->wv, w.WxT + dO, dm, dO, dO, d.ldp, 1, dkv);
-    add(p->wq, w.WxT + half, dm, dO, dO, d.ldp, 1, d.dq);
-    add(p->wo + dO, w.WxT + half + dO, dm, dO, dO, d.ldp, 1, dmrg);
+    // (rows c >= d_m, the static columns, are read only when the static memory is co-trained)
+    add(p->wk, w.WxT, dx, dO, dO, d.ldp, 1, dkv);
+    add(p->wv, w.WxT + dO, dx, dO, dO, d.ldp, 1, dkv);
+    add(p->wq, w.WxT + half, dx, dO, dO, d.ldp, 1, d.dq);
+    add(p->wo + dO, w.WxT + half + dO, dx, dO, dO, d.ldp, 1, dmrg);
     // {e | Phi} columns of W_k, W_v (the slots' own inputs), per head: head h owns output rows [h dh, (h + 1) dh)
     if (d.de + d.dt > 0) {
       const int dh = dO / d.H, dc = d.de + d.dt;
@@ -89,6 +90,7 @@ void prologue_fill(tgnn_ctx* ctx, const tgnn_params* p, const BatchSet* bs, cons
   pa.epoch = w.epoch;
   pa.ucount = w.ucount;
   pa.q_part = w.q_part; pa.q_part_n = QPHI_BLOCKS * d.dO;
+  pa.adam_t = (sgd != nullptr && ctx->adam) ? w.adam_t : nullptr;   // a step that updates the weights is one Adam step
 }
 
 dim3 prologue_grid(const PrologueArgs& pa) { return dim3(96, pa.n_pack + pa.zero.cnt + 1); }

@@ -69,6 +69,7 @@ __device__ __forceinline__ void prologue_block(const PrologueArgs& a, int bx, in
     for (int i = threadIdx.x; i < a.q_part_n; i += blockDim.x) a.q_part[i] = 0.f;
     if (threadIdx.x == 0) {
       if (a.loss) *a.loss = 0.f;
+      if (a.adam_t) *a.adam_t += 1;
       if (a.head_of_step) {
         *a.ucount_next = 0;
       } else {

@@ -97,6 +97,8 @@ static void layout(const Dims& d, Ws& w, Bump& b) {
   w.rowptr = b.take<int32_t>(U + 1); w.cursor = b.take<int32_t>(U); w.sorted = b.take<int32_t>(S);
   w.sorted_row = b.take<int32_t>(S); w.sort_total = b.take<int32_t>(1);
   w.ds_row = b.take<float>(S * d.ldh);
+  w.dstat = d.ds > 0 ? b.take<float>(S * d.ldst) : nullptr;
+  w.adam_dev = b.take<AdamSet>(1); w.adam_t = b.take<int32_t>(1);
   w.bs_dev = b.take<BatchSet>(1);
   w.sgd_dev = b.take<SgdSet>(1);
   w.q_part = b.take<float>((size_t)QPHI_BLOCKS * d.dO);
@@ -128,7 +130,7 @@ static void layout(const Dims& d, Ws& w, Bump& b) {
     w.rc_pk = root_chain_fits(d) ? b.take<float>(6 * ks * ks * 256) : nullptr;
   }
   w.WdecT = b.take<float>((size_t)d.dO * d.ldkv); w.WihT_phi = b.take<float>((size_t)d.dt * d.ld3);
-  w.WxT = b.take<float>((size_t)d.dm * d.ldp);
+  w.WxT = b.take<float>((size_t)d.dx * d.ldp);
   w.WoT_o = b.take<float>((size_t)d.dO * d.ldh);
   b.take<char>(256);
 }
@@ -329,7 +331,7 @@ static void attn_backward(tgnn_ctx* ctx, tgnn_params* g, const tgnn_params* p, i
 // the GRU gate pre-activations (ws.dgi, ws.dgh).  `with` (may be NULL): an independent product to run in the
 // same launch.
 static void node_proj_backward(tgnn_ctx* ctx, tgnn_params* g, int n_rows, const int* n_rows_dev, TnBatch& tn,
-                               bool through_gru, hipStream_t s, const NtProblem* with = nullptr) {
+                               bool through_gru, hipStream_t s) {
   const Dims& d = ctx->d; Ws& w = ctx->w;
   GruBwdOut gb;
   if (through_gru) {
@@ -338,8 +340,12 @@ static void node_proj_backward(tgnn_ctx* ctx, tgnn_params* g, int n_rows, const 
   }
   const NtProblem mine = nt_live(nt_problem(w.dP, d.ldp, w.WxT, d.ldp, nullptr, w.ds_row, d.ldh, n_rows, d.dm, d.ldp, d.ldh,
                                             false, n_rows_dev, RowAdd(), TimeGradOut(), gb), d.ldkv + 2 * d.dO);
-  if (with != nullptr) {
-    const NtProblem pr[2] = {mine, *with};   // the few, long workgroups of this one start first
+  if (ctx->train_static && through_gru && d.ds > 0) {
+    // co-trained static memory (Sec. 3.1): the same product for the static columns of the node rows, stored per row;
+    // the rows are scattered to the table by the step's last launch
+    const NtProblem stat = nt_live(nt_problem(w.dP, d.ldp, w.WxT + (size_t)d.dm * d.ldp, d.ldp, nullptr, w.dstat, d.ldst, n_rows,
+                                              d.ds, d.ldp, d.ldst, false, n_rows_dev), d.ldkv + 2 * d.dO);
+    const NtProblem pr[2] = {mine, stat};
     gemm_nt_group(pr, 2, s);
   } else {
     gemm_nt_group(&mine, 1, s);
@@ -418,7 +424,7 @@ int32_t tgnn_create(const tgnn_config* cfg, tgnn_ctx** out) {
   d.d_in = 2 * d.dm + d.dt + d.de; d.dx = d.dm + d.ds; d.dq = d.dx + d.dt; d.dkv = d.dx + d.de + d.dt; d.dO = d.dm;
   d.ldx = padrow(d.d_in); d.ldh = padrow(d.dm); d.ld3 = padrow(3 * d.dm); d.ldxr = padrow(d.dx);
   d.ldkv = padrow(2 * d.dO); d.ldp = 2 * d.ldkv; d.ldt = padrow(d.dt);
-  d.dcp = (d.de + d.dt + 3) & ~3; d.ldz = padrow(d.H * d.dcp); d.ldy = padrow(2 * d.dt);
+  d.dcp = (d.de + d.dt + 3) & ~3; d.ldz = padrow(d.H * d.dcp); d.ldy = padrow(2 * d.dt); d.ldst = padrow(d.ds > 0 ? d.ds : 1);
   const int nb = d.nrep < TGNN_MAX_BATCHES ? d.nrep : TGNN_MAX_BATCHES;
   const long long maxEv = (long long)d.maxB * nb;
   d.maxNeg = cfg->max_neg_sets > 1 ? cfg->max_neg_sets : 1;
@@ -1059,14 +1065,66 @@ static int enqueue_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
     tg.delta = w.delta; tg.w = p->time_w; tg.b = p->time_b; tg.g_w = grads->time_w; tg.g_b = grads->time_b;
     const NtProblem pr = nt_live(nt_problem(w.dgi, d.ld3, w.WihT_phi, d.ld3, nullptr, nullptr, d.ldt, U, d.dt, d.ld3, d.ldt,
                                             false, w.ucount, RowAdd(), tg), 3 * d.dm);
-    const WbArgs wb = writeback_args(d, w.bs_dev, bs.total, st, w.winkey, w.epoch, w.Xrow, d.ldxr, w.tau, w.slot_row, nullptr,
-                                     nullptr, nullptr, nullptr, out_winner, lr != 0.0f ? w.sgd_dev : nullptr, sgd_set.cnt, lr);
+    WbArgs wb = writeback_args(d, w.bs_dev, bs.total, st, w.winkey, w.epoch, w.Xrow, d.ldxr, w.tau, w.slot_row, nullptr,
+                               nullptr, nullptr, nullptr, out_winner, lr != 0.0f ? w.sgd_dev : nullptr, sgd_set.cnt, lr);
+    if (ctx->adam && lr != 0.0f) wb.adam = w.adam_dev;
+    if (ctx->train_static && d.ds > 0) {
+      StatUpd& u = wb.stat;
+      u.drow = w.dstat; u.ld = d.ldst; u.ds = d.ds; u.N = d.N; u.ulist = w.ulist; u.ucount = w.ucount;
+      u.stat = const_cast<float*>(st->stat); u.gstat = ctx->grad_static; u.lr = ctx->lr_static;
+      u.blocks = 64;
+    }
     gemm_nt_group(&pr, 1, s, &wb);
   }
   tm.end(17);
   if (out_logits)
     TGNN_HIP_CHECK(hipMemcpyAsync(out_logits, w.logits, sizeof(float) * B2, hipMemcpyDeviceToDevice, s));
   TGNN_LAUNCH_CHECK();
+  return TGNN_OK;
+}
+
+// captured steps hold the optimiser's launches: a change of optimiser or of static co-training drops them
+static void drop_graphs(tgnn_ctx* ctx) {
+  for (StepGraph& sg : ctx->graphs)
+    if (sg.used) {
+      (void)hipGraphExecDestroy(sg.exec);
+      (void)hipGraphDestroy(sg.graph);
+      sg.used = false;
+    }
+}
+
+int32_t tgnn_set_optimizer(tgnn_ctx* ctx, int32_t kind, tgnn_params* m, tgnn_params* v, float beta1, float beta2, float eps) {
+  if (ctx == nullptr) return set_error(TGNN_E_NULL_PTR, "ctx is NULL");
+  if (kind != 0 && kind != 1) return set_error(TGNN_E_INVALID_ARG, "kind must be 0 (SGD) or 1 (Adam)");
+  TGNN_HIP_CHECK(hipDeviceSynchronize());
+  drop_graphs(ctx);
+  if (kind == 0) { ctx->adam = false; return TGNN_OK; }
+  if (int rc = check_params(m, "m")) return rc;
+  if (int rc = check_params(v, "v")) return rc;
+  if (!(beta1 >= 0.f && beta1 < 1.f) || !(beta2 >= 0.f && beta2 < 1.f) || !(eps > 0.f))
+    return set_error(TGNN_E_INVALID_ARG, "Adam needs 0 <= beta1, beta2 < 1 and eps > 0");
+  AdamSet a;
+  memset(&a, 0, sizeof(a));
+  float* const* mm = reinterpret_cast<float* const*>(m);
+  float* const* vv = reinterpret_cast<float* const*>(v);
+  for (int i = 2; i < 19; ++i) { a.m[i - 2] = mm[i]; a.v[i - 2] = vv[i]; }   // the table of the update skips time_w, time_b
+  a.beta1 = beta1; a.beta2 = beta2; a.eps = eps; a.t = ctx->w.adam_t;
+  TGNN_HIP_CHECK(hipMemcpy(ctx->w.adam_dev, &a, sizeof(a), hipMemcpyHostToDevice));
+  TGNN_HIP_CHECK(hipMemset(ctx->w.adam_t, 0, sizeof(int32_t)));
+  ctx->adam = true;
+  return TGNN_OK;
+}
+
+int32_t tgnn_train_static(tgnn_ctx* ctx, int32_t enable, float* grad_static, float lr_static) {
+  if (ctx == nullptr) return set_error(TGNN_E_NULL_PTR, "ctx is NULL");
+  if (ctx->d.ds == 0) return set_error(TGNN_E_UNSUPPORTED_DIM, "the configuration has no static memory (d_static == 0)");
+  OPT_PTR(grad_static);
+  if (!(lr_static == lr_static)) return set_error(TGNN_E_INVALID_ARG, "lr_static is NaN");
+  TGNN_HIP_CHECK(hipDeviceSynchronize());
+  drop_graphs(ctx);
+  ctx->train_static = enable != 0;
+  ctx->grad_static = enable != 0 ? grad_static : nullptr;
+  ctx->lr_static = enable != 0 ? lr_static : 0.f;
   return TGNN_OK;
 }
 

@@ -27,6 +27,7 @@ struct Dims {
   int dcp;    // d_e + d_t rounded up to 4: a head's block of a row of U / G / Zs / Zp
   int ldz;    // rows of width H * dcp
   int ldy;    // rows of width 2 d_t: a root's time-encoding gradient sums {d/dw | d/db}
+  int ldst;   // rows of width d_s: gradient reaching a node row's static columns
   int maxNeg;   // negative sets a step may carry
   int maxEv, maxR, maxRK, maxS, maxU;
 };
@@ -65,6 +66,9 @@ struct Ws {
   int32_t *slot_row, *ucnt, *rowptr, *cursor, *sorted;  // [S] slot -> row; [maxU] slots per row; CSR of slots by row
   int32_t *sorted_row, *sort_total;            // [S] row of every sorted slot; [1] number of sorted slots
   float* ds_row;                               // [maxS, ldh] gradient reaching s' per row
+  float* dstat;                                // [maxS, ldst] gradient reaching the static columns per row (co-training)
+  struct AdamSet* adam_dev;                    // device copy of the Adam moment pointers and constants
+  int32_t* adam_t;                             // [1] Adam steps so far
   BatchSet* bs_dev;                            // device copy of the step's batch descriptors
   struct SgdSet* sgd_dev;                      // device copy of the parameter/gradient pointer table
   float* q_part;                               // [QPHI_BLOCKS, d_o] column sums of dq per block of roots
@@ -94,7 +98,7 @@ struct Ws {
   float *Wo_o;              // [d_o, ldh] W_o restricted to the attention-output columns
   float *rc_pk;             // six [d_o, d_o] blocks in MFMA B-operand order for the root chain (NULL: it does not fit)
   float *WdecT, *WihT_phi;
-  float *WxT;               // [d_m, ldp]   transposed Wx, dynamic columns only
+  float *WxT;               // [d_x, ldp]   transposed Wx (rows >= d_m: the static columns)
   float *WoT_o;             // [d_o, ldh]   transposed Wo_o
 };
 
@@ -156,6 +160,10 @@ struct tgnn_ctx {
   int last_attn_roots;
   int device;
   int step_parity = 0;             // which of the two row counters the next training step uses
+  bool adam = false;               // tgnn_set_optimizer: the in-step update is Adam's
+  bool train_static = false;       // tgnn_train_static
+  float* grad_static = nullptr;
+  float lr_static = 0.f;
 };
 
 namespace tgnn {
@@ -177,6 +185,25 @@ struct SgdSet {
   int cnt;
 };
 
+// Adam's moment tensors and constants (tgnn_set_optimizer), in the order of the SGD pointer table.
+struct AdamSet {
+  float* m[20];
+  float* v[20];
+  float beta1, beta2, eps;
+  const int32_t* t;   // device step counter (already counting the step being applied)
+};
+// Sparse update of the co-trained static memory: row r of drow is the gradient of static[ulist[r] % N].
+struct StatUpd {
+  const float* drow = nullptr;    // NULL: off
+  int ld = 0, ds = 0, N = 0;
+  const int32_t* ulist = nullptr;
+  const int32_t* ucount = nullptr;
+  float* stat = nullptr;
+  float* gstat = nullptr;         // may be NULL
+  float lr = 0.f;
+  int blocks = 0;
+};
+
 // Last-event-wins write-back (k_writeback.hip) as a record, so that it can ride in another launch.
 struct WbPtrs {
   float *mem, *mail;
@@ -195,11 +222,15 @@ struct WbArgs {
   const unsigned long long* epoch = nullptr;
   int32_t* out_winner = nullptr;
   int wb_blocks = 0;              // blocks of 256 threads for the scatter ...
-  const SgdSet* sgd = nullptr;    // ... followed by 64 per tensor for the SGD update p -= lr * g (NULL: none)
+  const SgdSet* sgd = nullptr;    // ... followed by 64 per tensor for the update p -= lr * g (NULL: none)
   int sgd_cnt = 0;
   float lr = 0.f;
+  const AdamSet* adam = nullptr;  // non-NULL: the update is Adam's
+  StatUpd stat;                   // ... followed by stat.blocks for the static-memory rows
 };
-inline int wb_total_blocks(const WbArgs& a) { return a.bs != nullptr ? a.wb_blocks + (a.sgd != nullptr ? 64 * a.sgd_cnt : 0) : 0; }
+inline int wb_total_blocks(const WbArgs& a) {
+  return a.bs != nullptr ? a.wb_blocks + (a.sgd != nullptr ? 64 * a.sgd_cnt : 0) + a.stat.blocks : 0;
+}
 
 // ---- k_gemm.hip ---------------------------------------------------------------------
 // C[m, n] = sum_k A[m, k] * B[n, k] + bias[n]  (m < M, n < N), optional ReLU; columns [N, n_store) of C are
@@ -363,6 +394,7 @@ struct PrologueArgs {
   // row counter of the next step (ucount_next) is cleared.  Otherwise: epoch += 1, *ucount = 0.
   int head_of_step;
   int32_t* ucount_next;
+  int32_t* adam_t;      // non-NULL: *adam_t += 1 (one Adam step is about to be applied)
 };
 void prologue_fill(tgnn_ctx* ctx, const tgnn_params* p, const BatchSet* bs, const SgdSet* sgd, const SgdSet* zero,
                    float* loss, PrologueArgs& pa);

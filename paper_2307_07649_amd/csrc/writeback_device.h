@@ -56,15 +56,50 @@ __device__ __forceinline__ void wb_scatter_block(const WbArgs& a, int block) {
   }
 }
 
+// Co-trained static memory (Sec. 3.1): row r of the step's distinct node rows carries the gradient of the static row of
+// node ulist[r] % N.  Rows of different memory replicas may be the same node, so the table is updated with atomics.
+__device__ __forceinline__ void stat_update_block(const StatUpd& u, int block) {
+  const int rows = *u.ucount;
+  const long long total = (long long)rows * u.ds;
+  for (long long i = block * 256LL + threadIdx.x; i < total; i += (long long)u.blocks * 256) {
+    const int r = (int)(i / u.ds), c = (int)(i - (long long)r * u.ds);
+    const float g = u.drow[(size_t)r * u.ld + c];
+    const size_t o = (size_t)(u.ulist[r] % u.N) * u.ds + c;
+    if (u.gstat != nullptr) atomicAdd(u.gstat + o, g);
+    if (u.lr != 0.f) atomicAdd(u.stat + o, -u.lr * g);
+  }
+}
+
 // block: 0 .. wb_total_blocks(a) - 1
 __device__ __forceinline__ void wb_sgd_block(const WbArgs& a, int block) {
   if (block >= a.wb_blocks) {
     const int extra = block - a.wb_blocks;
+    const int n_sgd = a.sgd != nullptr ? 64 * a.sgd_cnt : 0;
+    if (extra >= n_sgd) {
+      if (a.stat.drow != nullptr && extra - n_sgd < a.stat.blocks) stat_update_block(a.stat, extra - n_sgd);
+      return;
+    }
     const int t = extra >> 6, x = extra & 63;
-    if (a.sgd == nullptr || t >= a.sgd_cnt) return;
     float* p = a.sgd->p[t];
     const float* g = a.sgd->g[t];
     const int n = a.sgd->n[t];
+    if (a.adam != nullptr) {   // Adam with bias correction; the step count and the corrections in double
+      const AdamSet& ad = *a.adam;
+      float* m = ad.m[t];
+      float* v = ad.v[t];
+      const double steps = (double)*ad.t;
+      const float c1 = (float)(1.0 / (1.0 - pow((double)ad.beta1, steps)));
+      const float c2 = (float)(1.0 / (1.0 - pow((double)ad.beta2, steps)));
+      for (int i = x * 256 + threadIdx.x; i < n; i += 64 * 256) {
+        const float gi = g[i];
+        const float mi = ad.beta1 * m[i] + (1.0f - ad.beta1) * gi;
+        const float vi = ad.beta2 * v[i] + (1.0f - ad.beta2) * gi * gi;
+        m[i] = mi;
+        v[i] = vi;
+        p[i] -= a.lr * (mi * c1) / (sqrtf(vi * c2) + ad.eps);
+      }
+      return;
+    }
     for (int i = x * 256 + threadIdx.x; i < n; i += 64 * 256) p[i] -= a.lr * g[i];
     return;
   }

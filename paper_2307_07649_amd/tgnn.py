@@ -73,6 +73,8 @@ _SIGS = {
                                             C.POINTER(tgnn_params), C.POINTER(tgnn_batch), _I, _I, C.c_float, _P, _P, _P, _P]),
     "tgnn_train_steps": (_I, [_P, C.POINTER(tgnn_graph), C.POINTER(tgnn_state), C.POINTER(tgnn_params),
                               C.POINTER(tgnn_params), _I, C.POINTER(tgnn_batch), _I, C.c_float, _P, _P]),
+    "tgnn_set_optimizer": (_I, [_P, _I, C.POINTER(tgnn_params), C.POINTER(tgnn_params), C.c_float, C.c_float, C.c_float]),
+    "tgnn_train_static": (_I, [_P, _I, _P, C.c_float]),
     "tgnn_debug_read": (_I, [_P, _I, _P, C.c_int64, _P]),
     "tgnn_debug_copy": (_I, [_P, _P, C.c_int64, _P]),
     "tgnn_zero_params": (_I, [_P, C.POINTER(tgnn_params), _P]),
@@ -308,6 +310,15 @@ class Context:
         arr = (tgnn_batch * len(flat))(*flat)
         _check(_lib.tgnn_train_steps(self.h, C.byref(g.c), C.byref(st.c), C.byref(p.c), C.byref(grads.c), len(steps), arr,
                                      nb, lr, _ptr(out_loss), _stream()))
+
+    def tgnn_set_optimizer(self, kind, m: Params = None, v: Params = None, beta1=0.9, beta2=0.999, eps=1e-8):
+        self._opt = (m, v)      # keeps the moment tensors alive
+        _check(_lib.tgnn_set_optimizer(self.h, kind, C.byref(m.c) if m else None, C.byref(v.c) if v else None, beta1, beta2,
+                                       eps))
+
+    def tgnn_train_static(self, enable, grad_static=None, lr_static=0.0):
+        self._gstat = grad_static
+        _check(_lib.tgnn_train_static(self.h, 1 if enable else 0, _ptr(grad_static), lr_static))
 
     def tgnn_zero_params(self, grads: Params):
         _check(_lib.tgnn_zero_params(self.h, C.byref(grads.c), _stream()))

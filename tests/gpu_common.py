@@ -33,6 +33,14 @@ class OracleSide:
                     else O.build_adjacency(P["src"], P["dst"], P["ts"], d.n_nodes))
         self.states = [O.new_state(d.n_nodes, d.d_mem) for _ in range(n_replicas)]
         self.p = O.to_f64(P["params"])
+        self.static = P["static"]          # replaced by a float64 copy when the static memory is co-trained
+        self.adam_state = None; self.adam_hyper = (0.9, 0.999, 1e-8); self.lr_static = 0.0
+
+    def use_adam(self, beta1=0.9, beta2=0.999, eps=1e-8):
+        self.adam_state = O.adam_init(self.p); self.adam_hyper = (beta1, beta2, eps)
+
+    def train_static(self, lr_static):
+        self.static = np.asarray(self.P["static"], np.float64).copy(); self.lr_static = lr_static
 
     def step(self, batches, replicas=None, lr=0.0, gpu=None):
         """One oracle step.  gpu (a GpuSide.step result of the same step, optional): where the GPU gated a ReLU
@@ -43,7 +51,7 @@ class OracleSide:
         replicas = replicas if replicas is not None else list(range(len(batches)))
         sts = [self.states[r] for r in replicas]
         ef = self.P.get("efeat_host", self.P["efeat"])
-        fb = lambda i, gates=None: O.forward_backward(sts[i], self.adj, ef, self.P["static"], self.p, batches[i], self.d.k,
+        fb = lambda i, gates=None: O.forward_backward(sts[i], self.adj, ef, self.static, self.p, batches[i], self.d.k,
                                                       self.d.n_heads, self.dt_source, relu_gates=gates)
         outs = [fb(i) for i in range(len(batches))]
         flips = 0
@@ -62,7 +70,8 @@ class OracleSide:
                     outs[i] = fb(i, (gz, gh))
                     flips += n_diff
             assert flips <= 8, flips
-        res = O.apply_step(sts, self.p, batches, outs, lr)
+        res = O.apply_step(sts, self.p, batches, outs, lr, adam_state=self.adam_state, adam_hyper=self.adam_hyper,
+                           static=self.static if self.lr_static else None, lr_static=self.lr_static)
         res["relu_tie_flips"] = flips
         return res
 

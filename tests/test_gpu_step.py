@@ -222,3 +222,81 @@ def test_epoch_parallel_step_against_the_oracle(J, shape):
     b = batch_np(P, 0, d.batch)
     a1 = G1.step([b], n_neg_sets=1); a2 = G2.step([b])
     assert np.array_equal(a1["logits"], a2["logits"]) and np.array_equal(a1["winner"], a2["winner"])
+
+
+def test_adam_50_batches_against_the_oracle():
+    """Adam in the step's last launch (tgnn_set_optimizer): 50 consecutive C0 batches, parameters and both moment
+    tensors against the oracle's Adam.  The key bias is left out of the parameter comparison: its exact gradient is zero
+    (the softmax is invariant to a shift of a root's scores), both sides hold rounding noise of different size there, and
+    Adam's normalisation turns noise into steps of up to lr; its drift is bounded by n_steps * lr instead."""
+    import torch
+    from gpu_common import rel_err
+    from paper_2307_07649_amd import tgnn
+    P = make_problem("C0", random_phase=True)
+    d = P["d"]
+    G = GpuSide(P); Or = OracleSide(P)
+    m = tgnn.Params.zeros_like(G.params); v = tgnn.Params.zeros_like(G.params)
+    G.ctx.tgnn_set_optimizer(1, m, v, 0.9, 0.999, 1e-8)
+    Or.use_adam(0.9, 0.999, 1e-8)
+    lr = 1e-3
+    n_steps = 50
+    for s in range(n_steps):
+        b = batch_np(P, s * d.batch, (s + 1) * d.batch)
+        want = s in (0, 1, 25, 49)
+        g = G.step([b], lr=lr, want=want)
+        o = Or.step([b], lr=lr, gpu=g)
+        if want:
+            compare_step(g, o, label=f"adam step {s}")
+    compare_state(G.state_np(), Or.states[0], label="adam state")
+    gp, gm, gv = G.params.numpy(), m.numpy(), v.numpy()
+    for n in gp:
+        if n == "bk":
+            assert np.abs(gp[n] - Or.p[n]).max() <= n_steps * lr
+            continue
+        assert rel_err(gp[n], Or.p[n]) <= 1e-4, n
+        if n not in ("time_w", "time_b"):
+            assert rel_err(gm[n], Or.adam_state["m"][n]) <= 1e-4, ("m", n)
+            assert rel_err(gv[n], Or.adam_state["v"][n]) <= 2e-4, ("v", n)        # v is quadratic in the gradient
+    assert np.array_equal(gp["time_w"], P["params"]["time_w"]) and not gm["time_w"].any()
+    # moved by about n_steps * lr, i.e. the test would see a missing bias correction or a wrong moment
+    assert np.abs(gp["dec_ws"] - P["params"]["dec_ws"]).max() > 10 * lr
+    G.ctx.tgnn_set_optimizer(0)            # back to SGD: a step with lr = 0 leaves the parameters alone
+    before = G.params.numpy()
+    G.step([batch_np(P, 50 * d.batch, 51 * d.batch)], lr=0.0, want=False)
+    assert all(np.array_equal(before[n], x) for n, x in G.params.numpy().items())
+
+
+@pytest.mark.parametrize("nrep", [1, 3])
+def test_co_trained_static_memory_against_the_oracle(nrep):
+    """tgnn_train_static (Sec. 3.1, static memory as a co-trained embedding table): the gradient of the static rows
+    (dense [N, d_s], touched rows only) against the oracle on every checked step, and the table itself after 20 steps
+    of sparse SGD on it together with SGD on the weights; with three memory replicas the rows of one node in different
+    replicas add up."""
+    import torch
+    from gpu_common import rel_err
+    P = custom_problem(n_nodes=120, E=3000, d_mem=32, d_time=16, d_edge=8, d_static=20, n_heads=2, k=6, batch=100, seed=3)
+    d = P["d"]
+    G = GpuSide(P, n_replicas=nrep); Or = OracleSide(P, n_replicas=nrep)
+    gstat = torch.zeros(d.n_nodes, d.d_static, device="cuda")
+    lr_s = 5.0     # (the rows' gradients are ~1e-5: a rate that moves the table by a few per cent over the test)
+    G.ctx.tgnn_train_static(True, gstat, lr_s)
+    Or.train_static(lr_s)
+    n_steps = 20 // nrep + 2
+    for s in range(n_steps):
+        bl = [batch_np(P, (s * nrep + r) * d.batch, (s * nrep + r + 1) * d.batch) for r in range(nrep)]
+        gstat.zero_()
+        g = G.step(bl, lr=0.02)
+        o = Or.step(bl, lr=0.02, gpu=g)
+        compare_step(g, o, label=f"static nrep {nrep} step {s}")
+        ref = o["g_static"]
+        got = gstat.cpu().numpy()
+        assert rel_err(got, ref) <= 1e-4, (s, rel_err(got, ref))
+        assert np.all(got[np.all(ref == 0, axis=1)] == 0)              # untouched rows receive nothing
+    assert rel_err(G.state.stat.cpu().numpy(), Or.static) <= 1e-4
+    assert np.abs(Or.static - P["static"]).max() > 1e-3                # the table moved
+    for r in range(nrep):
+        compare_state(G.state_np(r), Or.states[r], label=f"replica {r}")
+    G.ctx.tgnn_train_static(False)
+    before = G.state.stat.clone()
+    G.step([batch_np(P, 0, d.batch)], lr=0.0, want=False)
+    assert torch.equal(before, G.state.stat)

@@ -253,3 +253,52 @@ def test_epoch_parallel_step_is_the_sum_of_its_trainers():
     O.apply_writeback(st_b, dict(bt, neg=negs[0]), singles[0])
     for key in st_a:
         assert np.array_equal(st_a[key], st_b[key])
+
+
+def test_static_memory_gradient_by_finite_differences():
+    """Co-trained static memory (Sec. 3.1): d loss / d static[w, c] against central differences, for nodes that are
+    roots, supporting nodes, both (several slots), and nodes the batch does not touch (zero)."""
+    P = tiny_problem(seed=21, n=50, d_s=3)
+    d = P["d"]
+    st = warm_state(P, 10)
+    bt = batch_of(P, 10 * d.batch, 11 * d.batch)
+    static = P["static"].astype(np.float64)
+    fb = O.forward_backward(st, P["adj"], P["efeat"], static, P["p"], bt, d.k, d.n_heads)
+    g = fb["g_static"]
+    assert g.shape == static.shape
+    refs = np.bincount(np.concatenate([np.concatenate([bt["src"], bt["dst"], bt["neg"]]), fb["nbr"][fb["nbr"] >= 0]]),
+                       minlength=d.n_nodes)
+    assert refs.max() >= 3 and (refs == 0).any()
+    assert np.all(g[refs == 0] == 0) and np.abs(g[refs > 0]).max() > 0
+    rng = np.random.default_rng(0)
+    nodes = list(rng.choice(np.nonzero(refs > 0)[0], 8, replace=False)) + [int(np.argmax(refs))]
+    for w in nodes:
+        for c in range(static.shape[1]):
+            h = 1e-6
+            sp = static.copy(); sp[w, c] += h
+            sm = static.copy(); sm[w, c] -= h
+            lp = O.forward_backward(st, P["adj"], P["efeat"], sp, P["p"], bt, d.k, d.n_heads, want_grads=False)["loss"]
+            lm = O.forward_backward(st, P["adj"], P["efeat"], sm, P["p"], bt, d.k, d.n_heads, want_grads=False)["loss"]
+            fd = (lp - lm) / (2 * h)
+            assert abs(fd - g[w, c]) <= 2e-7 * max(1.0, abs(fd)) + 1e-9, (w, c, fd, g[w, c])
+
+
+def test_adam_two_steps_by_hand():
+    """Two Adam steps on one scalar, worked out by hand with beta1 = 0.5, beta2 = 0.75, eps = 0, lr = 0.1, gradients
+    g1 = 2, g2 = -1:
+      step 1: m = 1, v = 1;       m^ = 1 / (1 - 0.5) = 2,      v^ = 1 / (1 - 0.75) = 4,        p = 1 - 0.1 * 2 / 2 = 0.9
+      step 2: m = 0, v = 1;       m^ = 0                                                         p stays 0.9
+    and a third with g3 = 4: m = 2, v = 4.75; m^ = 2 / (1 - 1/8) = 16/7, v^ = 4.75 / (1 - 27/64) = 304/37,
+      p = 0.9 - 0.1 * (16/7) / sqrt(304/37)."""
+    p = {n: np.array([1.0]) for n in O.PARAM_NAMES}
+    st = O.adam_init(p)
+    for g, want in ((2.0, 0.9), (-1.0, 0.9), (4.0, 0.9 - 0.1 * (16 / 7) / np.sqrt(304 / 37))):
+        O.adam(p, {n: np.array([g]) for n in O.PARAM_NAMES}, st, 0.1, 0.5, 0.75, 0.0)
+        assert abs(p["wq"][0] - want) < 1e-15 and abs(p["dec_b2"][0] - want) < 1e-15
+        assert p["time_w"][0] == 1.0 and p["time_b"][0] == 1.0          # frozen
+    assert st["t"] == 3
+    # with eps: p -= lr m^ / (sqrt(v^) + eps)
+    p = {n: np.array([0.0]) for n in O.PARAM_NAMES}
+    st = O.adam_init(p)
+    O.adam(p, {n: np.array([3.0]) for n in O.PARAM_NAMES}, st, 1.0, 0.9, 0.999, 1.0)
+    assert abs(p["wk"][0] + 3.0 / (3.0 + 1.0)) < 1e-15
