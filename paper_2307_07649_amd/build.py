@@ -28,16 +28,20 @@ def _compile(src: str, objdir: str) -> str:
     return obj
 
 
-def build_lib(jobs: int = 8) -> str:
-    objdir = os.path.join(HERE, "_build")
+def build_lib(jobs: int = 8, extra_flags=(), lib: str = LIB, objdir: str | None = None) -> str:
+    """extra_flags / lib / objdir: a variant build (e.g. -D overrides of tuning constants) beside the default one."""
+    global FLAGS
+    if extra_flags:
+        FLAGS = [*FLAGS, *extra_flags]
+    objdir = objdir or os.path.join(HERE, "_build")
     os.makedirs(objdir, exist_ok=True)
     with ThreadPoolExecutor(max_workers=jobs) as ex:
         objs = list(ex.map(lambda s: _compile(s, objdir), SOURCES))
-    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
+    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib, *objs]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"link failed:\n{r.stdout}\n{r.stderr}")
-    return LIB
+    return lib
 
 
 if __name__ == "__main__":

@@ -67,10 +67,9 @@ struct SlotRegs {
   float pv[FA_KR][FA_E];    // node part of the value
 };
 
-template <bool BWD>
-__device__ __forceinline__ void fast_load_slots(const FusedAttn& a, int lane, int c, const int (&e_j)[FA_KR],
-                                                const int (&row_j)[FA_KR], const double (&dt_j)[FA_KR], SlotRegs& s,
-                                                float (&st)[FA_KR][FA_NT]) {
+// the loads of every slot's edge-feature columns and node rows
+__device__ __forceinline__ void fast_issue_slots(const FusedAttn& a, int lane, int c, const int (&e_j)[FA_KR],
+                                                 const int (&row_j)[FA_KR], SlotRegs& s) {
 #pragma unroll
   for (int j = 0; j < FA_KR; ++j) {
     const bool on = j < c;
@@ -88,7 +87,12 @@ __device__ __forceinline__ void fast_load_slots(const FusedAttn& a, int lane, in
       s.pv[j][u] = (on && e < a.dO) ? prow[a.dO + e] : 0.f;
     }
   }
-  // time encoding of every slot, evaluated in place (Eq. 5-6); the backward pass also needs the sine
+}
+
+// time encoding of every slot, evaluated in place (Eq. 5-6); the backward pass also needs the sine
+template <bool BWD>
+__device__ __forceinline__ void fast_time_cols(const FusedAttn& a, int lane, int c, const double (&dt_j)[FA_KR],
+                                               SlotRegs& s, float (&st)[FA_KR][FA_NT]) {
 #pragma unroll
   for (int m = 0; m < FA_NT; ++m) {
     const int tc = lane + 64 * m;
@@ -102,6 +106,14 @@ __device__ __forceinline__ void fast_load_slots(const FusedAttn& a, int lane, in
       if (BWD) st[j][m] = sn;
     }
   }
+}
+
+template <bool BWD>
+__device__ __forceinline__ void fast_load_slots(const FusedAttn& a, int lane, int c, const int (&e_j)[FA_KR],
+                                                const int (&row_j)[FA_KR], const double (&dt_j)[FA_KR], SlotRegs& s,
+                                                float (&st)[FA_KR][FA_NT]) {
+  fast_issue_slots(a, lane, c, e_j, row_j, s);
+  fast_time_cols<BWD>(a, lane, c, dt_j, s, st);
 }
 
 // the per-head rows u_h (or g_h): edge-feature and time columns of head h's block of a row of pitch ldz
@@ -166,7 +178,7 @@ __device__ __forceinline__ void softmax_heads(float* sa, int HK, int k, int c, i
   }
 }
 
-__global__ __launch_bounds__(256) void fattn_fwd_fast_kernel(FusedAttn a) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) void fattn_fwd_fast_kernel(FusedAttn a) {
   extern __shared__ float lds[];
   int block = blockIdx.x;
   if (a.fill.ucnt != nullptr) {   // the first blocks are passengers: the fill pass of the slot sort
@@ -185,27 +197,38 @@ __global__ __launch_bounds__(256) void fattn_fwd_fast_kernel(FusedAttn a) {
   const int c = a.cnt[r];
   float* pr = a.prob + (size_t)r * HK;
   float* out = a.Onode + (size_t)r * a.ldh;
-  int my_e, my_row;
-  double my_dt;
-  slot_ids(a, r, min(lane, a.k - 1), lane < a.k ? c : 0, my_e, my_row, my_dt, true);
-  if (lane < a.k) a.dtk[(size_t)r * a.k + lane] = my_dt;
+  // Round trip 1 (issued together with the count above, none depends on another): this lane's slot ids, the root's
+  // node row and query time.  Padding slots carry -1 in both index arrays.
+  const int sl = r * a.k + min(lane, a.k - 1);
+  int my_e = a.neid != nullptr ? a.neid[sl] : sl;
+  int my_row = a.slot_row != nullptr ? a.slot_row[a.R + sl] : a.R + sl;
+  const int my_qrow = a.slot_row != nullptr ? a.slot_row[r] : r;
+  double my_dt = 0.0;
+  const bool from_tau = a.dt_in == nullptr && a.dt_source == 0;
+  if (a.dt_in != nullptr) my_dt = a.dt_in[sl];
+  else if (a.dt_source != 0) my_dt = a.root_t[r] - a.nts[sl];
+  else my_dt = a.root_t[r];
+  const bool own = lane < a.k && lane < c;
+  if (!own) { my_e = -1; my_row = 0; }
   if (c == 0) {
+    if (lane < a.k) a.dtk[(size_t)r * a.k + lane] = 0.0;
     for (int p = lane; p < HK; p += 64) pr[p] = 0.f;
     for (int e = lane; e < a.dO; e += 64) out[e] = 0.f;
     zero_head_rows(a, a.Zp + (size_t)r * a.ldz, lane);
     return;
   }
-  const size_t qrow = a.slot_row != nullptr ? (size_t)a.slot_row[r] : (size_t)r;
+  // Round trip 2: the update time of the neighbour's memory (Eq. 5-6: the time difference is taken against it),
+  // asked for first, and behind it the burst of everything else the root needs
+  double my_tau = 0.0;
+  if (from_tau && own) my_tau = a.tau[my_row];
+  const size_t qrow = (size_t)my_qrow;
   const float scale = 1.0f / sqrtf((float)c);
   int e_j[FA_KR], row_j[FA_KR];
-  double dt_j[FA_KR];
 #pragma unroll
   for (int j = 0; j < FA_KR; ++j) {
     // (readlane: one value for the whole wavefront, kept in scalar registers)
     e_j[j] = __builtin_amdgcn_readlane(my_e, j);
     row_j[j] = __builtin_amdgcn_readlane(my_row, j);
-    dt_j[j] = __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(my_dt), j),
-                               __builtin_amdgcn_readlane(__double2loint(my_dt), j));
   }
   // the burst: the root's query and u rows, then every slot's columns
   float qreg[FA_E];
@@ -217,8 +240,18 @@ __global__ __launch_bounds__(256) void fattn_fwd_fast_kernel(FusedAttn a) {
   HeadRow ur;
   load_head_row(a, a.U + qrow * a.ldz, lane, ur);
   SlotRegs s;
+  fast_issue_slots(a, lane, c, e_j, row_j, s);
+  // the time differences, once the update times are in
+  if (from_tau) my_dt -= my_tau;
+  if (!own) my_dt = 0.0;
+  if (lane < a.k) a.dtk[(size_t)r * a.k + lane] = my_dt;
+  double dt_j[FA_KR];
+#pragma unroll
+  for (int j = 0; j < FA_KR; ++j)
+    dt_j[j] = __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(my_dt), j),
+                               __builtin_amdgcn_readlane(__double2loint(my_dt), j));
   float unused[FA_KR][FA_NT];
-  fast_load_slots<false>(a, lane, c, e_j, row_j, dt_j, s, unused);
+  fast_time_cols<false>(a, lane, c, dt_j, s, unused);
   // scores (Eq. 7): per slot and head, this lane's share of q . Pk + u . c, summed over the wavefront
   float part[FA_KR][FA_HM];
 #pragma unroll

@@ -80,7 +80,9 @@ void gather_rows(const GatherArgs& a, hipStream_t s) {
                             (long long)((uintptr_t)a.efeat / 4)});
   // a row count that lives on the device is usually a small part of its bound: launch for a quarter of it (the
   // waves stride over the rows, so more rows only mean more rounds)
-  const int rows_launched = a.n_dev != nullptr ? std::min(a.n_slots, std::max(512, (a.n_slots + 3) / 4)) : a.n_slots;
+  const int rows_launched = a.n_dev == nullptr ? a.n_slots
+                            : a.launch_rows > 0 ? std::min(a.n_slots, a.launch_rows)
+                                                : std::min(a.n_slots, std::max(512, (a.n_slots + 3) / 4));
   const int blocks = (rows_launched + 3) / 4 + (a.map.ucnt != nullptr ? (a.map.S + 255) / 256 : 0);
   if (vec == 4) hipLaunchKernelGGL(gather_kernel<4>, dim3(blocks), dim3(256), 0, s, a);
   else if (vec == 2) hipLaunchKernelGGL(gather_kernel<2>, dim3(blocks), dim3(256), 0, s, a);

@@ -462,9 +462,12 @@ constexpr int TN_AHEAD = 4;   // 4-row steps whose loads a wavefront keeps in fl
 constexpr int TN_ROWS = 32;   // row chunks are multiples of this
 
 // A length is cut into 64-wide pieces plus at most two narrower ones (32 and/or 16 wide) for the remainder.
+#ifndef TGNN_TN_SPLIT48
+#define TGNN_TN_SPLIT48 1
+#endif
 __host__ __device__ inline int tn_pieces(int len) {
   const int r = len % TT;
-  return len / TT + (r == 0 ? 0 : (r > 32 && r <= 48) ? 2 : 1);
+  return len / TT + (r == 0 ? 0 : (TGNN_TN_SPLIT48 && r > 32 && r <= 48) ? 2 : 1);
 }
 __device__ __forceinline__ void tn_piece(int len, int idx, int& off, int& width) {
   const int full = len / TT;
@@ -473,7 +476,7 @@ __device__ __forceinline__ void tn_piece(int len, int idx, int& off, int& width)
   off = full * TT;
   if (r <= 16) width = 16;
   else if (r <= 32) width = 32;
-  else if (r <= 48) { if (idx == full) width = 32; else { off += 32; width = 16; } }
+  else if (TGNN_TN_SPLIT48 && r <= 48) { if (idx == full) width = 32; else { off += 32; width = 16; } }
   else width = TT;
 }
 // Column window of D that one head of head_n columns is tiled over (its start is rounded down to 16 bytes).
@@ -768,8 +771,14 @@ void TnBatch::add(const float* D, int ldd, const float* A, int lda, int M, int N
 // 0.5 to 0.8 us per 4-row step whatever the tile width, because the loads of narrow tiles are 64- to 256-byte
 // pieces of four rows and the texture addresser, not the MFMA pipe, is what the 16 wavefronts of a compute unit
 // queue for; the reduction and the atomics take 2 to 3 us.
-constexpr int TN_MAX_ROWS = 1024;
-constexpr int TN_WGS_PER_XCD = 80;
+#ifndef TGNN_TN_MAX_ROWS
+#define TGNN_TN_MAX_ROWS 1024
+#endif
+#ifndef TGNN_TN_WGS_PER_XCD
+#define TGNN_TN_WGS_PER_XCD 80
+#endif
+constexpr int TN_MAX_ROWS = TGNN_TN_MAX_ROWS;
+constexpr int TN_WGS_PER_XCD = TGNN_TN_WGS_PER_XCD;
 
 // Chunks of `rows_per_chunk` rows for every problem, then the placement on the eight XCDs: problems in order
 // of decreasing size, each rotated so that the XCDs which receive one chunk more than the others are the least
@@ -816,7 +825,10 @@ void TnBatch::launch(hipStream_t s) {
   const int max_rows = TN_MAX_ROWS;
   int rows[TN_MAX_GROUP];
   // a row count that lives on the device (distinct nodes of a step) is usually a small part of its bound
-  for (int i = 0; i < g.n; ++i) rows[i] = g.p[i].m_dev != nullptr ? (g.p[i].M + 7) / 8 : g.p[i].M;
+  for (int i = 0; i < g.n; ++i)
+    rows[i] = g.p[i].m_dev == nullptr ? g.p[i].M
+              : dev_rows_est > 0      ? std::min(g.p[i].M, dev_rows_est)
+                                      : (g.p[i].M + 7) / 8;
   // smallest chunk length (in units of TN_ROWS) whose placement fits the chip at once, by bisection
   int lo = 4, hi = max_rows / TN_ROWS;   // lo: at least four steps per wavefront; hi: taken if nothing smaller fits
   int longest = tn_place(g, rows, hi * TN_ROWS);

@@ -4,6 +4,7 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <algorithm>
 #include <new>
 #include <vector>
 
@@ -966,6 +967,9 @@ static int enqueue_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
   tm.end(2);
   // UPDT once per distinct (replica, node) among the root and supporting nodes, from the pre-batch state
   const int U = S < d.maxU ? S : d.maxU;   // launch bound; the actual row count is *w.ucount on the device
+  // distinct node rows to expect: an eighth of the slots (a step's slots repeat nodes many times over on the
+  // power-law graphs), but never more than there are nodes.  Kernels that stride over the rows are launched for it.
+  const int U_est = std::min(U, std::max(S / 8, 64));
   GatherArgs a;
   memset(&a, 0, sizeof(a));
   a.mem = st->mem; a.mail = st->mail; a.efeat = g->efeat; a.mem_ts = st->mem_ts; a.mail_ts = st->mail_ts;
@@ -977,6 +981,7 @@ static int enqueue_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
   a.o_tau = w.tau; a.o_delta = w.delta; a.o_has = w.has;
   a.time_w = p->time_w; a.time_b = p->time_b;
   a.n_slots = U; a.dm = d.dm; a.dt = d.dt; a.de = d.de;
+  a.launch_rows = U_est;
   a.map = sort_args(ctx, S);   // the slot -> row map rides along
   a.epoch_bump = w.epoch;      // the first launch worked with epoch + 1; from here on that is the epoch
   tm.begin(3);
@@ -995,7 +1000,7 @@ static int enqueue_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
   // The GRU gates (with the scan of the slot sort) -> node rows x = {s' | static}
   tm.begin(6);
   gru_gates_fwd(gru_gates_args(d, U, w.ucount, w.gi, w.gh, w.Hm, w.has, w.gates, w.Xrow, d.ldxr, d.ds ? st->stat : nullptr,
-                               w.ulist, w.dP, d.ldp, sort_args(ctx, S)), s);
+                               w.ulist, w.dP, d.ldp, sort_args(ctx, S), U_est), s);
   tm.end(6);
   // (the fill pass of the slot sort, needed by the backward pass only, rides in the attention launch)
   // Merge layer, decoder + loss and their backward pass down to the attention output are local to an event's
@@ -1034,6 +1039,7 @@ static int enqueue_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
   dec.p[0][0] = grads->dec_ws; dec.p[1][0] = grads->dec_wd; dec.ld[0][0] = dec.ld[1][0] = d.dO;
   dec.n_split = d.dO; dec.k_split = 1 << 30; dec.bias[1] = grads->dec_b1;   // every pair is in one W_d half
   TnBatch tn;
+  tn.dev_rows_est = U_est;
   tn.add(w.dPdec, d.ldkv, w.z, d.ldh, R, 2 * d.dO, d.dO, dec);
   if (!chain) {  // dz, gated by the ReLU of the merge layer
     RowAdd gate;

@@ -347,6 +347,9 @@ struct TnGroup {
 };
 struct TnBatch {
   TnGroup g;
+  // rows to expect of a problem whose row count lives on the device (the chunking is laid out for it; any count
+  // works, a poor guess only costs time).  0: an eighth of the problem's bound.
+  int dev_rows_est = 0;
   TnBatch() { g.n = 0; }
   void add(const float* D, int ldd, const float* A, int lda, int M, int N, int K, const OutMap& out,
            const int* m_dev = nullptr);
@@ -524,7 +527,7 @@ __host__ __device__ inline int gru_total_blocks(const GruFwdArgs& a) {
 }
 GruFwdArgs gru_gates_args(const Dims& d, int n, const int* n_dev, const float* gi, const float* gh, const float* Hm,
                           const int32_t* has, float* gates, float* x_out, int ld_x, const float* stat, const int32_t* gid,
-                          float* zero_buf, int zero_w, const SortArgs& scan = SortArgs());
+                          float* zero_buf, int zero_w, const SortArgs& scan = SortArgs(), int launch_rows = 0);
 void gru_gates_fwd(const GruFwdArgs& a, hipStream_t s);
 
 // ---- k_gather.hip -------------------------------------------------------------------
@@ -535,6 +538,7 @@ struct GatherArgs {
   const int32_t* mail_eid;  // NULL: the staged layout of tgnn_gru_update (row index = slot, has_in given)
   const int32_t* has_in;
   const int32_t* n_dev;     // device row count (NULL: n_slots)
+  int launch_rows;          // with n_dev: rows to launch for (0: a quarter of n_slots); the waves stride over the rest
   const int32_t* slot_gid;  // NULL: identity
   int gid_add;              // added to every non-negative slot_gid entry (replica offset)
   // destinations (pitches in floats)

@@ -12,7 +12,7 @@ import os
 import numpy as np
 import torch
 
-_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libtgnn.so")
+_LIB_PATH = os.environ.get("TGNN_LIB") or os.path.join(os.path.dirname(os.path.abspath(__file__)), "libtgnn.so")
 if not os.path.exists(_LIB_PATH):
     raise ImportError(f"{_LIB_PATH} not found: build it with `python -m paper_2307_07649_amd.build`")
 _lib = C.CDLL(_LIB_PATH)
