@@ -70,22 +70,60 @@ struct SlotRegs {
 // the loads of every slot's edge-feature columns and node rows
 __device__ __forceinline__ void fast_issue_slots(const FusedAttn& a, int lane, int c, const int (&e_j)[FA_KR],
                                                  const int (&row_j)[FA_KR], SlotRegs& s) {
+  // Column offsets are clamped into the row instead of guarded (no per-lane branch around a load); what a clamped
+  // lane reads is replaced by zero.  Absent slots (j >= c, uniform over the wavefront) are skipped.
+  int ecol[FA_NE], pcol[FA_E];
+  bool elive[FA_NE], plive[FA_E];
+#pragma unroll
+  for (int m = 0; m < FA_NE; ++m) {
+    elive[m] = lane + 64 * m < a.de;
+    ecol[m] = min(lane + 64 * m, max(a.de - 1, 0));
+  }
+#pragma unroll
+  for (int u = 0; u < FA_E; ++u) {
+    plive[u] = lane + 64 * u < a.dO;
+    pcol[u] = min(lane + 64 * u, a.dO - 1);
+  }
 #pragma unroll
   for (int j = 0; j < FA_KR; ++j) {
-    const bool on = j < c;
-    const float* erow = a.efeat + (size_t)(on ? e_j[j] : 0) * a.de;
 #pragma unroll
-    for (int m = 0; m < FA_NE; ++m) {
-      const int col = lane + 64 * m;
-      s.ce[j][m] = (on && col < a.de) ? erow[col] : 0.f;
+    for (int m = 0; m < FA_NE; ++m) s.ce[j][m] = 0.f;
+#pragma unroll
+    for (int u = 0; u < FA_E; ++u) s.pk[j][u] = s.pv[j][u] = 0.f;
+    if (j < c) {
+      if (a.de > 0) {
+        const float* erow = a.efeat + (size_t)e_j[j] * a.de;
+#pragma unroll
+        for (int m = 0; m < FA_NE; ++m) s.ce[j][m] = erow[ecol[m]];
+      }
+      const float* prow = a.P + (size_t)row_j[j] * a.ldp;
+#pragma unroll
+      for (int u = 0; u < FA_E; ++u) {
+        s.pk[j][u] = prow[pcol[u]];
+        s.pv[j][u] = prow[a.dO + pcol[u]];
+      }
     }
-    const float* prow = a.P + (size_t)(on ? row_j[j] : 0) * a.ldp;
+  }
+#pragma unroll
+  for (int j = 0; j < FA_KR; ++j) {
+#pragma unroll
+    for (int m = 0; m < FA_NE; ++m) s.ce[j][m] = elive[m] ? s.ce[j][m] : 0.f;
 #pragma unroll
     for (int u = 0; u < FA_E; ++u) {
-      const int e = lane + 64 * u;
-      s.pk[j][u] = (on && e < a.dO) ? prow[e] : 0.f;
-      s.pv[j][u] = (on && e < a.dO) ? prow[a.dO + e] : 0.f;
+      s.pk[j][u] = plive[u] ? s.pk[j][u] : 0.f;
+      s.pv[j][u] = plive[u] ? s.pv[j][u] : 0.f;
     }
+  }
+}
+
+// which head a lane's output columns lane + 64 u belong to: 1.0 where it is head hh, else 0 (0 beyond d_o)
+__device__ __forceinline__ void head_masks(const FusedAttn& a, int lane, float (&mh)[FA_HM][FA_E]) {
+#pragma unroll
+  for (int u = 0; u < FA_E; ++u) {
+    const int e = lane + 64 * u;
+    const int h = e / a.dh;   // (two divisions per wavefront, not one per slot and head)
+#pragma unroll
+    for (int hh = 0; hh < FA_HM; ++hh) mh[hh][u] = (e < a.dO && h == hh) ? 1.f : 0.f;
   }
 }
 
@@ -101,7 +139,11 @@ __device__ __forceinline__ void fast_time_cols(const FusedAttn& a, int lane, int
 #pragma unroll
     for (int j = 0; j < FA_KR; ++j) {
       float sn = 0.f, cs = 0.f;
-      if (live && j < c) sincos_reduced(fma(w, dt_j[j], b), sn, cs);
+      if (j < c) {   // (uniform over the wavefront; lanes beyond d_t compute on zeros and are masked)
+        sincos_reduced(fma(w, dt_j[j], b), sn, cs);
+        sn = live ? sn : 0.f;
+        cs = live ? cs : 0.f;
+      }
       s.ct[j][m] = cs;
       if (BWD) st[j][m] = sn;
     }
@@ -121,18 +163,23 @@ struct HeadRow {
   float e[FA_HM][FA_NE], t[FA_HM][FA_NT];
 };
 __device__ __forceinline__ void load_head_row(const FusedAttn& a, const float* row, int lane, HeadRow& h) {
+  // (clamped column offsets instead of per-lane guards around the loads; a head beyond H is uniform)
 #pragma unroll
   for (int hh = 0; hh < FA_HM; ++hh) {
     const float* blk = row + hh * a.dcp;
 #pragma unroll
     for (int m = 0; m < FA_NE; ++m) {
       const int col = lane + 64 * m;
-      h.e[hh][m] = (hh < a.H && col < a.de) ? blk[col] : 0.f;
+      float v = 0.f;
+      if (hh < a.H && a.de > 0) v = blk[min(col, a.de - 1)];
+      h.e[hh][m] = col < a.de ? v : 0.f;
     }
 #pragma unroll
     for (int m = 0; m < FA_NT; ++m) {
       const int tc = lane + 64 * m;
-      h.t[hh][m] = (hh < a.H && tc < a.dt) ? blk[a.de + tc] : 0.f;
+      float v = 0.f;
+      if (hh < a.H) v = blk[a.de + min(tc, a.dt - 1)];
+      h.t[hh][m] = tc < a.dt ? v : 0.f;
     }
   }
 }
@@ -253,6 +300,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
   float unused[FA_KR][FA_NT];
   fast_time_cols<false>(a, lane, c, dt_j, s, unused);
   // scores (Eq. 7): per slot and head, this lane's share of q . Pk + u . c, summed over the wavefront
+  float mh[FA_HM][FA_E], qh[FA_HM][FA_E];
+  head_masks(a, lane, mh);
+#pragma unroll
+  for (int hh = 0; hh < FA_HM; ++hh)
+#pragma unroll
+    for (int u = 0; u < FA_E; ++u) qh[hh][u] = mh[hh][u] * qreg[u];
   float part[FA_KR][FA_HM];
 #pragma unroll
   for (int j = 0; j < FA_KR; ++j) {
@@ -264,10 +317,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
 #pragma unroll
       for (int m = 0; m < FA_NT; ++m) acc += ur.t[hh][m] * s.ct[j][m];
 #pragma unroll
-      for (int u = 0; u < FA_E; ++u) {
-        const int e = lane + 64 * u;
-        if (e < a.dO && e / a.dh == hh) acc += qreg[u] * s.pk[j][u];
-      }
+      for (int u = 0; u < FA_E; ++u) acc += qh[hh][u] * s.pk[j][u];
       part[j][hh] = acc;
     }
   }
@@ -303,11 +353,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
 #pragma unroll
     for (int hh = 0; hh < FA_HM; ++hh) pj[hh] = (hh < a.H && j < a.k) ? sa[HK + hh * a.k + j] : 0.f;
 #pragma unroll
-    for (int u = 0; u < FA_E; ++u) {
-      const int e = lane + 64 * u;
-      const int h = min(e, a.dO - 1) / a.dh;
-      o[u] += (h == 0 ? pj[0] : pj[FA_HM - 1]) * s.pv[j][u];
-    }
+    for (int u = 0; u < FA_E; ++u) o[u] += (mh[0][u] * pj[0] + mh[FA_HM - 1][u] * pj[FA_HM - 1]) * s.pv[j][u];
 #pragma unroll
     for (int hh = 0; hh < FA_HM; ++hh) {
 #pragma unroll
@@ -370,6 +416,12 @@ __global__ __launch_bounds__(256) void fattn_bwd_fast_kernel(FusedAttn a) {
   float st[FA_KR][FA_NT];
   fast_load_slots<true>(a, lane, c, e_j, row_j, dt_j, s, st);
   // dp_jh = dO_h . V_jh = dO_h . Pv_h[w_j] + g_h . c_j
+  float mh[FA_HM][FA_E], doh[FA_HM][FA_E];
+  head_masks(a, lane, mh);
+#pragma unroll
+  for (int hh = 0; hh < FA_HM; ++hh)
+#pragma unroll
+    for (int u = 0; u < FA_E; ++u) doh[hh][u] = mh[hh][u] * doreg[u];
   float part[FA_KR][FA_HM];
 #pragma unroll
   for (int j = 0; j < FA_KR; ++j) {
@@ -381,10 +433,7 @@ __global__ __launch_bounds__(256) void fattn_bwd_fast_kernel(FusedAttn a) {
 #pragma unroll
       for (int m = 0; m < FA_NT; ++m) acc += gr.t[hh][m] * s.ct[j][m];
 #pragma unroll
-      for (int u = 0; u < FA_E; ++u) {
-        const int e = lane + 64 * u;
-        if (e < a.dO && e / a.dh == hh) acc += doreg[u] * s.pv[j][u];
-      }
+      for (int u = 0; u < FA_E; ++u) acc += doh[hh][u] * s.pv[j][u];
       part[j][hh] = acc;
     }
   }
@@ -439,11 +488,7 @@ __global__ __launch_bounds__(256) void fattn_bwd_fast_kernel(FusedAttn a) {
       pj[hh] = (hh < a.H && j < a.k) ? sa[hh * a.k + j] : 0.f;
     }
 #pragma unroll
-    for (int u = 0; u < FA_E; ++u) {
-      const int e = lane + 64 * u;
-      const int h = min(e, a.dO - 1) / a.dh;
-      dq[u] += (h == 0 ? dsj[0] : dsj[FA_HM - 1]) * s.pk[j][u];
-    }
+    for (int u = 0; u < FA_E; ++u) dq[u] += (mh[0][u] * dsj[0] + mh[FA_HM - 1][u] * dsj[FA_HM - 1]) * s.pk[j][u];
     const float dtf = (float)dt_j[j];
 #pragma unroll
     for (int hh = 0; hh < FA_HM; ++hh) {
