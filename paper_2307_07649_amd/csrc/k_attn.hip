@@ -229,7 +229,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
   extern __shared__ float lds[];
   int block = blockIdx.x;
   if (a.fill.ucnt != nullptr) {   // the first blocks are passengers: the fill pass of the slot sort
-    const int fill_blocks = (a.fill.S + 255) / 256;
+    const int fill_blocks = uniq_blocks(a.fill.S);
     if (block < fill_blocks) {
       uniq_fill_block(a.fill, block);
       return;
@@ -563,7 +563,7 @@ __global__ __launch_bounds__(256) void fattn_fwd_gen_kernel(FusedAttn a) {
   extern __shared__ __attribute__((aligned(16))) char lds_raw[];
   int block = blockIdx.x;
   if (a.fill.ucnt != nullptr) {
-    const int fill_blocks = (a.fill.S + 255) / 256;
+    const int fill_blocks = uniq_blocks(a.fill.S);
     if (block < fill_blocks) {
       uniq_fill_block(a.fill, block);
       return;
@@ -749,7 +749,7 @@ static bool fast_path(const FusedAttn& a) {
 
 void fattn_fwd(const FusedAttn& a, hipStream_t s) {
   if (a.R <= 0) return;
-  const int fill_blocks = a.fill.ucnt != nullptr ? (a.fill.S + 255) / 256 : 0;
+  const int fill_blocks = a.fill.ucnt != nullptr ? uniq_blocks(a.fill.S) : 0;
   const dim3 grid((a.R + 3) / 4 + fill_blocks);
   if (fast_path(a))
     hipLaunchKernelGGL(fattn_fwd_fast_kernel, grid, dim3(256), 4 * sizeof(float) * fattn_lds_floats(a.k, a.H), s, a);

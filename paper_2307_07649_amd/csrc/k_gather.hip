@@ -15,7 +15,7 @@ __global__ __launch_bounds__(256) void gather_kernel(GatherArgs a) {
   if (a.epoch_bump != nullptr && blockIdx.x == 0 && threadIdx.x == 0) *a.epoch_bump += 1ull;   // nothing here reads it
   int block = blockIdx.x, n_blocks = gridDim.x;
   if (a.map.ucnt != nullptr) {   // the first blocks are passengers: the slot -> row map
-    const int map_blocks = (a.map.S + (int)blockDim.x - 1) / (int)blockDim.x;
+    const int map_blocks = uniq_blocks(a.map.S);
     if (block < map_blocks) {
       uniq_map_block(a.map, block);
       return;
@@ -25,6 +25,13 @@ __global__ __launch_bounds__(256) void gather_kernel(GatherArgs a) {
   const int lane = threadIdx.x & 63;
   const int wpb = blockDim.x >> 6;
   const int n_slots = a.n_dev ? min(a.n_slots, *a.n_dev) : a.n_slots;
+  typedef float vecf __attribute__((ext_vector_type(VEC)));
+  // rows that fit a few vector registers per lane are moved in three round trips: the row's ids, then memory, mail
+  // and their times together, then the mail's edge-feature row; all stores come last (a store issued between two
+  // loads would make the later load wait for it)
+  constexpr int RM = 2, RL = 4, RE = 4;   // vectors per lane: memory, mail, edge-feature row
+  const bool fits = a.dm <= RM * 64 * VEC && 2 * a.dm <= RL * 64 * VEC && a.de <= RE * 64 * VEC && a.o_phi != nullptr &&
+                    a.o_ef != nullptr && a.mail_eid != nullptr;
   for (int s = block * wpb + (threadIdx.x >> 6); s < n_slots; s += n_blocks * wpb) {
     int gid = a.slot_gid ? a.slot_gid[s] : s;
     if (gid >= 0) gid += a.gid_add;
@@ -32,6 +39,60 @@ __global__ __launch_bounds__(256) void gather_kernel(GatherArgs a) {
     float* o_mail = a.o_mail + (size_t)s * a.p_mail;
     float* o_ef = a.o_ef ? a.o_ef + (size_t)s * a.p_ef : nullptr;
     float* o_phi = a.o_phi ? a.o_phi + (size_t)s * a.p_phi : nullptr;
+    if (fits && gid >= 0) {
+      const int nm = a.dm / VEC, nl = 2 * a.dm / VEC, ne = a.de / VEC;
+      const int me = a.mail_eid[gid];
+      const double mem_ts = a.mem_ts[gid], mail_ts = a.mail_ts[gid];
+      vecf rm[RM], rl[RL], re[RE];
+      const vecf* pm = reinterpret_cast<const vecf*>(a.mem + (size_t)gid * a.dm);
+      const vecf* pl = reinterpret_cast<const vecf*>(a.mail + (size_t)gid * 2 * a.dm);
+#pragma unroll
+      for (int u = 0; u < RM; ++u) rm[u] = pm[min(lane + 64 * u, nm - 1)];
+#pragma unroll
+      for (int u = 0; u < RL; ++u) rl[u] = pl[min(lane + 64 * u, nl - 1)];
+      const bool has = me >= 0;
+      if (has && ne > 0) {
+        const vecf* pe = reinterpret_cast<const vecf*>(a.efeat + (size_t)me * a.de);
+#pragma unroll
+        for (int u = 0; u < RE; ++u) re[u] = pe[min(lane + 64 * u, ne - 1)];
+      } else {
+#pragma unroll
+        for (int u = 0; u < RE; ++u) re[u] = vecf(0.f);
+      }
+      const double delta = has ? mail_ts - mem_ts : 0.0;
+      float phi[2];   // the first 128 time columns (the rest, if any, are written directly below)
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        const int c = lane + 64 * u;
+        phi[u] = c < a.dt ? time_enc(delta, a.time_w[c], a.time_b[c]) : 0.f;
+      }
+      // stores
+#pragma unroll
+      for (int u = 0; u < RM; ++u)
+        if (lane + 64 * u < nm) reinterpret_cast<vecf*>(o_mem)[lane + 64 * u] = rm[u];
+      for (int i = lane; i < a.z_mem; i += 64) o_mem[a.dm + i] = 0.f;
+#pragma unroll
+      for (int u = 0; u < RL; ++u)
+        if (lane + 64 * u < nl) reinterpret_cast<vecf*>(o_mail)[lane + 64 * u] = rl[u];
+      for (int i = lane; i < a.z_mail; i += 64) o_mail[2 * a.dm + i] = 0.f;
+#pragma unroll
+      for (int u = 0; u < RE; ++u)
+        if (lane + 64 * u < ne) reinterpret_cast<vecf*>(o_ef)[lane + 64 * u] = re[u];
+      for (int i = lane; i < a.z_ef; i += 64) o_ef[a.de + i] = 0.f;
+#pragma unroll
+      for (int u = 0; u < 2; ++u)
+        if (lane + 64 * u < a.dt) o_phi[lane + 64 * u] = phi[u];
+      for (int c = 128 + lane; c < a.dt; c += 64) o_phi[c] = time_enc(delta, a.time_w[c], a.time_b[c]);
+      for (int c = lane; c < a.z_phi; c += 64) o_phi[a.dt + c] = 0.f;
+      if (lane == 0) {
+        if (a.o_has) a.o_has[s] = has ? 1 : 0;
+        if (a.o_mem_ts) a.o_mem_ts[s] = mem_ts;
+        if (a.o_mail_ts) a.o_mail_ts[s] = mail_ts;
+        if (a.o_tau) a.o_tau[s] = has ? mail_ts : mem_ts;
+        if (a.o_delta) a.o_delta[s] = delta;
+      }
+      continue;
+    }
     int me = -1;
     double mem_ts = 0.0, mail_ts = 0.0;
     if (gid >= 0) {
@@ -83,7 +144,7 @@ void gather_rows(const GatherArgs& a, hipStream_t s) {
   const int rows_launched = a.n_dev == nullptr ? a.n_slots
                             : a.launch_rows > 0 ? std::min(a.n_slots, a.launch_rows)
                                                 : std::min(a.n_slots, std::max(512, (a.n_slots + 3) / 4));
-  const int blocks = (rows_launched + 3) / 4 + (a.map.ucnt != nullptr ? (a.map.S + 255) / 256 : 0);
+  const int blocks = (rows_launched + 3) / 4 + (a.map.ucnt != nullptr ? uniq_blocks(a.map.S) : 0);
   if (vec == 4) hipLaunchKernelGGL(gather_kernel<4>, dim3(blocks), dim3(256), 0, s, a);
   else if (vec == 2) hipLaunchKernelGGL(gather_kernel<2>, dim3(blocks), dim3(256), 0, s, a);
   else hipLaunchKernelGGL(gather_kernel<1>, dim3(blocks), dim3(256), 0, s, a);

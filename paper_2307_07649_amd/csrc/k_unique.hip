@@ -35,6 +35,12 @@ __device__ __forceinline__ float slot_grad(const SlotGrads& g, int sl, int c) {
 }
 
 constexpr int SEG_CHUNK = 16;
+// SPAN: consecutive chunks per wavefront (1, 2 or 4).  The accumulators of a run of equal rows carry over from chunk
+// to chunk, so a node with thousands of slots (a tenth of a step's slots sit on one node of a power-law graph) costs
+// one atomic row update per SPAN chunks.  Measured on MI355X it does not pay: the launch is bound by the chain of
+// dependent loads of a wavefront, not by the atomics on the popular rows (SPAN 4 against 1: 57 against 49 us for a
+// 4,000-event step, SPAN 2: 19 against 14 us for a 600-event step), so the launcher uses 1.
+template <int SPAN>
 __global__ __launch_bounds__(256) void seg_reduce_kernel(int R, int S, int dO, const int32_t* __restrict__ sort_total,
                                                          const int32_t* __restrict__ sorted,
                                                          const int32_t* __restrict__ sorted_row,
@@ -50,12 +56,11 @@ __global__ __launch_bounds__(256) void seg_reduce_kernel(int R, int S, int dO, c
     block -= nq;
   }
   const int lane = threadIdx.x & 63;
-  const int chunk = block * 4 + (threadIdx.x >> 6);
-  const int p0 = chunk * SEG_CHUNK;
-  // lanes fetch the chunk's slot ids and rows in parallel, without waiting for the length of the list (entries
+  const int p0 = (block * 4 + (threadIdx.x >> 6)) * SEG_CHUNK * SPAN;
+  // lanes fetch the span's slot ids and rows in parallel, without waiting for the length of the list (entries
   // past it are dropped below); they are broadcast afterwards
   int my_slot = -1, my_row = -1;
-  if (lane < SEG_CHUNK && p0 + lane < S) {
+  if (lane < SEG_CHUNK * SPAN && p0 + lane < S) {
     my_slot = sorted[p0 + lane];
     my_row = sorted_row[p0 + lane];
   }
@@ -69,15 +74,6 @@ __global__ __launch_bounds__(256) void seg_reduce_kernel(int R, int S, int dO, c
     const int sl = my_slot - R;
     my_r = sl / sg.k;
     my_j = sl - my_r * sg.k;
-  }
-  int slots[SEG_CHUNK], rows[SEG_CHUNK], rr[SEG_CHUNK], jj[SEG_CHUNK];
-#pragma unroll
-  for (int i = 0; i < SEG_CHUNK; ++i) {
-    // (readlane: the values are the same for every lane, so they live in scalar registers)
-    slots[i] = __builtin_amdgcn_readlane(my_slot, i);
-    rows[i] = __builtin_amdgcn_readlane(my_row, i);
-    rr[i] = __builtin_amdgcn_readlane(my_r, i);
-    jj[i] = __builtin_amdgcn_readlane(my_j, i);
   }
   const int HK = sg.H * sg.k;
   for (int cb = 0; cb < dO; cb += 128) {   // 128 columns of each of the two sections per pass, 2 + 2 per lane
@@ -106,46 +102,60 @@ __global__ __launch_bounds__(256) void seg_reduce_kernel(int R, int S, int dO, c
         }
       }
     };
-    // all row loads of the chunk are issued before any is consumed.  Which arrays a slot reads is uniform over the
-    // wavefront (a root slot: its dq and dz rows; a neighbour slot: its root's q and dO rows with the slot's score
-    // gradient and softmax weight per head: dK = ds q, dV = p dO)
-    float xa[SEG_CHUNK][2], xb[SEG_CHUNK][2], wa[SEG_CHUNK][2], wb[SEG_CHUNK][2];
 #pragma unroll
-    for (int i = 0; i < SEG_CHUNK; ++i) {
-      const bool on = rows[i] >= 0;
-      const bool root = slots[i] < R;
-      const size_t ro = (size_t)(root ? max(slots[i], 0) : rr[i]);
-      const float* pa = (root ? sg.dq : sg.Qroot) + ro * sg.ldh;
-      const float* pb = (root ? sg.dz : sg.dOmat) + ro * sg.ldh;
-      const float* qa = sg.dscore + ro * HK + jj[i];
-      const float* qb = sg.prob + ro * HK + jj[i];
+    for (int ci = 0; ci < SPAN; ++ci) {
+      if (p0 + ci * SEG_CHUNK >= total) break;   // uniform over the wavefront
+      __builtin_amdgcn_sched_barrier(0);         // one chunk's loads in flight at a time (registers)
+      int slots[SEG_CHUNK], rows[SEG_CHUNK], rr[SEG_CHUNK], jj[SEG_CHUNK];
 #pragma unroll
-      for (int u = 0; u < 2; ++u) {
-        const bool ld = on && live[u];
-        xa[i][u] = ld ? pa[ck[u]] : 0.f;
-        xb[i][u] = ld ? pb[ck[u]] : 0.f;
-        wa[i][u] = (ld && !root) ? qa[hoff[u]] : 1.f;
-        wb[i][u] = (ld && !root) ? qb[hoff[u]] : 1.f;
+      for (int i = 0; i < SEG_CHUNK; ++i) {
+        // (readlane: the values are the same for every lane, so they live in scalar registers)
+        slots[i] = __builtin_amdgcn_readlane(my_slot, ci * SEG_CHUNK + i);
+        rows[i] = __builtin_amdgcn_readlane(my_row, ci * SEG_CHUNK + i);
+        rr[i] = __builtin_amdgcn_readlane(my_r, ci * SEG_CHUNK + i);
+        jj[i] = __builtin_amdgcn_readlane(my_j, ci * SEG_CHUNK + i);
       }
-    }
+      // all row loads of the chunk are issued before any is consumed.  Which arrays a slot reads is uniform over the
+      // wavefront (a root slot: its dq and dz rows; a neighbour slot: its root's q and dO rows with the slot's score
+      // gradient and softmax weight per head: dK = ds q, dV = p dO)
+      float xa[SEG_CHUNK][2], xb[SEG_CHUNK][2], wa[SEG_CHUNK][2], wb[SEG_CHUNK][2];
 #pragma unroll
-    for (int i = 0; i < SEG_CHUNK; ++i) {
-      if (rows[i] != cur) {
-        flush();
+      for (int i = 0; i < SEG_CHUNK; ++i) {
+        const bool on = rows[i] >= 0;
+        const bool root = slots[i] < R;
+        const size_t ro = (size_t)(root ? max(slots[i], 0) : rr[i]);
+        const float* pa = (root ? sg.dq : sg.Qroot) + ro * sg.ldh;
+        const float* pb = (root ? sg.dz : sg.dOmat) + ro * sg.ldh;
+        const float* qa = sg.dscore + ro * HK + jj[i];
+        const float* qb = sg.prob + ro * HK + jj[i];
 #pragma unroll
-        for (int u = 0; u < 2; ++u) aK[u] = aV[u] = aQ[u] = aM[u] = 0.f;
-        any_kv = any_qm = false;
-        cur = rows[i];
+        for (int u = 0; u < 2; ++u) {
+          const bool ld = on && live[u];
+          xa[i][u] = ld ? pa[ck[u]] : 0.f;
+          xb[i][u] = ld ? pb[ck[u]] : 0.f;
+          wa[i][u] = (ld && !root) ? qa[hoff[u]] : 1.f;
+          wb[i][u] = (ld && !root) ? qb[hoff[u]] : 1.f;
+        }
       }
-      if (rows[i] >= 0) {
-        if (slots[i] < R) {
-          any_qm = true;
 #pragma unroll
-          for (int u = 0; u < 2; ++u) { aQ[u] += xa[i][u]; aM[u] += xb[i][u]; }
-        } else {
-          any_kv = true;
+      for (int i = 0; i < SEG_CHUNK; ++i) {
+        if (rows[i] != cur) {
+          flush();
 #pragma unroll
-          for (int u = 0; u < 2; ++u) { aK[u] += xa[i][u] * wa[i][u]; aV[u] += xb[i][u] * wb[i][u]; }
+          for (int u = 0; u < 2; ++u) aK[u] = aV[u] = aQ[u] = aM[u] = 0.f;
+          any_kv = any_qm = false;
+          cur = rows[i];
+        }
+        if (rows[i] >= 0) {
+          if (slots[i] < R) {
+            any_qm = true;
+#pragma unroll
+            for (int u = 0; u < 2; ++u) { aQ[u] += xa[i][u]; aM[u] += xb[i][u]; }
+          } else {
+            any_kv = true;
+#pragma unroll
+            for (int u = 0; u < 2; ++u) { aK[u] += xa[i][u] * wa[i][u]; aV[u] += xb[i][u] * wb[i][u]; }
+          }
         }
       }
     }
@@ -165,9 +175,16 @@ static SlotGrads slot_grads(tgnn_ctx* ctx, int R) {
 void seg_reduce(tgnn_ctx* ctx, int R, int S, const QPhi& qphi, hipStream_t s) {
   const Dims& d = ctx->d;
   Ws& w = ctx->w;
-  const int chunks = (S + SEG_CHUNK - 1) / SEG_CHUNK;
-  hipLaunchKernelGGL(seg_reduce_kernel, dim3((chunks + 3) / 4 + qphi_blocks(qphi)), dim3(256), 0, s, R, S, d.dO,
-                     w.sort_total, w.sorted, w.sorted_row, slot_grads(ctx, R), d.ldkv, w.dP, d.ldp, qphi);
+  const int span = 1;   // chunks per wavefront (see the kernel)
+  const int waves = (S + SEG_CHUNK * span - 1) / (SEG_CHUNK * span);
+  const dim3 grid((waves + 3) / 4 + qphi_blocks(qphi));
+#define TGNN_SEG_CASE(SP)                                                                                             \
+  hipLaunchKernelGGL(seg_reduce_kernel<SP>, grid, dim3(256), 0, s, R, S, d.dO, w.sort_total, w.sorted, w.sorted_row,  \
+                     slot_grads(ctx, R), d.ldkv, w.dP, d.ldp, qphi)
+  if (span == 4) TGNN_SEG_CASE(4);
+  else if (span == 2) TGNN_SEG_CASE(2);
+  else TGNN_SEG_CASE(1);
+#undef TGNN_SEG_CASE
 }
 
 // slot = row: dP[r] = {0 || dq[r] | dz[r]} for roots, dP[R + j] = {dKV[j] || 0} for neighbour slots

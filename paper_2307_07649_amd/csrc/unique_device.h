@@ -6,35 +6,6 @@
 
 namespace tgnn {
 
-// Adds 1 to counter[key] for every lane with key >= 0 and returns the value before this lane's increment.
-// Lanes of a wavefront that share a key are merged into one atomic (power-law graphs put thousands of
-// slots on one node, and atomics on one address serialise).  Every lane of the wavefront must call it.
-// The set of lanes that share lane j's key is the ballot of (key == key of lane j); 64 such ballots, each
-// written into lane j's registers, give every lane its set without a data-dependent loop.  The atomics of all
-// group leaders are then issued together, so the wave pays one round trip.
-__device__ __forceinline__ int wave_counted_add(int32_t* counter, int key, bool want_result) {
-  const int lane = threadIdx.x & 63;
-  unsigned lo = 0u, hi = 0u;
-#pragma unroll
-  for (int j = 0; j < 64; ++j) {
-    const int kj = __builtin_amdgcn_readlane(key, j);
-    const unsigned long long m = __ballot(key == kj);
-    lo = lane == j ? (unsigned)m : lo;
-    hi = lane == j ? (unsigned)(m >> 32) : hi;
-  }
-  const int count = __popc(lo) + __popc(hi);
-  const int rank = __builtin_amdgcn_mbcnt_hi(hi, __builtin_amdgcn_mbcnt_lo(lo, 0u));   // set members below this lane
-  const int leader = lo != 0u ? __ffs((int)lo) - 1 : 32 + __ffs((int)hi) - 1;
-  int base = 0;
-  if (key >= 0 && leader == lane) {
-    if (want_result) base = atomicAdd(counter + key, count);
-    else atomicAdd(counter + key, count);
-  }
-  if (!want_result) return 0;
-  base = __shfl(base, leader);
-  return base + rank;
-}
-
 // exclusive scan of ucnt[0 .. U) into rowptr[0 .. U] and cursor[0 .. U) by one block (any multiple of 64
 // threads up to 1024).  Each wavefront owns a contiguous range (a multiple of 256 elements) and walks it 256
 // elements at a time: a lane reads four consecutive counts, the wavefront scans the lane sums with shuffles.
@@ -96,26 +67,77 @@ __device__ __forceinline__ void uniq_scan_block(const SortArgs& a) {
   }
 }
 
+// The map and the fill pass count slots per node row.  On power-law graphs one node holds a tenth of a step's slots,
+// and atomics on one address complete one at a time in the L2 (tens of nanoseconds each), so the counts are first
+// taken per block in an LDS table (open addressing; LDS atomics on one word cost a few cycles) and only one global
+// atomic per block and distinct row follows.  A block of 256 threads takes UNIQ_PER_BLOCK consecutive slots.
+constexpr int UNIQ_PER_BLOCK = 1024;
+constexpr int UNIQ_TABLE = 2048;   // >= 2 x the distinct rows a block can meet
+__host__ __device__ inline int uniq_blocks(int S) { return (S + UNIQ_PER_BLOCK - 1) / UNIQ_PER_BLOCK; }
+
+struct UniqTable {
+  int key[UNIQ_TABLE];
+  int val[UNIQ_TABLE];
+};
+__device__ __forceinline__ void uniq_table_clear(UniqTable& t) {
+  for (int i = threadIdx.x; i < UNIQ_TABLE; i += blockDim.x) { t.key[i] = -1; t.val[i] = 0; }
+}
+// the entry of `row` (inserted if absent)
+__device__ __forceinline__ int uniq_table_slot(UniqTable& t, int row) {
+  int h = (int)(((unsigned)row * 2654435761u) >> 21) & (UNIQ_TABLE - 1);
+  for (;;) {
+    const int k = atomicCAS(&t.key[h], -1, row);
+    if (k == -1 || k == row) return h;
+    h = (h + 1) & (UNIQ_TABLE - 1);
+  }
+}
+
 // slot -> row, and the number of slots per row; `block` counts the blocks that do this work
 __device__ __forceinline__ void uniq_map_block(const SortArgs& a, int block) {
-  const int s = block * blockDim.x + threadIdx.x;
-  int row = -1;
-  if (s < a.S) {
+  __shared__ UniqTable tab;
+  uniq_table_clear(tab);
+  __syncthreads();
+  for (int s = block * UNIQ_PER_BLOCK + threadIdx.x; s < min(a.S, (block + 1) * UNIQ_PER_BLOCK); s += blockDim.x) {
     const int gid = a.slot_gid[s];
-    if (gid >= 0) row = a.uidx[gid];
+    const int row = gid >= 0 ? a.uidx[gid] : -1;
     a.slot_row[s] = row;
+    if (row >= 0) atomicAdd(&tab.val[uniq_table_slot(tab, row)], 1);
   }
-  wave_counted_add(a.ucnt, row, false);
+  __syncthreads();
+  for (int i = threadIdx.x; i < UNIQ_TABLE; i += blockDim.x)
+    if (tab.key[i] >= 0) atomicAdd(a.ucnt + tab.key[i], tab.val[i]);
 }
 
 // slot s goes to the next free position of its row's range; `block` counts the blocks that do this work
 __device__ __forceinline__ void uniq_fill_block(const SortArgs& a, int block) {
-  const int s = block * blockDim.x + threadIdx.x;
-  const int row = s < a.S ? a.slot_row[s] : -1;
-  const int pos = wave_counted_add(a.cursor, row, true);
-  if (row >= 0) {
-    a.sorted[pos] = s;
-    a.sorted_row[pos] = row;
+  __shared__ UniqTable tab;
+  uniq_table_clear(tab);
+  __syncthreads();
+  const int s_end = min(a.S, (block + 1) * UNIQ_PER_BLOCK);
+  // the block's slots per row, then one range per row claimed from the row's cursor, then positions inside it
+  int my_slot[UNIQ_PER_BLOCK / 256];
+#pragma unroll
+  for (int u = 0; u < UNIQ_PER_BLOCK / 256; ++u) {
+    const int s = block * UNIQ_PER_BLOCK + u * 256 + (int)threadIdx.x;
+    const int row = s < s_end ? a.slot_row[s] : -1;
+    my_slot[u] = -1;
+    if (row >= 0) {
+      my_slot[u] = uniq_table_slot(tab, row);
+      atomicAdd(&tab.val[my_slot[u]], 1);
+    }
+  }
+  __syncthreads();
+  for (int i = threadIdx.x; i < UNIQ_TABLE; i += blockDim.x)
+    if (tab.key[i] >= 0) tab.val[i] = atomicAdd(a.cursor + tab.key[i], tab.val[i]);
+  __syncthreads();
+#pragma unroll
+  for (int u = 0; u < UNIQ_PER_BLOCK / 256; ++u) {
+    if (my_slot[u] >= 0) {
+      const int s = block * UNIQ_PER_BLOCK + u * 256 + (int)threadIdx.x;
+      const int pos = atomicAdd(&tab.val[my_slot[u]], 1);
+      a.sorted[pos] = s;
+      a.sorted_row[pos] = tab.key[my_slot[u]];
+    }
   }
 }
 
