@@ -385,6 +385,44 @@ def run_config(tgnn, torch, P, args, detail):
     return res
 
 
+def run_epoch_parallel(tgnn, torch, P, args, J):
+    """tgnn_train_step_epoch_parallel on configuration P: J negative sets per positive mini-batch in one step (the
+    one-GPU share of J epoch-parallel trainers).  Events/s counts positive events, as everywhere."""
+    import synth
+    d = P["d"]
+    ctx = tgnn.Context(d.n_nodes, d.d_mem, d.d_time, d.d_edge, d.d_static, d.n_heads, d.k, d.batch, n_replicas=1,
+                       flags=tgnn.FLAG_OVERWRITE_GRADS, max_neg_sets=J)
+    graph = tgnn.Graph(P["src"], P["dst"], P["ts"], d.n_nodes, P["efeat"])
+    state = tgnn.State(d.n_nodes, d.d_mem, 1, P["static"])
+    params = tgnn.Params.from_numpy(P["params"]); grads = tgnn.Params.zeros_like(params)
+    loss = torch.zeros(4, device="cuda")
+    spans = [sp for sp in synth.batches_of(P["E"], d.batch) if sp[1] - sp[0] == d.batch]
+    negs = np.stack([synth.gen_negatives(P["name"], P["E"], group=g) for g in range(J)])       # [J, E]
+    dsrc, ddst = (torch.from_numpy(np.ascontiguousarray(P[n], np.int32)).cuda() for n in ("src", "dst"))
+    deid = torch.arange(P["E"], dtype=torch.int32, device="cuda")
+    dts = torch.from_numpy(np.ascontiguousarray(P["ts"], np.float64)).cuda()
+    n_steps = min(args.steps, len(spans) - args.warmup)
+    batches = [tgnn.Batch(dsrc[lo:hi], ddst[lo:hi], torch.from_numpy(np.ascontiguousarray(negs[:, lo:hi]).reshape(-1)).cuda(),
+                          deid[lo:hi], dts[lo:hi]) for (lo, hi) in spans[:args.warmup + n_steps]]
+    torch.cuda.synchronize()
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        for b in batches[:args.warmup]:
+            ctx.tgnn_train_step_epoch_parallel(graph, state, params, grads, [b], J, lr=args.lr, out_loss=loss)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for b in batches[args.warmup:]:
+            ctx.tgnn_train_step_epoch_parallel(graph, state, params, grads, [b], J, lr=args.lr, out_loss=loss)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+    res = {"workload": f"{P['name']} with {J} negative sets per mini-batch (roots per step: {(2 + J) * d.batch})",
+           "n_neg_sets": J, "steps": n_steps, "ms_per_step": dt / n_steps * 1e3,
+           "positive_events_per_s": n_steps * d.batch / dt, "trained_pairs_per_s": n_steps * d.batch * (1 + J) / dt,
+           "final_loss": float(loss[0].item())}
+    ctx.close()
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -429,10 +467,13 @@ def main():
     head = "C4" if args.config == "all" else args.config
     others = [c for c in ("C0", "C1", "C2", "C3") if args.config == "all"]
     configs = {}
+    epoch_parallel = None
     for name in others:
         P = build_problem(name, None)
         configs[name] = run_config(tgnn, torch, P, args, detail=False)
         print(f"bench.py: {name} {configs[name]['events_per_s']:.0f} events/s", file=sys.stderr, flush=True)
+        if name == "C1":
+            epoch_parallel = run_epoch_parallel(tgnn, torch, P, args, 4)
         del P
     P = build_problem(head, args.events)
     print(f"bench.py: {head} inputs ready", file=sys.stderr, flush=True)
@@ -469,6 +510,7 @@ def main():
         "weight_gradients": wg,
         "step_model": res["step_model"],
         "configs": configs,
+        "epoch_parallel": epoch_parallel,
         "stages_us": res.get("stages_us"), "stages_us_note": res.get("stages_us_note"),
     }
     if not args.no_cpu_baseline:
