@@ -40,7 +40,7 @@ extern "C" {
 #define TGNN_E_HIP (-8)
 
 #define TGNN_FLAG_OVERWRITE_GRADS 1 /* tgnn_train_step clears `grads` first instead of adding to them */
-#define TGNN_FLAG_NO_GRAPH 4        /* tgnn_train_step enqueues its launches (13 on the main path) one by one; by default it records
+#define TGNN_FLAG_NO_GRAPH 4        /* tgnn_train_step enqueues its launches (16 on the main path) one by one; by default it records
                                        them once per call signature (same pointers, batch sizes, lr, stream) into a
                                        HIP graph and replays that with one launch, updating only the batch
                                        descriptors.  Not used on the NULL (legacy default) stream, while the caller's stream is itself being captured
