@@ -8,10 +8,15 @@ namespace tgnn {
 // ulp is a quarter of a radian; so the argument is formed and reduced to [-pi/4, pi/4] in double, and only
 // the polynomial is evaluated in float (absolute error ~1e-7).
 __device__ __forceinline__ void sincos_reduced(double arg, float& s, float& c) {
-  const double j = rint(arg * 0.63661977236758134308);          // 2/pi
+  // j = arg * 2/pi rounded to the nearest integer, by adding and taking off 1.5 * 2^52 (round-to-nearest mode): the
+  // sum's low mantissa bits then are j's low bits in two's complement, which gives the quadrant j mod 4 without a
+  // double -> integer conversion (the 64-bit one is a dozen double-precision instructions).  |arg| < 2^51.
+  const double magic = 6755399441055744.0;
+  const double t = fma(arg, 0.63661977236758134308, magic);     // 2/pi
+  const int q = __double2loint(t) & 3;
+  const double j = t - magic;
   double r = fma(-j, 1.57079632679489655800e+00, arg);          // pi/2 high part
   r = fma(-j, 6.12323399573676603587e-17, r);                   // pi/2 low part
-  const int q = (int)((long long)j & 3);
   const float x = (float)r, x2 = x * x;
   const float sp = x + x * x2 * (-1.6666654611e-1f + x2 * (8.3321608736e-3f + x2 * (-1.9515295891e-4f)));
   const float cp = 1.0f - 0.5f * x2 +

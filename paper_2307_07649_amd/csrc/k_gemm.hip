@@ -91,17 +91,26 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, (TN <= 5
 
   // Row indices are clamped instead of guarded, so the hot loop has no branches: rows >= M and weight
   // rows >= N read valid memory whose products are dropped in the epilogue.
+  // the k range of this column tile: all of it, or with a block-diagonal B the stages its blocks reach into
+  int k_lo = 0, k_hi = Kp, k_end = q.k_live > 0 ? q.k_live : Kp;
+  if (q.bd_n > 0) {
+    const int h_lo = min(n0, N - 1) / q.bd_n, h_hi = (min(n0 + BN, N) - 1) / q.bd_n;
+    k_lo = (h_lo * q.bd_k) & ~(NT_BK - 1);
+    k_end = min(k_end, (h_hi + 1) * q.bd_k);
+    k_hi = min(Kp, (k_end + NT_BK - 1) & ~(NT_BK - 1));
+    if (k_hi <= k_lo) k_lo = max(k_hi - NT_BK, 0);   // (live columns end before the tile's blocks begin: one stage of zeros)
+  }
   const float* pa[A_PER];
   const float* pb[B_PER];
 #pragma unroll
   for (int u = 0; u < A_PER; ++u) {
     const int f = tid + u * 256;
-    pa[u] = A + (size_t)min(m0 + (f >> 3), M - 1) * lda + (f & 7) * 4;
+    pa[u] = A + (size_t)min(m0 + (f >> 3), M - 1) * lda + (f & 7) * 4 + k_lo;
   }
 #pragma unroll
   for (int u = 0; u < B_PER; ++u) {
     const int f = min(tid + u * 256, B_F4 - 1);
-    pb[u] = B + (size_t)min(n0 + (f >> 3), N - 1) * ldb + (f & 7) * 4;
+    pb[u] = B + (size_t)min(n0 + (f >> 3), N - 1) * ldb + (f & 7) * 4 + k_lo;
   }
   struct Regs {
     floatx4 a[A_PER], b[B_PER];
@@ -126,7 +135,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, (TN <= 5
     }
   };
   // the last stage stops after its first slab when the live columns end there
-  const int k_tail = q.k_live > 0 ? q.k_live - (Kp - NT_BK) : NT_BK;
+  const int k_tail = (q.k_live > 0 || q.bd_n > 0) ? k_end - (k_hi - NT_BK) : NT_BK;
   const bool short_tail = k_tail > 0 && k_tail <= 16;
   auto compute = [&](int buf, bool last = false) __attribute__((always_inline)) {
 #pragma unroll
@@ -150,7 +159,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, (TN <= 5
 
   // Kp is a multiple of the stage depth.  Stage s lives in register set s & 1 until it is stored to LDS
   // buffer s & 1; loads run two stages ahead of the MFMAs.
-  const int nk = Kp / NT_BK;
+  const int nk = (k_hi - k_lo) / NT_BK;
   // rows this lane writes: m0 + wave * 16 + lg * 4 + v.  Their gather-add source rows (or -1), and then the
   // values to add, are fetched now: two dependent loads that would otherwise sit between the last MFMA and
   // the stores.

@@ -242,8 +242,9 @@ static void attn_forward(tgnn_ctx* ctx, const tgnn_params* p, int R, int n_rows,
   gemm_nt_group(&node_part, 1, s);
   if (tm) { tm->end(9); tm->begin(8); }
   if (slot_part) {   // U = q (W_k^c)_h per head: A is the q section of P (its pad columns meet zero columns of the weights)
-    const NtProblem u = nt_live(nt_problem(w.P + d.ldkv, d.ldp, w.WkcT, d.ldh, nullptr, w.Umat, d.ldz, n_rows, d.H * d.dcp,
-                                           d.ldh, d.ldz, false, n_rows_dev), d.dO);
+    const NtProblem u = nt_blocks(nt_live(nt_problem(w.P + d.ldkv, d.ldp, w.WkcT, d.ldh, nullptr, w.Umat, d.ldz, n_rows,
+                                                     d.H * d.dcp, d.ldh, d.ldz, false, n_rows_dev), d.dO),
+                                  d.dcp, d.dO / d.H);
     gemm_nt_group(&u, 1, s);
   }
   if (tm) { tm->end(8); tm->begin(10); }
@@ -254,8 +255,9 @@ static void attn_forward(tgnn_ctx* ctx, const tgnn_params* p, int R, int n_rows,
   {   // attention output = node part + Zp (W_v^c)^T
     RowAdd add;
     add.src = w.Onode; add.ld = d.ldh; add.index = nullptr; add.row0 = 0;
-    const NtProblem o = nt_live(nt_problem(w.Zp, d.ldz, w.Wvc, d.ldz, nullptr, w.Omat, d.ldh, R, d.dO, d.ldz, d.ldh, false,
-                                           nullptr, add), d.H * d.dcp);
+    const NtProblem o = nt_blocks(nt_live(nt_problem(w.Zp, d.ldz, w.Wvc, d.ldz, nullptr, w.Omat, d.ldh, R, d.dO, d.ldz, d.ldh,
+                                                     false, nullptr, add), d.H * d.dcp),
+                                  d.dO / d.H, d.dcp);
     gemm_nt_group(&o, 1, s);
   }
   if (tm) tm->end(7);
@@ -287,8 +289,9 @@ static void attn_backward(tgnn_ctx* ctx, tgnn_params* g, const tgnn_params* p, i
   if (!have_dOmat) gemm_nt(w.dz, d.ldh, w.WoT_o, d.ldh, nullptr, w.dOmat, d.ldh, R, d.dO, d.ldh, d.ldh, false, s);
   if (tm) tm->begin(19);
   {   // G = dO (W_v^c)_h per head
-    const NtProblem gm = nt_live(nt_problem(w.dOmat, d.ldh, w.WvcT, d.ldh, nullptr, w.Gmat, d.ldz, R, d.H * d.dcp, d.ldh,
-                                            d.ldz, false), d.dO);
+    const NtProblem gm = nt_blocks(nt_live(nt_problem(w.dOmat, d.ldh, w.WvcT, d.ldh, nullptr, w.Gmat, d.ldz, R, d.H * d.dcp,
+                                                      d.ldh, d.ldz, false), d.dO),
+                                   d.dcp, d.dO / d.H);
     gemm_nt_group(&gm, 1, s);
   }
   if (tm) { tm->end(19); tm->begin(14); }
@@ -297,8 +300,9 @@ static void attn_backward(tgnn_ctx* ctx, tgnn_params* g, const tgnn_params* p, i
   {   // dq = node part + Zs (W_k^c)^T, with its column sums over the roots (for the query's Phi(0))
     RowAdd add;
     add.src = w.dqn; add.ld = d.ldh; add.index = nullptr; add.row0 = 0;
-    NtProblem dq = nt_live(nt_problem(w.Zs, d.ldz, w.Wkc, d.ldz, nullptr, w.dq, d.ldh, R, d.dO, d.ldz, d.ldh, false, nullptr,
-                                      add), d.H * d.dcp);
+    NtProblem dq = nt_blocks(nt_live(nt_problem(w.Zs, d.ldz, w.Wkc, d.ldz, nullptr, w.dq, d.ldh, R, d.dO, d.ldz, d.ldh, false,
+                                                nullptr, add), d.H * d.dcp),
+                             d.dO / d.H, d.dcp);
     dq.colsum = w.q_part; dq.colsum_rows = QPHI_BLOCKS;
     gemm_nt_group(&dq, 1, s);
   }

@@ -278,6 +278,9 @@ struct NtProblem {
   float* C;
   int lda, ldb, ldc, M, N, Kp, n_store, relu;
   int k_live;   // columns >= k_live of A and B are padding (0: not stated); lets the last stage stop after 16 columns
+  // bd_n > 0: B is block-diagonal, rows [h bd_n, (h + 1) bd_n) of it (output columns) are zero outside columns
+  // [h bd_k, (h + 1) bd_k): a column tile then runs only the k stages its blocks reach into
+  int bd_n, bd_k;
   const int* m_dev;
   int col_tiles, wg_begin;
   RowAdd add;
@@ -301,11 +304,13 @@ inline NtProblem nt_problem(const float* A, int lda, const float* B, int ldb, co
   NtProblem p;
   p.A = A; p.B = B; p.bias = bias; p.C = C; p.lda = lda; p.ldb = ldb; p.ldc = ldc; p.M = M; p.N = N; p.Kp = Kp;
   p.n_store = n_store; p.relu = relu ? 1 : 0; p.k_live = 0; p.m_dev = m_dev; p.col_tiles = 0; p.wg_begin = 0;
-  p.add = add; p.tg = tg; p.gb = gb; p.colsum = nullptr; p.colsum_rows = 1;
+  p.add = add; p.tg = tg; p.gb = gb; p.colsum = nullptr; p.colsum_rows = 1; p.bd_n = 0; p.bd_k = 0;
   return p;
 }
 // the same problem with its live column count stated
 inline NtProblem nt_live(NtProblem p, int k_live) { p.k_live = k_live; return p; }
+// the same problem with B stated to be block-diagonal (see NtProblem::bd_n)
+inline NtProblem nt_blocks(NtProblem p, int bd_n, int bd_k) { p.bd_n = bd_n; p.bd_k = bd_k; return p; }
 void gemm_nt_group(const NtProblem* probs, int n, hipStream_t s, const WbArgs* tail = nullptr);
 
 // Where the weight-gradient GEMM adds its result: element (n, k) goes to p[n >= n_split][k >= k_split]

@@ -61,6 +61,12 @@ CONFIGS = {
                n_src=10_000, n_dst=984, zipf_src=1.1, zipf_dst=1.3, ts="uniform", t_max=2.7e6,
                d_mem=100, d_time=100, d_edge=172, d_static=100, n_heads=2, k=10, batch=600,
                n_replicas=8, neg_range=(10_000, 10_984)),
+    # no edge features (Table 2: MOOC, 7,144 nodes = 7,047 users + 97 course items, 411,749 events, max(t) 2.6e7,
+    # pre-trained static node features of width 100)
+    "C5": dict(seed=5, n_nodes=7144, n_events=411_749, kind="bipartite_zipf",
+               n_src=7047, n_dst=97, zipf_src=0.9, zipf_dst=1.0, ts="uniform", t_max=2.6e7,
+               d_mem=100, d_time=100, d_edge=0, d_static=100, n_heads=2, k=10, batch=600,
+               n_replicas=1, neg_range=(7047, 7144)),
     "C4": dict(seed=4, n_nodes=16_682, n_events=20_000_000, kind="zipf", zipf=1.05,
                ts="bursty", t_max=1.4e5,
                d_mem=100, d_time=100, d_edge=186, d_static=0, n_heads=2, k=10, batch=4000,

@@ -59,6 +59,14 @@ def test_c2_full_size_late_in_the_stream():
     run(P, 4, lr=1e-3, check_at=(0, 2, 3), first=900)
 
 
+def test_c5_no_edge_features_full_size():
+    """C5 (a graph without edge features, d_e = 0, with static memory; Table 2's MOOC shape) at its full 411,749
+    events: 20 consecutive batches from the start with SGD, then three late in the stream."""
+    P = make_problem("C5")
+    run(P, 20, lr=1e-3, check_at=(0, 1, 10, 19))
+    run(P, 3, lr=1e-3, check_at=(0, 2), first=600)
+
+
 def test_c3_eight_replicas_time_shifted():
     P = make_problem("C3", n_events=48_000)
     d = P["d"]
