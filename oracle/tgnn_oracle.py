@@ -17,6 +17,8 @@ What each function follows (paper = DistTGL, arXiv 2307.07649):
   * static node memory combined with the dynamic memory            -- Sec. 3.1
   * self-supervision by temporal edges with sampled negative destinations -- Sec. 2.1, 3.2.2
   * memory and mails reset at the start of an epoch                -- Alg. 1
+  * dynamic edge classification with C classes and multi-label targets (the GDELT task)
+    and the mean reciprocal rank of the true destination among 49 sampled ones  -- Sec. 4 "Datasets"
 
 Where the paper is silent the readings are (they are listed with reasons in the design notes):
   undirected neighbour lists ordered by (time, event id); "most recent" = time strictly
@@ -33,7 +35,8 @@ for the sampler (and the indexed form against the scan); closed forms of the tim
 function and on the values the step feeds to the GRU, the keys and the query (hand-built states
 with known time differences and non-zero phases); a library GRU cell and its limits; attention
 special cases; ln 2 loss; central finite differences for every parameter tensor; brute-force
-last-writer-wins write-back.
+last-writer-wins write-back; the classification head: ln 2 at zero weights, a hand-computed event, finite
+differences; the reciprocal rank: hand-written score lists with ties.
 The step as a whole is "parity unpinned" against the paper, which prints no worked example.
 """
 from __future__ import annotations
@@ -312,6 +315,40 @@ def decoder_bwd(p, cache, logits, loss_scale=1.0, gate_h=None):
     return g, da.reshape(1 + J, B, da.shape[1]).sum(0), db[:B], db[B:]
 
 
+def edge_class_loss(p, z_src, z_dst, labels):
+    """Dynamic edge classification (Sec. 4 "Datasets": C classes, several of them true for an event): the
+    decoder's hidden layer as in decoder_loss, C outputs logit_c = W2[c] . ReLU(W_s z_src + W_d z_dst + b1) + b2[c]
+    (dec_w2 is [C, d_o], dec_b2 [C]); labels [B, C] in {0, 1}; loss = mean over the B events and the C classes of the
+    binary cross-entropy softplus(logit) - y logit."""
+    hpre = z_src @ p["dec_ws"].T + z_dst @ p["dec_wd"].T + p["dec_b1"]
+    h1 = np.maximum(hpre, 0.0)
+    logits = h1 @ p["dec_w2"].T + p["dec_b2"]
+    y = np.asarray(labels, F)
+    loss = float((_softplus(logits) - y * logits).mean()) if logits.size else 0.0
+    return loss, logits, dict(a=z_src, b=z_dst, hpre=hpre, h1=h1, y=y)
+
+
+def edge_class_bwd(p, cache, logits, loss_scale=1.0, gate_h=None):
+    """Gradients of edge_class_loss; returns (weight gradients, dz_src, dz_dst)."""
+    B, C = logits.shape
+    g = {}
+    dl = (_sigmoid(logits) - cache["y"]) / (B * C) * loss_scale
+    g["dec_w2"] = dl.T @ cache["h1"]; g["dec_b2"] = dl.sum(0)
+    dh = (dl @ p["dec_w2"]) * ((cache["hpre"] > 0) if gate_h is None else gate_h)
+    g["dec_ws"] = dh.T @ cache["a"]; g["dec_wd"] = dh.T @ cache["b"]; g["dec_b1"] = dh.sum(0)
+    return g, dh @ p["dec_ws"], dh @ p["dec_wd"]
+
+
+def reciprocal_rank(score_true, score_neg):
+    """Rank of the true destination among itself and the sampled negative destinations of its event (Sec. 4: 49 of
+    them, mean reciprocal rank reported).  score_true [B], score_neg [J, B].  rank = 1 + the number of negatives
+    that score strictly higher + half the number that score exactly the same (the expected rank when ties are broken
+    at random; the paper does not say how it breaks them).  Returns (rank [B], mean of 1 / rank)."""
+    st = np.asarray(score_true, F); sn = np.asarray(score_neg, F).reshape(-1, len(st))
+    rank = 1.0 + (sn > st[None, :]).sum(0) + 0.5 * (sn == st[None, :]).sum(0)
+    return rank, float((1.0 / rank).mean()) if len(st) else 0.0
+
+
 # --------------------------------------------------------------------------------------
 # last-event-wins write-back (COMB = most recent mail, Eq. 8; roots only, Sec. 3.2.1)
 # --------------------------------------------------------------------------------------
@@ -344,11 +381,15 @@ def forward_backward(state, graph, efeat, static, p, batch, k, n_heads, dt_sourc
     """graph = event_list(src, dst, ts): neighbours by the scan of sample_recent (a build_adjacency tuple
     instead selects sample_recent_indexed).  batch = dict(src, dst, neg, eid, t).  Returns dict(loss,
     logits, grads, nbr, neid, nts, cnt, s_new, tau, z, ...).  Does not modify `state`.
+    A batch with "labels" ([B, C]) is an edge-classification batch: no negative destinations, roots [src | dst],
+    the head of edge_class_loss.
     relu_gates = (gate_z, gate_h), optional: see attention_bwd / decoder_bwd."""
     src, dst = (np.asarray(batch[n], np.int64) for n in ("src", "dst"))
-    neg = np.asarray(batch["neg"], np.int64).reshape(-1)        # J sets of B negative destinations, one after the other
+    labels = batch.get("labels")
+    # J sets of B negative destinations, one after the other (none in an edge-classification batch)
+    neg = np.asarray(batch["neg"], np.int64).reshape(-1) if labels is None else np.zeros(0, np.int64)
     t = np.asarray(batch["t"], F)
-    B = len(src); J = len(neg) // B if B else 1; R = (2 + J) * B
+    B = len(src); J = (len(neg) // B if B else 1) if labels is None else 0; R = (2 + J) * B
     d_m = state["mem"].shape[1]; d_t = p["time_w"].shape[0]
     root_node = np.concatenate([src, dst, neg]); root_t = np.concatenate([t] * (2 + J))
     if isinstance(graph, dict):
@@ -371,14 +412,21 @@ def forward_backward(state, graph, efeat, static, p, batch, k, n_heads, dt_sourc
     ref_t = tau[R:].reshape(R, k) if dt_source == 0 else nts
     dt_nbr = np.where(valid, root_t[:, None] - ref_t, 0.0)
     z, ac = attention_fwd(p, x_root, x_nbr, e_nbr, dt_nbr, cnt, n_heads)
-    loss, logits, dc = decoder_loss(p, z[:B], z[B:2 * B], z[2 * B:])
+    if labels is None:
+        loss, logits, dc = decoder_loss(p, z[:B], z[B:2 * B], z[2 * B:])
+    else:
+        loss, logits, dc = edge_class_loss(p, z[:B], z[B:2 * B], labels)
     out = dict(loss=loss, logits=logits, nbr=nbr, neid=neid, nts=nts, cnt=cnt, s_new=s_new, tau=tau, z=z,
                dt_nbr=dt_nbr, zpre=ac["zpre"], hpre=dc["hpre"], gru_x=gc["x"], q_in=ac["q_in"], c_in=ac["c_in"])
     if not want_grads:
         return out
 
     gate_z, gate_h = relu_gates if relu_gates is not None else (None, None)
-    g, dzs, dzd, dzn = decoder_bwd(p, dc, logits, loss_scale, gate_h)
+    if labels is None:
+        g, dzs, dzd, dzn = decoder_bwd(p, dc, logits, loss_scale, gate_h)
+    else:
+        g, dzs, dzd = edge_class_bwd(p, dc, logits, loss_scale, gate_h)
+        dzn = np.zeros((0, dzs.shape[1]), F)
     ga, dx_root, dx_nbr = attention_bwd(p, ac, np.concatenate([dzs, dzd, dzn], 0), n_heads, gate_z)
     g.update(ga)
     # gradient reaching s' of every slot; it stops at the stored memory and mails (no BPTT)

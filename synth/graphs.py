@@ -22,6 +22,7 @@ class ModelDims:
     k: int
     batch: int
     n_replicas: int = 1
+    n_classes: int = 0     # > 0: edge classification with that many outputs instead of link prediction
 
     @property
     def d_in(self):        # GRU input: mail (2 d_mem) | time encoding | edge feature
@@ -78,7 +79,7 @@ def dims_of(name: str, **override) -> ModelDims:
     c = dict(CONFIGS[name]); c.update(override)
     return ModelDims(n_nodes=c["n_nodes"], d_mem=c["d_mem"], d_time=c["d_time"], d_edge=c["d_edge"],
                      d_static=c["d_static"], n_heads=c["n_heads"], k=c["k"], batch=c["batch"],
-                     n_replicas=c["n_replicas"])
+                     n_replicas=c["n_replicas"], n_classes=c.get("n_classes", 0))
 
 
 def _zipf_ids(rng, n_ids, a, size, lo=0):
@@ -158,6 +159,20 @@ def gen_negatives(name: str, n_events: int, group: int = 0):
     return rng.integers(lo, hi, n_events, dtype=np.int64).astype(np.int32)
 
 
+def gen_labels(n_events: int, n_classes: int, n_true: int, seed: int = 0):
+    """Multi-label targets of an edge-classification task, float32 [E, C] in {0, 1}: every event has `n_true`
+    distinct true classes (the GDELT task of Sec. 4 has 56 classes, 6 of them true), drawn with a skewed class
+    popularity (probability proportional to 1 / (1 + class index))."""
+    rng = np.random.Generator(np.random.PCG64(seed + 5000))
+    w = 1.0 / (1.0 + np.arange(n_classes))
+    # n_true distinct classes per event: the largest of exponential races (Gumbel top-k)
+    keys = np.log(w)[None, :] + rng.gumbel(size=(n_events, n_classes))
+    top = np.argpartition(-keys, n_true - 1, axis=1)[:, :n_true]
+    y = np.zeros((n_events, n_classes), np.float32)
+    np.put_along_axis(y, top, 1.0, axis=1)
+    return y
+
+
 def gen_static(name: str):
     """Frozen static node memory, N(0, 0.1), float32 [n_nodes, d_static]; None when d_static == 0."""
     c = CONFIGS[name]
@@ -175,7 +190,9 @@ PARAM_SHAPES = lambda d: {  # noqa: E731  (name -> (shape, fan_in))
     "wv": ((d.d_out, d.d_kv), d.d_kv), "bv": ((d.d_out,), d.d_kv),
     "wo": ((d.d_out, d.d_out + d.d_x), d.d_out + d.d_x), "bo": ((d.d_out,), d.d_out + d.d_x),
     "dec_ws": ((d.d_out, d.d_out), d.d_out), "dec_wd": ((d.d_out, d.d_out), d.d_out),
-    "dec_b1": ((d.d_out,), d.d_out), "dec_w2": ((d.d_out,), d.d_out), "dec_b2": ((1,), d.d_out),
+    "dec_b1": ((d.d_out,), d.d_out),
+    "dec_w2": (((d.n_classes, d.d_out) if d.n_classes else (d.d_out,)), d.d_out),
+    "dec_b2": ((d.n_classes if d.n_classes else 1,), d.d_out),
 }
 
 PARAM_ORDER = ["time_w", "time_b", "gru_wih", "gru_whh", "gru_bih", "gru_bhh", "wq", "bq", "wk", "bk",
