@@ -63,7 +63,8 @@ extern "C" {
 #define TGNN_MAX_BATCHES 16  /* mini-batches (memory replicas) per tgnn_train_step call */
 #define TGNN_MAX_STEPS_PER_CALL 8 /* consecutive training steps per tgnn_train_steps call */
 #define TGNN_MAX_HEADS 8
-#define TGNN_MAX_NEG_SETS 8  /* negative-destination sets per event in tgnn_train_step_epoch_parallel */
+#define TGNN_MAX_NEG_SETS 64 /* negative-destination sets per event (tgnn_train_step_epoch_parallel, tgnn_eval_step) */
+#define TGNN_MAX_CLASSES 256 /* outputs of the edge-classification head (tgnn_train_step_edge_class) */
 #define TGNN_NOALLOC_MAX_NODES 262144   /* tgnn_memory_writeback_noalloc: nodes its static scratch array covers (2 MiB) */
 #define TGNN_NOALLOC_MAX_EVENTS 1048576 /* ... and events per call */
 
@@ -76,8 +77,11 @@ typedef struct {
   int32_t dt_source;  /* time difference in the attention keys (Eq. 5-6): 0 = query time minus the update
                          time of the neighbour's memory as used (the paper's wording), 1 = minus the edge time */
   int32_t flags;      /* TGNN_FLAG_* bits */
-  int32_t max_neg_sets; /* largest number of negative-destination sets a step carries (tgnn_train_step_epoch_parallel);
-                           0 or 1: one, the plain step.  The workspace grows with it. */
+  int32_t max_neg_sets; /* largest number of negative-destination sets a step carries (tgnn_train_step_epoch_parallel,
+                           tgnn_eval_step); 0 or 1: one, the plain step.  The workspace grows with it. */
+  int32_t n_classes;    /* 0: link prediction (dec_w2 [d_o], dec_b2 [1]).  C > 0: the decoder is an edge-classification
+                           head with C outputs (dec_w2 [C, d_o], dec_b2 [C]); such a context trains with
+                           tgnn_train_step_edge_class only.  C <= TGNN_MAX_CLASSES. */
 } tgnn_config;
 
 /* Temporal CSR: node v's incident events (both directions) are entries indptr[v] .. indptr[v+1]-1 of
@@ -108,7 +112,8 @@ typedef struct {
  *           input columns ordered {mail (2 d_m) || Phi (d_t) || edge feature (d_e)}  (Eq. 1-2)
  *   wq [d_o, d_q], wk, wv [d_o, d_kv], biases [d_o]; key/value input {x_w || e_vw || Phi} (Eq. 4-6)
  *   wo [d_o, d_o + d_x], bo [d_o]                merge layer on {h_v || x_v}
- *   dec_ws, dec_wd [d_o, d_o], dec_b1 [d_o], dec_w2 [d_o], dec_b2 [1]        link decoder */
+ *   dec_ws, dec_wd [d_o, d_o], dec_b1 [d_o], dec_w2 [d_o], dec_b2 [1]        link decoder
+ *           (config.n_classes = C > 0: dec_w2 [C, d_o], dec_b2 [C], the edge-classification head) */
 typedef struct {
   float *time_w, *time_b, *gru_wih, *gru_whh, *gru_bih, *gru_bhh, *wq, *bq, *wk, *bk, *wv, *bv, *wo, *bo,
       *dec_ws, *dec_wd, *dec_b1, *dec_w2, *dec_b2;
@@ -248,6 +253,33 @@ int32_t tgnn_train_step_epoch_parallel(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_
                                        tgnn_params* grads, const tgnn_batch* batches, int32_t n_batches,
                                        int32_t n_neg_sets, float lr, float* out_loss, float* out_logits,
                                        int32_t* out_winner, void* stream);
+
+/* Dynamic edge classification (Sec. 4 "Datasets": the 56-class task with several true classes per event).  The step of
+ * tgnn_train_step with another head and no negative destinations: roots per batch are [src | dst] (batches[b].neg is
+ * not read), logit_{i,c} = dec_w2[c] . ReLU(W_s z_src_i + W_d z_dst_i + b1) + dec_b2[c] for the C = config.n_classes
+ * classes, and the loss is the mean over the events of a batch and the classes of the binary cross-entropy
+ * softplus(logit) - y logit, averaged over the batches.  Memory and mails are written back as in tgnn_train_step.
+ *   labels     HOST array of n_batches DEVICE pointers; labels[b] is [batches[b].n, C] float, 1 = class is true;
+ *   out_logits [sum n, C] or NULL;  out_winner [2 * sum n] or NULL.
+ * TGNN_E_INVALID_ARG on a context with n_classes == 0 (and the link-prediction steps refuse one with n_classes > 0). */
+int32_t tgnn_train_step_edge_class(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, const tgnn_params* p,
+                                   tgnn_params* grads, const tgnn_batch* batches, int32_t n_batches,
+                                   const float* const* labels, float lr, float* out_loss, float* out_logits,
+                                   int32_t* out_winner, void* stream);
+
+/* Evaluation pass of temporal link prediction (Sec. 4: the rank of the true destination among itself and 49 sampled
+ * negative destinations, mean reciprocal rank reported).  The forward half of tgnn_train_step_epoch_parallel with
+ * n_neg_sets negative destinations per event (batches[b].neg is [n_neg_sets, n]), then per event
+ * rank = 1 + #(negatives scoring strictly higher than the true destination) + 0.5 #(negatives scoring the same),
+ * and the write-back of memory and mails (evaluation events advance the memory like training events).  No gradients, no
+ * optimiser step, parameters untouched.
+ *   out_logits [(1 + n_neg_sets) * sum n] or NULL, laid out as in tgnn_train_step_epoch_parallel;
+ *   out_rank   [sum n] float;   out_rr_sum [1] float: the sum over the events of 1 / rank is ADDED to it;
+ *   out_winner [2 * sum n] or NULL.
+ * 1 <= n_neg_sets <= config.max_neg_sets. */
+int32_t tgnn_eval_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, const tgnn_params* p,
+                       const tgnn_batch* batches, int32_t n_batches, int32_t n_neg_sets, float* out_logits,
+                       float* out_rank, float* out_rr_sum, int32_t* out_winner, void* stream);
 
 /* Optimiser of the in-step update that tgnn_train_step (and its variants) apply when lr != 0.
  *   kind 0  plain SGD, p -= lr g (the default);

@@ -117,10 +117,11 @@ __global__ __launch_bounds__(256) void dec_pair_kernel(const BatchSet* __restric
   if (lane == 0) { red[wave][256] = gb; red[wave][257] = lsum; }
   __syncthreads();
   if (wave == 0) {
-    for (int c = lane; c < dO; c += 64) atomicAdd(g_w2 + c, red[0][c] + red[1][c] + red[2][c] + red[3][c]);
+    if (g_w2 != nullptr)    // (NULL in a forward-only pass)
+      for (int c = lane; c < dO; c += 64) atomicAdd(g_w2 + c, red[0][c] + red[1][c] + red[2][c] + red[3][c]);
     if (lane == 0) {
-      atomicAdd(g_b2, red[0][256] + red[1][256] + red[2][256] + red[3][256]);
-      atomicAdd(out_loss, red[0][257] + red[1][257] + red[2][257] + red[3][257]);
+      if (g_b2 != nullptr) atomicAdd(g_b2, red[0][256] + red[1][256] + red[2][256] + red[3][256]);
+      if (out_loss != nullptr) atomicAdd(out_loss, red[0][257] + red[1][257] + red[2][257] + red[3][257]);
     }
   }
 }
@@ -131,6 +132,121 @@ void decoder_pairs(const Dims& d, const BatchSet* bs, int total, const float* Pd
   if (total <= 0) return;
   hipLaunchKernelGGL(dec_pair_kernel, dim3(std::min((total + 3) / 4, DP_BLOCKS)), dim3(256), 0, s, bs, d.dO, Pdec, ldp, b1,
                      w2, b2, logits, out_loss, h1, d.ldh, dPdec, g_w2, g_b2);
+}
+
+// Edge-classification head (Sec. 4 "Datasets": C classes, several true per event).  One wavefront per event: hidden
+// layer h = ReLU(W_s z_src + W_d z_dst + b1) from the two roots' rows of Pdec, then class by class the logit
+// W2[c] . h + b2[c] (a row of W2 per lane round, summed over the wavefront), its cross-entropy term
+// softplus(logit) - y logit, d loss / d logit = (sigmoid(logit) - y) / (n C), and the hidden layer's gradient
+// sum_c dlogit_c W2[c] gated by the ReLU.  Roots of batch b: [src | dst] from root 2 * ev_off on.  The weight
+// gradients of W2 / b2 are left to the weight-gradient GEMM (dlog^T h1).
+__global__ __launch_bounds__(256) void dec_class_kernel(const BatchSet* __restrict__ bsp, int dO, int C,
+                                                        const float* __restrict__ Pdec, int ldp,
+                                                        const float* __restrict__ b1, const float* __restrict__ w2,
+                                                        const float* __restrict__ b2, float* __restrict__ logits,
+                                                        float* __restrict__ out_loss, float* __restrict__ h1, int ldh,
+                                                        float* __restrict__ dPdec, float* __restrict__ dlog, int ldc) {
+  __shared__ float red[4];
+  const BatchSet& bs = *bsp;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  float bb[4];
+#pragma unroll
+  for (int q = 0; q < 4; ++q) bb[q] = lane + 64 * q < dO ? b1[lane + 64 * q] : 0.f;
+  float lsum = 0.f;
+  for (int ev = blockIdx.x * 4 + wave; ev < bs.total; ev += gridDim.x * 4) {
+    const int b = batch_of_row(bs, ev, 1);
+    const int off = bs.b[b].ev_off, n = bs.b[b].n;
+    const int i = ev - off;
+    const size_t ra = (size_t)(2 * off + i) * ldp, rb = ra + (size_t)n * ldp;   // the source's and the destination's row
+    const float* __restrict__ y = bs.b[b].labels + (size_t)i * C;
+    const float inv = 1.0f / ((float)n * (float)C);
+    float h[4], dh[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int c = lane + 64 * q;
+      h[q] = c < dO ? fmaxf(Pdec[ra + c] + bb[q] + Pdec[rb + dO + c], 0.f) : 0.f;
+      if (c < dO) h1[(size_t)ev * ldh + c] = h[q];
+    }
+    float lterm = 0.f;
+    for (int cls = 0; cls < C; ++cls) {
+      const float* __restrict__ wr = w2 + (size_t)cls * dO;
+      float wv[4], acc = 0.f;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int c = lane + 64 * q;
+        wv[q] = c < dO ? wr[c] : 0.f;
+        acc += h[q] * wv[q];
+      }
+#pragma unroll
+      for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o);
+      const float lg = acc + b2[cls], yv = y[cls];
+      const float sgm = 1.0f / (1.0f + expf(-lg));
+      lterm += fmaxf(lg, 0.f) + log1pf(expf(-fabsf(lg))) - yv * lg;
+      const float dl = (sgm - yv) * inv;
+      if (lane == 0) {
+        logits[(size_t)ev * C + cls] = lg;
+        dlog[(size_t)ev * ldc + cls] = dl;
+      }
+#pragma unroll
+      for (int q = 0; q < 4; ++q) dh[q] += dl * wv[q];
+    }
+    if (lane == 0) lsum += lterm * inv / (float)bs.nb;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int c = lane + 64 * q;
+      if (c < dO) {
+        const float gq = h[q] > 0.f ? dh[q] : 0.f;
+        dPdec[ra + c] = gq; dPdec[ra + dO + c] = 0.f;
+        dPdec[rb + c] = 0.f; dPdec[rb + dO + c] = gq;
+      }
+    }
+  }
+  if (lane == 0) red[wave] = lsum;
+  __syncthreads();
+  if (threadIdx.x == 0 && out_loss != nullptr) atomicAdd(out_loss, red[0] + red[1] + red[2] + red[3]);
+}
+
+void decoder_classes(const Dims& d, const BatchSet* bs, int total, const float* Pdec, int ldp, const float* b1,
+                     const float* w2, const float* b2, float* logits, float* out_loss, float* h1, float* dPdec,
+                     float* dlog, hipStream_t s) {
+  if (total <= 0) return;
+  hipLaunchKernelGGL(dec_class_kernel, dim3(std::min((total + 3) / 4, 4 * DP_BLOCKS)), dim3(256), 0, s, bs, d.dO, d.nC, Pdec,
+                     ldp, b1, w2, b2, logits, out_loss, h1, d.ldh, dPdec, dlog, d.ldc);
+}
+
+// Rank of every event's true pair among its pairs with the sampled negative destinations (pair layout of the
+// epoch-parallel step); one thread per event, the sum of the reciprocal ranks once per block.
+__global__ __launch_bounds__(256) void rank_kernel(const BatchSet* __restrict__ bsp, const float* __restrict__ logits,
+                                                   float* __restrict__ rank, float* __restrict__ rr_sum) {
+  __shared__ float red[4];
+  const BatchSet& bs = *bsp;
+  const int ev = blockIdx.x * 256 + threadIdx.x;
+  float rr = 0.f;
+  if (ev < bs.total) {
+    const int b = batch_of_row(bs, ev, 1);
+    const int off = bs.b[b].ev_off, n = bs.b[b].n, J = bs.nneg;
+    const size_t r0 = (size_t)(1 + J) * off + (ev - off);
+    const float st = logits[r0];
+    int above = 0, same = 0;
+    for (int g = 0; g < J; ++g) {
+      const float sn = logits[r0 + (size_t)(1 + g) * n];
+      above += sn > st ? 1 : 0;
+      same += sn == st ? 1 : 0;
+    }
+    const float r = 1.0f + (float)above + 0.5f * (float)same;
+    rank[ev] = r;
+    rr = 1.0f / r;
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) rr += __shfl_xor(rr, o);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = rr;
+  __syncthreads();
+  if (threadIdx.x == 0) atomicAdd(rr_sum, red[0] + red[1] + red[2] + red[3]);
+}
+
+void reciprocal_ranks(const BatchSet* bs, int total, const float* logits, float* rank, float* rr_sum, hipStream_t s) {
+  if (total <= 0) return;
+  hipLaunchKernelGGL(rank_kernel, dim3((total + 255) / 256), dim3(256), 0, s, bs, logits, rank, rr_sum);
 }
 
 __global__ void mask_dz_kernel(int R, int dO, const float* __restrict__ dz_in, int p_in, const float* __restrict__ z,

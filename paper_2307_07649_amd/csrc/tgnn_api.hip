@@ -118,7 +118,9 @@ static void layout(const Dims& d, Ws& w, Bump& b) {
   w.Yt = b.take<float>(R * d.ldy);
   w.dscore = b.take<float>(R * d.H * d.k);
   w.Pdec = b.take<float>(R * d.ldkv); w.dPdec = b.take<float>(R * d.ldkv);
-  w.h1 = b.take<float>(B2 * d.ldh); w.logits = b.take<float>(B2);
+  w.h1 = b.take<float>(B2 * d.ldh);
+  w.logits = b.take<float>(std::max(B2, (size_t)d.maxEv * (size_t)d.nC));
+  w.dlog = b.take<float>(d.nC > 0 ? (size_t)d.maxEv * d.ldc : 4);
   w.loss_acc = b.take<float>(TGNN_MAX_BATCHES);
   w.Wih_p = b.take<float>((size_t)3 * d.dm * d.ldx); w.Whh_p = b.take<float>((size_t)3 * d.dm * d.ldh);
   w.Wdec_p = b.take<float>((size_t)2 * d.dO * d.ldh);
@@ -377,7 +379,7 @@ static void fill_param_set(const Dims& d, const tgnn_params* p, const tgnn_param
   float* const* gg = reinterpret_cast<float* const*>(g);
   const int sizes[19] = {d.dt, d.dt, 3 * d.dm * d.d_in, 3 * d.dm * d.dm, 3 * d.dm, 3 * d.dm, d.dO * d.dq, d.dO,
                          d.dO * d.dkv, d.dO, d.dO * d.dkv, d.dO, d.dO * (d.dO + d.dx), d.dO, d.dO * d.dO, d.dO * d.dO,
-                         d.dO, d.dO, 1};
+                         d.dO, d.nC > 0 ? d.nC * d.dO : d.dO, d.nC > 0 ? d.nC : 1};
   for (int i = first; i < 19; ++i) {
     set.p[set.cnt] = pp[i]; set.g[set.cnt] = gg ? gg[i] : nullptr; set.n[set.cnt] = sizes[i]; set.cnt++;
   }
@@ -419,6 +421,8 @@ int32_t tgnn_create(const tgnn_config* cfg, tgnn_ctx** out) {
     return set_error(TGNN_E_OUT_OF_RANGE, "max_neg_sets = %d outside [0, %d]", cfg->max_neg_sets, TGNN_MAX_NEG_SETS);
   if ((long long)cfg->n_nodes * cfg->n_replicas > 0x7fffffffLL)
     return set_error(TGNN_E_OUT_OF_RANGE, "n_nodes * n_replicas exceeds int32");
+  if (cfg->n_classes < 0 || cfg->n_classes > TGNN_MAX_CLASSES)
+    return set_error(TGNN_E_OUT_OF_RANGE, "n_classes = %d outside [0, %d]", cfg->n_classes, TGNN_MAX_CLASSES);
 
   tgnn_ctx* ctx = new (std::nothrow) tgnn_ctx();
   if (ctx == nullptr) return set_error(TGNN_E_WORKSPACE, "out of host memory");
@@ -433,6 +437,7 @@ int32_t tgnn_create(const tgnn_config* cfg, tgnn_ctx** out) {
   const int nb = d.nrep < TGNN_MAX_BATCHES ? d.nrep : TGNN_MAX_BATCHES;
   const long long maxEv = (long long)d.maxB * nb;
   d.maxNeg = cfg->max_neg_sets > 1 ? cfg->max_neg_sets : 1;
+  d.nC = cfg->n_classes; d.ldc = padrow(d.nC > 0 ? d.nC : 1);
   if (maxEv * (2 + d.maxNeg) * (1 + d.k) > 0x3fffffffLL) {
     delete ctx;
     return set_error(TGNN_E_OUT_OF_RANGE, "max_batch * n_replicas * (2 + max_neg_sets) * (1 + k) exceeds the slot index range");
@@ -715,7 +720,8 @@ int32_t tgnn_memory_writeback(tgnn_ctx* ctx, tgnn_state* st, int32_t replica, co
 // loss_in_array: out_loss is an element of tgnn_train_steps' loss array (checked there; only 4-byte aligned)
 static int train_step_impl(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, const tgnn_params* p, tgnn_params* grads,
                            const tgnn_batch* batches, int32_t n_batches, float lr, float* out_loss, float* out_logits,
-                           int32_t* out_winner, void* stream, bool loss_in_array, int nneg = 1);
+                           int32_t* out_winner, void* stream, bool loss_in_array, int nneg = 1,
+                           const float* const* labels = nullptr);
 
 int32_t tgnn_train_step_epoch_parallel(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, const tgnn_params* p,
                                        tgnn_params* grads, const tgnn_batch* batches, int32_t n_batches,
@@ -734,24 +740,63 @@ int32_t tgnn_train_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
   return train_step_impl(ctx, g, st, p, grads, batches, n_batches, lr, out_loss, out_logits, out_winner, stream, false);
 }
 
+int32_t tgnn_train_step_edge_class(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, const tgnn_params* p,
+                                   tgnn_params* grads, const tgnn_batch* batches, int32_t n_batches,
+                                   const float* const* labels, float lr, float* out_loss, float* out_logits,
+                                   int32_t* out_winner, void* stream) {
+  if (ctx == nullptr) return set_error(TGNN_E_NULL_PTR, "ctx is NULL");
+  if (labels == nullptr) return set_error(TGNN_E_NULL_PTR, "labels is NULL");
+  return train_step_impl(ctx, g, st, p, grads, batches, n_batches, lr, out_loss, out_logits, out_winner, stream, false, 0,
+                         labels);
+}
+
+int32_t tgnn_eval_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, const tgnn_params* p,
+                       const tgnn_batch* batches, int32_t n_batches, int32_t n_neg_sets, float* out_logits,
+                       float* out_rank, float* out_rr_sum, int32_t* out_winner, void* stream) {
+  if (ctx == nullptr) return set_error(TGNN_E_NULL_PTR, "ctx is NULL");
+  if (n_neg_sets < 1 || n_neg_sets > ctx->d.maxNeg)
+    return set_error(TGNN_E_OUT_OF_RANGE, "n_neg_sets = %d outside [1, %d] (config.max_neg_sets)", n_neg_sets, ctx->d.maxNeg);
+  REQ_PTR(out_rank); REQ_PTR(out_rr_sum);
+  tgnn_params no_grads;
+  memset(&no_grads, 0, sizeof(no_grads));
+  ctx->eval = true; ctx->out_rank = out_rank; ctx->out_rr = out_rr_sum;
+  const int rc = train_step_impl(ctx, g, st, p, &no_grads, batches, n_batches, 0.0f, nullptr, out_logits, out_winner, stream,
+                                 false, n_neg_sets);
+  ctx->eval = false; ctx->out_rank = nullptr; ctx->out_rr = nullptr;
+  return rc;
+}
+
 static int train_step_impl(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, const tgnn_params* p, tgnn_params* grads,
                            const tgnn_batch* batches, int32_t n_batches, float lr, float* out_loss, float* out_logits,
-                           int32_t* out_winner, void* stream, bool loss_in_array, int nneg) {
+                           int32_t* out_winner, void* stream, bool loss_in_array, int nneg, const float* const* labels) {
   if (ctx == nullptr) return set_error(TGNN_E_NULL_PTR, "ctx is NULL");
+  if ((ctx->d.nC > 0) != (labels != nullptr))
+    return set_error(TGNN_E_INVALID_ARG, ctx->d.nC > 0 ? "this context has an edge-classification head (n_classes > 0): "
+                                                         "use tgnn_train_step_edge_class"
+                                                       : "tgnn_train_step_edge_class needs a context with n_classes > 0");
   if (int rc = check_graph(ctx, g)) return rc;
   if (int rc = check_state(ctx, st)) return rc;
   if (int rc = check_params(p, "params")) return rc;
-  if (int rc = check_params(grads, "grads")) return rc;
+  if (!ctx->eval)
+    if (int rc = check_params(grads, "grads")) return rc;
   BatchSet bs;
   if (int rc = make_batchset(ctx, batches, n_batches, bs, nneg)) return rc;
-  for (int b = 0; b < bs.nb; ++b)
-    if (bs.b[b].n > 0) REQ_PTR(bs.b[b].neg);
-  if (!loss_in_array) REQ_PTR(out_loss);
+  for (int b = 0; b < bs.nb; ++b) {
+    if (labels != nullptr) {
+      bs.b[b].neg = nullptr;
+      bs.b[b].labels = labels[b];
+      if (bs.b[b].n > 0) REQ_PTR(bs.b[b].labels);
+    } else if (bs.b[b].n > 0) {
+      REQ_PTR(bs.b[b].neg);
+    }
+  }
+  bs.ncls = labels != nullptr ? ctx->d.nC : 0;
+  if (!loss_in_array && !ctx->eval) REQ_PTR(out_loss);
   OPT_PTR(out_logits); OPT_PTR(out_winner);
   if (!(lr == lr)) return set_error(TGNN_E_INVALID_ARG, "lr is NaN");
   hipStream_t s = as_stream(stream);
   if (bs.total == 0) {
-    zero_f32(out_loss, 1, s);
+    if (out_loss != nullptr) zero_f32(out_loss, 1, s);
     TGNN_LAUNCH_CHECK();
     return TGNN_OK;
   }
@@ -852,8 +897,10 @@ static int replay_steps(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
     const float* const* gg = reinterpret_cast<const float* const*>(grads);
     for (int i = 0; i < 19; ++i) { key.ptr[q++] = pp[i]; key.ptr[q++] = gg[i]; }
     key.ptr[q++] = out_loss; key.ptr[q++] = out_logits; key.ptr[q++] = out_winner; key.ptr[q++] = s;
+    key.ptr[q++] = ctx->out_rank; key.ptr[q++] = ctx->out_rr;
     for (int b = 0; b < bs.nb; ++b) { key.n[b] = bs.b[b].n; key.rep[b] = bs.b[b].replica; }
     key.nb = bs.nb; key.lr = lr; key.parity = parity; key.n_steps = n_steps; key.nneg = bs.nneg;
+    key.mode = ctx->eval ? 2 : bs.ncls > 0 ? 1 : 0;
   }
   StepGraph* hit = nullptr;
   StepGraph* victim = &ctx->graphs[0];
@@ -872,7 +919,8 @@ static int replay_steps(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
     int rc = TGNN_OK;
     for (int i = 0; i < n_steps && rc == TGNN_OK; ++i) {
       ctx->w.ucount = ctx->w.ucount_pair + ((parity + i) & 1);
-      rc = enqueue_step(ctx, g, st, p, grads, sets[i], lr, out_loss + i, out_logits, out_winner, s);
+      rc = enqueue_step(ctx, g, st, p, grads, sets[i], lr, out_loss != nullptr ? out_loss + i : nullptr, out_logits,
+                        out_winner, s);
     }
     hipGraph_t graph = nullptr;
     const hipError_t ce = hipStreamEndCapture(s, &graph);
@@ -932,8 +980,8 @@ static int replay_steps(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
     for (int i = 0; i < n_steps; ++i) {
       ctx->w.ucount = ctx->w.ucount_pair + ((parity + i) & 1);
       HeadArgs h;
-      head_fill(ctx, g, (2 + sets[i].nneg) * sets[i].total, p, &sets[i], lr != 0.0f ? &sgd_set : nullptr, overwrite ? &zero_set_ : nullptr,
-                out_loss + i, h);
+      head_fill(ctx, g, (2 + sets[i].nneg) * sets[i].total, p, &sets[i], lr != 0.0f ? &sgd_set : nullptr,
+                overwrite && !ctx->eval ? &zero_set_ : nullptr, out_loss != nullptr ? out_loss + i : nullptr, h);
       void* kargs[1] = {&h};
       hipKernelNodeParams np;
       memset(&np, 0, sizeof(np));
@@ -954,14 +1002,16 @@ static int enqueue_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
                         const BatchSet& bs, float lr, float* out_loss, float* out_logits, int32_t* out_winner,
                         hipStream_t s) {
   const Dims& d = ctx->d; Ws& w = ctx->w;
-  const int R = (2 + bs.nneg) * bs.total, S = R * (1 + d.k), B2 = (1 + bs.nneg) * bs.total;
+  const bool eval = ctx->eval, classes = bs.ncls > 0;
+  const int R = (2 + bs.nneg) * bs.total, S = R * (1 + d.k);
+  const int n_logits = classes ? bs.total * d.nC : (1 + bs.nneg) * bs.total;
 
   StageTimer tm{ctx, s};
   Side side{ctx, s, (ctx->cfg.flags & TGNN_FLAG_SIDE_STREAM) != 0};
   SgdSet sgd_set, zero_set_;
   fill_param_set(d, p, grads, 2, sgd_set);  // time_w, time_b stay frozen
   fill_param_set(d, grads, nullptr, 0, zero_set_);
-  const bool overwrite = (ctx->cfg.flags & TGNN_FLAG_OVERWRITE_GRADS) != 0;
+  const bool overwrite = (ctx->cfg.flags & TGNN_FLAG_OVERWRITE_GRADS) != 0 && !eval;
   tm.begin(2);
   {  // first launch: the sampler's blocks, then the prologue's
     HeadArgs h;
@@ -1009,7 +1059,8 @@ static int enqueue_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
   // (the fill pass of the slot sort, needed by the backward pass only, rides in the attention launch)
   // Merge layer, decoder + loss and their backward pass down to the attention output are local to an event's
   // three roots: one launch when the layer width allows it.
-  const bool chain = root_chain_fits(d) && bs.nneg == 1;   // (the one-launch chain is laid out for three roots per event)
+  // (the one-launch chain is laid out for three roots per event, the link decoder, and always runs its backward half)
+  const bool chain = root_chain_fits(d) && bs.nneg == 1 && !eval && !classes;
   const AttnIn ain{w.slot_row, w.cnt, g->efeat, w.neid, nullptr, p};
   attn_forward(ctx, p, R, U, w.ucount, ain, &tm, s, sort_args(ctx, S), !chain);
 
@@ -1029,10 +1080,26 @@ static int enqueue_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
     root_chain(ca, bs, (ctx->cfg.flags & TGNN_FLAG_WIDE_ROOT_TILES) != 0, s);
   } else {   // decoder + loss (also produces d loss / d hidden)
     gemm_nt(w.z, d.ldh, w.Wdec_p, d.ldh, nullptr, w.Pdec, d.ldkv, R, 2 * d.dO, d.ldh, 2 * d.dO, false, s);
-    decoder_pairs(d, w.bs_dev, bs.total, w.Pdec, d.ldkv, p->dec_b1, p->dec_w2, p->dec_b2, w.logits, out_loss, w.h1, w.dPdec,
-                  grads->dec_w2, grads->dec_b2, s);
+    if (classes)
+      decoder_classes(d, w.bs_dev, bs.total, w.Pdec, d.ldkv, p->dec_b1, p->dec_w2, p->dec_b2, w.logits, out_loss, w.h1,
+                      w.dPdec, w.dlog, s);
+    else
+      decoder_pairs(d, w.bs_dev, bs.total, w.Pdec, d.ldkv, p->dec_b1, p->dec_w2, p->dec_b2, w.logits, out_loss, w.h1, w.dPdec,
+                    grads->dec_w2, grads->dec_b2, s);
   }
   tm.end(12);
+  if (eval) {
+    // Evaluation (Sec. 4: rank of the true destination among the sampled ones): no backward half; the write-back
+    // scatter leaves in a launch of its own.
+    reciprocal_ranks(w.bs_dev, bs.total, w.logits, ctx->out_rank, ctx->out_rr, s);
+    WbArgs wb = writeback_args(d, w.bs_dev, bs.total, st, w.winkey, w.epoch, w.Xrow, d.ldxr, w.tau, w.slot_row, nullptr,
+                               nullptr, nullptr, nullptr, out_winner, nullptr, 0, 0.0f);
+    gemm_nt_group(nullptr, 0, s, &wb);
+    if (out_logits)
+      TGNN_HIP_CHECK(hipMemcpyAsync(out_logits, w.logits, sizeof(float) * n_logits, hipMemcpyDeviceToDevice, s));
+    TGNN_LAUNCH_CHECK();
+    return TGNN_OK;
+  }
 
   // Backward.  The data-gradient chain stays on the caller's stream; the weight-gradient GEMMs are queued and
   // leave in one launch at the end (side-stream mode: those known after the attention backward leave there,
@@ -1045,6 +1112,8 @@ static int enqueue_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
   TnBatch tn;
   tn.dev_rows_est = U_est;
   tn.add(w.dPdec, d.ldkv, w.z, d.ldh, R, 2 * d.dO, d.dO, dec);
+  if (classes)   // output layer of the classification head: d logit^T hidden, column sums to its bias
+    tn.add(w.dlog, d.ldc, w.h1, d.ldh, bs.total, d.nC, d.dO, single_out(grads->dec_w2, d.dO, grads->dec_b2));
   if (!chain) {  // dz, gated by the ReLU of the merge layer
     RowAdd gate;
     gate.gate = w.z; gate.ld_gate = d.ldh;
@@ -1088,7 +1157,7 @@ static int enqueue_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
   }
   tm.end(17);
   if (out_logits)
-    TGNN_HIP_CHECK(hipMemcpyAsync(out_logits, w.logits, sizeof(float) * B2, hipMemcpyDeviceToDevice, s));
+    TGNN_HIP_CHECK(hipMemcpyAsync(out_logits, w.logits, sizeof(float) * n_logits, hipMemcpyDeviceToDevice, s));
   TGNN_LAUNCH_CHECK();
   return TGNN_OK;
 }

@@ -29,6 +29,7 @@ struct Dims {
   int ldy;    // rows of width 2 d_t: a root's time-encoding gradient sums {d/dw | d/db}
   int ldst;   // rows of width d_s: gradient reaching a node row's static columns
   int maxNeg;   // negative sets a step may carry
+  int nC, ldc;  // classes of the edge-classification head (0: link prediction) and the pitch of its [events, nC] rows
   int maxEv, maxR, maxRK, maxS, maxU;
 };
 
@@ -36,13 +37,16 @@ struct BatchDesc {
   const int32_t *src, *dst, *neg, *eid;
   const double* t;
   int32_t n, replica, ev_off;
+  const float* labels;   // [n, ncls] class targets of an edge-classification batch, else NULL
 };
 // Roots of batch b are [src | dst | neg set 0 | ... | neg set nneg-1], n each, starting at root (2 + nneg) * ev_off;
 // its pairs are [true pairs | pairs with neg set 0 | ...], starting at pair (1 + nneg) * ev_off.
 struct BatchSet {
   BatchDesc b[TGNN_MAX_BATCHES];
   int32_t nb, total;
-  int32_t nneg;   // negative destinations per event (sets of the epoch-parallel step, Sec. 3.2.2); 1 in the plain step
+  int32_t nneg;   // negative destinations per event (sets of the epoch-parallel step, Sec. 3.2.2); 1 in the plain step;
+                  // 0 in an edge-classification step (roots [src | dst], one "pair" per event)
+  int32_t ncls;   // classes of the edge-classification head; 0: link prediction
 };
 
 // Device workspace.  S slots = R roots followed by R*k neighbour slots (slot R + r*k + j).
@@ -87,7 +91,8 @@ struct Ws {
   float *Yt;                                   // [R,ldy] per root: time-encoding gradient sums of its keys
   float *dscore;                               // [R,H*k] gradients of the attention scores
   // decoder
-  float *Pdec, *dPdec, *h1, *logits;           // [R,ldkv] [R,ldkv] [2B,ldh] [2B]
+  float *Pdec, *dPdec, *h1, *logits;           // [R,ldkv] [R,ldkv] [pairs,ldh] [pairs] (classification: [B, nC])
+  float* dlog;                                 // [B, ldc] d loss / d logit of the edge-classification head
   float* loss_acc;                                   // [TGNN_MAX_BATCHES] per-batch loss sums
   // packed weights
   float *Wih_p, *Whh_p, *Wdec_p;
@@ -123,7 +128,7 @@ constexpr int MAX_STEP_GRAPHS = 8;
 struct StepKey {
   const void* ptr[64];
   int32_t n[TGNN_MAX_BATCHES], rep[TGNN_MAX_BATCHES];
-  int32_t nb, parity, n_steps, nneg;
+  int32_t nb, parity, n_steps, nneg, mode;   // mode: 0 training, 1 edge classification, 2 evaluation
   float lr;
 };
 struct StepGraph {
@@ -160,6 +165,10 @@ struct tgnn_ctx {
   int last_attn_roots;
   int device;
   int step_parity = 0;             // which of the two row counters the next training step uses
+  // what the call in progress asks of its step beyond training (calls on one context are ordered by the caller)
+  bool eval = false;               // tgnn_eval_step: forward half, ranks and write-back only
+  float* out_rank = nullptr;       // ... its per-event ranks and the sum of their reciprocals
+  float* out_rr = nullptr;
   bool adam = false;               // tgnn_set_optimizer: the in-step update is Adam's
   bool train_static = false;       // tgnn_train_static
   float* grad_static = nullptr;
@@ -590,6 +599,13 @@ void fattn_bwd(const FusedAttn& a, hipStream_t s);
 void decoder_pairs(const Dims& d, const BatchSet* bs, int total, const float* Pdec, int ldp, const float* b1,
                    const float* w2, const float* b2, float* logits, float* out_loss, float* h1, float* dPdec,
                    float* g_w2, float* g_b2, hipStream_t s);
+// Edge-classification head (nC outputs, targets in the batch descriptors): hidden layer, logits [total, nC], loss,
+// d loss / d logit (dlog, pitch ldc), and per root the gradient of its Pdec row.
+void decoder_classes(const Dims& d, const BatchSet* bs, int total, const float* Pdec, int ldp, const float* b1,
+                     const float* w2, const float* b2, float* logits, float* out_loss, float* h1, float* dPdec,
+                     float* dlog, hipStream_t s);
+// rank[ev] = 1 + #(negative pairs of the event scoring above its true pair) + 0.5 #(scoring the same); rr_sum += sum 1/rank
+void reciprocal_ranks(const BatchSet* bs, int total, const float* logits, float* rank, float* rr_sum, hipStream_t s);
 void mask_dz(int R, int dO, const float* dz_in, int p_in, const float* z, int ldz, float* dz_out, hipStream_t s);
 // d_x_root[r, c] = ds_row[r, c];  d_x_nbr[j, c] = ds_row[R + j, c]   (c < dm, outputs pitch dm)
 void attn_dx_out(int R, int RK, int dm, const float* ds_row, int ldh, float* d_x_root, float* d_x_nbr, hipStream_t s);

@@ -30,7 +30,8 @@ FLAG_GENERIC_ATTN = 16
 
 class tgnn_config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("n_nodes", "d_mem", "d_time", "d_edge", "d_static", "n_heads", "k",
-                                         "max_batch", "n_replicas", "dt_source", "flags", "max_neg_sets")]
+                                         "max_batch", "n_replicas", "dt_source", "flags", "max_neg_sets",
+                                         "n_classes")]
 
 
 class tgnn_graph(C.Structure):
@@ -71,6 +72,11 @@ _SIGS = {
                              C.POINTER(tgnn_params), C.POINTER(tgnn_batch), _I, C.c_float, _P, _P, _P, _P]),
     "tgnn_train_step_epoch_parallel": (_I, [_P, C.POINTER(tgnn_graph), C.POINTER(tgnn_state), C.POINTER(tgnn_params),
                                             C.POINTER(tgnn_params), C.POINTER(tgnn_batch), _I, _I, C.c_float, _P, _P, _P, _P]),
+    "tgnn_train_step_edge_class": (_I, [_P, C.POINTER(tgnn_graph), C.POINTER(tgnn_state), C.POINTER(tgnn_params),
+                                        C.POINTER(tgnn_params), C.POINTER(tgnn_batch), _I, C.POINTER(_P), C.c_float, _P, _P,
+                                        _P, _P]),
+    "tgnn_eval_step": (_I, [_P, C.POINTER(tgnn_graph), C.POINTER(tgnn_state), C.POINTER(tgnn_params), C.POINTER(tgnn_batch),
+                            _I, _I, _P, _P, _P, _P, _P]),
     "tgnn_train_steps": (_I, [_P, C.POINTER(tgnn_graph), C.POINTER(tgnn_state), C.POINTER(tgnn_params),
                               C.POINTER(tgnn_params), _I, C.POINTER(tgnn_batch), _I, C.c_float, _P, _P]),
     "tgnn_set_optimizer": (_I, [_P, _I, C.POINTER(tgnn_params), C.POINTER(tgnn_params), C.c_float, C.c_float, C.c_float]),
@@ -210,9 +216,9 @@ class Batch:
 
 class Context:
     def __init__(self, n_nodes, d_mem, d_time, d_edge, d_static, n_heads, k, max_batch, n_replicas=1, dt_source=0,
-                 flags=0, max_neg_sets=1):
+                 flags=0, max_neg_sets=1, n_classes=0):
         self.cfg = tgnn_config(n_nodes, d_mem, d_time, d_edge, d_static, n_heads, k, max_batch, n_replicas, dt_source,
-                               flags, max_neg_sets)
+                               flags, max_neg_sets, n_classes)
         self.h = _P()
         _check(_lib.tgnn_create(C.byref(self.cfg), C.byref(self.h)))
         self.d_x = d_mem + d_static
@@ -302,6 +308,23 @@ class Context:
         _check(_lib.tgnn_train_step_epoch_parallel(self.h, C.byref(g.c), C.byref(st.c), C.byref(p.c), C.byref(grads.c), arr,
                                                    len(batches), n_neg_sets, lr, _ptr(out_loss), _ptr(out_logits),
                                                    _ptr(out_winner), _stream()))
+
+    def tgnn_train_step_edge_class(self, g: Graph, st: State, p: Params, grads: Params, batches, labels, lr=0.0,
+                                   out_loss=None, out_logits=None, out_winner=None):
+        """labels: one float32 device tensor [n, n_classes] per batch (the batches' `neg` is not read)."""
+        arr = (tgnn_batch * len(batches))(*[b.c for b in batches])
+        lab = (_P * len(batches))(*[_ptr(y) for y in labels])
+        _check(_lib.tgnn_train_step_edge_class(self.h, C.byref(g.c), C.byref(st.c), C.byref(p.c), C.byref(grads.c), arr,
+                                               len(batches), lab, lr, _ptr(out_loss), _ptr(out_logits), _ptr(out_winner),
+                                               _stream()))
+
+    def tgnn_eval_step(self, g: Graph, st: State, p: Params, batches, n_neg_sets, out_rank, out_rr_sum, out_logits=None,
+                       out_winner=None):
+        """Each batch's `neg` holds n_neg_sets sets of n negative destinations; out_rank [sum n] float32, out_rr_sum [1]
+        float32 (the sum of 1 / rank is added to it)."""
+        arr = (tgnn_batch * len(batches))(*[b.c for b in batches])
+        _check(_lib.tgnn_eval_step(self.h, C.byref(g.c), C.byref(st.c), C.byref(p.c), arr, len(batches), n_neg_sets,
+                                   _ptr(out_logits), _ptr(out_rank), _ptr(out_rr_sum), _ptr(out_winner), _stream()))
 
     def tgnn_train_steps(self, g: Graph, st: State, p: Params, grads: Params, steps, lr=0.0, out_loss=None):
         """steps: a list of steps, each a list of Batch (the same number per step); out_loss: device array [len(steps)]."""

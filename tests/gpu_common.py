@@ -87,7 +87,8 @@ class GpuSide:
         d = P["d"]
         self.P, self.d = P, d
         self.ctx = tgnn.Context(d.n_nodes, d.d_mem, d.d_time, d.d_edge, d.d_static, d.n_heads, d.k, d.batch,
-                                n_replicas=n_replicas, dt_source=dt_source, flags=flags, max_neg_sets=max_neg_sets)
+                                n_replicas=n_replicas, dt_source=dt_source, flags=flags, max_neg_sets=max_neg_sets,
+                                n_classes=d.n_classes)
         self.graph = tgnn.Graph(P["src"], P["dst"], P["ts"], d.n_nodes, P["efeat"])
         self.state = tgnn.State(d.n_nodes, d.d_mem, n_replicas, P["static"])
         self.params = tgnn.Params.from_numpy(P["params"])
@@ -95,20 +96,28 @@ class GpuSide:
         self.loss = torch.zeros(4, device="cuda")
 
     def step(self, batches, replicas=None, lr=0.0, want=True, n_neg_sets=1):
-        """n_neg_sets > 1: every batch's "neg" holds that many sets, [J, n] (tgnn_train_step_epoch_parallel)."""
+        """n_neg_sets > 1: every batch's "neg" holds that many sets, [J, n] (tgnn_train_step_epoch_parallel).
+        Batches with "labels" ([n, C]): tgnn_train_step_edge_class (roots [src | dst], logits [sum n, C])."""
         torch, tgnn = self.torch, self.tgnn
-        J = n_neg_sets
+        C = self.d.n_classes
+        J = 0 if C else n_neg_sets
         replicas = replicas if replicas is not None else list(range(len(batches)))
         bl = [tgnn.Batch(b["src"], b["dst"], np.asarray(b["neg"]).reshape(-1), b["eid"], b["t"], replica=r)
               for b, r in zip(batches, replicas)]
         tot = sum(b.n for b in bl)
-        if not hasattr(self, "_out") or self._out[0].numel() != (1 + J) * tot:      # stable output buffers: same graph key
-            self._out = (torch.empty((1 + J) * tot, device="cuda"), torch.empty(2 * tot, dtype=torch.int32, device="cuda"))
+        n_logits = tot * C if C else (1 + J) * tot
+        if not hasattr(self, "_out") or self._out[0].numel() != n_logits:      # stable output buffers: same graph key
+            self._out = (torch.empty(n_logits, device="cuda"), torch.empty(2 * tot, dtype=torch.int32, device="cuda"))
         logits, win = self._out
+        if C:
+            labels = [torch.from_numpy(np.ascontiguousarray(b["labels"], np.float32)).cuda() for b in batches]
         torch.cuda.synchronize()
         with torch.cuda.stream(self.stream):
             self.grads.zero_()
-            if J == 1:
+            if C:
+                self.ctx.tgnn_train_step_edge_class(self.graph, self.state, self.params, self.grads, bl, labels, lr=lr,
+                                                    out_loss=self.loss, out_logits=logits, out_winner=win)
+            elif J == 1:
                 self.ctx.tgnn_train_step(self.graph, self.state, self.params, self.grads, bl, lr=lr, out_loss=self.loss,
                                          out_logits=logits, out_winner=win)
             else:
@@ -118,8 +127,8 @@ class GpuSide:
         if not want:
             return None
         R = (2 + J) * tot; k = self.d.k
-        out = dict(loss=float(self.loss[0].item()), logits=logits.cpu().numpy(), winner=win.cpu().numpy(),
-                   grads=self.grads.numpy())
+        out = dict(loss=float(self.loss[0].item()), logits=logits.cpu().numpy().reshape((tot, C) if C else (-1,)),
+                   winner=win.cpu().numpy(), grads=self.grads.numpy())
         dbg = self.ctx.tgnn_debug_read
         out["nbr"] = dbg(0, torch.empty(R, k, dtype=torch.int32, device="cuda")).cpu().numpy()
         out["neid"] = dbg(1, torch.empty(R, k, dtype=torch.int32, device="cuda")).cpu().numpy()
@@ -128,7 +137,31 @@ class GpuSide:
         out["s_new"] = dbg(4, torch.empty(R * (1 + k), self.d.d_mem, device="cuda")).cpu().numpy()
         out["tau"] = dbg(5, torch.empty(R * (1 + k), dtype=torch.float64, device="cuda")).cpu().numpy()
         out["z"] = dbg(6, torch.empty(R, self.d.d_mem, device="cuda")).cpu().numpy()
-        out["h1"] = dbg(7, torch.empty((1 + J) * tot, self.d.d_mem, device="cuda")).cpu().numpy()
+        out["h1"] = dbg(7, torch.empty(max(1 + J, 1) * tot, self.d.d_mem, device="cuda")).cpu().numpy()
+        torch.cuda.synchronize()
+        return out
+
+    def eval_step(self, batches, n_neg_sets, replicas=None):
+        """tgnn_eval_step: every batch's "neg" holds n_neg_sets sets, [J, n].  Returns logits [(1 + J) sum n], rank
+        [sum n], the sum of the reciprocal ranks, winners, and the sampler's / UPDT's outputs like step()."""
+        torch, tgnn = self.torch, self.tgnn
+        J = n_neg_sets
+        replicas = replicas if replicas is not None else list(range(len(batches)))
+        bl = [tgnn.Batch(b["src"], b["dst"], np.asarray(b["neg"]).reshape(-1), b["eid"], b["t"], replica=r)
+              for b, r in zip(batches, replicas)]
+        tot = sum(b.n for b in bl)
+        logits = torch.empty((1 + J) * tot, device="cuda"); win = torch.empty(2 * tot, dtype=torch.int32, device="cuda")
+        rank = torch.empty(tot, device="cuda"); rr = torch.zeros(1, device="cuda")
+        torch.cuda.synchronize()
+        with torch.cuda.stream(self.stream):
+            self.ctx.tgnn_eval_step(self.graph, self.state, self.params, bl, J, rank, rr, out_logits=logits, out_winner=win)
+        torch.cuda.synchronize()
+        R = (2 + J) * tot; k = self.d.k
+        dbg = self.ctx.tgnn_debug_read
+        out = dict(logits=logits.cpu().numpy(), rank=rank.cpu().numpy(), rr_sum=float(rr.item()), winner=win.cpu().numpy())
+        out["nbr"] = dbg(0, torch.empty(R, k, dtype=torch.int32, device="cuda")).cpu().numpy()
+        out["cnt"] = dbg(3, torch.empty(R, dtype=torch.int32, device="cuda")).cpu().numpy()
+        out["z"] = dbg(6, torch.empty(R, self.d.d_mem, device="cuda")).cpu().numpy()
         torch.cuda.synchronize()
         return out
 

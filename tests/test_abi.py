@@ -36,7 +36,7 @@ def test_library_exports_every_declared_symbol(tgnn):
 
 def test_binding_structs_match_header_layout(tgnn):
     import ctypes as C
-    assert C.sizeof(tgnn.tgnn_config) == 12 * 4
+    assert C.sizeof(tgnn.tgnn_config) == 13 * 4
     assert C.sizeof(tgnn.tgnn_graph) == 6 * 8
     assert C.sizeof(tgnn.tgnn_state) == 6 * 8
     assert C.sizeof(tgnn.tgnn_params) == 19 * 8

@@ -1,0 +1,104 @@
+"""GPU parity of the edge-classification step (tgnn_train_step_edge_class) and of the evaluation pass (tgnn_eval_step,
+reciprocal rank among sampled negative destinations) against the oracle."""
+import numpy as np
+import pytest
+
+from gpu_common import GpuSide, OracleSide, batch_np, compare_state, compare_step, make_problem, rel_err, TOL
+from oracle import tgnn_oracle as O
+import synth
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("shape", [
+    dict(n_nodes=60, E=900, d_mem=16, d_time=8, d_edge=5, d_static=0, n_heads=2, k=5, batch=50, n_classes=7, n_true=2),
+    # the task's own widths (Sec. 4 "Datasets"): 56 classes, 6 of them true, 130 edge features
+    dict(n_nodes=300, E=1500, d_mem=100, d_time=100, d_edge=130, d_static=0, n_heads=2, k=10, batch=120, n_classes=56,
+         n_true=6),
+    dict(n_nodes=80, E=600, d_mem=132, d_time=12, d_edge=0, d_static=4, n_heads=2, k=4, batch=40, n_classes=1, n_true=1),
+])
+def test_edge_classification_steps_against_the_oracle(shape):
+    P = synth.custom_problem(**shape, seed=31)
+    d = P["d"]
+    G = GpuSide(P); Or = OracleSide(P)
+    n_steps = P["E"] // d.batch
+    for s in range(n_steps):
+        b = batch_np(P, s * d.batch, (s + 1) * d.batch)
+        assert b["labels"].shape == (d.batch, d.n_classes)
+        g = G.step([b], lr=0.05)
+        o = Or.step([b], lr=0.05, gpu=g)
+        assert g["logits"].shape == (d.batch, d.n_classes) and len(g["cnt"]) == 2 * d.batch
+        compare_step(g, o, label=f"edge classification C={d.n_classes} step {s}")
+    compare_state(G.state_np(), Or.states[0], label="edge classification state")
+    moved = False
+    for n, v in G.params.numpy().items():
+        assert v.shape == Or.p[n].shape and rel_err(v, Or.p[n]) <= 1e-4, n
+        moved |= n == "dec_w2" and np.abs(v - P["params"][n]).max() > 0
+    assert moved
+
+
+def test_edge_classification_two_replicas_and_entry_point_checks():
+    import torch
+    from paper_2307_07649_amd import tgnn
+    P = synth.custom_problem(n_nodes=70, E=800, d_mem=24, d_time=8, d_edge=6, d_static=0, n_heads=2, k=5, batch=40,
+                             n_classes=9, n_true=3, seed=5)
+    d = P["d"]
+    G = GpuSide(P, n_replicas=2); Or = OracleSide(P, n_replicas=2)
+    for s in range(4):
+        bs = [batch_np(P, (2 * s + r) * d.batch, (2 * s + r + 1) * d.batch - 7 * r) for r in range(2)]   # ragged second batch
+        g = G.step(bs, lr=0.02)
+        o = Or.step(bs, lr=0.02, gpu=g)
+        compare_step(g, o, label=f"edge classification 2 replicas step {s}")
+    # a context with a classification head refuses the link-prediction step, and the other way round
+    b = batch_np(P, 0, d.batch)
+    bl = [tgnn.Batch(b["src"], b["dst"], b["neg"], b["eid"], b["t"])]
+    with pytest.raises(tgnn.TgnnError):
+        G.ctx.tgnn_train_step(G.graph, G.state, G.params, G.grads, bl, lr=0.0, out_loss=G.loss)
+    P0 = synth.custom_problem(n_nodes=70, E=800, d_mem=24, d_time=8, d_edge=6, d_static=0, n_heads=2, k=5, batch=40, seed=5)
+    G0 = GpuSide(P0)
+    y = torch.zeros(d.batch, 9, device="cuda")
+    with pytest.raises(tgnn.TgnnError):
+        G0.ctx.tgnn_train_step_edge_class(G0.graph, G0.state, G0.params, G0.grads, bl, [y], lr=0.0, out_loss=G0.loss)
+
+
+@pytest.mark.parametrize("J,shape", [
+    (49, dict(n_nodes=200, E=1200, d_mem=32, d_time=16, d_edge=8, d_static=0, n_heads=2, k=10, batch=60)),
+    (49, dict(n_nodes=300, E=600, d_mem=100, d_time=100, d_edge=172, d_static=0, n_heads=2, k=10, batch=50)),
+    (1, dict(n_nodes=90, E=600, d_mem=20, d_time=6, d_edge=3, d_static=5, n_heads=1, k=4, batch=40)),
+])
+def test_evaluation_pass_against_the_oracle(J, shape):
+    """Scores of the true and the J sampled destinations against the oracle's forward pass (1e-4 of the largest score);
+    the ranks are an integer decision taken on floating-point scores, so both sides take it on the same scores: the
+    oracle's rank function applied to the GPU's own logits must reproduce the GPU's ranks exactly, and the sum of the
+    reciprocal ranks to fp32 rounding; memory after the pass as after training steps; parameters untouched."""
+    P = synth.custom_problem(**shape, seed=17)
+    d = P["d"]
+    rng = np.random.default_rng(3)
+    G = GpuSide(P, max_neg_sets=J); Or = OracleSide(P)
+    before = G.params.numpy()
+    n_steps = min(6, P["E"] // d.batch)
+    for s in range(n_steps):
+        b = batch_np(P, s * d.batch, (s + 1) * d.batch)
+        b["neg"] = rng.integers(0, d.n_nodes, (J, d.batch)).astype(np.int32)
+        if s == 2:
+            b["neg"][0] = b["dst"]                      # ties with the true destination: half a rank each
+        g = G.eval_step([b], J)
+        o = Or.step([b], lr=0.0)
+        ref = o["outs"][0]["logits"]
+        assert rel_err(g["logits"], ref) <= TOL, s
+        assert np.array_equal(g["winner"], o["winners"][0]) and np.array_equal(g["cnt"], o["outs"][0]["cnt"])
+        B = d.batch
+        rank, mrr = O.reciprocal_rank(g["logits"][:B].astype(np.float64), g["logits"][B:].reshape(J, B).astype(np.float64))
+        assert np.array_equal(g["rank"], rank.astype(np.float32)), s
+        assert abs(g["rr_sum"] / B - mrr) <= 1e-6
+        if s == 2:    # a negative destination that IS the true destination scores exactly the same: half a rank each
+            lg = g["logits"]
+            assert np.array_equal(lg[B:2 * B], lg[:B]) and (np.abs(g["rank"] * 2 % 2 - 1) < 1e-6).sum() > B // 2
+        # and against the oracle's own scores, wherever no two scores are within rounding of each other
+        o_rank, _ = O.reciprocal_rank(ref[:B], ref[B:].reshape(J, B))
+        gap = np.abs(ref[B:].reshape(J, B) - ref[:B][None, :])
+        safe = (gap > 1e-4 * np.abs(ref).max()).all(0) | (s == 2)
+        assert np.array_equal(g["rank"][safe & (s != 2)], o_rank[safe & (s != 2)].astype(np.float32))
+    compare_state(G.state_np(), Or.states[0], label="state after evaluation")
+    assert all(np.array_equal(before[n], v) for n, v in G.params.numpy().items())
+    assert not any(np.any(v) for v in G.grads.numpy().values())
