@@ -423,6 +423,96 @@ def run_epoch_parallel(tgnn, torch, P, args, J):
     return res
 
 
+def run_edge_class(tgnn, torch, args, n_events=2_000_000, n_classes=56, n_true=6, d_edge=130):
+    """tgnn_train_step_edge_class on the C4 graph recipe set up as the paper's own task on that graph (Sec. 4
+    "Datasets"): 130 edge features, a 56-class head with 6 true classes per event, no negative destinations (roots
+    [src | dst]).  First n_events events of the recipe; edge features and class targets are drawn on the GPU (seeded)."""
+    import synth
+    from synth.device import device_normal_table
+    P = synth.make_problem("C4", n_events=n_events, with_efeat=False, with_labels=False, d_edge=d_edge, n_classes=n_classes)
+    d = P["d"]
+    efeat = device_normal_table(P["E"], d.d_edge, seed=synth.CONFIGS["C4"]["seed"] + 1000)
+    ctx = tgnn.Context(d.n_nodes, d.d_mem, d.d_time, d.d_edge, d.d_static, d.n_heads, d.k, d.batch, n_replicas=1,
+                       flags=tgnn.FLAG_OVERWRITE_GRADS, n_classes=n_classes)
+    graph = tgnn.Graph(P["src"], P["dst"], P["ts"], d.n_nodes, efeat)
+    state = tgnn.State(d.n_nodes, d.d_mem, 1, P["static"])
+    params = tgnn.Params.from_numpy(P["params"]); grads = tgnn.Params.zeros_like(params)
+    loss = torch.zeros(4, device="cuda")
+    spans = [sp for sp in synth.batches_of(P["E"], d.batch) if sp[1] - sp[0] == d.batch]
+    n_steps = min(args.steps, len(spans) - args.warmup)
+    n_used = (args.warmup + n_steps) * d.batch
+    gen = torch.Generator(device="cuda"); gen.manual_seed(synth.CONFIGS["C4"]["seed"] + 5000)
+    # n_true distinct classes per event with a skewed class popularity (largest of exponential races)
+    keys = torch.log(1.0 / (1.0 + torch.arange(n_classes, device="cuda", dtype=torch.float32)))[None, :] \
+        - torch.log(-torch.log(torch.rand(n_used, n_classes, generator=gen, device="cuda").clamp_min(1e-12)))
+    labels = torch.zeros(n_used, n_classes, device="cuda")
+    labels.scatter_(1, keys.topk(n_true, dim=1).indices, 1.0)
+    del keys
+    dsrc, ddst = (torch.from_numpy(np.ascontiguousarray(P[n], np.int32)).cuda() for n in ("src", "dst"))
+    deid = torch.arange(P["E"], dtype=torch.int32, device="cuda")
+    dts = torch.from_numpy(np.ascontiguousarray(P["ts"], np.float64)).cuda()
+    batches = [tgnn.Batch(dsrc[lo:hi], ddst[lo:hi], ddst[lo:hi], deid[lo:hi], dts[lo:hi])      # (neg is not read)
+               for (lo, hi) in spans[:args.warmup + n_steps]]
+    ys = [labels[lo:hi] for (lo, hi) in spans[:args.warmup + n_steps]]
+    torch.cuda.synchronize()
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        for b, y in zip(batches[:args.warmup], ys):
+            ctx.tgnn_train_step_edge_class(graph, state, params, grads, [b], [y], lr=args.lr, out_loss=loss)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for b, y in zip(batches[args.warmup:], ys[args.warmup:]):
+            ctx.tgnn_train_step_edge_class(graph, state, params, grads, [b], [y], lr=args.lr, out_loss=loss)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+    res = {"workload": f"C4 graph recipe, first {P['E']} events, d_edge {d.d_edge}, {n_classes}-class head with {n_true} true "
+                       f"classes per event, batch {d.batch}, roots per step {2 * d.batch}, SGD lr {args.lr}",
+           "steps": n_steps, "ms_per_step": dt / n_steps * 1e3, "events_per_s": n_steps * d.batch / dt,
+           "final_loss": float(loss[0].item())}
+    ctx.close()
+    return res
+
+
+def run_evaluation(tgnn, torch, P, args, J=49):
+    """tgnn_eval_step on configuration P: the forward half with J sampled negative destinations per event, the rank of
+    the true destination among them, the memory write-back (Sec. 4: 49 negatives, mean reciprocal rank)."""
+    import synth
+    d = P["d"]
+    ctx = tgnn.Context(d.n_nodes, d.d_mem, d.d_time, d.d_edge, d.d_static, d.n_heads, d.k, d.batch, n_replicas=1,
+                       max_neg_sets=J)
+    graph = tgnn.Graph(P["src"], P["dst"], P["ts"], d.n_nodes, P["efeat"])
+    state = tgnn.State(d.n_nodes, d.d_mem, 1, P["static"])
+    params = tgnn.Params.from_numpy(P["params"])
+    spans = [sp for sp in synth.batches_of(P["E"], d.batch) if sp[1] - sp[0] == d.batch]
+    n_steps = min(args.steps, len(spans) - args.warmup)
+    negs = np.stack([synth.gen_negatives(P["name"], P["E"], group=g) for g in range(J)])       # [J, E]
+    dsrc, ddst = (torch.from_numpy(np.ascontiguousarray(P[n], np.int32)).cuda() for n in ("src", "dst"))
+    deid = torch.arange(P["E"], dtype=torch.int32, device="cuda")
+    dts = torch.from_numpy(np.ascontiguousarray(P["ts"], np.float64)).cuda()
+    batches = [tgnn.Batch(dsrc[lo:hi], ddst[lo:hi], torch.from_numpy(np.ascontiguousarray(negs[:, lo:hi]).reshape(-1)).cuda(),
+                          deid[lo:hi], dts[lo:hi]) for (lo, hi) in spans[:args.warmup + n_steps]]
+    rank = torch.empty(d.batch, device="cuda"); rr = torch.zeros(1, device="cuda")
+    torch.cuda.synchronize()
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        for b in batches[:args.warmup]:
+            ctx.tgnn_eval_step(graph, state, params, [b], J, rank, rr)
+        torch.cuda.synchronize()
+        rr.zero_()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for b in batches[args.warmup:]:
+            ctx.tgnn_eval_step(graph, state, params, [b], J, rank, rr)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+    res = {"workload": f"{P['name']}, {J} sampled negative destinations per event (roots per step: {(2 + J) * d.batch}), "
+                       "forward half + ranks + memory write-back, untrained weights",
+           "n_neg": J, "steps": n_steps, "ms_per_step": dt / n_steps * 1e3, "events_per_s": n_steps * d.batch / dt,
+           "scored_pairs_per_s": n_steps * d.batch * (1 + J) / dt, "mean_reciprocal_rank": float(rr.item()) / (n_steps * d.batch)}
+    ctx.close()
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -467,14 +557,20 @@ def main():
     head = "C4" if args.config == "all" else args.config
     others = [c for c in ("C0", "C1", "C2", "C3", "C5") if args.config == "all"]
     configs = {}
-    epoch_parallel = None
+    epoch_parallel = evaluation = edge_class = None
     for name in others:
         P = build_problem(name, None)
         configs[name] = run_config(tgnn, torch, P, args, detail=False)
         print(f"bench.py: {name} {configs[name]['events_per_s']:.0f} events/s", file=sys.stderr, flush=True)
         if name == "C1":
+            evaluation = run_evaluation(tgnn, torch, P, args)
+            print(f"bench.py: C1 evaluation {evaluation['events_per_s']:.0f} events/s", file=sys.stderr, flush=True)
             epoch_parallel = run_epoch_parallel(tgnn, torch, P, args, 4)
         del P
+    if args.config == "all":
+        edge_class = run_edge_class(tgnn, torch, args)
+        print(f"bench.py: edge classification {edge_class['events_per_s']:.0f} events/s", file=sys.stderr, flush=True)
+        torch.cuda.empty_cache()
     P = build_problem(head, args.events)
     print(f"bench.py: {head} inputs ready", file=sys.stderr, flush=True)
     res = run_config(tgnn, torch, P, args, detail=True)
@@ -511,6 +607,8 @@ def main():
         "step_model": res["step_model"],
         "configs": configs,
         "epoch_parallel": epoch_parallel,
+        "evaluation": evaluation,
+        "edge_classification": edge_class,
         "stages_us": res.get("stages_us"), "stages_us_note": res.get("stages_us_note"),
     }
     if not args.no_cpu_baseline:
