@@ -466,7 +466,10 @@ void gemm_nt(const float* A, int lda, const float* B, int ldb, const float* bias
 // The bias gradient rides along as column K of A, which the loader replaces by ones.
 // ------------------------------------------------------------------------------------------------
 constexpr int TT = 64;        // bulk tile edge
-constexpr int TN_W = 8;       // wavefronts per workgroup
+#ifndef TGNN_TN_WAVES
+#define TGNN_TN_WAVES 8
+#endif
+constexpr int TN_W = TGNN_TN_WAVES;   // wavefronts per workgroup
 constexpr int TN_AHEAD = 4;   // 4-row steps whose loads a wavefront keeps in flight
 constexpr int TN_ROWS = 32;   // row chunks are multiples of this
 

@@ -162,7 +162,7 @@ void head_fill(tgnn_ctx* ctx, const tgnn_graph* g, int n_roots, const tgnn_param
   h.sa.winkey = w.winkey; h.sa.bad_ids = w.bad_ids;
   h.sa.uq = UniqPtrs{w.utag, w.epoch, w.uidx, w.ucount, w.ulist, w.ucnt};
   h.sample_blocks = (n_roots + SAMPLE_WAVES - 1) / SAMPLE_WAVES;
-  h.pro_bx = 12;   // blocks of 1024 threads per grid row of the prologue (C1: 12 measured best of 2 .. 48; 24: +1.6 us per step)
+  h.pro_bx = 12 * 16 / SAMPLE_WAVES;   // blocks of 1024 threads per grid row of the prologue (C1: 12 measured best of 2 .. 48; 24: +1.6 us per step)
   prologue_fill(ctx, p, bs, sgd, zero, loss, h.pa);
   h.pa.head_of_step = 1;
   h.pa.ucount_next = w.ucount_pair + (w.ucount == w.ucount_pair ? 1 : 0);

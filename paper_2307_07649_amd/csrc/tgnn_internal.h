@@ -460,7 +460,10 @@ struct HeadArgs {
   int sample_blocks, pro_bx;   // pro_bx: prologue blocks per grid row
   PrologueArgs pa;
 };
-constexpr int SAMPLE_WAVES = 16;   // roots per block in the first launch of a step
+#ifndef TGNN_SAMPLE_WAVES
+#define TGNN_SAMPLE_WAVES 16
+#endif
+constexpr int SAMPLE_WAVES = TGNN_SAMPLE_WAVES;   // roots per block in the first launch of a step
 void head_fill(tgnn_ctx* ctx, const tgnn_graph* g, int n_roots, const tgnn_params* p, const BatchSet* bs,
                const struct SgdSet* sgd, const struct SgdSet* zero, float* loss, HeadArgs& h);
 dim3 head_grid(const HeadArgs& h);
