@@ -49,7 +49,7 @@ N_STAGES = 20
 
 
 # ---------------------------------------------------------------------------------------------------------
-# work models (documented in the design doc): what the method asks for per slot, and what the library executes
+# work models: what the method asks for per slot, and what the library executes after its exact shortcuts
 # ---------------------------------------------------------------------------------------------------------
 def flops_per_slot_model(d, B):
     """The method as stated: UPDT for every one of the 3B(1+k) slots, unsplit projections; fwd + bwd ~ 3x fwd."""

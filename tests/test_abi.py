@@ -109,3 +109,17 @@ def test_generators_are_seeded_and_shaped_like_the_configs():
     assert synth.gen_static("C1") is None
     g4 = synth.gen_graph("C4", n_events=50_000)
     assert np.all(g4["src"] != g4["dst"]) and abs(g4["ts"][-1] - 1.4e5) < 1e-6 and g4["efeat"].shape[1] == 186
+
+
+def test_create_rejects_bad_head_and_negative_set_counts(tgnn):
+    """n_classes and max_neg_sets are validated before anything touches a device."""
+    import ctypes as C
+    for field, bad in (("n_classes", -1), ("n_classes", 257), ("max_neg_sets", 65), ("max_neg_sets", -1)):
+        kw = dict(n_nodes=10, d_mem=8, d_time=4, d_edge=2, d_static=0, n_heads=2, k=3, max_batch=4, n_replicas=1,
+                  dt_source=0, flags=0, max_neg_sets=1, n_classes=0)
+        kw[field] = bad
+        cfg = tgnn.tgnn_config(*[kw[n] for n, _ in tgnn.tgnn_config._fields_])
+        h = C.c_void_p()
+        rc = tgnn._lib.tgnn_create(C.byref(cfg), C.byref(h))
+        assert rc == -4 and not h.value, (field, bad, rc)          # TGNN_E_OUT_OF_RANGE
+        assert field in tgnn._lib.tgnn_last_error().decode()
