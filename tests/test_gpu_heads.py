@@ -134,3 +134,28 @@ def test_empty_batches_and_argument_errors():
     assert float(rr[0]) == 2.5 and not rank.any()
     with pytest.raises(tgnn.TgnnError):          # the evaluation pass is link prediction: not on a classification context
         G.ctx.tgnn_eval_step(G.graph, G.state, G.params, [full], 1, rank, rr)
+
+
+def test_training_and_evaluation_steps_alternate_on_one_context():
+    """Train, evaluate, train ... on one context and one stream (each kind of step replays its own captured graph): the
+    state an evaluation step leaves is the one the next training step starts from, on both sides."""
+    P = synth.custom_problem(n_nodes=120, E=1200, d_mem=32, d_time=16, d_edge=8, d_static=0, n_heads=2, k=6, batch=60, seed=23)
+    d = P["d"]
+    J = 5
+    rng = np.random.default_rng(1)
+    G = GpuSide(P, max_neg_sets=J); Or = OracleSide(P)
+    for s in range(12):
+        b = batch_np(P, s * d.batch, (s + 1) * d.batch)
+        if s % 3 == 1:
+            b["neg"] = rng.integers(0, d.n_nodes, (J, d.batch)).astype(np.int32)
+            g = G.eval_step([b], J)
+            o = Or.step([b], lr=0.0)
+            assert rel_err(g["logits"], o["outs"][0]["logits"]) <= TOL, s
+            assert np.array_equal(g["winner"], o["winners"][0])
+        else:
+            g = G.step([b], lr=0.05)
+            o = Or.step([b], lr=0.05, gpu=g)
+            compare_step(g, o, label=f"train/eval alternating step {s}")
+    compare_state(G.state_np(), Or.states[0], label="train/eval alternating")
+    for n, v in G.params.numpy().items():
+        assert rel_err(v, Or.p[n]) <= 1e-4, n
