@@ -332,3 +332,34 @@ def test_co_trained_static_memory_against_the_oracle(nrep):
     before = G.state.stat.clone()
     G.step([batch_np(P, 0, d.batch)], lr=0.0, want=False)
     assert torch.equal(before, G.state.stat)
+
+
+@pytest.mark.parametrize("seed", list(range(40)))
+def test_random_shapes_against_the_oracle(seed):
+    """Seeded random widths, head counts, neighbour counts, batch sizes, negative-set counts and launch flags inside the
+    library's limits (including k up to 32, one-column time encodings, no edge features, widths that are not multiples of
+    anything): four consecutive steps each, every quantity of compare_step."""
+    rng = np.random.default_rng(1000 + seed)
+    H = int(rng.choice([1, 1, 2, 2, 3, 4, 5]))
+    d_mem = H * int(rng.integers(1, max(2, 160 // H)))
+    k = int(rng.choice([1, 2, 3, 5, 7, 10, 10, 12, 17, 32]))
+    while 16 * (d_mem + k * (d_mem + 1) + 2 * H * k) > 64 * 1024:      # the library's limit on k * d_mem (tgnn_create)
+        k -= 1
+    shape = dict(n_nodes=int(rng.integers(12, 220)), E=0, d_mem=d_mem, d_time=int(rng.choice([1, 2, 5, 16, 33, 100, 140])),
+                 d_edge=int(rng.choice([0, 1, 3, 16, 64, 172, 210])), d_static=int(rng.choice([0, 0, 1, 7, 20])),
+                 n_heads=H, k=k, batch=int(rng.integers(3, 90)))
+    shape["E"] = shape["batch"] * 5 + int(rng.integers(0, shape["batch"]))
+    J = int(rng.choice([1, 1, 1, 2, 3]))
+    flags = int(rng.choice([0, 0, 8, 16, 4]))
+    P = custom_problem(**shape, seed=seed, ties=bool(rng.integers(0, 2)), self_loops=float(rng.choice([0.0, 0.1])),
+                       neg_is_dst=float(rng.choice([0.0, 0.1])))
+    d = P["d"]
+    G = GpuSide(P, flags=flags, max_neg_sets=J); Or = OracleSide(P)
+    for s in range(4):
+        b = batch_np(P, s * d.batch, (s + 1) * d.batch)
+        if J > 1:
+            b["neg"] = rng.integers(0, d.n_nodes, (J, d.batch)).astype(np.int32)
+        g = G.step([b], lr=0.03, n_neg_sets=J)
+        o = Or.step([b], lr=0.03, gpu=g)
+        compare_step(g, o, label=f"random shape {seed} {shape} J={J} flags={flags} step {s}")
+    compare_state(G.state_np(), Or.states[0], label=f"random shape {seed}")
