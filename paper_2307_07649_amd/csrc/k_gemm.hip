@@ -473,9 +473,11 @@ constexpr int TN_W = TGNN_TN_WAVES;   // wavefronts per workgroup
 constexpr int TN_AHEAD = 4;   // 4-row steps whose loads a wavefront keeps in flight
 constexpr int TN_ROWS = 32;   // row chunks are multiples of this
 
-// A length is cut into 64-wide pieces plus at most two narrower ones (32 and/or 16 wide) for the remainder.
+// A length is cut into 64-wide pieces plus one narrower one (16, 32 or again 64 wide) for the remainder.  (With
+// TGNN_TN_SPLIT48 a remainder of 33 .. 48 becomes a 32- and a 16-wide piece instead of a padded 64-wide one: fewer
+// MFMAs, one more tile; measured on MI355X the extra tile costs slightly more than the padding.)
 #ifndef TGNN_TN_SPLIT48
-#define TGNN_TN_SPLIT48 1
+#define TGNN_TN_SPLIT48 0
 #endif
 __host__ __device__ inline int tn_pieces(int len) {
   const int r = len % TT;
