@@ -225,7 +225,13 @@ __device__ __forceinline__ void softmax_heads(float* sa, int HK, int k, int c, i
   }
 }
 
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) void fattn_fwd_fast_kernel(FusedAttn a) {
+// Wavefronts per SIMD the forward kernel is compiled for: with 4 (128 registers) it spills nine registers to scratch
+// memory and measured 4 to 19 % slower on MI355X than with 3 (no spill); the kernel is bound by instruction issue,
+// not by the number of loads in flight.
+#ifndef TGNN_FATTN_FWD_WAVES
+#define TGNN_FATTN_FWD_WAVES 3
+#endif
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(TGNN_FATTN_FWD_WAVES, TGNN_FATTN_FWD_WAVES))) void fattn_fwd_fast_kernel(FusedAttn a) {
   extern __shared__ float lds[];
   int block = blockIdx.x;
   if (a.fill.ucnt != nullptr) {   // the first blocks are passengers: the fill pass of the slot sort
@@ -370,7 +376,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
   store_head_row(a, a.Zp + (size_t)r * a.ldz, lane, zp);
 }
 
+#ifdef TGNN_FATTN_BWD_WAVES
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(TGNN_FATTN_BWD_WAVES, TGNN_FATTN_BWD_WAVES))) void fattn_bwd_fast_kernel(FusedAttn a) {
+#else
 __global__ __launch_bounds__(256) void fattn_bwd_fast_kernel(FusedAttn a) {
+#endif
   extern __shared__ float lds[];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int r = blockIdx.x * 4 + wave;

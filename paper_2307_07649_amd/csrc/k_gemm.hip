@@ -395,7 +395,10 @@ static int nt_tile_blocks(int M, int n_store) {
   const int nb = (n_store + 15) / 16;
   int best = 1;
   if (M > 4096 && M <= 65536) {
-    best = 2;
+#ifndef TGNN_NT_MID_TILE
+#define TGNN_NT_MID_TILE 2
+#endif
+    best = TGNN_NT_MID_TILE;
   } else if (M > 65536) {
     float best_cost = 1e30f;
     static const int cand[] = {5, 4, 7, 2};
