@@ -34,7 +34,10 @@ __device__ __forceinline__ float slot_grad(const SlotGrads& g, int sl, int c) {
   return g.prob[(size_t)r * g.H * g.k + (cc / g.dh) * g.k + j] * g.dOmat[(size_t)r * g.ldh + cc];
 }
 
-constexpr int SEG_CHUNK = 16;
+#ifndef TGNN_SEG_CHUNK
+#define TGNN_SEG_CHUNK 16
+#endif
+constexpr int SEG_CHUNK = TGNN_SEG_CHUNK;
 // SPAN: consecutive chunks per wavefront (1, 2 or 4).  The accumulators of a run of equal rows carry over from chunk
 // to chunk, so a node with thousands of slots (a tenth of a step's slots sit on one node of a power-law graph) costs
 // one atomic row update per SPAN chunks.  Measured on MI355X it does not pay: the launch is bound by the chain of
