@@ -1,6 +1,7 @@
 // Root construction and most-recent-neighbour sampling (Sec. 2.1 "most recent neighbors"; k = 10 in Sec. 4)
-// on the temporal CSR: one wavefront per query, a 64-ary search over the node's ascending time array
-// followed by one k-wide read of the newest entries below the query time.
+// on the temporal CSR: a group of 64 or 16 lanes per query, a search over the node's ascending time array with as
+// many probes per level as the group has lanes, followed by one k-wide read of the newest entries below the query
+// time.
 #include <string.h>
 
 #include "tgnn_internal.h"
@@ -8,94 +9,107 @@
 
 namespace tgnn {
 
-// FUSED: the query of wave r is root r of the step's batches ([src | dst | neg] per batch); the wave also
+// FUSED: the query of lane group r is root r of the step's batches ([src | dst | neg] per batch); the group also
 // records the root (node, time, slot ids), marks the write-back arbitration word of a positive endpoint
 // (last-event-wins: largest key survives) and claims rows for the root and its neighbours.  `bs` are the batch
 // descriptors (read from the kernel's argument block), `ep` the epoch of the step.
 // Otherwise the queries are the caller's (node, t) arrays.
-// `block` is the calling block's number among the sampling blocks; one wavefront per query.
-template <bool FUSED>
+// `block` is the calling block's number among the sampling blocks.
+// G lanes per query (64 or 16): a query is a chain of eight to ten dependent memory round trips (batch arrays,
+// list bounds, G-ary search, the k newest entries, row claim) during which most lanes have nothing to do, and a
+// compute unit holds at most 32 wavefronts: with a wavefront per query a 12,000-root step needs one and a half
+// rounds of them.  Four queries per wavefront (G = 16, k < 16) put all roots of such a step in flight at once; the
+// search takes one level more on lists of a few thousand entries.
+template <bool FUSED, int G>
 __device__ __forceinline__ void sample_block(const SampleArgs& a, const BatchSet& bs, unsigned long long ep, int block) {
   __shared__ int blk_count, blk_base;
+  constexpr int QW = 64 / G;   // queries per wavefront
   const UniqPtrs& uq = a.uq;
   const int N = a.N, n_roots = a.n_roots, k = a.k;
   const int lane = threadIdx.x & 63;
-  // (uniform per wavefront: the batch descriptors are then read with scalar loads)
-  const int r = block * (blockDim.x >> 6) + __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-  const bool active = r < n_roots;   // per wave; in the fused form idle waves still join the block barriers
-  if (!FUSED && !active) return;
+  const int grp = lane / G, gl = lane - grp * G;        // lane group and lane in it
+  const unsigned long long gmask = G == 64 ? ~0ull : ((1ull << (G & 63)) - 1ull) << (grp * G);
+  const int r = (block * (blockDim.x >> 6) + (int)(threadIdx.x >> 6)) * QW + grp;
+  const bool active = r < n_roots;   // per group; in the fused form idle groups still join the block barriers
+  if (!FUSED && G == 64 && !active) return;
   if (FUSED) {
     if (threadIdx.x == 0) blk_count = 0;
     __syncthreads();
   }
   int claim = -1;   // (replica, node) this lane wants a row for
-  if (active) {
-    int node, rep_base = 0, root_gid = -1;
-    double t;
-    if (FUSED) {
-      int b = 0;
-      const int n_roles = 2 + bs.nneg;
-      while (b + 1 < bs.nb && r >= n_roles * bs.b[b + 1].ev_off) ++b;
-      const int ev_off = bs.b[b].ev_off, n = bs.b[b].n;
-      const int local = r - n_roles * ev_off;
-      const int role = local / n, i = local - role * n;
-      const int32_t* nodes = role == 0 ? bs.b[b].src : role == 1 ? bs.b[b].dst : bs.b[b].neg + (size_t)(role - 2) * n;
-      node = nodes[i];
-      t = bs.b[b].t[i];
-      // an id outside [0, N) in the caller's batch arrays: the root is computed as node 0 (every index stays in
-      // range), takes no part in the write-back, and is counted for the caller to see
-      const bool bad = node < 0 || node >= N;
-      if (bad) node = 0;
-      rep_base = bs.b[b].replica * N;
-      root_gid = rep_base + node;
-      if (lane == 0) {
-        a.root_node[r] = node;
-        a.root_t[r] = t;
-        a.slot_gid[r] = root_gid;
-        a.slot_node[r] = node;
-        if (bad) atomicAdd(a.bad_ids, 1);
-        else if (role < 2) atomicMax(a.winkey + root_gid, wb_key(ep, ev_off + i, role));
+  {
+    int node = -1, rep_base = 0, root_gid = -1;
+    double t = 0.0;
+    if (active) {
+      if (FUSED) {
+        int b = 0;
+        const int n_roles = 2 + bs.nneg;
+        while (b + 1 < bs.nb && r >= n_roles * bs.b[b + 1].ev_off) ++b;
+        const int ev_off = bs.b[b].ev_off, n = bs.b[b].n;
+        const int local = r - n_roles * ev_off;
+        const int role = local / n, i = local - role * n;
+        const int32_t* nodes = role == 0 ? bs.b[b].src : role == 1 ? bs.b[b].dst : bs.b[b].neg + (size_t)(role - 2) * n;
+        node = nodes[i];
+        t = bs.b[b].t[i];
+        // an id outside [0, N) in the caller's batch arrays: the root is computed as node 0 (every index stays in
+        // range), takes no part in the write-back, and is counted for the caller to see
+        const bool bad = node < 0 || node >= N;
+        if (bad) node = 0;
+        rep_base = bs.b[b].replica * N;
+        root_gid = rep_base + node;
+        if (gl == 0) {
+          a.root_node[r] = node;
+          a.root_t[r] = t;
+          a.slot_gid[r] = root_gid;
+          a.slot_node[r] = node;
+          if (bad) atomicAdd(a.bad_ids, 1);
+          else if (role < 2) atomicMax(a.winkey + root_gid, wb_key(ep, ev_off + i, role));
+        }
+      } else {
+        node = a.q_node[r];
+        t = a.q_t[r];
       }
-    } else {
-      node = a.q_node[r];
-      t = a.q_t[r];
     }
     long long base = 0, lo = 0, hi = 0;
-    if (node >= 0 && node < N) {
+    if (active && node >= 0 && node < N) {
       base = a.indptr[node];
       lo = base;
       hi = a.indptr[node + 1];
     }
     // invariant: entries before lo are < t; entry hi (if inside the list) is >= t; answer in [lo, hi]
-    while (hi - lo > 64) {
-      const long long step = (hi - lo + 63) / 64;
-      const long long idx = lo + (long long)(lane + 1) * step - 1;
-      const bool below = idx < hi && a.g_ts[idx] < t;
-      const int nb = __popcll(__ballot(below));
-      const long long nlo = lo + (long long)nb * step;
-      const long long nhi = lo + (long long)(nb + 1) * step - 1;
-      lo = nlo;
-      hi = nhi < hi ? nhi : hi;
+    // (the loop runs while any group of the wavefront still has more than G candidates; a group that is done idles)
+    while (__any(hi - lo > G)) {
+      const bool more = hi - lo > G;
+      const long long step = (hi - lo + G - 1) / G;
+      const long long idx = lo + (long long)(gl + 1) * step - 1;
+      const bool below = more && idx < hi && a.g_ts[idx] < t;
+      const int nb = __popcll(__ballot(below) & gmask);
+      if (more) {
+        const long long nlo = lo + (long long)nb * step;
+        const long long nhi = lo + (long long)(nb + 1) * step - 1;
+        lo = nlo;
+        hi = nhi < hi ? nhi : hi;
+      }
     }
     {
-      const long long idx = lo + lane;
+      const long long idx = lo + gl;
       const bool below = idx < hi && a.g_ts[idx] < t;
-      lo += __popcll(__ballot(below));
+      lo += __popcll(__ballot(below) & gmask);
     }
     const long long pos = lo;  // first entry with time >= t
     const long long avail = pos - base;
     const int cnt = avail < k ? (int)avail : k;
-    if (lane == 0) a.out_cnt[r] = cnt;
+    if (active && gl == 0) a.out_cnt[r] = cnt;
     int nb = -1, ei = -1;
     double ts = 0.0;
-    if (lane < cnt) {
-      const long long idx = pos - 1 - lane;
+    if (active && gl < cnt) {
+      const long long idx = pos - 1 - gl;
       nb = a.g_nbr[idx];
       ei = a.g_eid[idx];
       ts = a.g_ts[idx];
     }
-    if (lane < k) {
-      const size_t o = (size_t)r * k + lane;
+    if (active && gl < k) {
+      const size_t o = (size_t)r * k + gl;
       a.out_nbr[o] = nb;
       a.out_eid[o] = ei;
       a.out_ts[o] = ts;
@@ -104,8 +118,8 @@ __device__ __forceinline__ void sample_block(const SampleArgs& a, const BatchSet
         a.slot_node[(size_t)n_roots + o] = nb;
       }
     }
-    // lanes 0 .. k-1 claim their neighbour, lane k (k < 64) the root itself
-    if (FUSED) claim = lane < k ? (nb >= 0 ? rep_base + nb : -1) : (lane == k ? root_gid : -1);
+    // lanes 0 .. k-1 of the group claim their neighbour, lane k (k < G) the root itself
+    if (FUSED && active) claim = gl < k ? (nb >= 0 ? rep_base + nb : -1) : (gl == k ? root_gid : -1);
   }
   if (FUSED) {
     // Row numbers for the nodes claimed first by this block: winners are counted per wave (ballot), per block
@@ -130,13 +144,14 @@ __device__ __forceinline__ void sample_block(const SampleArgs& a, const BatchSet
 }
 
 // plain sampling of the caller's queries
-__global__ __launch_bounds__(256) void sample_kernel(SampleArgs a, BatchSet none) { sample_block<false>(a, none, 0ull, blockIdx.x); }
+__global__ __launch_bounds__(256) void sample_kernel(SampleArgs a, BatchSet none) { sample_block<false, 64>(a, none, 0ull, blockIdx.x); }
 
 // The first launch of a training step: sampling blocks, then the prologue's blocks (see HeadArgs).
-__global__ __launch_bounds__(1024) void step_head_kernel(HeadArgs h) {
+__global__ __launch_bounds__(64 * SAMPLE_WAVES) void step_head_kernel(HeadArgs h) {
   if ((int)blockIdx.x < h.sample_blocks) {
     // the epoch counter still holds the previous step's value: nothing writes it during this launch
-    sample_block<true>(h.sa, h.pa.bs, *h.sa.uq.epoch + 1ull, blockIdx.x);
+    if (h.sa.k < 16) sample_block<true, 16>(h.sa, h.pa.bs, *h.sa.uq.epoch + 1ull, blockIdx.x);
+    else sample_block<true, 64>(h.sa, h.pa.bs, *h.sa.uq.epoch + 1ull, blockIdx.x);
     return;
   }
   const int pb = blockIdx.x - h.sample_blocks;
@@ -161,7 +176,8 @@ void head_fill(tgnn_ctx* ctx, const tgnn_graph* g, int n_roots, const tgnn_param
   h.sa.root_node = w.root_node; h.sa.root_t = w.root_t; h.sa.slot_gid = w.slot_gid; h.sa.slot_node = w.slot_node;
   h.sa.winkey = w.winkey; h.sa.bad_ids = w.bad_ids;
   h.sa.uq = UniqPtrs{w.utag, w.epoch, w.uidx, w.ucount, w.ulist, w.ucnt};
-  h.sample_blocks = (n_roots + SAMPLE_WAVES - 1) / SAMPLE_WAVES;
+  const int per_block = SAMPLE_WAVES * (d.k < 16 ? 4 : 1);   // four roots per wavefront when a lane group of 16 holds k + 1 claims
+  h.sample_blocks = (n_roots + per_block - 1) / per_block;
   h.pro_bx = 12 * 16 / SAMPLE_WAVES;   // blocks of 1024 threads per grid row of the prologue (C1: 12 measured best of 2 .. 48; 24: +1.6 us per step)
   prologue_fill(ctx, p, bs, sgd, zero, loss, h.pa);
   h.pa.head_of_step = 1;

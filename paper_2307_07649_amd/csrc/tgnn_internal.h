@@ -434,7 +434,7 @@ struct UniqPtrs {
   int32_t *uidx, *ucount, *ulist, *ucnt;
 };
 // The first launch of a training step: roots of every batch (node, time, slot ids), write-back arbitration marks,
-// neighbour sampling and row claims (blocks 0 .. sample_blocks - 1, one wavefront per root, 1024 threads per
+// neighbour sampling and row claims (blocks 0 .. sample_blocks - 1, a lane group of 16 or 64 per root, 64 * SAMPLE_WAVES threads per
 // block), and, in the blocks after those, everything the prologue does (it depends on nothing the sampler does
 // and the other way round: the sampler takes the batch descriptors from the argument block and uses epoch + 1,
 // which a later launch makes official).
@@ -461,9 +461,9 @@ struct HeadArgs {
   PrologueArgs pa;
 };
 #ifndef TGNN_SAMPLE_WAVES
-#define TGNN_SAMPLE_WAVES 16
+#define TGNN_SAMPLE_WAVES 8
 #endif
-constexpr int SAMPLE_WAVES = TGNN_SAMPLE_WAVES;   // roots per block in the first launch of a step
+constexpr int SAMPLE_WAVES = TGNN_SAMPLE_WAVES;   // wavefronts per block in the first launch of a step (four roots each when k < 16)
 void head_fill(tgnn_ctx* ctx, const tgnn_graph* g, int n_roots, const tgnn_params* p, const BatchSet* bs,
                const struct SgdSet* sgd, const struct SgdSet* zero, float* loss, HeadArgs& h);
 dim3 head_grid(const HeadArgs& h);
