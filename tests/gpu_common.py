@@ -96,7 +96,8 @@ class GpuSide:
         self.loss = torch.zeros(4, device="cuda")
 
     def step(self, batches, replicas=None, lr=0.0, want=True, n_neg_sets=1):
-        """n_neg_sets > 1: every batch's "neg" holds that many sets, [J, n] (tgnn_train_step_epoch_parallel).
+        """want: True = every output; "gates" = only the two ReLU layers' outputs (what OracleSide.step(gpu=...) reads);
+        False = nothing.  n_neg_sets > 1: every batch's "neg" holds that many sets, [J, n] (tgnn_train_step_epoch_parallel).
         Batches with "labels" ([n, C]): tgnn_train_step_edge_class (roots [src | dst], logits [sum n, C])."""
         torch, tgnn = self.torch, self.tgnn
         C = self.d.n_classes
@@ -127,6 +128,12 @@ class GpuSide:
         if not want:
             return None
         R = (2 + J) * tot; k = self.d.k
+        if want == "gates":     # only what OracleSide.step needs to take the GPU's ReLU decisions
+            dbg = self.ctx.tgnn_debug_read
+            out = dict(z=dbg(6, torch.empty(R, self.d.d_mem, device="cuda")).cpu().numpy(),
+                       h1=dbg(7, torch.empty(max(1 + J, 1) * tot, self.d.d_mem, device="cuda")).cpu().numpy())
+            torch.cuda.synchronize()
+            return out
         out = dict(loss=float(self.loss[0].item()), logits=logits.cpu().numpy().reshape((tot, C) if C else (-1,)),
                    winner=win.cpu().numpy(), grads=self.grads.numpy())
         dbg = self.ctx.tgnn_debug_read

@@ -19,7 +19,8 @@ def run(P, n_steps, lr, check_at, first=0):
         lo = (first + s) * d.batch; hi = min(lo + d.batch, P["E"])
         b = batch_np(P, lo, hi)
         want = s in check_at
-        g = G.step([b], lr=lr, want=want)
+        # (training on: the oracle takes the GPU's ReLU decisions on every step, see OracleSide.step)
+        g = G.step([b], lr=lr, want=True if want else ("gates" if lr else False))
         o = Or.step([b], lr=lr, gpu=g)
         if want:
             out[s] = compare_step(g, o, label=f"{P['name']} lr {lr} step {first + s}")
