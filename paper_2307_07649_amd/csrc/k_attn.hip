@@ -225,11 +225,12 @@ __device__ __forceinline__ void softmax_heads(float* sa, int HK, int k, int c, i
   }
 }
 
-// Wavefronts per SIMD the forward kernel is compiled for: with 4 (128 registers) it spills nine registers to scratch
-// memory and measured 4 to 19 % slower on MI355X than with 3 (no spill); the kernel is bound by instruction issue,
-// not by the number of loads in flight.
+// Wavefronts per SIMD the forward kernel is compiled for.  It needs 124 registers once the wave index and the
+// neighbour count are kept scalar, so four fit without a spill (with the count in a vector register it spilled nine
+// registers at four and measured 4 to 19 % slower than at three; at four without the spill it is another 6 % faster
+// on 12,000 roots).
 #ifndef TGNN_FATTN_FWD_WAVES
-#define TGNN_FATTN_FWD_WAVES 3
+#define TGNN_FATTN_FWD_WAVES 4
 #endif
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(TGNN_FATTN_FWD_WAVES, TGNN_FATTN_FWD_WAVES))) void fattn_fwd_fast_kernel(FusedAttn a) {
   extern __shared__ float lds[];
@@ -242,12 +243,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(TGNN_FATTN_
     }
     block -= fill_blocks;
   }
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  // (wave index and neighbour count are the same for all lanes: saying so keeps them, and every test on them, scalar)
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
   const int r = block * 4 + wave;
   if (r >= a.R) return;
   const int HK = a.H * a.k;
   float* sa = lds + (size_t)wave * fattn_lds_floats(a.k, a.H);   // [0, HK): scores, [HK, 2 HK): softmax weights
-  const int c = a.cnt[r];
+  const int c = __builtin_amdgcn_readfirstlane(a.cnt[r]);
   float* pr = a.prob + (size_t)r * HK;
   float* out = a.Onode + (size_t)r * a.ldh;
   // Round trip 1 (issued together with the count above, none depends on another): this lane's slot ids, the root's
@@ -382,12 +384,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(TGNN_FATTN_
 __global__ __launch_bounds__(256) void fattn_bwd_fast_kernel(FusedAttn a) {
 #endif
   extern __shared__ float lds[];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  // (wave index and neighbour count are the same for all lanes: saying so keeps them, and every test on them, scalar)
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
   const int r = blockIdx.x * 4 + wave;
   if (r >= a.R) return;
   const int HK = a.H * a.k;
   float* sa = lds + (size_t)wave * fattn_lds_floats(a.k, a.H);   // [0, HK): softmax weights, [HK, 2 HK): dp, then ds
-  const int c = a.cnt[r];
+  const int c = __builtin_amdgcn_readfirstlane(a.cnt[r]);
   float* yrow = a.Y + (size_t)r * a.ldy;
   if (c == 0) {
     for (int p = lane; p < HK; p += 64) a.dscore[(size_t)r * HK + p] = 0.f;
@@ -580,12 +583,13 @@ __global__ __launch_bounds__(256) void fattn_fwd_gen_kernel(FusedAttn a) {
     }
     block -= fill_blocks;
   }
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  // (wave index and neighbour count are the same for all lanes: saying so keeps them, and every test on them, scalar)
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
   const int r = block * 4 + wave;
   if (r >= a.R) return;
   const int HK = a.H * a.k, dc = a.de + a.dt;
   GenLds L = gen_lds(lds_raw, wave, a.k, a.H);
-  const int c = a.cnt[r];
+  const int c = __builtin_amdgcn_readfirstlane(a.cnt[r]);
   float* pr = a.prob + (size_t)r * HK;
   float* out = a.Onode + (size_t)r * a.ldh;
   for (int j = lane; j < a.k; j += 64) {
@@ -650,12 +654,13 @@ __global__ __launch_bounds__(256) void fattn_fwd_gen_kernel(FusedAttn a) {
 
 __global__ __launch_bounds__(256) void fattn_bwd_gen_kernel(FusedAttn a) {
   extern __shared__ __attribute__((aligned(16))) char lds_raw[];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  // (wave index and neighbour count are the same for all lanes: saying so keeps them, and every test on them, scalar)
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
   const int r = blockIdx.x * 4 + wave;
   if (r >= a.R) return;
   const int HK = a.H * a.k, dc = a.de + a.dt;
   GenLds L = gen_lds(lds_raw, wave, a.k, a.H);
-  const int c = a.cnt[r];
+  const int c = __builtin_amdgcn_readfirstlane(a.cnt[r]);
   float* yrow = a.Y + (size_t)r * a.ldy;
   if (c == 0) {
     for (int p = lane; p < HK; p += 64) a.dscore[(size_t)r * HK + p] = 0.f;
