@@ -70,20 +70,16 @@ struct SlotRegs {
 // the loads of every slot's edge-feature columns and node rows
 __device__ __forceinline__ void fast_issue_slots(const FusedAttn& a, int lane, int c, const int (&e_j)[FA_KR],
                                                  const int (&row_j)[FA_KR], SlotRegs& s) {
-  // Column offsets are clamped into the row instead of guarded (no per-lane branch around a load); what a clamped
-  // lane reads is replaced by zero.  Absent slots (j >= c, uniform over the wavefront) are skipped.
+  // Column offsets are clamped into the row instead of guarded (no per-lane branch around a load).  What a lane
+  // beyond the row's width reads that way (a copy of the row's last column) is NOT replaced by zero: everything a
+  // slot column is multiplied with (the per-head rows from load_head_row, the head-masked query and output-gradient
+  // rows) is zero on those lanes, and every sum that keeps slot columns is stored under a width guard.  Absent slots
+  // (j >= c, uniform over the wavefront) are skipped and stay zero.
   int ecol[FA_NE], pcol[FA_E];
-  bool elive[FA_NE], plive[FA_E];
 #pragma unroll
-  for (int m = 0; m < FA_NE; ++m) {
-    elive[m] = lane + 64 * m < a.de;
-    ecol[m] = min(lane + 64 * m, max(a.de - 1, 0));
-  }
+  for (int m = 0; m < FA_NE; ++m) ecol[m] = min(lane + 64 * m, max(a.de - 1, 0));
 #pragma unroll
-  for (int u = 0; u < FA_E; ++u) {
-    plive[u] = lane + 64 * u < a.dO;
-    pcol[u] = min(lane + 64 * u, a.dO - 1);
-  }
+  for (int u = 0; u < FA_E; ++u) pcol[u] = min(lane + 64 * u, a.dO - 1);
 #pragma unroll
   for (int j = 0; j < FA_KR; ++j) {
 #pragma unroll
@@ -102,16 +98,6 @@ __device__ __forceinline__ void fast_issue_slots(const FusedAttn& a, int lane, i
         s.pk[j][u] = prow[pcol[u]];
         s.pv[j][u] = prow[a.dO + pcol[u]];
       }
-    }
-  }
-#pragma unroll
-  for (int j = 0; j < FA_KR; ++j) {
-#pragma unroll
-    for (int m = 0; m < FA_NE; ++m) s.ce[j][m] = elive[m] ? s.ce[j][m] : 0.f;
-#pragma unroll
-    for (int u = 0; u < FA_E; ++u) {
-      s.pk[j][u] = plive[u] ? s.pk[j][u] : 0.f;
-      s.pv[j][u] = plive[u] ? s.pv[j][u] : 0.f;
     }
   }
 }
@@ -139,11 +125,8 @@ __device__ __forceinline__ void fast_time_cols(const FusedAttn& a, int lane, int
 #pragma unroll
     for (int j = 0; j < FA_KR; ++j) {
       float sn = 0.f, cs = 0.f;
-      if (j < c) {   // (uniform over the wavefront; lanes beyond d_t compute on zeros and are masked)
+      if (j < c)     // (uniform over the wavefront; lanes beyond d_t compute on w = b = 0, see fast_issue_slots)
         sincos_reduced(fma(w, dt_j[j], b), sn, cs);
-        sn = live ? sn : 0.f;
-        cs = live ? cs : 0.f;
-      }
       s.ct[j][m] = cs;
       if (BWD) st[j][m] = sn;
     }
