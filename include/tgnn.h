@@ -281,6 +281,16 @@ int32_t tgnn_eval_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, const
                        const tgnn_batch* batches, int32_t n_batches, int32_t n_neg_sets, float* out_logits,
                        float* out_rank, float* out_rr_sum, int32_t* out_winner, void* stream);
 
+/* Evaluation pass of the edge-classification task (Sec. 4: micro-averaged F1 reported).  The forward half of
+ * tgnn_train_step_edge_class, then over all events and classes the counts tp (logit > 0 and label set), fp (logit > 0,
+ * label not set) and fn (logit <= 0, label set), and the write-back of memory and mails.  No gradients, no optimiser
+ * step.  F1-micro = 2 tp / (2 tp + fp + fn) is left to the caller (counts of several calls add up).
+ *   labels      as in tgnn_train_step_edge_class;   out_logits [sum n, C] or NULL;
+ *   out_counts  [3] int32: tp, fp, fn are ADDED to it;   out_winner [2 * sum n] or NULL. */
+int32_t tgnn_eval_step_edge_class(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, const tgnn_params* p,
+                                  const tgnn_batch* batches, int32_t n_batches, const float* const* labels,
+                                  float* out_logits, int32_t* out_counts, int32_t* out_winner, void* stream);
+
 /* Optimiser of the in-step update that tgnn_train_step (and its variants) apply when lr != 0.
  *   kind 0  plain SGD, p -= lr g (the default);
  *   kind 1  Adam: m = beta1 m + (1 - beta1) g, v = beta2 v + (1 - beta2) g^2, p -= lr (m / (1 - beta1^t)) /

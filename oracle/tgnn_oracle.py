@@ -18,7 +18,8 @@ What each function follows (paper = DistTGL, arXiv 2307.07649):
   * self-supervision by temporal edges with sampled negative destinations -- Sec. 2.1, 3.2.2
   * memory and mails reset at the start of an epoch                -- Alg. 1
   * dynamic edge classification with C classes and multi-label targets (the GDELT task)
-    and the mean reciprocal rank of the true destination among 49 sampled ones  -- Sec. 4 "Datasets"
+    and the mean reciprocal rank of the true destination among 49 sampled ones; the counts behind
+    the micro-averaged F1 score                                     -- Sec. 4 "Datasets"
 
 Where the paper is silent the readings are (they are listed with reasons in the design notes):
   undirected neighbour lists ordered by (time, event id); "most recent" = time strictly
@@ -36,7 +37,7 @@ function and on the values the step feeds to the GRU, the keys and the query (ha
 with known time differences and non-zero phases); a library GRU cell and its limits; attention
 special cases; ln 2 loss; central finite differences for every parameter tensor; brute-force
 last-writer-wins write-back; the classification head: ln 2 at zero weights, a hand-computed event, finite
-differences; the reciprocal rank: hand-written score lists with ties.
+differences; the reciprocal rank: hand-written score lists with ties; the F1 counts: a hand-written table.
 The step as a whole is "parity unpinned" against the paper, which prints no worked example.
 """
 from __future__ import annotations
@@ -337,6 +338,16 @@ def edge_class_bwd(p, cache, logits, loss_scale=1.0, gate_h=None):
     dh = (dl @ p["dec_w2"]) * ((cache["hpre"] > 0) if gate_h is None else gate_h)
     g["dec_ws"] = dh.T @ cache["a"]; g["dec_wd"] = dh.T @ cache["b"]; g["dec_b1"] = dh.sum(0)
     return g, dh @ p["dec_ws"], dh @ p["dec_wd"]
+
+
+def f1_micro_counts(logits, labels):
+    """Counts behind the micro-averaged F1 score of the edge-classification task (Sec. 4: "we report the F1-Micro
+    score"): a class is predicted for an event when its logit is positive (probability above one half); over all
+    events and classes, tp = predicted and true, fp = predicted and not true, fn = true and not predicted.
+    F1-micro = 2 tp / (2 tp + fp + fn).  Returns (tp, fp, fn)."""
+    pred = np.asarray(logits) > 0
+    y = np.asarray(labels) > 0.5
+    return int((pred & y).sum()), int((pred & ~y).sum()), int((~pred & y).sum())
 
 
 def reciprocal_rank(score_true, score_neg):

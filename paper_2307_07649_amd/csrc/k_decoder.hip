@@ -249,6 +249,39 @@ void reciprocal_ranks(const BatchSet* bs, int total, const float* logits, float*
   hipLaunchKernelGGL(rank_kernel, dim3((total + 255) / 256), dim3(256), 0, s, bs, logits, rank, rr_sum);
 }
 
+// Predictions of the classification head against the targets: one thread per (event, class), counts summed per
+// block before the three device-wide atomics.
+__global__ __launch_bounds__(256) void class_count_kernel(const BatchSet* __restrict__ bsp, int C,
+                                                          const float* __restrict__ logits, int32_t* __restrict__ counts) {
+  __shared__ int red[3];
+  const BatchSet& bs = *bsp;
+  if (threadIdx.x < 3) red[threadIdx.x] = 0;
+  __syncthreads();
+  const long long i = blockIdx.x * 256ll + threadIdx.x;
+  int tp = 0, fp = 0, fn = 0;
+  if (i < (long long)bs.total * C) {
+    const int ev = (int)(i / C), cls = (int)(i - (long long)ev * C);
+    const int b = batch_of_row(bs, ev, 1);
+    const bool y = bs.b[b].labels[(size_t)(ev - bs.b[b].ev_off) * C + cls] > 0.5f;
+    const bool pred = logits[i] > 0.f;
+    tp = pred && y; fp = pred && !y; fn = !pred && y;
+  }
+  const int ntp = __popcll(__ballot(tp)), nfp = __popcll(__ballot(fp)), nfn = __popcll(__ballot(fn));
+  if ((threadIdx.x & 63) == 0) {
+    if (ntp) atomicAdd(&red[0], ntp);
+    if (nfp) atomicAdd(&red[1], nfp);
+    if (nfn) atomicAdd(&red[2], nfn);
+  }
+  __syncthreads();
+  if (threadIdx.x < 3 && red[threadIdx.x] != 0) atomicAdd(counts + threadIdx.x, red[threadIdx.x]);
+}
+
+void class_counts(const BatchSet* bs, int total, int C, const float* logits, int32_t* counts, hipStream_t s) {
+  if (total <= 0) return;
+  const long long n = (long long)total * C;
+  hipLaunchKernelGGL(class_count_kernel, dim3((int)((n + 255) / 256)), dim3(256), 0, s, bs, C, logits, counts);
+}
+
 __global__ void mask_dz_kernel(int R, int dO, const float* __restrict__ dz_in, int p_in, const float* __restrict__ z,
                                int ldz, float* __restrict__ dz_out) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;

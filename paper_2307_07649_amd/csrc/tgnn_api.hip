@@ -766,6 +766,21 @@ int32_t tgnn_eval_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, const
   return rc;
 }
 
+int32_t tgnn_eval_step_edge_class(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, const tgnn_params* p,
+                                  const tgnn_batch* batches, int32_t n_batches, const float* const* labels,
+                                  float* out_logits, int32_t* out_counts, int32_t* out_winner, void* stream) {
+  if (ctx == nullptr) return set_error(TGNN_E_NULL_PTR, "ctx is NULL");
+  if (labels == nullptr) return set_error(TGNN_E_NULL_PTR, "labels is NULL");
+  REQ_PTR(out_counts);
+  tgnn_params no_grads;
+  memset(&no_grads, 0, sizeof(no_grads));
+  ctx->eval = true; ctx->out_counts = out_counts;
+  const int rc = train_step_impl(ctx, g, st, p, &no_grads, batches, n_batches, 0.0f, nullptr, out_logits, out_winner, stream,
+                                 false, 0, labels);
+  ctx->eval = false; ctx->out_counts = nullptr;
+  return rc;
+}
+
 static int train_step_impl(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, const tgnn_params* p, tgnn_params* grads,
                            const tgnn_batch* batches, int32_t n_batches, float lr, float* out_loss, float* out_logits,
                            int32_t* out_winner, void* stream, bool loss_in_array, int nneg, const float* const* labels) {
@@ -897,10 +912,10 @@ static int replay_steps(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
     const float* const* gg = reinterpret_cast<const float* const*>(grads);
     for (int i = 0; i < 19; ++i) { key.ptr[q++] = pp[i]; key.ptr[q++] = gg[i]; }
     key.ptr[q++] = out_loss; key.ptr[q++] = out_logits; key.ptr[q++] = out_winner; key.ptr[q++] = s;
-    key.ptr[q++] = ctx->out_rank; key.ptr[q++] = ctx->out_rr;
+    key.ptr[q++] = ctx->out_rank; key.ptr[q++] = ctx->out_rr; key.ptr[q++] = ctx->out_counts;
     for (int b = 0; b < bs.nb; ++b) { key.n[b] = bs.b[b].n; key.rep[b] = bs.b[b].replica; }
     key.nb = bs.nb; key.lr = lr; key.parity = parity; key.n_steps = n_steps; key.nneg = bs.nneg;
-    key.mode = ctx->eval ? 2 : bs.ncls > 0 ? 1 : 0;
+    key.mode = (ctx->eval ? 2 : 0) + (bs.ncls > 0 ? 1 : 0);
   }
   StepGraph* hit = nullptr;
   StepGraph* victim = &ctx->graphs[0];
@@ -1091,7 +1106,8 @@ static int enqueue_step(tgnn_ctx* ctx, const tgnn_graph* g, tgnn_state* st, cons
   if (eval) {
     // Evaluation (Sec. 4: rank of the true destination among the sampled ones): no backward half; the write-back
     // scatter leaves in a launch of its own.
-    reciprocal_ranks(w.bs_dev, bs.total, w.logits, ctx->out_rank, ctx->out_rr, s);
+    if (classes) class_counts(w.bs_dev, bs.total, d.nC, w.logits, ctx->out_counts, s);
+    else reciprocal_ranks(w.bs_dev, bs.total, w.logits, ctx->out_rank, ctx->out_rr, s);
     WbArgs wb = writeback_args(d, w.bs_dev, bs.total, st, w.winkey, w.epoch, w.Xrow, d.ldxr, w.tau, w.slot_row, nullptr,
                                nullptr, nullptr, nullptr, out_winner, nullptr, 0, 0.0f);
     gemm_nt_group(nullptr, 0, s, &wb);

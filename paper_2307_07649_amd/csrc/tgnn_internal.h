@@ -169,6 +169,7 @@ struct tgnn_ctx {
   bool eval = false;               // tgnn_eval_step: forward half, ranks and write-back only
   float* out_rank = nullptr;       // ... its per-event ranks and the sum of their reciprocals
   float* out_rr = nullptr;
+  int32_t* out_counts = nullptr;   // ... or, on a classification context, its tp / fp / fn counts
   bool adam = false;               // tgnn_set_optimizer: the in-step update is Adam's
   bool train_static = false;       // tgnn_train_static
   float* grad_static = nullptr;
@@ -609,6 +610,8 @@ void decoder_classes(const Dims& d, const BatchSet* bs, int total, const float* 
                      float* dlog, hipStream_t s);
 // rank[ev] = 1 + #(negative pairs of the event scoring above its true pair) + 0.5 #(scoring the same); rr_sum += sum 1/rank
 void reciprocal_ranks(const BatchSet* bs, int total, const float* logits, float* rank, float* rr_sum, hipStream_t s);
+// counts[0..2] += tp, fp, fn of the predictions logit > 0 against the batches' class targets (logits [total, C])
+void class_counts(const BatchSet* bs, int total, int C, const float* logits, int32_t* counts, hipStream_t s);
 void mask_dz(int R, int dO, const float* dz_in, int p_in, const float* z, int ldz, float* dz_out, hipStream_t s);
 // d_x_root[r, c] = ds_row[r, c];  d_x_nbr[j, c] = ds_row[R + j, c]   (c < dm, outputs pitch dm)
 void attn_dx_out(int R, int RK, int dm, const float* ds_row, int ldh, float* d_x_root, float* d_x_nbr, hipStream_t s);

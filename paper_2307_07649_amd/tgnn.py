@@ -77,6 +77,8 @@ _SIGS = {
                                         _P, _P]),
     "tgnn_eval_step": (_I, [_P, C.POINTER(tgnn_graph), C.POINTER(tgnn_state), C.POINTER(tgnn_params), C.POINTER(tgnn_batch),
                             _I, _I, _P, _P, _P, _P, _P]),
+    "tgnn_eval_step_edge_class": (_I, [_P, C.POINTER(tgnn_graph), C.POINTER(tgnn_state), C.POINTER(tgnn_params),
+                                       C.POINTER(tgnn_batch), _I, C.POINTER(_P), _P, _P, _P, _P]),
     "tgnn_train_steps": (_I, [_P, C.POINTER(tgnn_graph), C.POINTER(tgnn_state), C.POINTER(tgnn_params),
                               C.POINTER(tgnn_params), _I, C.POINTER(tgnn_batch), _I, C.c_float, _P, _P]),
     "tgnn_set_optimizer": (_I, [_P, _I, C.POINTER(tgnn_params), C.POINTER(tgnn_params), C.c_float, C.c_float, C.c_float]),
@@ -325,6 +327,15 @@ class Context:
         arr = (tgnn_batch * len(batches))(*[b.c for b in batches])
         _check(_lib.tgnn_eval_step(self.h, C.byref(g.c), C.byref(st.c), C.byref(p.c), arr, len(batches), n_neg_sets,
                                    _ptr(out_logits), _ptr(out_rank), _ptr(out_rr_sum), _ptr(out_winner), _stream()))
+
+    def tgnn_eval_step_edge_class(self, g: Graph, st: State, p: Params, batches, labels, out_counts, out_logits=None,
+                                  out_winner=None):
+        """labels: one float32 device tensor [n, n_classes] per batch; out_counts: int32 device tensor [3], the counts
+        tp, fp, fn of the predictions logit > 0 are added to it."""
+        arr = (tgnn_batch * len(batches))(*[b.c for b in batches])
+        lab = (_P * len(batches))(*[_ptr(y) for y in labels])
+        _check(_lib.tgnn_eval_step_edge_class(self.h, C.byref(g.c), C.byref(st.c), C.byref(p.c), arr, len(batches), lab,
+                                              _ptr(out_logits), _ptr(out_counts), _ptr(out_winner), _stream()))
 
     def tgnn_train_steps(self, g: Graph, st: State, p: Params, grads: Params, steps, lr=0.0, out_loss=None):
         """steps: a list of steps, each a list of Batch (the same number per step); out_loss: device array [len(steps)]."""

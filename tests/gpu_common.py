@@ -172,6 +172,26 @@ class GpuSide:
         torch.cuda.synchronize()
         return out
 
+    def eval_class_step(self, batches, replicas=None):
+        """tgnn_eval_step_edge_class on batches with "labels": logits [sum n, C], the (tp, fp, fn) counts of this call,
+        winners."""
+        torch, tgnn = self.torch, self.tgnn
+        C = self.d.n_classes
+        replicas = replicas if replicas is not None else list(range(len(batches)))
+        bl = [tgnn.Batch(b["src"], b["dst"], np.asarray(b["neg"]).reshape(-1), b["eid"], b["t"], replica=r)
+              for b, r in zip(batches, replicas)]
+        tot = sum(b.n for b in bl)
+        labels = [torch.from_numpy(np.ascontiguousarray(b["labels"], np.float32)).cuda() for b in batches]
+        logits = torch.empty(tot * C, device="cuda"); win = torch.empty(2 * tot, dtype=torch.int32, device="cuda")
+        counts = torch.zeros(3, dtype=torch.int32, device="cuda")
+        torch.cuda.synchronize()
+        with torch.cuda.stream(self.stream):
+            self.ctx.tgnn_eval_step_edge_class(self.graph, self.state, self.params, bl, labels, counts, out_logits=logits,
+                                               out_winner=win)
+        torch.cuda.synchronize()
+        return dict(logits=logits.cpu().numpy().reshape(tot, C), counts=tuple(int(x) for x in counts.cpu().numpy()),
+                    winner=win.cpu().numpy())
+
     def state_np(self, replica=0):
         N = self.d.n_nodes
         s = slice(replica * N, (replica + 1) * N)

@@ -190,3 +190,35 @@ def test_edge_classification_with_adam():
             assert rel_err(after[2][n], st["v"][n]) <= 1e-6, (s, n)
     moved = np.abs(G.params.numpy()["dec_w2"] - P["params"]["dec_w2"]) > 0      # (hidden units that never fire stay put)
     assert moved.shape == (11, 24) and moved.all(axis=0).sum() > 12 and moved.any(axis=1).all()
+
+
+def test_classification_evaluation_pass_against_the_oracle():
+    """tgnn_eval_step_edge_class between training steps on one context: logits against the oracle's forward pass, the
+    tp / fp / fn counts exactly those of the oracle's counting function on the GPU's own logits (and on the oracle's,
+    where no logit is within rounding of zero), memory advanced, parameters untouched by the evaluation steps."""
+    P = synth.custom_problem(n_nodes=90, E=900, d_mem=32, d_time=16, d_edge=6, d_static=0, n_heads=2, k=5, batch=50,
+                             n_classes=13, n_true=4, seed=41)
+    d = P["d"]
+    G = GpuSide(P); Or = OracleSide(P)
+    total = np.zeros(3, np.int64)
+    for s in range(12):
+        b = batch_np(P, s * d.batch, (s + 1) * d.batch)
+        if s % 2 == 1:
+            before = G.params.numpy()
+            g = G.eval_class_step([b])
+            o = Or.step([b], lr=0.0)
+            ref = o["outs"][0]["logits"]
+            assert rel_err(g["logits"], ref) <= TOL, s
+            assert np.array_equal(g["winner"], o["winners"][0])
+            assert g["counts"] == O.f1_micro_counts(g["logits"], b["labels"]), s
+            if np.abs(ref).min() > 1e-4 * np.abs(ref).max():
+                assert g["counts"] == O.f1_micro_counts(ref, b["labels"]), s
+            assert sum(g["counts"][i] for i in (0, 2)) == int(b["labels"].sum())         # tp + fn = the true labels
+            assert all(np.array_equal(before[n], v) for n, v in G.params.numpy().items())
+            total += g["counts"]
+        else:
+            g = G.step([b], lr=0.05)
+            o = Or.step([b], lr=0.05, gpu=g)
+            compare_step(g, o, label=f"classification train/eval step {s}")
+    compare_state(G.state_np(), Or.states[0], label="classification train/eval")
+    assert total[0] + total[1] > 0          # the head does predict something

@@ -108,3 +108,14 @@ def test_labels_generator_shape():
     y = synth.gen_labels(1000, 56, 6, seed=1)
     assert y.shape == (1000, 56) and y.dtype == np.float32 and np.all(y.sum(1) == 6) and set(np.unique(y)) == {0.0, 1.0}
     assert y[:, 0].mean() > 3 * y[:, 55].mean()          # skewed class popularity
+
+
+def test_f1_micro_counts_by_hand():
+    logits = np.array([[2.0, -1.0, 0.5, -3.0], [0.0, 1.0, -0.1, 4.0]])
+    labels = np.array([[1, 0, 0, 1], [1, 1, 0, 0]], dtype=float)
+    # predicted: (0,0) (0,2) (1,1) (1,3);  true: (0,0) (0,3) (1,0) (1,1);  a logit of exactly 0 is not a prediction
+    tp, fp, fn = O.f1_micro_counts(logits, labels)
+    assert (tp, fp, fn) == (2, 2, 2)
+    assert abs(2 * tp / (2 * tp + fp + fn) - 0.5) < 1e-15
+    assert O.f1_micro_counts(np.full((3, 5), 7.0), np.ones((3, 5))) == (15, 0, 0)
+    assert O.f1_micro_counts(np.full((3, 5), -7.0), np.ones((3, 5))) == (0, 0, 15)
