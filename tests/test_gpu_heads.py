@@ -222,3 +222,35 @@ def test_classification_evaluation_pass_against_the_oracle():
             compare_step(g, o, label=f"classification train/eval step {s}")
     compare_state(G.state_np(), Or.states[0], label="classification train/eval")
     assert total[0] + total[1] > 0          # the head does predict something
+
+
+def test_evaluation_pass_two_replicas_ragged_batches():
+    """Two memory replicas in one evaluation call, batches of different lengths: scores, ranks (pair layout per batch) and
+    the memory of both replicas."""
+    P = synth.custom_problem(n_nodes=100, E=1000, d_mem=24, d_time=8, d_edge=4, d_static=3, n_heads=3, k=6, batch=50, seed=29)
+    d = P["d"]
+    J = 7
+    rng = np.random.default_rng(5)
+    G = GpuSide(P, n_replicas=2, max_neg_sets=J); Or = OracleSide(P, n_replicas=2)
+    for s in range(5):
+        bs = []
+        for r in range(2):
+            lo = (2 * s + r) * d.batch; hi = lo + d.batch - 13 * r
+            b = batch_np(P, lo, hi)
+            b["neg"] = rng.integers(0, d.n_nodes, (J, hi - lo)).astype(np.int32)
+            bs.append(b)
+        g = G.eval_step(bs, J)
+        o = Or.step(bs, lr=0.0)
+        ref = np.concatenate([x["logits"] for x in o["outs"]])
+        assert rel_err(g["logits"], ref) <= TOL, s
+        assert np.array_equal(g["winner"], np.concatenate(o["winners"]))
+        off_l = off_e = 0
+        for b in bs:
+            n = len(b["src"])
+            lg = g["logits"][off_l:off_l + (1 + J) * n].astype(np.float64)
+            rank, _ = O.reciprocal_rank(lg[:n], lg[n:].reshape(J, n))
+            assert np.array_equal(g["rank"][off_e:off_e + n], rank.astype(np.float32)), s
+            off_l += (1 + J) * n; off_e += n
+        assert abs(g["rr_sum"] - float((1.0 / g["rank"].astype(np.float64)).sum())) <= 1e-4
+    for r in range(2):
+        compare_state(G.state_np(r), Or.states[r], label=f"evaluation replica {r}")
